@@ -1,0 +1,414 @@
+"""CPU fp64 oracle for the Ouroboros training step.  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this
+module; the product path (the HIP library and its binding) never does.  It shares no
+code with the HIP path: plain numpy in fp64, no blocking, no fusion, no ring buffers.
+
+What it computes, with the passage of the paper each part follows:
+
+  * The network is a chain of L layers with a tied input-embedding / output-projection
+    matrix V = V_i = V_o (Section 2, Eq. 1-3) trained on the LM loss (Eq. 4).
+  * Backpropagation is the chain rule of Eq. 6; V_i and V_o are differentiated as two
+    separate leaves that hold equal values (Eq. 7).
+  * The layers are split into K contiguous modules G(1..K) (Section 3.1).  At iteration
+    t module k uses the gradient of mini-batch t-K+k evaluated at the full weight
+    vector of iteration t-K+k, or zero while t-K+k < 0 (Eq. 8).
+  * The tied matrix uses g_V = 1/2 dV_o(t) + 1/2 dV_i(t-K+1), zero while t-K+1 < 0
+    (Eq. 9; `embed_warm_mode=1` is the term-wise reading where only the V_i term is
+    dropped during those steps).
+  * SGD (Algorithm 1) or Adam (Algorithm 2, appendix): every group steps at every t,
+    also with a zero gradient; bias correction uses the global t+1; epsilon is added
+    outside the square root after bias correction.
+
+The paper does not define the Transformer layer itself; the oracle fixes the reading
+(post-LN blocks, bias-free attention projections, exact-erf GELU, fixed sinusoid
+positions, Transformer-XL relative attention with per-layer u, v, W_r and a constant
+segment memory).  Those readings are pinned by finite differences, closed forms and an
+independent autograd model in tests/, not by the paper: "parity unpinned" against the
+paper for the layer internals and for whole-trajectory loss values (the paper prints
+none).
+
+The oracle keeps the gradient of every past step in an unbounded list indexed by the
+step number (no modulo arithmetic), and `brute_check` re-derives any used gradient from
+a stored copy of that step's full weights and batch.
+"""
+from __future__ import annotations
+
+import copy
+import math
+
+import numpy as np
+from scipy.special import erf
+
+LN_EPS = 1e-5
+
+
+# ----------------------------------------------------------------------------- config
+class Config:
+    def __init__(self, n_layer, d_model, n_head, d_head, d_ff, vocab, seq_len, batch,
+                 n_module=1, mem_len=0, rel_pos=0, layers_per_module=None, optimizer=0,
+                 beta1=0.9, beta2=0.999, eps=1e-8, embed_warm_mode=0, emb_scale=1.0, **_):
+        assert n_head * d_head == d_model
+        assert d_model % 2 == 0
+        assert mem_len == 0 or rel_pos
+        self.n_layer, self.d_model, self.n_head, self.d_head = n_layer, d_model, n_head, d_head
+        self.d_ff, self.vocab, self.seq_len, self.batch = d_ff, vocab, seq_len, batch
+        self.n_module, self.mem_len, self.rel_pos = n_module, mem_len, rel_pos
+        self.optimizer, self.beta1, self.beta2, self.eps = optimizer, beta1, beta2, eps
+        self.embed_warm_mode, self.emb_scale = embed_warm_mode, emb_scale
+        if layers_per_module is None:
+            layers_per_module = split_layers(n_layer, n_module)
+        assert len(layers_per_module) == n_module and sum(layers_per_module) == n_layer
+        self.layers_per_module = list(layers_per_module)
+
+
+def split_layers(n_layer, n_module):
+    """Contiguous groups G(k) (Section 3.1); if K does not divide L the interior
+    modules take the extra layers first."""
+    base, rem = divmod(n_layer, n_module)
+    sizes = [base] * n_module
+    order = list(range(1, n_module - 1)) + [0, n_module - 1]
+    for i in range(rem):
+        sizes[order[i % n_module]] += 1
+    return sizes
+
+
+PARAM_ORDER_PLAIN = ["W_qkv", "W_o", "ln1_g", "ln1_b", "W_1", "b_1", "W_2", "b_2", "ln2_g", "ln2_b"]
+PARAM_ORDER_XL = ["W_qkv", "W_o", "W_r", "u", "v", "ln1_g", "ln1_b", "W_1", "b_1", "W_2", "b_2",
+                  "ln2_g", "ln2_b"]
+
+
+def param_shapes(cfg):
+    d, f, h, dh = cfg.d_model, cfg.d_ff, cfg.n_head, cfg.d_head
+    s = {"W_qkv": (d, 3 * d), "W_o": (d, d), "W_r": (d, d), "u": (h, dh), "v": (h, dh),
+         "ln1_g": (d,), "ln1_b": (d,), "W_1": (d, f), "b_1": (f,), "W_2": (f, d), "b_2": (d,),
+         "ln2_g": (d,), "ln2_b": (d,)}
+    order = PARAM_ORDER_XL if cfg.rel_pos else PARAM_ORDER_PLAIN
+    return [(n, s[n]) for n in order]
+
+
+def unpack_layers(cfg, blob, n_layers):
+    """Module blob (flat, documented order) -> list of per-layer dicts of fp64 arrays."""
+    blob = np.asarray(blob, dtype=np.float64)
+    out, off = [], 0
+    for _ in range(n_layers):
+        p = {}
+        for name, shape in param_shapes(cfg):
+            n = int(np.prod(shape))
+            p[name] = blob[off:off + n].reshape(shape).copy()
+            off += n
+        out.append(p)
+    assert off == blob.size
+    return out
+
+
+def pack_layers(cfg, layers):
+    parts = []
+    for p in layers:
+        for name, _ in param_shapes(cfg):
+            parts.append(np.asarray(p[name], dtype=np.float64).ravel())
+    return np.concatenate(parts) if parts else np.zeros(0)
+
+
+# ----------------------------------------------------------------------- elementary ops
+def sinusoid(positions, d):
+    """[len(positions), d] table: first half sin(p*w_m), second half cos(p*w_m),
+    w_m = 10000^(-2m/d), m < d/2."""
+    pos = np.asarray(positions, dtype=np.float64)[:, None]
+    m = np.arange(d // 2, dtype=np.float64)[None, :]
+    ang = pos * (10000.0 ** (-2.0 * m / d))
+    return np.concatenate([np.sin(ang), np.cos(ang)], axis=1)
+
+
+def layernorm_fwd(x, g, b):
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)          # biased variance
+    rstd = 1.0 / np.sqrt(var + LN_EPS)
+    xhat = (x - mu) * rstd
+    return xhat * g + b, (xhat, rstd)
+
+
+def layernorm_bwd(dy, g, cache):
+    xhat, rstd = cache
+    dg = (dy * xhat).reshape(-1, xhat.shape[-1]).sum(axis=0)
+    db = dy.reshape(-1, xhat.shape[-1]).sum(axis=0)
+    dxh = dy * g
+    dx = rstd * (dxh - dxh.mean(axis=-1, keepdims=True)
+                 - xhat * (dxh * xhat).mean(axis=-1, keepdims=True))
+    return dx, dg, db
+
+
+def gelu(x):
+    return 0.5 * x * (1.0 + erf(x / math.sqrt(2.0)))
+
+
+def gelu_grad(x):
+    return 0.5 * (1.0 + erf(x / math.sqrt(2.0))) + x * np.exp(-0.5 * x * x) / math.sqrt(2.0 * math.pi)
+
+
+def split_heads(x, h, dh):
+    """[B, S, h*dh] -> [B, h, S, dh]"""
+    b, s, _ = x.shape
+    return x.reshape(b, s, h, dh).transpose(0, 2, 1, 3)
+
+
+def merge_heads(x):
+    b, h, s, dh = x.shape
+    return x.transpose(0, 2, 1, 3).reshape(b, s, h * dh)
+
+
+# --------------------------------------------------------------------------- attention
+def attention_fwd(cfg, p, x, mem):
+    """Self-attention of one layer.  x [B,T,d] current segment, mem [B,Mv,d] or None
+    (a constant: previous inputs of this layer).  Query i sits at absolute position
+    Mv+i and sees keys j <= Mv+i of [mem ; x]."""
+    B, T, d = x.shape
+    H, dh = cfg.n_head, cfg.d_head
+    Mv = 0 if mem is None else mem.shape[1]
+    cat = x if Mv == 0 else np.concatenate([mem, x], axis=1)
+    S = Mv + T
+    Wq, Wk, Wv = p["W_qkv"][:, :d], p["W_qkv"][:, d:2 * d], p["W_qkv"][:, 2 * d:]
+    q = split_heads(x @ Wq, H, dh)            # [B,H,T,dh]
+    k = split_heads(cat @ Wk, H, dh)          # [B,H,S,dh]
+    v = split_heads(cat @ Wv, H, dh)
+    scale = 1.0 / math.sqrt(dh)
+    i_idx = np.arange(T)[:, None]
+    j_idx = np.arange(S)[None, :]
+    delta = Mv + i_idx - j_idx                # relative distance p_i - p_j
+    visible = delta >= 0
+    cache = dict(x=x, cat=cat, q=q, k=k, v=v, Mv=Mv, visible=visible, delta=delta)
+    if cfg.rel_pos:
+        R = sinusoid(np.arange(S), d)                         # R_delta, delta = 0..S-1
+        r = (R @ p["W_r"]).reshape(S, H, dh).transpose(1, 0, 2)   # [H,S,dh]
+        qu = q + p["u"][None, :, None, :]
+        qv = q + p["v"][None, :, None, :]
+        AC = qu @ k.transpose(0, 1, 3, 2)                     # [B,H,T,S]
+        QR = np.einsum("bhic,hpc->bhip", qv, r)               # [B,H,T,S] indexed by delta
+        dcl = np.where(visible, delta, 0)
+        BD = np.take_along_axis(QR, np.broadcast_to(dcl, QR.shape), axis=3)
+        s = (AC + BD) * scale
+        cache.update(R=R, r=r, qu=qu, qv=qv, dcl=dcl)
+    else:
+        s = (q @ k.transpose(0, 1, 3, 2)) * scale
+    s = np.where(visible, s, -np.inf)
+    s = s - s.max(axis=-1, keepdims=True)
+    e = np.exp(s)
+    P = e / e.sum(axis=-1, keepdims=True)
+    a = merge_heads(P @ v)                                    # [B,T,d]
+    o = a @ p["W_o"]
+    cache.update(P=P, a=a, scale=scale)
+    return o, cache
+
+
+def attention_bwd(cfg, p, do, c):
+    d = cfg.d_model
+    H, dh = cfg.n_head, cfg.d_head
+    x, cat, q, k, v, P, a, Mv, scale = (c[n] for n in ("x", "cat", "q", "k", "v", "P", "a", "Mv", "scale"))
+    B, T, _ = x.shape
+    g = {}
+    g["W_o"] = a.reshape(-1, d).T @ do.reshape(-1, d)
+    da = split_heads(do @ p["W_o"].T, H, dh)                  # [B,H,T,dh]
+    dv = P.transpose(0, 1, 3, 2) @ da
+    dP = da @ v.transpose(0, 1, 3, 2)
+    dS = P * (dP - (dP * P).sum(axis=-1, keepdims=True))
+    dS = np.where(c["visible"], dS, 0.0) * scale
+    if cfg.rel_pos:
+        r, qu, qv, R = c["r"], c["qu"], c["qv"], c["R"]
+        dqu = dS @ k
+        dk = dS.transpose(0, 1, 3, 2) @ qu
+        # dS[b,h,i,j] belongs to relative distance delta(i,j); for a fixed i the map
+        # j -> delta is one-to-one over the visible keys, so plain assignment is exact
+        dQR = np.zeros_like(dS)
+        ii, jj = np.nonzero(c["visible"])
+        dQR[:, :, ii, c["delta"][ii, jj]] = dS[:, :, ii, jj]
+        dqv = np.einsum("bhip,hpc->bhic", dQR, r)
+        dr = np.einsum("bhip,bhic->hpc", dQR, qv)             # [H,S,dh]
+        g["u"] = dqu.sum(axis=(0, 2))
+        g["v"] = dqv.sum(axis=(0, 2))
+        g["W_r"] = R.T @ dr.transpose(1, 0, 2).reshape(-1, d)
+        dq = dqu + dqv
+    else:
+        dq = dS @ k
+        dk = dS.transpose(0, 1, 3, 2) @ q
+    dq, dk, dv = merge_heads(dq), merge_heads(dk), merge_heads(dv)
+    x2, cat2 = x.reshape(-1, d), cat.reshape(-1, d)
+    g["W_qkv"] = np.concatenate([x2.T @ dq.reshape(-1, d), cat2.T @ dk.reshape(-1, d),
+                                 cat2.T @ dv.reshape(-1, d)], axis=1)
+    Wq, Wk, Wv = p["W_qkv"][:, :d], p["W_qkv"][:, d:2 * d], p["W_qkv"][:, 2 * d:]
+    dx = dq @ Wq.T + (dk[:, Mv:] @ Wk.T) + (dv[:, Mv:] @ Wv.T)    # memory is a constant
+    return dx, g
+
+
+# ------------------------------------------------------------------------------- layer
+def layer_fwd(cfg, p, x, mem):
+    o, ca = attention_fwd(cfg, p, x, mem)
+    y, c1 = layernorm_fwd(x + o, p["ln1_g"], p["ln1_b"])
+    z = y @ p["W_1"] + p["b_1"]
+    u = gelu(z)
+    f = u @ p["W_2"] + p["b_2"]
+    h, c2 = layernorm_fwd(y + f, p["ln2_g"], p["ln2_b"])
+    return h, dict(att=ca, ln1=c1, y=y, z=z, u=u, ln2=c2)
+
+
+def layer_bwd(cfg, p, dh, c):
+    d, F = cfg.d_model, cfg.d_ff
+    g = {}
+    ds2, g["ln2_g"], g["ln2_b"] = layernorm_bwd(dh, p["ln2_g"], c["ln2"])
+    g["W_2"] = c["u"].reshape(-1, F).T @ ds2.reshape(-1, d)
+    g["b_2"] = ds2.reshape(-1, d).sum(axis=0)
+    dz = (ds2 @ p["W_2"].T) * gelu_grad(c["z"])
+    g["W_1"] = c["y"].reshape(-1, d).T @ dz.reshape(-1, F)
+    g["b_1"] = dz.reshape(-1, F).sum(axis=0)
+    dy = ds2 + dz @ p["W_1"].T
+    ds1, g["ln1_g"], g["ln1_b"] = layernorm_bwd(dy, p["ln1_g"], c["ln1"])
+    dx_att, ga = attention_bwd(cfg, p, ds1, c["att"])
+    g.update(ga)
+    return ds1 + dx_att, g
+
+
+# ------------------------------------------------------------------------------- model
+def model_forward(cfg, layers, Vi, Vo, tokens, targets, mems=None):
+    """Eq. 1-4.  Returns loss (mean over all B*T targets, natural log) and a cache."""
+    B, T = tokens.shape
+    d = cfg.d_model
+    h = cfg.emb_scale * Vi[tokens]                            # Eq. 1: V_i enters layer 1
+    if not cfg.rel_pos:
+        h = h + sinusoid(np.arange(T), d)[None]
+    inputs, caches = [], []
+    for l, p in enumerate(layers):
+        inputs.append(h)
+        h, c = layer_fwd(cfg, p, h, None if mems is None else mems[l])
+        caches.append(c)
+    logits = h @ Vo.T                                         # Eq. 3: V_o leaves layer L
+    mx = logits.max(axis=-1, keepdims=True)
+    lse = mx[..., 0] + np.log(np.exp(logits - mx).sum(axis=-1))
+    tgt_logit = np.take_along_axis(logits, targets[..., None].astype(np.int64), axis=-1)[..., 0]
+    loss = float((lse - tgt_logit).mean())
+    return loss, dict(inputs=inputs, caches=caches, hL=h, logits=logits, lse=lse)
+
+
+def model_backward(cfg, layers, Vi, Vo, tokens, targets, fw):
+    """Eq. 6-7: full gradient {dw_l for all l, dV_i, dV_o}."""
+    B, T = tokens.shape
+    N = B * T
+    d = cfg.d_model
+    G = np.exp(fw["logits"] - fw["lse"][..., None])
+    np.put_along_axis(G, targets[..., None].astype(np.int64),
+                      np.take_along_axis(G, targets[..., None].astype(np.int64), axis=-1) - 1.0, axis=-1)
+    G /= N
+    dVo = G.reshape(N, -1).T @ fw["hL"].reshape(N, d)
+    dh = G @ Vo
+    grads = [None] * len(layers)
+    for l in reversed(range(len(layers))):
+        dh, grads[l] = layer_bwd(cfg, layers[l], dh, fw["caches"][l])
+    dVi = np.zeros_like(Vi)
+    np.add.at(dVi, tokens.reshape(-1), cfg.emb_scale * dh.reshape(N, d))
+    return grads, dVi, dVo
+
+
+def full_gradient(cfg, layers, V, tokens, targets, mems=None):
+    loss, fw = model_forward(cfg, layers, V, V, tokens, targets, mems)
+    grads, dVi, dVo = model_backward(cfg, layers, V, V, tokens, targets, fw)
+    return loss, grads, dVi, dVo, fw["inputs"]
+
+
+# ------------------------------------------------------------------- training iteration
+class Oracle:
+    """Algorithm 1 / Algorithm 2 with the delayed gradients of Eq. 8-9."""
+
+    def __init__(self, cfg: Config, blobs, keep_history=True):
+        """blobs: [V flat, module 1 flat, ..., module K flat] (documented blob order)."""
+        self.cfg = cfg
+        self.V = np.asarray(blobs[0], dtype=np.float64).reshape(cfg.vocab, cfg.d_model).copy()
+        self.layers = []
+        for k in range(cfg.n_module):
+            self.layers += unpack_layers(cfg, blobs[k + 1], cfg.layers_per_module[k])
+        self.bounds = np.concatenate([[0], np.cumsum(cfg.layers_per_module)])  # G(k) = [b[k-1], b[k])
+        self.t = 0
+        self.mems = None
+        self.grad_hist = []      # step -> (per-layer grads, dV_i, dV_o); never a ring
+        self.state_hist = []     # step -> (layers, V, mems, tokens, targets)
+        self.keep_history = keep_history
+        self.used = []           # step -> {k: tau} actually used, for the index pins
+        if cfg.optimizer == 1:
+            self.m = [{n: np.zeros_like(a) for n, a in p.items()} for p in self.layers]
+            self.v = [{n: np.zeros_like(a) for n, a in p.items()} for p in self.layers]
+            self.mV, self.vV = np.zeros_like(self.V), np.zeros_like(self.V)
+
+    def module_layers(self, k):
+        """Layer indices of G(k), k = 1..K."""
+        return range(int(self.bounds[k - 1]), int(self.bounds[k]))
+
+    def module_blob(self, k):
+        return self.V.ravel().copy() if k == 0 else pack_layers(self.cfg, [self.layers[l] for l in self.module_layers(k)])
+
+    def grad_blob(self, k, tau):
+        """Flat gradient of module k (1..K) computed at step tau."""
+        return pack_layers(self.cfg, [self.grad_hist[tau][0][l] for l in self.module_layers(k)])
+
+    def _apply(self, w, g, m, v, lr):
+        c = self.cfg
+        if c.optimizer == 0:
+            w -= lr * g                                      # Algorithm 1
+            return
+        m *= c.beta1; m += (1 - c.beta1) * g                 # Algorithm 2
+        v *= c.beta2; v += (1 - c.beta2) * g * g
+        mh = m / (1 - c.beta1 ** (self.t + 1))
+        vh = v / (1 - c.beta2 ** (self.t + 1))
+        w -= lr * mh / (np.sqrt(vh) + c.eps)
+
+    def step(self, tokens, targets, lr):
+        c, t, K = self.cfg, self.t, self.cfg.n_module
+        tokens = np.asarray(tokens); targets = np.asarray(targets)
+        if self.keep_history:
+            self.state_hist.append((copy.deepcopy(self.layers), self.V.copy(),
+                                    copy.deepcopy(self.mems), tokens.copy(), targets.copy()))
+        loss, grads, dVi, dVo, inputs = full_gradient(c, self.layers, self.V, tokens, targets, self.mems)
+        self.grad_hist.append((grads, dVi, dVo))
+        used = {}
+        for k in range(1, K + 1):                            # Eq. 8
+            tau = t - K + k
+            used[k] = tau if tau >= 0 else -1
+            for l in self.module_layers(k):
+                for name in self.layers[l]:
+                    g = self.grad_hist[tau][0][l][name] if tau >= 0 else np.zeros_like(self.layers[l][name])
+                    mm = self.m[l][name] if c.optimizer == 1 else None
+                    vv = self.v[l][name] if c.optimizer == 1 else None
+                    self._apply(self.layers[l][name], g, mm, vv, lr)
+        tau_i = t - K + 1                                    # Eq. 9
+        if tau_i >= 0:
+            gV = 0.5 * self.grad_hist[t][2] + 0.5 * self.grad_hist[tau_i][1]
+            used[0] = (t, tau_i)
+        elif c.embed_warm_mode == 1:
+            gV = 0.5 * self.grad_hist[t][2]
+            used[0] = (t, -1)
+        else:
+            gV = np.zeros_like(self.V)
+            used[0] = (-1, -1)
+        self._apply(self.V, gV, getattr(self, "mV", None), getattr(self, "vV", None), lr)
+        self.used.append(used)
+        if c.mem_len > 0:                                    # segment memory for step t+1
+            new = []
+            for l in range(c.n_layer):
+                cat = inputs[l] if self.mems is None else np.concatenate([self.mems[l], inputs[l]], axis=1)
+                new.append(cat[:, -c.mem_len:].copy())
+            self.mems = new
+        self.t += 1
+        return loss
+
+    def brute_check(self, t):
+        """Re-derive, from the stored full state of step tau, every gradient that the
+        update of iteration t consumed, and compare with what was used (Eq. 8-9)."""
+        K = self.cfg.n_module
+        worst = 0.0
+        for k in range(1, K + 1):
+            tau = t - K + k
+            assert self.used[t][k] == (tau if tau >= 0 else -1)
+            if tau < 0:
+                continue
+            layers, V, mems, tok, tgt = self.state_hist[tau]
+            _, grads, _, _, _ = full_gradient(self.cfg, layers, V, tok, tgt, mems)
+            for l in self.module_layers(k):
+                for name in grads[l]:
+                    worst = max(worst, float(np.abs(grads[l][name] - self.grad_hist[tau][0][l][name]).max()))
+        return worst

@@ -1,0 +1,213 @@
+"""Pins of the oracle's training iteration (Eq. 8, Eq. 9, Algorithm 1, Algorithm 2)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ouro_oracle as O
+import synth_inputs as S
+from tests import torch_ref
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def small_cfg(K, L=None, **kw):
+    base = dict(n_layer=L or K, d_model=8, n_head=2, d_head=4, d_ff=12, vocab=13, seq_len=5, batch=2,
+                n_module=K, mem_len=0, rel_pos=0, dtype=0, optimizer=0)
+    base.update(kw)
+    return base
+
+
+def make(K, seed=0, steps=8, **kw):
+    c = small_cfg(K, **kw)
+    cfg = O.Config(**c)
+    blobs = S.init_params(c, seed=seed, std=0.3, perturb=0.1)
+    tok, tgt = S.token_batches(c["vocab"], c["batch"], c["seq_len"], steps, 1.1, seed + 1,
+                               contiguous=bool(c["mem_len"]))
+    return c, cfg, blobs, tok, tgt
+
+
+def test_eq8_eq9_index_table_K4():
+    rows = [l.split() for l in open(os.path.join(GOLD, "eq8_index_table_K4.txt")) if not l.startswith("#")]
+    c, cfg, blobs, tok, tgt = make(4, steps=7)
+    orc = O.Oracle(cfg, blobs)
+    for t in range(7):
+        orc.step(tok[t], tgt[t], 0.05)
+    conv = lambda s: -1 if s == "-" else int(s)
+    for r in rows:
+        t = int(r[0])
+        for k in range(1, 5):
+            assert orc.used[t][k] == conv(r[k])
+        assert orc.used[t][0] == (conv(r[5]), conv(r[6]))
+
+
+@pytest.mark.parametrize("K", [1, 2, 3, 4])
+@pytest.mark.parametrize("opt", [0, 1])
+def test_brute_force_replay(K, opt):
+    """Every gradient consumed at iteration t equals the gradient recomputed from the
+    stored full state of iteration t-K+k; the weights follow by re-applying the
+    update rule outside the oracle."""
+    c, cfg, blobs, tok, tgt = make(K, seed=K, steps=K + 3, optimizer=opt)
+    orc = O.Oracle(cfg, blobs)
+    lr = 0.05 if opt == 0 else 0.01
+    # independent replay of Alg. 1 / Alg. 2 on flat module blobs
+    w = [np.asarray(b, np.float64).copy() for b in blobs]
+    m = [np.zeros_like(x) for x in w]; v = [np.zeros_like(x) for x in w]
+    for t in range(K + 3):
+        before = [orc.module_blob(k) for k in range(K + 1)]
+        for k in range(K + 1):
+            assert np.array_equal(before[k], w[k])
+        orc.step(tok[t], tgt[t], lr)
+        assert orc.brute_check(t) == 0.0
+        for k in range(K + 1):
+            if k == 0:
+                ti = t - K + 1
+                if ti >= 0:
+                    layers, V, mems, tk, tg = orc.state_hist[t]
+                    _, _, _, dVo, _ = O.full_gradient(cfg, layers, V, tk, tg, mems)
+                    layers, V, mems, tk, tg = orc.state_hist[ti]
+                    _, _, dVi, _, _ = O.full_gradient(cfg, layers, V, tk, tg, mems)
+                    g = (0.5 * dVo + 0.5 * dVi).ravel()
+                else:
+                    g = np.zeros_like(w[0])
+            else:
+                tau = t - K + k
+                if tau >= 0:
+                    layers, V, mems, tk, tg = orc.state_hist[tau]
+                    _, grads, _, _, _ = O.full_gradient(cfg, layers, V, tk, tg, mems)
+                    g = O.pack_layers(cfg, [grads[l] for l in orc.module_layers(k)])
+                else:
+                    g = np.zeros_like(w[k])
+            if opt == 0:
+                w[k] = w[k] - lr * g
+            else:
+                m[k] = 0.9 * m[k] + (1 - 0.9) * g
+                v[k] = 0.999 * v[k] + (1 - 0.999) * g * g
+                w[k] = w[k] - lr * (m[k] / (1 - 0.9 ** (t + 1))) / (np.sqrt(v[k] / (1 - 0.999 ** (t + 1))) + 1e-8)
+            assert np.abs(orc.module_blob(k) - w[k]).max() <= 1e-15 * max(1.0, np.abs(w[k]).max()), (t, k)
+            w[k] = orc.module_blob(k)
+
+
+def test_modules_frozen_until_first_gradient():
+    K = 4
+    c, cfg, blobs, tok, tgt = make(K, steps=6)
+    for opt in (0, 1):
+        cfg.optimizer = opt
+        orc = O.Oracle(cfg, blobs)
+        init = [orc.module_blob(k) for k in range(K + 1)]
+        for t in range(6):
+            orc.step(tok[t], tgt[t], 0.05)
+            for k in range(1, K + 1):
+                same = np.array_equal(orc.module_blob(k), init[k])
+                assert same == (t < K - k), (opt, t, k)       # first real update at t = K-k
+            assert np.array_equal(orc.module_blob(0), init[0]) == (t < K - 1)
+
+
+def test_embed_warm_mode_termwise():
+    K = 3
+    c, cfg, blobs, tok, tgt = make(K, steps=2, embed_warm_mode=1)
+    orc = O.Oracle(cfg, blobs)
+    V0 = orc.module_blob(0)
+    orc.step(tok[0], tgt[0], 0.1)
+    _, _, _, dVo = orc.grad_hist[0][0], None, None, orc.grad_hist[0][2]
+    assert np.abs(orc.module_blob(0) - (V0 - 0.1 * 0.5 * dVo.ravel())).max() < 1e-16
+    assert orc.used[0][0] == (0, -1)
+
+
+def test_tagged_gradient_plumbing(monkeypatch):
+    """Replace backprop by integer-tagged gradients g(t, group) so the final weights have
+    a closed form: w_k^T = -lr * sum over t with tau>=0 of (1000*tau + k)."""
+    K, T = 4, 9
+    c, cfg, blobs, tok, tgt = make(K, steps=T)
+    calls = {"t": 0}
+
+    def fake(cfg_, layers, V, tokens, targets, mems=None):
+        t = calls["t"]; calls["t"] += 1
+        bounds = np.concatenate([[0], np.cumsum(cfg_.layers_per_module)])
+        grads = []
+        for l, p in enumerate(layers):
+            k = int(np.searchsorted(bounds, l, side="right"))
+            grads.append({n: np.full_like(a, 1000.0 * t + k) for n, a in p.items()})
+        return 0.0, grads, np.full_like(V, 1000.0 * t + 0.25), np.full_like(V, 1000.0 * t + 0.75), [None] * len(layers)
+
+    monkeypatch.setattr(O, "full_gradient", fake)
+    zero = [np.zeros_like(b) for b in blobs]
+    orc = O.Oracle(cfg, zero)
+    lr = 2.0 ** -10
+    for t in range(T):
+        orc.step(tok[t], tgt[t], lr)
+    for k in range(1, K + 1):
+        expect = -lr * sum(1000.0 * (t - K + k) + k for t in range(T) if t - K + k >= 0)
+        assert np.all(orc.module_blob(k) == expect)
+    expect = -lr * sum(0.5 * (1000.0 * t + 0.75) + 0.5 * (1000.0 * (t - K + 1) + 0.25)
+                       for t in range(T) if t - K + 1 >= 0)
+    assert np.all(orc.module_blob(0) == expect)
+
+
+def test_sgd_linearity_and_tied_invariant():
+    K = 3
+    c, cfg, blobs, tok, tgt = make(K, steps=6)
+    orc = O.Oracle(cfg, blobs)
+    w0 = [orc.module_blob(k) for k in range(K + 1)]
+    lrs = [0.1, 0.05, 0.02, 0.07, 0.03, 0.01]
+    for t in range(6):
+        orc.step(tok[t], tgt[t], lrs[t])                      # the step uses gamma_t, not gamma_tau
+    for k in range(1, K + 1):
+        acc = sum(lrs[t] * orc.grad_blob(k, t - K + k) for t in range(6) if t - K + k >= 0)
+        assert np.abs(orc.module_blob(k) - (w0[k] - acc)).max() < 1e-14
+
+
+@pytest.mark.parametrize("opt", [0, 1])
+def test_K1_is_ordinary_backprop(opt):
+    """K=1: layer weights follow plain SGD/Adam on the autograd gradient; the tied matrix
+    receives the mean (half the sum) of its two gradients."""
+    c, cfg, blobs, tok, tgt = make(1, L=2, steps=3, optimizer=opt)
+    orc = O.Oracle(cfg, blobs)
+    tl = [{n: torch.tensor(a.copy(), requires_grad=True) for n, a in p.items()} for p in orc.layers]
+    tV = torch.tensor(orc.V.copy(), requires_grad=True)
+    params = [x for p in tl for x in p.values()] + [tV]
+    lr = 0.05 if opt == 0 else 0.01
+    optim = torch.optim.SGD(params, lr=lr) if opt == 0 else torch.optim.Adam(params, lr=lr, betas=(0.9, 0.999), eps=1e-8)
+    for t in range(3):
+        lo = orc.step(tok[t], tgt[t], lr)
+        Vi = tV.detach().clone().requires_grad_(True)
+        Vo = tV.detach().clone().requires_grad_(True)
+        optim.zero_grad()
+        loss, _ = torch_ref.forward(cfg, tl, Vi, Vo, torch.tensor(tok[t]), torch.tensor(tgt[t]))
+        loss.backward()
+        tV.grad = 0.5 * (Vi.grad + Vo.grad)
+        optim.step()
+        assert abs(lo - loss.item()) < 1e-12
+        for l in range(2):
+            for n in tl[l]:
+                assert np.abs(orc.layers[l][n] - tl[l][n].detach().numpy()).max() < 1e-10, (t, l, n)
+        assert np.abs(orc.V - tV.detach().numpy()).max() < 1e-10
+
+
+def test_adam_closed_forms():
+    cfg = O.Config(**small_cfg(1, optimizer=1))
+    orc = O.Oracle(cfg, S.init_params(small_cfg(1), seed=0))
+    w = np.array([1.0, -2.0, 3.0]); g = np.array([0.5, -4.0, 1e-3])
+    m = np.zeros(3); v = np.zeros(3)
+    orc._apply(w, g, m, v, 0.1)                                # t = 0: dw = -lr * g / (|g| + eps)
+    assert np.abs(w - (np.array([1.0, -2.0, 3.0]) - 0.1 * g / (np.abs(g) + 1e-8))).max() < 1e-15
+    w2 = np.array([1.0, -2.0]); m2 = np.zeros(2); v2 = np.zeros(2)
+    orc._apply(w2, np.zeros(2), m2, v2, 0.1)                   # zero gradient, zero moments: no change
+    assert np.array_equal(w2, [1.0, -2.0]) and not m2.any() and not v2.any()
+
+
+def test_xl_memory_carry():
+    c = small_cfg(2, L=2, rel_pos=1, mem_len=7)
+    cfg = O.Config(**c)
+    blobs = S.init_params(c, seed=3, std=0.3)
+    tok, tgt = S.token_batches(13, 2, 5, 3, 1.1, 4, contiguous=True)
+    assert np.array_equal(tok[1][:, 0], tgt[0][:, -1])          # streams are contiguous
+    orc = O.Oracle(cfg, blobs)
+    orc.step(tok[0], tgt[0], 0.05)
+    assert orc.mems[0].shape == (2, 5, 8)                       # valid length min(M, T) after one step
+    first_inputs = orc.mems[0].copy()
+    orc.step(tok[1], tgt[1], 0.05)
+    assert orc.mems[0].shape == (2, 7, 8)                       # last 7 rows of [old ; new]
+    assert np.array_equal(orc.mems[0][:, :2], first_inputs[:, 3:])
+    assert orc.brute_check(1) == 0.0
