@@ -1,0 +1,83 @@
+/* ouro_ops.h -- single-kernel entry points of libouro, for per-kernel parity tests and
+ * micro-benchmarks.  Every pointer is a device address unless named host_*; work is
+ * enqueued on `stream` (a hipStream_t, NULL = null stream) and the call returns at once.
+ * dtype: 0 = fp32 elements, 1 = bf16 elements ("T" below).  Returns OURO_OK or a negative
+ * OURO_E_* code (see ouro.h); buffers are owned by the caller.
+ */
+#ifndef OURO_OPS_H
+#define OURO_OPS_H
+#include <stddef.h>
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* C[M,N] = alpha * op(A) op(B) with fp32 accumulation, then
+ *   + bias[n] (fp32, may be NULL); epilogue 1: Z = v (type T), v = GELU(v);
+ *   epilogue 2: v *= GELU'(Z) ; + residual[m,n] (type T, may be NULL); stored as T, or
+ *   as fp32 when out_fp32; accumulate != 0 adds atomically into fp32 C instead
+ *   (no bias / residual / epilogue then).
+ * transA == 0: A is [M,K] row-major with leading dimension lda; 1: A is [K,M].
+ * transB == 0: B is [K,N]; 1: B is [N,K].  force_generic != 0 bypasses the MFMA kernel.
+ * These are the layer contractions of Eq. 2 / Eq. 6 (forward, input- and weight-gradient). */
+int ouro_op_gemm(void* stream, int dtype, int transA, int transB, int M, int N, int K, float alpha,
+                 const void* A, int lda, const void* B, int ldb, void* C, int ldc, int out_fp32,
+                 int accumulate, const float* bias, const void* residual, int ldr, int epilogue,
+                 void* Z, int ldz, int force_generic);
+/* 1 if ouro_op_gemm would run the MFMA kernel for these arguments (host only). */
+int ouro_op_gemm_uses_mfma(int dtype, int transA, int transB, int M, int N, int K, const void* A,
+                           int lda, const void* B, int ldb);
+
+/* Causal attention over [memory ; segment].  q, o, d_o, dq: rows b*T+i; k, v, dk, dv: rows
+ * b*S+j with S = Mv+T; head h in columns [h*dh, (h+1)*dh) of a row (ld* in elements).
+ * Query i sits at position Mv+i and sees keys j <= Mv+i.  lse: fp32 [B,H,T].
+ * rel != 0: score = ((q+u_h).k_j + (q+vb_h).r_h[Mv+i-j]) * scale, with u, vb [H,dh] (T) and
+ * r [S, H*dh] (T) indexed by distance; else score = q.k_j * scale. */
+int ouro_op_attention_fwd(void* stream, int dtype, int B, int H, int T, int S, int dh, int Mv,
+                          float scale, const void* q, int ldq, const void* k, int ldk,
+                          const void* v, int ldv, void* o, int ldo, float* lse, int rel,
+                          const void* u, const void* vb, const void* r, int ldr, int force_generic);
+/* Backward of the above.  du, dvb (fp32 [H,dh]) and dr (fp32 [S, H*dh]) are overwritten when
+ * rel != 0 (may be NULL otherwise).  scratch: fp32, ouro_op_attention_bwd_scratch() floats. */
+int ouro_op_attention_bwd(void* stream, int dtype, int B, int H, int T, int S, int dh, int Mv,
+                          float scale, const void* q, int ldq, const void* k, int ldk,
+                          const void* v, int ldv, const void* o, int ldo, const float* lse,
+                          const void* d_o, int lddo, void* dq, int lddq, void* dk, int lddk,
+                          void* dv, int lddv, int rel, const void* u, const void* vb, const void* r,
+                          int ldr, float* du, float* dvb, float* dr, float* scratch, int force_generic);
+size_t ouro_op_attention_bwd_scratch(int B, int H, int T, int S, int dh);
+
+/* y = (x-mean)*rstd*g + b over rows of d (biased variance, eps 1e-5); g, b, mean, rstd fp32. */
+int ouro_op_layernorm_fwd(void* stream, int dtype, const void* x, const float* g, const float* b,
+                          void* y, float* mean, float* rstd, int rows, int d);
+/* dx (T) and dg, db (fp32 [d], overwritten). */
+int ouro_op_layernorm_bwd(void* stream, int dtype, const void* dy, const void* x, const float* g,
+                          const float* mean, const float* rstd, void* dx, float* dg, float* db,
+                          int rows, int d);
+/* out[c] = sum_r x[r,c]  (fp32 [cols], overwritten). */
+int ouro_op_colsum(void* stream, int dtype, const void* x, int ldx, float* out, int rows, int cols);
+/* h[n,:] = scale*V[tok[n],:] (+ pe[n%T,:], fp32, may be NULL).  *flag (device int) gets bit 0 set
+ * for ids outside [0,vocab), whose rows become zero (Eq. 1). */
+int ouro_op_embed_fwd(void* stream, int dtype, const int32_t* tok, const void* V, const float* pe,
+                      void* h, int N, int T, int d, int vocab, float scale, int* flag);
+/* dVi (fp32 [vocab,d], overwritten) = scatter-add of scale*dh rows (Eq. 7, left). */
+int ouro_op_embed_bwd(void* stream, int dtype, const int32_t* tok, const void* dh, float* dVi,
+                      int N, int d, int vocab, float scale);
+/* Rows of fp32 logits [N, ld]: lse[n]; rowloss[n] = lse - logit[tgt]; G (T, [N, ldg]) =
+ * (softmax - onehot)/N; *loss = mean(rowloss) (Eq. 4).  flag bit 1: target out of range. */
+int ouro_op_softmax_ce(void* stream, int dtype, const float* logits, int ld, const int32_t* tgt,
+                       void* G, int ldg, float* lse, float* rowloss, float* loss, int N, int vocab,
+                       int* flag);
+/* Algorithm 1 (adam == 0) or Algorithm 2 on n fp32 elements with g = s0*g0 + s1*g1 (NULL = 0);
+ * t is the global iteration (bias correction 1-beta^(t+1)); shadow (bf16 copy of w) may be NULL. */
+int ouro_op_update(void* stream, float* w, float* m, float* v, void* shadow, const float* g0,
+                   float s0, const float* g1, float s1, size_t n, int adam, float lr, float beta1,
+                   float beta2, float eps, int64_t t);
+/* dst (type T) = src (fp32), n elements; and back. */
+int ouro_op_from_f32(void* stream, int dtype, void* dst, const float* src, size_t n);
+int ouro_op_to_f32(void* stream, int dtype, float* dst, const void* src, size_t n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

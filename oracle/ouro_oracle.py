@@ -158,10 +158,60 @@ def merge_heads(x):
 
 
 # --------------------------------------------------------------------------- attention
+def attention_core_fwd(q, k, v, Mv, scale, u=None, vb=None, r=None):
+    """Causal attention on projected heads.  q [B,H,T,dh]; k, v [B,H,S,dh], S = Mv+T.
+    Query i sits at absolute position Mv+i and sees keys j <= Mv+i.  With u, vb [H,dh] and
+    r [H,S,dh] (row = relative distance) the score is the Transformer-XL form
+    (q_i+u).k_j + (q_i+vb).r[Mv+i-j], indexed directly by distance (no shift trick)."""
+    T, S = q.shape[2], k.shape[2]
+    delta = Mv + np.arange(T)[:, None] - np.arange(S)[None, :]     # p_i - p_j
+    visible = delta >= 0
+    c = dict(q=q, k=k, v=v, Mv=Mv, visible=visible, delta=delta, scale=scale, rel=r is not None)
+    if r is not None:
+        qu = q + u[None, :, None, :]
+        qv = q + vb[None, :, None, :]
+        AC = qu @ k.transpose(0, 1, 3, 2)                          # [B,H,T,S]
+        QR = np.einsum("bhic,hpc->bhip", qv, r)                    # [B,H,T,S] indexed by distance
+        dcl = np.where(visible, delta, 0)
+        BD = np.take_along_axis(QR, np.broadcast_to(dcl, QR.shape), axis=3)
+        s = (AC + BD) * scale
+        c.update(r=r, qu=qu, qv=qv)
+    else:
+        s = (q @ k.transpose(0, 1, 3, 2)) * scale
+    s = np.where(visible, s, -np.inf)
+    mx = s.max(axis=-1, keepdims=True)
+    e = np.exp(s - mx)
+    den = e.sum(axis=-1, keepdims=True)
+    P = e / den
+    c.update(P=P, lse=(mx + np.log(den))[..., 0])
+    return P @ v, c
+
+
+def attention_core_bwd(do, c):
+    """Gradients of attention_core_fwd's output w.r.t. q, k, v (and u, vb, r)."""
+    q, k, v, P, scale = c["q"], c["k"], c["v"], c["P"], c["scale"]
+    dv = P.transpose(0, 1, 3, 2) @ do
+    dP = do @ v.transpose(0, 1, 3, 2)
+    dS = P * (dP - (dP * P).sum(axis=-1, keepdims=True))
+    dS = np.where(c["visible"], dS, 0.0) * scale
+    if not c["rel"]:
+        return dS @ k, dS.transpose(0, 1, 3, 2) @ q, dv, None, None, None
+    r, qu, qv = c["r"], c["qu"], c["qv"]
+    dqu = dS @ k
+    dk = dS.transpose(0, 1, 3, 2) @ qu
+    # dS[b,h,i,j] belongs to relative distance delta(i,j); for a fixed i the map
+    # j -> delta is one-to-one over the visible keys, so plain assignment is exact
+    dQR = np.zeros_like(dS)
+    ii, jj = np.nonzero(c["visible"])
+    dQR[:, :, ii, c["delta"][ii, jj]] = dS[:, :, ii, jj]
+    dqv = np.einsum("bhip,hpc->bhic", dQR, r)
+    dr = np.einsum("bhip,bhic->hpc", dQR, qv)                      # [H,S,dh]
+    return dqu + dqv, dk, dv, dqu.sum(axis=(0, 2)), dqv.sum(axis=(0, 2)), dr
+
+
 def attention_fwd(cfg, p, x, mem):
     """Self-attention of one layer.  x [B,T,d] current segment, mem [B,Mv,d] or None
-    (a constant: previous inputs of this layer).  Query i sits at absolute position
-    Mv+i and sees keys j <= Mv+i of [mem ; x]."""
+    (a constant: previous inputs of this layer); keys and values span [mem ; x]."""
     B, T, d = x.shape
     H, dh = cfg.n_head, cfg.d_head
     Mv = 0 if mem is None else mem.shape[1]
@@ -172,70 +222,35 @@ def attention_fwd(cfg, p, x, mem):
     k = split_heads(cat @ Wk, H, dh)          # [B,H,S,dh]
     v = split_heads(cat @ Wv, H, dh)
     scale = 1.0 / math.sqrt(dh)
-    i_idx = np.arange(T)[:, None]
-    j_idx = np.arange(S)[None, :]
-    delta = Mv + i_idx - j_idx                # relative distance p_i - p_j
-    visible = delta >= 0
-    cache = dict(x=x, cat=cat, q=q, k=k, v=v, Mv=Mv, visible=visible, delta=delta)
     if cfg.rel_pos:
-        R = sinusoid(np.arange(S), d)                         # R_delta, delta = 0..S-1
-        r = (R @ p["W_r"]).reshape(S, H, dh).transpose(1, 0, 2)   # [H,S,dh]
-        qu = q + p["u"][None, :, None, :]
-        qv = q + p["v"][None, :, None, :]
-        AC = qu @ k.transpose(0, 1, 3, 2)                     # [B,H,T,S]
-        QR = np.einsum("bhic,hpc->bhip", qv, r)               # [B,H,T,S] indexed by delta
-        dcl = np.where(visible, delta, 0)
-        BD = np.take_along_axis(QR, np.broadcast_to(dcl, QR.shape), axis=3)
-        s = (AC + BD) * scale
-        cache.update(R=R, r=r, qu=qu, qv=qv, dcl=dcl)
+        R = sinusoid(np.arange(S), d)                               # R_delta, delta = 0..S-1
+        r = (R @ p["W_r"]).reshape(S, H, dh).transpose(1, 0, 2)     # [H,S,dh]
+        oh, cc = attention_core_fwd(q, k, v, Mv, scale, p["u"], p["v"], r)
+        cc["R"] = R
     else:
-        s = (q @ k.transpose(0, 1, 3, 2)) * scale
-    s = np.where(visible, s, -np.inf)
-    s = s - s.max(axis=-1, keepdims=True)
-    e = np.exp(s)
-    P = e / e.sum(axis=-1, keepdims=True)
-    a = merge_heads(P @ v)                                    # [B,T,d]
-    o = a @ p["W_o"]
-    cache.update(P=P, a=a, scale=scale)
-    return o, cache
+        oh, cc = attention_core_fwd(q, k, v, Mv, scale)
+    a = merge_heads(oh)                                             # [B,T,d]
+    cc.update(x=x, cat=cat, a=a)
+    return a @ p["W_o"], cc
 
 
 def attention_bwd(cfg, p, do, c):
     d = cfg.d_model
     H, dh = cfg.n_head, cfg.d_head
-    x, cat, q, k, v, P, a, Mv, scale = (c[n] for n in ("x", "cat", "q", "k", "v", "P", "a", "Mv", "scale"))
-    B, T, _ = x.shape
+    x, cat, a, Mv = c["x"], c["cat"], c["a"], c["Mv"]
     g = {}
     g["W_o"] = a.reshape(-1, d).T @ do.reshape(-1, d)
-    da = split_heads(do @ p["W_o"].T, H, dh)                  # [B,H,T,dh]
-    dv = P.transpose(0, 1, 3, 2) @ da
-    dP = da @ v.transpose(0, 1, 3, 2)
-    dS = P * (dP - (dP * P).sum(axis=-1, keepdims=True))
-    dS = np.where(c["visible"], dS, 0.0) * scale
+    da = split_heads(do @ p["W_o"].T, H, dh)                        # [B,H,T,dh]
+    dq, dk, dv, du, dvb, dr = attention_core_bwd(da, c)
     if cfg.rel_pos:
-        r, qu, qv, R = c["r"], c["qu"], c["qv"], c["R"]
-        dqu = dS @ k
-        dk = dS.transpose(0, 1, 3, 2) @ qu
-        # dS[b,h,i,j] belongs to relative distance delta(i,j); for a fixed i the map
-        # j -> delta is one-to-one over the visible keys, so plain assignment is exact
-        dQR = np.zeros_like(dS)
-        ii, jj = np.nonzero(c["visible"])
-        dQR[:, :, ii, c["delta"][ii, jj]] = dS[:, :, ii, jj]
-        dqv = np.einsum("bhip,hpc->bhic", dQR, r)
-        dr = np.einsum("bhip,bhic->hpc", dQR, qv)             # [H,S,dh]
-        g["u"] = dqu.sum(axis=(0, 2))
-        g["v"] = dqv.sum(axis=(0, 2))
-        g["W_r"] = R.T @ dr.transpose(1, 0, 2).reshape(-1, d)
-        dq = dqu + dqv
-    else:
-        dq = dS @ k
-        dk = dS.transpose(0, 1, 3, 2) @ q
+        g["u"], g["v"] = du, dvb
+        g["W_r"] = c["R"].T @ dr.transpose(1, 0, 2).reshape(-1, d)
     dq, dk, dv = merge_heads(dq), merge_heads(dk), merge_heads(dv)
     x2, cat2 = x.reshape(-1, d), cat.reshape(-1, d)
     g["W_qkv"] = np.concatenate([x2.T @ dq.reshape(-1, d), cat2.T @ dk.reshape(-1, d),
                                  cat2.T @ dv.reshape(-1, d)], axis=1)
     Wq, Wk, Wv = p["W_qkv"][:, :d], p["W_qkv"][:, d:2 * d], p["W_qkv"][:, 2 * d:]
-    dx = dq @ Wq.T + (dk[:, Mv:] @ Wk.T) + (dv[:, Mv:] @ Wv.T)    # memory is a constant
+    dx = dq @ Wq.T + (dk[:, Mv:] @ Wk.T) + (dv[:, Mv:] @ Wv.T)      # memory is a constant
     return dx, g
 
 
@@ -267,6 +282,22 @@ def layer_bwd(cfg, p, dh, c):
 
 
 # ------------------------------------------------------------------------------- model
+def cross_entropy_fwd(logits, targets):
+    """Eq. 4 with f = mean over all targets of (logsumexp(logits) - logit[target])."""
+    mx = logits.max(axis=-1, keepdims=True)
+    lse = mx[..., 0] + np.log(np.exp(logits - mx).sum(axis=-1))
+    tgt_logit = np.take_along_axis(logits, targets[..., None].astype(np.int64), axis=-1)[..., 0]
+    return float((lse - tgt_logit).mean()), lse
+
+
+def cross_entropy_bwd(logits, lse, targets):
+    """d loss / d logits = (softmax - onehot) / (number of targets)."""
+    G = np.exp(logits - lse[..., None])
+    idx = targets[..., None].astype(np.int64)
+    np.put_along_axis(G, idx, np.take_along_axis(G, idx, axis=-1) - 1.0, axis=-1)
+    return G / targets.size
+
+
 def model_forward(cfg, layers, Vi, Vo, tokens, targets, mems=None):
     """Eq. 1-4.  Returns loss (mean over all B*T targets, natural log) and a cache."""
     B, T = tokens.shape
@@ -280,10 +311,7 @@ def model_forward(cfg, layers, Vi, Vo, tokens, targets, mems=None):
         h, c = layer_fwd(cfg, p, h, None if mems is None else mems[l])
         caches.append(c)
     logits = h @ Vo.T                                         # Eq. 3: V_o leaves layer L
-    mx = logits.max(axis=-1, keepdims=True)
-    lse = mx[..., 0] + np.log(np.exp(logits - mx).sum(axis=-1))
-    tgt_logit = np.take_along_axis(logits, targets[..., None].astype(np.int64), axis=-1)[..., 0]
-    loss = float((lse - tgt_logit).mean())
+    loss, lse = cross_entropy_fwd(logits, targets)
     return loss, dict(inputs=inputs, caches=caches, hL=h, logits=logits, lse=lse)
 
 
@@ -292,10 +320,7 @@ def model_backward(cfg, layers, Vi, Vo, tokens, targets, fw):
     B, T = tokens.shape
     N = B * T
     d = cfg.d_model
-    G = np.exp(fw["logits"] - fw["lse"][..., None])
-    np.put_along_axis(G, targets[..., None].astype(np.int64),
-                      np.take_along_axis(G, targets[..., None].astype(np.int64), axis=-1) - 1.0, axis=-1)
-    G /= N
+    G = cross_entropy_bwd(fw["logits"], fw["lse"], targets)
     dVo = G.reshape(N, -1).T @ fw["hL"].reshape(N, d)
     dh = G @ Vo
     grads = [None] * len(layers)

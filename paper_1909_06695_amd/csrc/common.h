@@ -1,0 +1,130 @@
+// Internal declarations shared by the HIP translation units of libouro (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+typedef __bf16 bf16_t;
+
+namespace ouro {
+
+// ----------------------------------------------------------------------------- helpers
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return (float)x; }
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return (bf16_t)x; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// exact GELU x*Phi(x) and its derivative Phi(x) + x*phi(x)
+__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float x) {
+  return 0.5f * (1.0f + erff(x * 0.70710678118654752f)) + x * 0.3989422804014327f * __expf(-0.5f * x * x);
+}
+
+// --------------------------------------------------------------------------------- GEMM
+// C[M,N] = op(A)[M,K] * op(B)[K,N], fp32 accumulation, then the epilogue
+//   v = acc (+ bias[n]); EPI_GELU: Z[m,n] = v, v = gelu(v); EPI_GELUGRAD: v *= gelu'(Z[m,n]);
+//   (+ residual[m,n]); store as T or fp32, or atomically add to fp32 C (split-K).
+// transA == 0: A stored [M,K] (lda >= K); transA == 1: A stored [K,M] (lda >= M).
+// transB == 0: B stored [K,N] (ldb >= N); transB == 1: B stored [N,K] (ldb >= K).
+enum { EPI_NONE = 0, EPI_GELU = 1, EPI_GELUGRAD = 2 };
+struct GemmDesc {
+  const void* A; const void* B; void* C;
+  int M, N, K, lda, ldb, ldc;
+  int transA, transB;
+  int out_fp32;          // C element type: 1 fp32, 0 same as inputs
+  int accumulate;        // 1: C (fp32) += result (atomic, allows split-K); else overwrite
+  const float* bias;     // [N] or null
+  const void* residual;  // [M, ldr] element type T, or null
+  int ldr;
+  int epilogue;
+  void* Z; int ldz;      // EPI_GELU: written (type T); EPI_GELUGRAD: read (type T)
+  float alpha;           // scales acc before the epilogue
+};
+// dtype 0: fp32 operands, 1: bf16 operands.  force_generic != 0 skips the MFMA kernel.
+hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_generic);
+// true if launch_gemm would take the MFMA path for this problem
+bool gemm_uses_mfma(int dtype, const GemmDesc& g);
+
+// ---------------------------------------------------------------------------- attention
+// q rows: (b*T + i), head h at columns [h*dh, (h+1)*dh) of a row of stride ldq elements.
+// k, v rows: (b*S + j), S = Mv + T keys per stream; query i sits at position Mv + i and
+// sees keys j <= Mv + i.  o like q.  lse [B,H,T] fp32 = log-sum-exp of the scaled scores.
+// Relative variant (rel != 0): score = ((q+u_h).k_j + (q+vb_h).r_h[Mv+i-j]) * scale, with
+// r rows indexed by distance (0..S-1), head h at columns [h*dh,..) of stride ldr.
+struct AttnDesc {
+  int B, H, T, S, dh, Mv;
+  const void* q; int ldq;
+  const void* k; int ldk;
+  const void* v; int ldv;
+  void* o; int ldo;
+  float* lse;
+  int rel;
+  const void* u; const void* vb;   // [H, dh] element type T
+  const void* r; int ldr;          // [S, H*dh] element type T
+  float scale;
+  // backward only
+  const void* d_o; int lddo;       // gradient of o
+  void* dq; int lddq;              // type T
+  void* dk; int lddk;              // type T, rows b*S + j
+  void* dv; int lddv;
+  float* du; float* dvb;           // fp32 [H, dh], accumulated into (caller zeroes)
+  float* dr;                       // fp32 [S, H*dh] dense, accumulated into (caller zeroes)
+  float* scratch;                  // fp32 workspace, attn_bwd_scratch_floats() elements
+};
+size_t attn_bwd_scratch_floats(int B, int H, int T, int S, int dh);
+hipError_t launch_attn_fwd(hipStream_t s, int dtype, const AttnDesc& a, int force_generic);
+hipError_t launch_attn_bwd(hipStream_t s, int dtype, const AttnDesc& a, int force_generic);
+
+// -------------------------------------------------------------------- row-wise kernels
+// y = LN(x) * g + b over rows of d elements (biased variance, eps 1e-5); saves mean, rstd.
+hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, const void* x, const float* g, const float* b,
+                                void* y, float* mean, float* rstd, int rows, int d);
+// dx from dy, x, stats; dg/db (fp32) are accumulated into (caller zeroes).
+hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const float* g,
+                                const float* mean, const float* rstd, void* dx, float* dg, float* db,
+                                int rows, int d);
+// out[c] += sum over rows of x[r, c]  (fp32 accumulate into, caller zeroes)
+hipError_t launch_colsum(hipStream_t s, int dtype, const void* x, int ldx, float* out, int rows, int cols);
+// h[n,:] = scale * V[tok[n],:] (+ pe[n % T,:]); ids outside [0,vocab) set *flag and give a zero row
+hipError_t launch_embed_fwd(hipStream_t s, int dtype, const int32_t* tok, const void* V, const float* pe,
+                            void* h, int N, int T, int d, int vocab, float scale, int* flag);
+// dVi[tok[n],:] += scale * dh[n,:]   (fp32 atomics; caller zeroes dVi)
+hipError_t launch_embed_bwd(hipStream_t s, int dtype, const int32_t* tok, const void* dh, float* dVi,
+                            int N, int d, int vocab, float scale);
+// per row n of logits [N, ld] (fp32): lse, rowloss = lse - logit[target]; G = (softmax - onehot)/N as T
+hipError_t launch_ce_rows(hipStream_t s, int dtype, const float* logits, int ld, const int32_t* tgt,
+                          void* G, int ldg, float* lse, float* rowloss, int N, int vocab, int* flag);
+// loss = sum(rowloss) (fixed order, one block)
+hipError_t launch_sum_rows(hipStream_t s, const float* rowloss, int N, float* loss);
+hipError_t launch_convert(hipStream_t s, int dtype_dst, void* dst, const float* src, size_t n);      // fp32 -> T
+hipError_t launch_to_f32(hipStream_t s, int dtype_src, float* dst, const void* src, size_t n);       // T -> fp32
+hipError_t launch_fill_zero(hipStream_t s, void* p, size_t bytes);                                   // bytes % 4 == 0
+// strided row copy: dst[b, r, :] = src[b, r0 + r, :]; rows of d elements of type T
+hipError_t launch_copy_rows(hipStream_t s, int dtype, void* dst, size_t dst_bstride, size_t dst_off,
+                            const void* src, size_t src_bstride, size_t src_off, int B, int rows, int d);
+
+// ------------------------------------------------------------------------------ update
+// Algorithm 1 / Algorithm 2 on n elements.  g = gscale0*g0 + gscale1*g1 (null pointers
+// count as zero).  Adam: bias corrections bc1 = 1-beta1^(t+1), bc2 = 1-beta2^(t+1).
+// shadow (bf16) may be null.
+struct UpdateDesc {
+  float* w; float* m; float* v; bf16_t* shadow;
+  const float* g0; const float* g1; float gscale0, gscale1;
+  size_t n; int adam;
+  float lr, beta1, beta2, eps, bc1, bc2;
+};
+hipError_t launch_update(hipStream_t s, const UpdateDesc& u);
+
+}  // namespace ouro

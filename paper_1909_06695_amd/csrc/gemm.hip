@@ -1,0 +1,359 @@
+// Dense contractions of the training step: a bf16 MFMA kernel (LDS double-buffered,
+// XOR-swizzled tiles, 32x32x16 matrix instructions, 64-wide wavefronts) and a plain
+// bounds-checked tiled kernel for fp32 operands and shapes the MFMA kernel does not take.
+#include "common.h"
+
+namespace ouro {
+
+struct GemmParams {
+  const void* A; const void* B; void* C;
+  int M, N, K, lda, ldb, ldc;
+  int out_fp32, accumulate;
+  const float* bias;
+  const void* residual; int ldr;
+  int epilogue;
+  void* Z; int ldz;
+  float alpha;
+  int kchunk;      // K range per blockIdx.z
+  int tilesN;      // tiles along N (MFMA kernel)
+};
+
+template <typename T>
+__device__ __forceinline__ void epilogue_store(const GemmParams& p, int m, int n, float acc) {
+  float v = acc * p.alpha;
+  if (p.accumulate) {
+    unsafeAtomicAdd(reinterpret_cast<float*>(p.C) + (size_t)m * p.ldc + n, v);
+    return;
+  }
+  if (p.bias) v += p.bias[n];
+  if (p.epilogue == EPI_GELU) {
+    reinterpret_cast<T*>(p.Z)[(size_t)m * p.ldz + n] = from_f32<T>(v);
+    v = gelu_f(v);
+  } else if (p.epilogue == EPI_GELUGRAD) {
+    v *= gelu_grad_f(to_f32(reinterpret_cast<const T*>(p.Z)[(size_t)m * p.ldz + n]));
+  }
+  if (p.residual) v += to_f32(reinterpret_cast<const T*>(p.residual)[(size_t)m * p.ldr + n]);
+  if (p.out_fp32) reinterpret_cast<float*>(p.C)[(size_t)m * p.ldc + n] = v;
+  else reinterpret_cast<T*>(p.C)[(size_t)m * p.ldc + n] = from_f32<T>(v);
+}
+
+// ------------------------------------------------------------------ plain tiled kernel
+template <typename T, bool TA, bool TB>
+__global__ __launch_bounds__(256) void gemm_plain_kernel(GemmParams p) {
+  constexpr int BM = 64, BN = 64, BK = 16;
+  __shared__ float As[BK][BM + 4];
+  __shared__ float Bs[BK][BN + 4];
+  const T* A = reinterpret_cast<const T*>(p.A);
+  const T* B = reinterpret_cast<const T*>(p.B);
+  const int tid = threadIdx.x;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int kbeg = blockIdx.z * p.kchunk;
+  const int kend = min(p.K, kbeg + p.kchunk);
+  const int tx = tid % 16, ty = tid / 16;
+  float acc[4][4] = {};
+  for (int k0 = kbeg; k0 < kend; k0 += BK) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int e = tid + i * 256;                 // 0..1023
+      int mm, kk;
+      if (TA) { mm = e % BM; kk = e / BM; } else { kk = e % BK; mm = e / BK; }
+      int gm = m0 + mm, gk = k0 + kk;
+      float v = 0.f;
+      if (gm < p.M && gk < kend) v = to_f32(TA ? A[(size_t)gk * p.lda + gm] : A[(size_t)gm * p.lda + gk]);
+      As[kk][mm] = v;
+      int nn, kb;
+      if (TB) { kb = e % BK; nn = e / BK; } else { nn = e % BN; kb = e / BN; }
+      int gn = n0 + nn; gk = k0 + kb;
+      v = 0.f;
+      if (gn < p.N && gk < kend) v = to_f32(TB ? B[(size_t)gn * p.ldb + gk] : B[(size_t)gk * p.ldb + gn]);
+      Bs[kb][nn] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < BK; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+      if (m < p.M && n < p.N) epilogue_store<T>(p, m, n, acc[i][j]);
+    }
+}
+
+// ------------------------------------------------------------------------- MFMA kernel
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+// 16-byte chunk c (8 bf16 along k) of tile row `row` lives at chunk c ^ swz(row) of that
+// row's 128 bytes: conflict-free for the per-row operand reads and for the transposing
+// writes alike.
+__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
+
+// Row-form operand: element (row, k) at src[row*ld + k] (k contiguous).
+template <int ROWS, int NT>
+__device__ __forceinline__ void load_rowform(const bf16_t* __restrict__ src, int ld, int row0, int rmax,
+                                             int k0, int kend, int tid, uint4* reg) {
+  constexpr int PER = ROWS * 8 / NT;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    int c = tid + i * NT;
+    int row = c >> 3, kc = c & 7;
+    int gr = row0 + row, gk = k0 + kc * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (gr < rmax && gk < kend) v = *reinterpret_cast<const uint4*>(src + (size_t)gr * ld + gk);
+    reg[i] = v;
+  }
+}
+template <int ROWS, int NT>
+__device__ __forceinline__ void store_rowform(uint4* lds, int tid, const uint4* reg) {
+  constexpr int PER = ROWS * 8 / NT;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    int c = tid + i * NT;
+    int row = c >> 3, kc = c & 7;
+    lds[row * 8 + (kc ^ swz(row))] = reg[i];
+  }
+}
+// Column-form operand: element (row, k) at src[k*ld + row] (row contiguous).  A thread
+// takes a 4(k) x 8(row) block: four 16-byte loads, transposed in registers into eight
+// 8-byte pieces (4 consecutive k for one row each).
+template <int ROWS, int NT>
+__device__ __forceinline__ void load_colform(const bf16_t* __restrict__ src, int ld, int row0, int rmax,
+                                             int k0, int kend, int tid, uint4* reg) {
+  constexpr int NBLK = 16 * (ROWS / 8);
+  constexpr int PER = NBLK / NT;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    int blk = tid + i * NT;
+    int rb = blk % (ROWS / 8), kb = blk / (ROWS / 8);
+    int gr = row0 + rb * 8;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      int gk = k0 + kb * 4 + kk;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (gr < rmax && gk < kend) v = *reinterpret_cast<const uint4*>(src + (size_t)gk * ld + gr);
+      reg[i * 4 + kk] = v;
+    }
+  }
+}
+template <int ROWS, int NT>
+__device__ __forceinline__ void store_colform(uint4* lds, int tid, const uint4* reg) {
+  constexpr int NBLK = 16 * (ROWS / 8);
+  constexpr int PER = NBLK / NT;
+  uint2* l2 = reinterpret_cast<uint2*>(lds);
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    int blk = tid + i * NT;
+    int rb = blk % (ROWS / 8), kb = blk / (ROWS / 8);
+    const uint32_t* w0 = reinterpret_cast<const uint32_t*>(&reg[i * 4 + 0]);
+    const uint32_t* w1 = reinterpret_cast<const uint32_t*>(&reg[i * 4 + 1]);
+    const uint32_t* w2 = reinterpret_cast<const uint32_t*>(&reg[i * 4 + 2]);
+    const uint32_t* w3 = reinterpret_cast<const uint32_t*>(&reg[i * 4 + 3]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {           // dword j holds rows 2j (low half) and 2j+1 (high half)
+      uint2 even, odd;
+      even.x = (w0[j] & 0xffffu) | (w1[j] << 16);
+      even.y = (w2[j] & 0xffffu) | (w3[j] << 16);
+      odd.x = (w0[j] >> 16) | (w1[j] & 0xffff0000u);
+      odd.y = (w2[j] >> 16) | (w3[j] & 0xffff0000u);
+      int r0 = rb * 8 + 2 * j, r1 = r0 + 1;
+      int kc = kb >> 1, half = kb & 1;
+      l2[(r0 * 8 + (kc ^ swz(r0))) * 2 + half] = even;
+      l2[(r1 * 8 + (kc ^ swz(r1))) * 2 + half] = odd;
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN, bool TA, bool TB>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
+  constexpr int BK = 64;
+  constexpr int NT = WM * WN * 64;
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int STAGE = (BM + BN) * 8;                      // uint4 per stage
+  constexpr int RA = TA ? (16 * (BM / 8) / NT) * 4 : BM * 8 / NT;
+  constexpr int RB = TB ? BN * 8 / NT : (16 * (BN / 8) / NT) * 4;
+  extern __shared__ uint4 smem[];
+  const bf16_t* A = reinterpret_cast<const bf16_t*>(p.A);
+  const bf16_t* B = reinterpret_cast<const bf16_t*>(p.B);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+
+  // spread consecutive tiles of one matrix band over one XCD (blocks go round-robin
+  // over the 8 XCDs, each with its own L2)
+  int bid = blockIdx.x;
+  {
+    int nb = gridDim.x, q = nb >> 3, r = nb & 7, x = bid & 7, idx = bid >> 3;
+    bid = x * q + min(x, r) + idx;
+  }
+  const int m0 = (bid / p.tilesN) * BM, n0 = (bid % p.tilesN) * BN;
+  const int kbeg = blockIdx.z * p.kchunk;
+  const int kend = min(p.K, kbeg + p.kchunk);
+  const int nk = (kend - kbeg + BK - 1) / BK;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  uint4 ra[RA], rb[RB];
+  auto gload = [&](int kt) {
+    int k0 = kbeg + kt * BK;
+    if (TA) load_colform<BM, NT>(A, p.lda, m0, p.M, k0, kend, tid, ra);
+    else load_rowform<BM, NT>(A, p.lda, m0, p.M, k0, kend, tid, ra);
+    if (TB) load_rowform<BN, NT>(B, p.ldb, n0, p.N, k0, kend, tid, rb);
+    else load_colform<BN, NT>(B, p.ldb, n0, p.N, k0, kend, tid, rb);
+  };
+  auto sstore = [&](int stage) {
+    uint4* sa = smem + stage * STAGE;
+    uint4* sb = sa + BM * 8;
+    if (TA) store_colform<BM, NT>(sa, tid, ra); else store_rowform<BM, NT>(sa, tid, ra);
+    if (TB) store_rowform<BN, NT>(sb, tid, rb); else store_colform<BN, NT>(sb, tid, rb);
+  };
+
+  if (nk > 0) {
+    gload(0);
+    sstore(0);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const bool more = kt + 1 < nk;
+    if (more) gload(kt + 1);
+    const uint4* sa = smem + (kt & 1) * STAGE;
+    const uint4* sb = sa + BM * 8;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 af[TM], bfr[TN];
+      const int c = ks * 2 + (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        int row = wm * (TM * 32) + i * 32 + (lane & 31);
+        uint4 t = sa[row * 8 + (c ^ swz(row))];
+        af[i] = *reinterpret_cast<bf16x8*>(&t);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        int row = wn * (TN * 32) + j * 32 + (lane & 31);
+        uint4 t = sb[row * 8 + (c ^ swz(row))];
+        bfr[j] = *reinterpret_cast<bf16x8*>(&t);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (more) sstore((kt + 1) & 1);
+    __syncthreads();
+  }
+
+  // accumulator layout of the 32x32 tile: column = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      int n = n0 + wn * (TN * 32) + j * 32 + (lane & 31);
+      int mb = m0 + wm * (TM * 32) + i * 32 + 4 * (lane >> 5);
+      if (n < p.N) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          int m = mb + 8 * (r >> 2) + (r & 3);
+          if (m < p.M) epilogue_store<bf16_t>(p, m, n, acc[i][j][r]);
+        }
+      }
+    }
+}
+
+// ----------------------------------------------------------------------------- launch
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+bool gemm_uses_mfma(int dtype, const GemmDesc& g) {
+  if (dtype != 1) return false;
+  if (!aligned16(g.A) || !aligned16(g.B)) return false;
+  if ((g.lda & 7) || (g.ldb & 7)) return false;
+  if (g.transA ? (g.M & 7) : (g.K & 7)) return false;
+  if (g.transB ? (g.K & 7) : (g.N & 7)) return false;
+  if (g.M < 32 || g.N < 32 || g.K < 32) return false;
+  return true;
+}
+
+template <int BM, int BN, int WM, int WN>
+static hipError_t launch_mfma_cfg(hipStream_t s, GemmParams& p, int transA, int transB, int splits) {
+  constexpr size_t smem = 2 * (size_t)(BM + BN) * 8 * sizeof(uint4);
+  int tilesM = (p.M + BM - 1) / BM;
+  p.tilesN = (p.N + BN - 1) / BN;
+  dim3 grid(tilesM * p.tilesN, 1, splits), block(WM * WN * 64);
+#define OURO_LAUNCH(TA_, TB_)                                                                   \
+  do {                                                                                          \
+    static bool attr_done = false;                                                              \
+    auto kern = gemm_mfma_kernel<BM, BN, WM, WN, TA_, TB_>;                                     \
+    if (!attr_done) {                                                                           \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                   \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);\
+      if (e != hipSuccess) return e;                                                            \
+      attr_done = true;                                                                         \
+    }                                                                                           \
+    hipLaunchKernelGGL(kern, grid, block, smem, s, p);                                          \
+  } while (0)
+  if (!transA && !transB) OURO_LAUNCH(false, false);
+  else if (!transA && transB) OURO_LAUNCH(false, true);
+  else if (transA && !transB) OURO_LAUNCH(true, false);
+  else OURO_LAUNCH(true, true);
+#undef OURO_LAUNCH
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_generic) {
+  if (g.M <= 0 || g.N <= 0) return hipSuccess;
+  GemmParams p;
+  p.A = g.A; p.B = g.B; p.C = g.C;
+  p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
+  p.out_fp32 = g.out_fp32; p.accumulate = g.accumulate;
+  p.bias = g.bias; p.residual = g.residual; p.ldr = g.ldr;
+  p.epilogue = g.epilogue; p.Z = g.Z; p.ldz = g.ldz; p.alpha = g.alpha;
+  p.kchunk = g.K; p.tilesN = 0;
+  if (g.accumulate && (!g.out_fp32 || g.bias || g.residual || g.epilogue != EPI_NONE)) return hipErrorInvalidValue;
+
+  if (!force_generic && gemm_uses_mfma(dtype, g)) {
+    constexpr int BM = 128, BN = 128;
+    int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+    int splits = 1;
+    if (g.accumulate && tiles < 384 && g.K >= 512) {
+      splits = (512 + tiles - 1) / tiles;
+      int maxs = g.K / 256;
+      if (splits > maxs) splits = maxs;
+      if (splits < 1) splits = 1;
+    }
+    int kchunk = (g.K + splits - 1) / splits;
+    kchunk = (kchunk + 63) / 64 * 64;
+    splits = (g.K + kchunk - 1) / kchunk;
+    p.kchunk = kchunk;
+    return launch_mfma_cfg<BM, BN, 2, 2>(s, p, g.transA, g.transB, splits);
+  }
+
+  dim3 grid((g.N + 63) / 64, (g.M + 63) / 64, 1), block(256);
+#define OURO_PLAIN(T_)                                                                        \
+  do {                                                                                        \
+    if (!g.transA && !g.transB) hipLaunchKernelGGL((gemm_plain_kernel<T_, false, false>), grid, block, 0, s, p); \
+    else if (!g.transA && g.transB) hipLaunchKernelGGL((gemm_plain_kernel<T_, false, true>), grid, block, 0, s, p); \
+    else if (g.transA && !g.transB) hipLaunchKernelGGL((gemm_plain_kernel<T_, true, false>), grid, block, 0, s, p); \
+    else hipLaunchKernelGGL((gemm_plain_kernel<T_, true, true>), grid, block, 0, s, p);       \
+  } while (0)
+  if (dtype == 1) OURO_PLAIN(bf16_t); else OURO_PLAIN(float);
+#undef OURO_PLAIN
+  return hipGetLastError();
+}
+
+}  // namespace ouro

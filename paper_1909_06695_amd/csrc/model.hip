@@ -1,0 +1,847 @@
+// Host side of the C boundary: configuration checks, arena layout, the per-iteration
+// call contract, the staleness rings (Eq. 8-9) and the sequence of kernel launches that
+// make up module_forward / module_backward / delayed_update.
+#include "common.h"
+#include "../../include/ouro.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace ouro;
+
+static thread_local std::string g_err;
+static int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+#define HIPCHK(expr)                                                                      \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess) return fail(OURO_E_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+extern "C" const char* ouro_last_error(void) { return g_err.c_str(); }
+
+// ------------------------------------------------------------------ staleness integers
+// Eq. 8: module k at iteration t consumes the gradient of iteration t-K+k.  A ring of
+// K-k+1 slots is enough: slot (t mod depth) is written at t and read K-k iterations
+// later, just before it would be overwritten.  Eq. 9: dV_i of iteration t-K+1 (ring of K
+// slots) and dV_o of iteration t (one slot).
+extern "C" int ouro_ring_depth(int K, int id, int64_t* depth) {
+  if (!depth || K < 1 || id < 0 || id > K + 1) return fail(OURO_E_ARG, "ring_depth: bad K=%d id=%d", K, id);
+  if (id == 0) *depth = K;
+  else if (id == K + 1) *depth = 1;
+  else *depth = K - id + 1;
+  return OURO_OK;
+}
+
+extern "C" int ouro_slot_index(int K, int id, int64_t t, int write, int64_t* slot, int64_t* tau) {
+  int64_t depth;
+  if (!slot || !tau || t < 0) return fail(OURO_E_ARG, "slot_index: bad argument");
+  int rc = ouro_ring_depth(K, id, &depth);
+  if (rc) return rc;
+  int64_t want = t;
+  if (!write) {
+    if (id == 0) want = t - K + 1;
+    else if (id <= K) want = t - K + id;
+  }
+  if (want < 0) { *slot = -1; *tau = -1; return OURO_OK; }
+  *slot = want % depth;
+  *tau = want;
+  return OURO_OK;
+}
+
+// ------------------------------------------------------------------------------ layout
+struct LayerOff {   // element offsets inside a module blob
+  size_t W_qkv, W_o, W_r, u, v, ln1_g, ln1_b, W_1, b_1, W_2, b_2, ln2_g, ln2_b, end;
+};
+static LayerOff layer_offsets(const ouro_config& c, size_t base) {
+  const size_t d = c.d_model, F = c.d_ff;
+  LayerOff o;
+  size_t p = base;
+  o.W_qkv = p; p += d * 3 * d;
+  o.W_o = p; p += d * d;
+  o.W_r = o.u = o.v = 0;
+  if (c.rel_pos) {
+    o.W_r = p; p += d * d;
+    o.u = p; p += d;
+    o.v = p; p += d;
+  }
+  o.ln1_g = p; p += d;
+  o.ln1_b = p; p += d;
+  o.W_1 = p; p += d * F;
+  o.b_1 = p; p += F;
+  o.W_2 = p; p += F * d;
+  o.b_2 = p; p += d;
+  o.ln2_g = p; p += d;
+  o.ln2_b = p; p += d;
+  o.end = p;
+  return o;
+}
+
+struct LayerBuf {   // saved activations of one layer (element type T unless noted)
+  char* x;          // input [N, d]
+  char* cat;        // [B, Mv+T, d] memory ; input (relative mode with memory)
+  char* qkv;        // plain: [N, 3d]; relative: q [N, d] then kv [B*S, 2d]
+  char* a;          // attention output before W_o [N, d]
+  char* s1;         // x + a W_o  [N, d]
+  char* y;          // LN1 output [N, d]
+  char* z;          // FFN pre-activation [N, F]
+  char* uact;       // GELU(z) [N, F]
+  char* s2;         // y + FFN [N, d]
+  char* r;          // W_r-projected distance table [S, d]
+  char* mem;        // segment memory [B, Mv, d]
+  float *lse, *mean1, *rstd1, *mean2, *rstd2;
+};
+
+struct Bump {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    size_t o = off;
+    off += (bytes + 255) & ~(size_t)255;
+    return o;
+  }
+};
+
+struct ouro_model {
+  ouro_config cfg;
+  std::vector<int> lpm;          // layers per module
+  std::vector<int> first_layer;  // first layer of module k (index k-1), plus end
+  std::vector<int> layer_mod;    // module (1..K) of each layer
+  std::vector<LayerOff> loff;    // per layer, offsets inside its module blob
+  hipStream_t stream;
+  char* arena;
+  size_t bytes;
+  int esz;                        // bytes per activation element
+  int N, S;                       // tokens per step, max keys per stream (T + M)
+  // parameter groups 0..K
+  std::vector<int64_t> count;
+  std::vector<float*> master, adam_m, adam_v;
+  std::vector<bf16_t*> shadow;
+  // gradient stores 0..K+1
+  std::vector<int64_t> gcount, depth;
+  std::vector<float*> ring;
+  std::vector<std::vector<int64_t>> tags;
+  std::vector<int64_t> last_slot, last_tau;
+  // activations
+  std::vector<LayerBuf> L;
+  char* hL;                       // final hidden state [N, d]
+  float* pe;                      // [T, d] fp32 (absolute mode)
+  char* rtab;                     // [S, d] distance sinusoids, type T (relative mode)
+  float* logits;                  // [N, vocab] fp32
+  char* G;                        // [N, vocab] type T
+  float *lse_ce, *rowloss, *loss;
+  int* flag;
+  // backward scratch
+  char *dh0, *dh1, *ds2, *dz, *dy, *ds1, *da, *dqkv, *dcat, *dr_t;
+  float *attn_scratch, *dr_f32, *dbg_f32;
+  size_t dbg_floats;
+  // iteration state
+  int64_t t;
+  int fwd_next, bwd_next;         // next module expected by forward (1..K+1) / backward (K..0)
+  uint64_t upd_mask, inject_mask;
+  int mem_valid;                  // valid rows in every layer memory
+  const int32_t* tok;
+  const int32_t* tgt;
+  // timing of the MFMA contraction kernel
+  int timing;
+  std::vector<hipEvent_t> ev;
+  size_t ev_used;
+  double timed_flops;
+  int64_t timed_launches;
+
+  const char* wT(int layer, size_t off) const {   // weight as activation-typed operand
+    int k = layer_mod[layer];
+    return cfg.dtype == 1 ? (const char*)(shadow[k] + off) : (const char*)(master[k] + off);
+  }
+  const float* wF(int layer, size_t off) const { return master[layer_mod[layer]] + off; }
+  const char* vT() const { return cfg.dtype == 1 ? (const char*)shadow[0] : (const char*)master[0]; }
+  float* slot_ptr(int id, int64_t slot) const { return ring[id] + (size_t)slot * gcount[id]; }
+};
+
+static int default_split(int L, int K, std::vector<int>& out) {
+  int base = L / K, rem = L % K;
+  out.assign(K, base);
+  std::vector<int> order;
+  for (int i = 1; i < K - 1; ++i) order.push_back(i);
+  order.push_back(0);
+  if (K > 1) order.push_back(K - 1);
+  for (int i = 0; i < rem; ++i) out[order[i % order.size()]] += 1;
+  return 0;
+}
+
+static int validate(const ouro_config* c, std::vector<int>& lpm) {
+  if (!c) return fail(OURO_E_ARG, "config is null");
+  if (c->n_layer < 1 || c->d_model < 2 || c->n_head < 1 || c->d_head < 1 || c->d_ff < 1 || c->vocab < 2 ||
+      c->seq_len < 1 || c->batch < 1 || c->mem_len < 0)
+    return fail(OURO_E_CONFIG, "sizes must be positive");
+  if ((int64_t)c->n_head * c->d_head != c->d_model) return fail(OURO_E_CONFIG, "n_head*d_head != d_model");
+  if (c->d_model % 2) return fail(OURO_E_CONFIG, "d_model must be even");
+  if (c->d_head > 256) return fail(OURO_E_CONFIG, "d_head > 256 unsupported");
+  if (c->n_module < 1 || c->n_module > c->n_layer || c->n_module > 62)
+    return fail(OURO_E_CONFIG, "n_module must be in [1, min(n_layer, 62)]");
+  if (c->mem_len > 0 && !c->rel_pos) return fail(OURO_E_CONFIG, "mem_len > 0 needs rel_pos = 1");
+  if (c->rel_pos != 0 && c->rel_pos != 1) return fail(OURO_E_CONFIG, "rel_pos must be 0 or 1");
+  if (c->dtype != 0 && c->dtype != 1) return fail(OURO_E_CONFIG, "dtype must be 0 or 1");
+  if (c->optimizer != 0 && c->optimizer != 1) return fail(OURO_E_CONFIG, "optimizer must be 0 or 1");
+  if (c->embed_warm_mode != 0 && c->embed_warm_mode != 1) return fail(OURO_E_CONFIG, "embed_warm_mode must be 0 or 1");
+  if (c->optimizer == 1 && !(c->beta1 >= 0 && c->beta1 < 1 && c->beta2 >= 0 && c->beta2 < 1 && c->eps > 0))
+    return fail(OURO_E_CONFIG, "Adam constants out of range");
+  if ((int64_t)c->batch * c->seq_len > (1 << 24)) return fail(OURO_E_CONFIG, "batch*seq_len too large");
+  if ((int64_t)(c->seq_len + c->mem_len) > 6000) return fail(OURO_E_CONFIG, "seq_len+mem_len > 6000 unsupported");
+  if (c->layers_per_module) {
+    int sum = 0;
+    lpm.assign(c->layers_per_module, c->layers_per_module + c->n_module);
+    for (int v : lpm) {
+      if (v < 1) return fail(OURO_E_CONFIG, "every module needs at least one layer");
+      sum += v;
+    }
+    if (sum != c->n_layer) return fail(OURO_E_CONFIG, "layers_per_module does not sum to n_layer");
+  } else {
+    default_split(c->n_layer, c->n_module, lpm);
+  }
+  return OURO_OK;
+}
+
+// Fills every pointer of m relative to base (base may be null: sizing only).
+static size_t lay_out(ouro_model& m, char* base) {
+  const ouro_config& c = m.cfg;
+  const int K = c.n_module, L = c.n_layer;
+  const size_t d = c.d_model, F = c.d_ff, V = c.vocab, T = c.seq_len, M = c.mem_len, B = c.batch;
+  const size_t N = B * T, S = T + M, es = m.esz;
+  Bump bp;
+  auto P = [&](size_t bytes) { return base + bp.take(bytes); };
+  m.count.assign(K + 1, 0);
+  m.count[0] = (int64_t)(V * d);
+  m.first_layer.assign(K + 1, 0);
+  m.layer_mod.assign(L, 0);
+  m.loff.resize(L);
+  int l = 0;
+  for (int k = 1; k <= K; ++k) {
+    m.first_layer[k - 1] = l;
+    size_t off = 0;
+    for (int i = 0; i < m.lpm[k - 1]; ++i, ++l) {
+      m.layer_mod[l] = k;
+      m.loff[l] = layer_offsets(c, off);
+      off = m.loff[l].end;
+    }
+    m.count[k] = (int64_t)off;
+  }
+  m.first_layer[K] = L;
+  m.master.assign(K + 1, nullptr); m.shadow.assign(K + 1, nullptr);
+  m.adam_m.assign(K + 1, nullptr); m.adam_v.assign(K + 1, nullptr);
+  for (int k = 0; k <= K; ++k) {
+    m.master[k] = (float*)P(m.count[k] * 4);
+    if (c.dtype == 1) m.shadow[k] = (bf16_t*)P(m.count[k] * 2);
+    if (c.optimizer == 1) {
+      m.adam_m[k] = (float*)P(m.count[k] * 4);
+      m.adam_v[k] = (float*)P(m.count[k] * 4);
+    }
+  }
+  m.gcount.assign(K + 2, 0); m.depth.assign(K + 2, 0); m.ring.assign(K + 2, nullptr);
+  for (int id = 0; id <= K + 1; ++id) {
+    m.gcount[id] = (id == 0 || id == K + 1) ? m.count[0] : m.count[id];
+    ouro_ring_depth(K, id, &m.depth[id]);
+    m.ring[id] = (float*)P((size_t)m.depth[id] * m.gcount[id] * 4);
+  }
+  m.L.resize(L);
+  const size_t qkv_elems = c.rel_pos ? (N * d + B * S * 2 * d) : (N * 3 * d);
+  for (int i = 0; i < L; ++i) {
+    LayerBuf& b = m.L[i];
+    b.x = P(N * d * es);
+    b.cat = (M > 0) ? P(B * S * d * es) : nullptr;
+    b.qkv = P(qkv_elems * es);
+    b.a = P(N * d * es);
+    b.s1 = P(N * d * es);
+    b.y = P(N * d * es);
+    b.z = P(N * F * es);
+    b.uact = P(N * F * es);
+    b.s2 = P(N * d * es);
+    b.r = c.rel_pos ? P(S * d * es) : nullptr;
+    b.mem = (M > 0) ? P(B * M * d * es) : nullptr;
+    b.lse = (float*)P(B * c.n_head * T * 4);
+    b.mean1 = (float*)P(N * 4); b.rstd1 = (float*)P(N * 4);
+    b.mean2 = (float*)P(N * 4); b.rstd2 = (float*)P(N * 4);
+  }
+  m.hL = P(N * d * es);
+  m.pe = c.rel_pos ? nullptr : (float*)P(T * d * 4);
+  m.rtab = c.rel_pos ? P(S * d * es) : nullptr;
+  m.logits = (float*)P(N * V * 4);
+  m.G = P(N * V * es);
+  m.lse_ce = (float*)P(N * 4);
+  m.rowloss = (float*)P(N * 4);
+  m.loss = (float*)P(256);
+  m.flag = (int*)P(256);
+  m.dh0 = P(N * d * es); m.dh1 = P(N * d * es);
+  m.ds2 = P(N * d * es); m.dz = P(N * F * es); m.dy = P(N * d * es);
+  m.ds1 = P(N * d * es); m.da = P(N * d * es);
+  m.dqkv = P(qkv_elems * es);
+  m.dcat = c.rel_pos ? P(B * S * d * es) : nullptr;
+  m.dr_t = c.rel_pos ? P(S * d * es) : nullptr;
+  m.dr_f32 = c.rel_pos ? (float*)P(S * d * 4) : nullptr;
+  m.attn_scratch = (float*)P(attn_bwd_scratch_floats(c.batch, c.n_head, c.seq_len, (int)S, c.d_head) * 4);
+  m.dbg_floats = N * d > B * M * d ? N * d : B * M * d;
+  if (m.dbg_floats < S * d) m.dbg_floats = S * d;
+  m.dbg_f32 = (float*)P(m.dbg_floats * 4);
+  return bp.off;
+}
+
+extern "C" int ouro_query_arena_bytes(const ouro_config* cfg, size_t* bytes) {
+  if (!bytes) return fail(OURO_E_ARG, "bytes is null");
+  ouro_model m;
+  int rc = validate(cfg, m.lpm);
+  if (rc) return rc;
+  m.cfg = *cfg;
+  m.esz = cfg->dtype == 1 ? 2 : 4;
+  *bytes = lay_out(m, nullptr);
+  return OURO_OK;
+}
+
+static void host_sinusoid(std::vector<float>& out, int rows, int d) {
+  out.resize((size_t)rows * d);
+  for (int p = 0; p < rows; ++p)
+    for (int i = 0; i < d / 2; ++i) {
+      double w = std::pow(10000.0, -2.0 * i / d);
+      out[(size_t)p * d + i] = (float)std::sin(p * w);
+      out[(size_t)p * d + d / 2 + i] = (float)std::cos(p * w);
+    }
+}
+
+extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t bytes, void* hip_stream,
+                                 ouro_model** out) {
+  if (!out) return fail(OURO_E_ARG, "out is null");
+  *out = nullptr;
+  ouro_model* m = new ouro_model();
+  int rc = validate(cfg, m->lpm);
+  if (rc) { delete m; return rc; }
+  m->cfg = *cfg;
+  m->cfg.layers_per_module = nullptr;
+  m->esz = cfg->dtype == 1 ? 2 : 4;
+  m->N = cfg->batch * cfg->seq_len;
+  m->S = cfg->seq_len + cfg->mem_len;
+  if (!dev_arena || (reinterpret_cast<uintptr_t>(dev_arena) & 255)) { delete m; return fail(OURO_E_ARENA, "arena null or not 256-byte aligned"); }
+  size_t need = lay_out(*m, (char*)dev_arena);
+  if (bytes < need) { delete m; return fail(OURO_E_ARENA, "arena has %zu bytes, %zu needed", bytes, need); }
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) { delete m; return fail(OURO_E_HIP, "no HIP device available"); }
+  m->arena = (char*)dev_arena;
+  m->bytes = need;
+  m->stream = (hipStream_t)hip_stream;
+  const int K = cfg->n_module;
+  m->tags.resize(K + 2);
+  for (int id = 0; id <= K + 1; ++id) m->tags[id].assign((size_t)m->depth[id], -1);
+  m->last_slot.assign(K + 2, -1); m->last_tau.assign(K + 2, -1);
+  m->t = 0; m->fwd_next = 1; m->bwd_next = K; m->upd_mask = 0; m->inject_mask = 0; m->mem_valid = 0;
+  m->tok = m->tgt = nullptr;
+  m->timing = 0; m->ev_used = 0; m->timed_flops = 0; m->timed_launches = 0;
+  // zero optimizer state, rings, everything else too (one fill over the arena)
+  hipError_t e = launch_fill_zero(m->stream, m->arena, need);
+  if (e != hipSuccess) { delete m; return fail(OURO_E_HIP, "arena clear: %s", hipGetErrorString(e)); }
+  std::vector<float> tab;
+  if (!cfg->rel_pos) {
+    host_sinusoid(tab, cfg->seq_len, cfg->d_model);
+    e = hipMemcpyAsync(m->pe, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, m->stream);
+  } else {
+    host_sinusoid(tab, m->S, cfg->d_model);
+    e = hipMemcpyAsync(m->dbg_f32, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, m->stream);
+    if (e == hipSuccess) e = launch_convert(m->stream, cfg->dtype, m->rtab, m->dbg_f32, tab.size());
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
+  if (e != hipSuccess) { delete m; return fail(OURO_E_HIP, "table upload: %s", hipGetErrorString(e)); }
+  *out = m;
+  return OURO_OK;
+}
+
+extern "C" int ouro_destroy_model(ouro_model* m) {
+  if (!m) return OURO_OK;
+  (void)hipStreamSynchronize(m->stream);
+  for (hipEvent_t e : m->ev) (void)hipEventDestroy(e);
+  delete m;
+  return OURO_OK;
+}
+
+extern "C" int ouro_param_count(const ouro_model* m, int group, int64_t* n) {
+  if (!m || !n || group < 0 || group > m->cfg.n_module) return fail(OURO_E_ARG, "param_count: bad argument");
+  *n = m->count[group];
+  return OURO_OK;
+}
+
+extern "C" int ouro_set_params(ouro_model* m, int group, const float* src, int64_t n, int src_is_device) {
+  if (!m || !src || group < 0 || group > m->cfg.n_module) return fail(OURO_E_ARG, "set_params: bad argument");
+  if (n != m->count[group]) return fail(OURO_E_ARG, "set_params: group %d has %lld elements, got %lld", group, (long long)m->count[group], (long long)n);
+  HIPCHK(hipMemcpyAsync(m->master[group], src, (size_t)n * 4, src_is_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, m->stream));
+  if (m->cfg.dtype == 1) HIPCHK(launch_convert(m->stream, 1, m->shadow[group], m->master[group], (size_t)n));
+  if (!src_is_device) HIPCHK(hipStreamSynchronize(m->stream));
+  return OURO_OK;
+}
+
+extern "C" int ouro_get_params(ouro_model* m, int group, float* dst, int64_t n, int dst_is_device) {
+  if (!m || !dst || group < 0 || group > m->cfg.n_module) return fail(OURO_E_ARG, "get_params: bad argument");
+  if (n != m->count[group]) return fail(OURO_E_ARG, "get_params: wrong element count");
+  HIPCHK(hipMemcpyAsync(dst, m->master[group], (size_t)n * 4, dst_is_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost, m->stream));
+  if (!dst_is_device) HIPCHK(hipStreamSynchronize(m->stream));
+  return OURO_OK;
+}
+
+extern "C" int64_t ouro_current_step(const ouro_model* m) { return m ? m->t : -1; }
+
+// --------------------------------------------------------------------- launch helpers
+static int run_gemm(ouro_model* m, GemmDesc g) {
+  const bool timed = m->timing && gemm_uses_mfma(m->cfg.dtype, g);
+  if (timed) {
+    while (m->ev.size() < m->ev_used + 2) {
+      hipEvent_t e;
+      HIPCHK(hipEventCreate(&e));
+      m->ev.push_back(e);
+    }
+    HIPCHK(hipEventRecord(m->ev[m->ev_used], m->stream));
+  }
+  HIPCHK(launch_gemm(m->stream, m->cfg.dtype, g, 0));
+  if (timed) {
+    HIPCHK(hipEventRecord(m->ev[m->ev_used + 1], m->stream));
+    m->ev_used += 2;
+    m->timed_flops += 2.0 * g.M * g.N * g.K;
+    m->timed_launches += 1;
+  }
+  return OURO_OK;
+}
+
+static GemmDesc gd(const void* A, int lda, int tA, const void* B, int ldb, int tB, void* C, int ldc, int M, int N, int K) {
+  GemmDesc g;
+  memset(&g, 0, sizeof g);
+  g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
+  g.transA = tA; g.transB = tB; g.alpha = 1.f;
+  return g;
+}
+#define RUN(expr) do { int rc_ = (expr); if (rc_) return rc_; } while (0)
+
+// ------------------------------------------------------------------------------ forward
+static int layer_forward(ouro_model* m, int l) {
+  const ouro_config& c = m->cfg;
+  const int d = c.d_model, F = c.d_ff, N = m->N, T = c.seq_len, B = c.batch, es = m->esz;
+  const LayerOff& o = m->loff[l];
+  LayerBuf& b = m->L[l];
+  char* out = (l + 1 < c.n_layer) ? m->L[l + 1].x : m->hL;
+  const int Mv = m->mem_valid, S = Mv + T;
+  AttnDesc a;
+  memset(&a, 0, sizeof a);
+  a.B = B; a.H = c.n_head; a.T = T; a.S = S; a.dh = c.d_head; a.Mv = Mv;
+  a.scale = 1.f / std::sqrt((float)c.d_head);
+  a.o = b.a; a.ldo = d; a.lse = b.lse;
+  if (!c.rel_pos) {
+    RUN(run_gemm(m, gd(b.x, d, 0, m->wT(l, o.W_qkv), 3 * d, 0, b.qkv, 3 * d, N, 3 * d, d)));
+    a.q = b.qkv; a.ldq = 3 * d;
+    a.k = b.qkv + (size_t)d * es; a.ldk = 3 * d;
+    a.v = b.qkv + (size_t)2 * d * es; a.ldv = 3 * d;
+  } else {
+    const char* cat = b.x;
+    if (Mv > 0) {
+      HIPCHK(launch_copy_rows(m->stream, c.dtype, b.cat, (size_t)S * d, 0, b.mem, (size_t)Mv * d, 0, B, Mv, d));
+      HIPCHK(launch_copy_rows(m->stream, c.dtype, b.cat, (size_t)S * d, (size_t)Mv * d, b.x, (size_t)T * d, 0, B, T, d));
+      cat = b.cat;
+    }
+    char* q = b.qkv;
+    char* kv = b.qkv + (size_t)N * d * es;
+    RUN(run_gemm(m, gd(b.x, d, 0, m->wT(l, o.W_qkv), 3 * d, 0, q, d, N, d, d)));
+    RUN(run_gemm(m, gd(cat, d, 0, m->wT(l, o.W_qkv) + (size_t)d * es, 3 * d, 0, kv, 2 * d, B * S, 2 * d, d)));
+    RUN(run_gemm(m, gd(m->rtab, d, 0, m->wT(l, o.W_r), d, 0, b.r, d, S, d, d)));
+    a.q = q; a.ldq = d;
+    a.k = kv; a.ldk = 2 * d;
+    a.v = kv + (size_t)d * es; a.ldv = 2 * d;
+    a.rel = 1; a.u = m->wT(l, o.u); a.vb = m->wT(l, o.v); a.r = b.r; a.ldr = d;
+  }
+  HIPCHK(launch_attn_fwd(m->stream, c.dtype, a, 0));
+  {
+    GemmDesc g = gd(b.a, d, 0, m->wT(l, o.W_o), d, 0, b.s1, d, N, d, d);
+    g.residual = b.x; g.ldr = d;
+    RUN(run_gemm(m, g));
+  }
+  HIPCHK(launch_layernorm_fwd(m->stream, c.dtype, b.s1, m->wF(l, o.ln1_g), m->wF(l, o.ln1_b), b.y, b.mean1, b.rstd1, N, d));
+  {
+    GemmDesc g = gd(b.y, d, 0, m->wT(l, o.W_1), F, 0, b.uact, F, N, F, d);
+    g.bias = m->wF(l, o.b_1); g.epilogue = EPI_GELU; g.Z = b.z; g.ldz = F;
+    RUN(run_gemm(m, g));
+  }
+  {
+    GemmDesc g = gd(b.uact, F, 0, m->wT(l, o.W_2), d, 0, b.s2, d, N, d, F);
+    g.bias = m->wF(l, o.b_2); g.residual = b.y; g.ldr = d;
+    RUN(run_gemm(m, g));
+  }
+  HIPCHK(launch_layernorm_fwd(m->stream, c.dtype, b.s2, m->wF(l, o.ln2_g), m->wF(l, o.ln2_b), out, b.mean2, b.rstd2, N, d));
+  return OURO_OK;
+}
+
+extern "C" int ouro_module_forward(ouro_model* m, int k, const int32_t* dev_tokens, const int32_t* dev_targets) {
+  if (!m) return fail(OURO_E_ARG, "model is null");
+  const ouro_config& c = m->cfg;
+  const int K = c.n_module;
+  if (k < 1 || k > K) return fail(OURO_E_ARG, "module_forward: k=%d outside 1..%d", k, K);
+  if (m->inject_mask) return fail(OURO_E_SEQUENCE, "module_forward after inject_grad in the same iteration");
+  if (k != m->fwd_next) return fail(OURO_E_SEQUENCE, "module_forward(%d) but module %d is next", k, m->fwd_next);
+  if (k == 1) {
+    if (!dev_tokens) return fail(OURO_E_ARG, "module_forward(1) needs tokens");
+    m->tok = dev_tokens;
+    HIPCHK(launch_fill_zero(m->stream, m->flag, 256));
+    HIPCHK(launch_embed_fwd(m->stream, c.dtype, m->tok, m->vT(), m->pe, m->L[0].x, m->N, c.seq_len, c.d_model, c.vocab, c.emb_scale, m->flag));
+  }
+  if (k == K && !dev_targets) return fail(OURO_E_ARG, "module_forward(K) needs targets");
+  for (int l = m->first_layer[k - 1]; l < m->first_layer[k]; ++l) RUN(layer_forward(m, l));
+  if (k == K) {
+    m->tgt = dev_targets;
+    const int d = c.d_model, V = c.vocab, N = m->N;
+    GemmDesc g = gd(m->hL, d, 0, m->vT(), d, 1, m->logits, V, N, V, d);   // logits = h_L V^T (Eq. 3)
+    g.out_fp32 = 1;
+    RUN(run_gemm(m, g));
+    HIPCHK(launch_ce_rows(m->stream, c.dtype, m->logits, V, m->tgt, m->G, V, m->lse_ce, m->rowloss, N, V, m->flag));
+    HIPCHK(launch_sum_rows(m->stream, m->rowloss, N, m->loss));
+  }
+  m->fwd_next = k + 1;
+  if (k == K) m->bwd_next = K;
+  return OURO_OK;
+}
+
+// ----------------------------------------------------------------------------- backward
+template <typename T>
+__global__ void add_rows_kernel(T* dst, size_t dst_bstride, const T* src, size_t src_bstride, size_t src_off, size_t n) {
+  const int b = blockIdx.y;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    size_t di = b * dst_bstride + i;
+    dst[di] = from_f32<T>(to_f32(dst[di]) + to_f32(src[b * src_bstride + src_off + i]));
+  }
+}
+
+static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot) {
+  const ouro_config& c = m->cfg;
+  const int d = c.d_model, F = c.d_ff, N = m->N, T = c.seq_len, B = c.batch, es = m->esz;
+  const LayerOff& o = m->loff[l];
+  LayerBuf& b = m->L[l];
+  const int Mv = m->mem_valid, S = Mv + T;
+  hipStream_t st = m->stream;
+  // LN2
+  HIPCHK(launch_layernorm_bwd(st, c.dtype, dh, b.s2, m->wF(l, o.ln2_g), b.mean2, b.rstd2, m->ds2, gslot + o.ln2_g, gslot + o.ln2_b, N, d));
+  // FFN2
+  {
+    GemmDesc g = gd(b.uact, F, 1, m->ds2, d, 0, gslot + o.W_2, d, F, d, N);
+    g.out_fp32 = 1; g.accumulate = 1;
+    RUN(run_gemm(m, g));
+  }
+  HIPCHK(launch_colsum(st, c.dtype, m->ds2, d, gslot + o.b_2, N, d));
+  {
+    GemmDesc g = gd(m->ds2, d, 0, m->wT(l, o.W_2), d, 1, m->dz, F, N, F, d);
+    g.epilogue = EPI_GELUGRAD; g.Z = b.z; g.ldz = F;
+    RUN(run_gemm(m, g));
+  }
+  // FFN1
+  {
+    GemmDesc g = gd(b.y, d, 1, m->dz, F, 0, gslot + o.W_1, F, d, F, N);
+    g.out_fp32 = 1; g.accumulate = 1;
+    RUN(run_gemm(m, g));
+  }
+  HIPCHK(launch_colsum(st, c.dtype, m->dz, F, gslot + o.b_1, N, F));
+  {
+    GemmDesc g = gd(m->dz, F, 0, m->wT(l, o.W_1), F, 1, m->dy, d, N, d, F);
+    g.residual = m->ds2; g.ldr = d;
+    RUN(run_gemm(m, g));
+  }
+  // LN1
+  HIPCHK(launch_layernorm_bwd(st, c.dtype, m->dy, b.s1, m->wF(l, o.ln1_g), b.mean1, b.rstd1, m->ds1, gslot + o.ln1_g, gslot + o.ln1_b, N, d));
+  // output projection
+  {
+    GemmDesc g = gd(b.a, d, 1, m->ds1, d, 0, gslot + o.W_o, d, d, d, N);
+    g.out_fp32 = 1; g.accumulate = 1;
+    RUN(run_gemm(m, g));
+  }
+  RUN(run_gemm(m, gd(m->ds1, d, 0, m->wT(l, o.W_o), d, 1, m->da, d, N, d, d)));
+  // attention
+  AttnDesc a;
+  memset(&a, 0, sizeof a);
+  a.B = B; a.H = c.n_head; a.T = T; a.S = S; a.dh = c.d_head; a.Mv = Mv;
+  a.scale = 1.f / std::sqrt((float)c.d_head);
+  a.o = b.a; a.ldo = d; a.lse = b.lse; a.d_o = m->da; a.lddo = d; a.scratch = m->attn_scratch;
+  if (!c.rel_pos) {
+    a.q = b.qkv; a.ldq = 3 * d;
+    a.k = b.qkv + (size_t)d * es; a.ldk = 3 * d;
+    a.v = b.qkv + (size_t)2 * d * es; a.ldv = 3 * d;
+    a.dq = m->dqkv; a.lddq = 3 * d;
+    a.dk = m->dqkv + (size_t)d * es; a.lddk = 3 * d;
+    a.dv = m->dqkv + (size_t)2 * d * es; a.lddv = 3 * d;
+    HIPCHK(launch_attn_bwd(st, c.dtype, a, 0));
+    {
+      GemmDesc g = gd(b.x, d, 1, m->dqkv, 3 * d, 0, gslot + o.W_qkv, 3 * d, d, 3 * d, N);
+      g.out_fp32 = 1; g.accumulate = 1;
+      RUN(run_gemm(m, g));
+    }
+    {
+      GemmDesc g = gd(m->dqkv, 3 * d, 0, m->wT(l, o.W_qkv), 3 * d, 1, dx, d, N, d, 3 * d);
+      g.residual = m->ds1; g.ldr = d;
+      RUN(run_gemm(m, g));
+    }
+  } else {
+    const char* cat = Mv > 0 ? b.cat : b.x;
+    char* q = b.qkv;
+    char* kv = b.qkv + (size_t)N * d * es;
+    char* dq = m->dqkv;
+    char* dkv = m->dqkv + (size_t)N * d * es;
+    a.q = q; a.ldq = d; a.k = kv; a.ldk = 2 * d; a.v = kv + (size_t)d * es; a.ldv = 2 * d;
+    a.rel = 1; a.u = m->wT(l, o.u); a.vb = m->wT(l, o.v); a.r = b.r; a.ldr = d;
+    a.dq = dq; a.lddq = d; a.dk = dkv; a.lddk = 2 * d; a.dv = dkv + (size_t)d * es; a.lddv = 2 * d;
+    a.du = gslot + o.u; a.dvb = gslot + o.v; a.dr = m->dr_f32;
+    HIPCHK(launch_fill_zero(st, m->dr_f32, (size_t)S * d * 4));
+    HIPCHK(launch_attn_bwd(st, c.dtype, a, 0));
+    // dW_r = R^T dr
+    const void* drp = m->dr_f32;
+    if (c.dtype == 1) { HIPCHK(launch_convert(st, 1, m->dr_t, m->dr_f32, (size_t)S * d)); drp = m->dr_t; }
+    {
+      GemmDesc g = gd(m->rtab, d, 1, drp, d, 0, gslot + o.W_r, d, d, d, S);
+      g.out_fp32 = 1; g.accumulate = 1;
+      RUN(run_gemm(m, g));
+    }
+    {
+      GemmDesc g = gd(b.x, d, 1, dq, d, 0, gslot + o.W_qkv, 3 * d, d, d, N);
+      g.out_fp32 = 1; g.accumulate = 1;
+      RUN(run_gemm(m, g));
+    }
+    {
+      GemmDesc g = gd(cat, d, 1, dkv, 2 * d, 0, gslot + o.W_qkv + d, 3 * d, d, 2 * d, B * S);
+      g.out_fp32 = 1; g.accumulate = 1;
+      RUN(run_gemm(m, g));
+    }
+    {
+      GemmDesc g = gd(dq, d, 0, m->wT(l, o.W_qkv), 3 * d, 1, dx, d, N, d, d);
+      g.residual = m->ds1; g.ldr = d;
+      RUN(run_gemm(m, g));
+    }
+    // the memory rows are constants: only the current rows of d[mem ; x] reach dx
+    RUN(run_gemm(m, gd(dkv, 2 * d, 0, m->wT(l, o.W_qkv) + (size_t)d * es, 3 * d, 1, m->dcat, d, B * S, d, 2 * d)));
+    {
+      size_t n = (size_t)T * d;
+      dim3 grid((unsigned)std::min<size_t>((n + 255) / 256, 1024), B), block(256);
+      if (c.dtype == 1) hipLaunchKernelGGL(add_rows_kernel<bf16_t>, grid, block, 0, st, (bf16_t*)dx, n, (const bf16_t*)m->dcat, (size_t)S * d, (size_t)Mv * d, n);
+      else hipLaunchKernelGGL(add_rows_kernel<float>, grid, block, 0, st, (float*)dx, n, (const float*)m->dcat, (size_t)S * d, (size_t)Mv * d, n);
+      HIPCHK(hipGetLastError());
+    }
+  }
+  return OURO_OK;
+}
+
+extern "C" int ouro_module_backward(ouro_model* m, int k) {
+  if (!m) return fail(OURO_E_ARG, "model is null");
+  const ouro_config& c = m->cfg;
+  const int K = c.n_module, d = c.d_model, V = c.vocab, N = m->N;
+  if (k < 1 || k > K) return fail(OURO_E_ARG, "module_backward: k=%d outside 1..%d", k, K);
+  if (m->inject_mask) return fail(OURO_E_SEQUENCE, "module_backward after inject_grad in the same iteration");
+  if (m->fwd_next != K + 1) return fail(OURO_E_SEQUENCE, "module_backward before forward of module %d", m->fwd_next);
+  if (k != m->bwd_next) return fail(OURO_E_SEQUENCE, "module_backward(%d) but module %d is next", k, m->bwd_next);
+  int64_t slot, tau;
+  ouro_slot_index(K, k, m->t, 1, &slot, &tau);
+  float* gslot = m->slot_ptr(k, slot);
+  HIPCHK(launch_fill_zero(m->stream, gslot, (size_t)m->gcount[k] * 4));
+  const int lastl = m->first_layer[K] - 1;
+  if (k == K) {
+    // Eq. 7 (right): dV_o = G^T h_L ; error gradient dh_L = G V
+    float* dvo = m->slot_ptr(K + 1, 0);
+    GemmDesc g = gd(m->G, V, 1, m->hL, d, 0, dvo, d, V, d, N);
+    g.out_fp32 = 1;
+    RUN(run_gemm(m, g));
+    m->tags[K + 1][0] = m->t;
+    RUN(run_gemm(m, gd(m->G, V, 0, m->vT(), d, 0, (lastl % 2) ? m->dh1 : m->dh0, d, N, d, V)));
+  }
+  // layer l reads its output gradient from dh[(l)%2] and writes its input gradient to dh[(l-1)%2]
+  for (int l = m->first_layer[k] - 1; l >= m->first_layer[k - 1]; --l) {
+    char* dh = (l % 2) ? m->dh1 : m->dh0;
+    char* dx = (l % 2) ? m->dh0 : m->dh1;
+    RUN(layer_backward(m, l, dh, dx, gslot));
+  }
+  m->tags[k][slot] = m->t;
+  if (k == 1) {
+    // Eq. 7 (left): dV_i rows = scattered error gradient of the embedding output
+    int64_t s0, t0;
+    ouro_slot_index(K, 0, m->t, 1, &s0, &t0);
+    float* dvi = m->slot_ptr(0, s0);
+    HIPCHK(launch_fill_zero(m->stream, dvi, (size_t)m->gcount[0] * 4));
+    HIPCHK(launch_embed_bwd(m->stream, c.dtype, m->tok, m->dh1, dvi, N, d, V, c.emb_scale));
+    m->tags[0][s0] = m->t;
+  }
+  m->bwd_next = k - 1;
+  return OURO_OK;
+}
+
+// ------------------------------------------------------------------------------- update
+static int close_iteration(ouro_model* m) {
+  const ouro_config& c = m->cfg;
+  if (c.mem_len > 0) {
+    // memory for t+1 = last M rows of [memory ; layer input] (constants, no gradient)
+    const int T = c.seq_len, d = c.d_model, Mv = m->mem_valid, S = Mv + T;
+    const int Mn = std::min(c.mem_len, S);
+    for (int l = 0; l < c.n_layer; ++l) {
+      LayerBuf& b = m->L[l];
+      const char* cat = Mv > 0 ? b.cat : b.x;
+      HIPCHK(launch_copy_rows(m->stream, c.dtype, b.mem, (size_t)Mn * d, 0, cat, (size_t)S * d, (size_t)(S - Mn) * d, c.batch, Mn, d));
+    }
+    m->mem_valid = Mn;
+  }
+  m->t += 1;
+  m->fwd_next = 1; m->bwd_next = c.n_module; m->upd_mask = 0; m->inject_mask = 0;
+  return OURO_OK;
+}
+
+extern "C" int ouro_delayed_update(ouro_model* m, int group, float lr) {
+  if (!m) return fail(OURO_E_ARG, "model is null");
+  const ouro_config& c = m->cfg;
+  const int K = c.n_module;
+  if (group < 0 || group > K) return fail(OURO_E_ARG, "delayed_update: group=%d outside 0..%d", group, K);
+  if (m->fwd_next != K + 1 || m->bwd_next != 0) return fail(OURO_E_SEQUENCE, "delayed_update before backward of module 1");
+  if (m->upd_mask & (1ull << group)) return fail(OURO_E_SEQUENCE, "delayed_update(%d) twice in one iteration", group);
+  UpdateDesc u;
+  memset(&u, 0, sizeof u);
+  u.w = m->master[group]; u.m = m->adam_m[group]; u.v = m->adam_v[group]; u.shadow = m->shadow[group];
+  u.n = (size_t)m->count[group]; u.adam = c.optimizer; u.lr = lr;
+  u.beta1 = c.beta1; u.beta2 = c.beta2; u.eps = c.eps;
+  u.bc1 = (float)(1.0 - std::pow((double)c.beta1, (double)(m->t + 1)));   // global t+1 (Algorithm 2)
+  u.bc2 = (float)(1.0 - std::pow((double)c.beta2, (double)(m->t + 1)));
+  int64_t slot, tau;
+  if (group >= 1) {
+    ouro_slot_index(K, group, m->t, 0, &slot, &tau);                        // Eq. 8
+    m->last_slot[group] = slot; m->last_tau[group] = tau;
+    if (tau >= 0) {
+      if (m->tags[group][slot] != tau) return fail(OURO_E_STALE, "module %d slot %lld holds iteration %lld, wanted %lld", group, (long long)slot, (long long)m->tags[group][slot], (long long)tau);
+      u.g0 = m->slot_ptr(group, slot); u.gscale0 = 1.f;
+    }
+  } else {
+    int64_t si, ti;                                                         // Eq. 9
+    ouro_slot_index(K, 0, m->t, 0, &si, &ti);
+    m->last_slot[0] = si; m->last_tau[0] = ti;
+    m->last_slot[K + 1] = -1; m->last_tau[K + 1] = -1;
+    if (ti >= 0 || c.embed_warm_mode == 1) {
+      if (m->tags[K + 1][0] != m->t) return fail(OURO_E_STALE, "dV_o slot holds iteration %lld, wanted %lld", (long long)m->tags[K + 1][0], (long long)m->t);
+      u.g0 = m->slot_ptr(K + 1, 0); u.gscale0 = 0.5f;
+      m->last_slot[K + 1] = 0; m->last_tau[K + 1] = m->t;
+    }
+    if (ti >= 0) {
+      if (m->tags[0][si] != ti) return fail(OURO_E_STALE, "dV_i slot %lld holds iteration %lld, wanted %lld", (long long)si, (long long)m->tags[0][si], (long long)ti);
+      u.g1 = m->slot_ptr(0, si); u.gscale1 = 0.5f;
+    }
+  }
+  HIPCHK(launch_update(m->stream, u));
+  m->upd_mask |= 1ull << group;
+  if (m->upd_mask == (1ull << (K + 1)) - 1) return close_iteration(m);
+  return OURO_OK;
+}
+
+static int read_loss(ouro_model* m, float* host_loss) {
+  struct { float loss; int flag; } h;
+  HIPCHK(hipMemcpyAsync(&h.loss, m->loss, 4, hipMemcpyDeviceToHost, m->stream));
+  HIPCHK(hipMemcpyAsync(&h.flag, m->flag, 4, hipMemcpyDeviceToHost, m->stream));
+  HIPCHK(hipStreamSynchronize(m->stream));
+  *host_loss = h.loss;
+  if (h.flag) return fail(OURO_E_TOKEN, "token or target id outside [0, vocab) (flag %d)", h.flag);
+  return OURO_OK;
+}
+
+extern "C" int ouro_get_loss(ouro_model* m, float* host_loss) {
+  if (!m || !host_loss) return fail(OURO_E_ARG, "get_loss: bad argument");
+  return read_loss(m, host_loss);
+}
+
+extern "C" int ouro_step(ouro_model* m, const int32_t* dev_tokens, const int32_t* dev_targets, float lr,
+                         float* host_loss) {
+  if (!m || !dev_tokens || !dev_targets) return fail(OURO_E_ARG, "step: null argument");
+  const int K = m->cfg.n_module;
+  for (int k = 1; k <= K; ++k) RUN(ouro_module_forward(m, k, dev_tokens, dev_targets));
+  for (int k = K; k >= 1; --k) RUN(ouro_module_backward(m, k));
+  for (int k = 1; k <= K; ++k) RUN(ouro_delayed_update(m, k, lr));
+  RUN(ouro_delayed_update(m, 0, lr));
+  if (host_loss) return read_loss(m, host_loss);
+  return OURO_OK;
+}
+
+// -------------------------------------------------------------------------- debug hooks
+extern "C" int ouro_debug_slot_tag(ouro_model* m, int id, int64_t slot, int64_t* tag) {
+  if (!m || !tag || id < 0 || id > m->cfg.n_module + 1 || slot < 0 || slot >= m->depth[id]) return fail(OURO_E_ARG, "slot_tag: bad argument");
+  *tag = m->tags[id][slot];
+  return OURO_OK;
+}
+
+extern "C" int ouro_debug_last_read(ouro_model* m, int id, int64_t* slot, int64_t* tau) {
+  if (!m || !slot || !tau || id < 0 || id > m->cfg.n_module + 1) return fail(OURO_E_ARG, "last_read: bad argument");
+  *slot = m->last_slot[id];
+  *tau = m->last_tau[id];
+  return OURO_OK;
+}
+
+extern "C" int ouro_debug_inject_grad(ouro_model* m, int id, const float* host_g, int64_t n) {
+  if (!m || !host_g) return fail(OURO_E_ARG, "inject_grad: null argument");
+  const int K = m->cfg.n_module;
+  if (id < 0 || id > K + 1) return fail(OURO_E_ARG, "inject_grad: id=%d outside 0..%d", id, K + 1);
+  if (n != m->gcount[id]) return fail(OURO_E_ARG, "inject_grad: store %d has %lld elements", id, (long long)m->gcount[id]);
+  if (m->fwd_next != 1 && !m->inject_mask) return fail(OURO_E_SEQUENCE, "inject_grad after module_forward in the same iteration");
+  if (m->inject_mask & (1ull << id)) return fail(OURO_E_SEQUENCE, "inject_grad(%d) twice in one iteration", id);
+  int64_t slot, tau;
+  ouro_slot_index(K, id, m->t, 1, &slot, &tau);
+  HIPCHK(hipMemcpyAsync(m->slot_ptr(id, slot), host_g, (size_t)n * 4, hipMemcpyHostToDevice, m->stream));
+  HIPCHK(hipStreamSynchronize(m->stream));
+  m->tags[id][slot] = m->t;
+  m->inject_mask |= 1ull << id;
+  if (m->inject_mask == (1ull << (K + 2)) - 1) { m->fwd_next = K + 1; m->bwd_next = 0; }
+  return OURO_OK;
+}
+
+extern "C" int ouro_get_grad_slot(ouro_model* m, int id, int64_t tau, float* host_dst, int64_t n) {
+  if (!m || !host_dst || id < 0 || id > m->cfg.n_module + 1 || tau < 0) return fail(OURO_E_ARG, "get_grad_slot: bad argument");
+  if (n != m->gcount[id]) return fail(OURO_E_ARG, "get_grad_slot: wrong element count");
+  int64_t slot = tau % m->depth[id];
+  if (m->tags[id][slot] != tau) return fail(OURO_E_STALE, "store %d no longer holds iteration %lld", id, (long long)tau);
+  HIPCHK(hipMemcpyAsync(host_dst, m->slot_ptr(id, slot), (size_t)n * 4, hipMemcpyDeviceToHost, m->stream));
+  HIPCHK(hipStreamSynchronize(m->stream));
+  return OURO_OK;
+}
+
+extern "C" int ouro_get_mems(ouro_model* m, int layer, float* host_dst, int64_t* valid_len) {
+  if (!m || !valid_len || layer < 0 || layer >= m->cfg.n_layer) return fail(OURO_E_ARG, "get_mems: bad argument");
+  *valid_len = m->mem_valid;
+  if (!host_dst || m->mem_valid == 0) return OURO_OK;
+  size_t n = (size_t)m->cfg.batch * m->mem_valid * m->cfg.d_model;
+  HIPCHK(launch_to_f32(m->stream, m->cfg.dtype, m->dbg_f32, m->L[layer].mem, n));
+  HIPCHK(hipMemcpyAsync(host_dst, m->dbg_f32, n * 4, hipMemcpyDeviceToHost, m->stream));
+  HIPCHK(hipStreamSynchronize(m->stream));
+  return OURO_OK;
+}
+
+extern "C" int ouro_debug_get_hidden(ouro_model* m, int layer, float* host_dst, int64_t n) {
+  if (!m || !host_dst || layer < 0 || layer > m->cfg.n_layer) return fail(OURO_E_ARG, "get_hidden: bad argument");
+  size_t cnt = (size_t)m->N * m->cfg.d_model;
+  if ((size_t)n != cnt) return fail(OURO_E_ARG, "get_hidden: wrong element count");
+  const char* src = layer < m->cfg.n_layer ? m->L[layer].x : m->hL;
+  HIPCHK(launch_to_f32(m->stream, m->cfg.dtype, m->dbg_f32, src, cnt));
+  HIPCHK(hipMemcpyAsync(host_dst, m->dbg_f32, cnt * 4, hipMemcpyDeviceToHost, m->stream));
+  HIPCHK(hipStreamSynchronize(m->stream));
+  return OURO_OK;
+}
+
+extern "C" int ouro_debug_gemm_timing(ouro_model* m, int timing, double* ms, int64_t* launches, double* flops) {
+  if (!m) return fail(OURO_E_ARG, "model is null");
+  HIPCHK(hipStreamSynchronize(m->stream));
+  double total = 0;
+  for (size_t i = 0; i + 1 < m->ev_used; i += 2) {
+    float t = 0;
+    HIPCHK(hipEventElapsedTime(&t, m->ev[i], m->ev[i + 1]));
+    total += t;
+  }
+  if (ms) *ms = total;
+  if (launches) *launches = m->timed_launches;
+  if (flops) *flops = m->timed_flops;
+  m->ev_used = 0; m->timed_flops = 0; m->timed_launches = 0;
+  m->timing = timing;
+  return OURO_OK;
+}

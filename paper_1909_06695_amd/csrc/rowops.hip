@@ -1,0 +1,508 @@
+// Bandwidth-bound kernels of the step: LayerNorm forward/backward, column sums (bias and
+// LayerNorm parameter gradients), embedding gather / scatter-add, softmax cross-entropy
+// rows, conversions, and the delayed SGD / Adam update.
+#include "common.h"
+
+namespace ouro {
+
+// 16-byte packs: 4 fp32 or 8 bf16
+template <typename T> struct Pack { static constexpr int N = 16 / sizeof(T); };
+template <typename T> __device__ __forceinline__ void load_pack(const T* p, float* out);
+template <> __device__ __forceinline__ void load_pack<float>(const float* p, float* out) {
+  float4 v = *reinterpret_cast<const float4*>(p);
+  out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+}
+template <> __device__ __forceinline__ void load_pack<bf16_t>(const bf16_t* p, float* out) {
+  uint4 v = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    out[2 * i] = __uint_as_float(w[i] << 16);
+    out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+}
+template <typename T> __device__ __forceinline__ void store_pack(T* p, const float* in);
+template <> __device__ __forceinline__ void store_pack<float>(float* p, const float* in) {
+  *reinterpret_cast<float4*>(p) = make_float4(in[0], in[1], in[2], in[3]);
+}
+template <> __device__ __forceinline__ void store_pack<bf16_t>(bf16_t* p, const float* in) {
+  union { bf16_t h[8]; uint4 v; } u;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) u.h[i] = (bf16_t)in[i];
+  *reinterpret_cast<uint4*>(p) = u.v;
+}
+
+// ------------------------------------------------------------------------ LayerNorm fwd
+// One wavefront per row.  VEC: row held in registers as up to MAXI 16-byte packs per lane.
+template <typename T, int MAXI>
+__global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const T* __restrict__ x, const float* __restrict__ g,
+                                                         const float* __restrict__ b, T* __restrict__ y,
+                                                         float* __restrict__ mean, float* __restrict__ rstd,
+                                                         int rows, int d) {
+  constexpr int N = Pack<T>::N;
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int nvec = d / N;
+  float v[MAXI][N];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXI; ++i) {
+    int vi = lane + 64 * i;
+    if (vi < nvec) {
+      load_pack<T>(x + (size_t)row * d + vi * N, v[i]);
+#pragma unroll
+      for (int e = 0; e < N; ++e) s += v[i][e];
+    }
+  }
+  const float mu = wave_sum(s) / d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXI; ++i) {
+    int vi = lane + 64 * i;
+    if (vi < nvec) {
+#pragma unroll
+      for (int e = 0; e < N; ++e) { float t = v[i][e] - mu; q += t * t; }
+    }
+  }
+  const float rs = rsqrtf(wave_sum(q) / d + 1e-5f);
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+#pragma unroll
+  for (int i = 0; i < MAXI; ++i) {
+    int vi = lane + 64 * i;
+    if (vi < nvec) {
+      float out[N];
+#pragma unroll
+      for (int e = 0; e < N; ++e) out[e] = (v[i][e] - mu) * rs * g[vi * N + e] + b[vi * N + e];
+      store_pack<T>(y + (size_t)row * d + vi * N, out);
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void ln_fwd_scalar_kernel(const T* __restrict__ x, const float* __restrict__ g,
+                                                            const float* __restrict__ b, T* __restrict__ y,
+                                                            float* __restrict__ mean, float* __restrict__ rstd,
+                                                            int rows, int d) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const T* xr = x + (size_t)row * d;
+  float s = 0.f;
+  for (int c = lane; c < d; c += 64) s += to_f32(xr[c]);
+  const float mu = wave_sum(s) / d;
+  float q = 0.f;
+  for (int c = lane; c < d; c += 64) { float t = to_f32(xr[c]) - mu; q += t * t; }
+  const float rs = rsqrtf(wave_sum(q) / d + 1e-5f);
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+  for (int c = lane; c < d; c += 64)
+    y[(size_t)row * d + c] = from_f32<T>((to_f32(xr[c]) - mu) * rs * g[c] + b[c]);
+}
+
+hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, const void* x, const float* g, const float* b,
+                                void* y, float* mean, float* rstd, int rows, int d) {
+  if (rows <= 0) return hipSuccess;
+  dim3 grid((rows + 3) / 4), block(256);
+  if (dtype == 1) {
+    if (d % 8 == 0 && d / 8 <= 256)
+      hipLaunchKernelGGL((ln_fwd_vec_kernel<bf16_t, 4>), grid, block, 0, s, (const bf16_t*)x, g, b, (bf16_t*)y, mean, rstd, rows, d);
+    else
+      hipLaunchKernelGGL(ln_fwd_scalar_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, g, b, (bf16_t*)y, mean, rstd, rows, d);
+  } else {
+    if (d % 4 == 0 && d / 4 <= 256)
+      hipLaunchKernelGGL((ln_fwd_vec_kernel<float, 4>), grid, block, 0, s, (const float*)x, g, b, (float*)y, mean, rstd, rows, d);
+    else
+      hipLaunchKernelGGL(ln_fwd_scalar_kernel<float>, grid, block, 0, s, (const float*)x, g, b, (float*)y, mean, rstd, rows, d);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------ LayerNorm bwd
+// dx = rstd * (dyg - mean(dyg) - xhat * mean(dyg * xhat)), dyg = dy * g
+template <typename T>
+__global__ __launch_bounds__(256) void ln_bwd_dx_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                        const float* __restrict__ g, const float* __restrict__ mean,
+                                                        const float* __restrict__ rstd, T* __restrict__ dx,
+                                                        int rows, int d) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const T* xr = x + (size_t)row * d;
+  const T* dyr = dy + (size_t)row * d;
+  const float mu = mean[row], rs = rstd[row];
+  float s1 = 0.f, s2 = 0.f;
+  for (int c = lane; c < d; c += 64) {
+    float xh = (to_f32(xr[c]) - mu) * rs;
+    float t = to_f32(dyr[c]) * g[c];
+    s1 += t;
+    s2 += t * xh;
+  }
+  s1 = wave_sum(s1) / d;
+  s2 = wave_sum(s2) / d;
+  for (int c = lane; c < d; c += 64) {
+    float xh = (to_f32(xr[c]) - mu) * rs;
+    float t = to_f32(dyr[c]) * g[c];
+    dx[(size_t)row * d + c] = from_f32<T>(rs * (t - s1 - xh * s2));
+  }
+}
+
+template <typename T, int MAXI>
+__global__ __launch_bounds__(256) void ln_bwd_dx_vec_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                            const float* __restrict__ g, const float* __restrict__ mean,
+                                                            const float* __restrict__ rstd, T* __restrict__ dx,
+                                                            int rows, int d) {
+  constexpr int N = Pack<T>::N;
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int nvec = d / N;
+  const float mu = mean[row], rs = rstd[row];
+  float xh[MAXI][N], t[MAXI][N];
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXI; ++i) {
+    int vi = lane + 64 * i;
+    if (vi < nvec) {
+      load_pack<T>(x + (size_t)row * d + vi * N, xh[i]);
+      load_pack<T>(dy + (size_t)row * d + vi * N, t[i]);
+#pragma unroll
+      for (int e = 0; e < N; ++e) {
+        xh[i][e] = (xh[i][e] - mu) * rs;
+        t[i][e] *= g[vi * N + e];
+        s1 += t[i][e];
+        s2 += t[i][e] * xh[i][e];
+      }
+    }
+  }
+  s1 = wave_sum(s1) / d;
+  s2 = wave_sum(s2) / d;
+#pragma unroll
+  for (int i = 0; i < MAXI; ++i) {
+    int vi = lane + 64 * i;
+    if (vi < nvec) {
+      float out[N];
+#pragma unroll
+      for (int e = 0; e < N; ++e) out[e] = rs * (t[i][e] - s1 - xh[i][e] * s2);
+      store_pack<T>(dx + (size_t)row * d + vi * N, out);
+    }
+  }
+}
+
+// Column sums over a chunk of rows; 64 columns x 4 row lanes per block, then atomics.
+// MODE 0: out0[c] += sum x[r,c].  MODE 1 (LayerNorm): out0[c] += sum dy*xhat, out1[c] += sum dy.
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, int ldx, const T* __restrict__ x2,
+                                                     const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                     float* __restrict__ out0, float* __restrict__ out1,
+                                                     int rows, int cols, int rows_per_block) {
+  __shared__ float red0[4][64];
+  __shared__ float red1[4][64];
+  const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cx;
+  const int rbeg = blockIdx.y * rows_per_block;
+  const int rend = min(rows, rbeg + rows_per_block);
+  float a0 = 0.f, a1 = 0.f;
+  if (c < cols) {
+    for (int r = rbeg + ry; r < rend; r += 4) {
+      float v = to_f32(x[(size_t)r * ldx + c]);
+      if (MODE == 0) {
+        a0 += v;
+      } else {
+        float xh = (to_f32(x2[(size_t)r * ldx + c]) - mean[r]) * rstd[r];
+        a0 += v * xh;
+        a1 += v;
+      }
+    }
+  }
+  red0[ry][cx] = a0;
+  red1[ry][cx] = a1;
+  __syncthreads();
+  if (ry == 0 && c < cols) {
+    float t0 = red0[0][cx] + red0[1][cx] + red0[2][cx] + red0[3][cx];
+    unsafeAtomicAdd(out0 + c, t0);
+    if (MODE == 1) {
+      float t1 = red1[0][cx] + red1[1][cx] + red1[2][cx] + red1[3][cx];
+      unsafeAtomicAdd(out1 + c, t1);
+    }
+  }
+}
+
+hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const float* g,
+                                const float* mean, const float* rstd, void* dx, float* dg, float* db,
+                                int rows, int d) {
+  if (rows <= 0) return hipSuccess;
+  dim3 grid((rows + 3) / 4), block(256);
+  const int rpb = 128;
+  dim3 g2((d + 63) / 64, (rows + rpb - 1) / rpb);
+  if (dtype == 1) {
+    if (d % 8 == 0 && d / 8 <= 256)
+      hipLaunchKernelGGL((ln_bwd_dx_vec_kernel<bf16_t, 4>), grid, block, 0, s, (const bf16_t*)dy, (const bf16_t*)x, g, mean, rstd, (bf16_t*)dx, rows, d);
+    else
+      hipLaunchKernelGGL(ln_bwd_dx_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)dy, (const bf16_t*)x, g, mean, rstd, (bf16_t*)dx, rows, d);
+    hipLaunchKernelGGL((colsum_kernel<bf16_t, 1>), g2, block, 0, s, (const bf16_t*)dy, d, (const bf16_t*)x, mean, rstd, dg, db, rows, d, rpb);
+  } else {
+    if (d % 4 == 0 && d / 4 <= 256)
+      hipLaunchKernelGGL((ln_bwd_dx_vec_kernel<float, 4>), grid, block, 0, s, (const float*)dy, (const float*)x, g, mean, rstd, (float*)dx, rows, d);
+    else
+      hipLaunchKernelGGL(ln_bwd_dx_kernel<float>, grid, block, 0, s, (const float*)dy, (const float*)x, g, mean, rstd, (float*)dx, rows, d);
+    hipLaunchKernelGGL((colsum_kernel<float, 1>), g2, block, 0, s, (const float*)dy, d, (const float*)x, mean, rstd, dg, db, rows, d, rpb);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_colsum(hipStream_t s, int dtype, const void* x, int ldx, float* out, int rows, int cols) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  const int rpb = 128;
+  dim3 grid((cols + 63) / 64, (rows + rpb - 1) / rpb), block(256);
+  if (dtype == 1)
+    hipLaunchKernelGGL((colsum_kernel<bf16_t, 0>), grid, block, 0, s, (const bf16_t*)x, ldx, (const bf16_t*)nullptr, nullptr, nullptr, out, nullptr, rows, cols, rpb);
+  else
+    hipLaunchKernelGGL((colsum_kernel<float, 0>), grid, block, 0, s, (const float*)x, ldx, (const float*)nullptr, nullptr, nullptr, out, nullptr, rows, cols, rpb);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------- embedding
+template <typename T>
+__global__ __launch_bounds__(256) void embed_fwd_kernel(const int32_t* __restrict__ tok, const T* __restrict__ V,
+                                                        const float* __restrict__ pe, T* __restrict__ h, int N, int T_,
+                                                        int d, int vocab, float scale, int* flag) {
+  const int lane = threadIdx.x & 63;
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (n >= N) return;
+  const int id = tok[n];
+  const bool ok = id >= 0 && id < vocab;
+  if (!ok && lane == 0) atomicOr(flag, 1);
+  const T* row = V + (size_t)(ok ? id : 0) * d;
+  const float* per = pe ? pe + (size_t)(n % T_) * d : nullptr;
+  for (int c = lane; c < d; c += 64) {
+    float v = ok ? scale * to_f32(row[c]) : 0.f;
+    if (per) v += per[c];
+    h[(size_t)n * d + c] = from_f32<T>(v);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void embed_bwd_kernel(const int32_t* __restrict__ tok, const T* __restrict__ dh,
+                                                        float* __restrict__ dVi, int N, int d, int vocab, float scale) {
+  const int lane = threadIdx.x & 63;
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (n >= N) return;
+  const int id = tok[n];
+  if (id < 0 || id >= vocab) return;
+  for (int c = lane; c < d; c += 64)
+    unsafeAtomicAdd(dVi + (size_t)id * d + c, scale * to_f32(dh[(size_t)n * d + c]));
+}
+
+hipError_t launch_embed_fwd(hipStream_t s, int dtype, const int32_t* tok, const void* V, const float* pe,
+                            void* h, int N, int T, int d, int vocab, float scale, int* flag) {
+  dim3 grid((N + 3) / 4), block(256);
+  if (dtype == 1) hipLaunchKernelGGL(embed_fwd_kernel<bf16_t>, grid, block, 0, s, tok, (const bf16_t*)V, pe, (bf16_t*)h, N, T, d, vocab, scale, flag);
+  else hipLaunchKernelGGL(embed_fwd_kernel<float>, grid, block, 0, s, tok, (const float*)V, pe, (float*)h, N, T, d, vocab, scale, flag);
+  return hipGetLastError();
+}
+
+hipError_t launch_embed_bwd(hipStream_t s, int dtype, const int32_t* tok, const void* dh, float* dVi,
+                            int N, int d, int vocab, float scale) {
+  dim3 grid((N + 3) / 4), block(256);
+  if (dtype == 1) hipLaunchKernelGGL(embed_bwd_kernel<bf16_t>, grid, block, 0, s, tok, (const bf16_t*)dh, dVi, N, d, vocab, scale);
+  else hipLaunchKernelGGL(embed_bwd_kernel<float>, grid, block, 0, s, tok, (const float*)dh, dVi, N, d, vocab, scale);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------ cross entropy
+// One block per row: online (max, sum) over the vocabulary, then G = (softmax - onehot)/N.
+template <typename T>
+__global__ __launch_bounds__(256) void ce_rows_kernel(const float* __restrict__ logits, int ld,
+                                                      const int32_t* __restrict__ tgt, T* __restrict__ G, int ldg,
+                                                      float* __restrict__ lse_out, float* __restrict__ rowloss,
+                                                      int N, int vocab, int* flag) {
+  __shared__ float sm_m[4], sm_s[4];
+  const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* row = logits + (size_t)n * ld;
+  float m = -INFINITY, ssum = 0.f;
+  for (int c = tid; c < vocab; c += 256) {
+    float v = row[c];
+    if (v > m) { ssum = ssum * __expf(m - v) + 1.f; m = v; }
+    else ssum += __expf(v - m);
+  }
+  float wm = wave_max(m);
+  ssum = (m == -INFINITY) ? 0.f : ssum * __expf(m - wm);
+  ssum = wave_sum(ssum);
+  if (lane == 0) { sm_m[wave] = wm; sm_s[wave] = ssum; }
+  __syncthreads();
+  float bm = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
+  float bs = 0.f;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) bs += sm_s[w] * __expf(sm_m[w] - bm);
+  const float lse = bm + logf(bs);
+  const int t = tgt[n];
+  const bool ok = t >= 0 && t < vocab;
+  if (tid == 0) {
+    lse_out[n] = lse;
+    rowloss[n] = ok ? lse - row[t] : 0.f;
+    if (!ok) atomicOr(flag, 2);
+  }
+  const float invN = 1.f / N;
+  for (int c = tid; c < vocab; c += 256) {
+    float gval = __expf(row[c] - lse);
+    if (ok && c == t) gval -= 1.f;
+    G[(size_t)n * ldg + c] = from_f32<T>(gval * invN);
+  }
+}
+
+hipError_t launch_ce_rows(hipStream_t s, int dtype, const float* logits, int ld, const int32_t* tgt,
+                          void* G, int ldg, float* lse, float* rowloss, int N, int vocab, int* flag) {
+  dim3 grid(N), block(256);
+  if (dtype == 1) hipLaunchKernelGGL(ce_rows_kernel<bf16_t>, grid, block, 0, s, logits, ld, tgt, (bf16_t*)G, ldg, lse, rowloss, N, vocab, flag);
+  else hipLaunchKernelGGL(ce_rows_kernel<float>, grid, block, 0, s, logits, ld, tgt, (float*)G, ldg, lse, rowloss, N, vocab, flag);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void sum_rows_kernel(const float* __restrict__ rowloss, int N, float* loss) {
+  __shared__ float red[256];
+  float a = 0.f;
+  for (int i = threadIdx.x; i < N; i += 256) a += rowloss[i];
+  red[threadIdx.x] = a;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *loss = red[0] / N;
+}
+
+hipError_t launch_sum_rows(hipStream_t s, const float* rowloss, int N, float* loss) {
+  hipLaunchKernelGGL(sum_rows_kernel, dim3(1), dim3(256), 0, s, rowloss, N, loss);
+  return hipGetLastError();
+}
+
+// -------------------------------------------------------------------------- conversions
+template <typename T>
+__global__ void convert_kernel(T* dst, const float* src, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] = from_f32<T>(src[i]);
+}
+template <typename T>
+__global__ void to_f32_kernel(float* dst, const T* src, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] = to_f32(src[i]);
+}
+__global__ void fill_zero_kernel(uint32_t* p, size_t nwords) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  const size_t n4 = nwords / 4;
+  uint4* p4 = reinterpret_cast<uint4*>(p);
+  for (size_t j = i; j < n4; j += stride) p4[j] = make_uint4(0, 0, 0, 0);
+  for (size_t j = n4 * 4 + i; j < nwords; j += stride) p[j] = 0;
+}
+static inline unsigned grid_for(size_t n, unsigned per_block = 256, unsigned cap = 8192) {
+  size_t g = (n + per_block - 1) / per_block;
+  if (g > cap) g = cap;
+  if (g < 1) g = 1;
+  return (unsigned)g;
+}
+hipError_t launch_convert(hipStream_t s, int dtype_dst, void* dst, const float* src, size_t n) {
+  if (n == 0) return hipSuccess;
+  if (dtype_dst == 1) hipLaunchKernelGGL(convert_kernel<bf16_t>, dim3(grid_for(n)), dim3(256), 0, s, (bf16_t*)dst, src, n);
+  else hipLaunchKernelGGL(convert_kernel<float>, dim3(grid_for(n)), dim3(256), 0, s, (float*)dst, src, n);
+  return hipGetLastError();
+}
+hipError_t launch_to_f32(hipStream_t s, int dtype_src, float* dst, const void* src, size_t n) {
+  if (n == 0) return hipSuccess;
+  if (dtype_src == 1) hipLaunchKernelGGL(to_f32_kernel<bf16_t>, dim3(grid_for(n)), dim3(256), 0, s, dst, (const bf16_t*)src, n);
+  else hipLaunchKernelGGL(to_f32_kernel<float>, dim3(grid_for(n)), dim3(256), 0, s, dst, (const float*)src, n);
+  return hipGetLastError();
+}
+hipError_t launch_fill_zero(hipStream_t s, void* p, size_t bytes) {
+  if (bytes == 0) return hipSuccess;
+  if ((bytes & 3) || (reinterpret_cast<uintptr_t>(p) & 15)) return hipErrorInvalidValue;
+  size_t nwords = bytes / 4;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(grid_for(nwords / 4 + 1)), dim3(256), 0, s, (uint32_t*)p, nwords);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ void copy_rows_kernel(T* dst, size_t dst_bstride, size_t dst_off, const T* src, size_t src_bstride,
+                                 size_t src_off, int rows, int d) {
+  const int b = blockIdx.y;
+  const size_t n = (size_t)rows * d;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[b * dst_bstride + dst_off + i] = src[b * src_bstride + src_off + i];
+}
+hipError_t launch_copy_rows(hipStream_t s, int dtype, void* dst, size_t dst_bstride, size_t dst_off,
+                            const void* src, size_t src_bstride, size_t src_off, int B, int rows, int d) {
+  if (B <= 0 || rows <= 0) return hipSuccess;
+  dim3 grid(grid_for((size_t)rows * d, 256, 1024), B), block(256);
+  if (dtype == 1) hipLaunchKernelGGL(copy_rows_kernel<bf16_t>, grid, block, 0, s, (bf16_t*)dst, dst_bstride, dst_off, (const bf16_t*)src, src_bstride, src_off, rows, d);
+  else hipLaunchKernelGGL(copy_rows_kernel<float>, grid, block, 0, s, (float*)dst, dst_bstride, dst_off, (const float*)src, src_bstride, src_off, rows, d);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------- update
+// Algorithm 1: w -= lr*g.  Algorithm 2: m = b1 m + (1-b1) g; v = b2 v + (1-b2) g^2;
+// w -= lr * (m/bc1) / (sqrt(v/bc2) + eps).  16 bytes per lane per stream.
+struct UpdParams {
+  float* w; float* m; float* v; bf16_t* shadow;
+  const float* g0; const float* g1; float s0, s1;
+  size_t n; float lr, b1, b2, eps, bc1, bc2;
+};
+template <bool ADAM>
+__device__ __forceinline__ float upd_one(float w, float g, float& m, float& v, const UpdParams& p) {
+  if (!ADAM) return w - p.lr * g;
+  m = p.b1 * m + (1.f - p.b1) * g;
+  v = p.b2 * v + (1.f - p.b2) * g * g;
+  float mh = m / p.bc1, vh = v / p.bc2;
+  return w - p.lr * (mh / (sqrtf(vh) + p.eps));
+}
+template <bool ADAM>
+__global__ __launch_bounds__(256) void update_kernel(UpdParams p) {
+  const size_t n4 = p.n / 4;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t j = i; j < n4; j += stride) {
+    float4 w = reinterpret_cast<float4*>(p.w)[j];
+    float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (p.g0) { float4 a = reinterpret_cast<const float4*>(p.g0)[j]; g.x = p.s0 * a.x; g.y = p.s0 * a.y; g.z = p.s0 * a.z; g.w = p.s0 * a.w; }
+    if (p.g1) { float4 a = reinterpret_cast<const float4*>(p.g1)[j]; g.x += p.s1 * a.x; g.y += p.s1 * a.y; g.z += p.s1 * a.z; g.w += p.s1 * a.w; }
+    float4 m = make_float4(0.f, 0.f, 0.f, 0.f), v = m;
+    if (ADAM) { m = reinterpret_cast<float4*>(p.m)[j]; v = reinterpret_cast<float4*>(p.v)[j]; }
+    w.x = upd_one<ADAM>(w.x, g.x, m.x, v.x, p);
+    w.y = upd_one<ADAM>(w.y, g.y, m.y, v.y, p);
+    w.z = upd_one<ADAM>(w.z, g.z, m.z, v.z, p);
+    w.w = upd_one<ADAM>(w.w, g.w, m.w, v.w, p);
+    reinterpret_cast<float4*>(p.w)[j] = w;
+    if (ADAM) { reinterpret_cast<float4*>(p.m)[j] = m; reinterpret_cast<float4*>(p.v)[j] = v; }
+    if (p.shadow) {
+      union { bf16_t h[4]; uint2 u; } cv;
+      cv.h[0] = (bf16_t)w.x; cv.h[1] = (bf16_t)w.y; cv.h[2] = (bf16_t)w.z; cv.h[3] = (bf16_t)w.w;
+      reinterpret_cast<uint2*>(p.shadow)[j] = cv.u;
+    }
+  }
+  for (size_t j = n4 * 4 + i; j < p.n; j += stride) {
+    float g = 0.f;
+    if (p.g0) g = p.s0 * p.g0[j];
+    if (p.g1) g += p.s1 * p.g1[j];
+    float m = 0.f, v = 0.f;
+    if (ADAM) { m = p.m[j]; v = p.v[j]; }
+    float w = upd_one<ADAM>(p.w[j], g, m, v, p);
+    p.w[j] = w;
+    if (ADAM) { p.m[j] = m; p.v[j] = v; }
+    if (p.shadow) p.shadow[j] = (bf16_t)w;
+  }
+}
+
+hipError_t launch_update(hipStream_t s, const UpdateDesc& u) {
+  if (u.n == 0) return hipSuccess;
+  UpdParams p;
+  p.w = u.w; p.m = u.m; p.v = u.v; p.shadow = u.shadow; p.g0 = u.g0; p.g1 = u.g1; p.s0 = u.gscale0; p.s1 = u.gscale1;
+  p.n = u.n; p.lr = u.lr; p.b1 = u.beta1; p.b2 = u.beta2; p.eps = u.eps; p.bc1 = u.bc1; p.bc2 = u.bc2;
+  dim3 grid(grid_for(u.n / 4 + 1, 256, 4096)), block(256);
+  if (u.adam) hipLaunchKernelGGL(update_kernel<true>, grid, block, 0, s, p);
+  else hipLaunchKernelGGL(update_kernel<false>, grid, block, 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace ouro

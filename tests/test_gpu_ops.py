@@ -1,0 +1,309 @@
+"""Per-kernel parity: each HIP kernel, called through the C boundary, against the CPU
+oracle's function for the same operation on the same seeded inputs."""
+import ctypes as C
+import math
+
+import numpy as np
+import pytest
+
+from oracle import ouro_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def L():
+    import paper_1909_06695_amd as P
+    return P.lib()
+
+
+def stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def dev(a, dtype):
+    """numpy -> device tensor of the op's element type (dtype 0 fp32, 1 bf16)."""
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16).contiguous() if dtype == 1 else t
+
+
+def host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def p(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def rel_err(a, b):
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def ok(rc):
+    assert rc == 0, L().ouro_last_error()
+
+
+TOL = {0: 2e-5, 1: 1e-2}
+
+
+# ------------------------------------------------------------------------------- GEMM
+@pytest.mark.parametrize("dtype,force", [(0, 0), (1, 1), (1, 0)])
+@pytest.mark.parametrize("tA,tB", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("M,N,K", [(200, 136, 328), (128, 256, 64), (72, 40, 1000), (384, 520, 96)])
+def test_gemm_forms(dtype, force, tA, tB, M, N, K):
+    rng = np.random.default_rng(M + 7 * N + 13 * K + tA * 2 + tB)
+    A = rng.standard_normal((K, M) if tA else (M, K)).astype(np.float32)
+    B = rng.standard_normal((N, K) if tB else (K, N)).astype(np.float32)
+    dA, dB = dev(A, dtype), dev(B, dtype)
+    out = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    ok(L().ouro_op_gemm(stream(), dtype, tA, tB, M, N, K, 1.0, p(dA), dA.shape[1], p(dB), dB.shape[1], p(out), N,
+                        1, 0, None, None, 0, 0, None, 0, force))
+    torch.cuda.synchronize()
+    a64, b64 = host(dA), host(dB)
+    ref = (a64.T if tA else a64) @ (b64.T if tB else b64)
+    assert rel_err(host(out), ref) < 2e-6
+    if dtype == 1 and not force:
+        assert L().ouro_op_gemm_uses_mfma(dtype, tA, tB, M, N, K, p(dA), dA.shape[1], p(dB), dB.shape[1]) == 1
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_gemm_epilogues_and_strides(dtype):
+    rng = np.random.default_rng(5)
+    M, N, K = 264, 200, 136
+    lda, ldb, ldc = K + 8, N + 16, N + 24
+    A = rng.standard_normal((M, lda)).astype(np.float32)
+    B = (rng.standard_normal((K, ldb)) * 0.2).astype(np.float32)
+    bias = rng.standard_normal(N).astype(np.float32)
+    R = rng.standard_normal((M, N)).astype(np.float32)
+    dA, dB, dR = dev(A, dtype), dev(B, dtype), dev(R, dtype)
+    dbias = torch.from_numpy(bias).cuda()
+    tdt = torch.bfloat16 if dtype else torch.float32
+    out = torch.zeros((M, ldc), dtype=tdt, device="cuda")
+    Z = torch.zeros((M, N), dtype=tdt, device="cuda")
+    a64, b64 = host(dA)[:, :K], host(dB)[:, :N]
+    pre = a64 @ b64 + bias
+    # bias + GELU (writes Z) + residual
+    ok(L().ouro_op_gemm(stream(), dtype, 0, 0, M, N, K, 1.0, p(dA), lda, p(dB), ldb, p(out), ldc, 0, 0, p(dbias), p(dR), N,
+                        1, p(Z), N, 0))
+    torch.cuda.synchronize()
+    assert rel_err(host(Z), pre) < TOL[dtype]
+    assert rel_err(host(out)[:, :N], O.gelu(pre) + host(dR)) < TOL[dtype]
+    assert np.all(host(out)[:, N:] == 0)
+    # multiply by GELU'(Z)
+    out2 = torch.zeros((M, N), dtype=tdt, device="cuda")
+    ok(L().ouro_op_gemm(stream(), dtype, 0, 0, M, N, K, 1.0, p(dA), lda, p(dB), ldb, p(out2), N, 0, 0, None, None, 0,
+                        2, p(Z), N, 0))
+    torch.cuda.synchronize()
+    assert rel_err(host(out2), (a64 @ b64) * O.gelu_grad(host(Z))) < TOL[dtype]
+    # accumulate (split-K path for bf16): C += A^T-form product
+    M2, N2, K2 = 136, 264, 4096
+    A2 = rng.standard_normal((K2, M2)).astype(np.float32)
+    B2 = rng.standard_normal((K2, N2)).astype(np.float32)
+    dA2, dB2 = dev(A2, dtype), dev(B2, dtype)
+    acc = torch.ones((M2, N2), dtype=torch.float32, device="cuda")
+    ok(L().ouro_op_gemm(stream(), dtype, 1, 0, M2, N2, K2, 1.0, p(dA2), M2, p(dB2), N2, p(acc), N2, 1, 1, None, None, 0,
+                        0, None, 0, 0))
+    torch.cuda.synchronize()
+    assert rel_err(host(acc), 1.0 + host(dA2).T @ host(dB2)) < 3e-6
+
+
+# -------------------------------------------------------------------------- attention
+def _attn_case(dtype, B, H, T, Mv, dh, rel, seed, force=1):
+    rng = np.random.default_rng(seed)
+    S = Mv + T
+    d = H * dh
+    q = rng.standard_normal((B * T, d)).astype(np.float32)
+    kv = rng.standard_normal((B * S, 2 * d)).astype(np.float32)
+    do = rng.standard_normal((B * T, d)).astype(np.float32)
+    u = (rng.standard_normal((H, dh)) * 0.5).astype(np.float32)
+    vb = (rng.standard_normal((H, dh)) * 0.5).astype(np.float32)
+    r = rng.standard_normal((S, d)).astype(np.float32)
+    dq_, dkv, ddo, du_, dvb_, dr_ = (dev(x, dtype) for x in (q, kv, do, u, vb, r))
+    tdt = torch.bfloat16 if dtype else torch.float32
+    o = torch.zeros((B * T, d), dtype=tdt, device="cuda")
+    lse = torch.zeros((B, H, T), dtype=torch.float32, device="cuda")
+    scale = 1.0 / math.sqrt(dh)
+    kptr = C.c_void_p(dkv.data_ptr())
+    vptr = C.c_void_p(dkv.data_ptr() + d * dkv.element_size())
+    ok(L().ouro_op_attention_fwd(stream(), dtype, B, H, T, S, dh, Mv, scale, p(dq_), d, kptr, 2 * d, vptr, 2 * d, p(o), d,
+                                 p(lse), rel, p(du_), p(dvb_), p(dr_), d, force))
+    # oracle on the same (rounded) inputs
+    q64 = host(dq_).reshape(B, T, H, dh).transpose(0, 2, 1, 3)
+    k64 = host(dkv)[:, :d].reshape(B, S, H, dh).transpose(0, 2, 1, 3)
+    v64 = host(dkv)[:, d:].reshape(B, S, H, dh).transpose(0, 2, 1, 3)
+    r64 = host(dr_).reshape(S, H, dh).transpose(1, 0, 2)
+    if rel:
+        oo, cache = O.attention_core_fwd(q64, k64, v64, Mv, scale, host(du_), host(dvb_), r64)
+    else:
+        oo, cache = O.attention_core_fwd(q64, k64, v64, Mv, scale)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    assert rel_err(host(o), oo.transpose(0, 2, 1, 3).reshape(B * T, d)) < tol
+    assert np.abs(host(lse) - cache["lse"]).max() < (1e-4 if dtype == 0 else 2e-2)
+    # backward
+    n_scr = L().ouro_op_attention_bwd_scratch(B, H, T, S, dh)
+    scr = torch.zeros(max(n_scr, 1), dtype=torch.float32, device="cuda")
+    gq = torch.zeros((B * T, d), dtype=tdt, device="cuda")
+    gkv = torch.zeros((B * S, 2 * d), dtype=tdt, device="cuda")
+    gu = torch.zeros((H, dh), dtype=torch.float32, device="cuda")
+    gvb = torch.zeros((H, dh), dtype=torch.float32, device="cuda")
+    gr = torch.zeros((S, d), dtype=torch.float32, device="cuda")
+    gk = C.c_void_p(gkv.data_ptr())
+    gv = C.c_void_p(gkv.data_ptr() + d * gkv.element_size())
+    ok(L().ouro_op_attention_bwd(stream(), dtype, B, H, T, S, dh, Mv, scale, p(dq_), d, kptr, 2 * d, vptr, 2 * d, p(o), d,
+                                 p(lse), p(ddo), d, p(gq), d, gk, 2 * d, gv, 2 * d, rel, p(du_), p(dvb_), p(dr_), d,
+                                 p(gu), p(gvb), p(gr), p(scr), force))
+    torch.cuda.synchronize()
+    do64 = host(ddo).reshape(B, T, H, dh).transpose(0, 2, 1, 3)
+    rq, rk, rv, ru, rvb, rr = O.attention_core_bwd(do64, cache)
+    mh = lambda x, n: x.transpose(0, 2, 1, 3).reshape(B * n, d)
+    btol = tol * 2
+    assert rel_err(host(gq), mh(rq, T)) < btol
+    assert rel_err(host(gkv)[:, :d], mh(rk, S)) < btol
+    assert rel_err(host(gkv)[:, d:], mh(rv, S)) < btol
+    if rel:
+        assert rel_err(host(gu), ru) < btol
+        assert rel_err(host(gvb), rvb) < btol
+        assert rel_err(host(gr), rr.transpose(1, 0, 2).reshape(S, d)) < btol
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("B,H,T,Mv,dh,rel", [(2, 2, 32, 0, 32, 0), (1, 3, 70, 0, 41, 0), (2, 2, 24, 17, 16, 1),
+                                               (1, 2, 67, 130, 41, 1), (1, 1, 1, 0, 8, 0), (2, 1, 5, 0, 8, 1)])
+def test_attention_general_kernel(dtype, B, H, T, Mv, dh, rel):
+    _attn_case(dtype, B, H, T, Mv, dh, rel, seed=B + H + T + Mv + dh)
+
+
+# ------------------------------------------------------------------ row-wise kernels
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("rows,d", [(37, 64), (130, 512), (9, 410), (5, 1024), (3, 4100)])
+def test_layernorm(dtype, rows, d):
+    rng = np.random.default_rng(rows + d)
+    x = (rng.standard_normal((rows, d)) * 2 + 0.5).astype(np.float32)
+    dy = rng.standard_normal((rows, d)).astype(np.float32)
+    g = (1 + 0.3 * rng.standard_normal(d)).astype(np.float32)
+    b = (0.2 * rng.standard_normal(d)).astype(np.float32)
+    dx_, ddy = dev(x, dtype), dev(dy, dtype)
+    dg_, db_ = torch.from_numpy(g).cuda(), torch.from_numpy(b).cuda()
+    tdt = torch.bfloat16 if dtype else torch.float32
+    y = torch.zeros((rows, d), dtype=tdt, device="cuda")
+    mean = torch.zeros(rows, device="cuda"); rstd = torch.zeros(rows, device="cuda")
+    ok(L().ouro_op_layernorm_fwd(stream(), dtype, p(dx_), p(dg_), p(db_), p(y), p(mean), p(rstd), rows, d))
+    yr, cache = O.layernorm_fwd(host(dx_), g.astype(np.float64), b.astype(np.float64))
+    torch.cuda.synchronize()
+    assert rel_err(host(y), yr) < TOL[dtype]
+    assert rel_err(host(rstd), cache[1][:, 0]) < 1e-5
+    gx = torch.zeros((rows, d), dtype=tdt, device="cuda")
+    gg = torch.full((d,), 7.0, device="cuda"); gb = torch.full((d,), 7.0, device="cuda")
+    ok(L().ouro_op_layernorm_bwd(stream(), dtype, p(ddy), p(dx_), p(dg_), p(mean), p(rstd), p(gx), p(gg), p(gb), rows, d))
+    torch.cuda.synchronize()
+    rx, rg, rb = O.layernorm_bwd(host(ddy), g.astype(np.float64), cache)
+    assert rel_err(host(gx), rx) < TOL[dtype]
+    assert rel_err(host(gg), rg) < 1e-4
+    assert rel_err(host(gb), rb) < 1e-4
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_colsum(dtype):
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((333, 200)).astype(np.float32)
+    dx_ = dev(x, dtype)
+    out = torch.full((150,), 3.0, device="cuda")
+    ok(L().ouro_op_colsum(stream(), dtype, p(dx_), 200, p(out), 333, 150))
+    torch.cuda.synchronize()
+    assert rel_err(host(out), host(dx_)[:, :150].sum(0)) < 1e-5
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_embedding_gather_scatter(dtype):
+    rng = np.random.default_rng(4)
+    vocab, d, T, B = 50, 24, 7, 5
+    N = B * T
+    V = rng.standard_normal((vocab, d)).astype(np.float32)
+    tok = rng.integers(0, vocab, N).astype(np.int32)
+    tok[:6] = 3                                           # a hot row
+    dV = dev(V, dtype)
+    dtok = torch.from_numpy(tok).cuda()
+    pe = rng.standard_normal((T, d)).astype(np.float32)
+    dpe = torch.from_numpy(pe).cuda()
+    tdt = torch.bfloat16 if dtype else torch.float32
+    h = torch.zeros((N, d), dtype=tdt, device="cuda")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ok(L().ouro_op_embed_fwd(stream(), dtype, p(dtok), p(dV), p(dpe), p(h), N, T, d, vocab, 1.5, p(flag)))
+    torch.cuda.synchronize()
+    ref = 1.5 * host(dV)[tok] + np.tile(pe, (B, 1))
+    if dtype == 0:
+        assert np.array_equal(host(h).astype(np.float32), ref.astype(np.float32))   # gather rows bit-exact
+    else:
+        assert rel_err(host(h), ref) < 4e-3
+    assert flag.item() == 0
+    dh = rng.standard_normal((N, d)).astype(np.float32)
+    ddh = dev(dh, dtype)
+    dVi = torch.full((vocab, d), 9.0, device="cuda")
+    ok(L().ouro_op_embed_bwd(stream(), dtype, p(dtok), p(ddh), p(dVi), N, d, vocab, 1.5))
+    torch.cuda.synchronize()
+    refg = np.zeros((vocab, d))
+    np.add.at(refg, tok, 1.5 * host(ddh))
+    assert rel_err(host(dVi), refg) < 1e-6
+    assert np.all(host(dVi)[np.setdiff1d(np.arange(vocab), tok)] == 0)
+    # out-of-range id: flagged, row skipped, nothing dereferenced
+    tok2 = tok.copy(); tok2[2] = vocab; tok2[3] = -1
+    dtok2 = torch.from_numpy(tok2).cuda()
+    ok(L().ouro_op_embed_fwd(stream(), dtype, p(dtok2), p(dV), None, p(h), N, T, d, vocab, 1.0, p(flag)))
+    torch.cuda.synchronize()
+    assert flag.item() == 1 and np.all(host(h)[2:4] == 0)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("N,vocab", [(12, 256), (7, 1000), (5, 50257)])
+def test_softmax_cross_entropy(dtype, N, vocab):
+    rng = np.random.default_rng(N + vocab)
+    logits = (rng.standard_normal((N, vocab)) * 3).astype(np.float32)
+    tgt = rng.integers(0, vocab, N).astype(np.int32)
+    dl = torch.from_numpy(logits).cuda()
+    dt = torch.from_numpy(tgt).cuda()
+    tdt = torch.bfloat16 if dtype else torch.float32
+    G = torch.zeros((N, vocab), dtype=tdt, device="cuda")
+    lse = torch.zeros(N, device="cuda"); rl = torch.zeros(N, device="cuda"); loss = torch.zeros(1, device="cuda")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ok(L().ouro_op_softmax_ce(stream(), dtype, p(dl), vocab, p(dt), p(G), vocab, p(lse), p(rl), p(loss), N, vocab, p(flag)))
+    torch.cuda.synchronize()
+    rloss, rlse = O.cross_entropy_fwd(logits.astype(np.float64), tgt)
+    rG = O.cross_entropy_bwd(logits.astype(np.float64), rlse, tgt)
+    assert abs(loss.item() - rloss) / rloss < 1e-5
+    assert np.abs(host(lse) - rlse).max() < 1e-4
+    assert rel_err(host(G), rG) < (1e-5 if dtype == 0 else 5e-3)
+    assert flag.item() == 0
+    # zero logits: loss = ln(vocab) (uniform softmax)
+    dl.zero_()
+    ok(L().ouro_op_softmax_ce(stream(), dtype, p(dl), vocab, p(dt), p(G), vocab, p(lse), p(rl), p(loss), N, vocab, p(flag)))
+    torch.cuda.synchronize()
+    assert abs(loss.item() - math.log(vocab)) < 1e-5
+
+
+@pytest.mark.parametrize("adam", [0, 1])
+@pytest.mark.parametrize("n", [1, 7, 4096, 100003])
+def test_update_kernel(adam, n):
+    rng = np.random.default_rng(n + adam)
+    w = rng.standard_normal(n).astype(np.float32)
+    g0 = rng.standard_normal(n).astype(np.float32); g1 = rng.standard_normal(n).astype(np.float32)
+    m = (rng.standard_normal(n) * 0.1).astype(np.float32); v = (rng.random(n) * 0.1).astype(np.float32)
+    dw, dg0, dg1, dm, dv = (torch.from_numpy(x.copy()).cuda() for x in (w, g0, g1, m, v))
+    sh = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    t = 5
+    ok(L().ouro_op_update(stream(), p(dw), p(dm), p(dv), p(sh), p(dg0), 0.5, p(dg1), 0.5, n, adam, 0.01, 0.9, 0.999, 1e-8, t))
+    torch.cuda.synchronize()
+    cfg = O.Config(n_layer=1, d_model=8, n_head=2, d_head=4, d_ff=8, vocab=8, seq_len=2, batch=1, optimizer=adam)
+    orc = O.Oracle.__new__(O.Oracle); orc.cfg = cfg; orc.t = t
+    w64, m64, v64 = w.astype(np.float64), m.astype(np.float64), v.astype(np.float64)
+    orc._apply(w64, 0.5 * g0.astype(np.float64) + 0.5 * g1.astype(np.float64), m64, v64, 0.01)
+    assert rel_err(host(dw), w64) < 1e-6
+    if adam:
+        assert rel_err(host(dm), m64) < 1e-6 and rel_err(host(dv), v64) < 1e-6
+    assert torch.equal(sh, dw.to(torch.bfloat16))            # bf16 copy = round-to-nearest-even of the master
+    # zero gradient (null pointers) with zero moments leaves the weights bit-identical
+    dw2 = torch.from_numpy(w.copy()).cuda(); z1 = torch.zeros(n, device="cuda"); z2 = torch.zeros(n, device="cuda")
+    ok(L().ouro_op_update(stream(), p(dw2), p(z1), p(z2), None, None, 1.0, None, 0.0, n, adam, 0.01, 0.9, 0.999, 1e-8, 0))
+    torch.cuda.synchronize()
+    assert np.array_equal(dw2.cpu().numpy(), w) and not z1.any() and not z2.any()

@@ -1,0 +1,225 @@
+"""End-to-end parity of the HIP training iteration against the CPU oracle, through the
+C boundary: losses, every gradient store, updated weights, segment memories, and the
+bit-exact staleness bookkeeping (Eq. 8-9)."""
+import numpy as np
+import pytest
+
+from oracle import ouro_oracle as O
+import synth_inputs as S
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def P():
+    import paper_1909_06695_amd as pkg
+    return pkg
+
+
+def rel_err(a, b):
+    a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=1e-4, module_api=False):
+    """Runs `steps` iterations on both sides; returns nothing, asserts parity."""
+    pkg = P()
+    blobs = S.init_params(c, seed=seed, std=std, perturb=perturb)
+    tok, tgt = S.token_batches(c["vocab"], c["batch"], c["seq_len"], steps, c.get("zipf_s", 1.1), seed + 1,
+                               contiguous=bool(c.get("mem_len", 0)))
+    cfg = O.Config(**c)
+    orc = O.Oracle(cfg, blobs)
+    m = pkg.create_model(**c)
+    K = c["n_module"]
+    for g in range(K + 1):
+        assert m.param_count(g) == blobs[g].size
+        m.set_params(g, blobs[g])
+    dtok = torch.from_numpy(tok).cuda(); dtgt = torch.from_numpy(tgt).cuda()
+    for t in range(steps):
+        lo = orc.step(tok[t], tgt[t], lr)
+        if module_api:
+            for k in range(1, K + 1):
+                m.module_forward(k, dtok[t], dtgt[t])
+            lg = m.get_loss()
+            for k in range(K, 0, -1):
+                m.module_backward(k)
+            order = list(range(K + 1))
+            np.random.default_rng(t).shuffle(order)          # updates commute within an iteration
+            for g in order:
+                m.delayed_update(g, lr)
+        else:
+            lg = m.step(dtok[t], dtgt[t], lr)
+        assert abs(lg - lo) / abs(lo) < tol, (t, lg, lo)
+        assert m.current_step() == t + 1
+        if check_grads:
+            grads, dVi, dVo = orc.grad_hist[t]
+            assert rel_err(m.get_grad_slot(K + 1, t), dVo.ravel()) < tol, ("dVo", t)
+            assert rel_err(m.get_grad_slot(0, t), dVi.ravel()) < tol, ("dVi", t)
+            for k in range(1, K + 1):
+                assert rel_err(m.get_grad_slot(k, t), orc.grad_blob(k, t)) < tol, ("module grad", k, t)
+                # per-parameter check so that small tensors (biases, u, v) are not drowned
+                off = 0
+                got = m.get_grad_slot(k, t)
+                for l in orc.module_layers(k):
+                    for name, shape in O.param_shapes(cfg):
+                        n = int(np.prod(shape))
+                        ref = grads[l][name].ravel()
+                        assert rel_err(got[off:off + n], ref) < 5 * tol, (name, l, t)
+                        off += n
+        for g in range(K + 1):
+            assert rel_err(m.get_params(g), orc.module_blob(g)) < tol, ("weights", g, t)
+        if c.get("mem_len", 0):
+            for l in range(c["n_layer"]):
+                mem = m.get_mems(l)
+                assert mem.shape == orc.mems[l].shape
+                assert rel_err(mem, orc.mems[l]) < tol
+    m.close()
+
+
+def test_config1_fp32_sgd_three_steps():
+    c = dict(S.CONFIGS["cfg1"])
+    run_both(c, steps=3, lr=c["lr"], seed=c["seed"])
+
+
+def test_config1_perturbed_params_module_api():
+    """Same shape with non-trivial biases / gains, Adam, more steps than K, driven through
+    module_forward / module_backward / delayed_update with shuffled update order."""
+    c = dict(S.CONFIGS["cfg1"], optimizer=1)
+    run_both(c, steps=5, lr=1e-3, seed=3, std=0.08, perturb=0.1, module_api=True)
+
+
+def test_ragged_shapes_K3_fp32():
+    c = dict(n_layer=4, d_model=40, n_head=5, d_head=8, d_ff=72, vocab=131, seq_len=19, mem_len=0, batch=3,
+             n_module=3, rel_pos=0, dtype=0, optimizer=0)
+    run_both(c, steps=5, lr=0.05, seed=5, std=0.1, perturb=0.1)
+
+
+def test_K1_fp32_adam():
+    c = dict(n_layer=2, d_model=32, n_head=2, d_head=16, d_ff=64, vocab=97, seq_len=16, mem_len=0, batch=2,
+             n_module=1, rel_pos=0, dtype=0, optimizer=1)
+    run_both(c, steps=3, lr=1e-3, seed=6, std=0.1, perturb=0.1)
+
+
+def test_xl_fp32_memory_carry():
+    """Relative attention with a segment memory that is empty, then partial, then rolling."""
+    c = dict(n_layer=3, d_model=32, n_head=2, d_head=16, d_ff=48, vocab=61, seq_len=6, mem_len=10, batch=2,
+             n_module=3, rel_pos=1, dtype=0, optimizer=0)
+    run_both(c, steps=5, lr=0.05, seed=7, std=0.15, perturb=0.1)
+
+
+def test_xl_fp32_odd_dims_adam():
+    c = dict(n_layer=2, d_model=82, n_head=2, d_head=41, d_ff=100, vocab=73, seq_len=9, mem_len=9, batch=2,
+             n_module=2, rel_pos=1, dtype=0, optimizer=1, embed_warm_mode=1)
+    run_both(c, steps=4, lr=1e-3, seed=8, std=0.1, perturb=0.1)
+
+
+def test_bf16_small_sgd():
+    """bf16 mode against the fp64 oracle within 2e-2 (several tiles of the MFMA kernels)."""
+    c = dict(n_layer=2, d_model=128, n_head=2, d_head=64, d_ff=512, vocab=512, seq_len=128, mem_len=0, batch=2,
+             n_module=2, rel_pos=0, dtype=1, optimizer=0)
+    run_both(c, steps=3, lr=0.05, seed=9, std=0.05, perturb=0.05, tol=2e-2)
+
+
+def test_staleness_plumbing_bit_exact():
+    """Integer-tagged gradients through inject_grad: final weights have a closed form that
+    fp32 represents exactly; slot tags and reads follow Eq. 8-9 at every iteration."""
+    pkg = P()
+    K, T = 4, 11
+    c = dict(n_layer=4, d_model=16, n_head=2, d_head=8, d_ff=16, vocab=32, seq_len=4, mem_len=0, batch=1,
+             n_module=K, rel_pos=0, dtype=0, optimizer=0)
+    m = pkg.create_model(**c)
+    for g in range(K + 1):
+        m.set_params(g, np.zeros(m.param_count(g), np.float32))
+    lr = 2.0 ** -10
+    val = lambda t, store: 1000.0 * t + (0.25 if store == 0 else 0.75 if store == K + 1 else store)
+    for t in range(T):
+        for store in range(K + 2):
+            m.inject_grad(store, np.full(m.grad_count(store), val(t, store), np.float32))
+            slot, tau = pkg.slot_index(K, store, t, True)
+            assert m.slot_tag(store, slot) == t
+        for g in range(K, -1, -1):
+            m.delayed_update(g, lr)
+        for k in range(1, K + 1):
+            tau = t - K + k
+            assert m.last_read(k) == ((tau % (K - k + 1), tau) if tau >= 0 else (-1, -1))
+        ti = t - K + 1
+        assert m.last_read(0) == ((ti % K, ti) if ti >= 0 else (-1, -1))
+        assert m.last_read(K + 1) == ((0, t) if ti >= 0 else (-1, -1))
+        assert m.current_step() == t + 1
+    for k in range(1, K + 1):
+        expect = np.float32(-lr * sum(val(t - K + k, k) for t in range(T) if t - K + k >= 0))
+        assert np.all(m.get_params(k) == expect)
+    expect = np.float32(-lr * sum(0.5 * val(t, K + 1) + 0.5 * val(t - K + 1, 0) for t in range(T) if t - K + 1 >= 0))
+    assert np.all(m.get_params(0) == expect)
+    m.close()
+
+
+def test_frozen_until_first_gradient_and_adam_zero_step():
+    pkg = P()
+    K = 3
+    c = dict(n_layer=3, d_model=16, n_head=2, d_head=8, d_ff=16, vocab=32, seq_len=8, mem_len=0, batch=2,
+             n_module=K, rel_pos=0, dtype=0, optimizer=1)
+    blobs = S.init_params(c, seed=1, std=0.1)
+    tok, tgt = S.token_batches(32, 2, 8, 4, 1.1, 2, False)
+    m = pkg.create_model(**c)
+    for g in range(K + 1):
+        m.set_params(g, blobs[g])
+    dtok = torch.from_numpy(tok).cuda(); dtgt = torch.from_numpy(tgt).cuda()
+    for t in range(4):
+        m.step(dtok[t], dtgt[t], 1e-2)
+        for k in range(1, K + 1):
+            same = np.array_equal(m.get_params(k), blobs[k])
+            assert same == (t < K - k), (t, k)
+        assert np.array_equal(m.get_params(0), blobs[0]) == (t < K - 1)
+    m.close()
+
+
+def test_call_order_and_error_codes():
+    pkg = P()
+    from paper_1909_06695_amd import binding as Bn
+    c = dict(n_layer=2, d_model=16, n_head=2, d_head=8, d_ff=16, vocab=32, seq_len=8, mem_len=0, batch=2,
+             n_module=2, rel_pos=0, dtype=0, optimizer=0)
+    m = pkg.create_model(**c)
+    blobs = S.init_params(c, seed=1)
+    for g in range(3):
+        m.set_params(g, blobs[g])
+    tok = torch.zeros((2, 8), dtype=torch.int32, device="cuda")
+    tgt = torch.ones((2, 8), dtype=torch.int32, device="cuda")
+
+    def code(fn, *a):
+        with pytest.raises(pkg.OuroError) as e:
+            fn(*a)
+        return e.value.code
+
+    assert code(m.module_forward, 2, tok, tgt) == Bn.E_SEQUENCE
+    assert code(m.module_backward, 2) == Bn.E_SEQUENCE
+    assert code(m.delayed_update, 1, 0.1) == Bn.E_SEQUENCE
+    assert code(m.module_forward, 3, tok, tgt) == Bn.E_ARG
+    assert code(m.module_forward, 1, None, None) == Bn.E_ARG
+    m.module_forward(1, tok, tgt)
+    assert code(m.module_forward, 1, tok, tgt) == Bn.E_SEQUENCE
+    assert code(m.module_backward, 2) == Bn.E_SEQUENCE
+    m.module_forward(2, tok, tgt)
+    assert code(m.module_backward, 1) == Bn.E_SEQUENCE
+    m.module_backward(2)
+    assert code(m.delayed_update, 2, 0.1) == Bn.E_SEQUENCE
+    m.module_backward(1)
+    m.delayed_update(2, 0.1)
+    assert code(m.delayed_update, 2, 0.1) == Bn.E_SEQUENCE
+    assert m.current_step() == 0
+    m.delayed_update(0, 0.1); m.delayed_update(1, 0.1)
+    assert m.current_step() == 1
+    assert code(m.set_params, 1, np.zeros(3, np.float32)) == Bn.E_ARG
+    assert code(m.get_grad_slot, 1, 5) == Bn.E_STALE
+    # out-of-range token and target ids are reported, never dereferenced
+    bad = tok.clone(); bad[0, 0] = 32
+    with pytest.raises(pkg.OuroError) as e:
+        m.step(bad, tgt, 0.1)
+    assert e.value.code == Bn.E_TOKEN
+    badt = tgt.clone(); badt[1, 3] = -7
+    with pytest.raises(pkg.OuroError) as e:
+        m.step(tok, badt, 0.1)
+    assert e.value.code == Bn.E_TOKEN
+    assert np.isfinite(m.step(tok, tgt, 0.1))
+    m.close()
