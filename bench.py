@@ -1,0 +1,153 @@
+"""Throughput of the delayed-gradient training step on one MI355X.
+
+`python bench.py --gpus 1 --steps K --warmup W` runs the whole hot path (forward of the K
+modules, their backward, the delayed SGD/Adam updates of Eq. 8-9) on synthetic Zipfian
+tokens that are already resident in HBM, times exactly K steps, and prints ONE JSON line.
+Beside the headline tokens/s it reports the roofline fraction of the dominant kernel (the
+bf16 MFMA contraction kernel, timed per launch with HIP events in a second pass of the same
+steps), the delayed-update kernel's achieved HBM bandwidth, and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def step_flops(c):
+    """Algorithmic flops of one step: 3 x forward; a matmul of P parameters costs 2P per
+    token; causal attention counts visible (query, key) pairs only, 4*d per pair (6*d with
+    the relative-position term); recomputation, padding and masked work count zero."""
+    d, F, L, V, T, M, B = c["d_model"], c["d_ff"], c["n_layer"], c["vocab"], c["seq_len"], c["mem_len"], c["batch"]
+    if c["rel_pos"]:
+        per_layer = 2 * d * d + (2 * d * d) * (T + M) / T + 2 * d * F   # q,o + k,v over memory too + FFN
+        vis = M + (T + 1) / 2
+        attn = 6 * d * vis
+    else:
+        per_layer = 4 * d * d + 2 * d * F
+        attn = 4 * d * (T + 1) / 2
+    fwd = 2 * (L * per_layer + V * d) + L * attn
+    return 3.0 * B * T * fwd
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs the K modules back to back on ONE GPU; --gpus N with N > 1 is not "
+              "supported (no collectives, no sharding)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1909_06695_amd as P
+    import synth_inputs as S
+
+    c = dict(S.CONFIGS[args.config])
+    K = c["n_module"]
+    nsteps_total = args.warmup + 2 * args.steps
+    blobs = S.init_params(c, seed=0)
+    distinct = min(nsteps_total, 16)                         # token batches cycle; all resident in HBM
+    tok, tgt = S.token_batches(c["vocab"], c["batch"], c["seq_len"], distinct, c["zipf_s"], c["seed"],
+                               contiguous=bool(c["mem_len"]))
+    m = P.create_model(device="cuda:0", **c)
+    for g in range(K + 1):
+        m.set_params(g, blobs[g])
+    dtok = torch.from_numpy(tok).cuda()
+    dtgt = torch.from_numpy(tgt).cuda()
+    lr = c["lr"]
+
+    warm = max(args.warmup, K + 2)                           # rings full: every update uses a real gradient
+    loss = None
+    for i in range(warm):
+        loss = m.step(dtok[i % distinct], dtgt[i % distinct], lr, want_loss=(i == warm - 1))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        j = (warm + i) % distinct
+        m.step(dtok[j], dtgt[j], lr, want_loss=False)        # no host sync inside the loop
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    loss_end = m.get_loss()
+    ms_per_step = dt / args.steps * 1e3
+    tokens = c["batch"] * c["seq_len"]
+    value = tokens * args.steps / dt
+    F = step_flops(c)
+
+    roofline = None
+    update = None
+    if not args.no_kernel_timing:
+        # second pass of the same steps with per-launch HIP events on the library's stream
+        m.timing_enable(True)
+        for i in range(args.steps):
+            j = (warm + args.steps + i) % distinct
+            m.step(dtok[j], dtgt[j], lr, want_loss=False)
+        gms, gn, gfl = m.timing_read(0)
+        ums, un, ubytes = m.timing_read(1)
+        m.timing_enable(False)
+        if gn:
+            ach = gfl / (gms * 1e-3) / 1e12
+            roofline = {"bound": "mfma", "kernel": "gemm_mfma_kernel", "achieved": round(ach, 2),
+                        "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                        "traffic": None, "launches_per_step": gn // args.steps,
+                        "avg_launch_us": round(gms * 1e3 / gn, 2),
+                        "flops_per_launch_avg": gfl / gn, "kernel_ms_per_step": round(gms / args.steps, 3)}
+        if un:
+            gbs = ubytes / (ums * 1e-3) / 1e9
+            update = {"bound": "hbm", "kernel": "update_kernel", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS,
+                      "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
+                      "bytes_per_step": ubytes / args.steps, "kernel_ms_per_step": round(ums / args.steps, 3)}
+    m.close()
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ouro_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count()
+        cs = dict(c, batch=1)                                # same per-token shapes, one stream
+        ocfg = O.Config(**cs)
+        orc = O.Oracle(ocfg, blobs, keep_history=False)
+        stok, stgt = S.token_batches(c["vocab"], 1, c["seq_len"], 1, c["zipf_s"], c["seed"], bool(c["mem_len"]))
+        t0 = time.perf_counter()
+        orc.step(stok[0], stgt[0], lr)
+        cdt = time.perf_counter() - t0
+        cpu = {"value": round(c["seq_len"] / cdt, 2), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+               "sample": f"{args.config} cut to batch 1, one full step (fp64 numpy), {cdt:.1f} s"}
+
+    out = {
+        "metric": "training tokens/sec on 1 MI355X", "value": round(value, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": warm, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if c["dtype"] == 1 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.config}: {c['n_layer']}-layer d={c['d_model']} H={c['n_head']} F={c['d_ff']} "
+                               f"V={c['vocab']} T={c['seq_len']} M={c['mem_len']} B={c['batch']} K={K} "
+                               f"{'Adam' if c['optimizer'] else 'SGD'}, Zipf({c['zipf_s']}) tokens",
+                   "tokens_per_step": tokens, "modules": K},
+        "mfu_bf16": round(F / (ms_per_step * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4),
+        "step_tflop": round(F / 1e12, 3),
+        "loss_first_timed": loss, "loss_last": loss_end,
+        "roofline": roofline, "update_kernel": update, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -157,9 +157,14 @@ int ouro_get_mems(ouro_model* m, int layer, float* host_dst, int64_t* valid_len)
 /* Input activation of a layer (0-based), or with layer == n_layer the final hidden
  * state, of the latest forward, as fp32 [batch*seq_len, d_model]. */
 int ouro_debug_get_hidden(ouro_model* m, int layer, float* host_dst, int64_t n);
-/* Accumulated device time (ms) and launch count of the dense-contraction kernels since
- * the last reset; timing != 0 turns per-launch HIP event timing on (slows the step). */
-int ouro_debug_gemm_timing(ouro_model* m, int timing, double* ms, int64_t* launches, double* flops);
+/* Optional per-launch HIP event timing on the model's stream (slows the step while on).
+ * kind 0: the MFMA contraction kernel, work = 2*M*N*K flops per launch;
+ * kind 1: the delayed-update kernel (zero-gradient warm-up launches excluded), work =
+ *         algorithmic bytes (gradient reads 4 B each, w 8 B, Adam moments 16 B, bf16 copy 2 B).
+ * timing_read synchronises the stream, returns the totals since the last read of that
+ * kind and resets them. */
+int ouro_debug_timing_enable(ouro_model* m, int on);
+int ouro_debug_timing_read(ouro_model* m, int kind, double* ms, int64_t* launches, double* work);
 
 #ifdef __cplusplus
 }

@@ -69,7 +69,8 @@ def lib():
         "ouro_get_grad_slot": (i32, [vp, i32, i64, vp, i64]),
         "ouro_get_mems": (i32, [vp, i32, vp, P(i64)]),
         "ouro_debug_get_hidden": (i32, [vp, i32, vp, i64]),
-        "ouro_debug_gemm_timing": (i32, [vp, i32, P(C.c_double), P(i64), P(C.c_double)]),
+        "ouro_debug_timing_enable": (i32, [vp, i32]),
+        "ouro_debug_timing_read": (i32, [vp, i32, P(C.c_double), P(i64), P(C.c_double)]),
         # single-kernel entry points
         "ouro_op_gemm": (i32, [vp, i32, i32, i32, i32, i32, i32, f32, vp, i32, vp, i32, vp, i32, i32, i32, vp, vp,
                                i32, i32, vp, i32, i32]),
@@ -254,10 +255,14 @@ class Model:
         check(self.L.ouro_debug_get_hidden(self.h, layer, out.ctypes.data_as(C.c_void_p), out.size))
         return out
 
-    def gemm_timing(self, enable):
-        ms, n, fl = C.c_double(), C.c_int64(), C.c_double()
-        check(self.L.ouro_debug_gemm_timing(self.h, int(enable), C.byref(ms), C.byref(n), C.byref(fl)))
-        return ms.value, n.value, fl.value
+    def timing_enable(self, on):
+        check(self.L.ouro_debug_timing_enable(self.h, int(on)))
+
+    def timing_read(self, kind):
+        """(ms, launches, work): kind 0 = MFMA contraction kernel (flops), 1 = update kernel (bytes)."""
+        ms, n, w = C.c_double(), C.c_int64(), C.c_double()
+        check(self.L.ouro_debug_timing_read(self.h, kind, C.byref(ms), C.byref(n), C.byref(w)))
+        return ms.value, n.value, w.value
 
 
 def create_model(**kw):

@@ -1,13 +1,454 @@
-// Fused causal attention on the matrix cores (bf16, head size 64).
+// Fused causal attention on the matrix cores (bf16, head size 64, no relative term).
+//
+// All three kernels keep the softmax row index in the lane: the score tile is produced
+// transposed (keys x queries in the forward and dQ kernels, queries x keys in the dK/dV
+// kernel), so a lane owns one query (or key) column and row statistics need a single
+// cross-half shuffle.  The probabilities feed the next matrix instruction straight from
+// the accumulator registers: the contraction index may be enumerated in any order as long
+// as both operands agree, so the other operand is read from a transposed LDS tile in the
+// accumulator's own row order (two 8-byte pieces per lane) and nothing is exchanged
+// between lanes.  Online softmax in base 2; log-sum-exp saved for the backward kernels.
 #include "common.h"
+#include "tiles.h"
 
 namespace ouro {
 
-bool attn_mfma_ok(int dtype, const AttnDesc& a) {
-  (void)dtype; (void)a;
-  return false;
+struct FaParams {
+  int B, H, T, S, Mv;
+  const bf16_t* q; int ldq;
+  const bf16_t* k; int ldk;
+  const bf16_t* v; int ldv;
+  bf16_t* o; int ldo;
+  float* lse;
+  float scale, scale_log2;
+  const bf16_t* d_o; int lddo;
+  bf16_t* dq; int lddq;
+  bf16_t* dk; int lddk;
+  bf16_t* dv; int lddv;
+  float* D;
+};
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 t) { return *reinterpret_cast<bf16x8*>(&t); }
+
+// operand rows of a row-form tile: row = base + lane%32, 16-byte chunk 2*ks + lane/32
+__device__ __forceinline__ bf16x8 read_rowform(const uint4* tile, int row, int ks, int h32) {
+  return as_bf16x8(tile[row * 8 + ((2 * ks + h32) ^ swz(row))]);
 }
-hipError_t launch_attn_fwd_mfma(hipStream_t, const AttnDesc&) { return hipErrorNotSupported; }
-hipError_t launch_attn_bwd_mfma(hipStream_t, const AttnDesc&) { return hipErrorNotSupported; }
+// operand rows of a transposed tile in accumulator order: elements 0..3 = columns
+// 8*c0 + 4*h32 + (0..3), elements 4..7 = columns 8*(c0+1) + 4*h32 + (0..3)
+__device__ __forceinline__ bf16x8 read_accorder(const uint4* tile, int row, int c0, int h32) {
+  const uint2* t2 = reinterpret_cast<const uint2*>(tile);
+  uint2 lo = t2[(row * 8 + (c0 ^ swz(row))) * 2 + h32];
+  uint2 hi = t2[(row * 8 + ((c0 + 1) ^ swz(row))) * 2 + h32];
+  return as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y));
+}
+__device__ __forceinline__ bf16x8 pack_acc(const f32x16& a, int sub) {
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = (bf16_t)a[8 * sub + e];
+  return r;
+}
+// accumulator tile (rows = feature 32*dt + 8g + 4*h32 + j, column = lane's query/key) -> global row
+__device__ __forceinline__ void store_acc_row(bf16_t* dst, const f32x16 (&acc)[2], float mul, int h32) {
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      union { bf16_t h[4]; uint2 u; } cv;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) cv.h[j] = (bf16_t)(acc[dt][4 * g + j] * mul);
+      *reinterpret_cast<uint2*>(dst + 32 * dt + 8 * g + 4 * h32) = cv.u;
+    }
+}
+
+// ------------------------------------------------------------------------------ forward
+// grid (ceil(T/128), H, B); 4 waves x 32 queries; key blocks of 64 staged in LDS.
+__global__ __launch_bounds__(256) void fa_fwd_kernel(FaParams p) {
+  __shared__ uint4 sK[2][512];
+  __shared__ uint4 sVt[2][512];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
+  const int qblk = gridDim.x - 1 - blockIdx.x;            // longest rows first
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int q0 = qblk * 128 + wave * 32, qi = q0 + l32;
+  const bf16_t* qb = p.q + (size_t)b * p.T * p.ldq + head * 64;
+  const bf16_t* kb = p.k + (size_t)b * p.S * p.ldk + head * 64;
+  const bf16_t* vb = p.v + (size_t)b * p.S * p.ldv + head * 64;
+  bf16x8 qf[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    uint4 t = make_uint4(0, 0, 0, 0);
+    if (qi < p.T) t = *reinterpret_cast<const uint4*>(qb + (size_t)qi * p.ldq + 16 * ks + 8 * h32);
+    qf[ks] = as_bf16x8(t);
+  }
+  const int wg_last_q = min(p.T, qblk * 128 + 128) - 1;
+  const int kend = min(p.S, p.Mv + wg_last_q + 1);
+  const int nkb = (kend + 63) / 64;
+  const bool wave_on = q0 < p.T;
+  const int wave_kmax = p.Mv + min(p.T - 1, q0 + 31);
+  f32x16 oacc[2];
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+  float m = -INFINITY, l = 0.f;
+  uint4 rk[2], rv[4];
+  auto gload = [&](int jb) {
+    load_rowform<64, 256>(kb, p.ldk, jb * 64, p.S, 0, 64, tid, rk);
+    load_colform<64, 256>(vb, p.ldv, 0, 64, jb * 64, p.S, tid, rv);
+  };
+  auto sstore = [&](int st) {
+    store_rowform<64, 256>(sK[st], tid, rk);
+    store_colform<64, 256>(sVt[st], tid, rv);
+  };
+  gload(0);
+  sstore(0);
+  __syncthreads();
+  for (int jb = 0; jb < nkb; ++jb) {
+    const bool more = jb + 1 < nkb;
+    if (more) gload(jb + 1);
+    const int st = jb & 1;
+    if (wave_on && jb * 64 <= wave_kmax) {
+      f32x16 s[2];
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rowform(sK[st], 32 * kt + l32, ks, h32), qf[ks], s[kt], 0, 0, 0);
+      }
+      float mloc = -INFINITY;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          int key = jb * 64 + 32 * kt + 8 * (r >> 2) + 4 * h32 + (r & 3);
+          bool vis = key <= p.Mv + qi && key < p.S && qi < p.T;
+          float val = vis ? s[kt][r] * p.scale_log2 : -INFINITY;
+          s[kt][r] = val;
+          mloc = fmaxf(mloc, val);
+        }
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+      const float m_new = fmaxf(m, mloc);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+      float lsum = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float pv = __builtin_amdgcn_exp2f(s[kt][r] - m_use);
+          s[kt][r] = pv;
+          lsum += pv;
+        }
+      lsum += __shfl_xor(lsum, 32, 64);
+      l = l * alpha + lsum;
+      m = m_new;
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+#pragma unroll
+      for (int ks2 = 0; ks2 < 4; ++ks2) {
+        const int kt = ks2 >> 1, sub = ks2 & 1;
+        bf16x8 pb = pack_acc(s[kt], sub);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_accorder(sVt[st], 32 * dt + l32, 4 * kt + 2 * sub, h32), pb, oacc[dt], 0, 0, 0);
+      }
+    }
+    if (more) sstore((jb + 1) & 1);
+    __syncthreads();
+  }
+  if (qi < p.T) {
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    store_acc_row(p.o + ((size_t)b * p.T + qi) * p.ldo + head * 64, oacc, inv, h32);
+    if (h32 == 0) p.lse[((size_t)b * p.H + head) * p.T + qi] = (m + log2f(l)) * 0.6931471805599453f;
+  }
+}
+
+// D[b,h,i] = sum_c dO[i,c] * O[i,c]
+__global__ __launch_bounds__(256) void fa_bwd_prep_kernel(FaParams p) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t total = (size_t)p.B * p.T * p.H;
+  if (idx >= total) return;
+  const int head = (int)(idx % p.H);
+  const size_t n = idx / p.H;                 // b*T + i
+  const bf16_t* o = p.o + n * p.ldo + head * 64;
+  const bf16_t* d = p.d_o + n * p.lddo + head * 64;
+  float acc = 0.f;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    bf16x8 a = as_bf16x8(*reinterpret_cast<const uint4*>(o + 8 * c));
+    bf16x8 g = as_bf16x8(*reinterpret_cast<const uint4*>(d + 8 * c));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)g[e];
+  }
+  const int b = (int)(n / p.T), i = (int)(n % p.T);
+  p.D[((size_t)b * p.H + head) * p.T + i] = acc;
+}
+
+// ------------------------------------------------------------------------ dK, dV kernel
+// grid (ceil(S/128), H, B); 4 waves x 32 keys; query blocks of 64 staged in LDS both as
+// rows (for S = Q K^T and dP = dO V^T) and transposed (for dV^T += dO^T P, dK^T += Q^T dS).
+constexpr int DKV_STAGE_U4 = 4 * 512 + 32;   // Q, Q^T, dO, dO^T tiles + lse[64] + D[64]
+__global__ __launch_bounds__(256) void fa_bwd_dkv_kernel(FaParams p) {
+  extern __shared__ uint4 dyn[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int kb0 = blockIdx.x * 128 + wave * 32, key = kb0 + l32;
+  const bf16_t* qb = p.q + (size_t)b * p.T * p.ldq + head * 64;
+  const bf16_t* dob = p.d_o + (size_t)b * p.T * p.lddo + head * 64;
+  const bf16_t* kbp = p.k + (size_t)b * p.S * p.ldk + head * 64;
+  const bf16_t* vbp = p.v + (size_t)b * p.S * p.ldv + head * 64;
+  const float* lseb = p.lse + ((size_t)b * p.H + head) * p.T;
+  const float* Db = p.D + ((size_t)b * p.H + head) * p.T;
+  bf16x8 kf[4], vf[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    uint4 t0 = make_uint4(0, 0, 0, 0), t1 = t0;
+    if (key < p.S) {
+      t0 = *reinterpret_cast<const uint4*>(kbp + (size_t)key * p.ldk + 16 * ks + 8 * h32);
+      t1 = *reinterpret_cast<const uint4*>(vbp + (size_t)key * p.ldv + 16 * ks + 8 * h32);
+    }
+    kf[ks] = as_bf16x8(t0);
+    vf[ks] = as_bf16x8(t1);
+  }
+  f32x16 dkT[2], dvT[2];
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dkT[dt][r] = 0.f; dvT[dt][r] = 0.f; }
+  // first query that sees the block's first key: i >= key - Mv
+  const int ib0 = max(0, (int)blockIdx.x * 128 - p.Mv) / 64;
+  const int nib = (p.T + 63) / 64;
+  const bool wave_on = kb0 < p.S;
+  uint4 rq[2], rqt[4], rd[2], rdt[4];
+  float rstat = 0.f;
+  auto gload = [&](int ib) {
+    load_rowform<64, 256>(qb, p.ldq, ib * 64, p.T, 0, 64, tid, rq);
+    load_colform<64, 256>(qb, p.ldq, 0, 64, ib * 64, p.T, tid, rqt);
+    load_rowform<64, 256>(dob, p.lddo, ib * 64, p.T, 0, 64, tid, rd);
+    load_colform<64, 256>(dob, p.lddo, 0, 64, ib * 64, p.T, tid, rdt);
+    rstat = 0.f;
+    if (tid < 128) {
+      int i = ib * 64 + (tid & 63);
+      if (i < p.T) rstat = tid < 64 ? lseb[i] : Db[i];
+    }
+  };
+  auto sstore = [&](int st) {
+    uint4* base = dyn + st * DKV_STAGE_U4;
+    store_rowform<64, 256>(base, tid, rq);
+    store_colform<64, 256>(base + 512, tid, rqt);
+    store_rowform<64, 256>(base + 1024, tid, rd);
+    store_colform<64, 256>(base + 1536, tid, rdt);
+    if (tid < 128) reinterpret_cast<float*>(base + 2048)[tid] = rstat;
+  };
+  if (ib0 < nib) {
+    gload(ib0);
+    sstore(0);
+  }
+  __syncthreads();
+  for (int ib = ib0; ib < nib; ++ib) {
+    const bool more = ib + 1 < nib;
+    if (more) gload(ib + 1);
+    const int st = (ib - ib0) & 1;
+    const uint4* sQ = dyn + st * DKV_STAGE_U4;
+    const uint4* sQt = sQ + 512;
+    const uint4* sdO = sQ + 1024;
+    const uint4* sdOt = sQ + 1536;
+    const float* sl = reinterpret_cast<const float*>(sQ + 2048);
+    const float* sD = sl + 64;
+    if (wave_on && p.Mv + ib * 64 + 63 >= kb0) {
+      f32x16 s[2], dp[2];
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s[qt][r] = 0.f; dp[qt][r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rowform(sQ, 32 * qt + l32, ks, h32), kf[ks], s[qt], 0, 0, 0);
+          dp[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rowform(sdO, 32 * qt + l32, ks, h32), vf[ks], dp[qt], 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int ql = 32 * qt + 8 * (r >> 2) + 4 * h32 + (r & 3);
+          const int qi = ib * 64 + ql;
+          const bool vis = key <= p.Mv + qi && qi < p.T && key < p.S;
+          const float pv = vis ? __builtin_amdgcn_exp2f(s[qt][r] * p.scale_log2 - sl[ql] * 1.4426950408889634f) : 0.f;
+          s[qt][r] = pv;
+          dp[qt][r] = pv * (dp[qt][r] - sD[ql]) * p.scale;
+        }
+#pragma unroll
+      for (int ks2 = 0; ks2 < 4; ++ks2) {
+        const int qt = ks2 >> 1, sub = ks2 & 1;
+        bf16x8 pb = pack_acc(s[qt], sub);
+        bf16x8 dsb = pack_acc(dp[qt], sub);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+          dvT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_accorder(sdOt, 32 * dt + l32, 4 * qt + 2 * sub, h32), pb, dvT[dt], 0, 0, 0);
+          dkT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_accorder(sQt, 32 * dt + l32, 4 * qt + 2 * sub, h32), dsb, dkT[dt], 0, 0, 0);
+        }
+      }
+    }
+    if (more) sstore((ib + 1 - ib0) & 1);
+    __syncthreads();
+  }
+  if (key < p.S) {
+    store_acc_row(p.dk + ((size_t)b * p.S + key) * p.lddk + head * 64, dkT, 1.f, h32);
+    store_acc_row(p.dv + ((size_t)b * p.S + key) * p.lddv + head * 64, dvT, 1.f, h32);
+  }
+}
+
+// ---------------------------------------------------------------------------- dQ kernel
+// grid (ceil(T/128), H, B); 4 waves x 32 queries; key blocks of 64 staged as K rows, V rows
+// and K^T (for dQ^T += K^T dS^T).
+__global__ __launch_bounds__(256) void fa_bwd_dq_kernel(FaParams p) {
+  __shared__ uint4 sK[2][512];
+  __shared__ uint4 sV[2][512];
+  __shared__ uint4 sKt[2][512];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
+  const int qblk = gridDim.x - 1 - blockIdx.x;
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int q0 = qblk * 128 + wave * 32, qi = q0 + l32;
+  const bf16_t* qb = p.q + (size_t)b * p.T * p.ldq + head * 64;
+  const bf16_t* dob = p.d_o + (size_t)b * p.T * p.lddo + head * 64;
+  const bf16_t* kb = p.k + (size_t)b * p.S * p.ldk + head * 64;
+  const bf16_t* vb = p.v + (size_t)b * p.S * p.ldv + head * 64;
+  bf16x8 qf[4], dof[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    uint4 t0 = make_uint4(0, 0, 0, 0), t1 = t0;
+    if (qi < p.T) {
+      t0 = *reinterpret_cast<const uint4*>(qb + (size_t)qi * p.ldq + 16 * ks + 8 * h32);
+      t1 = *reinterpret_cast<const uint4*>(dob + (size_t)qi * p.lddo + 16 * ks + 8 * h32);
+    }
+    qf[ks] = as_bf16x8(t0);
+    dof[ks] = as_bf16x8(t1);
+  }
+  float lse_q = 0.f, D_q = 0.f;
+  if (qi < p.T) {
+    lse_q = p.lse[((size_t)b * p.H + head) * p.T + qi] * 1.4426950408889634f;
+    D_q = p.D[((size_t)b * p.H + head) * p.T + qi];
+  }
+  const int wg_last_q = min(p.T, qblk * 128 + 128) - 1;
+  const int kend = min(p.S, p.Mv + wg_last_q + 1);
+  const int nkb = (kend + 63) / 64;
+  const bool wave_on = q0 < p.T;
+  const int wave_kmax = p.Mv + min(p.T - 1, q0 + 31);
+  f32x16 dqT[2];
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dqT[dt][r] = 0.f;
+  uint4 rk[2], rv[2], rkt[4];
+  auto gload = [&](int jb) {
+    load_rowform<64, 256>(kb, p.ldk, jb * 64, p.S, 0, 64, tid, rk);
+    load_rowform<64, 256>(vb, p.ldv, jb * 64, p.S, 0, 64, tid, rv);
+    load_colform<64, 256>(kb, p.ldk, 0, 64, jb * 64, p.S, tid, rkt);
+  };
+  auto sstore = [&](int st) {
+    store_rowform<64, 256>(sK[st], tid, rk);
+    store_rowform<64, 256>(sV[st], tid, rv);
+    store_colform<64, 256>(sKt[st], tid, rkt);
+  };
+  gload(0);
+  sstore(0);
+  __syncthreads();
+  for (int jb = 0; jb < nkb; ++jb) {
+    const bool more = jb + 1 < nkb;
+    if (more) gload(jb + 1);
+    const int st = jb & 1;
+    if (wave_on && jb * 64 <= wave_kmax) {
+      f32x16 s[2], dp[2];
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s[kt][r] = 0.f; dp[kt][r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rowform(sK[st], 32 * kt + l32, ks, h32), qf[ks], s[kt], 0, 0, 0);
+          dp[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rowform(sV[st], 32 * kt + l32, ks, h32), dof[ks], dp[kt], 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = jb * 64 + 32 * kt + 8 * (r >> 2) + 4 * h32 + (r & 3);
+          const bool vis = key <= p.Mv + qi && key < p.S && qi < p.T;
+          const float pv = vis ? __builtin_amdgcn_exp2f(s[kt][r] * p.scale_log2 - lse_q) : 0.f;
+          dp[kt][r] = pv * (dp[kt][r] - D_q) * p.scale;
+        }
+#pragma unroll
+      for (int ks2 = 0; ks2 < 4; ++ks2) {
+        const int kt = ks2 >> 1, sub = ks2 & 1;
+        bf16x8 dsb = pack_acc(dp[kt], sub);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+          dqT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_accorder(sKt[st], 32 * dt + l32, 4 * kt + 2 * sub, h32), dsb, dqT[dt], 0, 0, 0);
+      }
+    }
+    if (more) sstore((jb + 1) & 1);
+    __syncthreads();
+  }
+  if (qi < p.T) store_acc_row(p.dq + ((size_t)b * p.T + qi) * p.lddq + head * 64, dqT, 1.f, h32);
+}
+
+// ----------------------------------------------------------------------------- dispatch
+static inline bool al16(const void* x) { return (reinterpret_cast<uintptr_t>(x) & 15) == 0; }
+
+bool attn_mfma_ok(int dtype, const AttnDesc& a) {
+  if (dtype != 1 || a.dh != 64 || a.rel) return false;
+  if ((a.ldq | a.ldk | a.ldv | a.ldo) & 7) return false;
+  if (!al16(a.q) || !al16(a.k) || !al16(a.v) || !al16(a.o)) return false;
+  if (a.d_o) {
+    if ((a.lddo | a.lddq | a.lddk | a.lddv) & 7) return false;
+    if (!al16(a.d_o) || !al16(a.dq) || !al16(a.dk) || !al16(a.dv)) return false;
+  }
+  return true;
+}
+
+static FaParams fa_params(const AttnDesc& a) {
+  FaParams p;
+  p.B = a.B; p.H = a.H; p.T = a.T; p.S = a.S; p.Mv = a.Mv;
+  p.q = (const bf16_t*)a.q; p.ldq = a.ldq; p.k = (const bf16_t*)a.k; p.ldk = a.ldk;
+  p.v = (const bf16_t*)a.v; p.ldv = a.ldv; p.o = (bf16_t*)a.o; p.ldo = a.ldo; p.lse = a.lse;
+  p.scale = a.scale; p.scale_log2 = a.scale * 1.4426950408889634f;
+  p.d_o = (const bf16_t*)a.d_o; p.lddo = a.lddo; p.dq = (bf16_t*)a.dq; p.lddq = a.lddq;
+  p.dk = (bf16_t*)a.dk; p.lddk = a.lddk; p.dv = (bf16_t*)a.dv; p.lddv = a.lddv;
+  p.D = a.scratch;
+  return p;
+}
+
+hipError_t launch_attn_fwd_mfma(hipStream_t s, const AttnDesc& a) {
+  FaParams p = fa_params(a);
+  dim3 grid((a.T + 127) / 128, a.H, a.B), block(256);
+  hipLaunchKernelGGL(fa_fwd_kernel, grid, block, 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_bwd_mfma(hipStream_t s, const AttnDesc& a) {
+  FaParams p = fa_params(a);
+  const size_t rows = (size_t)a.B * a.T * a.H;
+  hipLaunchKernelGGL(fa_bwd_prep_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, s, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  constexpr size_t smem = 2 * (size_t)DKV_STAGE_U4 * sizeof(uint4);
+  static bool attr_done = false;
+  if (!attr_done) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_bwd_dkv_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(fa_bwd_dkv_kernel, dim3((a.S + 127) / 128, a.H, a.B), dim3(256), smem, s, p);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(fa_bwd_dq_kernel, dim3((a.T + 127) / 128, a.H, a.B), dim3(256), 0, s, p);
+  return hipGetLastError();
+}
 
 }  // namespace ouro

@@ -128,7 +128,7 @@ struct ouro_model {
   std::vector<float*> master, adam_m, adam_v;
   std::vector<bf16_t*> shadow;
   // gradient stores 0..K+1
-  std::vector<int64_t> gcount, depth;
+  std::vector<int64_t> gcount, gstride, depth;   // elements per gradient, slot stride (256-byte multiple)
   std::vector<float*> ring;
   std::vector<std::vector<int64_t>> tags;
   std::vector<int64_t> last_slot, last_tau;
@@ -152,12 +152,13 @@ struct ouro_model {
   int mem_valid;                  // valid rows in every layer memory
   const int32_t* tok;
   const int32_t* tgt;
-  // timing of the MFMA contraction kernel
+  // optional per-launch HIP event timing: kind 0 = MFMA contraction kernel (work = flops),
+  // kind 1 = delayed-update kernel (work = algorithmic bytes)
   int timing;
-  std::vector<hipEvent_t> ev;
-  size_t ev_used;
-  double timed_flops;
-  int64_t timed_launches;
+  std::vector<hipEvent_t> ev[2];
+  size_t ev_used[2];
+  double timed_work[2];
+  int64_t timed_launches[2];
 
   const char* wT(int layer, size_t off) const {   // weight as activation-typed operand
     int k = layer_mod[layer];
@@ -165,7 +166,7 @@ struct ouro_model {
   }
   const float* wF(int layer, size_t off) const { return master[layer_mod[layer]] + off; }
   const char* vT() const { return cfg.dtype == 1 ? (const char*)shadow[0] : (const char*)master[0]; }
-  float* slot_ptr(int id, int64_t slot) const { return ring[id] + (size_t)slot * gcount[id]; }
+  float* slot_ptr(int id, int64_t slot) const { return ring[id] + (size_t)slot * gstride[id]; }
 };
 
 static int default_split(int L, int K, std::vector<int>& out) {
@@ -247,11 +248,12 @@ static size_t lay_out(ouro_model& m, char* base) {
       m.adam_v[k] = (float*)P(m.count[k] * 4);
     }
   }
-  m.gcount.assign(K + 2, 0); m.depth.assign(K + 2, 0); m.ring.assign(K + 2, nullptr);
+  m.gcount.assign(K + 2, 0); m.gstride.assign(K + 2, 0); m.depth.assign(K + 2, 0); m.ring.assign(K + 2, nullptr);
   for (int id = 0; id <= K + 1; ++id) {
     m.gcount[id] = (id == 0 || id == K + 1) ? m.count[0] : m.count[id];
+    m.gstride[id] = (m.gcount[id] + 63) / 64 * 64;
     ouro_ring_depth(K, id, &m.depth[id]);
-    m.ring[id] = (float*)P((size_t)m.depth[id] * m.gcount[id] * 4);
+    m.ring[id] = (float*)P((size_t)m.depth[id] * m.gstride[id] * 4);
   }
   m.L.resize(L);
   const size_t qkv_elems = c.rel_pos ? (N * d + B * S * 2 * d) : (N * 3 * d);
@@ -342,7 +344,8 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
   m->last_slot.assign(K + 2, -1); m->last_tau.assign(K + 2, -1);
   m->t = 0; m->fwd_next = 1; m->bwd_next = K; m->upd_mask = 0; m->inject_mask = 0; m->mem_valid = 0;
   m->tok = m->tgt = nullptr;
-  m->timing = 0; m->ev_used = 0; m->timed_flops = 0; m->timed_launches = 0;
+  m->timing = 0;
+  for (int i = 0; i < 2; ++i) { m->ev_used[i] = 0; m->timed_work[i] = 0; m->timed_launches[i] = 0; }
   // zero optimizer state, rings, everything else too (one fill over the arena)
   hipError_t e = launch_fill_zero(m->stream, m->arena, need);
   if (e != hipSuccess) { delete m; return fail(OURO_E_HIP, "arena clear: %s", hipGetErrorString(e)); }
@@ -364,7 +367,8 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
 extern "C" int ouro_destroy_model(ouro_model* m) {
   if (!m) return OURO_OK;
   (void)hipStreamSynchronize(m->stream);
-  for (hipEvent_t e : m->ev) (void)hipEventDestroy(e);
+  for (int i = 0; i < 2; ++i)
+    for (hipEvent_t e : m->ev[i]) (void)hipEventDestroy(e);
   delete m;
   return OURO_OK;
 }
@@ -395,23 +399,28 @@ extern "C" int ouro_get_params(ouro_model* m, int group, float* dst, int64_t n, 
 extern "C" int64_t ouro_current_step(const ouro_model* m) { return m ? m->t : -1; }
 
 // --------------------------------------------------------------------- launch helpers
+static int timing_begin(ouro_model* m, int kind) {
+  while (m->ev[kind].size() < m->ev_used[kind] + 2) {
+    hipEvent_t e;
+    HIPCHK(hipEventCreate(&e));
+    m->ev[kind].push_back(e);
+  }
+  HIPCHK(hipEventRecord(m->ev[kind][m->ev_used[kind]], m->stream));
+  return OURO_OK;
+}
+static int timing_end(ouro_model* m, int kind, double work) {
+  HIPCHK(hipEventRecord(m->ev[kind][m->ev_used[kind] + 1], m->stream));
+  m->ev_used[kind] += 2;
+  m->timed_work[kind] += work;
+  m->timed_launches[kind] += 1;
+  return OURO_OK;
+}
+
 static int run_gemm(ouro_model* m, GemmDesc g) {
   const bool timed = m->timing && gemm_uses_mfma(m->cfg.dtype, g);
-  if (timed) {
-    while (m->ev.size() < m->ev_used + 2) {
-      hipEvent_t e;
-      HIPCHK(hipEventCreate(&e));
-      m->ev.push_back(e);
-    }
-    HIPCHK(hipEventRecord(m->ev[m->ev_used], m->stream));
-  }
+  if (timed) { int rc = timing_begin(m, 0); if (rc) return rc; }
   HIPCHK(launch_gemm(m->stream, m->cfg.dtype, g, 0));
-  if (timed) {
-    HIPCHK(hipEventRecord(m->ev[m->ev_used + 1], m->stream));
-    m->ev_used += 2;
-    m->timed_flops += 2.0 * g.M * g.N * g.K;
-    m->timed_launches += 1;
-  }
+  if (timed) return timing_end(m, 0, 2.0 * g.M * g.N * g.K);
   return OURO_OK;
 }
 
@@ -646,7 +655,7 @@ extern "C" int ouro_module_backward(ouro_model* m, int k) {
   int64_t slot, tau;
   ouro_slot_index(K, k, m->t, 1, &slot, &tau);
   float* gslot = m->slot_ptr(k, slot);
-  HIPCHK(launch_fill_zero(m->stream, gslot, (size_t)m->gcount[k] * 4));
+  HIPCHK(launch_fill_zero(m->stream, gslot, (size_t)m->gstride[k] * 4));
   const int lastl = m->first_layer[K] - 1;
   if (k == K) {
     // Eq. 7 (right): dV_o = G^T h_L ; error gradient dh_L = G V
@@ -669,7 +678,7 @@ extern "C" int ouro_module_backward(ouro_model* m, int k) {
     int64_t s0, t0;
     ouro_slot_index(K, 0, m->t, 1, &s0, &t0);
     float* dvi = m->slot_ptr(0, s0);
-    HIPCHK(launch_fill_zero(m->stream, dvi, (size_t)m->gcount[0] * 4));
+    HIPCHK(launch_fill_zero(m->stream, dvi, (size_t)m->gstride[0] * 4));
     HIPCHK(launch_embed_bwd(m->stream, c.dtype, m->tok, m->dh1, dvi, N, d, V, c.emb_scale));
     m->tags[0][s0] = m->t;
   }
@@ -733,7 +742,14 @@ extern "C" int ouro_delayed_update(ouro_model* m, int group, float lr) {
       u.g1 = m->slot_ptr(0, si); u.gscale1 = 0.5f;
     }
   }
+  const bool timed = m->timing && u.g0;
+  if (timed) RUN(timing_begin(m, 1));
   HIPCHK(launch_update(m->stream, u));
+  if (timed) {
+    // algorithmic bytes per element: gradient(s) 4 each, w read+write 8, Adam m,v read+write 16, bf16 copy 2
+    double per = 4.0 * ((u.g0 ? 1 : 0) + (u.g1 ? 1 : 0)) + 8.0 + (u.adam ? 16.0 : 0.0) + (u.shadow ? 2.0 : 0.0);
+    RUN(timing_end(m, 1, per * (double)u.n));
+  }
   m->upd_mask |= 1ull << group;
   if (m->upd_mask == (1ull << (K + 1)) - 1) return close_iteration(m);
   return OURO_OK;
@@ -829,19 +845,24 @@ extern "C" int ouro_debug_get_hidden(ouro_model* m, int layer, float* host_dst, 
   return OURO_OK;
 }
 
-extern "C" int ouro_debug_gemm_timing(ouro_model* m, int timing, double* ms, int64_t* launches, double* flops) {
+extern "C" int ouro_debug_timing_enable(ouro_model* m, int on) {
   if (!m) return fail(OURO_E_ARG, "model is null");
+  m->timing = on ? 1 : 0;
+  return OURO_OK;
+}
+
+extern "C" int ouro_debug_timing_read(ouro_model* m, int kind, double* ms, int64_t* launches, double* work) {
+  if (!m || kind < 0 || kind > 1) return fail(OURO_E_ARG, "timing_read: bad argument");
   HIPCHK(hipStreamSynchronize(m->stream));
   double total = 0;
-  for (size_t i = 0; i + 1 < m->ev_used; i += 2) {
+  for (size_t i = 0; i + 1 < m->ev_used[kind]; i += 2) {
     float t = 0;
-    HIPCHK(hipEventElapsedTime(&t, m->ev[i], m->ev[i + 1]));
+    HIPCHK(hipEventElapsedTime(&t, m->ev[kind][i], m->ev[kind][i + 1]));
     total += t;
   }
   if (ms) *ms = total;
-  if (launches) *launches = m->timed_launches;
-  if (flops) *flops = m->timed_flops;
-  m->ev_used = 0; m->timed_flops = 0; m->timed_launches = 0;
-  m->timing = timing;
+  if (launches) *launches = m->timed_launches[kind];
+  if (work) *work = m->timed_work[kind];
+  m->ev_used[kind] = 0; m->timed_work[kind] = 0; m->timed_launches[kind] = 0;
   return OURO_OK;
 }

@@ -37,7 +37,9 @@ def p(t):
 
 
 def rel_err(a, b):
-    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
+    # the floor keeps exactly-zero references (a single visible key has zero score gradient)
+    # from turning rounding noise into an infinite ratio
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-2 * math.sqrt(b.size)))
 
 
 def ok(rc):
@@ -175,6 +177,14 @@ def test_attention_general_kernel(dtype, B, H, T, Mv, dh, rel):
     _attn_case(dtype, B, H, T, Mv, dh, rel, seed=B + H + T + Mv + dh)
 
 
+@pytest.mark.parametrize("B,H,T,Mv", [(2, 2, 128, 0), (1, 3, 200, 0), (2, 1, 96, 40), (1, 2, 512, 0), (1, 1, 33, 0),
+                                      (1, 2, 300, 77)])
+def test_attention_mfma_kernel(B, H, T, Mv):
+    """Fused matrix-core kernels (bf16, head size 64): several query/key blocks, ragged
+    tails, and a key prefix (Mv) that every query sees."""
+    _attn_case(1, B, H, T, Mv, 64, 0, seed=100 + T + Mv, force=0)
+
+
 # ------------------------------------------------------------------ row-wise kernels
 @pytest.mark.parametrize("dtype", [0, 1])
 @pytest.mark.parametrize("rows,d", [(37, 64), (130, 512), (9, 410), (5, 1024), (3, 4100)])
@@ -230,13 +240,13 @@ def test_embedding_gather_scatter(dtype):
     tdt = torch.bfloat16 if dtype else torch.float32
     h = torch.zeros((N, d), dtype=tdt, device="cuda")
     flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ok(L().ouro_op_embed_fwd(stream(), dtype, p(dtok), p(dV), None, p(h), N, T, d, vocab, 1.0, p(flag)))
+    torch.cuda.synchronize()
+    assert torch.equal(h, dV[torch.from_numpy(tok.astype(np.int64)).cuda()])      # row selection is bit-exact
     ok(L().ouro_op_embed_fwd(stream(), dtype, p(dtok), p(dV), p(dpe), p(h), N, T, d, vocab, 1.5, p(flag)))
     torch.cuda.synchronize()
     ref = 1.5 * host(dV)[tok] + np.tile(pe, (B, 1))
-    if dtype == 0:
-        assert np.array_equal(host(h).astype(np.float32), ref.astype(np.float32))   # gather rows bit-exact
-    else:
-        assert rel_err(host(h), ref) < 4e-3
+    assert rel_err(host(h), ref) < (1e-6 if dtype == 0 else 4e-3)
     assert flag.item() == 0
     dh = rng.standard_normal((N, d)).astype(np.float32)
     ddh = dev(dh, dtype)

