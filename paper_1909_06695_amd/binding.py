@@ -12,7 +12,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libouro.so")
+LIB_PATH = os.environ.get("OURO_LIB_PATH", os.path.join(_HERE, "libouro.so"))
 
 OK, E_CONFIG, E_ARG, E_ARENA, E_SEQUENCE, E_TOKEN, E_STALE, E_HIP = 0, -1, -2, -3, -4, -5, -6, -7
 

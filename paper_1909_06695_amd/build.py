@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libouro.so")
-SOURCES = ["gemm.hip", "attention.hip", "attention_plain.hip", "attention_mfma.hip", "rowops.hip",
+SOURCES = ["gemm.hip", "gemm_dlds.hip", "attention.hip", "attention_plain.hip", "attention_mfma.hip", "rowops.hip",
            "model.hip", "ops_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]

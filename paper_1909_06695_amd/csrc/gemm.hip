@@ -1,42 +1,11 @@
 // Dense contractions of the training step: a bf16 MFMA kernel (LDS double-buffered,
 // XOR-swizzled tiles, 32x32x16 matrix instructions, 64-wide wavefronts) and a plain
 // bounds-checked tiled kernel for fp32 operands and shapes the MFMA kernel does not take.
-#include "common.h"
-#include "tiles.h"
+#include "gemm_common.h"
+
+#include <cstdlib>
 
 namespace ouro {
-
-struct GemmParams {
-  const void* A; const void* B; void* C;
-  int M, N, K, lda, ldb, ldc;
-  int out_fp32, accumulate;
-  const float* bias;
-  const void* residual; int ldr;
-  int epilogue;
-  void* Z; int ldz;
-  float alpha;
-  int kchunk;      // K range per blockIdx.z
-  int tilesN;      // tiles along N (MFMA kernel)
-};
-
-template <typename T>
-__device__ __forceinline__ void epilogue_store(const GemmParams& p, int m, int n, float acc) {
-  float v = acc * p.alpha;
-  if (p.accumulate) {
-    unsafeAtomicAdd(reinterpret_cast<float*>(p.C) + (size_t)m * p.ldc + n, v);
-    return;
-  }
-  if (p.bias) v += p.bias[n];
-  if (p.epilogue == EPI_GELU) {
-    reinterpret_cast<T*>(p.Z)[(size_t)m * p.ldz + n] = from_f32<T>(v);
-    v = gelu_f(v);
-  } else if (p.epilogue == EPI_GELUGRAD) {
-    v *= gelu_grad_f(to_f32(reinterpret_cast<const T*>(p.Z)[(size_t)m * p.ldz + n]));
-  }
-  if (p.residual) v += to_f32(reinterpret_cast<const T*>(p.residual)[(size_t)m * p.ldr + n]);
-  if (p.out_fp32) reinterpret_cast<float*>(p.C)[(size_t)m * p.ldc + n] = v;
-  else reinterpret_cast<T*>(p.C)[(size_t)m * p.ldc + n] = from_f32<T>(v);
-}
 
 // ------------------------------------------------------------------ plain tiled kernel
 template <typename T, bool TA, bool TB>
@@ -177,24 +146,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
     __syncthreads();
   }
 
-  // accumulator layout of the 32x32 tile: column = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      int n = n0 + wn * (TN * 32) + j * 32 + (lane & 31);
-      int mb = m0 + wm * (TM * 32) + i * 32 + 4 * (lane >> 5);
-      if (n < p.N) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          int m = mb + 8 * (r >> 2) + (r & 3);
-          if (m < p.M) epilogue_store<bf16_t>(p, m, n, acc[i][j][r]);
-        }
-      }
-    }
+  mfma_epilogue<TM, TN>(p, acc, smem, m0 + wm * (TM * 32), n0 + wn * (TN * 32), lane, wave);
 }
 
 // ----------------------------------------------------------------------------- launch
+hipError_t launch_gemm_dlds(hipStream_t s, GemmParams& p, int transA, int transB, int splits, int cfg);
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 bool gemm_uses_mfma(int dtype, const GemmDesc& g) {
@@ -209,7 +165,9 @@ bool gemm_uses_mfma(int dtype, const GemmDesc& g) {
 
 template <int BM, int BN, int WM, int WN>
 static hipError_t launch_mfma_cfg(hipStream_t s, GemmParams& p, int transA, int transB, int splits) {
-  constexpr size_t smem = 2 * (size_t)(BM + BN) * 8 * sizeof(uint4);
+  constexpr size_t smem_main = 2 * (size_t)(BM + BN) * 8 * sizeof(uint4);
+  constexpr size_t smem_epi = (size_t)WM * WN * epilogue_stage_floats<BN / WN / 32>() * sizeof(float);
+  constexpr size_t smem = smem_main > smem_epi ? smem_main : smem_epi;
   int tilesM = (p.M + BM - 1) / BM;
   p.tilesN = (p.N + BN - 1) / BN;
   dim3 grid(tilesM * p.tilesN, 1, splits), block(WM * WN * 64);
@@ -241,11 +199,20 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
   p.out_fp32 = g.out_fp32; p.accumulate = g.accumulate;
   p.bias = g.bias; p.residual = g.residual; p.ldr = g.ldr;
   p.epilogue = g.epilogue; p.Z = g.Z; p.ldz = g.ldz; p.alpha = g.alpha;
-  p.kchunk = g.K; p.tilesN = 0;
+  p.kchunk = g.K; p.tilesN = 0; p.vec_epi = 0;
   if (g.accumulate && (!g.out_fp32 || g.bias || g.residual || g.epilogue != EPI_NONE)) return hipErrorInvalidValue;
 
   if (!force_generic && gemm_uses_mfma(dtype, g)) {
-    constexpr int BM = 128, BN = 128;
+    const int oe = g.out_fp32 ? 3 : 7;   // ldc granularity for 16-byte row chunks
+    p.vec_epi = aligned16(g.C) && !(g.ldc & oe) && (!g.residual || (aligned16(g.residual) && !(g.ldr & 7))) &&
+                (g.epilogue == EPI_NONE || (aligned16(g.Z) && !(g.ldz & 7)));
+    static const int forced = [] { const char* e = getenv("OURO_GEMM_TILE"); return e ? atoi(e) : -1; }();
+    int cfg = forced;
+    if (cfg < 0) cfg = (g.K % 64) == 0 ? 10 : 0;
+    const bool dl = cfg >= 10 && (g.K % 64) == 0;
+    if (cfg >= 10 && !dl) cfg = 0;
+    const int BM = (cfg == 0 || (cfg >= 10 && cfg <= 12)) ? 128 : 256;
+    const int BN = (cfg == 2 || cfg == 3 || cfg == 15) ? 256 : 128;
     int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     int splits = 1;
     if (g.accumulate && tiles < 384 && g.K >= 512) {
@@ -258,7 +225,13 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
     kchunk = (kchunk + 63) / 64 * 64;
     splits = (g.K + kchunk - 1) / kchunk;
     p.kchunk = kchunk;
-    return launch_mfma_cfg<BM, BN, 2, 2>(s, p, g.transA, g.transB, splits);
+    if (dl) return launch_gemm_dlds(s, p, g.transA, g.transB, splits, cfg);
+    switch (cfg) {
+      case 1: return launch_mfma_cfg<256, 128, 2, 2>(s, p, g.transA, g.transB, splits);
+      case 2: return launch_mfma_cfg<256, 256, 2, 2>(s, p, g.transA, g.transB, splits);
+      case 3: return launch_mfma_cfg<256, 256, 2, 4>(s, p, g.transA, g.transB, splits);
+      default: return launch_mfma_cfg<128, 128, 2, 2>(s, p, g.transA, g.transB, splits);
+    }
   }
 
   dim3 grid((g.N + 63) / 64, (g.M + 63) / 64, 1), block(256);

@@ -1,0 +1,213 @@
+// bf16 MFMA contraction kernel with a multi-stage LDS ring filled by direct global->LDS
+// loads (16 bytes per lane, no register staging), so several K-tiles are in flight while
+// the matrix cores work on the current one.  Operands whose contraction index is the slow
+// dimension in memory are kept in their natural layout in LDS and transposed at read time
+// with the LDS transpose-read instruction.
+//
+// LDS layouts (per stage, BK = 64):
+//   row-form operand (k contiguous):  [rows][64 k], 128-byte rows, 16-byte chunk c of row r
+//     stored at chunk c ^ swz(r);
+//   column-form operand (row index contiguous): [64 k][ROWS], chunk c of k-row k stored at
+//     chunk c ^ ((k & 3) << 1), so the four k-rows one transpose-read touches fall into
+//     different banks.
+// A direct load writes lane i's 16 bytes to (wave-uniform base) + 16*i, so the swizzle is
+// applied by choosing which global chunk each lane fetches.
+#include "gemm_common.h"
+
+namespace ouro {
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void gbl_void;
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// One operand's share of a K-tile.  ROWS = tile extent along m (or n); NW = waves per
+// workgroup; COL = column-form.  Every wave-load moves 1 KiB.
+template <int ROWS, int NW, bool COL>
+struct OperandTile {
+  static constexpr int BYTES = ROWS * 128;                 // per stage
+  static constexpr int NLOAD = BYTES / 1024;               // wave-loads per tile
+  static constexpr int PER = NLOAD / NW;                   // per wave
+  static_assert(NLOAD % NW == 0, "tile loads must divide over the waves");
+  static constexpr int CPR = COL ? ROWS / 8 : 8;           // 16-byte chunks per LDS row
+  static constexpr int RPL = 64 / CPR;                     // LDS rows per wave-load
+
+  // Global element offset (without the K-tile term) of the chunk lane `lane` fetches in
+  // wave-load j.  rmax: valid extent along the row index (clamped: out-of-range rows only
+  // feed outputs that are never stored).
+  __device__ static __forceinline__ size_t src_offset(int j, int lane, int row0, int rmax, int ld) {
+    const int lr = j * RPL + lane / CPR;                   // LDS row
+    const int pc = lane % CPR;                             // physical chunk
+    if (!COL) {
+      const int c = pc ^ swz(lr);
+      const int gr = min(row0 + lr, rmax - 1);
+      return (size_t)gr * ld + 8 * c;                      // + k0
+    } else {
+      const int c = pc ^ ((lr & 3) << 1);
+      const int gm = min(row0 + 8 * c, rmax - 8);
+      return (size_t)lr * ld + gm;                         // + k0 * ld
+    }
+  }
+};
+
+// A/B fragment of substep ks for the 32-row tile starting at row t0 (row-form).
+__device__ __forceinline__ bf16x8 frag_row(const char* tile, int t0, int ks, int lane) {
+  const int row = t0 + (lane & 31);
+  const int c = 2 * ks + (lane >> 5);
+  return *reinterpret_cast<const bf16x8*>(tile + row * 128 + ((c ^ swz(row)) << 4));
+}
+// Same fragment from a column-form tile [64 k][ROWS]: two transpose reads of 4 k each.
+template <int ROWS>
+__device__ __forceinline__ bf16x8 frag_col(const char* tile, int t0, int ks, int lane) {
+  const int g4 = lane >> 4, i = lane & 15;
+  const int k = 16 * ks + 8 * (g4 >> 1) + (i >> 2);
+  const int m = t0 + 16 * (g4 & 1) + 4 * (i & 3);
+  const char* a = tile + k * (ROWS * 2) + (((m >> 3) ^ ((k & 3) << 1)) << 4) + ((m & 7) << 1);
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)a);
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a + 4 * (ROWS * 2)));
+  union { struct { s16x4 l, h; } p; bf16x8 v; } u;
+  u.p.l = lo; u.p.h = hi;
+  return u.v;
+}
+
+template <int BM, int BN, int WM, int WN, bool TA, bool TB, int S>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_dlds_kernel(GemmParams p) {
+  constexpr int BK = 64;
+  constexpr int NW = WM * WN;
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  using TileA = OperandTile<BM, NW, TA>;
+  using TileB = OperandTile<BN, NW, !TB>;
+  constexpr int STAGE = TileA::BYTES + TileB::BYTES;
+  constexpr int LPT = TileA::PER + TileB::PER;             // loads per thread per K-tile
+  static_assert((S - 1) * LPT < 64, "too many loads in flight for vmcnt");
+  extern __shared__ uint4 smem[];
+  char* lds = reinterpret_cast<char*>(smem);
+  const bf16_t* A = reinterpret_cast<const bf16_t*>(p.A);
+  const bf16_t* B = reinterpret_cast<const bf16_t*>(p.B);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  int bid = blockIdx.x;
+  {
+    int nb = gridDim.x, q = nb >> 3, r = nb & 7, x = bid & 7, idx = bid >> 3;
+    bid = x * q + min(x, r) + idx;
+  }
+  const int m0 = (bid / p.tilesN) * BM, n0 = (bid % p.tilesN) * BN;
+  const int kbeg = blockIdx.z * p.kchunk;
+  const int kend = min(p.K, kbeg + p.kchunk);
+  const int nk = (kend - kbeg) / BK;                        // launcher guarantees exact tiles
+
+  const bf16_t* ga[TileA::PER];
+  const bf16_t* gb[TileB::PER];
+#pragma unroll
+  for (int i = 0; i < TileA::PER; ++i)
+    ga[i] = A + TileA::src_offset(wave + i * NW, lane, m0, p.M, p.lda) + (TA ? (size_t)kbeg * p.lda : (size_t)kbeg);
+#pragma unroll
+  for (int i = 0; i < TileB::PER; ++i)
+    gb[i] = B + TileB::src_offset(wave + i * NW, lane, n0, p.N, p.ldb) + (TB ? (size_t)kbeg : (size_t)kbeg * p.ldb);
+  const size_t stepA = TA ? (size_t)BK * p.lda : (size_t)BK;
+  const size_t stepB = TB ? (size_t)BK : (size_t)BK * p.ldb;
+
+  auto issue = [&](int kt) __attribute__((always_inline)) {
+    char* st = lds + (kt % S) * STAGE;
+#pragma unroll
+    for (int i = 0; i < TileA::PER; ++i)
+      __builtin_amdgcn_global_load_lds((gbl_void*)(ga[i] + kt * stepA), (lds_void*)(st + (wave + i * NW) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < TileB::PER; ++i)
+      __builtin_amdgcn_global_load_lds((gbl_void*)(gb[i] + kt * stepB),
+                                       (lds_void*)(st + TileA::BYTES + (wave + i * NW) * 1024), 16, 0, 0);
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+#pragma unroll
+  for (int s = 0; s < S - 1; ++s)
+    if (s < nk) issue(s);
+
+  for (int kt = 0; kt < nk; ++kt) {
+    // tile kt has landed once at most the loads of the younger tiles are outstanding
+    if (kt + S - 1 <= nk) wait_vmcnt<(S - 2) * LPT>();
+    else wait_vmcnt<0>();
+    __syncthreads();                                        // tile kt visible; stage (kt-1)%S free
+#if !defined(OURO_ABLATE) || OURO_ABLATE != 1
+    if (kt + S - 1 < nk) issue(kt + S - 1);
+#endif
+    const char* sa = lds + (kt % S) * STAGE;
+    const char* sb = sa + TileA::BYTES;
+#if defined(OURO_ABLATE) && OURO_ABLATE == 2
+    if (p.alpha == 12345.f)
+#endif
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 af[TM], bfr[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        af[i] = TA ? frag_col<BM>(sa, wm * (TM * 32) + i * 32, ks, lane) : frag_row(sa, wm * (TM * 32) + i * 32, ks, lane);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        bfr[j] = TB ? frag_row(sb, wn * (TN * 32) + j * 32, ks, lane) : frag_col<BN>(sb, wn * (TN * 32) + j * 32, ks, lane);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+  }
+  __syncthreads();                                          // operand reads done: LDS reusable
+  mfma_epilogue<TM, TN>(p, acc, smem, m0 + wm * (TM * 32), n0 + wn * (TN * 32), lane, wave);
+}
+
+template <int BM, int BN, int WM, int WN, int S>
+hipError_t launch_dlds_cfg(hipStream_t s, GemmParams& p, int transA, int transB, int splits) {
+  constexpr size_t smem_main = (size_t)S * (BM + BN) * 128;
+  constexpr size_t smem_epi = (size_t)WM * WN * epilogue_stage_floats<BN / WN / 32>() * sizeof(float);
+  constexpr size_t smem = smem_main > smem_epi ? smem_main : smem_epi;
+  int tilesM = (p.M + BM - 1) / BM;
+  p.tilesN = (p.N + BN - 1) / BN;
+  dim3 grid(tilesM * p.tilesN, 1, splits), block(WM * WN * 64);
+#define OURO_LAUNCH(TA_, TB_)                                                                    \
+  do {                                                                                           \
+    static bool attr_done = false;                                                               \
+    auto kern = gemm_dlds_kernel<BM, BN, WM, WN, TA_, TB_, S>;                                   \
+    if (!attr_done) {                                                                            \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                    \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
+      if (e != hipSuccess) return e;                                                             \
+      attr_done = true;                                                                          \
+    }                                                                                            \
+    hipLaunchKernelGGL(kern, grid, block, smem, s, p);                                           \
+  } while (0)
+  if (!transA && !transB) OURO_LAUNCH(false, false);
+  else if (!transA && transB) OURO_LAUNCH(false, true);
+  else if (transA && !transB) OURO_LAUNCH(true, false);
+  else OURO_LAUNCH(true, true);
+#undef OURO_LAUNCH
+  return hipGetLastError();
+}
+
+// cfg: 10 = 128x128 S2, 11 = 128x128 S3, 12 = 128x128 S4, 13 = 256x128 (2x2 waves) S3,
+//      14 = 256x128 with 8 waves (4x2) S3, 15 = 256x256 8 waves (2x4) S2
+hipError_t launch_gemm_dlds(hipStream_t s, GemmParams& p, int transA, int transB, int splits, int cfg) {
+  switch (cfg) {
+    case 10: return launch_dlds_cfg<128, 128, 2, 2, 2>(s, p, transA, transB, splits);
+    case 11: return launch_dlds_cfg<128, 128, 2, 2, 3>(s, p, transA, transB, splits);
+    case 12: return launch_dlds_cfg<128, 128, 2, 2, 4>(s, p, transA, transB, splits);
+    case 13: return launch_dlds_cfg<256, 128, 2, 2, 3>(s, p, transA, transB, splits);
+    case 14: return launch_dlds_cfg<256, 128, 4, 2, 3>(s, p, transA, transB, splits);
+    case 15: return launch_dlds_cfg<256, 256, 2, 4, 2>(s, p, transA, transB, splits);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace ouro

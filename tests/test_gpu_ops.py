@@ -52,7 +52,8 @@ TOL = {0: 2e-5, 1: 1e-2}
 # ------------------------------------------------------------------------------- GEMM
 @pytest.mark.parametrize("dtype,force", [(0, 0), (1, 1), (1, 0)])
 @pytest.mark.parametrize("tA,tB", [(0, 0), (0, 1), (1, 0), (1, 1)])
-@pytest.mark.parametrize("M,N,K", [(200, 136, 328), (128, 256, 64), (72, 40, 1000), (384, 520, 96)])
+@pytest.mark.parametrize("M,N,K", [(200, 136, 328), (128, 256, 64), (72, 40, 1000), (384, 520, 96), (136, 264, 512),
+                                   (392, 136, 192), (520, 392, 1024)])
 def test_gemm_forms(dtype, force, tA, tB, M, N, K):
     rng = np.random.default_rng(M + 7 * N + 13 * K + tA * 2 + tB)
     A = rng.standard_normal((K, M) if tA else (M, K)).astype(np.float32)
