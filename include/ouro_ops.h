@@ -63,9 +63,10 @@ int ouro_op_embed_fwd(void* stream, int dtype, const int32_t* tok, const void* V
 /* dVi (fp32 [vocab,d], overwritten) = scatter-add of scale*dh rows (Eq. 7, left). */
 int ouro_op_embed_bwd(void* stream, int dtype, const int32_t* tok, const void* dh, float* dVi,
                       int N, int d, int vocab, float scale);
-/* Rows of fp32 logits [N, ld]: lse[n]; rowloss[n] = lse - logit[tgt]; G (T, [N, ldg]) =
- * (softmax - onehot)/N; *loss = mean(rowloss) (Eq. 4).  flag bit 1: target out of range. */
-int ouro_op_softmax_ce(void* stream, int dtype, const float* logits, int ld, const int32_t* tgt,
+/* Rows of logits [N, ld] (type T): lse[n]; rowloss[n] = lse - logit[tgt]; G (T, [N, ldg]) =
+ * (softmax - onehot)/N, which may be the logits buffer itself (in place); *loss =
+ * mean(rowloss) (Eq. 4).  flag bit 1: target out of range. */
+int ouro_op_softmax_ce(void* stream, int dtype, const void* logits, int ld, const int32_t* tgt,
                        void* G, int ldg, float* lse, float* rowloss, float* loss, int N, int vocab,
                        int* flag);
 /* Algorithm 1 (adam == 0) or Algorithm 2 on n fp32 elements with g = s0*g0 + s1*g1 (NULL = 0);

@@ -211,8 +211,8 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
     if (cfg < 0) cfg = (g.K % 64) == 0 ? 10 : 0;
     const bool dl = cfg >= 10 && (g.K % 64) == 0;
     if (cfg >= 10 && !dl) cfg = 0;
-    const int BM = (cfg == 0 || (cfg >= 10 && cfg <= 12)) ? 128 : 256;
-    const int BN = (cfg == 2 || cfg == 3 || cfg == 15) ? 256 : 128;
+    const int BM = (cfg == 0 || (cfg >= 10 && cfg <= 12) || cfg >= 16) ? 128 : 256;
+    const int BN = (cfg == 2 || cfg == 3 || cfg == 15 || cfg == 17) ? 256 : 128;
     int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     int splits = 1;
     if (g.accumulate && tiles < 384 && g.K >= 512) {

@@ -206,6 +206,9 @@ hipError_t launch_gemm_dlds(hipStream_t s, GemmParams& p, int transA, int transB
     case 13: return launch_dlds_cfg<256, 128, 2, 2, 3>(s, p, transA, transB, splits);
     case 14: return launch_dlds_cfg<256, 128, 4, 2, 3>(s, p, transA, transB, splits);
     case 15: return launch_dlds_cfg<256, 256, 2, 4, 2>(s, p, transA, transB, splits);
+    case 16: return launch_dlds_cfg<128, 128, 4, 2, 2>(s, p, transA, transB, splits);
+    case 17: return launch_dlds_cfg<128, 256, 2, 4, 2>(s, p, transA, transB, splits);
+    case 18: return launch_dlds_cfg<128, 128, 2, 4, 2>(s, p, transA, transB, splits);
     default: return hipErrorInvalidValue;
   }
 }

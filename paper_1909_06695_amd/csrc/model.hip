@@ -137,8 +137,8 @@ struct ouro_model {
   char* hL;                       // final hidden state [N, d]
   float* pe;                      // [T, d] fp32 (absolute mode)
   char* rtab;                     // [S, d] distance sinusoids, type T (relative mode)
-  float* logits;                  // [N, vocab] fp32
-  char* G;                        // [N, vocab] type T
+  char* G;                        // [N, ldv] type T: logits, then overwritten by d loss / d logits
+  int ldv;                        // vocab rounded up to 8 (16-byte rows)
   float *lse_ce, *rowloss, *loss;
   int* flag;
   // backward scratch
@@ -277,8 +277,8 @@ static size_t lay_out(ouro_model& m, char* base) {
   m.hL = P(N * d * es);
   m.pe = c.rel_pos ? nullptr : (float*)P(T * d * 4);
   m.rtab = c.rel_pos ? P(S * d * es) : nullptr;
-  m.logits = (float*)P(N * V * 4);
-  m.G = P(N * V * es);
+  m.ldv = (int)((V + 7) / 8 * 8);
+  m.G = P(N * (size_t)m.ldv * es);
   m.lse_ce = (float*)P(N * 4);
   m.rowloss = (float*)P(N * 4);
   m.loss = (float*)P(256);
@@ -507,10 +507,9 @@ extern "C" int ouro_module_forward(ouro_model* m, int k, const int32_t* dev_toke
   if (k == K) {
     m->tgt = dev_targets;
     const int d = c.d_model, V = c.vocab, N = m->N;
-    GemmDesc g = gd(m->hL, d, 0, m->vT(), d, 1, m->logits, V, N, V, d);   // logits = h_L V^T (Eq. 3)
-    g.out_fp32 = 1;
+    GemmDesc g = gd(m->hL, d, 0, m->vT(), d, 1, m->G, m->ldv, N, V, d);   // logits = h_L V^T (Eq. 3)
     RUN(run_gemm(m, g));
-    HIPCHK(launch_ce_rows(m->stream, c.dtype, m->logits, V, m->tgt, m->G, V, m->lse_ce, m->rowloss, N, V, m->flag));
+    HIPCHK(launch_ce_rows(m->stream, c.dtype, m->G, m->ldv, m->tgt, m->G, m->ldv, m->lse_ce, m->rowloss, N, V, m->flag));
     HIPCHK(launch_sum_rows(m->stream, m->rowloss, N, m->loss));
   }
   m->fwd_next = k + 1;
@@ -660,11 +659,11 @@ extern "C" int ouro_module_backward(ouro_model* m, int k) {
   if (k == K) {
     // Eq. 7 (right): dV_o = G^T h_L ; error gradient dh_L = G V
     float* dvo = m->slot_ptr(K + 1, 0);
-    GemmDesc g = gd(m->G, V, 1, m->hL, d, 0, dvo, d, V, d, N);
+    GemmDesc g = gd(m->G, m->ldv, 1, m->hL, d, 0, dvo, d, V, d, N);
     g.out_fp32 = 1;
     RUN(run_gemm(m, g));
     m->tags[K + 1][0] = m->t;
-    RUN(run_gemm(m, gd(m->G, V, 0, m->vT(), d, 0, (lastl % 2) ? m->dh1 : m->dh0, d, N, d, V)));
+    RUN(run_gemm(m, gd(m->G, m->ldv, 0, m->vT(), d, 0, (lastl % 2) ? m->dh1 : m->dh0, d, N, d, V)));
   }
   // layer l reads its output gradient from dh[(l)%2] and writes its input gradient to dh[(l-1)%2]
   for (int l = m->first_layer[k] - 1; l >= m->first_layer[k - 1]; --l) {

@@ -121,7 +121,7 @@ extern "C" int ouro_op_embed_bwd(void* stream, int dtype, const int32_t* tok, co
   return rc_of(launch_embed_bwd(s, dtype, tok, dh, dVi, N, d, vocab, scale));
 }
 
-extern "C" int ouro_op_softmax_ce(void* stream, int dtype, const float* logits, int ld, const int32_t* tgt, void* G,
+extern "C" int ouro_op_softmax_ce(void* stream, int dtype, const void* logits, int ld, const int32_t* tgt, void* G,
                                   int ldg, float* lse, float* rowloss, float* loss, int N, int vocab, int* flag) {
   if (!logits || !tgt || !G || !lse || !rowloss || !loss || !flag || N < 1 || ld < vocab || ldg < vocab) return OURO_E_ARG;
   hipStream_t s = (hipStream_t)stream;

@@ -3,6 +3,8 @@
 // rows, conversions, and the delayed SGD / Adam update.
 #include "common.h"
 
+#include <algorithm>
+
 namespace ouro {
 
 // 16-byte packs: 4 fp32 or 8 bf16
@@ -146,48 +148,6 @@ __global__ __launch_bounds__(256) void ln_bwd_dx_kernel(const T* __restrict__ dy
   }
 }
 
-template <typename T, int MAXI>
-__global__ __launch_bounds__(256) void ln_bwd_dx_vec_kernel(const T* __restrict__ dy, const T* __restrict__ x,
-                                                            const float* __restrict__ g, const float* __restrict__ mean,
-                                                            const float* __restrict__ rstd, T* __restrict__ dx,
-                                                            int rows, int d) {
-  constexpr int N = Pack<T>::N;
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
-  const int nvec = d / N;
-  const float mu = mean[row], rs = rstd[row];
-  float xh[MAXI][N], t[MAXI][N];
-  float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-  for (int i = 0; i < MAXI; ++i) {
-    int vi = lane + 64 * i;
-    if (vi < nvec) {
-      load_pack<T>(x + (size_t)row * d + vi * N, xh[i]);
-      load_pack<T>(dy + (size_t)row * d + vi * N, t[i]);
-#pragma unroll
-      for (int e = 0; e < N; ++e) {
-        xh[i][e] = (xh[i][e] - mu) * rs;
-        t[i][e] *= g[vi * N + e];
-        s1 += t[i][e];
-        s2 += t[i][e] * xh[i][e];
-      }
-    }
-  }
-  s1 = wave_sum(s1) / d;
-  s2 = wave_sum(s2) / d;
-#pragma unroll
-  for (int i = 0; i < MAXI; ++i) {
-    int vi = lane + 64 * i;
-    if (vi < nvec) {
-      float out[N];
-#pragma unroll
-      for (int e = 0; e < N; ++e) out[e] = rs * (t[i][e] - s1 - xh[i][e] * s2);
-      store_pack<T>(dx + (size_t)row * d + vi * N, out);
-    }
-  }
-}
-
 // Column sums over a chunk of rows; 64 columns x 4 row lanes per block, then atomics.
 // MODE 0: out0[c] += sum x[r,c].  MODE 1 (LayerNorm): out0[c] += sum dy*xhat, out1[c] += sum dy.
 template <typename T, int MODE>
@@ -227,6 +187,109 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, in
   }
 }
 
+// Vector path of the LayerNorm backward: one wavefront per row, rows strided over the grid;
+// the row's packs stay in registers, dg / db partial sums are kept per lane over all the
+// wave's rows, reduced over the block's four waves through LDS and added atomically once.
+template <typename T, int MAXI>
+__global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                           const float* __restrict__ g, const float* __restrict__ mean,
+                                                           const float* __restrict__ rstd, T* __restrict__ dx,
+                                                           float* __restrict__ dg, float* __restrict__ db, int rows, int d) {
+  constexpr int N = Pack<T>::N;
+  extern __shared__ float red[];                 // [4][d]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nvec = d / N;
+  float gl[MAXI][N], ag[MAXI][N], ab[MAXI][N];
+#pragma unroll
+  for (int i = 0; i < MAXI; ++i) {
+    int vi = lane + 64 * i;
+#pragma unroll
+    for (int e = 0; e < N; ++e) {
+      gl[i][e] = vi < nvec ? g[vi * N + e] : 0.f;
+      ag[i][e] = 0.f;
+      ab[i][e] = 0.f;
+    }
+  }
+  for (int row = blockIdx.x * 4 + wave; row < rows; row += gridDim.x * 4) {
+    const float mu = mean[row], rs = rstd[row];
+    float xh[MAXI][N], t[MAXI][N];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXI; ++i) {
+      int vi = lane + 64 * i;
+      if (vi < nvec) {
+        load_pack<T>(x + (size_t)row * d + vi * N, xh[i]);
+        load_pack<T>(dy + (size_t)row * d + vi * N, t[i]);
+#pragma unroll
+        for (int e = 0; e < N; ++e) {
+          xh[i][e] = (xh[i][e] - mu) * rs;
+          ag[i][e] += t[i][e] * xh[i][e];
+          ab[i][e] += t[i][e];
+          t[i][e] *= gl[i][e];
+          s1 += t[i][e];
+          s2 += t[i][e] * xh[i][e];
+        }
+      }
+    }
+    s1 = wave_sum(s1) / d;
+    s2 = wave_sum(s2) / d;
+#pragma unroll
+    for (int i = 0; i < MAXI; ++i) {
+      int vi = lane + 64 * i;
+      if (vi < nvec) {
+        float out[N];
+#pragma unroll
+        for (int e = 0; e < N; ++e) out[e] = rs * (t[i][e] - s1 - xh[i][e] * s2);
+        store_pack<T>(dx + (size_t)row * d + vi * N, out);
+      }
+    }
+  }
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+    for (int i = 0; i < MAXI; ++i) {
+      int vi = lane + 64 * i;
+      if (vi < nvec) {
+#pragma unroll
+        for (int e = 0; e < N; ++e) red[wave * d + vi * N + e] = pass ? ab[i][e] : ag[i][e];
+      }
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < d; c += 256)
+      unsafeAtomicAdd((pass ? db : dg) + c, red[c] + red[d + c] + red[2 * d + c] + red[3 * d + c]);
+    __syncthreads();
+  }
+}
+
+// Vector column sum: a wave covers 64 packs of one row (1 KiB), the block's four waves take
+// alternate rows; partial sums are reduced through LDS and added atomically.
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_vec_kernel(const T* __restrict__ x, int ldx, float* __restrict__ out,
+                                                         int rows, int rows_per_block) {
+  constexpr int N = Pack<T>::N;
+  __shared__ float red[4][64 * N];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c0 = (blockIdx.x * 64 + lane) * N;
+  const int rbeg = blockIdx.y * rows_per_block;
+  const int rend = min(rows, rbeg + rows_per_block);
+  float acc[N];
+#pragma unroll
+  for (int e = 0; e < N; ++e) acc[e] = 0.f;
+  for (int r = rbeg + wave; r < rend; r += 4) {
+    float v[N];
+    load_pack<T>(x + (size_t)r * ldx + c0, v);
+#pragma unroll
+    for (int e = 0; e < N; ++e) acc[e] += v[e];
+  }
+#pragma unroll
+  for (int e = 0; e < N; ++e) red[wave][lane * N + e] = acc[e];
+  __syncthreads();
+  for (int c = threadIdx.x; c < 64 * N; c += 256)
+    unsafeAtomicAdd(out + blockIdx.x * 64 * N + c, red[0][c] + red[1][c] + red[2][c] + red[3][c]);
+}
+
+static inline bool ptr16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
 hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const float* g,
                                 const float* mean, const float* rstd, void* dx, float* dg, float* db,
                                 int rows, int d) {
@@ -234,17 +297,22 @@ hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const 
   dim3 grid((rows + 3) / 4), block(256);
   const int rpb = 128;
   dim3 g2((d + 63) / 64, (rows + rpb - 1) / rpb);
+  const int pack = dtype == 1 ? 8 : 4;
+  if (d % pack == 0 && d / pack <= 256 && ptr16(dy) && ptr16(x) && ptr16(dx)) {
+    dim3 gf(std::min((rows + 3) / 4, 256));
+    size_t smem = 4 * (size_t)d * sizeof(float);
+    const int npl = (d / pack + 63) / 64;      // packs per lane
+#define OURO_LNB(T_, MI_) hipLaunchKernelGGL((ln_bwd_fused_kernel<T_, MI_>), gf, block, smem, s, (const T_*)dy, (const T_*)x, g, mean, rstd, (T_*)dx, dg, db, rows, d)
+    if (dtype == 1) { if (npl <= 1) OURO_LNB(bf16_t, 1); else if (npl <= 2) OURO_LNB(bf16_t, 2); else OURO_LNB(bf16_t, 4); }
+    else { if (npl <= 1) OURO_LNB(float, 1); else if (npl <= 2) OURO_LNB(float, 2); else OURO_LNB(float, 4); }
+#undef OURO_LNB
+    return hipGetLastError();
+  }
   if (dtype == 1) {
-    if (d % 8 == 0 && d / 8 <= 256)
-      hipLaunchKernelGGL((ln_bwd_dx_vec_kernel<bf16_t, 4>), grid, block, 0, s, (const bf16_t*)dy, (const bf16_t*)x, g, mean, rstd, (bf16_t*)dx, rows, d);
-    else
-      hipLaunchKernelGGL(ln_bwd_dx_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)dy, (const bf16_t*)x, g, mean, rstd, (bf16_t*)dx, rows, d);
+    hipLaunchKernelGGL(ln_bwd_dx_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)dy, (const bf16_t*)x, g, mean, rstd, (bf16_t*)dx, rows, d);
     hipLaunchKernelGGL((colsum_kernel<bf16_t, 1>), g2, block, 0, s, (const bf16_t*)dy, d, (const bf16_t*)x, mean, rstd, dg, db, rows, d, rpb);
   } else {
-    if (d % 4 == 0 && d / 4 <= 256)
-      hipLaunchKernelGGL((ln_bwd_dx_vec_kernel<float, 4>), grid, block, 0, s, (const float*)dy, (const float*)x, g, mean, rstd, (float*)dx, rows, d);
-    else
-      hipLaunchKernelGGL(ln_bwd_dx_kernel<float>, grid, block, 0, s, (const float*)dy, (const float*)x, g, mean, rstd, (float*)dx, rows, d);
+    hipLaunchKernelGGL(ln_bwd_dx_kernel<float>, grid, block, 0, s, (const float*)dy, (const float*)x, g, mean, rstd, (float*)dx, rows, d);
     hipLaunchKernelGGL((colsum_kernel<float, 1>), g2, block, 0, s, (const float*)dy, d, (const float*)x, mean, rstd, dg, db, rows, d, rpb);
   }
   return hipGetLastError();
@@ -252,8 +320,17 @@ hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const 
 
 hipError_t launch_colsum(hipStream_t s, int dtype, const void* x, int ldx, float* out, int rows, int cols) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
+  dim3 block(256);
+  const int pack = dtype == 1 ? 8 : 4;
+  if (cols % (64 * pack) == 0 && ldx % pack == 0 && ptr16(x)) {
+    const int rpb = 64;
+    dim3 grid(cols / (64 * pack), (rows + rpb - 1) / rpb);
+    if (dtype == 1) hipLaunchKernelGGL(colsum_vec_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, ldx, out, rows, rpb);
+    else hipLaunchKernelGGL(colsum_vec_kernel<float>, grid, block, 0, s, (const float*)x, ldx, out, rows, rpb);
+    return hipGetLastError();
+  }
   const int rpb = 128;
-  dim3 grid((cols + 63) / 64, (rows + rpb - 1) / rpb), block(256);
+  dim3 grid((cols + 63) / 64, (rows + rpb - 1) / rpb);
   if (dtype == 1)
     hipLaunchKernelGGL((colsum_kernel<bf16_t, 0>), grid, block, 0, s, (const bf16_t*)x, ldx, (const bf16_t*)nullptr, nullptr, nullptr, out, nullptr, rows, cols, rpb);
   else
@@ -310,21 +387,36 @@ hipError_t launch_embed_bwd(hipStream_t s, int dtype, const int32_t* tok, const 
 }
 
 // ------------------------------------------------------------------------ cross entropy
-// One block per row: online (max, sum) over the vocabulary, then G = (softmax - onehot)/N.
-template <typename T>
-__global__ __launch_bounds__(256) void ce_rows_kernel(const float* __restrict__ logits, int ld,
+// One block per row of logits (type T): online (max, sum) over the vocabulary in 16-byte
+// packs, then G = (softmax - onehot)/N written over the same positions (G may alias the
+// logits: a thread overwrites only elements it alone reads in the second pass, and the
+// target logit is fetched before the block-wide barrier).
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void ce_rows_kernel(const T* __restrict__ logits, int ld,
                                                       const int32_t* __restrict__ tgt, T* __restrict__ G, int ldg,
                                                       float* __restrict__ lse_out, float* __restrict__ rowloss,
                                                       int N, int vocab, int* flag) {
+  constexpr int P = Pack<T>::N;
   __shared__ float sm_m[4], sm_s[4];
   const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const float* row = logits + (size_t)n * ld;
+  const T* row = logits + (size_t)n * ld;
+  T* grow = G + (size_t)n * ldg;
+  const int t = tgt[n];
+  const bool ok = t >= 0 && t < vocab;
+  const float tl = ok ? to_f32(row[t]) : 0.f;
+  const int nvec = VEC ? vocab / P : 0;
   float m = -INFINITY, ssum = 0.f;
-  for (int c = tid; c < vocab; c += 256) {
-    float v = row[c];
+  auto upd = [&](float v) __attribute__((always_inline)) {
     if (v > m) { ssum = ssum * __expf(m - v) + 1.f; m = v; }
     else ssum += __expf(v - m);
+  };
+  for (int vi = tid; vi < nvec; vi += 256) {
+    float v[P];
+    load_pack<T>(row + vi * P, v);
+#pragma unroll
+    for (int e = 0; e < P; ++e) upd(v[e]);
   }
+  for (int c = nvec * P + tid; c < vocab; c += 256) upd(to_f32(row[c]));
   float wm = wave_max(m);
   ssum = (m == -INFINITY) ? 0.f : ssum * __expf(m - wm);
   ssum = wave_sum(ssum);
@@ -335,26 +427,42 @@ __global__ __launch_bounds__(256) void ce_rows_kernel(const float* __restrict__ 
 #pragma unroll
   for (int w = 0; w < 4; ++w) bs += sm_s[w] * __expf(sm_m[w] - bm);
   const float lse = bm + logf(bs);
-  const int t = tgt[n];
-  const bool ok = t >= 0 && t < vocab;
   if (tid == 0) {
     lse_out[n] = lse;
-    rowloss[n] = ok ? lse - row[t] : 0.f;
+    rowloss[n] = ok ? lse - tl : 0.f;
     if (!ok) atomicOr(flag, 2);
   }
   const float invN = 1.f / N;
-  for (int c = tid; c < vocab; c += 256) {
-    float gval = __expf(row[c] - lse);
+  for (int vi = tid; vi < nvec; vi += 256) {
+    float v[P];
+    load_pack<T>(row + vi * P, v);
+#pragma unroll
+    for (int e = 0; e < P; ++e) {
+      float gval = __expf(v[e] - lse);
+      if (ok && vi * P + e == t) gval -= 1.f;
+      v[e] = gval * invN;
+    }
+    store_pack<T>(grow + vi * P, v);
+  }
+  for (int c = nvec * P + tid; c < vocab; c += 256) {
+    float gval = __expf(to_f32(row[c]) - lse);
     if (ok && c == t) gval -= 1.f;
-    G[(size_t)n * ldg + c] = from_f32<T>(gval * invN);
+    grow[c] = from_f32<T>(gval * invN);
   }
 }
 
-hipError_t launch_ce_rows(hipStream_t s, int dtype, const float* logits, int ld, const int32_t* tgt,
+hipError_t launch_ce_rows(hipStream_t s, int dtype, const void* logits, int ld, const int32_t* tgt,
                           void* G, int ldg, float* lse, float* rowloss, int N, int vocab, int* flag) {
   dim3 grid(N), block(256);
-  if (dtype == 1) hipLaunchKernelGGL(ce_rows_kernel<bf16_t>, grid, block, 0, s, logits, ld, tgt, (bf16_t*)G, ldg, lse, rowloss, N, vocab, flag);
-  else hipLaunchKernelGGL(ce_rows_kernel<float>, grid, block, 0, s, logits, ld, tgt, (float*)G, ldg, lse, rowloss, N, vocab, flag);
+  const int pack = dtype == 1 ? 8 : 4;
+  const bool vec = ld % pack == 0 && ldg % pack == 0 && ptr16(logits) && ptr16(G);
+  if (dtype == 1) {
+    if (vec) hipLaunchKernelGGL((ce_rows_kernel<bf16_t, true>), grid, block, 0, s, (const bf16_t*)logits, ld, tgt, (bf16_t*)G, ldg, lse, rowloss, N, vocab, flag);
+    else hipLaunchKernelGGL((ce_rows_kernel<bf16_t, false>), grid, block, 0, s, (const bf16_t*)logits, ld, tgt, (bf16_t*)G, ldg, lse, rowloss, N, vocab, flag);
+  } else {
+    if (vec) hipLaunchKernelGGL((ce_rows_kernel<float, true>), grid, block, 0, s, (const float*)logits, ld, tgt, (float*)G, ldg, lse, rowloss, N, vocab, flag);
+    else hipLaunchKernelGGL((ce_rows_kernel<float, false>), grid, block, 0, s, (const float*)logits, ld, tgt, (float*)G, ldg, lse, rowloss, N, vocab, flag);
+  }
   return hipGetLastError();
 }
 

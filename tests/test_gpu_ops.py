@@ -272,23 +272,31 @@ def test_softmax_cross_entropy(dtype, N, vocab):
     rng = np.random.default_rng(N + vocab)
     logits = (rng.standard_normal((N, vocab)) * 3).astype(np.float32)
     tgt = rng.integers(0, vocab, N).astype(np.int32)
-    dl = torch.from_numpy(logits).cuda()
-    dt = torch.from_numpy(tgt).cuda()
+    ld = (vocab + 7) // 8 * 8                                  # padded rows, as the model lays them out
     tdt = torch.bfloat16 if dtype else torch.float32
-    G = torch.zeros((N, vocab), dtype=tdt, device="cuda")
+    dl = torch.zeros((N, ld), dtype=tdt, device="cuda")
+    dl[:, :vocab] = dev(logits, dtype)
+    l64 = host(dl)[:, :vocab]                                  # the (rounded) logits both sides see
+    dt = torch.from_numpy(tgt).cuda()
+    G = torch.zeros((N, ld), dtype=tdt, device="cuda")
     lse = torch.zeros(N, device="cuda"); rl = torch.zeros(N, device="cuda"); loss = torch.zeros(1, device="cuda")
     flag = torch.zeros(1, dtype=torch.int32, device="cuda")
-    ok(L().ouro_op_softmax_ce(stream(), dtype, p(dl), vocab, p(dt), p(G), vocab, p(lse), p(rl), p(loss), N, vocab, p(flag)))
+    ok(L().ouro_op_softmax_ce(stream(), dtype, p(dl), ld, p(dt), p(G), ld, p(lse), p(rl), p(loss), N, vocab, p(flag)))
     torch.cuda.synchronize()
-    rloss, rlse = O.cross_entropy_fwd(logits.astype(np.float64), tgt)
-    rG = O.cross_entropy_bwd(logits.astype(np.float64), rlse, tgt)
+    rloss, rlse = O.cross_entropy_fwd(l64, tgt)
+    rG = O.cross_entropy_bwd(l64, rlse, tgt)
     assert abs(loss.item() - rloss) / rloss < 1e-5
     assert np.abs(host(lse) - rlse).max() < 1e-4
-    assert rel_err(host(G), rG) < (1e-5 if dtype == 0 else 5e-3)
+    assert rel_err(host(G)[:, :vocab], rG) < (1e-5 if dtype == 0 else 5e-3)
     assert flag.item() == 0
+    # in place: G written over the logits
+    dl2 = dl.clone()
+    ok(L().ouro_op_softmax_ce(stream(), dtype, p(dl2), ld, p(dt), p(dl2), ld, p(lse), p(rl), p(loss), N, vocab, p(flag)))
+    torch.cuda.synchronize()
+    assert torch.equal(dl2[:, :vocab], G[:, :vocab])
     # zero logits: loss = ln(vocab) (uniform softmax)
     dl.zero_()
-    ok(L().ouro_op_softmax_ce(stream(), dtype, p(dl), vocab, p(dt), p(G), vocab, p(lse), p(rl), p(loss), N, vocab, p(flag)))
+    ok(L().ouro_op_softmax_ce(stream(), dtype, p(dl), ld, p(dt), p(G), ld, p(lse), p(rl), p(loss), N, vocab, p(flag)))
     torch.cuda.synchronize()
     assert abs(loss.item() - math.log(vocab)) < 1e-5
 
