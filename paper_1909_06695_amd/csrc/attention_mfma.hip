@@ -5,9 +5,14 @@
 // kernel), so a lane owns one query (or key) column and row statistics need a single
 // cross-half shuffle.  The probabilities feed the next matrix instruction straight from
 // the accumulator registers: the contraction index may be enumerated in any order as long
-// as both operands agree, so the other operand is read from a transposed LDS tile in the
-// accumulator's own row order (two 8-byte pieces per lane) and nothing is exchanged
-// between lanes.  Online softmax in base 2; log-sum-exp saved for the backward kernels.
+// as both operands agree, so the other operand is fetched in the accumulator's own row
+// order and nothing is exchanged between lanes.
+//
+// K / V / Q / dO tiles (64 rows x 64 features) go global -> LDS with direct 16-byte loads
+// into a three-stage ring, one copy per tile: products that contract over the feature
+// index read rows (16 bytes per lane); products that contract over the row index read the
+// same tile with the LDS transpose-read instruction.  Online softmax in base 2; the
+// log-sum-exp is saved for the backward kernels.
 #include "common.h"
 #include "tiles.h"
 
@@ -28,19 +33,65 @@ struct FaParams {
   float* D;
 };
 
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void gbl_void;
+
+constexpr int TILE_BYTES = 64 * 128;
+constexpr int NSTAGE = 3;
+
+// chunk swizzle of a tile row: a bijection of the low three row bits whose values over
+// four consecutive rows differ in bits 1-2, so that both the 16-byte row reads and the
+// transposed 4-row reads spread over the banks
+__device__ __forceinline__ int swza(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+
+template <int N>
+__device__ __forceinline__ void fa_wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 t) { return *reinterpret_cast<bf16x8*>(&t); }
 
-// operand rows of a row-form tile: row = base + lane%32, 16-byte chunk 2*ks + lane/32
-__device__ __forceinline__ bf16x8 read_rowform(const uint4* tile, int row, int ks, int h32) {
-  return as_bf16x8(tile[row * 8 + ((2 * ks + h32) ^ swz(row))]);
+// Direct load of rows [row0, row0+64) x 64 features of src into an LDS tile (4 waves, two
+// 1 KiB wave-loads each).  Rows past rmax-1 repeat the last valid row; callers mask them.
+__device__ __forceinline__ void dma_tile(const bf16_t* src, int ld, int row0, int rmax, char* tile, int wave, int lane) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int j = wave * 2 + i;
+    const int row = 8 * j + (lane >> 3);
+    const int c = (lane & 7) ^ swza(row);
+    const int gr = min(row0 + row, rmax - 1);
+    __builtin_amdgcn_global_load_lds((gbl_void*)(src + (size_t)gr * ld + 8 * c), (lds_void*)(tile + j * 1024), 16, 0, 0);
+  }
 }
-// operand rows of a transposed tile in accumulator order: elements 0..3 = columns
-// 8*c0 + 4*h32 + (0..3), elements 4..7 = columns 8*(c0+1) + 4*h32 + (0..3)
-__device__ __forceinline__ bf16x8 read_accorder(const uint4* tile, int row, int c0, int h32) {
-  const uint2* t2 = reinterpret_cast<const uint2*>(tile);
-  uint2 lo = t2[(row * 8 + (c0 ^ swz(row))) * 2 + h32];
-  uint2 hi = t2[(row * 8 + ((c0 + 1) ^ swz(row))) * 2 + h32];
-  return as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y));
+// 64 floats src[i0 .. i0+63] (index clamped to n-1) into LDS, one dword per lane.
+__device__ __forceinline__ void dma_floats(const float* src, int i0, int n, char* dst, int lane) {
+  const int i = min(i0 + lane, n - 1);
+  __builtin_amdgcn_global_load_lds((gbl_void*)(src + i), (lds_void*)dst, 4, 0, 0);
+}
+
+// operand whose contraction index is the feature: row = r0 + lane%32, features 16*ks + 8*(lane/32) ..+7
+__device__ __forceinline__ bf16x8 read_rows(const char* tile, int r0, int ks, int lane) {
+  const int row = r0 + (lane & 31);
+  const int c = 2 * ks + (lane >> 5);
+  return *reinterpret_cast<const bf16x8*>(tile + row * 128 + ((c ^ swza(row)) << 4));
+}
+// operand whose contraction index is the tile row, in accumulator order: lane owns feature
+// f0 + lane%32; elements 0..3 = tile rows k0 + 4*(lane/32) + (0..3), elements 4..7 = rows
+// k0 + 8 + 4*(lane/32) + (0..3).  Two transpose reads (each 16-lane group gathers a
+// 4-row x 16-feature block).
+__device__ __forceinline__ bf16x8 read_rows_t(const char* tile, int f0, int k0, int lane) {
+  const int g4 = lane >> 4, i = lane & 15;
+  const int f = f0 + 16 * (g4 & 1) + 4 * (i & 3);
+  const int ka = k0 + 4 * (g4 >> 1) + (i >> 2);
+  const int kb = ka + 8;
+  const char* a0 = tile + ka * 128 + (((f >> 3) ^ swza(ka)) << 4) + ((f & 7) << 1);
+  const char* a1 = tile + kb * 128 + (((f >> 3) ^ swza(kb)) << 4) + ((f & 7) << 1);
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)a0);
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)a1);
+  union { struct { s16x4 l, h; } p; bf16x8 v; } u;
+  u.p.l = lo; u.p.h = hi;
+  return u.v;
 }
 __device__ __forceinline__ bf16x8 pack_acc(const f32x16& a, int sub) {
   bf16x8 r;
@@ -62,10 +113,9 @@ __device__ __forceinline__ void store_acc_row(bf16_t* dst, const f32x16 (&acc)[2
 }
 
 // ------------------------------------------------------------------------------ forward
-// grid (ceil(T/128), H, B); 4 waves x 32 queries; key blocks of 64 staged in LDS.
+// grid (ceil(T/128), H, B); 4 waves x 32 queries; key blocks of 64.
 __global__ __launch_bounds__(256) void fa_fwd_kernel(FaParams p) {
-  __shared__ uint4 sK[2][512];
-  __shared__ uint4 sVt[2][512];
+  __shared__ __attribute__((aligned(16))) char lds[NSTAGE * 2 * TILE_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
   const int qblk = gridDim.x - 1 - blockIdx.x;            // longest rows first
   const int head = blockIdx.y, b = blockIdx.z;
@@ -91,22 +141,22 @@ __global__ __launch_bounds__(256) void fa_fwd_kernel(FaParams p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
   float m = -INFINITY, l = 0.f;
-  uint4 rk[2], rv[4];
-  auto gload = [&](int jb) {
-    load_rowform<64, 256>(kb, p.ldk, jb * 64, p.S, 0, 64, tid, rk);
-    load_colform<64, 256>(vb, p.ldv, 0, 64, jb * 64, p.S, tid, rv);
+  auto issue = [&](int jb) __attribute__((always_inline)) {
+    char* st = lds + (jb % NSTAGE) * (2 * TILE_BYTES);
+    dma_tile(kb, p.ldk, jb * 64, p.S, st, wave, lane);
+    dma_tile(vb, p.ldv, jb * 64, p.S, st + TILE_BYTES, wave, lane);
   };
-  auto sstore = [&](int st) {
-    store_rowform<64, 256>(sK[st], tid, rk);
-    store_colform<64, 256>(sVt[st], tid, rv);
-  };
-  gload(0);
-  sstore(0);
-  __syncthreads();
+  constexpr int LPT = 4;                                   // loads per thread per stage
+#pragma unroll
+  for (int s = 0; s < NSTAGE - 1; ++s)
+    if (s < nkb) issue(s);
   for (int jb = 0; jb < nkb; ++jb) {
-    const bool more = jb + 1 < nkb;
-    if (more) gload(jb + 1);
-    const int st = jb & 1;
+    if (jb + NSTAGE - 1 <= nkb) fa_wait_vmcnt<(NSTAGE - 2) * LPT>();
+    else fa_wait_vmcnt<0>();
+    __syncthreads();
+    if (jb + NSTAGE - 1 < nkb) issue(jb + NSTAGE - 1);
+    const char* sK = lds + (jb % NSTAGE) * (2 * TILE_BYTES);
+    const char* sV = sK + TILE_BYTES;
     if (wave_on && jb * 64 <= wave_kmax) {
       f32x16 s[2];
 #pragma unroll
@@ -115,7 +165,7 @@ __global__ __launch_bounds__(256) void fa_fwd_kernel(FaParams p) {
         for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
-          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rowform(sK[st], 32 * kt + l32, ks, h32), qf[ks], s[kt], 0, 0, 0);
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sK, 32 * kt, ks, lane), qf[ks], s[kt], 0, 0, 0);
       }
       float mloc = -INFINITY;
 #pragma unroll
@@ -154,11 +204,9 @@ __global__ __launch_bounds__(256) void fa_fwd_kernel(FaParams p) {
         bf16x8 pb = pack_acc(s[kt], sub);
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
-          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_accorder(sVt[st], 32 * dt + l32, 4 * kt + 2 * sub, h32), pb, oacc[dt], 0, 0, 0);
+          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sV, 32 * dt, 32 * kt + 16 * sub, lane), pb, oacc[dt], 0, 0, 0);
       }
     }
-    if (more) sstore((jb + 1) & 1);
-    __syncthreads();
   }
   if (qi < p.T) {
     const float inv = l > 0.f ? 1.f / l : 0.f;
@@ -189,14 +237,15 @@ __global__ __launch_bounds__(256) void fa_bwd_prep_kernel(FaParams p) {
 }
 
 // ------------------------------------------------------------------------ dK, dV kernel
-// grid (ceil(S/128), H, B); 4 waves x 32 keys; query blocks of 64 staged in LDS both as
-// rows (for S = Q K^T and dP = dO V^T) and transposed (for dV^T += dO^T P, dK^T += Q^T dS).
-constexpr int DKV_STAGE_U4 = 4 * 512 + 32;   // Q, Q^T, dO, dO^T tiles + lse[64] + D[64]
+// grid (ceil(S/128), H, B); 4 waves x 32 keys; query blocks of 64: S = Q K^T and dP = dO V^T
+// read Q / dO rows, dV^T += dO^T P and dK^T += Q^T dS read the same tiles transposed.
+constexpr int DKV_STAGE = 2 * TILE_BYTES + 1024;   // Q, dO, lse[64], D[64], two spare lines
 __global__ __launch_bounds__(256) void fa_bwd_dkv_kernel(FaParams p) {
-  extern __shared__ uint4 dyn[];
+  __shared__ __attribute__((aligned(16))) char lds[NSTAGE * DKV_STAGE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
+  const int kblk = blockIdx.x;                            // key block 0 sees every query: longest first
   const int head = blockIdx.y, b = blockIdx.z;
-  const int kb0 = blockIdx.x * 128 + wave * 32, key = kb0 + l32;
+  const int kb0 = kblk * 128 + wave * 32, key = kb0 + l32;
   const bf16_t* qb = p.q + (size_t)b * p.T * p.ldq + head * 64;
   const bf16_t* dob = p.d_o + (size_t)b * p.T * p.lddo + head * 64;
   const bf16_t* kbp = p.k + (size_t)b * p.S * p.ldk + head * 64;
@@ -219,45 +268,33 @@ __global__ __launch_bounds__(256) void fa_bwd_dkv_kernel(FaParams p) {
   for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dkT[dt][r] = 0.f; dvT[dt][r] = 0.f; }
-  // first query that sees the block's first key: i >= key - Mv
-  const int ib0 = max(0, (int)blockIdx.x * 128 - p.Mv) / 64;
+  // first query block that sees the workgroup's first key: i >= key - Mv
+  const int ib0 = max(0, kblk * 128 - p.Mv) / 64;
   const int nib = (p.T + 63) / 64;
+  const int nit = nib - ib0;
   const bool wave_on = kb0 < p.S;
-  uint4 rq[2], rqt[4], rd[2], rdt[4];
-  float rstat = 0.f;
-  auto gload = [&](int ib) {
-    load_rowform<64, 256>(qb, p.ldq, ib * 64, p.T, 0, 64, tid, rq);
-    load_colform<64, 256>(qb, p.ldq, 0, 64, ib * 64, p.T, tid, rqt);
-    load_rowform<64, 256>(dob, p.lddo, ib * 64, p.T, 0, 64, tid, rd);
-    load_colform<64, 256>(dob, p.lddo, 0, 64, ib * 64, p.T, tid, rdt);
-    rstat = 0.f;
-    if (tid < 128) {
-      int i = ib * 64 + (tid & 63);
-      if (i < p.T) rstat = tid < 64 ? lseb[i] : Db[i];
-    }
+  auto issue = [&](int it) __attribute__((always_inline)) {
+    char* st = lds + (it % NSTAGE) * DKV_STAGE;
+    const int i0 = (ib0 + it) * 64;
+    dma_tile(qb, p.ldq, i0, p.T, st, wave, lane);
+    dma_tile(dob, p.lddo, i0, p.T, st + TILE_BYTES, wave, lane);
+    // waves 0/1 fetch lse / D; waves 2/3 repeat them into spare lines so that every wave
+    // has the same number of loads in flight
+    dma_floats((wave & 1) ? Db : lseb, i0, p.T, st + 2 * TILE_BYTES + wave * 256, lane);
   };
-  auto sstore = [&](int st) {
-    uint4* base = dyn + st * DKV_STAGE_U4;
-    store_rowform<64, 256>(base, tid, rq);
-    store_colform<64, 256>(base + 512, tid, rqt);
-    store_rowform<64, 256>(base + 1024, tid, rd);
-    store_colform<64, 256>(base + 1536, tid, rdt);
-    if (tid < 128) reinterpret_cast<float*>(base + 2048)[tid] = rstat;
-  };
-  if (ib0 < nib) {
-    gload(ib0);
-    sstore(0);
-  }
-  __syncthreads();
-  for (int ib = ib0; ib < nib; ++ib) {
-    const bool more = ib + 1 < nib;
-    if (more) gload(ib + 1);
-    const int st = (ib - ib0) & 1;
-    const uint4* sQ = dyn + st * DKV_STAGE_U4;
-    const uint4* sQt = sQ + 512;
-    const uint4* sdO = sQ + 1024;
-    const uint4* sdOt = sQ + 1536;
-    const float* sl = reinterpret_cast<const float*>(sQ + 2048);
+  constexpr int LPT = 5;
+#pragma unroll
+  for (int s = 0; s < NSTAGE - 1; ++s)
+    if (s < nit) issue(s);
+  for (int it = 0; it < nit; ++it) {
+    if (it + NSTAGE - 1 <= nit) fa_wait_vmcnt<(NSTAGE - 2) * LPT>();
+    else fa_wait_vmcnt<0>();
+    __syncthreads();
+    if (it + NSTAGE - 1 < nit) issue(it + NSTAGE - 1);
+    const int ib = ib0 + it;
+    const char* sQ = lds + (it % NSTAGE) * DKV_STAGE;
+    const char* sdO = sQ + TILE_BYTES;
+    const float* sl = reinterpret_cast<const float*>(sQ + 2 * TILE_BYTES);
     const float* sD = sl + 64;
     if (wave_on && p.Mv + ib * 64 + 63 >= kb0) {
       f32x16 s[2], dp[2];
@@ -267,8 +304,8 @@ __global__ __launch_bounds__(256) void fa_bwd_dkv_kernel(FaParams p) {
         for (int r = 0; r < 16; ++r) { s[qt][r] = 0.f; dp[qt][r] = 0.f; }
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-          s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rowform(sQ, 32 * qt + l32, ks, h32), kf[ks], s[qt], 0, 0, 0);
-          dp[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rowform(sdO, 32 * qt + l32, ks, h32), vf[ks], dp[qt], 0, 0, 0);
+          s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sQ, 32 * qt, ks, lane), kf[ks], s[qt], 0, 0, 0);
+          dp[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sdO, 32 * qt, ks, lane), vf[ks], dp[qt], 0, 0, 0);
         }
       }
 #pragma unroll
@@ -289,13 +326,11 @@ __global__ __launch_bounds__(256) void fa_bwd_dkv_kernel(FaParams p) {
         bf16x8 dsb = pack_acc(dp[qt], sub);
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt) {
-          dvT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_accorder(sdOt, 32 * dt + l32, 4 * qt + 2 * sub, h32), pb, dvT[dt], 0, 0, 0);
-          dkT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_accorder(sQt, 32 * dt + l32, 4 * qt + 2 * sub, h32), dsb, dkT[dt], 0, 0, 0);
+          dvT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sdO, 32 * dt, 32 * qt + 16 * sub, lane), pb, dvT[dt], 0, 0, 0);
+          dkT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sQ, 32 * dt, 32 * qt + 16 * sub, lane), dsb, dkT[dt], 0, 0, 0);
         }
       }
     }
-    if (more) sstore((ib + 1 - ib0) & 1);
-    __syncthreads();
   }
   if (key < p.S) {
     store_acc_row(p.dk + ((size_t)b * p.S + key) * p.lddk + head * 64, dkT, 1.f, h32);
@@ -304,12 +339,10 @@ __global__ __launch_bounds__(256) void fa_bwd_dkv_kernel(FaParams p) {
 }
 
 // ---------------------------------------------------------------------------- dQ kernel
-// grid (ceil(T/128), H, B); 4 waves x 32 queries; key blocks of 64 staged as K rows, V rows
-// and K^T (for dQ^T += K^T dS^T).
+// grid (ceil(T/128), H, B); 4 waves x 32 queries; key blocks of 64: S^T = K Q^T and
+// dP^T = V dO^T read K / V rows, dQ^T += K^T dS^T reads the K tile transposed.
 __global__ __launch_bounds__(256) void fa_bwd_dq_kernel(FaParams p) {
-  __shared__ uint4 sK[2][512];
-  __shared__ uint4 sV[2][512];
-  __shared__ uint4 sKt[2][512];
+  __shared__ __attribute__((aligned(16))) char lds[NSTAGE * 2 * TILE_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
   const int qblk = gridDim.x - 1 - blockIdx.x;
   const int head = blockIdx.y, b = blockIdx.z;
@@ -344,24 +377,22 @@ __global__ __launch_bounds__(256) void fa_bwd_dq_kernel(FaParams p) {
   for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) dqT[dt][r] = 0.f;
-  uint4 rk[2], rv[2], rkt[4];
-  auto gload = [&](int jb) {
-    load_rowform<64, 256>(kb, p.ldk, jb * 64, p.S, 0, 64, tid, rk);
-    load_rowform<64, 256>(vb, p.ldv, jb * 64, p.S, 0, 64, tid, rv);
-    load_colform<64, 256>(kb, p.ldk, 0, 64, jb * 64, p.S, tid, rkt);
+  auto issue = [&](int jb) __attribute__((always_inline)) {
+    char* st = lds + (jb % NSTAGE) * (2 * TILE_BYTES);
+    dma_tile(kb, p.ldk, jb * 64, p.S, st, wave, lane);
+    dma_tile(vb, p.ldv, jb * 64, p.S, st + TILE_BYTES, wave, lane);
   };
-  auto sstore = [&](int st) {
-    store_rowform<64, 256>(sK[st], tid, rk);
-    store_rowform<64, 256>(sV[st], tid, rv);
-    store_colform<64, 256>(sKt[st], tid, rkt);
-  };
-  gload(0);
-  sstore(0);
-  __syncthreads();
+  constexpr int LPT = 4;
+#pragma unroll
+  for (int s = 0; s < NSTAGE - 1; ++s)
+    if (s < nkb) issue(s);
   for (int jb = 0; jb < nkb; ++jb) {
-    const bool more = jb + 1 < nkb;
-    if (more) gload(jb + 1);
-    const int st = jb & 1;
+    if (jb + NSTAGE - 1 <= nkb) fa_wait_vmcnt<(NSTAGE - 2) * LPT>();
+    else fa_wait_vmcnt<0>();
+    __syncthreads();
+    if (jb + NSTAGE - 1 < nkb) issue(jb + NSTAGE - 1);
+    const char* sK = lds + (jb % NSTAGE) * (2 * TILE_BYTES);
+    const char* sV = sK + TILE_BYTES;
     if (wave_on && jb * 64 <= wave_kmax) {
       f32x16 s[2], dp[2];
 #pragma unroll
@@ -370,8 +401,8 @@ __global__ __launch_bounds__(256) void fa_bwd_dq_kernel(FaParams p) {
         for (int r = 0; r < 16; ++r) { s[kt][r] = 0.f; dp[kt][r] = 0.f; }
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rowform(sK[st], 32 * kt + l32, ks, h32), qf[ks], s[kt], 0, 0, 0);
-          dp[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rowform(sV[st], 32 * kt + l32, ks, h32), dof[ks], dp[kt], 0, 0, 0);
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sK, 32 * kt, ks, lane), qf[ks], s[kt], 0, 0, 0);
+          dp[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sV, 32 * kt, ks, lane), dof[ks], dp[kt], 0, 0, 0);
         }
       }
 #pragma unroll
@@ -389,11 +420,9 @@ __global__ __launch_bounds__(256) void fa_bwd_dq_kernel(FaParams p) {
         bf16x8 dsb = pack_acc(dp[kt], sub);
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
-          dqT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_accorder(sKt[st], 32 * dt + l32, 4 * kt + 2 * sub, h32), dsb, dqT[dt], 0, 0, 0);
+          dqT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sK, 32 * dt, 32 * kt + 16 * sub, lane), dsb, dqT[dt], 0, 0, 0);
       }
     }
-    if (more) sstore((jb + 1) & 1);
-    __syncthreads();
   }
   if (qi < p.T) store_acc_row(p.dq + ((size_t)b * p.T + qi) * p.lddq + head * 64, dqT, 1.f, h32);
 }
@@ -437,14 +466,7 @@ hipError_t launch_attn_bwd_mfma(hipStream_t s, const AttnDesc& a) {
   hipLaunchKernelGGL(fa_bwd_prep_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  constexpr size_t smem = 2 * (size_t)DKV_STAGE_U4 * sizeof(uint4);
-  static bool attr_done = false;
-  if (!attr_done) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_bwd_dkv_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
-  hipLaunchKernelGGL(fa_bwd_dkv_kernel, dim3((a.S + 127) / 128, a.H, a.B), dim3(256), smem, s, p);
+  hipLaunchKernelGGL(fa_bwd_dkv_kernel, dim3((a.S + 127) / 128, a.H, a.B), dim3(256), 0, s, p);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(fa_bwd_dq_kernel, dim3((a.T + 127) / 128, a.H, a.B), dim3(256), 0, s, p);
