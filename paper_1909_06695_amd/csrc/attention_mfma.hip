@@ -47,7 +47,7 @@ __device__ __forceinline__ int swza(int row) { return ((row & 3) << 1) | ((row >
 
 template <int N>
 __device__ __forceinline__ void fa_wait_vmcnt() {
-  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (0 << 8));   // also all LDS operations
 }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 t) { return *reinterpret_cast<bf16x8*>(&t); }
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(256) void fa_fwd_kernel(FaParams p) {
   for (int jb = 0; jb < nkb; ++jb) {
     if (jb + NSTAGE - 1 <= nkb) fa_wait_vmcnt<(NSTAGE - 2) * LPT>();
     else fa_wait_vmcnt<0>();
-    __syncthreads();
+    __builtin_amdgcn_s_barrier();   // unfenced: younger tiles' loads stay in flight
     if (jb + NSTAGE - 1 < nkb) issue(jb + NSTAGE - 1);
     const char* sK = lds + (jb % NSTAGE) * (2 * TILE_BYTES);
     const char* sV = sK + TILE_BYTES;
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(256) void fa_bwd_dkv_kernel(FaParams p) {
   for (int it = 0; it < nit; ++it) {
     if (it + NSTAGE - 1 <= nit) fa_wait_vmcnt<(NSTAGE - 2) * LPT>();
     else fa_wait_vmcnt<0>();
-    __syncthreads();
+    __builtin_amdgcn_s_barrier();   // unfenced: younger tiles' loads stay in flight
     if (it + NSTAGE - 1 < nit) issue(it + NSTAGE - 1);
     const int ib = ib0 + it;
     const char* sQ = lds + (it % NSTAGE) * DKV_STAGE;
@@ -389,7 +389,7 @@ __global__ __launch_bounds__(256) void fa_bwd_dq_kernel(FaParams p) {
   for (int jb = 0; jb < nkb; ++jb) {
     if (jb + NSTAGE - 1 <= nkb) fa_wait_vmcnt<(NSTAGE - 2) * LPT>();
     else fa_wait_vmcnt<0>();
-    __syncthreads();
+    __builtin_amdgcn_s_barrier();   // unfenced: younger tiles' loads stay in flight
     if (jb + NSTAGE - 1 < nkb) issue(jb + NSTAGE - 1);
     const char* sK = lds + (jb % NSTAGE) * (2 * TILE_BYTES);
     const char* sV = sK + TILE_BYTES;

@@ -208,11 +208,12 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
                 (g.epilogue == EPI_NONE || (aligned16(g.Z) && !(g.ldz & 7)));
     static const int forced = [] { const char* e = getenv("OURO_GEMM_TILE"); return e ? atoi(e) : -1; }();
     int cfg = forced;
-    if (cfg < 0) cfg = (g.K % 64) == 0 ? 10 : 0;
-    const bool dl = cfg >= 10 && (g.K % 64) == 0;
+    if (cfg < 0) cfg = (g.K % 64) == 0 ? 18 : 0;
+    const size_t bytesA = 2 * (size_t)(g.transA ? g.K : g.M) * g.lda, bytesB = 2 * (size_t)(g.transB ? g.N : g.K) * g.ldb;
+    const bool dl = cfg >= 10 && (g.K % 64) == 0 && bytesA < (1ull << 31) && bytesB < (1ull << 31);
     if (cfg >= 10 && !dl) cfg = 0;
-    const int BM = (cfg == 0 || (cfg >= 10 && cfg <= 12) || cfg >= 16) ? 128 : 256;
-    const int BN = (cfg == 2 || cfg == 3 || cfg == 15 || cfg == 17) ? 256 : 128;
+    const int BM = (cfg == 0 || (cfg >= 10 && cfg <= 12) || (cfg >= 16 && cfg <= 18)) ? 128 : 256;
+    const int BN = (cfg == 2 || cfg == 3 || cfg == 15 || cfg == 17 || cfg == 19) ? 256 : 128;
     int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     int splits = 1;
     if (g.accumulate && tiles < 384 && g.K >= 512) {

@@ -20,10 +20,12 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void gbl_void;
 
+// Wait until at most N vector-memory operations are outstanding and every LDS operation of
+// this wave has completed.
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   static_assert(N >= 0 && N < 64, "vmcnt range");
-  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (0 << 8));
 }
 
 // One operand's share of a K-tile.  ROWS = tile extent along m (or n); NW = waves per
@@ -101,25 +103,29 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dlds_kernel(GemmParams p) {
   const int kend = min(p.K, kbeg + p.kchunk);
   const int nk = (kend - kbeg) / BK;                        // launcher guarantees exact tiles
 
-  const bf16_t* ga[TileA::PER];
-  const bf16_t* gb[TileB::PER];
+  // per-load byte offsets from the operand base (32-bit: the launcher keeps operands under
+  // 2 GiB); the K-tile term is a uniform add at issue time
+  uint32_t oa[TileA::PER], ob[TileB::PER];
 #pragma unroll
   for (int i = 0; i < TileA::PER; ++i)
-    ga[i] = A + TileA::src_offset(wave + i * NW, lane, m0, p.M, p.lda) + (TA ? (size_t)kbeg * p.lda : (size_t)kbeg);
+    oa[i] = (uint32_t)(2 * (TileA::src_offset(wave + i * NW, lane, m0, p.M, p.lda) + (TA ? (size_t)kbeg * p.lda : (size_t)kbeg)));
 #pragma unroll
   for (int i = 0; i < TileB::PER; ++i)
-    gb[i] = B + TileB::src_offset(wave + i * NW, lane, n0, p.N, p.ldb) + (TB ? (size_t)kbeg : (size_t)kbeg * p.ldb);
-  const size_t stepA = TA ? (size_t)BK * p.lda : (size_t)BK;
-  const size_t stepB = TB ? (size_t)BK : (size_t)BK * p.ldb;
+    ob[i] = (uint32_t)(2 * (TileB::src_offset(wave + i * NW, lane, n0, p.N, p.ldb) + (TB ? (size_t)kbeg : (size_t)kbeg * p.ldb)));
+  const uint32_t stepA = 2u * (TA ? (uint32_t)BK * p.lda : (uint32_t)BK);
+  const uint32_t stepB = 2u * (TB ? (uint32_t)BK : (uint32_t)BK * p.ldb);
+  const char* Ab = reinterpret_cast<const char*>(A);
+  const char* Bb = reinterpret_cast<const char*>(B);
 
   auto issue = [&](int kt) __attribute__((always_inline)) {
     char* st = lds + (kt % S) * STAGE;
+    const uint32_t ka = (uint32_t)kt * stepA, kb = (uint32_t)kt * stepB;
 #pragma unroll
     for (int i = 0; i < TileA::PER; ++i)
-      __builtin_amdgcn_global_load_lds((gbl_void*)(ga[i] + kt * stepA), (lds_void*)(st + (wave + i * NW) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gbl_void*)(Ab + (oa[i] + ka)), (lds_void*)(st + (wave + i * NW) * 1024), 16, 0, 0);
 #pragma unroll
     for (int i = 0; i < TileB::PER; ++i)
-      __builtin_amdgcn_global_load_lds((gbl_void*)(gb[i] + kt * stepB),
+      __builtin_amdgcn_global_load_lds((gbl_void*)(Bb + (ob[i] + kb)),
                                        (lds_void*)(st + TileA::BYTES + (wave + i * NW) * 1024), 16, 0, 0);
   };
 
@@ -139,7 +145,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dlds_kernel(GemmParams p) {
     // tile kt has landed once at most the loads of the younger tiles are outstanding
     if (kt + S - 1 <= nk) wait_vmcnt<(S - 2) * LPT>();
     else wait_vmcnt<0>();
-    __syncthreads();                                        // tile kt visible; stage (kt-1)%S free
+    // plain hardware barrier: a fenced barrier would drain the younger tiles' loads too.
+    // Before it every wave has waited for its own share of tile kt and for its LDS reads of
+    // tile kt-1; after it tile kt is complete in LDS and stage (kt-1)%S may be refilled.
+    __builtin_amdgcn_s_barrier();
 #if !defined(OURO_ABLATE) || OURO_ABLATE != 1
     if (kt + S - 1 < nk) issue(kt + S - 1);
 #endif
@@ -148,20 +157,45 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dlds_kernel(GemmParams p) {
 #if defined(OURO_ABLATE) && OURO_ABLATE == 2
     if (p.alpha == 12345.f)
 #endif
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 af[TM], bfr[TN];
+    {
+      // fragments of substep ks+1 are fetched before the matrix instructions of substep ks
+      // are issued, so LDS latency hides behind the matrix pipe even with one wave per SIMD
+      bf16x8 af[2][TM], bfr[2][TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        af[i] = TA ? frag_col<BM>(sa, wm * (TM * 32) + i * 32, ks, lane) : frag_row(sa, wm * (TM * 32) + i * 32, ks, lane);
+        af[0][i] = TA ? frag_col<BM>(sa, wm * (TM * 32) + i * 32, 0, lane) : frag_row(sa, wm * (TM * 32) + i * 32, 0, lane);
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        bfr[j] = TB ? frag_row(sb, wn * (TN * 32) + j * 32, ks, lane) : frag_col<BN>(sb, wn * (TN * 32) + j * 32, ks, lane);
+        bfr[0][j] = TB ? frag_row(sb, wn * (TN * 32) + j * 32, 0, lane) : frag_col<BN>(sb, wn * (TN * 32) + j * 32, 0, lane);
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int ks = 0; ks < 4; ++ks) {
+        const int cur = ks & 1, nxt = cur ^ 1;
+        if (ks < 3) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          for (int i = 0; i < TM; ++i)
+            af[nxt][i] = TA ? frag_col<BM>(sa, wm * (TM * 32) + i * 32, ks + 1, lane)
+                            : frag_row(sa, wm * (TM * 32) + i * 32, ks + 1, lane);
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            bfr[nxt][j] = TB ? frag_row(sb, wn * (TN * 32) + j * 32, ks + 1, lane)
+                             : frag_col<BN>(sb, wn * (TN * 32) + j * 32, ks + 1, lane);
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+        if (ks < 3) {
+          // interleave: one LDS fragment read per group of matrix instructions
+          constexpr int NRD = (TA ? 2 : 1) * TM + (TB ? 1 : 2) * TN;
+          constexpr int PERG = (TM * TN + NRD - 1) / NRD;
+#pragma unroll
+          for (int g = 0; g < NRD; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, PERG, 0);
+          }
+        }
+      }
     }
   }
   __syncthreads();                                          // operand reads done: LDS reusable
@@ -209,6 +243,8 @@ hipError_t launch_gemm_dlds(hipStream_t s, GemmParams& p, int transA, int transB
     case 16: return launch_dlds_cfg<128, 128, 4, 2, 2>(s, p, transA, transB, splits);
     case 17: return launch_dlds_cfg<128, 256, 2, 4, 2>(s, p, transA, transB, splits);
     case 18: return launch_dlds_cfg<128, 128, 2, 4, 2>(s, p, transA, transB, splits);
+    case 19: return launch_dlds_cfg<256, 256, 2, 2, 2>(s, p, transA, transB, splits);
+    case 20: return launch_dlds_cfg<256, 128, 2, 2, 2>(s, p, transA, transB, splits);
     default: return hipErrorInvalidValue;
   }
 }
