@@ -142,7 +142,9 @@ struct ouro_model {
   float *lse_ce, *rowloss, *loss;
   int* flag;
   // backward scratch
-  char *dh0, *dh1, *ds2, *dz, *dy, *ds1, *da, *dqkv, *dcat, *dr_t;
+  char *dh0, *dh1, *dy, *da, *dcat, *dr_t;
+  // gradients that the weight-gradient GEMMs read on the side stream: two sets, by layer parity
+  char *ds2[2], *dz[2], *ds1[2], *dqkv[2];
   float *attn_scratch, *dr_f32, *dbg_f32;
   size_t dbg_floats;
   // iteration state
@@ -152,6 +154,15 @@ struct ouro_model {
   int mem_valid;                  // valid rows in every layer memory
   const int32_t* tok;
   const int32_t* tgt;
+  // Weight-gradient GEMMs and bias column sums only feed the gradient ring, so they run on
+  // a second stream beside the error-gradient chain (both default priority); events order
+  // them against the producers of their operands and against the reuse of those buffers.
+  hipStream_t side;
+  bool use_side;
+  hipEvent_t ev_ready[4];      // ds2 / dz / ds1 / dqkv of the current layer written (main)
+  hipEvent_t ev_side_done[2];  // side work that reads buffer set p finished
+  bool side_busy[2];
+  hipEvent_t ev_join;
   // optional per-launch HIP event timing: kind 0 = MFMA contraction kernel (work = flops),
   // kind 1 = delayed-update kernel (work = algorithmic bytes)
   int timing;
@@ -284,9 +295,11 @@ static size_t lay_out(ouro_model& m, char* base) {
   m.loss = (float*)P(256);
   m.flag = (int*)P(256);
   m.dh0 = P(N * d * es); m.dh1 = P(N * d * es);
-  m.ds2 = P(N * d * es); m.dz = P(N * F * es); m.dy = P(N * d * es);
-  m.ds1 = P(N * d * es); m.da = P(N * d * es);
-  m.dqkv = P(qkv_elems * es);
+  m.dy = P(N * d * es); m.da = P(N * d * es);
+  for (int p2 = 0; p2 < 2; ++p2) {
+    m.ds2[p2] = P(N * d * es); m.dz[p2] = P(N * F * es);
+    m.ds1[p2] = P(N * d * es); m.dqkv[p2] = P(qkv_elems * es);
+  }
   m.dcat = c.rel_pos ? P(B * S * d * es) : nullptr;
   m.dr_t = c.rel_pos ? P(S * d * es) : nullptr;
   m.dr_f32 = c.rel_pos ? (float*)P(S * d * 4) : nullptr;
@@ -346,6 +359,17 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
   m->tok = m->tgt = nullptr;
   m->timing = 0;
   for (int i = 0; i < 2; ++i) { m->ev_used[i] = 0; m->timed_work[i] = 0; m->timed_launches[i] = 0; }
+  m->side = nullptr; m->use_side = false; m->ev_join = nullptr;
+  for (int i = 0; i < 4; ++i) m->ev_ready[i] = nullptr;
+  for (int i = 0; i < 2; ++i) { m->ev_side_done[i] = nullptr; m->side_busy[i] = false; }
+  {
+    hipError_t es_ = hipStreamCreateWithFlags(&m->side, hipStreamNonBlocking);
+    for (int i = 0; i < 4 && es_ == hipSuccess; ++i) es_ = hipEventCreateWithFlags(&m->ev_ready[i], hipEventDisableTiming);
+    for (int i = 0; i < 2 && es_ == hipSuccess; ++i) es_ = hipEventCreateWithFlags(&m->ev_side_done[i], hipEventDisableTiming);
+    if (es_ == hipSuccess) es_ = hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming);
+    if (es_ != hipSuccess) { delete m; return fail(OURO_E_HIP, "side stream / events: %s", hipGetErrorString(es_)); }
+    m->use_side = true;
+  }
   // zero optimizer state, rings, everything else too (one fill over the arena)
   hipError_t e = launch_fill_zero(m->stream, m->arena, need);
   if (e != hipSuccess) { delete m; return fail(OURO_E_HIP, "arena clear: %s", hipGetErrorString(e)); }
@@ -367,6 +391,10 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
 extern "C" int ouro_destroy_model(ouro_model* m) {
   if (!m) return OURO_OK;
   (void)hipStreamSynchronize(m->stream);
+  if (m->side) { (void)hipStreamSynchronize(m->side); (void)hipStreamDestroy(m->side); }
+  for (int i = 0; i < 4; ++i) if (m->ev_ready[i]) (void)hipEventDestroy(m->ev_ready[i]);
+  for (int i = 0; i < 2; ++i) if (m->ev_side_done[i]) (void)hipEventDestroy(m->ev_side_done[i]);
+  if (m->ev_join) (void)hipEventDestroy(m->ev_join);
   for (int i = 0; i < 2; ++i)
     for (hipEvent_t e : m->ev[i]) (void)hipEventDestroy(e);
   delete m;
@@ -399,30 +427,31 @@ extern "C" int ouro_get_params(ouro_model* m, int group, float* dst, int64_t n, 
 extern "C" int64_t ouro_current_step(const ouro_model* m) { return m ? m->t : -1; }
 
 // --------------------------------------------------------------------- launch helpers
-static int timing_begin(ouro_model* m, int kind) {
+static int timing_begin(ouro_model* m, int kind, hipStream_t st) {
   while (m->ev[kind].size() < m->ev_used[kind] + 2) {
     hipEvent_t e;
     HIPCHK(hipEventCreate(&e));
     m->ev[kind].push_back(e);
   }
-  HIPCHK(hipEventRecord(m->ev[kind][m->ev_used[kind]], m->stream));
+  HIPCHK(hipEventRecord(m->ev[kind][m->ev_used[kind]], st));
   return OURO_OK;
 }
-static int timing_end(ouro_model* m, int kind, double work) {
-  HIPCHK(hipEventRecord(m->ev[kind][m->ev_used[kind] + 1], m->stream));
+static int timing_end(ouro_model* m, int kind, double work, hipStream_t st) {
+  HIPCHK(hipEventRecord(m->ev[kind][m->ev_used[kind] + 1], st));
   m->ev_used[kind] += 2;
   m->timed_work[kind] += work;
   m->timed_launches[kind] += 1;
   return OURO_OK;
 }
 
-static int run_gemm(ouro_model* m, GemmDesc g) {
+static int run_gemm_on(ouro_model* m, GemmDesc g, hipStream_t st) {
   const bool timed = m->timing && gemm_uses_mfma(m->cfg.dtype, g);
-  if (timed) { int rc = timing_begin(m, 0); if (rc) return rc; }
-  HIPCHK(launch_gemm(m->stream, m->cfg.dtype, g, 0));
-  if (timed) return timing_end(m, 0, 2.0 * g.M * g.N * g.K);
+  if (timed) { int rc = timing_begin(m, 0, st); if (rc) return rc; }
+  HIPCHK(launch_gemm(st, m->cfg.dtype, g, 0));
+  if (timed) return timing_end(m, 0, 2.0 * g.M * g.N * g.K, st);
   return OURO_OK;
 }
+static int run_gemm(ouro_model* m, GemmDesc g) { return run_gemm_on(m, g, m->stream); }
 
 static GemmDesc gd(const void* A, int lda, int tA, const void* B, int ldb, int tB, void* C, int ldc, int M, int N, int K) {
   GemmDesc g;
@@ -536,41 +565,56 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   LayerBuf& b = m->L[l];
   const int Mv = m->mem_valid, S = Mv + T;
   hipStream_t st = m->stream;
+  const int ps = l & 1;                               // buffer set of this layer
+  const bool side = m->use_side && !c.rel_pos;
+  hipStream_t sw = side ? m->side : st;               // stream of the weight-gradient work
+  char* ds2 = m->ds2[ps]; char* dz = m->dz[ps]; char* ds1 = m->ds1[ps]; char* dqkv = m->dqkv[ps];
+  // the side stream may still be reading this buffer set (layer l+2 of this module)
+  if (side && m->side_busy[ps]) { HIPCHK(hipStreamWaitEvent(st, m->ev_side_done[ps], 0)); m->side_busy[ps] = false; }
+  auto ready = [&](int i) -> int {                    // operand i written on main; side may start
+    if (!side) return OURO_OK;
+    HIPCHK(hipEventRecord(m->ev_ready[i], st));
+    HIPCHK(hipStreamWaitEvent(sw, m->ev_ready[i], 0));
+    return OURO_OK;
+  };
   // LN2
-  HIPCHK(launch_layernorm_bwd(st, c.dtype, dh, b.s2, m->wF(l, o.ln2_g), b.mean2, b.rstd2, m->ds2, gslot + o.ln2_g, gslot + o.ln2_b, N, d));
+  HIPCHK(launch_layernorm_bwd(st, c.dtype, dh, b.s2, m->wF(l, o.ln2_g), b.mean2, b.rstd2, ds2, gslot + o.ln2_g, gslot + o.ln2_b, N, d));
+  RUN(ready(0));
   // FFN2
   {
-    GemmDesc g = gd(b.uact, F, 1, m->ds2, d, 0, gslot + o.W_2, d, F, d, N);
+    GemmDesc g = gd(b.uact, F, 1, ds2, d, 0, gslot + o.W_2, d, F, d, N);
     g.out_fp32 = 1; g.accumulate = 1;
-    RUN(run_gemm(m, g));
+    RUN(run_gemm_on(m, g, sw));
   }
-  HIPCHK(launch_colsum(st, c.dtype, m->ds2, d, gslot + o.b_2, N, d));
+  HIPCHK(launch_colsum(sw, c.dtype, ds2, d, gslot + o.b_2, N, d));
   {
-    GemmDesc g = gd(m->ds2, d, 0, m->wT(l, o.W_2), d, 1, m->dz, F, N, F, d);
+    GemmDesc g = gd(ds2, d, 0, m->wT(l, o.W_2), d, 1, dz, F, N, F, d);
     g.epilogue = EPI_GELUGRAD; g.Z = b.z; g.ldz = F;
     RUN(run_gemm(m, g));
   }
+  RUN(ready(1));
   // FFN1
   {
-    GemmDesc g = gd(b.y, d, 1, m->dz, F, 0, gslot + o.W_1, F, d, F, N);
+    GemmDesc g = gd(b.y, d, 1, dz, F, 0, gslot + o.W_1, F, d, F, N);
     g.out_fp32 = 1; g.accumulate = 1;
-    RUN(run_gemm(m, g));
+    RUN(run_gemm_on(m, g, sw));
   }
-  HIPCHK(launch_colsum(st, c.dtype, m->dz, F, gslot + o.b_1, N, F));
+  HIPCHK(launch_colsum(sw, c.dtype, dz, F, gslot + o.b_1, N, F));
   {
-    GemmDesc g = gd(m->dz, F, 0, m->wT(l, o.W_1), F, 1, m->dy, d, N, d, F);
-    g.residual = m->ds2; g.ldr = d;
+    GemmDesc g = gd(dz, F, 0, m->wT(l, o.W_1), F, 1, m->dy, d, N, d, F);
+    g.residual = ds2; g.ldr = d;
     RUN(run_gemm(m, g));
   }
   // LN1
-  HIPCHK(launch_layernorm_bwd(st, c.dtype, m->dy, b.s1, m->wF(l, o.ln1_g), b.mean1, b.rstd1, m->ds1, gslot + o.ln1_g, gslot + o.ln1_b, N, d));
+  HIPCHK(launch_layernorm_bwd(st, c.dtype, m->dy, b.s1, m->wF(l, o.ln1_g), b.mean1, b.rstd1, ds1, gslot + o.ln1_g, gslot + o.ln1_b, N, d));
+  RUN(ready(2));
   // output projection
   {
-    GemmDesc g = gd(b.a, d, 1, m->ds1, d, 0, gslot + o.W_o, d, d, d, N);
+    GemmDesc g = gd(b.a, d, 1, ds1, d, 0, gslot + o.W_o, d, d, d, N);
     g.out_fp32 = 1; g.accumulate = 1;
-    RUN(run_gemm(m, g));
+    RUN(run_gemm_on(m, g, sw));
   }
-  RUN(run_gemm(m, gd(m->ds1, d, 0, m->wT(l, o.W_o), d, 1, m->da, d, N, d, d)));
+  RUN(run_gemm(m, gd(ds1, d, 0, m->wT(l, o.W_o), d, 1, m->da, d, N, d, d)));
   // attention
   AttnDesc a;
   memset(&a, 0, sizeof a);
@@ -581,26 +625,27 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     a.q = b.qkv; a.ldq = 3 * d;
     a.k = b.qkv + (size_t)d * es; a.ldk = 3 * d;
     a.v = b.qkv + (size_t)2 * d * es; a.ldv = 3 * d;
-    a.dq = m->dqkv; a.lddq = 3 * d;
-    a.dk = m->dqkv + (size_t)d * es; a.lddk = 3 * d;
-    a.dv = m->dqkv + (size_t)2 * d * es; a.lddv = 3 * d;
+    a.dq = dqkv; a.lddq = 3 * d;
+    a.dk = dqkv + (size_t)d * es; a.lddk = 3 * d;
+    a.dv = dqkv + (size_t)2 * d * es; a.lddv = 3 * d;
     HIPCHK(launch_attn_bwd(st, c.dtype, a, 0));
+    RUN(ready(3));
     {
-      GemmDesc g = gd(b.x, d, 1, m->dqkv, 3 * d, 0, gslot + o.W_qkv, 3 * d, d, 3 * d, N);
+      GemmDesc g = gd(b.x, d, 1, dqkv, 3 * d, 0, gslot + o.W_qkv, 3 * d, d, 3 * d, N);
       g.out_fp32 = 1; g.accumulate = 1;
-      RUN(run_gemm(m, g));
+      RUN(run_gemm_on(m, g, sw));
     }
     {
-      GemmDesc g = gd(m->dqkv, 3 * d, 0, m->wT(l, o.W_qkv), 3 * d, 1, dx, d, N, d, 3 * d);
-      g.residual = m->ds1; g.ldr = d;
+      GemmDesc g = gd(dqkv, 3 * d, 0, m->wT(l, o.W_qkv), 3 * d, 1, dx, d, N, d, 3 * d);
+      g.residual = ds1; g.ldr = d;
       RUN(run_gemm(m, g));
     }
   } else {
     const char* cat = Mv > 0 ? b.cat : b.x;
     char* q = b.qkv;
     char* kv = b.qkv + (size_t)N * d * es;
-    char* dq = m->dqkv;
-    char* dkv = m->dqkv + (size_t)N * d * es;
+    char* dq = dqkv;
+    char* dkv = dqkv + (size_t)N * d * es;
     a.q = q; a.ldq = d; a.k = kv; a.ldk = 2 * d; a.v = kv + (size_t)d * es; a.ldv = 2 * d;
     a.rel = 1; a.u = m->wT(l, o.u); a.vb = m->wT(l, o.v); a.r = b.r; a.ldr = d;
     a.dq = dq; a.lddq = d; a.dk = dkv; a.lddk = 2 * d; a.dv = dkv + (size_t)d * es; a.lddv = 2 * d;
@@ -627,7 +672,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     }
     {
       GemmDesc g = gd(dq, d, 0, m->wT(l, o.W_qkv), 3 * d, 1, dx, d, N, d, d);
-      g.residual = m->ds1; g.ldr = d;
+      g.residual = ds1; g.ldr = d;
       RUN(run_gemm(m, g));
     }
     // the memory rows are constants: only the current rows of d[mem ; x] reach dx
@@ -640,6 +685,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
       HIPCHK(hipGetLastError());
     }
   }
+  if (side) { HIPCHK(hipEventRecord(m->ev_side_done[ps], sw)); m->side_busy[ps] = true; }
   return OURO_OK;
 }
 
@@ -661,7 +707,13 @@ extern "C" int ouro_module_backward(ouro_model* m, int k) {
     float* dvo = m->slot_ptr(K + 1, 0);
     GemmDesc g = gd(m->G, m->ldv, 1, m->hL, d, 0, dvo, d, V, d, N);
     g.out_fp32 = 1;
-    RUN(run_gemm(m, g));
+    if (m->use_side) {        // independent of the error-gradient chain: beside dh_L = G V
+      HIPCHK(hipEventRecord(m->ev_ready[0], m->stream));
+      HIPCHK(hipStreamWaitEvent(m->side, m->ev_ready[0], 0));
+      RUN(run_gemm_on(m, g, m->side));
+    } else {
+      RUN(run_gemm(m, g));
+    }
     m->tags[K + 1][0] = m->t;
     RUN(run_gemm(m, gd(m->G, m->ldv, 0, m->vT(), d, 0, (lastl % 2) ? m->dh1 : m->dh0, d, N, d, V)));
   }
@@ -670,6 +722,11 @@ extern "C" int ouro_module_backward(ouro_model* m, int k) {
     char* dh = (l % 2) ? m->dh1 : m->dh0;
     char* dx = (l % 2) ? m->dh0 : m->dh1;
     RUN(layer_backward(m, l, dh, dx, gslot));
+  }
+  if (m->use_side) {          // the module's gradient is complete once the side work has joined
+    HIPCHK(hipEventRecord(m->ev_join, m->side));
+    HIPCHK(hipStreamWaitEvent(m->stream, m->ev_join, 0));
+    m->side_busy[0] = m->side_busy[1] = false;
   }
   m->tags[k][slot] = m->t;
   if (k == 1) {
@@ -742,12 +799,12 @@ extern "C" int ouro_delayed_update(ouro_model* m, int group, float lr) {
     }
   }
   const bool timed = m->timing && u.g0;
-  if (timed) RUN(timing_begin(m, 1));
+  if (timed) RUN(timing_begin(m, 1, m->stream));
   HIPCHK(launch_update(m->stream, u));
   if (timed) {
     // algorithmic bytes per element: gradient(s) 4 each, w read+write 8, Adam m,v read+write 16, bf16 copy 2
     double per = 4.0 * ((u.g0 ? 1 : 0) + (u.g1 ? 1 : 0)) + 8.0 + (u.adam ? 16.0 : 0.0) + (u.shadow ? 2.0 : 0.0);
-    RUN(timing_end(m, 1, per * (double)u.n));
+    RUN(timing_end(m, 1, per * (double)u.n, m->stream));
   }
   m->upd_mask |= 1ull << group;
   if (m->upd_mask == (1ull << (K + 1)) - 1) return close_iteration(m);
