@@ -208,12 +208,17 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
                 (g.epilogue == EPI_NONE || (aligned16(g.Z) && !(g.ldz & 7)));
     static const int forced = [] { const char* e = getenv("OURO_GEMM_TILE"); return e ? atoi(e) : -1; }();
     int cfg = forced;
-    if (cfg < 0) cfg = (g.K % 64) == 0 ? 18 : 0;
+    if (cfg < 0) {
+      // 128x128 tiles (8 waves) when they fill the chip at least twice over; otherwise, and for
+      // the split-K weight gradients, 128x64 tiles put more workgroups on every compute unit
+      const int t128 = ((g.M + 127) / 128) * ((g.N + 127) / 128);
+      cfg = (g.K % 64) != 0 ? 0 : (g.accumulate || t128 <= 384) ? 22 : 18;
+    }
     const size_t bytesA = 2 * (size_t)(g.transA ? g.K : g.M) * g.lda, bytesB = 2 * (size_t)(g.transB ? g.N : g.K) * g.ldb;
     const bool dl = cfg >= 10 && (g.K % 64) == 0 && bytesA < (1ull << 31) && bytesB < (1ull << 31);
     if (cfg >= 10 && !dl) cfg = 0;
-    const int BM = (cfg == 0 || (cfg >= 10 && cfg <= 12) || (cfg >= 16 && cfg <= 18)) ? 128 : 256;
-    const int BN = (cfg == 2 || cfg == 3 || cfg == 15 || cfg == 17 || cfg == 19) ? 256 : 128;
+    const int BM = (cfg == 21 || cfg == 23) ? 64 : (cfg == 0 || (cfg >= 10 && cfg <= 12) || (cfg >= 16 && cfg <= 18) || cfg == 22) ? 128 : 256;
+    const int BN = cfg == 22 ? 64 : (cfg == 2 || cfg == 3 || cfg == 15 || cfg == 17 || cfg == 19) ? 256 : 128;
     int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     int splits = 1;
     if (g.accumulate && tiles < 384 && g.K >= 512) {

@@ -245,6 +245,9 @@ hipError_t launch_gemm_dlds(hipStream_t s, GemmParams& p, int transA, int transB
     case 18: return launch_dlds_cfg<128, 128, 2, 4, 2>(s, p, transA, transB, splits);
     case 19: return launch_dlds_cfg<256, 256, 2, 2, 2>(s, p, transA, transB, splits);
     case 20: return launch_dlds_cfg<256, 128, 2, 2, 2>(s, p, transA, transB, splits);
+    case 21: return launch_dlds_cfg<64, 128, 1, 4, 2>(s, p, transA, transB, splits);
+    case 22: return launch_dlds_cfg<128, 64, 4, 1, 2>(s, p, transA, transB, splits);
+    case 23: return launch_dlds_cfg<64, 128, 2, 4, 3>(s, p, transA, transB, splits);
     default: return hipErrorInvalidValue;
   }
 }

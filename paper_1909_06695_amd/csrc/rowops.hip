@@ -210,37 +210,56 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* __restrict__
       ab[i][e] = 0.f;
     }
   }
-  for (int row = blockIdx.x * 4 + wave; row < rows; row += gridDim.x * 4) {
-    const float mu = mean[row], rs = rstd[row];
-    float xh[MAXI][N], t[MAXI][N];
-    float s1 = 0.f, s2 = 0.f;
+  // two rows per trip: their loads are issued together so one row's latency hides the other's
+  const int rstep = gridDim.x * 4;
+  for (int row0 = blockIdx.x * 4 + wave; row0 < rows; row0 += 2 * rstep) {
+    float xh[2][MAXI][N], t[2][MAXI][N], mu[2], rs[2];
 #pragma unroll
-    for (int i = 0; i < MAXI; ++i) {
-      int vi = lane + 64 * i;
-      if (vi < nvec) {
-        load_pack<T>(x + (size_t)row * d + vi * N, xh[i]);
-        load_pack<T>(dy + (size_t)row * d + vi * N, t[i]);
+    for (int u = 0; u < 2; ++u) {
+      const int row = row0 + u * rstep;
+      if (row < rows) {
+        mu[u] = mean[row]; rs[u] = rstd[row];
 #pragma unroll
-        for (int e = 0; e < N; ++e) {
-          xh[i][e] = (xh[i][e] - mu) * rs;
-          ag[i][e] += t[i][e] * xh[i][e];
-          ab[i][e] += t[i][e];
-          t[i][e] *= gl[i][e];
-          s1 += t[i][e];
-          s2 += t[i][e] * xh[i][e];
+        for (int i = 0; i < MAXI; ++i) {
+          int vi = lane + 64 * i;
+          if (vi < nvec) {
+            load_pack<T>(x + (size_t)row * d + vi * N, xh[u][i]);
+            load_pack<T>(dy + (size_t)row * d + vi * N, t[u][i]);
+          }
         }
       }
     }
-    s1 = wave_sum(s1) / d;
-    s2 = wave_sum(s2) / d;
 #pragma unroll
-    for (int i = 0; i < MAXI; ++i) {
-      int vi = lane + 64 * i;
-      if (vi < nvec) {
-        float out[N];
+    for (int u = 0; u < 2; ++u) {
+      const int row = row0 + u * rstep;
+      if (row >= rows) continue;
+      float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-        for (int e = 0; e < N; ++e) out[e] = rs * (t[i][e] - s1 - xh[i][e] * s2);
-        store_pack<T>(dx + (size_t)row * d + vi * N, out);
+      for (int i = 0; i < MAXI; ++i) {
+        int vi = lane + 64 * i;
+        if (vi < nvec) {
+#pragma unroll
+          for (int e = 0; e < N; ++e) {
+            xh[u][i][e] = (xh[u][i][e] - mu[u]) * rs[u];
+            ag[i][e] += t[u][i][e] * xh[u][i][e];
+            ab[i][e] += t[u][i][e];
+            t[u][i][e] *= gl[i][e];
+            s1 += t[u][i][e];
+            s2 += t[u][i][e] * xh[u][i][e];
+          }
+        }
+      }
+      s1 = wave_sum(s1) / d;
+      s2 = wave_sum(s2) / d;
+#pragma unroll
+      for (int i = 0; i < MAXI; ++i) {
+        int vi = lane + 64 * i;
+        if (vi < nvec) {
+          float out[N];
+#pragma unroll
+          for (int e = 0; e < N; ++e) out[e] = rs[u] * (t[u][i][e] - s1 - xh[u][i][e] * s2);
+          store_pack<T>(dx + (size_t)row * d + vi * N, out);
+        }
       }
     }
   }
@@ -299,7 +318,7 @@ hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const 
   dim3 g2((d + 63) / 64, (rows + rpb - 1) / rpb);
   const int pack = dtype == 1 ? 8 : 4;
   if (d % pack == 0 && d / pack <= 256 && ptr16(dy) && ptr16(x) && ptr16(dx)) {
-    dim3 gf(std::min((rows + 3) / 4, 256));
+    dim3 gf(std::min((rows + 3) / 4, 512));
     size_t smem = 4 * (size_t)d * sizeof(float);
     const int npl = (d / pack + 63) / 64;      // packs per lane
 #define OURO_LNB(T_, MI_) hipLaunchKernelGGL((ln_bwd_fused_kernel<T_, MI_>), gf, block, smem, s, (const T_*)dy, (const T_*)x, g, mean, rstd, (T_*)dx, dg, db, rows, d)
@@ -570,23 +589,38 @@ __global__ __launch_bounds__(256) void update_kernel(UpdParams p) {
   const size_t n4 = p.n / 4;
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (size_t j = i; j < n4; j += stride) {
-    float4 w = reinterpret_cast<float4*>(p.w)[j];
-    float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (p.g0) { float4 a = reinterpret_cast<const float4*>(p.g0)[j]; g.x = p.s0 * a.x; g.y = p.s0 * a.y; g.z = p.s0 * a.z; g.w = p.s0 * a.w; }
-    if (p.g1) { float4 a = reinterpret_cast<const float4*>(p.g1)[j]; g.x += p.s1 * a.x; g.y += p.s1 * a.y; g.z += p.s1 * a.z; g.w += p.s1 * a.w; }
-    float4 m = make_float4(0.f, 0.f, 0.f, 0.f), v = m;
-    if (ADAM) { m = reinterpret_cast<float4*>(p.m)[j]; v = reinterpret_cast<float4*>(p.v)[j]; }
-    w.x = upd_one<ADAM>(w.x, g.x, m.x, v.x, p);
-    w.y = upd_one<ADAM>(w.y, g.y, m.y, v.y, p);
-    w.z = upd_one<ADAM>(w.z, g.z, m.z, v.z, p);
-    w.w = upd_one<ADAM>(w.w, g.w, m.w, v.w, p);
-    reinterpret_cast<float4*>(p.w)[j] = w;
-    if (ADAM) { reinterpret_cast<float4*>(p.m)[j] = m; reinterpret_cast<float4*>(p.v)[j] = v; }
-    if (p.shadow) {
-      union { bf16_t h[4]; uint2 u; } cv;
-      cv.h[0] = (bf16_t)w.x; cv.h[1] = (bf16_t)w.y; cv.h[2] = (bf16_t)w.z; cv.h[3] = (bf16_t)w.w;
-      reinterpret_cast<uint2*>(p.shadow)[j] = cv.u;
+  // two 16-byte packs per trip and stream: all loads are issued before the arithmetic
+  for (size_t j0 = i; j0 < n4; j0 += 2 * stride) {
+    float4 w[2], g[2], m[2], v[2];
+    bool on[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const size_t j = j0 + u * stride;
+      on[u] = j < n4;
+      g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      m[u] = g[u]; v[u] = g[u]; w[u] = g[u];
+      if (on[u]) {
+        w[u] = reinterpret_cast<float4*>(p.w)[j];
+        if (p.g0) { float4 a = reinterpret_cast<const float4*>(p.g0)[j]; g[u].x = p.s0 * a.x; g[u].y = p.s0 * a.y; g[u].z = p.s0 * a.z; g[u].w = p.s0 * a.w; }
+        if (p.g1) { float4 a = reinterpret_cast<const float4*>(p.g1)[j]; g[u].x += p.s1 * a.x; g[u].y += p.s1 * a.y; g[u].z += p.s1 * a.z; g[u].w += p.s1 * a.w; }
+        if (ADAM) { m[u] = reinterpret_cast<float4*>(p.m)[j]; v[u] = reinterpret_cast<float4*>(p.v)[j]; }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      if (!on[u]) continue;
+      const size_t j = j0 + u * stride;
+      w[u].x = upd_one<ADAM>(w[u].x, g[u].x, m[u].x, v[u].x, p);
+      w[u].y = upd_one<ADAM>(w[u].y, g[u].y, m[u].y, v[u].y, p);
+      w[u].z = upd_one<ADAM>(w[u].z, g[u].z, m[u].z, v[u].z, p);
+      w[u].w = upd_one<ADAM>(w[u].w, g[u].w, m[u].w, v[u].w, p);
+      reinterpret_cast<float4*>(p.w)[j] = w[u];
+      if (ADAM) { reinterpret_cast<float4*>(p.m)[j] = m[u]; reinterpret_cast<float4*>(p.v)[j] = v[u]; }
+      if (p.shadow) {
+        union { bf16_t h[4]; uint2 q; } cv;
+        cv.h[0] = (bf16_t)w[u].x; cv.h[1] = (bf16_t)w[u].y; cv.h[2] = (bf16_t)w[u].z; cv.h[3] = (bf16_t)w[u].w;
+        reinterpret_cast<uint2*>(p.shadow)[j] = cv.q;
+      }
     }
   }
   for (size_t j = n4 * 4 + i; j < p.n; j += stride) {
