@@ -47,6 +47,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batch", type=int, default=16, help="streams in the CPU oracle sample")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--serial", action="store_true",
+                    help="run every kernel on one stream in the timed steps too (the mode the roofline pass and "
+                         "the committed kernel traces use; the default overlaps independent kernels on extra streams)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the K modules back to back on ONE GPU; --gpus N with N > 1 is not "
@@ -73,6 +76,8 @@ def main():
     dtgt = torch.from_numpy(tgt).cuda()
     lr = c["lr"]
 
+    if args.serial:
+        m.set_overlap(False)
     warm = max(args.warmup, K + 2)                           # rings full: every update uses a real gradient
     loss = None
     for i in range(warm):
@@ -93,7 +98,9 @@ def main():
     roofline = None
     update = None
     if not args.no_kernel_timing:
-        # second pass of the same steps with per-launch HIP events on the library's stream
+        # second pass of the same steps with per-launch HIP events on the library's stream; one
+        # stream, so that each bracket (like a profiler's kernel duration) holds that launch alone
+        m.set_overlap(False)
         m.timing_enable(True)
         for i in range(args.steps):
             j = (warm + args.steps + i) % distinct
@@ -105,7 +112,8 @@ def main():
             ach = gfl / (gms * 1e-3) / 1e12
             roofline = {"bound": "mfma", "kernel": "gemm_dlds_kernel (bf16 MFMA contraction, all launches)", "achieved": round(ach, 2),
                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                        "traffic": None, "launches_per_step": gn // args.steps,
+                        "traffic": None, "timed": "second pass, one stream, HIP events per launch",
+                        "launches_per_step": gn // args.steps,
                         "avg_launch_us": round(gms * 1e3 / gn, 2),
                         "flops_per_launch_avg": gfl / gn, "kernel_ms_per_step": round(gms / args.steps, 3)}
         if un:
@@ -145,6 +153,7 @@ def main():
                    "tokens_per_step": tokens, "modules": K},
         "mfu_bf16": round(F / (ms_per_step * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4),
         "step_tflop": round(F / 1e12, 3),
+        "streams": "serial" if args.serial else "overlapped",
         "loss_first_timed": loss, "loss_last": loss_end,
         "roofline": roofline, "update_kernel": update, "cpu_baseline": cpu,
     }

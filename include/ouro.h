@@ -164,6 +164,13 @@ int ouro_debug_get_hidden(ouro_model* m, int layer, float* host_dst, int64_t n);
  * timing_read synchronises the stream, returns the totals since the last read of that
  * kind and resets them. */
 int ouro_debug_timing_enable(ouro_model* m, int on);
+/* Stream overlap switch. on = 1 (default): weight-gradient contractions run on a second
+ * stream beside the error-gradient chain and ouro_step enqueues each module's update behind
+ * its backward pass on a third. on = 0: every kernel runs on the model's stream in program
+ * order, so a HIP-event bracket or a profiler's kernel duration measures that kernel alone.
+ * The results are the same in both modes up to the order of atomic float additions. Call it
+ * between iterations; it drains the extra streams. */
+int ouro_debug_set_overlap(ouro_model* m, int on);
 int ouro_debug_timing_read(ouro_model* m, int kind, double* ms, int64_t* launches, double* work);
 
 #ifdef __cplusplus

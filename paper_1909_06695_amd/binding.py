@@ -70,6 +70,7 @@ def lib():
         "ouro_get_mems": (i32, [vp, i32, vp, P(i64)]),
         "ouro_debug_get_hidden": (i32, [vp, i32, vp, i64]),
         "ouro_debug_timing_enable": (i32, [vp, i32]),
+        "ouro_debug_set_overlap": (i32, [vp, i32]),
         "ouro_debug_timing_read": (i32, [vp, i32, P(C.c_double), P(i64), P(C.c_double)]),
         # single-kernel entry points
         "ouro_op_gemm": (i32, [vp, i32, i32, i32, i32, i32, i32, f32, vp, i32, vp, i32, vp, i32, i32, i32, vp, vp,
@@ -257,6 +258,9 @@ class Model:
 
     def timing_enable(self, on):
         check(self.L.ouro_debug_timing_enable(self.h, int(on)))
+
+    def set_overlap(self, on):
+        check(self.L.ouro_debug_set_overlap(self.h, int(on)))
 
     def timing_read(self, kind):
         """(ms, launches, work): kind 0 = MFMA contraction kernel (flops), 1 = update kernel (bytes)."""

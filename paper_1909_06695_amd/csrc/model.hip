@@ -163,6 +163,11 @@ struct ouro_model {
   hipEvent_t ev_side_done[2];  // side work that reads buffer set p finished
   bool side_busy[2];
   hipEvent_t ev_join;
+  // A third stream carries (inside ouro_step) the update of a module as soon as its backward
+  // pass is done, beside the backward of the modules below.
+  hipStream_t aux;
+  hipEvent_t ev_bwd_done, ev_upd_done;
+  bool upd_pending;            // updates enqueued on aux that main has not waited for yet
   // optional per-launch HIP event timing: kind 0 = MFMA contraction kernel (work = flops),
   // kind 1 = delayed-update kernel (work = algorithmic bytes)
   int timing;
@@ -360,6 +365,7 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
   m->timing = 0;
   for (int i = 0; i < 2; ++i) { m->ev_used[i] = 0; m->timed_work[i] = 0; m->timed_launches[i] = 0; }
   m->side = nullptr; m->use_side = false; m->ev_join = nullptr;
+  m->aux = nullptr; m->ev_bwd_done = m->ev_upd_done = nullptr; m->upd_pending = false;
   for (int i = 0; i < 4; ++i) m->ev_ready[i] = nullptr;
   for (int i = 0; i < 2; ++i) { m->ev_side_done[i] = nullptr; m->side_busy[i] = false; }
   {
@@ -367,6 +373,9 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
     for (int i = 0; i < 4 && es_ == hipSuccess; ++i) es_ = hipEventCreateWithFlags(&m->ev_ready[i], hipEventDisableTiming);
     for (int i = 0; i < 2 && es_ == hipSuccess; ++i) es_ = hipEventCreateWithFlags(&m->ev_side_done[i], hipEventDisableTiming);
     if (es_ == hipSuccess) es_ = hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming);
+    if (es_ == hipSuccess) es_ = hipStreamCreateWithFlags(&m->aux, hipStreamNonBlocking);
+    for (hipEvent_t* pe : {&m->ev_bwd_done, &m->ev_upd_done})
+      if (es_ == hipSuccess) es_ = hipEventCreateWithFlags(pe, hipEventDisableTiming);
     if (es_ != hipSuccess) { delete m; return fail(OURO_E_HIP, "side stream / events: %s", hipGetErrorString(es_)); }
     m->use_side = true;
   }
@@ -395,6 +404,8 @@ extern "C" int ouro_destroy_model(ouro_model* m) {
   for (int i = 0; i < 4; ++i) if (m->ev_ready[i]) (void)hipEventDestroy(m->ev_ready[i]);
   for (int i = 0; i < 2; ++i) if (m->ev_side_done[i]) (void)hipEventDestroy(m->ev_side_done[i]);
   if (m->ev_join) (void)hipEventDestroy(m->ev_join);
+  if (m->aux) { (void)hipStreamSynchronize(m->aux); (void)hipStreamDestroy(m->aux); }
+  for (hipEvent_t e : {m->ev_bwd_done, m->ev_upd_done}) if (e) (void)hipEventDestroy(e);
   for (int i = 0; i < 2; ++i)
     for (hipEvent_t e : m->ev[i]) (void)hipEventDestroy(e);
   delete m;
@@ -761,13 +772,10 @@ static int close_iteration(ouro_model* m) {
   return OURO_OK;
 }
 
-extern "C" int ouro_delayed_update(ouro_model* m, int group, float lr) {
-  if (!m) return fail(OURO_E_ARG, "model is null");
+// One optimizer step of a parameter group with the gradient Eq. 8 / Eq. 9 select, on stream st.
+static int update_group(ouro_model* m, int group, float lr, hipStream_t st) {
   const ouro_config& c = m->cfg;
   const int K = c.n_module;
-  if (group < 0 || group > K) return fail(OURO_E_ARG, "delayed_update: group=%d outside 0..%d", group, K);
-  if (m->fwd_next != K + 1 || m->bwd_next != 0) return fail(OURO_E_SEQUENCE, "delayed_update before backward of module 1");
-  if (m->upd_mask & (1ull << group)) return fail(OURO_E_SEQUENCE, "delayed_update(%d) twice in one iteration", group);
   UpdateDesc u;
   memset(&u, 0, sizeof u);
   u.w = m->master[group]; u.m = m->adam_m[group]; u.v = m->adam_v[group]; u.shadow = m->shadow[group];
@@ -799,16 +807,32 @@ extern "C" int ouro_delayed_update(ouro_model* m, int group, float lr) {
     }
   }
   const bool timed = m->timing && u.g0;
-  if (timed) RUN(timing_begin(m, 1, m->stream));
-  HIPCHK(launch_update(m->stream, u));
+  if (timed) RUN(timing_begin(m, 1, st));
+  HIPCHK(launch_update(st, u));
   if (timed) {
     // algorithmic bytes per element: gradient(s) 4 each, w read+write 8, Adam m,v read+write 16, bf16 copy 2
     double per = 4.0 * ((u.g0 ? 1 : 0) + (u.g1 ? 1 : 0)) + 8.0 + (u.adam ? 16.0 : 0.0) + (u.shadow ? 2.0 : 0.0);
-    RUN(timing_end(m, 1, per * (double)u.n, m->stream));
+    RUN(timing_end(m, 1, per * (double)u.n, st));
   }
   m->upd_mask |= 1ull << group;
-  if (m->upd_mask == (1ull << (K + 1)) - 1) return close_iteration(m);
+  if (m->upd_mask == (1ull << (K + 1)) - 1) {
+    if (m->upd_pending) {       // the next iteration reads every weight: main waits for aux
+      HIPCHK(hipEventRecord(m->ev_upd_done, m->aux));
+      HIPCHK(hipStreamWaitEvent(m->stream, m->ev_upd_done, 0));
+      m->upd_pending = false;
+    }
+    return close_iteration(m);
+  }
   return OURO_OK;
+}
+
+extern "C" int ouro_delayed_update(ouro_model* m, int group, float lr) {
+  if (!m) return fail(OURO_E_ARG, "model is null");
+  const int K = m->cfg.n_module;
+  if (group < 0 || group > K) return fail(OURO_E_ARG, "delayed_update: group=%d outside 0..%d", group, K);
+  if (m->fwd_next != K + 1 || m->bwd_next != 0) return fail(OURO_E_SEQUENCE, "delayed_update before backward of module 1");
+  if (m->upd_mask & (1ull << group)) return fail(OURO_E_SEQUENCE, "delayed_update(%d) twice in one iteration", group);
+  return update_group(m, group, lr, m->stream);
 }
 
 static int read_loss(ouro_model* m, float* host_loss) {
@@ -831,9 +855,26 @@ extern "C" int ouro_step(ouro_model* m, const int32_t* dev_tokens, const int32_t
   if (!m || !dev_tokens || !dev_targets) return fail(OURO_E_ARG, "step: null argument");
   const int K = m->cfg.n_module;
   for (int k = 1; k <= K; ++k) RUN(ouro_module_forward(m, k, dev_tokens, dev_targets));
-  for (int k = K; k >= 1; --k) RUN(ouro_module_backward(m, k));
-  for (int k = 1; k <= K; ++k) RUN(ouro_delayed_update(m, k, lr));
-  RUN(ouro_delayed_update(m, 0, lr));
+  // Module k's weights are last read by its own backward pass, and the gradient Eq. 8 hands
+  // it is either an older ring slot or (k = K) the one that pass just completed; V is last
+  // read by module K's backward, and for K > 1 Eq. 9 pairs the fresh dV_o with an older dV_i.
+  // So each update is enqueued on the third stream right behind that backward pass and
+  // overlaps the backward passes of the modules below; the results are those of the serial
+  // order, since the groups are disjoint. Per-launch timing keeps the serial order.
+  const bool early = m->use_side && !m->timing;
+  for (int k = K; k >= 1; --k) {
+    RUN(ouro_module_backward(m, k));
+    if (early && k > 1) {
+      HIPCHK(hipEventRecord(m->ev_bwd_done, m->stream));
+      HIPCHK(hipStreamWaitEvent(m->aux, m->ev_bwd_done, 0));
+      m->upd_pending = true;
+      RUN(update_group(m, k, lr, m->aux));
+      if (k == K) RUN(update_group(m, 0, lr, m->aux));
+    }
+  }
+  const uint64_t done = m->upd_mask;    // the last update closes the iteration and clears the mask
+  for (int k = 0; k <= K; ++k)
+    if (!(done & (1ull << k))) RUN(update_group(m, k, lr, m->stream));
   if (host_loss) return read_loss(m, host_loss);
   return OURO_OK;
 }
@@ -904,6 +945,17 @@ extern "C" int ouro_debug_get_hidden(ouro_model* m, int layer, float* host_dst, 
 extern "C" int ouro_debug_timing_enable(ouro_model* m, int on) {
   if (!m) return fail(OURO_E_ARG, "model is null");
   m->timing = on ? 1 : 0;
+  return OURO_OK;
+}
+
+extern "C" int ouro_debug_set_overlap(ouro_model* m, int on) {
+  if (!m) return fail(OURO_E_ARG, "model is null");
+  if (m->fwd_next != 1) return fail(OURO_E_SEQUENCE, "set_overlap inside an iteration");
+  HIPCHK(hipStreamSynchronize(m->stream));
+  HIPCHK(hipStreamSynchronize(m->side));
+  HIPCHK(hipStreamSynchronize(m->aux));
+  m->side_busy[0] = m->side_busy[1] = false;
+  m->use_side = on != 0;
   return OURO_OK;
 }
 
