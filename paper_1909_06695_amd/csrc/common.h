@@ -104,10 +104,13 @@ hipError_t launch_attn_bwd(hipStream_t s, int dtype, const AttnDesc& a, int forc
 // y = LN(x) * g + b over rows of d elements (biased variance, eps 1e-5); saves mean, rstd.
 hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, const void* x, const float* g, const float* b,
                                 void* y, float* mean, float* rstd, int rows, int d);
-// dx from dy, x, stats; dg/db (fp32) are accumulated into (caller zeroes).
+// dx from dy, x, stats; dg/db (fp32) are accumulated into (caller zeroes). dg == nullptr: dx only.
 hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const float* g,
                                 const float* mean, const float* rstd, void* dx, float* dg, float* db,
                                 int rows, int d);
+// dg[c] += sum_r dy*xhat, db[c] += sum_r dy alone (any stream that sees dy, x and the stats)
+hipError_t launch_layernorm_bwd_params(hipStream_t s, int dtype, const void* dy, const void* x, const float* mean,
+                                       const float* rstd, float* dg, float* db, int rows, int d);
 // out[c] += sum over rows of x[r, c]  (fp32 accumulate into, caller zeroes)
 hipError_t launch_colsum(hipStream_t s, int dtype, const void* x, int ldx, float* out, int rows, int cols);
 // h[n,:] = scale * V[tok[n],:] (+ pe[n % T,:]); ids outside [0,vocab) set *flag and give a zero row

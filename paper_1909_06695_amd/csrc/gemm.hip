@@ -217,8 +217,8 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
     const size_t bytesA = 2 * (size_t)(g.transA ? g.K : g.M) * g.lda, bytesB = 2 * (size_t)(g.transB ? g.N : g.K) * g.ldb;
     const bool dl = cfg >= 10 && (g.K % 64) == 0 && bytesA < (1ull << 31) && bytesB < (1ull << 31);
     if (cfg >= 10 && !dl) cfg = 0;
-    const int BM = (cfg == 21 || cfg == 23) ? 64 : (cfg == 0 || (cfg >= 10 && cfg <= 12) || (cfg >= 16 && cfg <= 18) || cfg == 22) ? 128 : 256;
-    const int BN = cfg == 22 ? 64 : (cfg == 2 || cfg == 3 || cfg == 15 || cfg == 17 || cfg == 19) ? 256 : 128;
+    const int BM = (cfg == 21 || cfg == 23) ? 64 : (cfg == 0 || (cfg >= 10 && cfg <= 12) || (cfg >= 16 && cfg <= 18) || cfg == 22 || (cfg >= 24 && cfg != 34)) ? 128 : 256;
+    const int BN = (cfg == 22 || cfg == 25 || cfg == 32 || cfg == 33) ? 64 : (cfg == 2 || cfg == 3 || cfg == 15 || cfg == 17 || cfg == 19) ? 256 : 128;
     int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     int splits = 1;
     if (g.accumulate && tiles < 384 && g.K >= 512) {

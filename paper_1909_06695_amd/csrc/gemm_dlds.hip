@@ -202,8 +202,124 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dlds_kernel(GemmParams p) {
   mfma_epilogue<TM, TN>(p, acc, smem, m0 + wm * (TM * 32), n0 + wn * (TN * 32), lane, wave);
 }
 
-template <int BM, int BN, int WM, int WN, int S>
-hipError_t launch_dlds_cfg(hipStream_t s, GemmParams& p, int transA, int transB, int splits) {
+// Same ring, deeper software pipeline: the fragments of a whole K-tile live in registers and
+// are refilled for K-tile kt+1 right behind the matrix instructions of K-tile kt that last
+// used them, so an LDS read has a full K-tile of matrix work to hide behind.  Stage kt+1 is
+// being read while kt computes, so S >= 3 and S-2 stages are in flight from memory.
+template <int BM, int BN, int WM, int WN, bool TA, bool TB, int S>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_pipe_kernel(GemmParams p) {
+  constexpr int BK = 64;
+  constexpr int NW = WM * WN;
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  using TileA = OperandTile<BM, NW, TA>;
+  using TileB = OperandTile<BN, NW, !TB>;
+  constexpr int STAGE = TileA::BYTES + TileB::BYTES;
+  constexpr int LPT = TileA::PER + TileB::PER;
+  static_assert(S >= 3, "one stage is read while another computes");
+  static_assert((S - 2) * LPT < 64, "too many loads in flight for vmcnt");
+  extern __shared__ uint4 smem[];
+  char* lds = reinterpret_cast<char*>(smem);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  int bid = blockIdx.x;
+  {
+    int nb = gridDim.x, q = nb >> 3, r = nb & 7, x = bid & 7, idx = bid >> 3;
+    bid = x * q + min(x, r) + idx;
+  }
+  const int m0 = (bid / p.tilesN) * BM, n0 = (bid % p.tilesN) * BN;
+  const int kbeg = blockIdx.z * p.kchunk;
+  const int kend = min(p.K, kbeg + p.kchunk);
+  const int nk = (kend - kbeg) / BK;
+
+  uint32_t oa[TileA::PER], ob[TileB::PER];
+#pragma unroll
+  for (int i = 0; i < TileA::PER; ++i)
+    oa[i] = (uint32_t)(2 * (TileA::src_offset(wave + i * NW, lane, m0, p.M, p.lda) + (TA ? (size_t)kbeg * p.lda : (size_t)kbeg)));
+#pragma unroll
+  for (int i = 0; i < TileB::PER; ++i)
+    ob[i] = (uint32_t)(2 * (TileB::src_offset(wave + i * NW, lane, n0, p.N, p.ldb) + (TB ? (size_t)kbeg : (size_t)kbeg * p.ldb)));
+  const uint32_t stepA = 2u * (TA ? (uint32_t)BK * p.lda : (uint32_t)BK);
+  const uint32_t stepB = 2u * (TB ? (uint32_t)BK : (uint32_t)BK * p.ldb);
+  const char* Ab = reinterpret_cast<const char*>(p.A);
+  const char* Bb = reinterpret_cast<const char*>(p.B);
+
+  auto issue = [&](int kt) __attribute__((always_inline)) {
+    char* st = lds + (kt % S) * STAGE;
+    const uint32_t ka = (uint32_t)kt * stepA, kb = (uint32_t)kt * stepB;
+#pragma unroll
+    for (int i = 0; i < TileA::PER; ++i)
+      __builtin_amdgcn_global_load_lds((gbl_void*)(Ab + (oa[i] + ka)), (lds_void*)(st + (wave + i * NW) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < TileB::PER; ++i)
+      __builtin_amdgcn_global_load_lds((gbl_void*)(Bb + (ob[i] + kb)),
+                                       (lds_void*)(st + TileA::BYTES + (wave + i * NW) * 1024), 16, 0, 0);
+  };
+  bf16x8 af[4][TM], bfr[4][TN];
+  auto fetch = [&](int kt, int ks) __attribute__((always_inline)) {
+    const char* sa = lds + (kt % S) * STAGE;
+    const char* sb = sa + TileA::BYTES;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      af[ks][i] = TA ? frag_col<BM>(sa, wm * (TM * 32) + i * 32, ks, lane) : frag_row(sa, wm * (TM * 32) + i * 32, ks, lane);
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      bfr[ks][j] = TB ? frag_row(sb, wn * (TN * 32) + j * 32, ks, lane) : frag_col<BN>(sb, wn * (TN * 32) + j * 32, ks, lane);
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // tiles 0 .. S-2 on their way; tile 0 into registers
+#pragma unroll
+  for (int s = 0; s < S - 1; ++s)
+    if (s < nk) issue(s);
+  if (nk >= S - 1) wait_vmcnt<(S - 2) * LPT>();
+  else wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) fetch(0, ks);
+
+  for (int kt = 0; kt < nk; ++kt) {
+    // tile kt+1 has landed once only the loads of tiles kt+2 .. kt+S-2 are outstanding
+    if (kt + S - 1 <= nk) wait_vmcnt<(S - 3) * LPT>();
+    else wait_vmcnt<0>();
+    // After this barrier tile kt+1 is complete in LDS, and every wave has issued the matrix
+    // instructions of tile kt-1, which consumed the last reads of stage (kt-1)%S: refill it.
+    __builtin_amdgcn_s_barrier();
+    if (kt + S - 1 < nk) issue(kt + S - 1);
+    const bool more = kt + 1 < nk;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], bfr[ks][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (more) fetch(kt + 1, ks);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  __syncthreads();                                          // operand reads done: LDS reusable
+  mfma_epilogue<TM, TN>(p, acc, smem, m0 + wm * (TM * 32), n0 + wn * (TN * 32), lane, wave);
+}
+
+template <int BM, int BN, int WM, int WN, bool TA, bool TB, int S, bool PIPE>
+struct KernelOf {
+  static auto get() { return gemm_dlds_kernel<BM, BN, WM, WN, TA, TB, S>; }
+};
+template <int BM, int BN, int WM, int WN, bool TA, bool TB, int S>
+struct KernelOf<BM, BN, WM, WN, TA, TB, S, true> {
+  static auto get() { return gemm_pipe_kernel<BM, BN, WM, WN, TA, TB, S>; }
+};
+
+template <int BM, int BN, int WM, int WN, int S, bool PIPE>
+hipError_t launch_dlds_cfg_impl(hipStream_t s, GemmParams& p, int transA, int transB, int splits) {
   constexpr size_t smem_main = (size_t)S * (BM + BN) * 128;
   constexpr size_t smem_epi = (size_t)WM * WN * epilogue_stage_floats<BN / WN / 32>() * sizeof(float);
   constexpr size_t smem = smem_main > smem_epi ? smem_main : smem_epi;
@@ -213,7 +329,7 @@ hipError_t launch_dlds_cfg(hipStream_t s, GemmParams& p, int transA, int transB,
 #define OURO_LAUNCH(TA_, TB_)                                                                    \
   do {                                                                                           \
     static bool attr_done = false;                                                               \
-    auto kern = gemm_dlds_kernel<BM, BN, WM, WN, TA_, TB_, S>;                                   \
+    auto kern = KernelOf<BM, BN, WM, WN, TA_, TB_, S, PIPE>::get();                              \
     if (!attr_done) {                                                                            \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                    \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
@@ -228,6 +344,15 @@ hipError_t launch_dlds_cfg(hipStream_t s, GemmParams& p, int transA, int transB,
   else OURO_LAUNCH(true, true);
 #undef OURO_LAUNCH
   return hipGetLastError();
+}
+
+template <int BM, int BN, int WM, int WN, int S>
+hipError_t launch_dlds_cfg(hipStream_t s, GemmParams& p, int transA, int transB, int splits) {
+  return launch_dlds_cfg_impl<BM, BN, WM, WN, S, false>(s, p, transA, transB, splits);
+}
+template <int BM, int BN, int WM, int WN, int S>
+hipError_t launch_pipe_cfg(hipStream_t s, GemmParams& p, int transA, int transB, int splits) {
+  return launch_dlds_cfg_impl<BM, BN, WM, WN, S, true>(s, p, transA, transB, splits);
 }
 
 // cfg: 10 = 128x128 S2, 11 = 128x128 S3, 12 = 128x128 S4, 13 = 256x128 (2x2 waves) S3,
@@ -248,6 +373,15 @@ hipError_t launch_gemm_dlds(hipStream_t s, GemmParams& p, int transA, int transB
     case 21: return launch_dlds_cfg<64, 128, 1, 4, 2>(s, p, transA, transB, splits);
     case 22: return launch_dlds_cfg<128, 64, 4, 1, 2>(s, p, transA, transB, splits);
     case 23: return launch_dlds_cfg<64, 128, 2, 4, 3>(s, p, transA, transB, splits);
+    case 24: return launch_dlds_cfg<128, 128, 2, 4, 3>(s, p, transA, transB, splits);
+    case 25: return launch_dlds_cfg<128, 64, 4, 1, 3>(s, p, transA, transB, splits);
+    case 26: return launch_dlds_cfg<128, 128, 2, 4, 4>(s, p, transA, transB, splits);
+    case 30: return launch_pipe_cfg<128, 128, 2, 2, 4>(s, p, transA, transB, splits);
+    case 31: return launch_pipe_cfg<128, 128, 2, 4, 4>(s, p, transA, transB, splits);
+    case 32: return launch_pipe_cfg<128, 64, 4, 1, 3>(s, p, transA, transB, splits);
+    case 33: return launch_pipe_cfg<128, 64, 4, 1, 4>(s, p, transA, transB, splits);
+    case 34: return launch_pipe_cfg<256, 128, 4, 2, 3>(s, p, transA, transB, splits);
+    case 35: return launch_pipe_cfg<128, 128, 2, 2, 3>(s, p, transA, transB, splits);
     default: return hipErrorInvalidValue;
   }
 }

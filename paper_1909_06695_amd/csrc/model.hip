@@ -142,7 +142,7 @@ struct ouro_model {
   float *lse_ce, *rowloss, *loss;
   int* flag;
   // backward scratch
-  char *dh0, *dh1, *dy, *da, *dcat, *dr_t;
+  char *dhb[3], *dy[2], *da, *dcat, *dr_t;   // layer l reads dhb[l % 3], writes dhb[(l + 2) % 3]
   // gradients that the weight-gradient GEMMs read on the side stream: two sets, by layer parity
   char *ds2[2], *dz[2], *ds1[2], *dqkv[2];
   float *attn_scratch, *dr_f32, *dbg_f32;
@@ -299,8 +299,8 @@ static size_t lay_out(ouro_model& m, char* base) {
   m.rowloss = (float*)P(N * 4);
   m.loss = (float*)P(256);
   m.flag = (int*)P(256);
-  m.dh0 = P(N * d * es); m.dh1 = P(N * d * es);
-  m.dy = P(N * d * es); m.da = P(N * d * es);
+  for (int i = 0; i < 3; ++i) m.dhb[i] = P(N * d * es);
+  m.dy[0] = P(N * d * es); m.dy[1] = P(N * d * es); m.da = P(N * d * es);
   for (int p2 = 0; p2 < 2; ++p2) {
     m.ds2[p2] = P(N * d * es); m.dz[p2] = P(N * F * es);
     m.ds1[p2] = P(N * d * es); m.dqkv[p2] = P(qkv_elems * es);
@@ -580,6 +580,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   const bool side = m->use_side && !c.rel_pos;
   hipStream_t sw = side ? m->side : st;               // stream of the weight-gradient work
   char* ds2 = m->ds2[ps]; char* dz = m->dz[ps]; char* ds1 = m->ds1[ps]; char* dqkv = m->dqkv[ps];
+  char* dy = m->dy[ps];
   // the side stream may still be reading this buffer set (layer l+2 of this module)
   if (side && m->side_busy[ps]) { HIPCHK(hipStreamWaitEvent(st, m->ev_side_done[ps], 0)); m->side_busy[ps] = false; }
   auto ready = [&](int i) -> int {                    // operand i written on main; side may start
@@ -589,8 +590,11 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     return OURO_OK;
   };
   // LN2
-  HIPCHK(launch_layernorm_bwd(st, c.dtype, dh, b.s2, m->wF(l, o.ln2_g), b.mean2, b.rstd2, ds2, gslot + o.ln2_g, gslot + o.ln2_b, N, d));
+  // with the side stream the scale/shift gradients (column sums over dh and s2) run there too
+  HIPCHK(launch_layernorm_bwd(st, c.dtype, dh, b.s2, m->wF(l, o.ln2_g), b.mean2, b.rstd2, ds2,
+                              side ? nullptr : gslot + o.ln2_g, gslot + o.ln2_b, N, d));
   RUN(ready(0));
+  if (side) HIPCHK(launch_layernorm_bwd_params(sw, c.dtype, dh, b.s2, b.mean2, b.rstd2, gslot + o.ln2_g, gslot + o.ln2_b, N, d));
   // FFN2
   {
     GemmDesc g = gd(b.uact, F, 1, ds2, d, 0, gslot + o.W_2, d, F, d, N);
@@ -612,13 +616,15 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   }
   HIPCHK(launch_colsum(sw, c.dtype, dz, F, gslot + o.b_1, N, F));
   {
-    GemmDesc g = gd(dz, F, 0, m->wT(l, o.W_1), F, 1, m->dy, d, N, d, F);
+    GemmDesc g = gd(dz, F, 0, m->wT(l, o.W_1), F, 1, dy, d, N, d, F);
     g.residual = ds2; g.ldr = d;
     RUN(run_gemm(m, g));
   }
   // LN1
-  HIPCHK(launch_layernorm_bwd(st, c.dtype, m->dy, b.s1, m->wF(l, o.ln1_g), b.mean1, b.rstd1, ds1, gslot + o.ln1_g, gslot + o.ln1_b, N, d));
+  HIPCHK(launch_layernorm_bwd(st, c.dtype, dy, b.s1, m->wF(l, o.ln1_g), b.mean1, b.rstd1, ds1,
+                              side ? nullptr : gslot + o.ln1_g, gslot + o.ln1_b, N, d));
   RUN(ready(2));
+  if (side) HIPCHK(launch_layernorm_bwd_params(sw, c.dtype, dy, b.s1, b.mean1, b.rstd1, gslot + o.ln1_g, gslot + o.ln1_b, N, d));
   // output projection
   {
     GemmDesc g = gd(b.a, d, 1, ds1, d, 0, gslot + o.W_o, d, d, d, N);
@@ -700,8 +706,9 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   return OURO_OK;
 }
 
-extern "C" int ouro_module_backward(ouro_model* m, int k) {
-  if (!m) return fail(OURO_E_ARG, "model is null");
+// defer_join: leave the side stream's share of this module's gradient unjoined (ev_join is
+// recorded on the side stream; the caller orders the gradient's reader behind it).
+static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
   const ouro_config& c = m->cfg;
   const int K = c.n_module, d = c.d_model, V = c.vocab, N = m->N;
   if (k < 1 || k > K) return fail(OURO_E_ARG, "module_backward: k=%d outside 1..%d", k, K);
@@ -726,18 +733,21 @@ extern "C" int ouro_module_backward(ouro_model* m, int k) {
       RUN(run_gemm(m, g));
     }
     m->tags[K + 1][0] = m->t;
-    RUN(run_gemm(m, gd(m->G, m->ldv, 0, m->vT(), d, 0, (lastl % 2) ? m->dh1 : m->dh0, d, N, d, V)));
+    RUN(run_gemm(m, gd(m->G, m->ldv, 0, m->vT(), d, 0, m->dhb[lastl % 3], d, N, d, V)));
   }
-  // layer l reads its output gradient from dh[(l)%2] and writes its input gradient to dh[(l-1)%2]
+  // layer l reads its output gradient from dhb[l % 3] and writes its input gradient to dhb[(l + 2) % 3]:
+  // three buffers, so that side-stream readers of layer l's input are two layers away from its next writer
   for (int l = m->first_layer[k] - 1; l >= m->first_layer[k - 1]; --l) {
-    char* dh = (l % 2) ? m->dh1 : m->dh0;
-    char* dx = (l % 2) ? m->dh0 : m->dh1;
+    char* dh = m->dhb[l % 3];
+    char* dx = m->dhb[(l + 2) % 3];
     RUN(layer_backward(m, l, dh, dx, gslot));
   }
   if (m->use_side) {          // the module's gradient is complete once the side work has joined
     HIPCHK(hipEventRecord(m->ev_join, m->side));
-    HIPCHK(hipStreamWaitEvent(m->stream, m->ev_join, 0));
-    m->side_busy[0] = m->side_busy[1] = false;
+    if (!defer_join) {
+      HIPCHK(hipStreamWaitEvent(m->stream, m->ev_join, 0));
+      m->side_busy[0] = m->side_busy[1] = false;
+    }
   }
   m->tags[k][slot] = m->t;
   if (k == 1) {
@@ -746,11 +756,16 @@ extern "C" int ouro_module_backward(ouro_model* m, int k) {
     ouro_slot_index(K, 0, m->t, 1, &s0, &t0);
     float* dvi = m->slot_ptr(0, s0);
     HIPCHK(launch_fill_zero(m->stream, dvi, (size_t)m->gstride[0] * 4));
-    HIPCHK(launch_embed_bwd(m->stream, c.dtype, m->tok, m->dh1, dvi, N, d, V, c.emb_scale));
+    HIPCHK(launch_embed_bwd(m->stream, c.dtype, m->tok, m->dhb[2], dvi, N, d, V, c.emb_scale));
     m->tags[0][s0] = m->t;
   }
   m->bwd_next = k - 1;
   return OURO_OK;
+}
+
+extern "C" int ouro_module_backward(ouro_model* m, int k) {
+  if (!m) return fail(OURO_E_ARG, "model is null");
+  return module_backward_impl(m, k, false);
 }
 
 // ------------------------------------------------------------------------------- update
@@ -863,10 +878,12 @@ extern "C" int ouro_step(ouro_model* m, const int32_t* dev_tokens, const int32_t
   // order, since the groups are disjoint. Per-launch timing keeps the serial order.
   const bool early = m->use_side && !m->timing;
   for (int k = K; k >= 1; --k) {
-    RUN(ouro_module_backward(m, k));
+    RUN(module_backward_impl(m, k, early && k > 1));
     if (early && k > 1) {
+      // the update waits for both halves of the gradient; the main stream goes straight on
       HIPCHK(hipEventRecord(m->ev_bwd_done, m->stream));
       HIPCHK(hipStreamWaitEvent(m->aux, m->ev_bwd_done, 0));
+      HIPCHK(hipStreamWaitEvent(m->aux, m->ev_join, 0));
       m->upd_pending = true;
       RUN(update_group(m, k, lr, m->aux));
       if (k == K) RUN(update_group(m, 0, lr, m->aux));

@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, in
 // Vector path of the LayerNorm backward: one wavefront per row, rows strided over the grid;
 // the row's packs stay in registers, dg / db partial sums are kept per lane over all the
 // wave's rows, reduced over the block's four waves through LDS and added atomically once.
-template <typename T, int MAXI>
+template <typename T, int MAXI, bool PARAMS>
 __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                            const float* __restrict__ g, const float* __restrict__ mean,
                                                            const float* __restrict__ rstd, T* __restrict__ dx,
@@ -241,8 +241,10 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* __restrict__
 #pragma unroll
           for (int e = 0; e < N; ++e) {
             xh[u][i][e] = (xh[u][i][e] - mu[u]) * rs[u];
-            ag[i][e] += t[u][i][e] * xh[u][i][e];
-            ab[i][e] += t[u][i][e];
+            if (PARAMS) {
+              ag[i][e] += t[u][i][e] * xh[u][i][e];
+              ab[i][e] += t[u][i][e];
+            }
             t[u][i][e] *= gl[i][e];
             s1 += t[u][i][e];
             s2 += t[u][i][e] * xh[u][i][e];
@@ -263,6 +265,7 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* __restrict__
       }
     }
   }
+  if (!PARAMS) return;
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
 #pragma unroll
@@ -307,33 +310,109 @@ __global__ __launch_bounds__(256) void colsum_vec_kernel(const T* __restrict__ x
     unsafeAtomicAdd(out + blockIdx.x * 64 * N + c, red[0][c] + red[1][c] + red[2][c] + red[3][c]);
 }
 
+// Scale and shift gradients of LayerNorm as column sums: dg[c] += sum_r dy*xhat, db[c] += sum_r dy.
+// A wave covers 64 packs of one row, the block's sixteen waves take alternate rows; the partial
+// sums meet in LDS and leave as one atomic per column and block.  Adds to one address complete
+// one after the other, so the grid has few, large blocks.
+template <typename T>
+__global__ __launch_bounds__(1024) void ln_param_vec_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                            const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                            float* __restrict__ dg, float* __restrict__ db, int rows, int d,
+                                                            int rows_per_block) {
+  constexpr int N = Pack<T>::N;
+  constexpr int NWV = 16;
+  extern __shared__ float red[];                 // [2][NWV][64 * N]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c0 = (blockIdx.x * 64 + lane) * N;
+  const bool live = c0 < d;
+  const int rbeg = blockIdx.y * rows_per_block;
+  const int rend = min(rows, rbeg + rows_per_block);
+  float a0[N], a1[N];
+#pragma unroll
+  for (int e = 0; e < N; ++e) a0[e] = a1[e] = 0.f;
+  if (live) {
+    for (int r = rbeg + wave; r < rend; r += NWV) {
+      float v[N], xv[N];
+      load_pack<T>(dy + (size_t)r * d + c0, v);
+      load_pack<T>(x + (size_t)r * d + c0, xv);
+      const float mu = mean[r], rs = rstd[r];
+#pragma unroll
+      for (int e = 0; e < N; ++e) {
+        a0[e] += v[e] * ((xv[e] - mu) * rs);
+        a1[e] += v[e];
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < N; ++e) {
+    red[(0 * NWV + wave) * 64 * N + lane * N + e] = a0[e];
+    red[(1 * NWV + wave) * 64 * N + lane * N + e] = a1[e];
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < 2 * 64 * N; c += 1024) {
+    const int which = c / (64 * N), cc = c % (64 * N);
+    const int col = blockIdx.x * 64 * N + cc;
+    if (col < d) {
+      float t = 0.f;
+#pragma unroll
+      for (int w = 0; w < NWV; ++w) t += red[(which * NWV + w) * 64 * N + cc];
+      unsafeAtomicAdd((which ? db : dg) + col, t);
+    }
+  }
+}
+
 static inline bool ptr16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
+static bool ln_vec_ok(int dtype, const void* dy, const void* x, int d) {
+  const int pack = dtype == 1 ? 8 : 4;
+  return d % pack == 0 && d / pack <= 256 && ptr16(dy) && ptr16(x);
+}
+
+// dg == nullptr: input gradient only (the parameter gradients then come from
+// launch_layernorm_bwd_params, on any stream that sees dy and x).
 hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const float* g,
                                 const float* mean, const float* rstd, void* dx, float* dg, float* db,
                                 int rows, int d) {
   if (rows <= 0) return hipSuccess;
   dim3 grid((rows + 3) / 4), block(256);
-  const int rpb = 128;
-  dim3 g2((d + 63) / 64, (rows + rpb - 1) / rpb);
-  const int pack = dtype == 1 ? 8 : 4;
-  if (d % pack == 0 && d / pack <= 256 && ptr16(dy) && ptr16(x) && ptr16(dx)) {
+  if (ln_vec_ok(dtype, dy, x, d) && ptr16(dx)) {
+    const int pack = dtype == 1 ? 8 : 4;
     dim3 gf(std::min((rows + 3) / 4, 512));
-    size_t smem = 4 * (size_t)d * sizeof(float);
     const int npl = (d / pack + 63) / 64;      // packs per lane
-#define OURO_LNB(T_, MI_) hipLaunchKernelGGL((ln_bwd_fused_kernel<T_, MI_>), gf, block, smem, s, (const T_*)dy, (const T_*)x, g, mean, rstd, (T_*)dx, dg, db, rows, d)
+#define OURO_LNB(T_, MI_) hipLaunchKernelGGL((ln_bwd_fused_kernel<T_, MI_, false>), gf, block, 0, s, (const T_*)dy, (const T_*)x, g, mean, rstd, (T_*)dx, nullptr, nullptr, rows, d)
     if (dtype == 1) { if (npl <= 1) OURO_LNB(bf16_t, 1); else if (npl <= 2) OURO_LNB(bf16_t, 2); else OURO_LNB(bf16_t, 4); }
     else { if (npl <= 1) OURO_LNB(float, 1); else if (npl <= 2) OURO_LNB(float, 2); else OURO_LNB(float, 4); }
 #undef OURO_LNB
-    return hipGetLastError();
-  }
-  if (dtype == 1) {
+  } else if (dtype == 1) {
     hipLaunchKernelGGL(ln_bwd_dx_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)dy, (const bf16_t*)x, g, mean, rstd, (bf16_t*)dx, rows, d);
-    hipLaunchKernelGGL((colsum_kernel<bf16_t, 1>), g2, block, 0, s, (const bf16_t*)dy, d, (const bf16_t*)x, mean, rstd, dg, db, rows, d, rpb);
   } else {
     hipLaunchKernelGGL(ln_bwd_dx_kernel<float>, grid, block, 0, s, (const float*)dy, (const float*)x, g, mean, rstd, (float*)dx, rows, d);
-    hipLaunchKernelGGL((colsum_kernel<float, 1>), g2, block, 0, s, (const float*)dy, d, (const float*)x, mean, rstd, dg, db, rows, d, rpb);
   }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !dg) return e;
+  return launch_layernorm_bwd_params(s, dtype, dy, x, mean, rstd, dg, db, rows, d);
+}
+
+hipError_t launch_layernorm_bwd_params(hipStream_t s, int dtype, const void* dy, const void* x, const float* mean,
+                                       const float* rstd, float* dg, float* db, int rows, int d) {
+  if (rows <= 0) return hipSuccess;
+  dim3 block(256);
+  if (ln_vec_ok(dtype, dy, x, d)) {
+    const int pack = dtype == 1 ? 8 : 4;
+    const int gx = (d + 64 * pack - 1) / (64 * pack);
+    const int rpb = 64;                          // four rows per wave
+    dim3 grid(gx, (rows + rpb - 1) / rpb), blk(1024);
+    const size_t smem = 2 * 16 * 64 * (size_t)pack * sizeof(float);
+    if (dtype == 1) hipLaunchKernelGGL(ln_param_vec_kernel<bf16_t>, grid, blk, smem, s, (const bf16_t*)dy, (const bf16_t*)x, mean, rstd, dg, db, rows, d, rpb);
+    else hipLaunchKernelGGL(ln_param_vec_kernel<float>, grid, blk, smem, s, (const float*)dy, (const float*)x, mean, rstd, dg, db, rows, d, rpb);
+    return hipGetLastError();
+  }
+  const int rpb = 128;
+  dim3 g2((d + 63) / 64, (rows + rpb - 1) / rpb);
+  if (dtype == 1)
+    hipLaunchKernelGGL((colsum_kernel<bf16_t, 1>), g2, block, 0, s, (const bf16_t*)dy, d, (const bf16_t*)x, mean, rstd, dg, db, rows, d, rpb);
+  else
+    hipLaunchKernelGGL((colsum_kernel<float, 1>), g2, block, 0, s, (const float*)dy, d, (const float*)x, mean, rstd, dg, db, rows, d, rpb);
   return hipGetLastError();
 }
 
