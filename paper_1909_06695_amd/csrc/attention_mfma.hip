@@ -31,6 +31,7 @@ struct FaParams {
   bf16_t* dk; int lddk;
   bf16_t* dv; int lddv;
   float* D;
+  float* lse2;
 };
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -112,13 +113,38 @@ __device__ __forceinline__ void store_acc_row(bf16_t* dst, const f32x16 (&acc)[2
     }
 }
 
+
+// Workgroup -> (block along the causal axis, head, batch).  Causal work per block grows
+// linearly along the axis, consecutive workgroup ids go to consecutive XCDs, and within an
+// XCD workgroups are placed on compute units in id order.  So ids are decoded such that every
+// XCD gets every block index equally often and the second half of an XCD's workgroups runs
+// through the blocks in the opposite order: the two workgroups that share a compute unit
+// then carry complementary loads.  `rank` counts from the heaviest block (0) to the lightest.
+__device__ __forceinline__ void fa_decode_block(int& rank, int& head, int& b) {
+  const int gx = gridDim.x, groups = gridDim.y * gridDim.z;
+  int grp;
+  if ((groups & 7) == 0 && ((groups >> 3) & 1) == 0) {
+    const int lin = blockIdx.x + gx * (blockIdx.y + gridDim.y * blockIdx.z);
+    const int xcd = lin & 7, slot = lin >> 3, per = (gx * groups) >> 3;
+    rank = slot % gx;
+    grp = xcd + 8 * (slot / gx);
+    if (slot >= (per >> 1)) rank = gx - 1 - rank;
+  } else {
+    rank = blockIdx.x;
+    grp = blockIdx.y + gridDim.y * blockIdx.z;
+  }
+  head = grp % gridDim.y;
+  b = grp / gridDim.y;
+}
+
 // ------------------------------------------------------------------------------ forward
 // grid (ceil(T/128), H, B); 4 waves x 32 queries; key blocks of 64.
 __global__ __launch_bounds__(256) void fa_fwd_kernel(FaParams p) {
   __shared__ __attribute__((aligned(16))) char lds[NSTAGE * 2 * TILE_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
-  const int qblk = gridDim.x - 1 - blockIdx.x;            // longest rows first
-  const int head = blockIdx.y, b = blockIdx.z;
+  int rank, head, b;
+  fa_decode_block(rank, head, b);
+  const int qblk = gridDim.x - 1 - rank;                  // the last query block has the longest rows
   const int q0 = qblk * 128 + wave * 32, qi = q0 + l32;
   const bf16_t* qb = p.q + (size_t)b * p.T * p.ldq + head * 64;
   const bf16_t* kb = p.k + (size_t)b * p.S * p.ldk + head * 64;
@@ -158,53 +184,79 @@ __global__ __launch_bounds__(256) void fa_fwd_kernel(FaParams p) {
     const char* sK = lds + (jb % NSTAGE) * (2 * TILE_BYTES);
     const char* sV = sK + TILE_BYTES;
     if (wave_on && jb * 64 <= wave_kmax) {
+      // keys 32..63 of a diagonal block are masked for every query of some waves: skip them
+      const int nkt = (jb * 64 + 32 <= wave_kmax) ? 2 : 1;
+      // no element of the block is masked when its last key is visible to the wave's first query
+      const bool edge = jb * 64 + 63 > p.Mv + q0 || jb * 64 + 63 >= p.S || q0 + 31 >= p.T;
       f32x16 s[2];
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt) {
+        if (kt < nkt) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+          for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sK, 32 * kt, ks, lane), qf[ks], s[kt], 0, 0, 0);
-      }
-      float mloc = -INFINITY;
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          int key = jb * 64 + 32 * kt + 8 * (r >> 2) + 4 * h32 + (r & 3);
-          bool vis = key <= p.Mv + qi && key < p.S && qi < p.T;
-          float val = vis ? s[kt][r] * p.scale_log2 : -INFINITY;
-          s[kt][r] = val;
-          mloc = fmaxf(mloc, val);
+          for (int ks = 0; ks < 4; ++ks)
+            s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sK, 32 * kt, ks, lane), qf[ks], s[kt], 0, 0, 0);
         }
-      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-      const float m_new = fmaxf(m, mloc);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+      }
+      float mloc = -INFINITY;                              // of the raw scores (the scale is positive)
+      if (edge) {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+          if (kt < nkt) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              int key = jb * 64 + 32 * kt + 8 * (r >> 2) + 4 * h32 + (r & 3);
+              bool vis = key <= p.Mv + qi && key < p.S && qi < p.T;
+              float val = vis ? s[kt][r] : -INFINITY;
+              s[kt][r] = val;
+              mloc = fmaxf(mloc, val);
+            }
+          }
+      } else {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[kt][r]);
+      }
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64)) * p.scale_log2;
+      // The reference maximum only moves when a row's maximum grows by more than 2^8: any
+      // reference gives the same quotient, and probabilities up to 2^8 are harmless in fp32
+      // and bf16, so most blocks skip the rescaling of the output accumulator.
+      const bool grow = mloc > m + 8.f;
+      if (__any(grow)) {
+        const float m_new = grow ? mloc : m;
+        const float alpha = grow ? __builtin_amdgcn_exp2f(m - m_new) : 1.f;
+        l *= alpha;
+        m = m_new;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+      }
+      const float neg_m = (m == -INFINITY) ? 0.f : -m;
       float lsum = 0.f;
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
+        if (kt < nkt) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float pv = __builtin_amdgcn_exp2f(s[kt][r] - m_use);
-          s[kt][r] = pv;
-          lsum += pv;
+          for (int r = 0; r < 16; ++r) {
+            float pv = __builtin_amdgcn_exp2f(fmaf(s[kt][r], p.scale_log2, neg_m));
+            s[kt][r] = pv;
+            lsum += pv;
+          }
         }
       lsum += __shfl_xor(lsum, 32, 64);
-      l = l * alpha + lsum;
-      m = m_new;
-#pragma unroll
-      for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+      l += lsum;
 #pragma unroll
       for (int ks2 = 0; ks2 < 4; ++ks2) {
         const int kt = ks2 >> 1, sub = ks2 & 1;
-        bf16x8 pb = pack_acc(s[kt], sub);
+        if (kt < nkt) {
+          bf16x8 pb = pack_acc(s[kt], sub);
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
-          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sV, 32 * dt, 32 * kt + 16 * sub, lane), pb, oacc[dt], 0, 0, 0);
+          for (int dt = 0; dt < 2; ++dt)
+            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sV, 32 * dt, 32 * kt + 16 * sub, lane), pb, oacc[dt], 0, 0, 0);
+        }
       }
     }
   }
@@ -215,7 +267,7 @@ __global__ __launch_bounds__(256) void fa_fwd_kernel(FaParams p) {
   }
 }
 
-// D[b,h,i] = sum_c dO[i,c] * O[i,c]
+// D[b,h,i] = sum_c dO[i,c] * O[i,c]; lse2 = lse / ln 2
 __global__ __launch_bounds__(256) void fa_bwd_prep_kernel(FaParams p) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   const size_t total = (size_t)p.B * p.T * p.H;
@@ -233,24 +285,27 @@ __global__ __launch_bounds__(256) void fa_bwd_prep_kernel(FaParams p) {
     for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)g[e];
   }
   const int b = (int)(n / p.T), i = (int)(n % p.T);
-  p.D[((size_t)b * p.H + head) * p.T + i] = acc;
+  const size_t r = ((size_t)b * p.H + head) * p.T + i;
+  p.D[r] = acc;
+  p.lse2[r] = p.lse[r] * 1.4426950408889634f;    // base-2 log-sum-exp for the gradient kernels
 }
 
 // ------------------------------------------------------------------------ dK, dV kernel
 // grid (ceil(S/128), H, B); 4 waves x 32 keys; query blocks of 64: S = Q K^T and dP = dO V^T
 // read Q / dO rows, dV^T += dO^T P and dK^T += Q^T dS read the same tiles transposed.
 constexpr int DKV_STAGE = 2 * TILE_BYTES + 1024;   // Q, dO, lse[64], D[64], two spare lines
-__global__ __launch_bounds__(256) void fa_bwd_dkv_kernel(FaParams p) {
+// two workgroups per compute unit (256 registers per lane): both halves of a complementary pair resident
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void fa_bwd_dkv_kernel(FaParams p) {
   __shared__ __attribute__((aligned(16))) char lds[NSTAGE * DKV_STAGE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
-  const int kblk = blockIdx.x;                            // key block 0 sees every query: longest first
-  const int head = blockIdx.y, b = blockIdx.z;
+  int kblk, head, b;                                      // key block 0 sees every query: the heaviest
+  fa_decode_block(kblk, head, b);
   const int kb0 = kblk * 128 + wave * 32, key = kb0 + l32;
   const bf16_t* qb = p.q + (size_t)b * p.T * p.ldq + head * 64;
   const bf16_t* dob = p.d_o + (size_t)b * p.T * p.lddo + head * 64;
   const bf16_t* kbp = p.k + (size_t)b * p.S * p.ldk + head * 64;
   const bf16_t* vbp = p.v + (size_t)b * p.S * p.ldv + head * 64;
-  const float* lseb = p.lse + ((size_t)b * p.H + head) * p.T;
+  const float* lseb = p.lse2 + ((size_t)b * p.H + head) * p.T;
   const float* Db = p.D + ((size_t)b * p.H + head) * p.T;
   bf16x8 kf[4], vf[4];
 #pragma unroll
@@ -297,43 +352,65 @@ __global__ __launch_bounds__(256) void fa_bwd_dkv_kernel(FaParams p) {
     const float* sl = reinterpret_cast<const float*>(sQ + 2 * TILE_BYTES);
     const float* sD = sl + 64;
     if (wave_on && p.Mv + ib * 64 + 63 >= kb0) {
+      // queries 0..31 of a diagonal block see none of some waves' keys: skip them
+      const int qt0 = (p.Mv + ib * 64 + 31 >= kb0) ? 0 : 1;
+      // nothing is masked when the block's first query sees the wave's last key
+      const bool edge = kb0 + 31 > p.Mv + ib * 64 || ib * 64 + 63 >= p.T || kb0 + 31 >= p.S;
       f32x16 s[2], dp[2];
 #pragma unroll
       for (int qt = 0; qt < 2; ++qt) {
+        if (qt >= qt0) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { s[qt][r] = 0.f; dp[qt][r] = 0.f; }
+          for (int r = 0; r < 16; ++r) { s[qt][r] = 0.f; dp[qt][r] = 0.f; }
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sQ, 32 * qt, ks, lane), kf[ks], s[qt], 0, 0, 0);
-          dp[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sdO, 32 * qt, ks, lane), vf[ks], dp[qt], 0, 0, 0);
+          for (int ks = 0; ks < 4; ++ks) {
+            s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sQ, 32 * qt, ks, lane), kf[ks], s[qt], 0, 0, 0);
+            dp[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sdO, 32 * qt, ks, lane), vf[ks], dp[qt], 0, 0, 0);
+          }
         }
       }
+      // P = exp2(s * scale * log2 e - lse2); dS = P (dP - D); the factor `scale` of dS is
+      // applied once, to the finished dK
 #pragma unroll
       for (int qt = 0; qt < 2; ++qt)
+        if (qt >= qt0) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int ql = 32 * qt + 8 * (r >> 2) + 4 * h32 + (r & 3);
-          const int qi = ib * 64 + ql;
-          const bool vis = key <= p.Mv + qi && qi < p.T && key < p.S;
-          const float pv = vis ? __builtin_amdgcn_exp2f(s[qt][r] * p.scale_log2 - sl[ql] * 1.4426950408889634f) : 0.f;
-          s[qt][r] = pv;
-          dp[qt][r] = pv * (dp[qt][r] - sD[ql]) * p.scale;
+          for (int g = 0; g < 4; ++g) {
+            const int ql0 = 32 * qt + 8 * g + 4 * h32;
+            const float4 l4 = *reinterpret_cast<const float4*>(sl + ql0);
+            const float4 d4 = *reinterpret_cast<const float4*>(sD + ql0);
+            const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const int r = 4 * g + j;
+              float pv = __builtin_amdgcn_exp2f(fmaf(s[qt][r], p.scale_log2, -lv[j]));
+              if (edge) {
+                const int qi = ib * 64 + ql0 + j;
+                const bool vis = key <= p.Mv + qi && qi < p.T && key < p.S;
+                pv = vis ? pv : 0.f;
+              }
+              s[qt][r] = pv;
+              dp[qt][r] = pv * (dp[qt][r] - dv4[j]);
+            }
+          }
         }
 #pragma unroll
       for (int ks2 = 0; ks2 < 4; ++ks2) {
         const int qt = ks2 >> 1, sub = ks2 & 1;
-        bf16x8 pb = pack_acc(s[qt], sub);
-        bf16x8 dsb = pack_acc(dp[qt], sub);
+        if (qt >= qt0) {
+          bf16x8 pb = pack_acc(s[qt], sub);
+          bf16x8 dsb = pack_acc(dp[qt], sub);
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
-          dvT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sdO, 32 * dt, 32 * qt + 16 * sub, lane), pb, dvT[dt], 0, 0, 0);
-          dkT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sQ, 32 * dt, 32 * qt + 16 * sub, lane), dsb, dkT[dt], 0, 0, 0);
+          for (int dt = 0; dt < 2; ++dt) {
+            dvT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sdO, 32 * dt, 32 * qt + 16 * sub, lane), pb, dvT[dt], 0, 0, 0);
+            dkT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sQ, 32 * dt, 32 * qt + 16 * sub, lane), dsb, dkT[dt], 0, 0, 0);
+          }
         }
       }
     }
   }
   if (key < p.S) {
-    store_acc_row(p.dk + ((size_t)b * p.S + key) * p.lddk + head * 64, dkT, 1.f, h32);
+    store_acc_row(p.dk + ((size_t)b * p.S + key) * p.lddk + head * 64, dkT, p.scale, h32);
     store_acc_row(p.dv + ((size_t)b * p.S + key) * p.lddv + head * 64, dvT, 1.f, h32);
   }
 }
@@ -344,8 +421,9 @@ __global__ __launch_bounds__(256) void fa_bwd_dkv_kernel(FaParams p) {
 __global__ __launch_bounds__(256) void fa_bwd_dq_kernel(FaParams p) {
   __shared__ __attribute__((aligned(16))) char lds[NSTAGE * 2 * TILE_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
-  const int qblk = gridDim.x - 1 - blockIdx.x;
-  const int head = blockIdx.y, b = blockIdx.z;
+  int rank, head, b;
+  fa_decode_block(rank, head, b);
+  const int qblk = gridDim.x - 1 - rank;
   const int q0 = qblk * 128 + wave * 32, qi = q0 + l32;
   const bf16_t* qb = p.q + (size_t)b * p.T * p.ldq + head * 64;
   const bf16_t* dob = p.d_o + (size_t)b * p.T * p.lddo + head * 64;
@@ -364,7 +442,7 @@ __global__ __launch_bounds__(256) void fa_bwd_dq_kernel(FaParams p) {
   }
   float lse_q = 0.f, D_q = 0.f;
   if (qi < p.T) {
-    lse_q = p.lse[((size_t)b * p.H + head) * p.T + qi] * 1.4426950408889634f;
+    lse_q = p.lse2[((size_t)b * p.H + head) * p.T + qi];
     D_q = p.D[((size_t)b * p.H + head) * p.T + qi];
   }
   const int wg_last_q = min(p.T, qblk * 128 + 128) - 1;
@@ -394,37 +472,49 @@ __global__ __launch_bounds__(256) void fa_bwd_dq_kernel(FaParams p) {
     const char* sK = lds + (jb % NSTAGE) * (2 * TILE_BYTES);
     const char* sV = sK + TILE_BYTES;
     if (wave_on && jb * 64 <= wave_kmax) {
+      const int nkt = (jb * 64 + 32 <= wave_kmax) ? 2 : 1;
+      const bool edge = jb * 64 + 63 > p.Mv + q0 || jb * 64 + 63 >= p.S || q0 + 31 >= p.T;
       f32x16 s[2], dp[2];
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt) {
+        if (kt < nkt) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { s[kt][r] = 0.f; dp[kt][r] = 0.f; }
+          for (int r = 0; r < 16; ++r) { s[kt][r] = 0.f; dp[kt][r] = 0.f; }
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sK, 32 * kt, ks, lane), qf[ks], s[kt], 0, 0, 0);
-          dp[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sV, 32 * kt, ks, lane), dof[ks], dp[kt], 0, 0, 0);
+          for (int ks = 0; ks < 4; ++ks) {
+            s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sK, 32 * kt, ks, lane), qf[ks], s[kt], 0, 0, 0);
+            dp[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sV, 32 * kt, ks, lane), dof[ks], dp[kt], 0, 0, 0);
+          }
         }
       }
+      // dS without its factor `scale`, which the finished dQ takes once
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
+        if (kt < nkt) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = jb * 64 + 32 * kt + 8 * (r >> 2) + 4 * h32 + (r & 3);
-          const bool vis = key <= p.Mv + qi && key < p.S && qi < p.T;
-          const float pv = vis ? __builtin_amdgcn_exp2f(s[kt][r] * p.scale_log2 - lse_q) : 0.f;
-          dp[kt][r] = pv * (dp[kt][r] - D_q) * p.scale;
+          for (int r = 0; r < 16; ++r) {
+            float pv = __builtin_amdgcn_exp2f(fmaf(s[kt][r], p.scale_log2, -lse_q));
+            if (edge) {
+              const int key = jb * 64 + 32 * kt + 8 * (r >> 2) + 4 * h32 + (r & 3);
+              const bool vis = key <= p.Mv + qi && key < p.S && qi < p.T;
+              pv = vis ? pv : 0.f;
+            }
+            dp[kt][r] = pv * (dp[kt][r] - D_q);
+          }
         }
 #pragma unroll
       for (int ks2 = 0; ks2 < 4; ++ks2) {
         const int kt = ks2 >> 1, sub = ks2 & 1;
-        bf16x8 dsb = pack_acc(dp[kt], sub);
+        if (kt < nkt) {
+          bf16x8 dsb = pack_acc(dp[kt], sub);
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
-          dqT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sK, 32 * dt, 32 * kt + 16 * sub, lane), dsb, dqT[dt], 0, 0, 0);
+          for (int dt = 0; dt < 2; ++dt)
+            dqT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sK, 32 * dt, 32 * kt + 16 * sub, lane), dsb, dqT[dt], 0, 0, 0);
+        }
       }
     }
   }
-  if (qi < p.T) store_acc_row(p.dq + ((size_t)b * p.T + qi) * p.lddq + head * 64, dqT, 1.f, h32);
+  if (qi < p.T) store_acc_row(p.dq + ((size_t)b * p.T + qi) * p.lddq + head * 64, dqT, p.scale, h32);
 }
 
 // ----------------------------------------------------------------------------- dispatch
@@ -450,6 +540,7 @@ static FaParams fa_params(const AttnDesc& a) {
   p.d_o = (const bf16_t*)a.d_o; p.lddo = a.lddo; p.dq = (bf16_t*)a.dq; p.lddq = a.lddq;
   p.dk = (bf16_t*)a.dk; p.lddk = a.lddk; p.dv = (bf16_t*)a.dv; p.lddv = a.lddv;
   p.D = a.scratch;
+  p.lse2 = a.scratch ? a.scratch + (size_t)a.B * a.H * a.T : nullptr;
   return p;
 }
 
