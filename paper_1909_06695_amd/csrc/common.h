@@ -65,7 +65,12 @@ struct GemmDesc {
   void* Z; int ldz;      // EPI_GELU: written (type T); EPI_GELUGRAD: read (type T)
   float alpha;           // scales acc before the epilogue
 };
-// dtype 0: fp32 operands, 1: bf16 operands.  force_generic != 0 skips the MFMA kernel.
+// MFMA tile configurations (bf16): register-staged 128x128 (any K multiple of 8), and three
+// direct-to-LDS kernels that need K % 64 == 0 and operands under 2 GiB.
+enum { GEMM_TILE_STAGED128 = 10, GEMM_TILE_128x128 = 11, GEMM_TILE_128x64 = 12, GEMM_TILE_PIPE128 = 13 };
+// dtype 0: fp32 operands, 1: bf16 operands.  force_generic: 0 = automatic choice, 1 = the
+// plain tiled kernel, GEMM_TILE_* = that MFMA configuration where the problem admits MFMA
+// (a direct-to-LDS configuration falls back to the staged one when its conditions fail).
 hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_generic);
 // true if launch_gemm would take the MFMA path for this problem
 bool gemm_uses_mfma(int dtype, const GemmDesc& g);

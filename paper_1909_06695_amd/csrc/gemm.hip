@@ -202,23 +202,26 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
   p.kchunk = g.K; p.tilesN = 0; p.vec_epi = 0;
   if (g.accumulate && (!g.out_fp32 || g.bias || g.residual || g.epilogue != EPI_NONE)) return hipErrorInvalidValue;
 
-  if (!force_generic && gemm_uses_mfma(dtype, g)) {
+  if (force_generic != 1 && gemm_uses_mfma(dtype, g)) {
     const int oe = g.out_fp32 ? 3 : 7;   // ldc granularity for 16-byte row chunks
     p.vec_epi = aligned16(g.C) && !(g.ldc & oe) && (!g.residual || (aligned16(g.residual) && !(g.ldr & 7))) &&
                 (g.epilogue == EPI_NONE || (aligned16(g.Z) && !(g.ldz & 7)));
-    static const int forced = [] { const char* e = getenv("OURO_GEMM_TILE"); return e ? atoi(e) : -1; }();
-    int cfg = forced;
+    int cfg = force_generic >= 2 ? force_generic : -1;
     if (cfg < 0) {
-      // 128x128 tiles (8 waves) when they fill the chip at least twice over; otherwise, and for
-      // the split-K weight gradients, 128x64 tiles put more workgroups on every compute unit
+      // 128x128 tiles (8 waves, two workgroups per CU) when they fill the chip at least twice
+      // over; with one tile per CU and a long contraction the register-prefetch kernel with its
+      // four-stage ring; otherwise, and for the split-K weight gradients, 128x64 tiles, which
+      // put more workgroups on every compute unit
       const int t128 = ((g.M + 127) / 128) * ((g.N + 127) / 128);
-      cfg = (g.K % 64) != 0 ? 0 : (g.accumulate || t128 <= 384) ? 22 : 18;
+      if (g.accumulate || t128 <= 384) cfg = (!g.accumulate && t128 <= 256 && g.K >= 1024 && g.K <= 8192) ? GEMM_TILE_PIPE128 : GEMM_TILE_128x64;
+      else cfg = GEMM_TILE_128x128;
     }
     const size_t bytesA = 2 * (size_t)(g.transA ? g.K : g.M) * g.lda, bytesB = 2 * (size_t)(g.transB ? g.N : g.K) * g.ldb;
-    const bool dl = cfg >= 10 && (g.K % 64) == 0 && bytesA < (1ull << 31) && bytesB < (1ull << 31);
-    if (cfg >= 10 && !dl) cfg = 0;
-    const int BM = (cfg == 21 || cfg == 23) ? 64 : (cfg == 0 || (cfg >= 10 && cfg <= 12) || (cfg >= 16 && cfg <= 18) || cfg == 22 || (cfg >= 24 && cfg != 34)) ? 128 : 256;
-    const int BN = (cfg == 22 || cfg == 25 || cfg == 32 || cfg == 33) ? 64 : (cfg == 2 || cfg == 3 || cfg == 15 || cfg == 17 || cfg == 19) ? 256 : 128;
+    // direct global->LDS loads need whole 64-wide K tiles and 32-bit operand offsets
+    if ((g.K % 64) != 0 || bytesA >= (1ull << 31) || bytesB >= (1ull << 31)) cfg = GEMM_TILE_STAGED128;
+    if (cfg != GEMM_TILE_STAGED128 && cfg != GEMM_TILE_128x128 && cfg != GEMM_TILE_128x64 && cfg != GEMM_TILE_PIPE128)
+      return hipErrorInvalidValue;
+    const int BM = 128, BN = cfg == GEMM_TILE_128x64 ? 64 : 128;
     int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     int splits = 1;
     if (g.accumulate && tiles < 384 && g.K >= 512) {
@@ -231,13 +234,8 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
     kchunk = (kchunk + 63) / 64 * 64;
     splits = (g.K + kchunk - 1) / kchunk;
     p.kchunk = kchunk;
-    if (dl) return launch_gemm_dlds(s, p, g.transA, g.transB, splits, cfg);
-    switch (cfg) {
-      case 1: return launch_mfma_cfg<256, 128, 2, 2>(s, p, g.transA, g.transB, splits);
-      case 2: return launch_mfma_cfg<256, 256, 2, 2>(s, p, g.transA, g.transB, splits);
-      case 3: return launch_mfma_cfg<256, 256, 2, 4>(s, p, g.transA, g.transB, splits);
-      default: return launch_mfma_cfg<128, 128, 2, 2>(s, p, g.transA, g.transB, splits);
-    }
+    if (cfg != GEMM_TILE_STAGED128) return launch_gemm_dlds(s, p, g.transA, g.transB, splits, cfg);
+    return launch_mfma_cfg<128, 128, 2, 2>(s, p, g.transA, g.transB, splits);
   }
 
   dim3 grid((g.N + 63) / 64, (g.M + 63) / 64, 1), block(256);

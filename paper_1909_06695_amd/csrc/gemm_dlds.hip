@@ -149,14 +149,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dlds_kernel(GemmParams p) {
     // Before it every wave has waited for its own share of tile kt and for its LDS reads of
     // tile kt-1; after it tile kt is complete in LDS and stage (kt-1)%S may be refilled.
     __builtin_amdgcn_s_barrier();
-#if !defined(OURO_ABLATE) || OURO_ABLATE != 1
     if (kt + S - 1 < nk) issue(kt + S - 1);
-#endif
     const char* sa = lds + (kt % S) * STAGE;
     const char* sb = sa + TileA::BYTES;
-#if defined(OURO_ABLATE) && OURO_ABLATE == 2
-    if (p.alpha == 12345.f)
-#endif
     {
       // fragments of substep ks+1 are fetched before the matrix instructions of substep ks
       // are issued, so LDS latency hides behind the matrix pipe even with one wave per SIMD
@@ -355,33 +350,11 @@ hipError_t launch_pipe_cfg(hipStream_t s, GemmParams& p, int transA, int transB,
   return launch_dlds_cfg_impl<BM, BN, WM, WN, S, true>(s, p, transA, transB, splits);
 }
 
-// cfg: 10 = 128x128 S2, 11 = 128x128 S3, 12 = 128x128 S4, 13 = 256x128 (2x2 waves) S3,
-//      14 = 256x128 with 8 waves (4x2) S3, 15 = 256x256 8 waves (2x4) S2
 hipError_t launch_gemm_dlds(hipStream_t s, GemmParams& p, int transA, int transB, int splits, int cfg) {
   switch (cfg) {
-    case 10: return launch_dlds_cfg<128, 128, 2, 2, 2>(s, p, transA, transB, splits);
-    case 11: return launch_dlds_cfg<128, 128, 2, 2, 3>(s, p, transA, transB, splits);
-    case 12: return launch_dlds_cfg<128, 128, 2, 2, 4>(s, p, transA, transB, splits);
-    case 13: return launch_dlds_cfg<256, 128, 2, 2, 3>(s, p, transA, transB, splits);
-    case 14: return launch_dlds_cfg<256, 128, 4, 2, 3>(s, p, transA, transB, splits);
-    case 15: return launch_dlds_cfg<256, 256, 2, 4, 2>(s, p, transA, transB, splits);
-    case 16: return launch_dlds_cfg<128, 128, 4, 2, 2>(s, p, transA, transB, splits);
-    case 17: return launch_dlds_cfg<128, 256, 2, 4, 2>(s, p, transA, transB, splits);
-    case 18: return launch_dlds_cfg<128, 128, 2, 4, 2>(s, p, transA, transB, splits);
-    case 19: return launch_dlds_cfg<256, 256, 2, 2, 2>(s, p, transA, transB, splits);
-    case 20: return launch_dlds_cfg<256, 128, 2, 2, 2>(s, p, transA, transB, splits);
-    case 21: return launch_dlds_cfg<64, 128, 1, 4, 2>(s, p, transA, transB, splits);
-    case 22: return launch_dlds_cfg<128, 64, 4, 1, 2>(s, p, transA, transB, splits);
-    case 23: return launch_dlds_cfg<64, 128, 2, 4, 3>(s, p, transA, transB, splits);
-    case 24: return launch_dlds_cfg<128, 128, 2, 4, 3>(s, p, transA, transB, splits);
-    case 25: return launch_dlds_cfg<128, 64, 4, 1, 3>(s, p, transA, transB, splits);
-    case 26: return launch_dlds_cfg<128, 128, 2, 4, 4>(s, p, transA, transB, splits);
-    case 30: return launch_pipe_cfg<128, 128, 2, 2, 4>(s, p, transA, transB, splits);
-    case 31: return launch_pipe_cfg<128, 128, 2, 4, 4>(s, p, transA, transB, splits);
-    case 32: return launch_pipe_cfg<128, 64, 4, 1, 3>(s, p, transA, transB, splits);
-    case 33: return launch_pipe_cfg<128, 64, 4, 1, 4>(s, p, transA, transB, splits);
-    case 34: return launch_pipe_cfg<256, 128, 4, 2, 3>(s, p, transA, transB, splits);
-    case 35: return launch_pipe_cfg<128, 128, 2, 2, 3>(s, p, transA, transB, splits);
+    case GEMM_TILE_128x128: return launch_dlds_cfg<128, 128, 2, 4, 2>(s, p, transA, transB, splits);
+    case GEMM_TILE_128x64: return launch_dlds_cfg<128, 64, 4, 1, 2>(s, p, transA, transB, splits);
+    case GEMM_TILE_PIPE128: return launch_pipe_cfg<128, 128, 2, 4, 4>(s, p, transA, transB, splits);
     default: return hipErrorInvalidValue;
   }
 }

@@ -50,7 +50,8 @@ TOL = {0: 2e-5, 1: 1e-2}
 
 
 # ------------------------------------------------------------------------------- GEMM
-@pytest.mark.parametrize("dtype,force", [(0, 0), (1, 1), (1, 0)])
+# force: 0 automatic, 1 plain kernel, 10..13 one MFMA tile configuration each
+@pytest.mark.parametrize("dtype,force", [(0, 0), (1, 1), (1, 0), (1, 10), (1, 11), (1, 12), (1, 13)])
 @pytest.mark.parametrize("tA,tB", [(0, 0), (0, 1), (1, 0), (1, 1)])
 @pytest.mark.parametrize("M,N,K", [(200, 136, 328), (128, 256, 64), (72, 40, 1000), (384, 520, 96), (136, 264, 512),
                                    (392, 136, 192), (520, 392, 1024)])
@@ -66,12 +67,12 @@ def test_gemm_forms(dtype, force, tA, tB, M, N, K):
     a64, b64 = host(dA), host(dB)
     ref = (a64.T if tA else a64) @ (b64.T if tB else b64)
     assert rel_err(host(out), ref) < 2e-6
-    if dtype == 1 and not force:
+    if dtype == 1 and force != 1:
         assert L().ouro_op_gemm_uses_mfma(dtype, tA, tB, M, N, K, p(dA), dA.shape[1], p(dB), dB.shape[1]) == 1
 
 
-@pytest.mark.parametrize("dtype", [0, 1])
-def test_gemm_epilogues_and_strides(dtype):
+@pytest.mark.parametrize("dtype,force", [(0, 0), (1, 0), (1, 10), (1, 11), (1, 12), (1, 13)])
+def test_gemm_epilogues_and_strides(dtype, force):
     rng = np.random.default_rng(5)
     M, N, K = 264, 200, 136
     lda, ldb, ldc = K + 8, N + 16, N + 24
@@ -88,7 +89,7 @@ def test_gemm_epilogues_and_strides(dtype):
     pre = a64 @ b64 + bias
     # bias + GELU (writes Z) + residual
     ok(L().ouro_op_gemm(stream(), dtype, 0, 0, M, N, K, 1.0, p(dA), lda, p(dB), ldb, p(out), ldc, 0, 0, p(dbias), p(dR), N,
-                        1, p(Z), N, 0))
+                        1, p(Z), N, force))
     torch.cuda.synchronize()
     assert rel_err(host(Z), pre) < TOL[dtype]
     assert rel_err(host(out)[:, :N], O.gelu(pre) + host(dR)) < TOL[dtype]
@@ -96,7 +97,7 @@ def test_gemm_epilogues_and_strides(dtype):
     # multiply by GELU'(Z)
     out2 = torch.zeros((M, N), dtype=tdt, device="cuda")
     ok(L().ouro_op_gemm(stream(), dtype, 0, 0, M, N, K, 1.0, p(dA), lda, p(dB), ldb, p(out2), N, 0, 0, None, None, 0,
-                        2, p(Z), N, 0))
+                        2, p(Z), N, force))
     torch.cuda.synchronize()
     assert rel_err(host(out2), (a64 @ b64) * O.gelu_grad(host(Z))) < TOL[dtype]
     # accumulate (split-K path for bf16): C += A^T-form product
@@ -106,7 +107,7 @@ def test_gemm_epilogues_and_strides(dtype):
     dA2, dB2 = dev(A2, dtype), dev(B2, dtype)
     acc = torch.ones((M2, N2), dtype=torch.float32, device="cuda")
     ok(L().ouro_op_gemm(stream(), dtype, 1, 0, M2, N2, K2, 1.0, p(dA2), M2, p(dB2), N2, p(acc), N2, 1, 1, None, None, 0,
-                        0, None, 0, 0))
+                        0, None, 0, force))
     torch.cuda.synchronize()
     assert rel_err(host(acc), 1.0 + host(dA2).T @ host(dB2)) < 3e-6
 
