@@ -172,6 +172,11 @@ int ouro_debug_timing_enable(ouro_model* m, int on);
  * between iterations; it drains the extra streams. */
 int ouro_debug_set_overlap(ouro_model* m, int on);
 int ouro_debug_timing_read(ouro_model* m, int kind, double* ms, int64_t* launches, double* work);
+/* Cost of one timing bracket by itself: enqueues `reps` (at most 4096) empty brackets (two
+ * event records with nothing between them) back to back on the model's stream and returns their
+ * mean elapsed time in milliseconds. A bracket around a kernel reads that kernel's duration plus
+ * this event-marker cost, so callers subtract it to compare with a profiler's kernel durations. */
+int ouro_debug_timing_overhead(ouro_model* m, int reps, double* ms_mean);
 
 #ifdef __cplusplus
 }

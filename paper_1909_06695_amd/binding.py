@@ -71,6 +71,7 @@ def lib():
         "ouro_debug_get_hidden": (i32, [vp, i32, vp, i64]),
         "ouro_debug_timing_enable": (i32, [vp, i32]),
         "ouro_debug_set_overlap": (i32, [vp, i32]),
+        "ouro_debug_timing_overhead": (i32, [vp, i32, P(C.c_double)]),
         "ouro_debug_timing_read": (i32, [vp, i32, P(C.c_double), P(i64), P(C.c_double)]),
         # single-kernel entry points
         "ouro_op_gemm": (i32, [vp, i32, i32, i32, i32, i32, i32, f32, vp, i32, vp, i32, vp, i32, i32, i32, vp, vp,
@@ -258,6 +259,12 @@ class Model:
 
     def timing_enable(self, on):
         check(self.L.ouro_debug_timing_enable(self.h, int(on)))
+
+    def timing_overhead(self, reps=200):
+        """Mean elapsed milliseconds of an empty timing bracket (two event records)."""
+        ms = C.c_double()
+        check(self.L.ouro_debug_timing_overhead(self.h, int(reps), C.byref(ms)))
+        return ms.value
 
     def set_overlap(self, on):
         check(self.L.ouro_debug_set_overlap(self.h, int(on)))

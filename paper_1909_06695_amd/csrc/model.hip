@@ -965,6 +965,31 @@ extern "C" int ouro_debug_timing_enable(ouro_model* m, int on) {
   return OURO_OK;
 }
 
+extern "C" int ouro_debug_timing_overhead(ouro_model* m, int reps, double* ms_mean) {
+  if (!m || !ms_mean || reps < 1 || reps > 4096) return fail(OURO_E_ARG, "timing_overhead: bad argument");
+  // empty brackets (two event records, nothing between), enqueued back to back as in a
+  // timed step and read after one wait
+  const int warm = 8;
+  std::vector<hipEvent_t> ev(2 * (size_t)(reps + warm), nullptr);
+  hipError_t e = hipSuccess;
+  for (size_t i = 0; i < ev.size() && e == hipSuccess; ++i) e = hipEventCreate(&ev[i]);
+  for (int i = 0; i < reps + warm && e == hipSuccess; ++i) {
+    e = hipEventRecord(ev[2 * i], m->stream);
+    if (e == hipSuccess) e = hipEventRecord(ev[2 * i + 1], m->stream);
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
+  double total = 0;
+  for (int i = warm; i < reps + warm && e == hipSuccess; ++i) {
+    float t = 0;
+    e = hipEventElapsedTime(&t, ev[2 * i], ev[2 * i + 1]);
+    total += t;
+  }
+  for (hipEvent_t x : ev) if (x) (void)hipEventDestroy(x);
+  if (e != hipSuccess) return fail(OURO_E_HIP, "timing_overhead: %s", hipGetErrorString(e));
+  *ms_mean = total / reps;
+  return OURO_OK;
+}
+
 extern "C" int ouro_debug_set_overlap(ouro_model* m, int on) {
   if (!m) return fail(OURO_E_ARG, "model is null");
   if (m->fwd_next != 1) return fail(OURO_E_SEQUENCE, "set_overlap inside an iteration");
