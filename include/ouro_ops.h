@@ -19,9 +19,10 @@ extern "C" {
  *   (no bias / residual / epilogue then).
  * transA == 0: A is [M,K] row-major with leading dimension lda; 1: A is [K,M].
  * transB == 0: B is [K,N]; 1: B is [N,K].  force_generic: 0 = automatic kernel choice, 1 = the
- * plain tiled kernel, 10..13 = one MFMA tile configuration (10 register-staged 128x128,
+ * plain tiled kernel, 10..14 = one MFMA tile configuration (10 register-staged 128x128,
  * 11 direct-to-LDS 128x128, 12 direct-to-LDS 128x64, 13 register-prefetch 128x128 with a
- * four-stage ring; 11..13 fall back to 10 unless K % 64 == 0), for tests and tuning.
+ * four-stage ring, 14 direct-to-LDS 256x256; 11..14 fall back to 10 unless K % 64 == 0),
+ * for tests and tuning.
  * These are the layer contractions of Eq. 2 / Eq. 6 (forward, input- and weight-gradient). */
 int ouro_op_gemm(void* stream, int dtype, int transA, int transB, int M, int N, int K, float alpha,
                  const void* A, int lda, const void* B, int ldb, void* C, int ldc, int out_fp32,

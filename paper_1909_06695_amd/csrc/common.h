@@ -65,9 +65,9 @@ struct GemmDesc {
   void* Z; int ldz;      // EPI_GELU: written (type T); EPI_GELUGRAD: read (type T)
   float alpha;           // scales acc before the epilogue
 };
-// MFMA tile configurations (bf16): register-staged 128x128 (any K multiple of 8), and three
+// MFMA tile configurations (bf16): register-staged 128x128 (any K multiple of 8), and four
 // direct-to-LDS kernels that need K % 64 == 0 and operands under 2 GiB.
-enum { GEMM_TILE_STAGED128 = 10, GEMM_TILE_128x128 = 11, GEMM_TILE_128x64 = 12, GEMM_TILE_PIPE128 = 13 };
+enum { GEMM_TILE_STAGED128 = 10, GEMM_TILE_128x128 = 11, GEMM_TILE_128x64 = 12, GEMM_TILE_PIPE128 = 13, GEMM_TILE_256x256 = 14 };
 // dtype 0: fp32 operands, 1: bf16 operands.  force_generic: 0 = automatic choice, 1 = the
 // plain tiled kernel, GEMM_TILE_* = that MFMA configuration where the problem admits MFMA
 // (a direct-to-LDS configuration falls back to the staged one when its conditions fail).

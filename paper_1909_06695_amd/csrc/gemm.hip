@@ -213,15 +213,18 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
       // four-stage ring; otherwise, and for the split-K weight gradients, 128x64 tiles, which
       // put more workgroups on every compute unit
       const int t128 = ((g.M + 127) / 128) * ((g.N + 127) / 128);
-      if (g.accumulate || t128 <= 384) cfg = (!g.accumulate && t128 <= 256 && g.K >= 1024 && g.K <= 8192) ? GEMM_TILE_PIPE128 : GEMM_TILE_128x64;
+      const int t256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
+      // 256x256 tiles halve the operand bytes per flop; they pay once there are several per CU
+      // (the logits) or one per CU with a long contraction (dV_o)
+      if (!g.accumulate && (t256 >= 1024 || (t256 >= 256 && g.K >= 4096))) cfg = GEMM_TILE_256x256;
+      else if (g.accumulate || t128 <= 384) cfg = (!g.accumulate && t128 <= 256 && g.K >= 1024 && g.K <= 8192) ? GEMM_TILE_PIPE128 : GEMM_TILE_128x64;
       else cfg = GEMM_TILE_128x128;
     }
     const size_t bytesA = 2 * (size_t)(g.transA ? g.K : g.M) * g.lda, bytesB = 2 * (size_t)(g.transB ? g.N : g.K) * g.ldb;
     // direct global->LDS loads need whole 64-wide K tiles and 32-bit operand offsets
     if ((g.K % 64) != 0 || bytesA >= (1ull << 31) || bytesB >= (1ull << 31)) cfg = GEMM_TILE_STAGED128;
-    if (cfg != GEMM_TILE_STAGED128 && cfg != GEMM_TILE_128x128 && cfg != GEMM_TILE_128x64 && cfg != GEMM_TILE_PIPE128)
-      return hipErrorInvalidValue;
-    const int BM = 128, BN = cfg == GEMM_TILE_128x64 ? 64 : 128;
+    if (cfg < GEMM_TILE_STAGED128 || cfg > GEMM_TILE_256x256) return hipErrorInvalidValue;
+    const int BM = cfg == GEMM_TILE_256x256 ? 256 : 128, BN = cfg == GEMM_TILE_128x64 ? 64 : BM;
     int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     int splits = 1;
     if (g.accumulate && tiles < 384 && g.K >= 512) {

@@ -355,6 +355,7 @@ hipError_t launch_gemm_dlds(hipStream_t s, GemmParams& p, int transA, int transB
     case GEMM_TILE_128x128: return launch_dlds_cfg<128, 128, 2, 4, 2>(s, p, transA, transB, splits);
     case GEMM_TILE_128x64: return launch_dlds_cfg<128, 64, 4, 1, 2>(s, p, transA, transB, splits);
     case GEMM_TILE_PIPE128: return launch_pipe_cfg<128, 128, 2, 4, 4>(s, p, transA, transB, splits);
+    case GEMM_TILE_256x256: return launch_dlds_cfg<256, 256, 2, 4, 2>(s, p, transA, transB, splits);
     default: return hipErrorInvalidValue;
   }
 }

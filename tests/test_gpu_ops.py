@@ -50,8 +50,8 @@ TOL = {0: 2e-5, 1: 1e-2}
 
 
 # ------------------------------------------------------------------------------- GEMM
-# force: 0 automatic, 1 plain kernel, 10..13 one MFMA tile configuration each
-@pytest.mark.parametrize("dtype,force", [(0, 0), (1, 1), (1, 0), (1, 10), (1, 11), (1, 12), (1, 13)])
+# force: 0 automatic, 1 plain kernel, 10..14 one MFMA tile configuration each
+@pytest.mark.parametrize("dtype,force", [(0, 0), (1, 1), (1, 0), (1, 10), (1, 11), (1, 12), (1, 13), (1, 14)])
 @pytest.mark.parametrize("tA,tB", [(0, 0), (0, 1), (1, 0), (1, 1)])
 @pytest.mark.parametrize("M,N,K", [(200, 136, 328), (128, 256, 64), (72, 40, 1000), (384, 520, 96), (136, 264, 512),
                                    (392, 136, 192), (520, 392, 1024)])
@@ -71,7 +71,7 @@ def test_gemm_forms(dtype, force, tA, tB, M, N, K):
         assert L().ouro_op_gemm_uses_mfma(dtype, tA, tB, M, N, K, p(dA), dA.shape[1], p(dB), dB.shape[1]) == 1
 
 
-@pytest.mark.parametrize("dtype,force", [(0, 0), (1, 0), (1, 10), (1, 11), (1, 12), (1, 13)])
+@pytest.mark.parametrize("dtype,force", [(0, 0), (1, 0), (1, 10), (1, 11), (1, 12), (1, 13), (1, 14)])
 def test_gemm_epilogues_and_strides(dtype, force):
     rng = np.random.default_rng(5)
     M, N, K = 264, 200, 136
