@@ -217,6 +217,7 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
       // 256x256 tiles halve the operand bytes per flop; they pay once there are several per CU
       // (the logits) or one per CU with a long contraction (dV_o)
       if (!g.accumulate && (t256 >= 1024 || (t256 >= 256 && g.K >= 4096))) cfg = GEMM_TILE_256x256;
+      else if (g.accumulate && t128 >= 192) cfg = GEMM_TILE_128x128;   // split-K with two workgroups per CU
       else if (g.accumulate || t128 <= 384) cfg = (!g.accumulate && t128 <= 256 && g.K >= 1024 && g.K <= 8192) ? GEMM_TILE_PIPE128 : GEMM_TILE_128x64;
       else cfg = GEMM_TILE_128x128;
     }

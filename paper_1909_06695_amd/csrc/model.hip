@@ -145,7 +145,7 @@ struct ouro_model {
   char *dhb[3], *dy[2], *da, *dcat, *dr_t;   // layer l reads dhb[l % 3], writes dhb[(l + 2) % 3]
   // gradients that the weight-gradient GEMMs read on the side stream: two sets, by layer parity
   char *ds2[2], *dz[2], *ds1[2], *dqkv[2];
-  float *attn_scratch, *dr_f32, *dbg_f32;
+  float *attn_scratch, *dr_f32, *dbg_f32, *dh_f32;
   size_t dbg_floats;
   // iteration state
   int64_t t;
@@ -312,6 +312,7 @@ static size_t lay_out(ouro_model& m, char* base) {
   m.dbg_floats = N * d > B * M * d ? N * d : B * M * d;
   if (m.dbg_floats < S * d) m.dbg_floats = S * d;
   m.dbg_f32 = (float*)P(m.dbg_floats * 4);
+  m.dh_f32 = c.dtype == 1 ? (float*)P(N * d * 4) : nullptr;
   return bp.off;
 }
 
@@ -733,7 +734,18 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
       RUN(run_gemm(m, g));
     }
     m->tags[K + 1][0] = m->t;
-    RUN(run_gemm(m, gd(m->G, m->ldv, 0, m->vT(), d, 0, m->dhb[lastl % 3], d, N, d, V)));
+    GemmDesc gh = gd(m->G, m->ldv, 0, m->vT(), d, 0, m->dhb[lastl % 3], d, N, d, V);
+    if (c.dtype == 1 && gemm_uses_mfma(c.dtype, gh) && V >= 8192) {
+      // The contraction runs over the whole vocabulary onto a narrow output: split it over
+      // the grid (two workgroups per CU instead of one), adding into an fp32 buffer that is
+      // then rounded to the activation type.
+      HIPCHK(launch_fill_zero(m->stream, m->dh_f32, (size_t)N * d * 4));
+      gh.C = m->dh_f32; gh.out_fp32 = 1; gh.accumulate = 1;
+      RUN(run_gemm(m, gh));
+      HIPCHK(launch_convert(m->stream, c.dtype, m->dhb[lastl % 3], m->dh_f32, (size_t)N * d));
+    } else {
+      RUN(run_gemm(m, gh));
+    }
   }
   // layer l reads its output gradient from dhb[l % 3] and writes its input gradient to dhb[(l + 2) % 3]:
   // three buffers, so that side-stream readers of layer l's input are two layers away from its next writer
