@@ -138,7 +138,8 @@ struct ouro_model {
   float* pe;                      // [T, d] fp32 (absolute mode)
   char* rtab;                     // [S, d] distance sinusoids, type T (relative mode)
   char* G;                        // [N, ldv] type T: logits, then overwritten by d loss / d logits
-  int ldv;                        // vocab rounded up to 8 (16-byte rows)
+  int ldv;                        // vocab rounded up to 64: leading dimension of G and, in bf16 mode, the
+                                  // extent the two contractions over / onto the vocabulary run with (padding is zero)
   float *lse_ce, *rowloss, *loss;
   int* flag;
   // backward scratch
@@ -235,6 +236,7 @@ static size_t lay_out(ouro_model& m, char* base) {
   const int K = c.n_module, L = c.n_layer;
   const size_t d = c.d_model, F = c.d_ff, V = c.vocab, T = c.seq_len, M = c.mem_len, B = c.batch;
   const size_t N = B * T, S = T + M, es = m.esz;
+  const size_t vpad = (V + 63) / 64 * 64;
   Bump bp;
   auto P = [&](size_t bytes) { return base + bp.take(bytes); };
   m.count.assign(K + 1, 0);
@@ -258,7 +260,8 @@ static size_t lay_out(ouro_model& m, char* base) {
   m.adam_m.assign(K + 1, nullptr); m.adam_v.assign(K + 1, nullptr);
   for (int k = 0; k <= K; ++k) {
     m.master[k] = (float*)P(m.count[k] * 4);
-    if (c.dtype == 1) m.shadow[k] = (bf16_t*)P(m.count[k] * 2);
+    // V's bf16 copy carries zero rows up to the padded vocabulary (never written after the arena clear)
+    if (c.dtype == 1) m.shadow[k] = (bf16_t*)P((k == 0 ? vpad * d : (size_t)m.count[k]) * 2);
     if (c.optimizer == 1) {
       m.adam_m[k] = (float*)P(m.count[k] * 4);
       m.adam_v[k] = (float*)P(m.count[k] * 4);
@@ -268,6 +271,7 @@ static size_t lay_out(ouro_model& m, char* base) {
   for (int id = 0; id <= K + 1; ++id) {
     m.gcount[id] = (id == 0 || id == K + 1) ? m.count[0] : m.count[id];
     m.gstride[id] = (m.gcount[id] + 63) / 64 * 64;
+    if (id == K + 1 && (int64_t)(vpad * d) > m.gstride[id]) m.gstride[id] = (int64_t)(vpad * d);   // dV_o rows of the padding
     ouro_ring_depth(K, id, &m.depth[id]);
     m.ring[id] = (float*)P((size_t)m.depth[id] * m.gstride[id] * 4);
   }
@@ -293,7 +297,7 @@ static size_t lay_out(ouro_model& m, char* base) {
   m.hL = P(N * d * es);
   m.pe = c.rel_pos ? nullptr : (float*)P(T * d * 4);
   m.rtab = c.rel_pos ? P(S * d * es) : nullptr;
-  m.ldv = (int)((V + 7) / 8 * 8);
+  m.ldv = (int)vpad;
   m.G = P(N * (size_t)m.ldv * es);
   m.lse_ce = (float*)P(N * 4);
   m.rowloss = (float*)P(N * 4);
@@ -724,7 +728,10 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
   if (k == K) {
     // Eq. 7 (right): dV_o = G^T h_L ; error gradient dh_L = G V
     float* dvo = m->slot_ptr(K + 1, 0);
-    GemmDesc g = gd(m->G, m->ldv, 1, m->hL, d, 0, dvo, d, V, d, N);
+    // bf16 mode: both contractions run over the padded vocabulary (G's padding columns and
+    // V's padding rows are zero), which keeps them on the MFMA kernels for any vocabulary size
+    const int Vx = c.dtype == 1 ? m->ldv : V;
+    GemmDesc g = gd(m->G, m->ldv, 1, m->hL, d, 0, dvo, d, Vx, d, N);
     g.out_fp32 = 1;
     if (m->use_side) {        // independent of the error-gradient chain: beside dh_L = G V
       HIPCHK(hipEventRecord(m->ev_ready[0], m->stream));
@@ -734,7 +741,7 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
       RUN(run_gemm(m, g));
     }
     m->tags[K + 1][0] = m->t;
-    GemmDesc gh = gd(m->G, m->ldv, 0, m->vT(), d, 0, m->dhb[lastl % 3], d, N, d, V);
+    GemmDesc gh = gd(m->G, m->ldv, 0, m->vT(), d, 0, m->dhb[lastl % 3], d, N, d, Vx);
     if (c.dtype == 1 && gemm_uses_mfma(c.dtype, gh) && V >= 8192) {
       // The contraction runs over the whole vocabulary onto a narrow output: split it over
       // the grid (two workgroups per CU instead of one), adding into an fp32 buffer that is

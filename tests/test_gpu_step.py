@@ -140,6 +140,14 @@ def test_bf16_small_sgd():
     run_both(c, steps=3, lr=0.05, seed=9, std=0.05, perturb=0.05, tol=2e-2)
 
 
+def test_bf16_odd_vocab_adam():
+    """bf16 mode with a vocabulary that is no multiple of 8 (the zero-padded vocabulary keeps the
+    dh = G V and dV_o = G^T h contractions on the MFMA kernels) and K = 3 with Adam."""
+    c = dict(n_layer=3, d_model=128, n_head=2, d_head=64, d_ff=256, vocab=1001, seq_len=96, mem_len=0, batch=3,
+             n_module=3, rel_pos=0, dtype=1, optimizer=1, embed_warm_mode=0)
+    run_both(c, steps=5, lr=1e-3, seed=21, std=0.05, perturb=0.05, tol=2e-2)
+
+
 def test_staleness_plumbing_bit_exact():
     """Integer-tagged gradients through inject_grad: final weights have a closed form that
     fp32 represents exactly; slot tags and reads follow Eq. 8-9 at every iteration."""
