@@ -267,29 +267,6 @@ __global__ __launch_bounds__(256) void fa_fwd_kernel(FaParams p) {
   }
 }
 
-// D[b,h,i] = sum_c dO[i,c] * O[i,c]; lse2 = lse / ln 2
-__global__ __launch_bounds__(256) void fa_bwd_prep_kernel(FaParams p) {
-  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-  const size_t total = (size_t)p.B * p.T * p.H;
-  if (idx >= total) return;
-  const int head = (int)(idx % p.H);
-  const size_t n = idx / p.H;                 // b*T + i
-  const bf16_t* o = p.o + n * p.ldo + head * 64;
-  const bf16_t* d = p.d_o + n * p.lddo + head * 64;
-  float acc = 0.f;
-#pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    bf16x8 a = as_bf16x8(*reinterpret_cast<const uint4*>(o + 8 * c));
-    bf16x8 g = as_bf16x8(*reinterpret_cast<const uint4*>(d + 8 * c));
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)g[e];
-  }
-  const int b = (int)(n / p.T), i = (int)(n % p.T);
-  const size_t r = ((size_t)b * p.H + head) * p.T + i;
-  p.D[r] = acc;
-  p.lse2[r] = p.lse[r] * 1.4426950408889634f;    // base-2 log-sum-exp for the gradient kernels
-}
-
 // ------------------------------------------------------------------------ dK, dV kernel
 // grid (ceil(S/128), H, B); 4 waves x 32 keys; query blocks of 64: S = Q K^T and dP = dO V^T
 // read Q / dO rows, dV^T += dO^T P and dK^T += Q^T dS read the same tiles transposed.
@@ -440,10 +417,26 @@ __global__ __launch_bounds__(256) void fa_bwd_dq_kernel(FaParams p) {
     qf[ks] = as_bf16x8(t0);
     dof[ks] = as_bf16x8(t1);
   }
+  // D = sum_c dO[i,c] O[i,c] and the base-2 log-sum-exp of the lane's query; both are also
+  // left in the scratch arrays for the dK/dV kernel, which runs after this one
   float lse_q = 0.f, D_q = 0.f;
-  if (qi < p.T) {
-    lse_q = p.lse2[((size_t)b * p.H + head) * p.T + qi];
-    D_q = p.D[((size_t)b * p.H + head) * p.T + qi];
+  {
+    const bf16_t* ob = p.o + (size_t)b * p.T * p.ldo + head * 64;
+    float part = 0.f;
+    if (qi < p.T) {
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        bf16x8 of = as_bf16x8(*reinterpret_cast<const uint4*>(ob + (size_t)qi * p.ldo + 16 * ks + 8 * h32));
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part += (float)of[e] * (float)dof[ks][e];
+      }
+    }
+    D_q = part + __shfl_xor(part, 32, 64);
+    if (qi < p.T) {
+      const size_t r = ((size_t)b * p.H + head) * p.T + qi;
+      lse_q = p.lse[r] * 1.4426950408889634f;
+      if (h32 == 0) { p.D[r] = D_q; p.lse2[r] = lse_q; }
+    }
   }
   const int wg_last_q = min(p.T, qblk * 128 + 128) - 1;
   const int kend = min(p.S, p.Mv + wg_last_q + 1);
@@ -553,14 +546,11 @@ hipError_t launch_attn_fwd_mfma(hipStream_t s, const AttnDesc& a) {
 
 hipError_t launch_attn_bwd_mfma(hipStream_t s, const AttnDesc& a) {
   FaParams p = fa_params(a);
-  const size_t rows = (size_t)a.B * a.T * a.H;
-  hipLaunchKernelGGL(fa_bwd_prep_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, s, p);
+  // the dQ kernel also produces the row sums D and the base-2 log-sum-exp the dK/dV kernel reads
+  hipLaunchKernelGGL(fa_bwd_dq_kernel, dim3((a.T + 127) / 128, a.H, a.B), dim3(256), 0, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(fa_bwd_dkv_kernel, dim3((a.S + 127) / 128, a.H, a.B), dim3(256), 0, s, p);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(fa_bwd_dq_kernel, dim3((a.T + 127) / 128, a.H, a.B), dim3(256), 0, s, p);
   return hipGetLastError();
 }
 
