@@ -7,14 +7,15 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libouro.so")
-SOURCES = ["gemm.hip", "gemm_dlds.hip", "attention.hip", "attention_plain.hip", "attention_mfma.hip", "rowops.hip",
+SOURCES = ["gemm.hip", "gemm_dlds.hip", "attention.hip", "attention_plain.hip", "attention_mfma.hip", "attention_xl.hip", "rowops.hip",
            "model.hip", "ops_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 # The attention kernels run elementwise arithmetic on matrix-instruction results every
 # iteration: with the accumulators in ordinary vector registers no copies to and from the
 # accumulator file are needed.
-EXTRA = {"attention_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+EXTRA = {"attention_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+         "attention_xl.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def build(verbose=True):

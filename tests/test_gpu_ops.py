@@ -187,6 +187,14 @@ def test_attention_mfma_kernel(B, H, T, Mv):
     _attn_case(1, B, H, T, Mv, 64, 0, seed=100 + T + Mv, force=0)
 
 
+@pytest.mark.parametrize("B,H,T,Mv", [(2, 2, 128, 0), (1, 3, 200, 0), (2, 1, 96, 40), (1, 2, 384, 384), (1, 1, 33, 0),
+                                      (1, 2, 300, 77), (2, 2, 150, 150)])
+def test_attention_xl_mfma_kernel(B, H, T, Mv):
+    """Fused matrix-core kernels with the relative-position term (bf16, head size 64): with and
+    without memory, several query/key blocks, ragged tails."""
+    _attn_case(1, B, H, T, Mv, 64, 1, seed=200 + T + Mv, force=0)
+
+
 # ------------------------------------------------------------------ row-wise kernels
 @pytest.mark.parametrize("dtype", [0, 1])
 @pytest.mark.parametrize("rows,d", [(37, 64), (130, 512), (9, 410), (5, 1024), (3, 4100)])

@@ -148,6 +148,14 @@ def test_bf16_odd_vocab_adam():
     run_both(c, steps=5, lr=1e-3, seed=21, std=0.05, perturb=0.05, tol=2e-2)
 
 
+def test_xl_bf16_mfma_path_memory_carry():
+    """Transformer-XL blocks in bf16 with head size 64 (the fused relative-position kernels),
+    memory shorter than, equal to and rolling past the segment over four steps."""
+    c = dict(n_layer=2, d_model=128, n_head=2, d_head=64, d_ff=256, vocab=512, seq_len=80, mem_len=112, batch=2,
+             n_module=2, rel_pos=1, dtype=1, optimizer=0, embed_warm_mode=1)
+    run_both(c, steps=4, lr=0.05, seed=31, std=0.05, perturb=0.05, tol=2e-2)
+
+
 def test_staleness_plumbing_bit_exact():
     """Integer-tagged gradients through inject_grad: final weights have a closed form that
     fp32 represents exactly; slot tags and reads follow Eq. 8-9 at every iteration."""
