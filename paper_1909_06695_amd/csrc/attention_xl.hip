@@ -432,6 +432,8 @@ __global__ __launch_bounds__(256) void fa_xl_dkv_kernel(FaParams p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dkT[dt][r] = 0.f; dvT[dt][r] = 0.f; }
   float tsum = 0.f;                                        // sum over queries of dS(i, key), this half's rows
+  f32x16 carry[2];                                         // dr tile that the next query block continues
+  bool have_carry = false;
   const int ib0 = max(0, K0 - p.Mv) / 64;
   const int nib = (p.T + 63) / 64;
   const int nit = nib - ib0;
@@ -542,14 +544,16 @@ __global__ __launch_bounds__(256) void fa_xl_dkv_kernel(FaParams p) {
           }
         }
       }
-      // dS back into the distance layout (same rotation reversed), then dr = dS_delta^T (q + v)
+      // dS back into the distance layout (same rotation reversed), then dr = dS_delta^T (q + v).
+      // The window moves up by 64 distances per query block, so this block's tile 2 is the
+      // next block's tile 0: it stays in registers and only tiles 0 and 1 go to memory.
 #pragma unroll
       for (int t = 0; t < 3; ++t) {
         f32x16 dr[2];
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) dr[dt][r] = 0.f;
+          for (int r = 0; r < 16; ++r) dr[dt][r] = (t == 0 && have_carry) ? carry[dt][r] : 0.f;
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
           const int qt = t - tt;                           // query tile whose rotation lands in tile t
@@ -573,15 +577,21 @@ __global__ __launch_bounds__(256) void fa_xl_dkv_kernel(FaParams p) {
             }
           }
         }
-        // rows = distances dmin + 32 t + acc_row, lanes = features 32 dt + l32
+        if (t == 2 && it + 1 < nit) {
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
+          for (int dt = 0; dt < 2; ++dt) carry[dt] = dr[dt];
+        } else {
+          // rows = distances dmin + 32 t + acc_row, lanes = features 32 dt + l32
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int delta = dmin + 32 * t + acc_row(r, h32);
-            if (delta >= 0 && delta < p.S) unsafeAtomicAdd(p.dr + (size_t)delta * HD + head * 64 + 32 * dt + l32, dr[dt][r] * p.scale);
-          }
+          for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int delta = dmin + 32 * t + acc_row(r, h32);
+              if (delta >= 0 && delta < p.S) unsafeAtomicAdd(p.dr + (size_t)delta * HD + head * 64 + 32 * dt + l32, dr[dt][r] * p.scale);
+            }
+        }
       }
+      have_carry = it + 1 < nit;
     }
   }
   if (key < p.S) {
