@@ -143,10 +143,10 @@ struct ouro_model {
   float *lse_ce, *rowloss, *loss;
   int* flag;
   // backward scratch
-  char *dhb[3], *dy[2], *da, *dcat, *dr_t;   // layer l reads dhb[l % 3], writes dhb[(l + 2) % 3]
+  char *dhb[3], *dy[2], *da, *dcat, *dr_t[2];   // layer l reads dhb[l % 3], writes dhb[(l + 2) % 3]
   // gradients that the weight-gradient GEMMs read on the side stream: two sets, by layer parity
   char *ds2[2], *dz[2], *ds1[2], *dqkv[2];
-  float *attn_scratch, *dr_f32, *dbg_f32, *dh_f32;
+  float *attn_scratch, *dr_f32[2], *dbg_f32, *dh_f32;
   size_t dbg_floats;
   // iteration state
   int64_t t;
@@ -310,8 +310,10 @@ static size_t lay_out(ouro_model& m, char* base) {
     m.ds1[p2] = P(N * d * es); m.dqkv[p2] = P(qkv_elems * es);
   }
   m.dcat = c.rel_pos ? P(B * S * d * es) : nullptr;
-  m.dr_t = c.rel_pos ? P(S * d * es) : nullptr;
-  m.dr_f32 = c.rel_pos ? (float*)P(S * d * 4) : nullptr;
+  for (int p2 = 0; p2 < 2; ++p2) {
+    m.dr_t[p2] = c.rel_pos ? P(S * d * es) : nullptr;
+    m.dr_f32[p2] = c.rel_pos ? (float*)P(S * d * 4) : nullptr;
+  }
   m.attn_scratch = (float*)P(attn_bwd_scratch_floats(c.batch, c.n_head, c.seq_len, (int)S, c.d_head) * 4);
   m.dbg_floats = N * d > B * M * d ? N * d : B * M * d;
   if (m.dbg_floats < S * d) m.dbg_floats = S * d;
@@ -582,7 +584,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   const int Mv = m->mem_valid, S = Mv + T;
   hipStream_t st = m->stream;
   const int ps = l & 1;                               // buffer set of this layer
-  const bool side = m->use_side && !c.rel_pos;
+  const bool side = m->use_side;
   hipStream_t sw = side ? m->side : st;               // stream of the weight-gradient work
   char* ds2 = m->ds2[ps]; char* dz = m->dz[ps]; char* ds1 = m->ds1[ps]; char* dqkv = m->dqkv[ps];
   char* dy = m->dy[ps];
@@ -671,26 +673,28 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     a.q = q; a.ldq = d; a.k = kv; a.ldk = 2 * d; a.v = kv + (size_t)d * es; a.ldv = 2 * d;
     a.rel = 1; a.u = m->wT(l, o.u); a.vb = m->wT(l, o.v); a.r = b.r; a.ldr = d;
     a.dq = dq; a.lddq = d; a.dk = dkv; a.lddk = 2 * d; a.dv = dkv + (size_t)d * es; a.lddv = 2 * d;
-    a.du = gslot + o.u; a.dvb = gslot + o.v; a.dr = m->dr_f32;
-    HIPCHK(launch_fill_zero(st, m->dr_f32, (size_t)S * d * 4));
+    float* drf = m->dr_f32[ps];
+    a.du = gslot + o.u; a.dvb = gslot + o.v; a.dr = drf;
+    HIPCHK(launch_fill_zero(st, drf, (size_t)S * d * 4));
     HIPCHK(launch_attn_bwd(st, c.dtype, a, 0));
-    // dW_r = R^T dr
-    const void* drp = m->dr_f32;
-    if (c.dtype == 1) { HIPCHK(launch_convert(st, 1, m->dr_t, m->dr_f32, (size_t)S * d)); drp = m->dr_t; }
+    const void* drp = drf;
+    if (c.dtype == 1) { HIPCHK(launch_convert(st, 1, m->dr_t[ps], drf, (size_t)S * d)); drp = m->dr_t[ps]; }
+    RUN(ready(3));
+    // weight gradients: dW_r = R^T dr, dW_q = x^T dq, dW_kv = [mem ; x]^T dkv
     {
       GemmDesc g = gd(m->rtab, d, 1, drp, d, 0, gslot + o.W_r, d, d, d, S);
       g.out_fp32 = 1; g.accumulate = 1;
-      RUN(run_gemm(m, g));
+      RUN(run_gemm_on(m, g, sw));
     }
     {
       GemmDesc g = gd(b.x, d, 1, dq, d, 0, gslot + o.W_qkv, 3 * d, d, d, N);
       g.out_fp32 = 1; g.accumulate = 1;
-      RUN(run_gemm(m, g));
+      RUN(run_gemm_on(m, g, sw));
     }
     {
       GemmDesc g = gd(cat, d, 1, dkv, 2 * d, 0, gslot + o.W_qkv + d, 3 * d, d, 2 * d, B * S);
       g.out_fp32 = 1; g.accumulate = 1;
-      RUN(run_gemm(m, g));
+      RUN(run_gemm_on(m, g, sw));
     }
     {
       GemmDesc g = gd(dq, d, 0, m->wT(l, o.W_qkv), 3 * d, 1, dx, d, N, d, d);
