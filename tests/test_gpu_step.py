@@ -156,6 +156,55 @@ def test_xl_bf16_mfma_path_memory_carry():
     run_both(c, steps=4, lr=0.05, seed=31, std=0.05, perturb=0.05, tol=2e-2)
 
 
+@pytest.mark.parametrize("rel_pos,mem_len", [(0, 0), (1, 96)])
+def test_stream_overlap_matches_one_stream(rel_pos, mem_len):
+    """The three-stream schedule of step() (weight gradients and updates beside the
+    error-gradient chain) against the same steps on one stream: equal up to the order of fp32
+    atomic additions, over more iterations than the rings are deep."""
+    c = dict(n_layer=4, d_model=128, n_head=2, d_head=64, d_ff=256, vocab=512, seq_len=96, mem_len=mem_len, batch=2,
+             n_module=4, rel_pos=rel_pos, dtype=1, optimizer=1, embed_warm_mode=0)
+    steps, lr = 7, 1e-3
+    blobs = S.init_params(c, seed=5, std=0.05, perturb=0.05)
+    tok, tgt = S.token_batches(c["vocab"], c["batch"], c["seq_len"], steps, 1.1, 6, contiguous=bool(mem_len))
+    dtok = torch.from_numpy(tok).cuda(); dtgt = torch.from_numpy(tgt).cuda()
+    out = []
+    for overlap in (True, False):
+        m = P().create_model(**c)
+        for g in range(c["n_module"] + 1):
+            m.set_params(g, blobs[g])
+        m.set_overlap(overlap)
+        losses = [m.step(dtok[t], dtgt[t], lr) for t in range(steps)]
+        out.append((losses, [m.get_params(g) for g in range(c["n_module"] + 1)]))
+        m.close()
+    (la, wa), (lb, wb) = out
+    assert np.allclose(la, lb, rtol=1e-4, atol=0)
+    for a, b in zip(wa, wb):
+        # Adam turns a last-bit difference of a tiny gradient into a step of up to lr
+        assert np.abs(a - b).max() <= 2 * lr * steps
+        assert rel_err(a, b) < 2e-3
+
+
+def test_timing_hooks():
+    """Per-launch timing brackets and the empty-bracket cost: plausible, positive numbers."""
+    c = dict(S.CONFIGS["cfg1"])
+    m = P().create_model(**c)
+    blobs = S.init_params(c, seed=0)
+    for g in range(c["n_module"] + 1):
+        m.set_params(g, blobs[g])
+    tok, tgt = S.token_batches(c["vocab"], c["batch"], c["seq_len"], 1, c["zipf_s"], c["seed"], False)
+    dtok = torch.from_numpy(tok).cuda(); dtgt = torch.from_numpy(tgt).cuda()
+    m.set_overlap(False)
+    m.timing_enable(True)
+    for _ in range(3):
+        m.step(dtok[0], dtgt[0], c["lr"])
+    ms, n, work = m.timing_read(1)                      # update kernel: bytes
+    assert n > 0 and ms > 0 and work > 0
+    m.timing_enable(False)
+    ovh = m.timing_overhead(50)
+    assert 0 < ovh < 1.0                                 # milliseconds per empty bracket
+    m.close()
+
+
 def test_staleness_plumbing_bit_exact():
     """Integer-tagged gradients through inject_grad: final weights have a closed form that
     fp32 represents exactly; slot tags and reads follow Eq. 8-9 at every iteration."""
