@@ -51,13 +51,15 @@ int ouro_op_attention_bwd(void* stream, int dtype, int B, int H, int T, int S, i
                           int ldr, float* du, float* dvb, float* dr, float* scratch, int force_generic);
 size_t ouro_op_attention_bwd_scratch(int B, int H, int T, int S, int dh);
 
-/* y = (x-mean)*rstd*g + b over rows of d (biased variance, eps 1e-5); g, b, mean, rstd fp32. */
+/* y = (x-mean)*rstd*g + b over rows of d (biased variance, eps 1e-5); g, b, mean, rstd fp32.
+ * dn in (0, d): the statistics run over the first dn columns only and the other d-dn columns are
+ * zero padding (x, g, b zero there; y then is zero there too).  dn = 0 means dn = d. */
 int ouro_op_layernorm_fwd(void* stream, int dtype, const void* x, const float* g, const float* b,
-                          void* y, float* mean, float* rstd, int rows, int d);
-/* dx (T) and dg, db (fp32 [d], overwritten). */
+                          void* y, float* mean, float* rstd, int rows, int d, int dn);
+/* dx (T) and dg, db (fp32 [d], overwritten).  dn as above; dx is zero in the padding columns. */
 int ouro_op_layernorm_bwd(void* stream, int dtype, const void* dy, const void* x, const float* g,
                           const float* mean, const float* rstd, void* dx, float* dg, float* db,
-                          int rows, int d);
+                          int rows, int d, int dn);
 /* out[c] = sum_r x[r,c]  (fp32 [cols], overwritten). */
 int ouro_op_colsum(void* stream, int dtype, const void* x, int ldx, float* out, int rows, int cols);
 /* h[n,:] = scale*V[tok[n],:] (+ pe[n%T,:], fp32, may be NULL).  *flag (device int) gets bit 0 set

@@ -83,8 +83,8 @@ def lib():
                                         i32, vp, vp, i32, vp, i32, vp, i32, vp, i32, i32, vp, vp, vp, i32, vp, vp,
                                         vp, vp, i32]),
         "ouro_op_attention_bwd_scratch": (sz, [i32, i32, i32, i32, i32]),
-        "ouro_op_layernorm_fwd": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, i32, i32]),
-        "ouro_op_layernorm_bwd": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32]),
+        "ouro_op_layernorm_fwd": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32]),
+        "ouro_op_layernorm_bwd": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32]),
         "ouro_op_colsum": (i32, [vp, i32, vp, i32, vp, i32, i32]),
         "ouro_op_embed_fwd": (i32, [vp, i32, vp, vp, vp, vp, i32, i32, i32, i32, f32, vp]),
         "ouro_op_embed_bwd": (i32, [vp, i32, vp, vp, vp, i32, i32, i32, f32]),

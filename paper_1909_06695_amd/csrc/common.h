@@ -107,12 +107,15 @@ hipError_t launch_attn_bwd(hipStream_t s, int dtype, const AttnDesc& a, int forc
 
 // -------------------------------------------------------------------- row-wise kernels
 // y = LN(x) * g + b over rows of d elements (biased variance, eps 1e-5); saves mean, rstd.
+// Rows are d wide; the statistics run over the first dn columns (dn = 0: all d).  With dn < d the
+// remaining columns are zero padding: they must hold zero scale and shift, and the input
+// gradient is written as zero there.
 hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, const void* x, const float* g, const float* b,
-                                void* y, float* mean, float* rstd, int rows, int d);
+                                void* y, float* mean, float* rstd, int rows, int d, int dn = 0);
 // dx from dy, x, stats; dg/db (fp32) are accumulated into (caller zeroes). dg == nullptr: dx only.
 hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const float* g,
                                 const float* mean, const float* rstd, void* dx, float* dg, float* db,
-                                int rows, int d);
+                                int rows, int d, int dn = 0);
 // dg[c] += sum_r dy*xhat, db[c] += sum_r dy alone (any stream that sees dy, x and the stats)
 hipError_t launch_layernorm_bwd_params(hipStream_t s, int dtype, const void* dy, const void* x, const float* mean,
                                        const float* rstd, float* dg, float* db, int rows, int d);

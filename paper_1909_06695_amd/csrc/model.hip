@@ -64,17 +64,18 @@ extern "C" int ouro_slot_index(int K, int id, int64_t t, int write, int64_t* slo
 struct LayerOff {   // element offsets inside a module blob
   size_t W_qkv, W_o, W_r, u, v, ln1_g, ln1_b, W_1, b_1, W_2, b_2, ln2_g, ln2_b, end;
 };
-static LayerOff layer_offsets(const ouro_config& c, size_t base) {
-  const size_t d = c.d_model, F = c.d_ff;
+// Offsets of one layer's tensors, in the documented order, for a model width d, a joint width
+// hd of all heads (n_head * d_head) and an inner width F.
+static LayerOff layer_offsets(bool rel, size_t d, size_t hd, size_t F, size_t base) {
   LayerOff o;
   size_t p = base;
-  o.W_qkv = p; p += d * 3 * d;
-  o.W_o = p; p += d * d;
+  o.W_qkv = p; p += d * 3 * hd;
+  o.W_o = p; p += hd * d;
   o.W_r = o.u = o.v = 0;
-  if (c.rel_pos) {
-    o.W_r = p; p += d * d;
-    o.u = p; p += d;
-    o.v = p; p += d;
+  if (rel) {
+    o.W_r = p; p += d * hd;
+    o.u = p; p += hd;
+    o.v = p; p += hd;
   }
   o.ln1_g = p; p += d;
   o.ln1_b = p; p += d;
@@ -87,6 +88,15 @@ static LayerOff layer_offsets(const ouro_config& c, size_t base) {
   o.end = p;
   return o;
 }
+
+// One tensor of a parameter group: where it sits in the caller's blob (rows x cols, dense) and in
+// the stored one (leading dimension pcols).  A "head" axis runs over n_head slices of d_head
+// elements, stored d_head_stored apart.
+struct TensorMap {
+  size_t loff, poff;
+  int rows, cols, pcols;
+  bool row_heads, col_heads;
+};
 
 struct LayerBuf {   // saved activations of one layer (element type T unless noted)
   char* x;          // input [N, d]
@@ -117,7 +127,16 @@ struct ouro_model {
   std::vector<int> lpm;          // layers per module
   std::vector<int> first_layer;  // first layer of module k (index k-1), plus end
   std::vector<int> layer_mod;    // module (1..K) of each layer
-  std::vector<LayerOff> loff;    // per layer, offsets inside its module blob
+  std::vector<LayerOff> loff;    // per layer, offsets inside its module's stored blob
+  // Stored widths.  bf16 mode with d_head <= 64 stores every tensor with d_head rounded up to
+  // 64, d_model and d_ff rounded up to multiples of 64, the padding zero: the contractions and
+  // the attention then run on the MFMA kernels for any such shape.  Zero padding is preserved
+  // by every step (a zero weight with a zero gradient stays zero under SGD and Adam), so the
+  // results in the unpadded positions are those of the unpadded model.
+  bool padded;
+  int pd, pdh, phd, pF;           // stored d_model, d_head, n_head * d_head, d_ff
+  std::vector<std::vector<TensorMap>> tmap;   // per group 0..K
+  std::vector<int64_t> pcount;    // stored elements per group
   hipStream_t stream;
   char* arena;
   size_t bytes;
@@ -128,7 +147,7 @@ struct ouro_model {
   std::vector<float*> master, adam_m, adam_v;
   std::vector<bf16_t*> shadow;
   // gradient stores 0..K+1
-  std::vector<int64_t> gcount, gstride, depth;   // elements per gradient, slot stride (256-byte multiple)
+  std::vector<int64_t> gcount, gstride, depth;   // elements per gradient (caller's), slot stride (stored, 256-byte multiple)
   std::vector<float*> ring;
   std::vector<std::vector<int64_t>> tags;
   std::vector<int64_t> last_slot, last_tau;
@@ -234,61 +253,92 @@ static int validate(const ouro_config* c, std::vector<int>& lpm) {
 static size_t lay_out(ouro_model& m, char* base) {
   const ouro_config& c = m.cfg;
   const int K = c.n_module, L = c.n_layer;
-  const size_t d = c.d_model, F = c.d_ff, V = c.vocab, T = c.seq_len, M = c.mem_len, B = c.batch;
+  const size_t V = c.vocab, T = c.seq_len, M = c.mem_len, B = c.batch;
   const size_t N = B * T, S = T + M, es = m.esz;
   const size_t vpad = (V + 63) / 64 * 64;
+  const size_t dl = c.d_model, Fl = c.d_ff, dhl = c.d_head, H = c.n_head;   // the caller's widths
+  auto up64 = [](size_t x) { return (x + 63) / 64 * 64; };
+  m.padded = c.dtype == 1 && dhl <= 64 && (dhl != 64 || dl % 64 || Fl % 64);
+  m.pd = (int)(m.padded ? up64(dl) : dl);
+  m.pdh = (int)(m.padded ? 64 : dhl);
+  m.phd = (int)(H * m.pdh);
+  m.pF = (int)(m.padded ? up64(Fl) : Fl);
+  const size_t d = m.pd, F = m.pF, hd = m.phd;                              // stored widths from here on
   Bump bp;
   auto P = [&](size_t bytes) { return base + bp.take(bytes); };
-  m.count.assign(K + 1, 0);
-  m.count[0] = (int64_t)(V * d);
+  m.count.assign(K + 1, 0); m.pcount.assign(K + 1, 0);
+  m.count[0] = (int64_t)(V * dl); m.pcount[0] = (int64_t)(V * d);
+  m.tmap.assign(K + 1, {});
+  m.tmap[0].push_back({0, 0, (int)V, (int)dl, (int)d, false, false});
   m.first_layer.assign(K + 1, 0);
   m.layer_mod.assign(L, 0);
   m.loff.resize(L);
   int l = 0;
   for (int k = 1; k <= K; ++k) {
     m.first_layer[k - 1] = l;
-    size_t off = 0;
+    size_t off = 0, lo_off = 0;
     for (int i = 0; i < m.lpm[k - 1]; ++i, ++l) {
       m.layer_mod[l] = k;
-      m.loff[l] = layer_offsets(c, off);
-      off = m.loff[l].end;
+      const LayerOff po = layer_offsets(c.rel_pos != 0, d, hd, F, off);
+      const LayerOff lo = layer_offsets(c.rel_pos != 0, dl, dl, Fl, lo_off);
+      m.loff[l] = po;
+      std::vector<TensorMap>& tm = m.tmap[k];
+      tm.push_back({lo.W_qkv, po.W_qkv, (int)dl, (int)(3 * dl), (int)(3 * hd), false, true});
+      tm.push_back({lo.W_o, po.W_o, (int)dl, (int)dl, (int)d, true, false});
+      if (c.rel_pos) {
+        tm.push_back({lo.W_r, po.W_r, (int)dl, (int)dl, (int)hd, false, true});
+        tm.push_back({lo.u, po.u, 1, (int)dl, (int)hd, false, true});
+        tm.push_back({lo.v, po.v, 1, (int)dl, (int)hd, false, true});
+      }
+      tm.push_back({lo.ln1_g, po.ln1_g, 1, (int)dl, (int)d, false, false});
+      tm.push_back({lo.ln1_b, po.ln1_b, 1, (int)dl, (int)d, false, false});
+      tm.push_back({lo.W_1, po.W_1, (int)dl, (int)Fl, (int)F, false, false});
+      tm.push_back({lo.b_1, po.b_1, 1, (int)Fl, (int)F, false, false});
+      tm.push_back({lo.W_2, po.W_2, (int)Fl, (int)dl, (int)d, false, false});
+      tm.push_back({lo.b_2, po.b_2, 1, (int)dl, (int)d, false, false});
+      tm.push_back({lo.ln2_g, po.ln2_g, 1, (int)dl, (int)d, false, false});
+      tm.push_back({lo.ln2_b, po.ln2_b, 1, (int)dl, (int)d, false, false});
+      off = po.end;
+      lo_off = lo.end;
     }
-    m.count[k] = (int64_t)off;
+    m.count[k] = (int64_t)lo_off;
+    m.pcount[k] = (int64_t)off;
   }
   m.first_layer[K] = L;
   m.master.assign(K + 1, nullptr); m.shadow.assign(K + 1, nullptr);
   m.adam_m.assign(K + 1, nullptr); m.adam_v.assign(K + 1, nullptr);
   for (int k = 0; k <= K; ++k) {
-    m.master[k] = (float*)P(m.count[k] * 4);
+    m.master[k] = (float*)P(m.pcount[k] * 4);
     // V's bf16 copy carries zero rows up to the padded vocabulary (never written after the arena clear)
-    if (c.dtype == 1) m.shadow[k] = (bf16_t*)P((k == 0 ? vpad * d : (size_t)m.count[k]) * 2);
+    if (c.dtype == 1) m.shadow[k] = (bf16_t*)P((k == 0 ? vpad * d : (size_t)m.pcount[k]) * 2);
     if (c.optimizer == 1) {
-      m.adam_m[k] = (float*)P(m.count[k] * 4);
-      m.adam_v[k] = (float*)P(m.count[k] * 4);
+      m.adam_m[k] = (float*)P(m.pcount[k] * 4);
+      m.adam_v[k] = (float*)P(m.pcount[k] * 4);
     }
   }
   m.gcount.assign(K + 2, 0); m.gstride.assign(K + 2, 0); m.depth.assign(K + 2, 0); m.ring.assign(K + 2, nullptr);
   for (int id = 0; id <= K + 1; ++id) {
-    m.gcount[id] = (id == 0 || id == K + 1) ? m.count[0] : m.count[id];
-    m.gstride[id] = (m.gcount[id] + 63) / 64 * 64;
+    const int grp = (id == 0 || id == K + 1) ? 0 : id;
+    m.gcount[id] = m.count[grp];
+    m.gstride[id] = (m.pcount[grp] + 63) / 64 * 64;
     if (id == K + 1 && (int64_t)(vpad * d) > m.gstride[id]) m.gstride[id] = (int64_t)(vpad * d);   // dV_o rows of the padding
     ouro_ring_depth(K, id, &m.depth[id]);
     m.ring[id] = (float*)P((size_t)m.depth[id] * m.gstride[id] * 4);
   }
   m.L.resize(L);
-  const size_t qkv_elems = c.rel_pos ? (N * d + B * S * 2 * d) : (N * 3 * d);
+  const size_t qkv_elems = c.rel_pos ? (N * hd + B * S * 2 * hd) : (N * 3 * hd);
   for (int i = 0; i < L; ++i) {
     LayerBuf& b = m.L[i];
     b.x = P(N * d * es);
     b.cat = (M > 0) ? P(B * S * d * es) : nullptr;
     b.qkv = P(qkv_elems * es);
-    b.a = P(N * d * es);
+    b.a = P(N * hd * es);
     b.s1 = P(N * d * es);
     b.y = P(N * d * es);
     b.z = P(N * F * es);
     b.uact = P(N * F * es);
     b.s2 = P(N * d * es);
-    b.r = c.rel_pos ? P(S * d * es) : nullptr;
+    b.r = c.rel_pos ? P(S * hd * es) : nullptr;
     b.mem = (M > 0) ? P(B * M * d * es) : nullptr;
     b.lse = (float*)P(B * c.n_head * T * 4);
     b.mean1 = (float*)P(N * 4); b.rstd1 = (float*)P(N * 4);
@@ -304,17 +354,17 @@ static size_t lay_out(ouro_model& m, char* base) {
   m.loss = (float*)P(256);
   m.flag = (int*)P(256);
   for (int i = 0; i < 3; ++i) m.dhb[i] = P(N * d * es);
-  m.dy[0] = P(N * d * es); m.dy[1] = P(N * d * es); m.da = P(N * d * es);
+  m.dy[0] = P(N * d * es); m.dy[1] = P(N * d * es); m.da = P(N * hd * es);
   for (int p2 = 0; p2 < 2; ++p2) {
     m.ds2[p2] = P(N * d * es); m.dz[p2] = P(N * F * es);
     m.ds1[p2] = P(N * d * es); m.dqkv[p2] = P(qkv_elems * es);
   }
   m.dcat = c.rel_pos ? P(B * S * d * es) : nullptr;
   for (int p2 = 0; p2 < 2; ++p2) {
-    m.dr_t[p2] = c.rel_pos ? P(S * d * es) : nullptr;
-    m.dr_f32[p2] = c.rel_pos ? (float*)P(S * d * 4) : nullptr;
+    m.dr_t[p2] = c.rel_pos ? P(S * hd * es) : nullptr;
+    m.dr_f32[p2] = c.rel_pos ? (float*)P(S * hd * 4) : nullptr;
   }
-  m.attn_scratch = (float*)P(attn_bwd_scratch_floats(c.batch, c.n_head, c.seq_len, (int)S, c.d_head) * 4);
+  m.attn_scratch = (float*)P(attn_bwd_scratch_floats(c.batch, c.n_head, c.seq_len, (int)S, m.pdh) * 4);
   m.dbg_floats = N * d > B * M * d ? N * d : B * M * d;
   if (m.dbg_floats < S * d) m.dbg_floats = S * d;
   m.dbg_f32 = (float*)P(m.dbg_floats * 4);
@@ -333,15 +383,20 @@ extern "C" int ouro_query_arena_bytes(const ouro_config* cfg, size_t* bytes) {
   return OURO_OK;
 }
 
-static void host_sinusoid(std::vector<float>& out, int rows, int d) {
-  out.resize((size_t)rows * d);
+// rows x d sinusoids in rows of ld floats (columns d..ld-1 zero)
+static void host_sinusoid(std::vector<float>& out, int rows, int d, int ld) {
+  out.assign((size_t)rows * ld, 0.f);
   for (int p = 0; p < rows; ++p)
     for (int i = 0; i < d / 2; ++i) {
       double w = std::pow(10000.0, -2.0 * i / d);
-      out[(size_t)p * d + i] = (float)std::sin(p * w);
-      out[(size_t)p * d + d / 2 + i] = (float)std::cos(p * w);
+      out[(size_t)p * ld + i] = (float)std::sin(p * w);
+      out[(size_t)p * ld + d / 2 + i] = (float)std::cos(p * w);
     }
 }
+
+// Copies a parameter group between the caller's dense blob and the stored layout (host memory
+// both; the stored blob is zero-filled by the caller before to_stored).
+static void remap_group(const ouro_model* m, int group, float* stored, float* blob, bool to_stored);
 
 extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t bytes, void* hip_stream,
                                  ouro_model** out) {
@@ -391,10 +446,10 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
   if (e != hipSuccess) { delete m; return fail(OURO_E_HIP, "arena clear: %s", hipGetErrorString(e)); }
   std::vector<float> tab;
   if (!cfg->rel_pos) {
-    host_sinusoid(tab, cfg->seq_len, cfg->d_model);
+    host_sinusoid(tab, cfg->seq_len, cfg->d_model, m->pd);
     e = hipMemcpyAsync(m->pe, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, m->stream);
   } else {
-    host_sinusoid(tab, m->S, cfg->d_model);
+    host_sinusoid(tab, m->S, cfg->d_model, m->pd);
     e = hipMemcpyAsync(m->dbg_f32, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, m->stream);
     if (e == hipSuccess) e = launch_convert(m->stream, cfg->dtype, m->rtab, m->dbg_f32, tab.size());
   }
@@ -428,6 +483,21 @@ extern "C" int ouro_param_count(const ouro_model* m, int group, int64_t* n) {
 extern "C" int ouro_set_params(ouro_model* m, int group, const float* src, int64_t n, int src_is_device) {
   if (!m || !src || group < 0 || group > m->cfg.n_module) return fail(OURO_E_ARG, "set_params: bad argument");
   if (n != m->count[group]) return fail(OURO_E_ARG, "set_params: group %d has %lld elements, got %lld", group, (long long)m->count[group], (long long)n);
+  if (m->padded) {
+    std::vector<float> blob, stored((size_t)m->pcount[group], 0.f);
+    const float* hsrc = src;
+    if (src_is_device) {
+      blob.resize((size_t)n);
+      HIPCHK(hipMemcpyAsync(blob.data(), src, (size_t)n * 4, hipMemcpyDeviceToHost, m->stream));
+      HIPCHK(hipStreamSynchronize(m->stream));
+      hsrc = blob.data();
+    }
+    remap_group(m, group, stored.data(), const_cast<float*>(hsrc), true);
+    HIPCHK(hipMemcpyAsync(m->master[group], stored.data(), stored.size() * 4, hipMemcpyHostToDevice, m->stream));
+    HIPCHK(launch_convert(m->stream, 1, m->shadow[group], m->master[group], stored.size()));
+    HIPCHK(hipStreamSynchronize(m->stream));
+    return OURO_OK;
+  }
   HIPCHK(hipMemcpyAsync(m->master[group], src, (size_t)n * 4, src_is_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, m->stream));
   if (m->cfg.dtype == 1) HIPCHK(launch_convert(m->stream, 1, m->shadow[group], m->master[group], (size_t)n));
   if (!src_is_device) HIPCHK(hipStreamSynchronize(m->stream));
@@ -437,12 +507,44 @@ extern "C" int ouro_set_params(ouro_model* m, int group, const float* src, int64
 extern "C" int ouro_get_params(ouro_model* m, int group, float* dst, int64_t n, int dst_is_device) {
   if (!m || !dst || group < 0 || group > m->cfg.n_module) return fail(OURO_E_ARG, "get_params: bad argument");
   if (n != m->count[group]) return fail(OURO_E_ARG, "get_params: wrong element count");
+  if (m->padded) {
+    std::vector<float> stored((size_t)m->pcount[group]), blob;
+    HIPCHK(hipMemcpyAsync(stored.data(), m->master[group], stored.size() * 4, hipMemcpyDeviceToHost, m->stream));
+    HIPCHK(hipStreamSynchronize(m->stream));
+    if (!dst_is_device) { remap_group(m, group, stored.data(), dst, false); return OURO_OK; }
+    blob.resize((size_t)n);
+    remap_group(m, group, stored.data(), blob.data(), false);
+    HIPCHK(hipMemcpyAsync(dst, blob.data(), (size_t)n * 4, hipMemcpyHostToDevice, m->stream));
+    HIPCHK(hipStreamSynchronize(m->stream));
+    return OURO_OK;
+  }
   HIPCHK(hipMemcpyAsync(dst, m->master[group], (size_t)n * 4, dst_is_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost, m->stream));
   if (!dst_is_device) HIPCHK(hipStreamSynchronize(m->stream));
   return OURO_OK;
 }
 
 extern "C" int64_t ouro_current_step(const ouro_model* m) { return m ? m->t : -1; }
+
+static void remap_group(const ouro_model* m, int group, float* stored, float* blob, bool to_stored) {
+  const int dh = m->cfg.d_head, pdh = m->pdh;
+  for (const TensorMap& t : m->tmap[group]) {
+    for (int r = 0; r < t.rows; ++r) {
+      const size_t pr = t.row_heads ? (size_t)(r / dh) * pdh + r % dh : (size_t)r;
+      float* srow = stored + t.poff + pr * t.pcols;
+      float* brow = blob + t.loff + (size_t)r * t.cols;
+      if (!t.col_heads) {
+        if (to_stored) memcpy(srow, brow, (size_t)t.cols * 4);
+        else memcpy(brow, srow, (size_t)t.cols * 4);
+      } else {
+        for (int c0 = 0; c0 < t.cols; c0 += dh) {
+          float* sp = srow + (size_t)(c0 / dh) * pdh;
+          if (to_stored) memcpy(sp, brow + c0, (size_t)dh * 4);
+          else memcpy(brow + c0, sp, (size_t)dh * 4);
+        }
+      }
+    }
+  }
+}
 
 // --------------------------------------------------------------------- launch helpers
 static int timing_begin(ouro_model* m, int kind, hipStream_t st) {
@@ -483,21 +585,22 @@ static GemmDesc gd(const void* A, int lda, int tA, const void* B, int ldb, int t
 // ------------------------------------------------------------------------------ forward
 static int layer_forward(ouro_model* m, int l) {
   const ouro_config& c = m->cfg;
-  const int d = c.d_model, F = c.d_ff, N = m->N, T = c.seq_len, B = c.batch, es = m->esz;
+  const int d = m->pd, F = m->pF, hd = m->phd, dn = c.d_model;   // stored widths; dn = normalised width
+  const int N = m->N, T = c.seq_len, B = c.batch, es = m->esz;
   const LayerOff& o = m->loff[l];
   LayerBuf& b = m->L[l];
   char* out = (l + 1 < c.n_layer) ? m->L[l + 1].x : m->hL;
   const int Mv = m->mem_valid, S = Mv + T;
   AttnDesc a;
   memset(&a, 0, sizeof a);
-  a.B = B; a.H = c.n_head; a.T = T; a.S = S; a.dh = c.d_head; a.Mv = Mv;
+  a.B = B; a.H = c.n_head; a.T = T; a.S = S; a.dh = m->pdh; a.Mv = Mv;
   a.scale = 1.f / std::sqrt((float)c.d_head);
-  a.o = b.a; a.ldo = d; a.lse = b.lse;
+  a.o = b.a; a.ldo = hd; a.lse = b.lse;
   if (!c.rel_pos) {
-    RUN(run_gemm(m, gd(b.x, d, 0, m->wT(l, o.W_qkv), 3 * d, 0, b.qkv, 3 * d, N, 3 * d, d)));
-    a.q = b.qkv; a.ldq = 3 * d;
-    a.k = b.qkv + (size_t)d * es; a.ldk = 3 * d;
-    a.v = b.qkv + (size_t)2 * d * es; a.ldv = 3 * d;
+    RUN(run_gemm(m, gd(b.x, d, 0, m->wT(l, o.W_qkv), 3 * hd, 0, b.qkv, 3 * hd, N, 3 * hd, d)));
+    a.q = b.qkv; a.ldq = 3 * hd;
+    a.k = b.qkv + (size_t)hd * es; a.ldk = 3 * hd;
+    a.v = b.qkv + (size_t)2 * hd * es; a.ldv = 3 * hd;
   } else {
     const char* cat = b.x;
     if (Mv > 0) {
@@ -506,22 +609,22 @@ static int layer_forward(ouro_model* m, int l) {
       cat = b.cat;
     }
     char* q = b.qkv;
-    char* kv = b.qkv + (size_t)N * d * es;
-    RUN(run_gemm(m, gd(b.x, d, 0, m->wT(l, o.W_qkv), 3 * d, 0, q, d, N, d, d)));
-    RUN(run_gemm(m, gd(cat, d, 0, m->wT(l, o.W_qkv) + (size_t)d * es, 3 * d, 0, kv, 2 * d, B * S, 2 * d, d)));
-    RUN(run_gemm(m, gd(m->rtab, d, 0, m->wT(l, o.W_r), d, 0, b.r, d, S, d, d)));
-    a.q = q; a.ldq = d;
-    a.k = kv; a.ldk = 2 * d;
-    a.v = kv + (size_t)d * es; a.ldv = 2 * d;
-    a.rel = 1; a.u = m->wT(l, o.u); a.vb = m->wT(l, o.v); a.r = b.r; a.ldr = d;
+    char* kv = b.qkv + (size_t)N * hd * es;
+    RUN(run_gemm(m, gd(b.x, d, 0, m->wT(l, o.W_qkv), 3 * hd, 0, q, hd, N, hd, d)));
+    RUN(run_gemm(m, gd(cat, d, 0, m->wT(l, o.W_qkv) + (size_t)hd * es, 3 * hd, 0, kv, 2 * hd, B * S, 2 * hd, d)));
+    RUN(run_gemm(m, gd(m->rtab, d, 0, m->wT(l, o.W_r), hd, 0, b.r, hd, S, hd, d)));
+    a.q = q; a.ldq = hd;
+    a.k = kv; a.ldk = 2 * hd;
+    a.v = kv + (size_t)hd * es; a.ldv = 2 * hd;
+    a.rel = 1; a.u = m->wT(l, o.u); a.vb = m->wT(l, o.v); a.r = b.r; a.ldr = hd;
   }
   HIPCHK(launch_attn_fwd(m->stream, c.dtype, a, 0));
   {
-    GemmDesc g = gd(b.a, d, 0, m->wT(l, o.W_o), d, 0, b.s1, d, N, d, d);
+    GemmDesc g = gd(b.a, hd, 0, m->wT(l, o.W_o), d, 0, b.s1, d, N, d, hd);
     g.residual = b.x; g.ldr = d;
     RUN(run_gemm(m, g));
   }
-  HIPCHK(launch_layernorm_fwd(m->stream, c.dtype, b.s1, m->wF(l, o.ln1_g), m->wF(l, o.ln1_b), b.y, b.mean1, b.rstd1, N, d));
+  HIPCHK(launch_layernorm_fwd(m->stream, c.dtype, b.s1, m->wF(l, o.ln1_g), m->wF(l, o.ln1_b), b.y, b.mean1, b.rstd1, N, d, dn));
   {
     GemmDesc g = gd(b.y, d, 0, m->wT(l, o.W_1), F, 0, b.uact, F, N, F, d);
     g.bias = m->wF(l, o.b_1); g.epilogue = EPI_GELU; g.Z = b.z; g.ldz = F;
@@ -532,7 +635,7 @@ static int layer_forward(ouro_model* m, int l) {
     g.bias = m->wF(l, o.b_2); g.residual = b.y; g.ldr = d;
     RUN(run_gemm(m, g));
   }
-  HIPCHK(launch_layernorm_fwd(m->stream, c.dtype, b.s2, m->wF(l, o.ln2_g), m->wF(l, o.ln2_b), out, b.mean2, b.rstd2, N, d));
+  HIPCHK(launch_layernorm_fwd(m->stream, c.dtype, b.s2, m->wF(l, o.ln2_g), m->wF(l, o.ln2_b), out, b.mean2, b.rstd2, N, d, dn));
   return OURO_OK;
 }
 
@@ -547,13 +650,13 @@ extern "C" int ouro_module_forward(ouro_model* m, int k, const int32_t* dev_toke
     if (!dev_tokens) return fail(OURO_E_ARG, "module_forward(1) needs tokens");
     m->tok = dev_tokens;
     HIPCHK(launch_fill_zero(m->stream, m->flag, 256));
-    HIPCHK(launch_embed_fwd(m->stream, c.dtype, m->tok, m->vT(), m->pe, m->L[0].x, m->N, c.seq_len, c.d_model, c.vocab, c.emb_scale, m->flag));
+    HIPCHK(launch_embed_fwd(m->stream, c.dtype, m->tok, m->vT(), m->pe, m->L[0].x, m->N, c.seq_len, m->pd, c.vocab, c.emb_scale, m->flag));
   }
   if (k == K && !dev_targets) return fail(OURO_E_ARG, "module_forward(K) needs targets");
   for (int l = m->first_layer[k - 1]; l < m->first_layer[k]; ++l) RUN(layer_forward(m, l));
   if (k == K) {
     m->tgt = dev_targets;
-    const int d = c.d_model, V = c.vocab, N = m->N;
+    const int d = m->pd, V = c.vocab, N = m->N;
     GemmDesc g = gd(m->hL, d, 0, m->vT(), d, 1, m->G, m->ldv, N, V, d);   // logits = h_L V^T (Eq. 3)
     RUN(run_gemm(m, g));
     HIPCHK(launch_ce_rows(m->stream, c.dtype, m->G, m->ldv, m->tgt, m->G, m->ldv, m->lse_ce, m->rowloss, N, V, m->flag));
@@ -578,7 +681,8 @@ __global__ void add_rows_kernel(T* dst, size_t dst_bstride, const T* src, size_t
 
 static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot) {
   const ouro_config& c = m->cfg;
-  const int d = c.d_model, F = c.d_ff, N = m->N, T = c.seq_len, B = c.batch, es = m->esz;
+  const int d = m->pd, F = m->pF, hd = m->phd, dn = c.d_model;   // stored widths; dn = normalised width
+  const int N = m->N, T = c.seq_len, B = c.batch, es = m->esz;
   const LayerOff& o = m->loff[l];
   LayerBuf& b = m->L[l];
   const int Mv = m->mem_valid, S = Mv + T;
@@ -599,7 +703,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   // LN2
   // with the side stream the scale/shift gradients (column sums over dh and s2) run there too
   HIPCHK(launch_layernorm_bwd(st, c.dtype, dh, b.s2, m->wF(l, o.ln2_g), b.mean2, b.rstd2, ds2,
-                              side ? nullptr : gslot + o.ln2_g, gslot + o.ln2_b, N, d));
+                              side ? nullptr : gslot + o.ln2_g, gslot + o.ln2_b, N, d, dn));
   RUN(ready(0));
   if (side) HIPCHK(launch_layernorm_bwd_params(sw, c.dtype, dh, b.s2, b.mean2, b.rstd2, gslot + o.ln2_g, gslot + o.ln2_b, N, d));
   // FFN2
@@ -629,80 +733,80 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   }
   // LN1
   HIPCHK(launch_layernorm_bwd(st, c.dtype, dy, b.s1, m->wF(l, o.ln1_g), b.mean1, b.rstd1, ds1,
-                              side ? nullptr : gslot + o.ln1_g, gslot + o.ln1_b, N, d));
+                              side ? nullptr : gslot + o.ln1_g, gslot + o.ln1_b, N, d, dn));
   RUN(ready(2));
   if (side) HIPCHK(launch_layernorm_bwd_params(sw, c.dtype, dy, b.s1, b.mean1, b.rstd1, gslot + o.ln1_g, gslot + o.ln1_b, N, d));
   // output projection
   {
-    GemmDesc g = gd(b.a, d, 1, ds1, d, 0, gslot + o.W_o, d, d, d, N);
+    GemmDesc g = gd(b.a, hd, 1, ds1, d, 0, gslot + o.W_o, d, hd, d, N);
     g.out_fp32 = 1; g.accumulate = 1;
     RUN(run_gemm_on(m, g, sw));
   }
-  RUN(run_gemm(m, gd(ds1, d, 0, m->wT(l, o.W_o), d, 1, m->da, d, N, d, d)));
+  RUN(run_gemm(m, gd(ds1, d, 0, m->wT(l, o.W_o), d, 1, m->da, hd, N, hd, d)));
   // attention
   AttnDesc a;
   memset(&a, 0, sizeof a);
-  a.B = B; a.H = c.n_head; a.T = T; a.S = S; a.dh = c.d_head; a.Mv = Mv;
+  a.B = B; a.H = c.n_head; a.T = T; a.S = S; a.dh = m->pdh; a.Mv = Mv;
   a.scale = 1.f / std::sqrt((float)c.d_head);
-  a.o = b.a; a.ldo = d; a.lse = b.lse; a.d_o = m->da; a.lddo = d; a.scratch = m->attn_scratch;
+  a.o = b.a; a.ldo = hd; a.lse = b.lse; a.d_o = m->da; a.lddo = hd; a.scratch = m->attn_scratch;
   if (!c.rel_pos) {
-    a.q = b.qkv; a.ldq = 3 * d;
-    a.k = b.qkv + (size_t)d * es; a.ldk = 3 * d;
-    a.v = b.qkv + (size_t)2 * d * es; a.ldv = 3 * d;
-    a.dq = dqkv; a.lddq = 3 * d;
-    a.dk = dqkv + (size_t)d * es; a.lddk = 3 * d;
-    a.dv = dqkv + (size_t)2 * d * es; a.lddv = 3 * d;
+    a.q = b.qkv; a.ldq = 3 * hd;
+    a.k = b.qkv + (size_t)hd * es; a.ldk = 3 * hd;
+    a.v = b.qkv + (size_t)2 * hd * es; a.ldv = 3 * hd;
+    a.dq = dqkv; a.lddq = 3 * hd;
+    a.dk = dqkv + (size_t)hd * es; a.lddk = 3 * hd;
+    a.dv = dqkv + (size_t)2 * hd * es; a.lddv = 3 * hd;
     HIPCHK(launch_attn_bwd(st, c.dtype, a, 0));
     RUN(ready(3));
     {
-      GemmDesc g = gd(b.x, d, 1, dqkv, 3 * d, 0, gslot + o.W_qkv, 3 * d, d, 3 * d, N);
+      GemmDesc g = gd(b.x, d, 1, dqkv, 3 * hd, 0, gslot + o.W_qkv, 3 * hd, d, 3 * hd, N);
       g.out_fp32 = 1; g.accumulate = 1;
       RUN(run_gemm_on(m, g, sw));
     }
     {
-      GemmDesc g = gd(dqkv, 3 * d, 0, m->wT(l, o.W_qkv), 3 * d, 1, dx, d, N, d, 3 * d);
+      GemmDesc g = gd(dqkv, 3 * hd, 0, m->wT(l, o.W_qkv), 3 * hd, 1, dx, d, N, d, 3 * hd);
       g.residual = ds1; g.ldr = d;
       RUN(run_gemm(m, g));
     }
   } else {
     const char* cat = Mv > 0 ? b.cat : b.x;
     char* q = b.qkv;
-    char* kv = b.qkv + (size_t)N * d * es;
+    char* kv = b.qkv + (size_t)N * hd * es;
     char* dq = dqkv;
-    char* dkv = dqkv + (size_t)N * d * es;
-    a.q = q; a.ldq = d; a.k = kv; a.ldk = 2 * d; a.v = kv + (size_t)d * es; a.ldv = 2 * d;
-    a.rel = 1; a.u = m->wT(l, o.u); a.vb = m->wT(l, o.v); a.r = b.r; a.ldr = d;
-    a.dq = dq; a.lddq = d; a.dk = dkv; a.lddk = 2 * d; a.dv = dkv + (size_t)d * es; a.lddv = 2 * d;
+    char* dkv = dqkv + (size_t)N * hd * es;
+    a.q = q; a.ldq = hd; a.k = kv; a.ldk = 2 * hd; a.v = kv + (size_t)hd * es; a.ldv = 2 * hd;
+    a.rel = 1; a.u = m->wT(l, o.u); a.vb = m->wT(l, o.v); a.r = b.r; a.ldr = hd;
+    a.dq = dq; a.lddq = hd; a.dk = dkv; a.lddk = 2 * hd; a.dv = dkv + (size_t)hd * es; a.lddv = 2 * hd;
     float* drf = m->dr_f32[ps];
     a.du = gslot + o.u; a.dvb = gslot + o.v; a.dr = drf;
-    HIPCHK(launch_fill_zero(st, drf, (size_t)S * d * 4));
+    HIPCHK(launch_fill_zero(st, drf, (size_t)S * hd * 4));
     HIPCHK(launch_attn_bwd(st, c.dtype, a, 0));
     const void* drp = drf;
-    if (c.dtype == 1) { HIPCHK(launch_convert(st, 1, m->dr_t[ps], drf, (size_t)S * d)); drp = m->dr_t[ps]; }
+    if (c.dtype == 1) { HIPCHK(launch_convert(st, 1, m->dr_t[ps], drf, (size_t)S * hd)); drp = m->dr_t[ps]; }
     RUN(ready(3));
     // weight gradients: dW_r = R^T dr, dW_q = x^T dq, dW_kv = [mem ; x]^T dkv
     {
-      GemmDesc g = gd(m->rtab, d, 1, drp, d, 0, gslot + o.W_r, d, d, d, S);
+      GemmDesc g = gd(m->rtab, d, 1, drp, hd, 0, gslot + o.W_r, hd, d, hd, S);
       g.out_fp32 = 1; g.accumulate = 1;
       RUN(run_gemm_on(m, g, sw));
     }
     {
-      GemmDesc g = gd(b.x, d, 1, dq, d, 0, gslot + o.W_qkv, 3 * d, d, d, N);
+      GemmDesc g = gd(b.x, d, 1, dq, hd, 0, gslot + o.W_qkv, 3 * hd, d, hd, N);
       g.out_fp32 = 1; g.accumulate = 1;
       RUN(run_gemm_on(m, g, sw));
     }
     {
-      GemmDesc g = gd(cat, d, 1, dkv, 2 * d, 0, gslot + o.W_qkv + d, 3 * d, d, 2 * d, B * S);
+      GemmDesc g = gd(cat, d, 1, dkv, 2 * hd, 0, gslot + o.W_qkv + hd, 3 * hd, d, 2 * hd, B * S);
       g.out_fp32 = 1; g.accumulate = 1;
       RUN(run_gemm_on(m, g, sw));
     }
     {
-      GemmDesc g = gd(dq, d, 0, m->wT(l, o.W_qkv), 3 * d, 1, dx, d, N, d, d);
+      GemmDesc g = gd(dq, hd, 0, m->wT(l, o.W_qkv), 3 * hd, 1, dx, d, N, d, hd);
       g.residual = ds1; g.ldr = d;
       RUN(run_gemm(m, g));
     }
     // the memory rows are constants: only the current rows of d[mem ; x] reach dx
-    RUN(run_gemm(m, gd(dkv, 2 * d, 0, m->wT(l, o.W_qkv) + (size_t)d * es, 3 * d, 1, m->dcat, d, B * S, d, 2 * d)));
+    RUN(run_gemm(m, gd(dkv, 2 * hd, 0, m->wT(l, o.W_qkv) + (size_t)hd * es, 3 * hd, 1, m->dcat, d, B * S, d, 2 * hd)));
     {
       size_t n = (size_t)T * d;
       dim3 grid((unsigned)std::min<size_t>((n + 255) / 256, 1024), B), block(256);
@@ -719,7 +823,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
 // recorded on the side stream; the caller orders the gradient's reader behind it).
 static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
   const ouro_config& c = m->cfg;
-  const int K = c.n_module, d = c.d_model, V = c.vocab, N = m->N;
+  const int K = c.n_module, d = m->pd, V = c.vocab, N = m->N;
   if (k < 1 || k > K) return fail(OURO_E_ARG, "module_backward: k=%d outside 1..%d", k, K);
   if (m->inject_mask) return fail(OURO_E_SEQUENCE, "module_backward after inject_grad in the same iteration");
   if (m->fwd_next != K + 1) return fail(OURO_E_SEQUENCE, "module_backward before forward of module %d", m->fwd_next);
@@ -796,7 +900,7 @@ static int close_iteration(ouro_model* m) {
   const ouro_config& c = m->cfg;
   if (c.mem_len > 0) {
     // memory for t+1 = last M rows of [memory ; layer input] (constants, no gradient)
-    const int T = c.seq_len, d = c.d_model, Mv = m->mem_valid, S = Mv + T;
+    const int T = c.seq_len, d = m->pd, Mv = m->mem_valid, S = Mv + T;
     const int Mn = std::min(c.mem_len, S);
     for (int l = 0; l < c.n_layer; ++l) {
       LayerBuf& b = m->L[l];
@@ -817,7 +921,7 @@ static int update_group(ouro_model* m, int group, float lr, hipStream_t st) {
   UpdateDesc u;
   memset(&u, 0, sizeof u);
   u.w = m->master[group]; u.m = m->adam_m[group]; u.v = m->adam_v[group]; u.shadow = m->shadow[group];
-  u.n = (size_t)m->count[group]; u.adam = c.optimizer; u.lr = lr;
+  u.n = (size_t)m->pcount[group]; u.adam = c.optimizer; u.lr = lr;
   u.beta1 = c.beta1; u.beta2 = c.beta2; u.eps = c.eps;
   u.bc1 = (float)(1.0 - std::pow((double)c.beta1, (double)(m->t + 1)));   // global t+1 (Algorithm 2)
   u.bc2 = (float)(1.0 - std::pow((double)c.beta2, (double)(m->t + 1)));
@@ -942,7 +1046,14 @@ extern "C" int ouro_debug_inject_grad(ouro_model* m, int id, const float* host_g
   if (m->inject_mask & (1ull << id)) return fail(OURO_E_SEQUENCE, "inject_grad(%d) twice in one iteration", id);
   int64_t slot, tau;
   ouro_slot_index(K, id, m->t, 1, &slot, &tau);
-  HIPCHK(hipMemcpyAsync(m->slot_ptr(id, slot), host_g, (size_t)n * 4, hipMemcpyHostToDevice, m->stream));
+  if (m->padded) {
+    const int grp = (id == 0 || id == K + 1) ? 0 : id;
+    std::vector<float> stored((size_t)m->pcount[grp], 0.f);
+    remap_group(m, grp, stored.data(), const_cast<float*>(host_g), true);
+    HIPCHK(hipMemcpyAsync(m->slot_ptr(id, slot), stored.data(), stored.size() * 4, hipMemcpyHostToDevice, m->stream));
+  } else {
+    HIPCHK(hipMemcpyAsync(m->slot_ptr(id, slot), host_g, (size_t)n * 4, hipMemcpyHostToDevice, m->stream));
+  }
   HIPCHK(hipStreamSynchronize(m->stream));
   m->tags[id][slot] = m->t;
   m->inject_mask |= 1ull << id;
@@ -955,7 +1066,23 @@ extern "C" int ouro_get_grad_slot(ouro_model* m, int id, int64_t tau, float* hos
   if (n != m->gcount[id]) return fail(OURO_E_ARG, "get_grad_slot: wrong element count");
   int64_t slot = tau % m->depth[id];
   if (m->tags[id][slot] != tau) return fail(OURO_E_STALE, "store %d no longer holds iteration %lld", id, (long long)tau);
+  if (m->padded) {
+    const int grp = (id == 0 || id == m->cfg.n_module + 1) ? 0 : id;
+    std::vector<float> stored((size_t)m->pcount[grp]);
+    HIPCHK(hipMemcpyAsync(stored.data(), m->slot_ptr(id, slot), stored.size() * 4, hipMemcpyDeviceToHost, m->stream));
+    HIPCHK(hipStreamSynchronize(m->stream));
+    remap_group(m, grp, stored.data(), host_dst, false);
+    return OURO_OK;
+  }
   HIPCHK(hipMemcpyAsync(host_dst, m->slot_ptr(id, slot), (size_t)n * 4, hipMemcpyDeviceToHost, m->stream));
+  HIPCHK(hipStreamSynchronize(m->stream));
+  return OURO_OK;
+}
+
+// rows of the stored width in dbg_f32 -> dense rows of d_model floats in host memory
+static int rows_to_host(ouro_model* m, float* host_dst, size_t rows) {
+  const size_t dl = m->cfg.d_model;
+  HIPCHK(hipMemcpy2DAsync(host_dst, dl * 4, m->dbg_f32, (size_t)m->pd * 4, dl * 4, rows, hipMemcpyDeviceToHost, m->stream));
   HIPCHK(hipStreamSynchronize(m->stream));
   return OURO_OK;
 }
@@ -964,11 +1091,9 @@ extern "C" int ouro_get_mems(ouro_model* m, int layer, float* host_dst, int64_t*
   if (!m || !valid_len || layer < 0 || layer >= m->cfg.n_layer) return fail(OURO_E_ARG, "get_mems: bad argument");
   *valid_len = m->mem_valid;
   if (!host_dst || m->mem_valid == 0) return OURO_OK;
-  size_t n = (size_t)m->cfg.batch * m->mem_valid * m->cfg.d_model;
-  HIPCHK(launch_to_f32(m->stream, m->cfg.dtype, m->dbg_f32, m->L[layer].mem, n));
-  HIPCHK(hipMemcpyAsync(host_dst, m->dbg_f32, n * 4, hipMemcpyDeviceToHost, m->stream));
-  HIPCHK(hipStreamSynchronize(m->stream));
-  return OURO_OK;
+  const size_t rows = (size_t)m->cfg.batch * m->mem_valid;
+  HIPCHK(launch_to_f32(m->stream, m->cfg.dtype, m->dbg_f32, m->L[layer].mem, rows * m->pd));
+  return rows_to_host(m, host_dst, rows);
 }
 
 extern "C" int ouro_debug_get_hidden(ouro_model* m, int layer, float* host_dst, int64_t n) {
@@ -976,10 +1101,8 @@ extern "C" int ouro_debug_get_hidden(ouro_model* m, int layer, float* host_dst, 
   size_t cnt = (size_t)m->N * m->cfg.d_model;
   if ((size_t)n != cnt) return fail(OURO_E_ARG, "get_hidden: wrong element count");
   const char* src = layer < m->cfg.n_layer ? m->L[layer].x : m->hL;
-  HIPCHK(launch_to_f32(m->stream, m->cfg.dtype, m->dbg_f32, src, cnt));
-  HIPCHK(hipMemcpyAsync(host_dst, m->dbg_f32, cnt * 4, hipMemcpyDeviceToHost, m->stream));
-  HIPCHK(hipStreamSynchronize(m->stream));
-  return OURO_OK;
+  HIPCHK(launch_to_f32(m->stream, m->cfg.dtype, m->dbg_f32, src, (size_t)m->N * m->pd));
+  return rows_to_host(m, host_dst, (size_t)m->N);
 }
 
 extern "C" int ouro_debug_timing_enable(ouro_model* m, int on) {

@@ -86,18 +86,18 @@ extern "C" int ouro_op_attention_bwd(void* stream, int dtype, int B, int H, int 
 }
 
 extern "C" int ouro_op_layernorm_fwd(void* stream, int dtype, const void* x, const float* g, const float* b, void* y,
-                                     float* mean, float* rstd, int rows, int d) {
-  if (!x || !g || !b || !y || !mean || !rstd || rows < 0 || d < 1) return OURO_E_ARG;
-  return rc_of(launch_layernorm_fwd((hipStream_t)stream, dtype, x, g, b, y, mean, rstd, rows, d));
+                                     float* mean, float* rstd, int rows, int d, int dn) {
+  if (!x || !g || !b || !y || !mean || !rstd || rows < 0 || d < 1 || dn < 0 || dn > d) return OURO_E_ARG;
+  return rc_of(launch_layernorm_fwd((hipStream_t)stream, dtype, x, g, b, y, mean, rstd, rows, d, dn));
 }
 
 extern "C" int ouro_op_layernorm_bwd(void* stream, int dtype, const void* dy, const void* x, const float* g,
                                      const float* mean, const float* rstd, void* dx, float* dg, float* db, int rows,
-                                     int d) {
-  if (!dy || !x || !g || !mean || !rstd || !dx || !dg || !db || rows < 0 || d < 1) return OURO_E_ARG;
+                                     int d, int dn) {
+  if (!dy || !x || !g || !mean || !rstd || !dx || !dg || !db || rows < 0 || d < 1 || dn < 0 || dn > d) return OURO_E_ARG;
   hipStream_t s = (hipStream_t)stream;
   if (launch_fill_zero(s, dg, (size_t)d * 4) != hipSuccess || launch_fill_zero(s, db, (size_t)d * 4) != hipSuccess) return OURO_E_HIP;
-  return rc_of(launch_layernorm_bwd(s, dtype, dy, x, g, mean, rstd, dx, dg, db, rows, d));
+  return rc_of(launch_layernorm_bwd(s, dtype, dy, x, g, mean, rstd, dx, dg, db, rows, d, dn));
 }
 
 extern "C" int ouro_op_colsum(void* stream, int dtype, const void* x, int ldx, float* out, int rows, int cols) {

@@ -40,7 +40,7 @@ template <typename T, int MAXI>
 __global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const T* __restrict__ x, const float* __restrict__ g,
                                                          const float* __restrict__ b, T* __restrict__ y,
                                                          float* __restrict__ mean, float* __restrict__ rstd,
-                                                         int rows, int d) {
+                                                         int rows, int d, int dn) {
   constexpr int N = Pack<T>::N;
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -57,17 +57,17 @@ __global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const T* __restrict__ x
       for (int e = 0; e < N; ++e) s += v[i][e];
     }
   }
-  const float mu = wave_sum(s) / d;
+  const float mu = wave_sum(s) / dn;
   float q = 0.f;
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) {
     int vi = lane + 64 * i;
     if (vi < nvec) {
 #pragma unroll
-      for (int e = 0; e < N; ++e) { float t = v[i][e] - mu; q += t * t; }
+      for (int e = 0; e < N; ++e) { float t = v[i][e] - mu; q += vi * N + e < dn ? t * t : 0.f; }
     }
   }
-  const float rs = rsqrtf(wave_sum(q) / d + 1e-5f);
+  const float rs = rsqrtf(wave_sum(q) / dn + 1e-5f);
   if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) {
@@ -85,36 +85,37 @@ template <typename T>
 __global__ __launch_bounds__(256) void ln_fwd_scalar_kernel(const T* __restrict__ x, const float* __restrict__ g,
                                                             const float* __restrict__ b, T* __restrict__ y,
                                                             float* __restrict__ mean, float* __restrict__ rstd,
-                                                            int rows, int d) {
+                                                            int rows, int d, int dn) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
   const T* xr = x + (size_t)row * d;
   float s = 0.f;
-  for (int c = lane; c < d; c += 64) s += to_f32(xr[c]);
-  const float mu = wave_sum(s) / d;
+  for (int c = lane; c < dn; c += 64) s += to_f32(xr[c]);
+  const float mu = wave_sum(s) / dn;
   float q = 0.f;
-  for (int c = lane; c < d; c += 64) { float t = to_f32(xr[c]) - mu; q += t * t; }
-  const float rs = rsqrtf(wave_sum(q) / d + 1e-5f);
+  for (int c = lane; c < dn; c += 64) { float t = to_f32(xr[c]) - mu; q += t * t; }
+  const float rs = rsqrtf(wave_sum(q) / dn + 1e-5f);
   if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
   for (int c = lane; c < d; c += 64)
     y[(size_t)row * d + c] = from_f32<T>((to_f32(xr[c]) - mu) * rs * g[c] + b[c]);
 }
 
 hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, const void* x, const float* g, const float* b,
-                                void* y, float* mean, float* rstd, int rows, int d) {
+                                void* y, float* mean, float* rstd, int rows, int d, int dn) {
   if (rows <= 0) return hipSuccess;
+  if (dn <= 0 || dn > d) dn = d;
   dim3 grid((rows + 3) / 4), block(256);
   if (dtype == 1) {
     if (d % 8 == 0 && d / 8 <= 256)
-      hipLaunchKernelGGL((ln_fwd_vec_kernel<bf16_t, 4>), grid, block, 0, s, (const bf16_t*)x, g, b, (bf16_t*)y, mean, rstd, rows, d);
+      hipLaunchKernelGGL((ln_fwd_vec_kernel<bf16_t, 4>), grid, block, 0, s, (const bf16_t*)x, g, b, (bf16_t*)y, mean, rstd, rows, d, dn);
     else
-      hipLaunchKernelGGL(ln_fwd_scalar_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, g, b, (bf16_t*)y, mean, rstd, rows, d);
+      hipLaunchKernelGGL(ln_fwd_scalar_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, g, b, (bf16_t*)y, mean, rstd, rows, d, dn);
   } else {
     if (d % 4 == 0 && d / 4 <= 256)
-      hipLaunchKernelGGL((ln_fwd_vec_kernel<float, 4>), grid, block, 0, s, (const float*)x, g, b, (float*)y, mean, rstd, rows, d);
+      hipLaunchKernelGGL((ln_fwd_vec_kernel<float, 4>), grid, block, 0, s, (const float*)x, g, b, (float*)y, mean, rstd, rows, d, dn);
     else
-      hipLaunchKernelGGL(ln_fwd_scalar_kernel<float>, grid, block, 0, s, (const float*)x, g, b, (float*)y, mean, rstd, rows, d);
+      hipLaunchKernelGGL(ln_fwd_scalar_kernel<float>, grid, block, 0, s, (const float*)x, g, b, (float*)y, mean, rstd, rows, d, dn);
   }
   return hipGetLastError();
 }
@@ -125,7 +126,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void ln_bwd_dx_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                         const float* __restrict__ g, const float* __restrict__ mean,
                                                         const float* __restrict__ rstd, T* __restrict__ dx,
-                                                        int rows, int d) {
+                                                        int rows, int d, int dn) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -139,12 +140,12 @@ __global__ __launch_bounds__(256) void ln_bwd_dx_kernel(const T* __restrict__ dy
     s1 += t;
     s2 += t * xh;
   }
-  s1 = wave_sum(s1) / d;
-  s2 = wave_sum(s2) / d;
+  s1 = wave_sum(s1) / dn;
+  s2 = wave_sum(s2) / dn;
   for (int c = lane; c < d; c += 64) {
     float xh = (to_f32(xr[c]) - mu) * rs;
     float t = to_f32(dyr[c]) * g[c];
-    dx[(size_t)row * d + c] = from_f32<T>(rs * (t - s1 - xh * s2));
+    dx[(size_t)row * d + c] = from_f32<T>(c < dn ? rs * (t - s1 - xh * s2) : 0.f);
   }
 }
 
@@ -194,7 +195,8 @@ template <typename T, int MAXI, bool PARAMS>
 __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                            const float* __restrict__ g, const float* __restrict__ mean,
                                                            const float* __restrict__ rstd, T* __restrict__ dx,
-                                                           float* __restrict__ dg, float* __restrict__ db, int rows, int d) {
+                                                           float* __restrict__ dg, float* __restrict__ db, int rows, int d,
+                                                           int dn) {
   constexpr int N = Pack<T>::N;
   extern __shared__ float red[];                 // [4][d]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -251,15 +253,15 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* __restrict__
           }
         }
       }
-      s1 = wave_sum(s1) / d;
-      s2 = wave_sum(s2) / d;
+      s1 = wave_sum(s1) / dn;
+      s2 = wave_sum(s2) / dn;
 #pragma unroll
       for (int i = 0; i < MAXI; ++i) {
         int vi = lane + 64 * i;
         if (vi < nvec) {
           float out[N];
 #pragma unroll
-          for (int e = 0; e < N; ++e) out[e] = rs[u] * (t[u][i][e] - s1 - xh[u][i][e] * s2);
+          for (int e = 0; e < N; ++e) out[e] = vi * N + e < dn ? rs[u] * (t[u][i][e] - s1 - xh[u][i][e] * s2) : 0.f;
           store_pack<T>(dx + (size_t)row * d + vi * N, out);
         }
       }
@@ -372,21 +374,22 @@ static bool ln_vec_ok(int dtype, const void* dy, const void* x, int d) {
 // launch_layernorm_bwd_params, on any stream that sees dy and x).
 hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const float* g,
                                 const float* mean, const float* rstd, void* dx, float* dg, float* db,
-                                int rows, int d) {
+                                int rows, int d, int dn) {
   if (rows <= 0) return hipSuccess;
+  if (dn <= 0 || dn > d) dn = d;
   dim3 grid((rows + 3) / 4), block(256);
   if (ln_vec_ok(dtype, dy, x, d) && ptr16(dx)) {
     const int pack = dtype == 1 ? 8 : 4;
     dim3 gf(std::min((rows + 3) / 4, 512));
     const int npl = (d / pack + 63) / 64;      // packs per lane
-#define OURO_LNB(T_, MI_) hipLaunchKernelGGL((ln_bwd_fused_kernel<T_, MI_, false>), gf, block, 0, s, (const T_*)dy, (const T_*)x, g, mean, rstd, (T_*)dx, nullptr, nullptr, rows, d)
+#define OURO_LNB(T_, MI_) hipLaunchKernelGGL((ln_bwd_fused_kernel<T_, MI_, false>), gf, block, 0, s, (const T_*)dy, (const T_*)x, g, mean, rstd, (T_*)dx, nullptr, nullptr, rows, d, dn)
     if (dtype == 1) { if (npl <= 1) OURO_LNB(bf16_t, 1); else if (npl <= 2) OURO_LNB(bf16_t, 2); else OURO_LNB(bf16_t, 4); }
     else { if (npl <= 1) OURO_LNB(float, 1); else if (npl <= 2) OURO_LNB(float, 2); else OURO_LNB(float, 4); }
 #undef OURO_LNB
   } else if (dtype == 1) {
-    hipLaunchKernelGGL(ln_bwd_dx_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)dy, (const bf16_t*)x, g, mean, rstd, (bf16_t*)dx, rows, d);
+    hipLaunchKernelGGL(ln_bwd_dx_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)dy, (const bf16_t*)x, g, mean, rstd, (bf16_t*)dx, rows, d, dn);
   } else {
-    hipLaunchKernelGGL(ln_bwd_dx_kernel<float>, grid, block, 0, s, (const float*)dy, (const float*)x, g, mean, rstd, (float*)dx, rows, d);
+    hipLaunchKernelGGL(ln_bwd_dx_kernel<float>, grid, block, 0, s, (const float*)dy, (const float*)x, g, mean, rstd, (float*)dx, rows, d, dn);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !dg) return e;

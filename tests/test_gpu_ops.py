@@ -209,19 +209,52 @@ def test_layernorm(dtype, rows, d):
     tdt = torch.bfloat16 if dtype else torch.float32
     y = torch.zeros((rows, d), dtype=tdt, device="cuda")
     mean = torch.zeros(rows, device="cuda"); rstd = torch.zeros(rows, device="cuda")
-    ok(L().ouro_op_layernorm_fwd(stream(), dtype, p(dx_), p(dg_), p(db_), p(y), p(mean), p(rstd), rows, d))
+    ok(L().ouro_op_layernorm_fwd(stream(), dtype, p(dx_), p(dg_), p(db_), p(y), p(mean), p(rstd), rows, d, 0))
     yr, cache = O.layernorm_fwd(host(dx_), g.astype(np.float64), b.astype(np.float64))
     torch.cuda.synchronize()
     assert rel_err(host(y), yr) < TOL[dtype]
     assert rel_err(host(rstd), cache[1][:, 0]) < 1e-5
     gx = torch.zeros((rows, d), dtype=tdt, device="cuda")
     gg = torch.full((d,), 7.0, device="cuda"); gb = torch.full((d,), 7.0, device="cuda")
-    ok(L().ouro_op_layernorm_bwd(stream(), dtype, p(ddy), p(dx_), p(dg_), p(mean), p(rstd), p(gx), p(gg), p(gb), rows, d))
+    ok(L().ouro_op_layernorm_bwd(stream(), dtype, p(ddy), p(dx_), p(dg_), p(mean), p(rstd), p(gx), p(gg), p(gb), rows, d, 0))
     torch.cuda.synchronize()
     rx, rg, rb = O.layernorm_bwd(host(ddy), g.astype(np.float64), cache)
     assert rel_err(host(gx), rx) < TOL[dtype]
     assert rel_err(host(gg), rg) < 1e-4
     assert rel_err(host(gb), rb) < 1e-4
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("rows,dn,d", [(37, 410, 448), (9, 41, 64), (130, 100, 101)])
+def test_layernorm_zero_padded_rows(dtype, rows, dn, d):
+    """Rows of d columns whose last d-dn are zero padding: statistics over dn columns only, the
+    padding stays zero in y and dx, and the first dn columns equal LayerNorm of the unpadded rows."""
+    rng = np.random.default_rng(rows + d)
+    x = np.zeros((rows, d), np.float32); dy = np.zeros((rows, d), np.float32)
+    g = np.zeros(d, np.float32); b = np.zeros(d, np.float32)
+    x[:, :dn] = rng.standard_normal((rows, dn)) * 2 + 0.5
+    dy[:, :dn] = rng.standard_normal((rows, dn))
+    g[:dn] = 1 + 0.3 * rng.standard_normal(dn); b[:dn] = 0.2 * rng.standard_normal(dn)
+    dx_, ddy = dev(x, dtype), dev(dy, dtype)
+    dg_, db_ = torch.from_numpy(g).cuda(), torch.from_numpy(b).cuda()
+    tdt = torch.bfloat16 if dtype else torch.float32
+    y = torch.full((rows, d), 3.0, dtype=tdt, device="cuda")
+    mean = torch.zeros(rows, device="cuda"); rstd = torch.zeros(rows, device="cuda")
+    ok(L().ouro_op_layernorm_fwd(stream(), dtype, p(dx_), p(dg_), p(db_), p(y), p(mean), p(rstd), rows, d, dn))
+    yr, cache = O.layernorm_fwd(host(dx_)[:, :dn], g[:dn].astype(np.float64), b[:dn].astype(np.float64))
+    torch.cuda.synchronize()
+    assert rel_err(host(y)[:, :dn], yr) < TOL[dtype]
+    assert not host(y)[:, dn:].any()
+    assert rel_err(host(rstd), cache[1][:, 0]) < 1e-5
+    gx = torch.full((rows, d), 3.0, dtype=tdt, device="cuda")
+    gg = torch.full((d,), 7.0, device="cuda"); gb = torch.full((d,), 7.0, device="cuda")
+    ok(L().ouro_op_layernorm_bwd(stream(), dtype, p(ddy), p(dx_), p(dg_), p(mean), p(rstd), p(gx), p(gg), p(gb), rows, d, dn))
+    torch.cuda.synchronize()
+    rx, rg, rb = O.layernorm_bwd(host(ddy)[:, :dn], g[:dn].astype(np.float64), cache)
+    assert rel_err(host(gx)[:, :dn], rx) < TOL[dtype]
+    assert not host(gx)[:, dn:].any()
+    assert rel_err(host(gg)[:dn], rg) < 1e-4 and not host(gg)[dn:].any()
+    assert rel_err(host(gb)[:dn], rb) < 1e-4 and not host(gb)[dn:].any()
 
 
 @pytest.mark.parametrize("dtype", [0, 1])

@@ -156,14 +156,32 @@ def test_xl_bf16_mfma_path_memory_carry():
     run_both(c, steps=4, lr=0.05, seed=31, std=0.05, perturb=0.05, tol=2e-2)
 
 
+def test_bf16_widths_off_the_tile_grid_adam():
+    """bf16 mode with d_head = 41, d_model = 82, d_ff = 100: stored zero-padded to 64 / 128 / 128 so
+    that the MFMA kernels run; every result the caller sees (loss, gradients, weights) is that of
+    the unpadded model.  Adam over more steps than K: padding that picked up a value would leak
+    into the visible weights."""
+    c = dict(n_layer=3, d_model=82, n_head=2, d_head=41, d_ff=100, vocab=203, seq_len=70, mem_len=0, batch=3,
+             n_module=3, rel_pos=0, dtype=1, optimizer=1, embed_warm_mode=0)
+    run_both(c, steps=6, lr=1e-3, seed=41, std=0.05, perturb=0.05, tol=2e-2)
+
+
+def test_xl_bf16_widths_off_the_tile_grid_memory_carry():
+    """The same zero-padded storage with Transformer-XL blocks (W_r, u, v per head) and a rolling
+    memory; head size 32 here."""
+    c = dict(n_layer=2, d_model=96, n_head=3, d_head=32, d_ff=200, vocab=301, seq_len=40, mem_len=56, batch=2,
+             n_module=2, rel_pos=1, dtype=1, optimizer=0, embed_warm_mode=1)
+    run_both(c, steps=4, lr=0.05, seed=43, std=0.05, perturb=0.05, tol=2e-2)
+
+
 @pytest.mark.parametrize("rel_pos,mem_len", [(0, 0), (1, 96)])
 def test_stream_overlap_matches_one_stream(rel_pos, mem_len):
     """The three-stream schedule of step() (weight gradients and updates beside the
     error-gradient chain) against the same steps on one stream: equal up to the order of fp32
     atomic additions, over more iterations than the rings are deep."""
     c = dict(n_layer=4, d_model=128, n_head=2, d_head=64, d_ff=256, vocab=512, seq_len=96, mem_len=mem_len, batch=2,
-             n_module=4, rel_pos=rel_pos, dtype=1, optimizer=1, embed_warm_mode=0)
-    steps, lr = 7, 1e-3
+             n_module=4, rel_pos=rel_pos, dtype=1, optimizer=0, embed_warm_mode=0)
+    steps, lr = 7, 0.05
     blobs = S.init_params(c, seed=5, std=0.05, perturb=0.05)
     tok, tgt = S.token_batches(c["vocab"], c["batch"], c["seq_len"], steps, 1.1, 6, contiguous=bool(mem_len))
     dtok = torch.from_numpy(tok).cuda(); dtgt = torch.from_numpy(tgt).cuda()
@@ -179,9 +197,9 @@ def test_stream_overlap_matches_one_stream(rel_pos, mem_len):
     (la, wa), (lb, wb) = out
     assert np.allclose(la, lb, rtol=1e-4, atol=0)
     for a, b in zip(wa, wb):
-        # Adam turns a last-bit difference of a tiny gradient into a step of up to lr
-        assert np.abs(a - b).max() <= 2 * lr * steps
-        assert rel_err(a, b) < 2e-3
+        # SGD: a last-bit difference of an fp32 sum can flip the bf16 rounding of a weight's
+        # copy now and then, nothing more
+        assert rel_err(a, b) < 1e-3
 
 
 def test_timing_hooks():
@@ -314,4 +332,12 @@ def test_bench_config_full_size_first_steps():
     size: loss, every gradient store and the updated weights of the first two iterations
     against the oracle.  bf16 tolerance; see run_both for the Adam-conditioned weight check."""
     c = dict(S.CONFIGS["cfg2"])
+    run_both(c, steps=2, lr=c["lr"], seed=0, tol=2e-2)
+
+
+def test_xl_config_full_size_first_steps():
+    """The Transformer-XL workload with widths off the tile grid (16 layers, d=410, 10 heads of 41,
+    d_ff=2100, segment and memory 150) at full size, stored zero-padded: two iterations (empty,
+    then full memory) against the oracle."""
+    c = dict(S.CONFIGS["cfg3"])
     run_both(c, steps=2, lr=c["lr"], seed=0, tol=2e-2)
