@@ -141,6 +141,14 @@ int64_t ouro_current_step(const ouro_model* m);
 int ouro_slot_index(int K, int id, int64_t t, int write, int64_t* slot, int64_t* tau);
 int ouro_ring_depth(int K, int id, int64_t* depth);
 
+/* --- step size (Section 4.1: gradual warm-up, then a cosine schedule); pure host function ---
+ * *lr = gamma_t for iteration t >= 0: base*(t+1)/warmup while t < warmup; then
+ * floor + (base-floor)*(1+cos(pi*(t-warmup)/(total-warmup)))/2 until t = total; floor from
+ * there on.  Requires 0 <= warmup < total (warmup = 0: no warm-up) and 0 <= floor <= base;
+ * OURO_E_ARG otherwise.  The caller passes the result to ouro_step / ouro_delayed_update, which
+ * take the step size per call (a stale gradient is applied with the current gamma_t). */
+int ouro_lr_schedule(double base, int64_t warmup, int64_t total, double floor, int64_t t, double* lr);
+
 /* --- test / debug surface --- */
 int ouro_debug_slot_tag(ouro_model* m, int id, int64_t slot, int64_t* tag); /* -1 = never written */
 int ouro_debug_last_read(ouro_model* m, int id, int64_t* slot, int64_t* tau);

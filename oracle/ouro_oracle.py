@@ -16,6 +16,8 @@ What it computes, with the passage of the paper each part follows:
   * The tied matrix uses g_V = 1/2 dV_o(t) + 1/2 dV_i(t-K+1), zero while t-K+1 < 0
     (Eq. 9; `embed_warm_mode=1` is the term-wise reading where only the V_i term is
     dropped during those steps).
+  * The step size follows a linear warm-up and then a cosine decay (`learning_rate`,
+    Section 4.1).
   * SGD (Algorithm 1) or Adam (Algorithm 2, appendix): every group steps at every t,
     also with a zero gradient; bias correction uses the global t+1; epsilon is added
     outside the square root after bias correction.
@@ -335,6 +337,23 @@ def full_gradient(cfg, layers, V, tokens, targets, mems=None):
     loss, fw = model_forward(cfg, layers, V, V, tokens, targets, mems)
     grads, dVi, dVo = model_backward(cfg, layers, V, V, tokens, targets, fw)
     return loss, grads, dVi, dVo, fw["inputs"]
+
+
+# -------------------------------------------------------------------------- step size
+def learning_rate(t, base, warmup, total, floor=0.0):
+    """Step size gamma_t of iteration t = 0, 1, ... (Section 4.1, "Warm-up Training" and
+    the cosine schedule named beside the optimiser settings).
+
+    Reading (the paper gives the two phases and the warm-up length, not the formula):
+    a gradual linear warm-up that reaches `base` at the last warm-up iteration,
+    gamma_t = base * (t+1) / warmup for t < warmup, then one half cosine period from
+    `base` down to `floor` at iteration `total` (the cited restart schedule with a
+    single period), constant `floor` afterwards."""
+    if t < warmup:
+        return base * (t + 1) / warmup
+    if t >= total:
+        return floor
+    return floor + (base - floor) * 0.5 * (1.0 + math.cos(math.pi * (t - warmup) / (total - warmup)))
 
 
 # ------------------------------------------------------------------- training iteration

@@ -63,6 +63,7 @@ def lib():
         "ouro_current_step": (i64, [vp]),
         "ouro_slot_index": (i32, [i32, i32, i64, i32, P(i64), P(i64)]),
         "ouro_ring_depth": (i32, [i32, i32, P(i64)]),
+        "ouro_lr_schedule": (i32, [C.c_double, i64, i64, C.c_double, i64, P(C.c_double)]),
         "ouro_debug_slot_tag": (i32, [vp, i32, i64, P(i64)]),
         "ouro_debug_last_read": (i32, [vp, i32, P(i64), P(i64)]),
         "ouro_debug_inject_grad": (i32, [vp, i32, vp, i64]),
@@ -133,6 +134,13 @@ def slot_index(K, store, t, write):
     s, tau = C.c_int64(), C.c_int64()
     check(lib().ouro_slot_index(K, store, t, int(write), C.byref(s), C.byref(tau)))
     return s.value, tau.value
+
+
+def lr_schedule(base, warmup, total, t, floor=0.0):
+    """Step size of iteration t: linear warm-up, then cosine decay to `floor` at `total`."""
+    v = C.c_double()
+    check(lib().ouro_lr_schedule(float(base), int(warmup), int(total), float(floor), int(t), C.byref(v)))
+    return v.value
 
 
 def ring_depth(K, store):

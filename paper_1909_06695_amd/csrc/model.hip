@@ -60,6 +60,16 @@ extern "C" int ouro_slot_index(int K, int id, int64_t t, int write, int64_t* slo
   return OURO_OK;
 }
 
+extern "C" int ouro_lr_schedule(double base, int64_t warmup, int64_t total, double floor, int64_t t, double* lr) {
+  if (!lr) return fail(OURO_E_ARG, "lr_schedule: lr is null");
+  if (!(warmup >= 0 && warmup < total && t >= 0 && floor >= 0 && floor <= base))
+    return fail(OURO_E_ARG, "lr_schedule: need 0 <= warmup < total, t >= 0, 0 <= floor <= base");
+  if (t < warmup) *lr = base * (double)(t + 1) / (double)warmup;
+  else if (t >= total) *lr = floor;
+  else *lr = floor + (base - floor) * 0.5 * (1.0 + std::cos(M_PI * (double)(t - warmup) / (double)(total - warmup)));
+  return OURO_OK;
+}
+
 // ------------------------------------------------------------------------------ layout
 struct LayerOff {   // element offsets inside a module blob
   size_t W_qkv, W_o, W_r, u, v, ln1_g, ln1_b, W_1, b_1, W_2, b_2, ln2_g, ln2_b, end;

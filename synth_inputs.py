@@ -74,6 +74,23 @@ def token_batches(vocab: int, batch: int, seq_len: int, steps: int, s: float, se
     return np.ascontiguousarray(tok), np.ascontiguousarray(tgt)
 
 
+def markov_token_batches(vocab: int, batch: int, seq_len: int, steps: int, s: float, seed: int,
+                         follow: float = 0.75):
+    """(tokens, targets) int32 [steps, batch, seq_len] from a first-order Markov source:
+    with probability `follow` the next id is a fixed function of the current one
+    (id * 5 + 3 mod vocab), otherwise a fresh Zipf(s) draw.  A structured stand-in for
+    text: its entropy rate is well below its unigram entropy, so a model that learns
+    the context beats any context-free predictor.  Every step draws fresh blocks."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    fresh = zipf_tokens(rng, (steps, batch, seq_len + 1), vocab, s)
+    keep = rng.random(size=(steps, batch, seq_len + 1)) < follow
+    blk = fresh.copy()
+    for i in range(1, seq_len + 1):
+        succ = (blk[:, :, i - 1].astype(np.int64) * 5 + 3) % vocab
+        blk[:, :, i] = np.where(keep[:, :, i], succ, fresh[:, :, i])
+    return np.ascontiguousarray(blk[:, :, :seq_len]), np.ascontiguousarray(blk[:, :, 1:])
+
+
 def layer_param_layout(d_model: int, n_head: int, d_head: int, d_ff: int, rel_pos: int):
     """Ordered (name, shape, kind) list of one layer's parameters in the fp32 blob.
 

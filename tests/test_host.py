@@ -84,3 +84,16 @@ def test_create_model_rejects_bad_arena_without_touching_it():
     assert rc == binding.E_ARENA and not h.value
     rc = P.lib().ouro_create_model(ctypes.byref(cfg), ctypes.c_void_p(256), 16, None, ctypes.byref(h))
     assert rc == binding.E_ARENA and not h.value
+
+
+def test_lr_schedule_matches_the_oracle():
+    """The library's host-side step-size function against the oracle's, over both phases and
+    the boundaries (both fp64: agreement to rounding); bad arguments are refused."""
+    from oracle import ouro_oracle as O
+    for base, W, T, floor in [(2.5e-4, 5000, 200000, 0.0), (1e-3, 0, 1000, 1e-5), (0.1, 50, 51, 0.0), (3e-4, 500, 40000, 3e-6)]:
+        for t in sorted({0, 1, W - 1 if W else 0, W, W + 1, (W + T) // 2, T - 1, T, T + 7, 12345 % (T + 1)}):
+            got, ref = P.lr_schedule(base, W, T, t, floor), O.learning_rate(t, base, W, T, floor)
+            assert abs(got - ref) <= 1e-15 + 1e-13 * abs(ref), (base, W, T, floor, t)
+    for bad in [(1.0, 10, 10, 0, 0.0), (1.0, -1, 10, 0, 0.0), (1.0, 2, 10, -1, 0.0), (1.0, 2, 10, 0, 2.0), (1.0, 2, 10, 0, -0.1)]:
+        with pytest.raises(P.OuroError):
+            P.lr_schedule(bad[0], bad[1], bad[2], bad[3], bad[4])

@@ -211,3 +211,30 @@ def test_xl_memory_carry():
     assert orc.mems[0].shape == (2, 7, 8)                       # last 7 rows of [old ; new]
     assert np.array_equal(orc.mems[0][:, :2], first_inputs[:, 3:])
     assert orc.brute_check(1) == 0.0
+
+
+def test_learning_rate_schedule_closed_forms():
+    """Warm-up then cosine (Section 4.1), pinned by what the two phases fix: the warm-up is an
+    arithmetic progression that ends exactly at the base rate; the cosine phase starts there,
+    passes the midpoint of [floor, base] half-way, is point-symmetric about it, decreases
+    monotonically and ends at the floor, where it stays."""
+    base, W, T, floor = 2.5e-4, 5000, 200000, 1e-6
+    lr = lambda t: O.learning_rate(t, base, W, T, floor)
+    assert lr(0) == base / W and lr(W - 1) == base
+    d = [lr(t + 1) - lr(t) for t in range(0, W - 1, 97)]
+    assert np.allclose(d, base / W, rtol=1e-9)
+    assert lr(W) == base
+    mid = W + (T - W) // 2
+    assert abs(lr(mid) - 0.5 * (base + floor)) < 1e-15
+    for x in (1, 17, 4000, 90000):
+        assert abs(lr(W + x) + lr(T - x) - (base + floor)) < 1e-15
+    ts = np.arange(W, T + 1, 331)
+    v = np.array([lr(int(t)) for t in ts])
+    assert np.all(np.diff(v) < 0)
+    assert lr(T) == floor and lr(T + 12345) == floor
+    # quarter points of a cosine: (1 + cos(pi/4)) / 2 and (1 + cos(3 pi/4)) / 2
+    q = (T - W) // 4
+    assert abs(lr(W + q) - (floor + (base - floor) * (2 + np.sqrt(2)) / 4)) < 1e-15
+    assert abs(lr(W + 3 * q) - (floor + (base - floor) * (2 - np.sqrt(2)) / 4)) < 1e-15
+    # no warm-up
+    assert O.learning_rate(0, 1.0, 0, 10) == 1.0 and abs(O.learning_rate(5, 1.0, 0, 10) - 0.5) < 1e-15
