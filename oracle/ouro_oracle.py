@@ -30,6 +30,11 @@ independent autograd model in tests/, not by the paper: "parity unpinned" agains
 paper for the layer internals and for whole-trajectory loss values (the paper prints
 none).
 
+`RecomputeOracle` is the memory-saving schedule of Section 3.2 ("Memory Consumption") and
+Section 4.1 ("Repeatable Dropout"): every module stores only its input of each iteration,
+re-runs its forward pass on the input of mini-batch t-K+k with the weights it holds now, and
+back-propagates the error gradient the module above produced one iteration earlier.
+
 The oracle keeps the gradient of every past step in an unbounded list indexed by the
 step number (no modulo arithmetic), and `brute_check` re-derives any used gradient from
 a stored copy of that step's full weights and batch.
@@ -456,3 +461,147 @@ class Oracle:
                 for name in grads[l]:
                     worst = max(worst, float(np.abs(grads[l][name] - self.grad_hist[tau][0][l][name]).max()))
         return worst
+
+
+# ------------------------------------------------- stored-input / recompute schedule
+def module_fwd(cfg, k, layers_k, V, inp, mems_k):
+    """Forward pass of module k on its stored input: token ids for k = 1 (the embedding
+    lookup of Eq. 1 belongs to module 1), the hidden state at the module boundary
+    otherwise.  Returns the module's output and the per-layer caches."""
+    if k == 1:
+        h = cfg.emb_scale * V[inp]
+        if not cfg.rel_pos:
+            h = h + sinusoid(np.arange(inp.shape[1]), cfg.d_model)[None]
+    else:
+        h = inp
+    caches = []
+    for i, p in enumerate(layers_k):
+        h, c = layer_fwd(cfg, p, h, None if mems_k is None else mems_k[i])
+        caches.append(c)
+    return h, caches
+
+
+def module_bwd(cfg, layers_k, caches, dh):
+    """Eq. 6 inside one module: error gradient of the module's output -> per-layer weight
+    gradients and the error gradient of the module's input."""
+    grads = [None] * len(layers_k)
+    for i in reversed(range(len(layers_k))):
+        dh, grads[i] = layer_bwd(cfg, layers_k[i], dh, caches[i])
+    return dh, grads
+
+
+class RecomputeOracle(Oracle):
+    """The schedule the paper runs on its GPUs (Section 3.2, "Memory Consumption"): module k
+    stores its input of every iteration instead of a gradient.  At iteration t it
+
+      * runs the forward pass of mini-batch t on the current weights (all modules in
+        sequence; the loss reported is that of mini-batch t),
+      * and, "in parallel" over k, takes mini-batch tau = t-K+k: it recomputes its
+        activations from the stored input of iteration tau with the weights it holds at
+        iteration t, and back-propagates the error gradient of its output that module
+        k+1 produced at iteration t-1 (module K differentiates the loss of mini-batch t
+        itself).  The error gradient of its own input goes to module k-1, which uses
+        it at iteration t+1; module 1 turns it into dV_i of mini-batch t-K+1.
+      * Then every group takes its step with the gradient just computed (zero while
+        tau < 0); V mixes dV_o(t) and that dV_i as in Eq. 9.
+
+    Reading: the paper says that inputs are stored and activations recomputed, not with
+    which weights; this class recomputes with the module's current weights (what a
+    device that keeps one copy of its weights does).  With frozen weights the gradients
+    coincide with Eq. 8's; with moving weights they differ from it at first order in the
+    step size.  Segment memories are part of a module's stored input.
+
+    grad_hist[t] holds what iteration t computed: module k's entry is the gradient of
+    mini-batch t-K+k (zeros while that is negative), dV_i that of mini-batch t-K+1."""
+
+    def __init__(self, cfg, blobs, keep_history=True):
+        super().__init__(cfg, blobs, keep_history)
+        self.inputs = {}         # (k, t) -> (input of module k at iteration t, its layers' memories)
+        self.mail = {}           # k -> (tau, error gradient of module k's output for mini-batch tau)
+        self.batch_of = []       # t -> {k: tau}
+
+    def step(self, tokens, targets, lr):
+        c, t, K = self.cfg, self.t, self.cfg.n_module
+        tokens = np.asarray(tokens); targets = np.asarray(targets)
+        # forward pass of mini-batch t, storing every module's input
+        h = tokens
+        layer_inputs = []
+        for k in range(1, K + 1):
+            ls = list(self.module_layers(k))
+            mems_k = None if self.mems is None else [self.mems[l] for l in ls]
+            self.inputs[(k, t)] = (h.copy(), copy.deepcopy(mems_k))
+            if k == 1:
+                x = c.emb_scale * self.V[tokens]
+                if not c.rel_pos:
+                    x = x + sinusoid(np.arange(tokens.shape[1]), c.d_model)[None]
+            else:
+                x = h
+            caches = []
+            for i, l in enumerate(ls):
+                layer_inputs.append(x)
+                x, cc = layer_fwd(c, self.layers[l], x, None if mems_k is None else mems_k[i])
+                caches.append(cc)
+            h = x
+        hL, top_caches = h, caches
+        logits = hL @ self.V.T
+        loss, lse = cross_entropy_fwd(logits, targets)
+        # backward passes, one per module, all from the state iteration t-1 left behind
+        N, d = tokens.size, c.d_model
+        grads = [{n: np.zeros_like(a) for n, a in p.items()} for p in self.layers]
+        dVi, dVo = np.zeros_like(self.V), np.zeros_like(self.V)
+        new_mail, batch_of = {}, {}
+        for k in range(1, K + 1):
+            tau = t - K + k
+            batch_of[k] = tau if tau >= 0 else -1
+            if tau < 0:
+                continue
+            ls = list(self.module_layers(k))
+            layers_k = [self.layers[l] for l in ls]
+            if k == K:                                        # tau = t: the pass just made
+                G = cross_entropy_bwd(logits, lse, targets)
+                dVo = G.reshape(N, -1).T @ hL.reshape(N, d)
+                dh = G @ self.V
+                caches_k = top_caches
+            else:
+                inp, mems_k = self.inputs[(k, tau)]
+                _, caches_k = module_fwd(c, k, layers_k, self.V, inp, mems_k)
+                mtau, dh = self.mail[k]
+                assert mtau == tau
+            dx, gk = module_bwd(c, layers_k, caches_k, dh)
+            for i, l in enumerate(ls):
+                grads[l] = gk[i]
+            if k > 1:
+                new_mail[k - 1] = (tau, dx)
+            else:
+                tok_tau = self.inputs[(1, tau)][0]
+                np.add.at(dVi, tok_tau.reshape(-1), c.emb_scale * dx.reshape(N, d))
+        self.mail = new_mail
+        self.grad_hist.append((grads, dVi, dVo))
+        self.batch_of.append(batch_of)
+        used = {}
+        for k in range(1, K + 1):
+            used[k] = t if batch_of[k] >= 0 else -1
+            for l in self.module_layers(k):
+                for name in self.layers[l]:
+                    mm = self.m[l][name] if c.optimizer == 1 else None
+                    vv = self.v[l][name] if c.optimizer == 1 else None
+                    self._apply(self.layers[l][name], grads[l][name], mm, vv, lr)
+        if batch_of[1] >= 0:                                  # Eq. 9
+            gV = 0.5 * dVo + 0.5 * dVi
+            used[0] = (t, t)
+        elif c.embed_warm_mode == 1:
+            gV = 0.5 * dVo
+            used[0] = (t, -1)
+        else:
+            gV = np.zeros_like(self.V)
+            used[0] = (-1, -1)
+        self._apply(self.V, gV, getattr(self, "mV", None), getattr(self, "vV", None), lr)
+        self.used.append(used)
+        if c.mem_len > 0:
+            new = []
+            for l in range(c.n_layer):
+                cat = layer_inputs[l] if self.mems is None else np.concatenate([self.mems[l], layer_inputs[l]], axis=1)
+                new.append(cat[:, -c.mem_len:].copy())
+            self.mems = new
+        self.t += 1
+        return loss

@@ -238,3 +238,132 @@ def test_learning_rate_schedule_closed_forms():
     assert abs(lr(W + 3 * q) - (floor + (base - floor) * (2 - np.sqrt(2)) / 4)) < 1e-15
     # no warm-up
     assert O.learning_rate(0, 1.0, 0, 10) == 1.0 and abs(O.learning_rate(5, 1.0, 0, 10) - 0.5) < 1e-15
+
+
+# ------------------------------------------------ stored-input / recompute schedule
+@pytest.mark.parametrize("K,kw", [(2, {}), (3, {}), (4, {}), (3, dict(rel_pos=1, mem_len=7, L=5))])
+def test_recompute_with_frozen_weights_is_eq8(K, kw):
+    """With step size 0 the weights never move, so recomputing from the stored input with the
+    current weights must give exactly Eq. 8's gradient: the k-th slice of the full gradient of
+    mini-batch t-K+k.  This pins the index plumbing of the schedule (which stored input, which
+    error gradient, which iteration) to the already pinned full gradient."""
+    c, cfg, blobs, tok, tgt = make(K, seed=10 + K, steps=K + 3, **kw)
+    a, b = O.Oracle(cfg, blobs), O.RecomputeOracle(cfg, blobs)
+    for t in range(K + 3):
+        la, lb = a.step(tok[t], tgt[t], 0.0), b.step(tok[t], tgt[t], 0.0)
+        assert la == lb
+        for k in range(1, K + 1):
+            tau = t - K + k
+            assert b.batch_of[t][k] == (tau if tau >= 0 else -1)
+            assert b.used[t][k] == (t if tau >= 0 else -1)
+            for l in b.module_layers(k):
+                for n in b.layers[l]:
+                    ref = a.grad_hist[tau][0][l][n] if tau >= 0 else np.zeros_like(b.layers[l][n])
+                    assert np.abs(b.grad_hist[t][0][l][n] - ref).max() < 1e-12, (t, k, l, n)
+        ti = t - K + 1
+        assert np.abs(b.grad_hist[t][1] - (a.grad_hist[ti][1] if ti >= 0 else 0.0)).max() < 1e-12
+        assert np.abs(b.grad_hist[t][2] - a.grad_hist[t][2]).max() < 1e-12
+
+
+@pytest.mark.parametrize("opt", [0, 1])
+def test_recompute_K1_is_the_plain_schedule(opt):
+    c, cfg, blobs, tok, tgt = make(1, L=2, steps=4, optimizer=opt)
+    a, b = O.Oracle(cfg, blobs), O.RecomputeOracle(cfg, blobs)
+    for t in range(4):
+        assert a.step(tok[t], tgt[t], 0.03) == b.step(tok[t], tgt[t], 0.03)
+        for k in range(2):
+            assert np.array_equal(a.module_blob(k), b.module_blob(k))
+
+
+@pytest.mark.parametrize("opt,kw", [(0, {}), (1, {}), (0, dict(rel_pos=1, mem_len=6))])
+def test_recompute_schedule_against_autograd_pipeline(opt, kw):
+    """The whole schedule rebuilt from torch autograd, module by module: every iteration each
+    module re-runs its layers on its stored (detached) input of mini-batch t-K+k with the
+    weights it holds now and calls backward with the error gradient its upper neighbour left the
+    iteration before; the tied matrix mixes the two halves as in Eq. 9.  Weights, error
+    gradients and losses must follow the oracle's over more iterations than the pipeline is deep,
+    with weights that move (so a recompute with stale weights, or a wrong mailbox delay, shows)."""
+    K, L, steps = 3, 4, 7
+    c, cfg, blobs, tok, tgt = make(K, L=L, seed=5, steps=steps, optimizer=opt, **kw)
+    orc = O.RecomputeOracle(cfg, blobs)
+    lr = 0.05 if opt == 0 else 0.01
+    tl = [{n: torch.tensor(a.copy(), requires_grad=True) for n, a in p.items()} for p in orc.layers]
+    tV = torch.tensor(orc.V.copy(), requires_grad=True)
+    params = [x for p in tl for x in p.values()] + [tV]
+    optim = torch.optim.SGD(params, lr=lr) if opt == 0 else torch.optim.Adam(params, lr=lr, betas=(0.9, 0.999), eps=1e-8)
+    bounds = np.concatenate([[0], np.cumsum(cfg.layers_per_module)])
+    stored, mail, mems = {}, {}, None
+    for t in range(steps):
+        lo = orc.step(tok[t], tgt[t], lr)
+        optim.zero_grad()
+        for x in params:
+            x.grad = torch.zeros_like(x)
+        ttok, ttgt = torch.tensor(tok[t]), torch.tensor(tgt[t])
+        with torch.no_grad():                                  # forward of mini-batch t: store inputs
+            h, layer_in = ttok, []
+            for k in range(1, K + 1):
+                mk = None if mems is None else [mems[l] for l in range(bounds[k - 1], bounds[k])]
+                stored[(k, t)] = (h, mk)
+                x = torch_ref.embed(cfg, tV, h) if k == 1 else h
+                for i, l in enumerate(range(bounds[k - 1], bounds[k])):
+                    layer_in.append(x)
+                    x = torch_ref.layer_forward(cfg, tl[l], x, None if mk is None else mk[i])
+                h = x
+            loss_t = torch.nn.functional.cross_entropy(h.reshape(-1, cfg.d_model) @ tV.t(), ttgt.reshape(-1).long()).item()
+        assert abs(lo - loss_t) < 1e-12
+        new_mail = {}
+        gVi = torch.zeros_like(tV); gVo = torch.zeros_like(tV)
+        for k in range(1, K + 1):
+            tau = t - K + k
+            if tau < 0:
+                continue
+            inp, mk = stored[(k, tau)]
+            Vi = tV.detach().clone().requires_grad_(True)
+            Vo = tV.detach().clone().requires_grad_(True)
+            if k == 1:
+                x0 = None
+                x = torch_ref.embed(cfg, Vi, inp)
+            else:
+                x0 = inp.detach().clone().requires_grad_(True)
+                x = x0
+            for i, l in enumerate(range(bounds[k - 1], bounds[k])):
+                x = torch_ref.layer_forward(cfg, tl[l], x, None if mk is None else mk[i])
+            if k == K:
+                lossk = torch.nn.functional.cross_entropy(x.reshape(-1, cfg.d_model) @ Vo.t(), ttgt.reshape(-1).long())
+                lossk.backward()
+                gVo = Vo.grad
+            else:
+                x.backward(mail[k])
+            if k == 1:
+                gVi = Vi.grad
+            else:
+                new_mail[k - 1] = x0.grad
+        mail = new_mail
+        if t - K + 1 >= 0:
+            tV.grad = 0.5 * gVo + 0.5 * gVi
+        else:
+            tV.grad = torch.zeros_like(tV)
+        optim.step()
+        if cfg.mem_len:
+            mems = [(layer_in[l] if mems is None else torch.cat([mems[l], layer_in[l]], dim=1))[:, -cfg.mem_len:] for l in range(L)]
+        for k in list(orc.mail):
+            assert np.abs(orc.mail[k][1] - mail[k].numpy()).max() < 1e-10, (t, k)
+        for l in range(L):
+            for n in tl[l]:
+                assert np.abs(orc.layers[l][n] - tl[l][n].detach().numpy()).max() < 1e-9, (t, l, n)
+        assert np.abs(orc.V - tV.detach().numpy()).max() < 1e-9
+
+
+def test_recompute_differs_from_eq8_once_weights_move():
+    """The two schedules are different iterations: same losses and gradients until the first
+    delayed gradient meets weights that have moved, different from there on (so the frozen-weight
+    pin above does not hide an oracle that simply replays Eq. 8)."""
+    K = 3
+    c, cfg, blobs, tok, tgt = make(K, seed=2, steps=6)
+    a, b = O.Oracle(cfg, blobs), O.RecomputeOracle(cfg, blobs)
+    diff = []
+    for t in range(6):
+        a.step(tok[t], tgt[t], 0.1); b.step(tok[t], tgt[t], 0.1)
+        diff.append(max(np.abs(a.module_blob(k) - b.module_blob(k)).max() for k in range(K + 1)))
+    assert diff[0] == 0.0                      # only module K (tau = t) has a gradient: identical
+    assert diff[-1] > 1e-4
