@@ -68,6 +68,13 @@ typedef struct {
   int32_t embed_warm_mode; /* Eq. 9 while t-K+1 < 0.  0: g_V = 0 (literal);
                               1: only the input-embedding term is dropped                   */
   float emb_scale;   /* factor on the embedding lookup (1.0)                                */
+  int32_t schedule;  /* 0: Eq. 8 to the letter: the gradient of mini-batch t-K+k at the full
+                           weights of iteration t-K+k, kept in a ring of gradients;
+                        1: the memory-saving schedule of Section 3.2 ("Memory Consumption"):
+                           each module keeps its inputs instead, recomputes its activations
+                           of mini-batch t-K+k with the weights it holds at iteration t and
+                           back-propagates the error gradient its upper neighbour produced
+                           at iteration t-1 (needs mem_len = 0)                             */
 } ouro_config;
 
 /* Parameter groups: group 0 is V [vocab, d_model]; group k = 1..K is module k.
@@ -122,7 +129,17 @@ int ouro_get_params(ouro_model* m, int group, float* dst, int64_t n, int dst_is_
  *   lr is gamma_t of the current iteration.
  * ouro_step: all of the above for one mini-batch.  If host_loss is not NULL the
  *   stream is synchronised and the loss (and OURO_E_TOKEN, if any id was out of
- *   range; such ids are skipped, never dereferenced) is returned. */
+ *   range; such ids are skipped, never dereferenced) is returned.
+ *
+ * schedule = 1 keeps the same calls and order.  module_forward(k), k < K, also stores the
+ *   module's input (token ids for k = 1) in a ring of depth K-k+1, tagged t.
+ *   module_backward(k), k < K, does nothing while t-K+k < 0; otherwise it recomputes the
+ *   module's activations from the stored input of iteration t-K+k (OURO_E_STALE if the slot's
+ *   tag differs) with the current weights, takes the error gradient module k+1 left at
+ *   iteration t-1 and writes the gradient store of module k (depth 1, tagged t) and the error
+ *   gradient for module k-1 (k = 1: dV_i of mini-batch t-K+1).  The token buffer of
+ *   iteration t may be released once module_forward(1) has run on the stream.
+ *   delayed_update applies what this iteration computed (zero while t-K+k < 0; Eq. 9 for V). */
 int ouro_module_forward(ouro_model* m, int k, const int32_t* dev_tokens, const int32_t* dev_targets);
 int ouro_module_backward(ouro_model* m, int k);
 int ouro_delayed_update(ouro_model* m, int group, float lr);
@@ -152,6 +169,10 @@ int ouro_lr_schedule(double base, int64_t warmup, int64_t total, double floor, i
 /* --- test / debug surface --- */
 int ouro_debug_slot_tag(ouro_model* m, int id, int64_t slot, int64_t* tag); /* -1 = never written */
 int ouro_debug_last_read(ouro_model* m, int id, int64_t* slot, int64_t* tau);
+/* schedule = 1: tag (iteration, -1 = never written) of slot `slot` of module k's input ring, and
+ * the slot and mini-batch the last module_backward(k) recomputed from (-1, -1: it computed nothing). */
+int ouro_debug_input_tag(ouro_model* m, int k, int64_t slot, int64_t* tag);
+int ouro_debug_last_input_read(ouro_model* m, int k, int64_t* slot, int64_t* tau);
 /* Stands in for forward+backward of the current iteration: writes the fp32 host vector g
  * (the store's element count) as store `id`'s gradient of iteration t.  After all K+2
  * stores are injected the iteration is in the "backward done" state. */

@@ -30,7 +30,7 @@ class Config(C.Structure):
                 ("n_module", C.c_int32), ("layers_per_module", C.POINTER(C.c_int32)),
                 ("rel_pos", C.c_int32), ("dtype", C.c_int32), ("optimizer", C.c_int32),
                 ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
-                ("embed_warm_mode", C.c_int32), ("emb_scale", C.c_float)]
+                ("embed_warm_mode", C.c_int32), ("emb_scale", C.c_float), ("schedule", C.c_int32)]
 
 
 _lib = None
@@ -66,6 +66,8 @@ def lib():
         "ouro_lr_schedule": (i32, [C.c_double, i64, i64, C.c_double, i64, P(C.c_double)]),
         "ouro_debug_slot_tag": (i32, [vp, i32, i64, P(i64)]),
         "ouro_debug_last_read": (i32, [vp, i32, P(i64), P(i64)]),
+        "ouro_debug_input_tag": (i32, [vp, i32, i64, P(i64)]),
+        "ouro_debug_last_input_read": (i32, [vp, i32, P(i64), P(i64)]),
         "ouro_debug_inject_grad": (i32, [vp, i32, vp, i64]),
         "ouro_get_grad_slot": (i32, [vp, i32, i64, vp, i64]),
         "ouro_get_mems": (i32, [vp, i32, vp, P(i64)]),
@@ -116,13 +118,13 @@ def check(rc):
 
 def make_config(n_layer, d_model, n_head, d_head, d_ff, vocab, seq_len, batch, n_module=1, mem_len=0,
                 rel_pos=0, dtype=0, optimizer=0, layers_per_module=None, beta1=0.9, beta2=0.999,
-                eps=1e-8, embed_warm_mode=0, emb_scale=1.0, **_):
+                eps=1e-8, embed_warm_mode=0, emb_scale=1.0, schedule=0, **_):
     cfg = Config()
     cfg.n_layer, cfg.d_model, cfg.n_head, cfg.d_head = n_layer, d_model, n_head, d_head
     cfg.d_ff, cfg.vocab, cfg.seq_len, cfg.mem_len, cfg.batch = d_ff, vocab, seq_len, mem_len, batch
     cfg.n_module, cfg.rel_pos, cfg.dtype, cfg.optimizer = n_module, rel_pos, dtype, optimizer
     cfg.beta1, cfg.beta2, cfg.eps = beta1, beta2, eps
-    cfg.embed_warm_mode, cfg.emb_scale = embed_warm_mode, emb_scale
+    cfg.embed_warm_mode, cfg.emb_scale, cfg.schedule = embed_warm_mode, emb_scale, schedule
     if layers_per_module is not None:
         arr = (C.c_int32 * len(layers_per_module))(*layers_per_module)
         cfg._keep = arr
@@ -237,6 +239,16 @@ class Model:
     def last_read(self, store):
         s, tau = C.c_int64(), C.c_int64()
         check(self.L.ouro_debug_last_read(self.h, store, C.byref(s), C.byref(tau)))
+        return s.value, tau.value
+
+    def input_tag(self, k, slot):
+        t = C.c_int64()
+        check(self.L.ouro_debug_input_tag(self.h, k, slot, C.byref(t)))
+        return t.value
+
+    def last_input_read(self, k):
+        s, tau = C.c_int64(), C.c_int64()
+        check(self.L.ouro_debug_last_input_read(self.h, k, C.byref(s), C.byref(tau)))
         return s.value, tau.value
 
     def grad_count(self, store):

@@ -177,6 +177,17 @@ struct ouro_model {
   char *ds2[2], *dz[2], *ds1[2], *dqkv[2];
   float *attn_scratch, *dr_f32[2], *dbg_f32, *dh_f32;
   size_t dbg_floats;
+  // Stored-input schedule (cfg.schedule == 1): module k < K keeps the input of its last
+  // K-k+1 forward passes (token ids for k = 1, the hidden state at the boundary otherwise),
+  // tagged with the iteration; the error gradient of module k's output travels from module
+  // k+1 to module k through a double-buffered mailbox (written at t, read at t+1).
+  std::vector<char*> inring;
+  std::vector<size_t> instride;
+  std::vector<int64_t> indepth, in_last_slot, in_last_tau;
+  std::vector<std::vector<int64_t>> intags;
+  std::vector<char*> mail[2];
+  std::vector<int64_t> mailtag[2];
+  char* hscratch;                 // output of a recomputed module's last layer (never read)
   // iteration state
   int64_t t;
   int fwd_next, bwd_next;         // next module expected by forward (1..K+1) / backward (K..0)
@@ -241,6 +252,8 @@ static int validate(const ouro_config* c, std::vector<int>& lpm) {
   if (c->dtype != 0 && c->dtype != 1) return fail(OURO_E_CONFIG, "dtype must be 0 or 1");
   if (c->optimizer != 0 && c->optimizer != 1) return fail(OURO_E_CONFIG, "optimizer must be 0 or 1");
   if (c->embed_warm_mode != 0 && c->embed_warm_mode != 1) return fail(OURO_E_CONFIG, "embed_warm_mode must be 0 or 1");
+  if (c->schedule != 0 && c->schedule != 1) return fail(OURO_E_CONFIG, "schedule must be 0 or 1");
+  if (c->schedule == 1 && c->mem_len > 0) return fail(OURO_E_CONFIG, "schedule 1 with a segment memory is not supported");
   if (c->optimizer == 1 && !(c->beta1 >= 0 && c->beta1 < 1 && c->beta2 >= 0 && c->beta2 < 1 && c->eps > 0))
     return fail(OURO_E_CONFIG, "Adam constants out of range");
   if ((int64_t)c->batch * c->seq_len > (1 << 24)) return fail(OURO_E_CONFIG, "batch*seq_len too large");
@@ -333,7 +346,20 @@ static size_t lay_out(ouro_model& m, char* base) {
     m.gstride[id] = (m.pcount[grp] + 63) / 64 * 64;
     if (id == K + 1 && (int64_t)(vpad * d) > m.gstride[id]) m.gstride[id] = (int64_t)(vpad * d);   // dV_o rows of the padding
     ouro_ring_depth(K, id, &m.depth[id]);
+    if (c.schedule == 1) m.depth[id] = 1;     // a gradient is applied in the iteration that computes it
     m.ring[id] = (float*)P((size_t)m.depth[id] * m.gstride[id] * 4);
+  }
+  m.inring.assign(K + 1, nullptr); m.instride.assign(K + 1, 0); m.indepth.assign(K + 1, 0);
+  for (int p2 = 0; p2 < 2; ++p2) m.mail[p2].assign(K + 1, nullptr);
+  m.hscratch = nullptr;
+  if (c.schedule == 1) {
+    for (int k = 1; k < K; ++k) {
+      m.indepth[k] = K - k + 1;
+      m.instride[k] = ((k == 1 ? N * 4 : N * d * es) + 255) & ~(size_t)255;
+      m.inring[k] = P(m.instride[k] * (size_t)m.indepth[k]);
+      for (int p2 = 0; p2 < 2; ++p2) m.mail[p2][k] = P(N * d * es);
+    }
+    m.hscratch = P(N * d * es);
   }
   m.L.resize(L);
   const size_t qkv_elems = c.rel_pos ? (N * hd + B * S * 2 * hd) : (N * 3 * hd);
@@ -432,6 +458,10 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
   m->tags.resize(K + 2);
   for (int id = 0; id <= K + 1; ++id) m->tags[id].assign((size_t)m->depth[id], -1);
   m->last_slot.assign(K + 2, -1); m->last_tau.assign(K + 2, -1);
+  m->intags.resize(K + 1);
+  for (int k = 0; k <= K; ++k) m->intags[k].assign((size_t)m->indepth[k], -1);
+  m->in_last_slot.assign(K + 1, -1); m->in_last_tau.assign(K + 1, -1);
+  for (int p2 = 0; p2 < 2; ++p2) m->mailtag[p2].assign(K + 1, -1);
   m->t = 0; m->fwd_next = 1; m->bwd_next = K; m->upd_mask = 0; m->inject_mask = 0; m->mem_valid = 0;
   m->tok = m->tgt = nullptr;
   m->timing = 0;
@@ -593,13 +623,14 @@ static GemmDesc gd(const void* A, int lda, int tA, const void* B, int ldb, int t
 #define RUN(expr) do { int rc_ = (expr); if (rc_) return rc_; } while (0)
 
 // ------------------------------------------------------------------------------ forward
-static int layer_forward(ouro_model* m, int l) {
+// out_override: where the layer's output goes instead of the next layer's input buffer
+static int layer_forward(ouro_model* m, int l, char* out_override = nullptr) {
   const ouro_config& c = m->cfg;
   const int d = m->pd, F = m->pF, hd = m->phd, dn = c.d_model;   // stored widths; dn = normalised width
   const int N = m->N, T = c.seq_len, B = c.batch, es = m->esz;
   const LayerOff& o = m->loff[l];
   LayerBuf& b = m->L[l];
-  char* out = (l + 1 < c.n_layer) ? m->L[l + 1].x : m->hL;
+  char* out = out_override ? out_override : (l + 1 < c.n_layer) ? m->L[l + 1].x : m->hL;
   const int Mv = m->mem_valid, S = Mv + T;
   AttnDesc a;
   memset(&a, 0, sizeof a);
@@ -663,6 +694,14 @@ extern "C" int ouro_module_forward(ouro_model* m, int k, const int32_t* dev_toke
     HIPCHK(launch_embed_fwd(m->stream, c.dtype, m->tok, m->vT(), m->pe, m->L[0].x, m->N, c.seq_len, m->pd, c.vocab, c.emb_scale, m->flag));
   }
   if (k == K && !dev_targets) return fail(OURO_E_ARG, "module_forward(K) needs targets");
+  if (c.schedule == 1 && k < K) {
+    // the module's input of this iteration, for the backward pass K-k iterations from now
+    const int64_t slot = m->t % m->indepth[k];
+    char* dst = m->inring[k] + (size_t)slot * m->instride[k];
+    if (k == 1) HIPCHK(hipMemcpyAsync(dst, m->tok, (size_t)m->N * 4, hipMemcpyDeviceToDevice, m->stream));
+    else HIPCHK(hipMemcpyAsync(dst, m->L[m->first_layer[k - 1]].x, (size_t)m->N * m->pd * m->esz, hipMemcpyDeviceToDevice, m->stream));
+    m->intags[k][slot] = m->t;
+  }
   for (int l = m->first_layer[k - 1]; l < m->first_layer[k]; ++l) RUN(layer_forward(m, l));
   if (k == K) {
     m->tgt = dev_targets;
@@ -838,11 +877,41 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
   if (m->inject_mask) return fail(OURO_E_SEQUENCE, "module_backward after inject_grad in the same iteration");
   if (m->fwd_next != K + 1) return fail(OURO_E_SEQUENCE, "module_backward before forward of module %d", m->fwd_next);
   if (k != m->bwd_next) return fail(OURO_E_SEQUENCE, "module_backward(%d) but module %d is next", k, m->bwd_next);
+  const bool stored = c.schedule == 1;          // stored-input schedule: this pass is for mini-batch t-K+k
   int64_t slot, tau;
-  ouro_slot_index(K, k, m->t, 1, &slot, &tau);
+  if (stored) { slot = 0; tau = m->t - K + k; }
+  else ouro_slot_index(K, k, m->t, 1, &slot, &tau);
+  if (stored && tau < 0) {
+    // no error gradient has reached this module yet: it computes nothing (zero gradient)
+    m->in_last_slot[k] = -1; m->in_last_tau[k] = -1;
+    if (m->use_side) HIPCHK(hipEventRecord(m->ev_join, m->side));
+    m->bwd_next = k - 1;
+    return OURO_OK;
+  }
+  const int first = m->first_layer[k - 1], last = m->first_layer[k] - 1;
+  const int32_t* tok = m->tok;
+  char* dh_top = m->dhb[last % 3];
+  if (stored && k < K) {
+    // recompute the module's activations from its stored input of iteration tau with the
+    // weights it holds now; the last layer's output is not needed
+    const int64_t is = tau % m->indepth[k];
+    if (m->intags[k][is] != tau) return fail(OURO_E_STALE, "module %d input slot %lld holds iteration %lld, wanted %lld", k, (long long)is, (long long)m->intags[k][is], (long long)tau);
+    m->in_last_slot[k] = is; m->in_last_tau[k] = tau;
+    const char* src = m->inring[k] + (size_t)is * m->instride[k];
+    if (k == 1) {
+      tok = (const int32_t*)src;
+      HIPCHK(launch_embed_fwd(m->stream, c.dtype, tok, m->vT(), m->pe, m->L[0].x, N, c.seq_len, d, V, c.emb_scale, m->flag));
+    } else {
+      HIPCHK(hipMemcpyAsync(m->L[first].x, src, (size_t)N * d * m->esz, hipMemcpyDeviceToDevice, m->stream));
+    }
+    for (int l = first; l <= last; ++l) RUN(layer_forward(m, l, l == last ? m->hscratch : nullptr));
+    // error gradient of this module's output, left by module k+1 one iteration ago
+    const int pr = (int)((m->t + 1) & 1);
+    if (m->mailtag[pr][k] != tau) return fail(OURO_E_STALE, "module %d error gradient is of mini-batch %lld, wanted %lld", k, (long long)m->mailtag[pr][k], (long long)tau);
+    dh_top = m->mail[pr][k];
+  }
   float* gslot = m->slot_ptr(k, slot);
   HIPCHK(launch_fill_zero(m->stream, gslot, (size_t)m->gstride[k] * 4));
-  const int lastl = m->first_layer[K] - 1;
   if (k == K) {
     // Eq. 7 (right): dV_o = G^T h_L ; error gradient dh_L = G V
     float* dvo = m->slot_ptr(K + 1, 0);
@@ -859,7 +928,7 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
       RUN(run_gemm(m, g));
     }
     m->tags[K + 1][0] = m->t;
-    GemmDesc gh = gd(m->G, m->ldv, 0, m->vT(), d, 0, m->dhb[lastl % 3], d, N, d, Vx);
+    GemmDesc gh = gd(m->G, m->ldv, 0, m->vT(), d, 0, dh_top, d, N, d, Vx);
     if (c.dtype == 1 && gemm_uses_mfma(c.dtype, gh) && V >= 8192) {
       // The contraction runs over the whole vocabulary onto a narrow output: split it over
       // the grid (two workgroups per CU instead of one), adding into an fp32 buffer that is
@@ -867,16 +936,23 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
       HIPCHK(launch_fill_zero(m->stream, m->dh_f32, (size_t)N * d * 4));
       gh.C = m->dh_f32; gh.out_fp32 = 1; gh.accumulate = 1;
       RUN(run_gemm(m, gh));
-      HIPCHK(launch_convert(m->stream, c.dtype, m->dhb[lastl % 3], m->dh_f32, (size_t)N * d));
+      HIPCHK(launch_convert(m->stream, c.dtype, dh_top, m->dh_f32, (size_t)N * d));
     } else {
       RUN(run_gemm(m, gh));
     }
   }
   // layer l reads its output gradient from dhb[l % 3] and writes its input gradient to dhb[(l + 2) % 3]:
-  // three buffers, so that side-stream readers of layer l's input are two layers away from its next writer
-  for (int l = m->first_layer[k] - 1; l >= m->first_layer[k - 1]; --l) {
-    char* dh = m->dhb[l % 3];
+  // three buffers, so that side-stream readers of layer l's input are two layers away from its next writer.
+  // Stored-input schedule: the top layer of a module below K reads the mailbox instead, and the
+  // bottom layer of a module above 1 writes the mailbox of the module below.
+  for (int l = last; l >= first; --l) {
+    char* dh = l == last ? dh_top : m->dhb[l % 3];
     char* dx = m->dhb[(l + 2) % 3];
+    if (stored && k > 1 && l == first) {
+      const int pw = (int)(m->t & 1);
+      dx = m->mail[pw][k - 1];
+      m->mailtag[pw][k - 1] = tau;
+    }
     RUN(layer_backward(m, l, dh, dx, gslot));
   }
   if (m->use_side) {          // the module's gradient is complete once the side work has joined
@@ -889,11 +965,11 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
   m->tags[k][slot] = m->t;
   if (k == 1) {
     // Eq. 7 (left): dV_i rows = scattered error gradient of the embedding output
-    int64_t s0, t0;
-    ouro_slot_index(K, 0, m->t, 1, &s0, &t0);
+    int64_t s0 = 0, t0;
+    if (!stored) ouro_slot_index(K, 0, m->t, 1, &s0, &t0);
     float* dvi = m->slot_ptr(0, s0);
     HIPCHK(launch_fill_zero(m->stream, dvi, (size_t)m->gstride[0] * 4));
-    HIPCHK(launch_embed_bwd(m->stream, c.dtype, m->tok, m->dhb[2], dvi, N, d, V, c.emb_scale));
+    HIPCHK(launch_embed_bwd(m->stream, c.dtype, tok, m->dhb[2], dvi, N, d, V, c.emb_scale));
     m->tags[0][s0] = m->t;
   }
   m->bwd_next = k - 1;
@@ -936,7 +1012,16 @@ static int update_group(ouro_model* m, int group, float lr, hipStream_t st) {
   u.bc1 = (float)(1.0 - std::pow((double)c.beta1, (double)(m->t + 1)));   // global t+1 (Algorithm 2)
   u.bc2 = (float)(1.0 - std::pow((double)c.beta2, (double)(m->t + 1)));
   int64_t slot, tau;
-  if (group >= 1) {
+  const bool stored = c.schedule == 1;
+  if (group >= 1 && stored) {
+    // the gradient of mini-batch t-K+k was computed in this iteration (or nothing was)
+    tau = m->t - K + group;
+    m->last_slot[group] = tau >= 0 ? 0 : -1; m->last_tau[group] = tau >= 0 ? tau : -1;
+    if (tau >= 0) {
+      if (m->tags[group][0] != m->t) return fail(OURO_E_STALE, "module %d gradient is of iteration %lld, wanted %lld", group, (long long)m->tags[group][0], (long long)m->t);
+      u.g0 = m->slot_ptr(group, 0); u.gscale0 = 1.f;
+    }
+  } else if (group >= 1) {
     ouro_slot_index(K, group, m->t, 0, &slot, &tau);                        // Eq. 8
     m->last_slot[group] = slot; m->last_tau[group] = tau;
     if (tau >= 0) {
@@ -946,6 +1031,8 @@ static int update_group(ouro_model* m, int group, float lr, hipStream_t st) {
   } else {
     int64_t si, ti;                                                         // Eq. 9
     ouro_slot_index(K, 0, m->t, 0, &si, &ti);
+    int64_t want = ti;                        // tag the dV_i slot must carry
+    if (stored) { si = ti >= 0 ? 0 : -1; want = m->t; }
     m->last_slot[0] = si; m->last_tau[0] = ti;
     m->last_slot[K + 1] = -1; m->last_tau[K + 1] = -1;
     if (ti >= 0 || c.embed_warm_mode == 1) {
@@ -954,7 +1041,7 @@ static int update_group(ouro_model* m, int group, float lr, hipStream_t st) {
       m->last_slot[K + 1] = 0; m->last_tau[K + 1] = m->t;
     }
     if (ti >= 0) {
-      if (m->tags[0][si] != ti) return fail(OURO_E_STALE, "dV_i slot %lld holds iteration %lld, wanted %lld", (long long)si, (long long)m->tags[0][si], (long long)ti);
+      if (m->tags[0][si] != want) return fail(OURO_E_STALE, "dV_i slot %lld holds iteration %lld, wanted %lld", (long long)si, (long long)m->tags[0][si], (long long)want);
       u.g1 = m->slot_ptr(0, si); u.gscale1 = 0.5f;
     }
   }
@@ -1023,7 +1110,8 @@ extern "C" int ouro_step(ouro_model* m, const int32_t* dev_tokens, const int32_t
       HIPCHK(hipStreamWaitEvent(m->aux, m->ev_join, 0));
       m->upd_pending = true;
       RUN(update_group(m, k, lr, m->aux));
-      if (k == K) RUN(update_group(m, 0, lr, m->aux));
+      // (stored-input schedule: module 1's recomputation still reads V, so V waits)
+      if (k == K && m->cfg.schedule == 0) RUN(update_group(m, 0, lr, m->aux));
     }
   }
   const uint64_t done = m->upd_mask;    // the last update closes the iteration and clears the mask
@@ -1047,6 +1135,19 @@ extern "C" int ouro_debug_last_read(ouro_model* m, int id, int64_t* slot, int64_
   return OURO_OK;
 }
 
+extern "C" int ouro_debug_input_tag(ouro_model* m, int k, int64_t slot, int64_t* tag) {
+  if (!m || !tag || k < 1 || k > m->cfg.n_module || slot < 0 || slot >= m->indepth[k]) return fail(OURO_E_ARG, "input_tag: bad argument");
+  *tag = m->intags[k][slot];
+  return OURO_OK;
+}
+
+extern "C" int ouro_debug_last_input_read(ouro_model* m, int k, int64_t* slot, int64_t* tau) {
+  if (!m || !slot || !tau || k < 1 || k > m->cfg.n_module) return fail(OURO_E_ARG, "last_input_read: bad argument");
+  *slot = m->in_last_slot[k];
+  *tau = m->in_last_tau[k];
+  return OURO_OK;
+}
+
 extern "C" int ouro_debug_inject_grad(ouro_model* m, int id, const float* host_g, int64_t n) {
   if (!m || !host_g) return fail(OURO_E_ARG, "inject_grad: null argument");
   const int K = m->cfg.n_module;
@@ -1056,6 +1157,7 @@ extern "C" int ouro_debug_inject_grad(ouro_model* m, int id, const float* host_g
   if (m->inject_mask & (1ull << id)) return fail(OURO_E_SEQUENCE, "inject_grad(%d) twice in one iteration", id);
   int64_t slot, tau;
   ouro_slot_index(K, id, m->t, 1, &slot, &tau);
+  if (m->cfg.schedule == 1) slot = 0;
   if (m->padded) {
     const int grp = (id == 0 || id == K + 1) ? 0 : id;
     std::vector<float> stored((size_t)m->pcount[grp], 0.f);

@@ -29,7 +29,8 @@ def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=
     tok, tgt = S.token_batches(c["vocab"], c["batch"], c["seq_len"], steps, c.get("zipf_s", 1.1), seed + 1,
                                contiguous=bool(c.get("mem_len", 0)))
     cfg = O.Config(**c)
-    orc = O.Oracle(cfg, blobs)
+    stored = c.get("schedule", 0) == 1                    # stored-input / recompute schedule
+    orc = (O.RecomputeOracle if stored else O.Oracle)(cfg, blobs)
     m = pkg.create_model(**c)
     K = c["n_module"]
     for g in range(K + 1):
@@ -71,8 +72,18 @@ def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=
         if check_grads:
             grads, dVi, dVo = orc.grad_hist[t]
             assert rel_err(m.get_grad_slot(K + 1, t), dVo.ravel()) < tol, ("dVo", t)
-            assert rel_err(m.get_grad_slot(0, t), dVi.ravel()) < tol, ("dVi", t)
+            if not stored or t - K + 1 >= 0:
+                assert rel_err(m.get_grad_slot(0, t), dVi.ravel()) < tol, ("dVi", t)
             for k in range(1, K + 1):
+                if stored:
+                    # the pass of iteration t is for mini-batch t-K+k, recomputed from input slot (t-K+k) mod (K-k+1)
+                    tau = t - K + k
+                    if k < K:
+                        assert m.last_input_read(k) == ((tau % (K - k + 1), tau) if tau >= 0 else (-1, -1))
+                        assert m.input_tag(k, t % (K - k + 1)) == t
+                    assert m.last_read(k) == ((0, tau) if tau >= 0 else (-1, -1))
+                    if tau < 0:
+                        continue
                 assert rel_err(m.get_grad_slot(k, t), orc.grad_blob(k, t)) < tol, ("module grad", k, t)
                 # per-parameter check so that small tensors (biases, u, v) are not drowned
                 off = 0
@@ -131,6 +142,34 @@ def test_xl_fp32_odd_dims_adam():
     c = dict(n_layer=2, d_model=82, n_head=2, d_head=41, d_ff=100, vocab=73, seq_len=9, mem_len=9, batch=2,
              n_module=2, rel_pos=1, dtype=0, optimizer=1, embed_warm_mode=1)
     run_both(c, steps=4, lr=1e-3, seed=8, std=0.1, perturb=0.1)
+
+
+@pytest.mark.parametrize("K,opt,api", [(2, 0, False), (3, 0, True), (4, 1, False), (1, 1, False)])
+def test_stored_input_schedule_fp32(K, opt, api):
+    """The memory-saving schedule (stored module inputs, recomputation with the current weights,
+    error gradients handed down one iteration late) against its oracle in fp32: losses, every
+    gradient with the mini-batch and ring slot it was recomputed from, and the weights, over more
+    iterations than the pipeline is deep."""
+    c = dict(n_layer=max(K, 4), d_model=40, n_head=5, d_head=8, d_ff=72, vocab=131, seq_len=19, mem_len=0, batch=3,
+             n_module=K, rel_pos=0, dtype=0, optimizer=opt, schedule=1)
+    run_both(c, steps=K + 4, lr=0.05 if opt == 0 else 1e-3, seed=50 + K, std=0.1, perturb=0.1, module_api=api)
+
+
+def test_stored_input_schedule_xl_blocks_fp32():
+    c = dict(n_layer=3, d_model=32, n_head=2, d_head=16, d_ff=48, vocab=61, seq_len=12, mem_len=0, batch=2,
+             n_module=3, rel_pos=1, dtype=0, optimizer=0, schedule=1, embed_warm_mode=1)
+    run_both(c, steps=6, lr=0.05, seed=57, std=0.15, perturb=0.1)
+
+
+def test_stored_input_schedule_bf16():
+    """bf16 mode, K = 4, shapes that span several MFMA tiles; then K = 3 with Adam through the
+    zero-padded storage."""
+    c = dict(n_layer=4, d_model=128, n_head=2, d_head=64, d_ff=256, vocab=1001, seq_len=96, mem_len=0, batch=3,
+             n_module=4, rel_pos=0, dtype=1, optimizer=0, schedule=1)
+    run_both(c, steps=7, lr=0.05, seed=61, std=0.05, perturb=0.05, tol=2e-2)
+    c = dict(n_layer=3, d_model=82, n_head=2, d_head=41, d_ff=100, vocab=203, seq_len=70, mem_len=0, batch=3,
+             n_module=3, rel_pos=0, dtype=1, optimizer=1, schedule=1)
+    run_both(c, steps=5, lr=1e-3, seed=63, std=0.05, perturb=0.05, tol=2e-2)
 
 
 def test_bf16_small_sgd():
