@@ -64,6 +64,9 @@ def main():
     ap.add_argument("--serial", action="store_true",
                     help="run every kernel on one stream in the timed steps too (the mode the roofline pass and "
                          "the committed kernel traces use; the default overlaps independent kernels on extra streams)")
+    ap.add_argument("--schedule", type=int, default=0, choices=[0, 1],
+                    help="0: gradient rings, Eq. 8 to the letter (the headline workload); 1: stored module inputs "
+                         "and recomputation (the paper's memory-saving schedule; one more forward pass per module below K)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the K modules back to back on ONE GPU; --gpus N with N > 1 is not "
@@ -77,6 +80,7 @@ def main():
     import synth_inputs as S
 
     c = dict(S.CONFIGS[args.config])
+    c["schedule"] = args.schedule
     K = c["n_module"]
     nsteps_total = args.warmup + 2 * args.steps
     blobs = S.init_params(c, seed=0)
@@ -177,6 +181,7 @@ def main():
         "mfu_bf16": round(F / (ms_per_step * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4),
         "step_tflop": round(F / 1e12, 3),
         "streams": "serial" if args.serial else "overlapped",
+        "schedule": "stored inputs + recompute" if args.schedule else "gradient rings (Eq. 8)",
         "loss_first_timed": loss, "loss_last": loss_end,
         "roofline": roofline, "update_kernel": update, "cpu_baseline": cpu,
     }

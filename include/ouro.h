@@ -74,7 +74,7 @@ typedef struct {
                            each module keeps its inputs instead, recomputes its activations
                            of mini-batch t-K+k with the weights it holds at iteration t and
                            back-propagates the error gradient its upper neighbour produced
-                           at iteration t-1 (needs mem_len = 0)                             */
+                           at iteration t-1; segment memories are stored with the inputs     */
 } ouro_config;
 
 /* Parameter groups: group 0 is V [vocab, d_model]; group k = 1..K is module k.

@@ -119,7 +119,10 @@ struct LayerBuf {   // saved activations of one layer (element type T unless not
   char* uact;       // GELU(z) [N, F]
   char* s2;         // y + FFN [N, d]
   char* r;          // W_r-projected distance table [S, d]
-  char* mem;        // segment memory [B, Mv, d]
+  char* mem;        // segment memory [B, Mv, d] (stored-input schedule: the ring slot in use)
+  char* memring;    // stored-input schedule: the memories of iterations t-(K-k) .. t+1, slot = iteration mod memdepth
+  size_t memstride;
+  int memdepth;
   float *lse, *mean1, *rstd1, *mean2, *rstd2;
 };
 
@@ -253,7 +256,6 @@ static int validate(const ouro_config* c, std::vector<int>& lpm) {
   if (c->optimizer != 0 && c->optimizer != 1) return fail(OURO_E_CONFIG, "optimizer must be 0 or 1");
   if (c->embed_warm_mode != 0 && c->embed_warm_mode != 1) return fail(OURO_E_CONFIG, "embed_warm_mode must be 0 or 1");
   if (c->schedule != 0 && c->schedule != 1) return fail(OURO_E_CONFIG, "schedule must be 0 or 1");
-  if (c->schedule == 1 && c->mem_len > 0) return fail(OURO_E_CONFIG, "schedule 1 with a segment memory is not supported");
   if (c->optimizer == 1 && !(c->beta1 >= 0 && c->beta1 < 1 && c->beta2 >= 0 && c->beta2 < 1 && c->eps > 0))
     return fail(OURO_E_CONFIG, "Adam constants out of range");
   if ((int64_t)c->batch * c->seq_len > (1 << 24)) return fail(OURO_E_CONFIG, "batch*seq_len too large");
@@ -375,7 +377,17 @@ static size_t lay_out(ouro_model& m, char* base) {
     b.uact = P(N * F * es);
     b.s2 = P(N * d * es);
     b.r = c.rel_pos ? P(S * hd * es) : nullptr;
-    b.mem = (M > 0) ? P(B * M * d * es) : nullptr;
+    b.memring = nullptr; b.memstride = 0; b.memdepth = 0;
+    if (M > 0 && c.schedule == 1) {
+      // a module's memories are part of its stored input: one slot per iteration still to be
+      // recomputed, plus the one the running forward pass fills for the next iteration
+      b.memdepth = K - m.layer_mod[i] + 2;
+      b.memstride = (B * M * d * es + 255) & ~(size_t)255;
+      b.memring = P(b.memstride * (size_t)b.memdepth);
+      b.mem = b.memring;
+    } else {
+      b.mem = (M > 0) ? P(B * M * d * es) : nullptr;
+    }
     b.lse = (float*)P(B * c.n_head * T * 4);
     b.mean1 = (float*)P(N * 4); b.rstd1 = (float*)P(N * 4);
     b.mean2 = (float*)P(N * 4); b.rstd2 = (float*)P(N * 4);
@@ -623,6 +635,17 @@ static GemmDesc gd(const void* A, int lda, int tA, const void* B, int ldb, int t
 #define RUN(expr) do { int rc_ = (expr); if (rc_) return rc_; } while (0)
 
 // ------------------------------------------------------------------------------ forward
+// Valid rows of every segment memory at the forward pass of iteration t.
+static int mem_valid_at(const ouro_model* m, int64_t t) {
+  const int64_t rows = t * (int64_t)m->cfg.seq_len;
+  return (int)std::min<int64_t>(m->cfg.mem_len, rows);
+}
+// Stored-input schedule: layer l uses the memory of iteration t from here on.
+static void select_memory(ouro_model* m, int l, int64_t t) {
+  LayerBuf& b = m->L[l];
+  if (b.memring) b.mem = b.memring + (size_t)(t % b.memdepth) * b.memstride;
+}
+
 // out_override: where the layer's output goes instead of the next layer's input buffer
 static int layer_forward(ouro_model* m, int l, char* out_override = nullptr) {
   const ouro_config& c = m->cfg;
@@ -702,7 +725,18 @@ extern "C" int ouro_module_forward(ouro_model* m, int k, const int32_t* dev_toke
     else HIPCHK(hipMemcpyAsync(dst, m->L[m->first_layer[k - 1]].x, (size_t)m->N * m->pd * m->esz, hipMemcpyDeviceToDevice, m->stream));
     m->intags[k][slot] = m->t;
   }
-  for (int l = m->first_layer[k - 1]; l < m->first_layer[k]; ++l) RUN(layer_forward(m, l));
+  for (int l = m->first_layer[k - 1]; l < m->first_layer[k]; ++l) {
+    RUN(layer_forward(m, l));
+    LayerBuf& b = m->L[l];
+    if (b.memring) {
+      // the memory of iteration t+1 = last M rows of [memory ; layer input], taken now: the
+      // backward passes of this iteration recompute over these buffers
+      const int T = c.seq_len, dd = m->pd, Mv = m->mem_valid, S = Mv + T, Mn = std::min(c.mem_len, S);
+      const char* cat = Mv > 0 ? b.cat : b.x;
+      char* nxt = b.memring + (size_t)((m->t + 1) % b.memdepth) * b.memstride;
+      HIPCHK(launch_copy_rows(m->stream, c.dtype, nxt, (size_t)Mn * dd, 0, cat, (size_t)S * dd, (size_t)(S - Mn) * dd, c.batch, Mn, dd));
+    }
+  }
   if (k == K) {
     m->tgt = dev_targets;
     const int d = m->pd, V = c.vocab, N = m->N;
@@ -904,7 +938,11 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
     } else {
       HIPCHK(hipMemcpyAsync(m->L[first].x, src, (size_t)N * d * m->esz, hipMemcpyDeviceToDevice, m->stream));
     }
-    for (int l = first; l <= last; ++l) RUN(layer_forward(m, l, l == last ? m->hscratch : nullptr));
+    m->mem_valid = mem_valid_at(m, tau);            // this module works on iteration tau's memories
+    for (int l = first; l <= last; ++l) {
+      select_memory(m, l, tau);
+      RUN(layer_forward(m, l, l == last ? m->hscratch : nullptr));
+    }
     // error gradient of this module's output, left by module k+1 one iteration ago
     const int pr = (int)((m->t + 1) & 1);
     if (m->mailtag[pr][k] != tau) return fail(OURO_E_STALE, "module %d error gradient is of mini-batch %lld, wanted %lld", k, (long long)m->mailtag[pr][k], (long long)tau);
@@ -955,6 +993,7 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
     }
     RUN(layer_backward(m, l, dh, dx, gslot));
   }
+  if (stored) m->mem_valid = mem_valid_at(m, m->t);
   if (m->use_side) {          // the module's gradient is complete once the side work has joined
     HIPCHK(hipEventRecord(m->ev_join, m->side));
     if (!defer_join) {
@@ -984,7 +1023,11 @@ extern "C" int ouro_module_backward(ouro_model* m, int k) {
 // ------------------------------------------------------------------------------- update
 static int close_iteration(ouro_model* m) {
   const ouro_config& c = m->cfg;
-  if (c.mem_len > 0) {
+  if (c.mem_len > 0 && c.schedule == 1) {
+    // the forward pass already filled the slots of iteration t+1
+    for (int l = 0; l < c.n_layer; ++l) select_memory(m, l, m->t + 1);
+    m->mem_valid = mem_valid_at(m, m->t + 1);
+  } else if (c.mem_len > 0) {
     // memory for t+1 = last M rows of [memory ; layer input] (constants, no gradient)
     const int T = c.seq_len, d = m->pd, Mv = m->mem_valid, S = Mv + T;
     const int Mn = std::min(c.mem_len, S);

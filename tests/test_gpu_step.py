@@ -161,6 +161,18 @@ def test_stored_input_schedule_xl_blocks_fp32():
     run_both(c, steps=6, lr=0.05, seed=57, std=0.15, perturb=0.1)
 
 
+def test_stored_input_schedule_with_segment_memory():
+    """Transformer-XL memories under the stored-input schedule: a module recomputes mini-batch
+    t-K+k against the memories its layers held at that iteration, while the forward pass rolls
+    them on.  fp32 (general kernels), then bf16 at head size 64 (fused kernels)."""
+    c = dict(n_layer=4, d_model=32, n_head=2, d_head=16, d_ff=48, vocab=61, seq_len=6, mem_len=10, batch=2,
+             n_module=3, rel_pos=1, dtype=0, optimizer=0, schedule=1)
+    run_both(c, steps=7, lr=0.05, seed=71, std=0.15, perturb=0.1)
+    c = dict(n_layer=3, d_model=128, n_head=2, d_head=64, d_ff=256, vocab=512, seq_len=80, mem_len=112, batch=2,
+             n_module=3, rel_pos=1, dtype=1, optimizer=0, embed_warm_mode=1, schedule=1)
+    run_both(c, steps=6, lr=0.05, seed=73, std=0.05, perturb=0.05, tol=2e-2)
+
+
 def test_stored_input_schedule_bf16():
     """bf16 mode, K = 4, shapes that span several MFMA tiles; then K = 3 with Adam through the
     zero-padded storage."""
