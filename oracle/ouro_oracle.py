@@ -54,7 +54,8 @@ LN_EPS = 1e-5
 class Config:
     def __init__(self, n_layer, d_model, n_head, d_head, d_ff, vocab, seq_len, batch,
                  n_module=1, mem_len=0, rel_pos=0, layers_per_module=None, optimizer=0,
-                 beta1=0.9, beta2=0.999, eps=1e-8, embed_warm_mode=0, emb_scale=1.0, **_):
+                 beta1=0.9, beta2=0.999, eps=1e-8, embed_warm_mode=0, emb_scale=1.0,
+                 dropout=0.0, seed=0, **_):
         assert n_head * d_head == d_model
         assert d_model % 2 == 0
         assert mem_len == 0 or rel_pos
@@ -63,6 +64,8 @@ class Config:
         self.n_module, self.mem_len, self.rel_pos = n_module, mem_len, rel_pos
         self.optimizer, self.beta1, self.beta2, self.eps = optimizer, beta1, beta2, eps
         self.embed_warm_mode, self.emb_scale = embed_warm_mode, emb_scale
+        assert 0.0 <= dropout < 1.0
+        self.dropout, self.seed = float(dropout), int(seed)
         if layers_per_module is None:
             layers_per_module = split_layers(n_layer, n_module)
         assert len(layers_per_module) == n_module and sum(layers_per_module) == n_layer
@@ -261,29 +264,78 @@ def attention_bwd(cfg, p, do, c):
     return dx, g
 
 
+# ----------------------------------------------------------------------------- dropout
+MASK64 = (1 << 64) - 1
+
+
+def random_u32(seed, stream, idx):
+    """Counter-based generator shared (as an algorithm, not as code) with the HIP path:
+    the high 32 bits of output number idx + stream*2^40 + 1 of the SplitMix64 sequence
+    (Steele, Lea, Flood 2014) started at `seed`, i.e. the 64-bit finaliser applied to
+    seed + gamma*(idx + stream*2^40 + 1).  idx: uint64 array; returns uint32."""
+    idx = np.asarray(idx, dtype=np.uint64)
+    with np.errstate(over="ignore"):
+        ctr = idx + np.uint64((int(stream) << 40) + 1)
+        z = np.uint64(int(seed) & MASK64) + np.uint64(0x9E3779B97F4A7C15) * ctr
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        z = z ^ (z >> np.uint64(31))
+    return (z >> np.uint64(32)).astype(np.uint32)
+
+
+def dropout_mask(cfg, seed, stream, shape):
+    """Inverted dropout (Srivastava et al. 2014, cited in Section 4.1): element i (row-major
+    index) is kept iff its 32 random bits are >= floor(p * 2^32); kept elements are scaled
+    by 1/(1-p).  The mask is a pure function of (seed, stream, i): "repeatable"."""
+    n = int(np.prod(shape))
+    bits = random_u32(seed, stream, np.arange(n, dtype=np.uint64))
+    thresh = np.uint32(int(cfg.dropout * 4294967296.0))
+    return ((bits >= thresh).astype(np.float64) / (1.0 - cfg.dropout)).reshape(shape)
+
+
+def embed_stream():
+    return 0
+
+
+def layer_stream(l, site):
+    """site 1: output of the attention projection; site 2: output of the feed-forward block."""
+    return 2 * l + site
+
+
 # ------------------------------------------------------------------------------- layer
-def layer_fwd(cfg, p, x, mem):
+def layer_fwd(cfg, p, x, mem, drop=None):
+    """drop = (seed, layer index) switches dropout on at the two sublayer outputs, before the
+    residual additions (the paper names dropout, Section 4.1, not its places: a reading)."""
     o, ca = attention_fwd(cfg, p, x, mem)
+    m1 = m2 = None
+    if drop is not None and cfg.dropout > 0:
+        m1 = dropout_mask(cfg, drop[0], layer_stream(drop[1], 1), o.shape)
+        o = o * m1
     y, c1 = layernorm_fwd(x + o, p["ln1_g"], p["ln1_b"])
     z = y @ p["W_1"] + p["b_1"]
     u = gelu(z)
     f = u @ p["W_2"] + p["b_2"]
+    if m1 is not None:
+        m2 = dropout_mask(cfg, drop[0], layer_stream(drop[1], 2), f.shape)
+        f = f * m2
     h, c2 = layernorm_fwd(y + f, p["ln2_g"], p["ln2_b"])
-    return h, dict(att=ca, ln1=c1, y=y, z=z, u=u, ln2=c2)
+    return h, dict(att=ca, ln1=c1, y=y, z=z, u=u, ln2=c2, m1=m1, m2=m2)
 
 
 def layer_bwd(cfg, p, dh, c):
     d, F = cfg.d_model, cfg.d_ff
     g = {}
-    ds2, g["ln2_g"], g["ln2_b"] = layernorm_bwd(dh, p["ln2_g"], c["ln2"])
+    ds2_res, g["ln2_g"], g["ln2_b"] = layernorm_bwd(dh, p["ln2_g"], c["ln2"])
+    ds2 = ds2_res if c.get("m2") is None else ds2_res * c["m2"]      # into the feed-forward branch
     g["W_2"] = c["u"].reshape(-1, F).T @ ds2.reshape(-1, d)
     g["b_2"] = ds2.reshape(-1, d).sum(axis=0)
     dz = (ds2 @ p["W_2"].T) * gelu_grad(c["z"])
     g["W_1"] = c["y"].reshape(-1, d).T @ dz.reshape(-1, F)
     g["b_1"] = dz.reshape(-1, F).sum(axis=0)
-    dy = ds2 + dz @ p["W_1"].T
+    dy = ds2_res + dz @ p["W_1"].T
     ds1, g["ln1_g"], g["ln1_b"] = layernorm_bwd(dy, p["ln1_g"], c["ln1"])
-    dx_att, ga = attention_bwd(cfg, p, ds1, c["att"])
+    do = ds1 if c.get("m1") is None else ds1 * c["m1"]                # into the attention branch
+    dx_att, ga = attention_bwd(cfg, p, do, c["att"])
     g.update(ga)
     return ds1 + dx_att, g
 
@@ -305,21 +357,30 @@ def cross_entropy_bwd(logits, lse, targets):
     return G / targets.size
 
 
-def model_forward(cfg, layers, Vi, Vo, tokens, targets, mems=None):
-    """Eq. 1-4.  Returns loss (mean over all B*T targets, natural log) and a cache."""
-    B, T = tokens.shape
-    d = cfg.d_model
+def embed_fwd(cfg, Vi, tokens, seed=None):
+    """Eq. 1 (+ fixed positions, + dropout on the sum when a seed is given)."""
     h = cfg.emb_scale * Vi[tokens]                            # Eq. 1: V_i enters layer 1
     if not cfg.rel_pos:
-        h = h + sinusoid(np.arange(T), d)[None]
+        h = h + sinusoid(np.arange(tokens.shape[1]), cfg.d_model)[None]
+    m0 = None
+    if seed is not None and cfg.dropout > 0:
+        m0 = dropout_mask(cfg, seed, embed_stream(), h.shape)
+        h = h * m0
+    return h, m0
+
+
+def model_forward(cfg, layers, Vi, Vo, tokens, targets, mems=None, seed=None):
+    """Eq. 1-4.  Returns loss (mean over all B*T targets, natural log) and a cache.
+    seed: dropout seed of this pass (None or cfg.dropout = 0: no dropout)."""
+    h, m0 = embed_fwd(cfg, Vi, tokens, seed)
     inputs, caches = [], []
     for l, p in enumerate(layers):
         inputs.append(h)
-        h, c = layer_fwd(cfg, p, h, None if mems is None else mems[l])
+        h, c = layer_fwd(cfg, p, h, None if mems is None else mems[l], None if seed is None else (seed, l))
         caches.append(c)
     logits = h @ Vo.T                                         # Eq. 3: V_o leaves layer L
     loss, lse = cross_entropy_fwd(logits, targets)
-    return loss, dict(inputs=inputs, caches=caches, hL=h, logits=logits, lse=lse)
+    return loss, dict(inputs=inputs, caches=caches, hL=h, logits=logits, lse=lse, m0=m0)
 
 
 def model_backward(cfg, layers, Vi, Vo, tokens, targets, fw):
@@ -333,13 +394,15 @@ def model_backward(cfg, layers, Vi, Vo, tokens, targets, fw):
     grads = [None] * len(layers)
     for l in reversed(range(len(layers))):
         dh, grads[l] = layer_bwd(cfg, layers[l], dh, fw["caches"][l])
+    if fw.get("m0") is not None:
+        dh = dh * fw["m0"]
     dVi = np.zeros_like(Vi)
     np.add.at(dVi, tokens.reshape(-1), cfg.emb_scale * dh.reshape(N, d))
     return grads, dVi, dVo
 
 
-def full_gradient(cfg, layers, V, tokens, targets, mems=None):
-    loss, fw = model_forward(cfg, layers, V, V, tokens, targets, mems)
+def full_gradient(cfg, layers, V, tokens, targets, mems=None, seed=None):
+    loss, fw = model_forward(cfg, layers, V, V, tokens, targets, mems, seed)
     grads, dVi, dVo = model_backward(cfg, layers, V, V, tokens, targets, fw)
     return loss, grads, dVi, dVo, fw["inputs"]
 
@@ -384,6 +447,11 @@ class Oracle:
             self.v = [{n: np.zeros_like(a) for n, a in p.items()} for p in self.layers]
             self.mV, self.vV = np.zeros_like(self.V), np.zeros_like(self.V)
 
+    def seed_of(self, t):
+        """Dropout seed of mini-batch t (stored with the module inputs, Section 4.1
+        "Repeatable Dropout"): the configured seed plus t; None when dropout is off."""
+        return (self.cfg.seed + t) & MASK64 if self.cfg.dropout > 0 else None
+
     def module_layers(self, k):
         """Layer indices of G(k), k = 1..K."""
         return range(int(self.bounds[k - 1]), int(self.bounds[k]))
@@ -412,7 +480,8 @@ class Oracle:
         if self.keep_history:
             self.state_hist.append((copy.deepcopy(self.layers), self.V.copy(),
                                     copy.deepcopy(self.mems), tokens.copy(), targets.copy()))
-        loss, grads, dVi, dVo, inputs = full_gradient(c, self.layers, self.V, tokens, targets, self.mems)
+        loss, grads, dVi, dVo, inputs = full_gradient(c, self.layers, self.V, tokens, targets, self.mems,
+                                                      self.seed_of(t))
         self.grad_hist.append((grads, dVi, dVo))
         used = {}
         for k in range(1, K + 1):                            # Eq. 8
@@ -456,7 +525,7 @@ class Oracle:
             if tau < 0:
                 continue
             layers, V, mems, tok, tgt = self.state_hist[tau]
-            _, grads, _, _, _ = full_gradient(self.cfg, layers, V, tok, tgt, mems)
+            _, grads, _, _, _ = full_gradient(self.cfg, layers, V, tok, tgt, mems, self.seed_of(tau))
             for l in self.module_layers(k):
                 for name in grads[l]:
                     worst = max(worst, float(np.abs(grads[l][name] - self.grad_hist[tau][0][l][name]).max()))
@@ -464,21 +533,23 @@ class Oracle:
 
 
 # ------------------------------------------------- stored-input / recompute schedule
-def module_fwd(cfg, k, layers_k, V, inp, mems_k):
+def module_fwd(cfg, k, layers_k, V, inp, mems_k, seed=None, first_layer=0):
     """Forward pass of module k on its stored input: token ids for k = 1 (the embedding
     lookup of Eq. 1 belongs to module 1), the hidden state at the module boundary
-    otherwise.  Returns the module's output and the per-layer caches."""
+    otherwise.  seed: the stored dropout seed of that mini-batch; first_layer: index of
+    the module's first layer in the network (it keys the dropout streams).  Returns the
+    module's output, the per-layer caches and the embedding mask (k = 1, else None)."""
+    m0 = None
     if k == 1:
-        h = cfg.emb_scale * V[inp]
-        if not cfg.rel_pos:
-            h = h + sinusoid(np.arange(inp.shape[1]), cfg.d_model)[None]
+        h, m0 = embed_fwd(cfg, V, inp, seed)
     else:
         h = inp
     caches = []
     for i, p in enumerate(layers_k):
-        h, c = layer_fwd(cfg, p, h, None if mems_k is None else mems_k[i])
+        h, c = layer_fwd(cfg, p, h, None if mems_k is None else mems_k[i],
+                         None if seed is None else (seed, first_layer + i))
         caches.append(c)
-    return h, caches
+    return h, caches, m0
 
 
 def module_bwd(cfg, layers_k, caches, dh):
@@ -514,8 +585,11 @@ class RecomputeOracle(Oracle):
     grad_hist[t] holds what iteration t computed: module k's entry is the gradient of
     mini-batch t-K+k (zeros while that is negative), dV_i that of mini-batch t-K+1."""
 
-    def __init__(self, cfg, blobs, keep_history=True):
+    def __init__(self, cfg, blobs, keep_history=True, repeatable=True):
+        """repeatable=False is the ablation of Section 4.2 (recompute under the dropout seed
+        of the running iteration instead of the stored one); tests use it as a planted error."""
         super().__init__(cfg, blobs, keep_history)
+        self.repeatable = repeatable
         self.inputs = {}         # (k, t) -> (input of module k at iteration t, its layers' memories)
         self.mail = {}           # k -> (tau, error gradient of module k's output for mini-batch tau)
         self.batch_of = []       # t -> {k: tau}
@@ -523,23 +597,23 @@ class RecomputeOracle(Oracle):
     def step(self, tokens, targets, lr):
         c, t, K = self.cfg, self.t, self.cfg.n_module
         tokens = np.asarray(tokens); targets = np.asarray(targets)
-        # forward pass of mini-batch t, storing every module's input
+        # forward pass of mini-batch t, storing every module's input (and the dropout seed)
         h = tokens
         layer_inputs = []
+        seed_t = self.seed_of(t)
         for k in range(1, K + 1):
             ls = list(self.module_layers(k))
             mems_k = None if self.mems is None else [self.mems[l] for l in ls]
-            self.inputs[(k, t)] = (h.copy(), copy.deepcopy(mems_k))
+            self.inputs[(k, t)] = (h.copy(), copy.deepcopy(mems_k), seed_t)
             if k == 1:
-                x = c.emb_scale * self.V[tokens]
-                if not c.rel_pos:
-                    x = x + sinusoid(np.arange(tokens.shape[1]), c.d_model)[None]
+                x, m0_t = embed_fwd(c, self.V, tokens, seed_t)
             else:
                 x = h
             caches = []
             for i, l in enumerate(ls):
                 layer_inputs.append(x)
-                x, cc = layer_fwd(c, self.layers[l], x, None if mems_k is None else mems_k[i])
+                x, cc = layer_fwd(c, self.layers[l], x, None if mems_k is None else mems_k[i],
+                                  None if seed_t is None else (seed_t, l))
                 caches.append(cc)
             h = x
         hL, top_caches = h, caches
@@ -562,9 +636,12 @@ class RecomputeOracle(Oracle):
                 dVo = G.reshape(N, -1).T @ hL.reshape(N, d)
                 dh = G @ self.V
                 caches_k = top_caches
+                m0 = m0_t if K == 1 else None
             else:
-                inp, mems_k = self.inputs[(k, tau)]
-                _, caches_k = module_fwd(c, k, layers_k, self.V, inp, mems_k)
+                inp, mems_k, seed_tau = self.inputs[(k, tau)]
+                if not self.repeatable:
+                    seed_tau = seed_t
+                _, caches_k, m0 = module_fwd(c, k, layers_k, self.V, inp, mems_k, seed_tau, ls[0])
                 mtau, dh = self.mail[k]
                 assert mtau == tau
             dx, gk = module_bwd(c, layers_k, caches_k, dh)
@@ -574,6 +651,8 @@ class RecomputeOracle(Oracle):
                 new_mail[k - 1] = (tau, dx)
             else:
                 tok_tau = self.inputs[(1, tau)][0]
+                if m0 is not None:
+                    dx = dx * m0
                 np.add.at(dVi, tok_tau.reshape(-1), c.emb_scale * dx.reshape(N, d))
         self.mail = new_mail
         self.grad_hist.append((grads, dVi, dVo))

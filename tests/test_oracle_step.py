@@ -122,7 +122,7 @@ def test_tagged_gradient_plumbing(monkeypatch):
     c, cfg, blobs, tok, tgt = make(K, steps=T)
     calls = {"t": 0}
 
-    def fake(cfg_, layers, V, tokens, targets, mems=None):
+    def fake(cfg_, layers, V, tokens, targets, mems=None, seed=None):
         t = calls["t"]; calls["t"] += 1
         bounds = np.concatenate([[0], np.cumsum(cfg_.layers_per_module)])
         grads = []
@@ -367,3 +367,131 @@ def test_recompute_differs_from_eq8_once_weights_move():
         diff.append(max(np.abs(a.module_blob(k) - b.module_blob(k)).max() for k in range(K + 1)))
     assert diff[0] == 0.0                      # only module K (tau = t) has a gradient: identical
     assert diff[-1] > 1e-4
+
+
+# ---------------------------------------------------------------- repeatable dropout
+def splitmix64_python(seed, n):
+    """The SplitMix64 sequence written with Python integers (state += gamma; finalise)."""
+    M = (1 << 64) - 1
+    out, s = [], seed & M
+    for _ in range(n):
+        s = (s + 0x9E3779B97F4A7C15) & M
+        z = s
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & M
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & M
+        out.append(z ^ (z >> 31))
+    return out
+
+
+def test_random_bits_are_the_splitmix_sequence_and_look_uniform():
+    """The vectorised generator against the sequential definition in big-integer arithmetic
+    (stream 0: output i is element i+1 of the sequence; stream s starts 2^40*s further on), then
+    what dropout needs of it: the keep rate within binomial bounds for several p, balanced bits,
+    and no visible correlation between neighbours, streams or consecutive seeds."""
+    seq = splitmix64_python(12345, 40)
+    got = O.random_u32(12345, 0, np.arange(40))
+    assert [int(x) for x in got] == [z >> 32 for z in seq]
+    g = 0x9E3779B97F4A7C15
+    jump = splitmix64_python((12345 + g * (3 << 40)) & ((1 << 64) - 1), 5)
+    assert [int(x) for x in O.random_u32(12345, 3, np.arange(5))] == [z >> 32 for z in jump]
+    n = 1 << 20
+    idx = np.arange(n, dtype=np.uint64)
+    a = O.random_u32(7, 5, idx)
+    for p in (0.1, 0.5, 0.9):
+        keep = (a >= np.uint32(int(p * 2 ** 32))).mean()
+        assert abs(keep - (1 - p)) < 5 * np.sqrt(p * (1 - p) / n)
+    for bit in range(32):
+        assert abs(((a >> np.uint32(bit)) & 1).mean() - 0.5) < 5 * 0.5 / np.sqrt(n)
+    u = a.astype(np.float64) / 2 ** 32 - 0.5
+    for other in (np.roll(u, 1), O.random_u32(7, 6, idx) / 2 ** 32 - 0.5, O.random_u32(8, 5, idx) / 2 ** 32 - 0.5):
+        assert abs(np.mean(u * other)) < 5 / (12 * np.sqrt(n))
+
+
+def test_dropout_mask_semantics():
+    cfg = O.Config(**small_cfg(1, dropout=0.25, seed=9))
+    m = O.dropout_mask(cfg, 9, 3, (4, 5, 6))
+    assert set(np.unique(m)) == {0.0, 1 / 0.75}
+    assert np.array_equal(m, O.dropout_mask(cfg, 9, 3, (4, 5, 6)))          # repeatable
+    assert not np.array_equal(m, O.dropout_mask(cfg, 10, 3, (4, 5, 6)))
+    assert not np.array_equal(m, O.dropout_mask(cfg, 9, 4, (4, 5, 6)))
+    assert np.array_equal(m.ravel()[:30], O.dropout_mask(cfg, 9, 3, (30,)))   # row-major element index
+    big = O.dropout_mask(cfg, 1, 0, (1 << 18,))
+    assert abs(big.mean() - 1.0) < 0.01                                     # inverted scaling keeps the mean
+    cfg0 = O.Config(**small_cfg(1, dropout=0.0))
+    assert np.all(O.dropout_mask(cfg0, 1, 0, (100,)) == 1.0)
+
+
+@pytest.mark.parametrize("kw", [{}, dict(rel_pos=1, mem_len=4)])
+def test_dropout_gradients_by_finite_differences_and_autograd(kw):
+    """With the masks fixed by the seed the network is a smooth function again: the oracle's
+    gradient under dropout against central differences along random directions, and against the
+    autograd model that receives the same masks as constants."""
+    c = small_cfg(1, L=2, dropout=0.3, seed=4, **kw)
+    cfg = O.Config(**c)
+    blobs = S.init_params(c, seed=1, std=0.3, perturb=0.1)
+    tok, tgt = S.token_batches(13, 2, 5, 1, 1.1, 2, False)
+    orc = O.Oracle(cfg, blobs)
+    rng = np.random.default_rng(0)
+    mems = [rng.standard_normal((2, 4, 8)) for _ in range(2)] if kw else None
+    seed = 77
+    loss, grads, dVi, dVo, _ = O.full_gradient(cfg, orc.layers, orc.V, tok[0], tgt[0], mems, seed)
+    loss0, *_ = O.full_gradient(cfg, orc.layers, orc.V, tok[0], tgt[0], mems, None)
+    assert abs(loss - loss0) > 1e-3                                         # dropout is on
+    for _ in range(4):
+        dirs = [{n: rng.standard_normal(a.shape) for n, a in p.items()} for p in orc.layers]
+        dV = rng.standard_normal(orc.V.shape)
+        eps = 1e-6
+        def at(sgn):
+            ls = [{n: a + sgn * eps * dirs[l][n] for n, a in p.items()} for l, p in enumerate(orc.layers)]
+            V = orc.V + sgn * eps * dV
+            return O.model_forward(cfg, ls, V, V, tok[0], tgt[0], mems, seed)[0]
+        fd = (at(+1) - at(-1)) / (2 * eps)
+        an = sum(float((grads[l][n] * dirs[l][n]).sum()) for l in range(2) for n in grads[l]) + float(((dVi + dVo) * dV).sum())
+        assert abs(fd - an) < 1e-6 * max(1.0, abs(an))
+    # autograd with the same masks
+    tl = [{n: torch.tensor(a.copy(), requires_grad=True) for n, a in p.items()} for p in orc.layers]
+    Vi = torch.tensor(orc.V.copy(), requires_grad=True); Vo = torch.tensor(orc.V.copy(), requires_grad=True)
+    masks = {"emb": torch.tensor(O.dropout_mask(cfg, seed, O.embed_stream(), (2, 5, 8)))}
+    for l in range(2):
+        for site in (1, 2):
+            masks[(l, site)] = torch.tensor(O.dropout_mask(cfg, seed, O.layer_stream(l, site), (2, 5, 8)))
+    tm = None if mems is None else [torch.tensor(x) for x in mems]
+    tloss, _ = torch_ref.forward(cfg, tl, Vi, Vo, torch.tensor(tok[0]), torch.tensor(tgt[0]), tm, masks)
+    tloss.backward()
+    assert abs(tloss.item() - loss) < 1e-12
+    assert np.abs(Vi.grad.numpy() - dVi).max() < 1e-10 and np.abs(Vo.grad.numpy() - dVo).max() < 1e-10
+    for l in range(2):
+        for n in grads[l]:
+            assert np.abs(tl[l][n].grad.numpy() - grads[l][n]).max() < 1e-10, (l, n)
+
+
+def test_repeatable_dropout_in_the_recompute_schedule():
+    """Section 4.1, "Repeatable Dropout": with the seed stored beside the module input, the
+    recomputation sees the masks of the original pass, so at frozen weights the schedule still
+    yields Eq. 8's gradient (now of the dropout network of mini-batch t-K+k).  Recomputing under
+    the running iteration's seed instead (the ablation) breaks exactly that."""
+    K = 3
+    c, cfg, blobs, tok, tgt = make(K, seed=21, steps=K + 3, dropout=0.2)
+    cfg.seed = 1000
+    a, b = O.Oracle(cfg, blobs), O.RecomputeOracle(cfg, blobs)
+    bad = O.RecomputeOracle(cfg, blobs, repeatable=False)
+    worst_bad = 0.0
+    for t in range(K + 3):
+        la, lb = a.step(tok[t], tgt[t], 0.0), b.step(tok[t], tgt[t], 0.0)
+        bad.step(tok[t], tgt[t], 0.0)
+        assert la == lb
+        assert a.brute_check(t) == 0.0
+        for k in range(1, K + 1):
+            tau = t - K + k
+            if tau < 0:
+                continue
+            for l in b.module_layers(k):
+                for n in b.layers[l]:
+                    ref = a.grad_hist[tau][0][l][n]
+                    assert np.abs(b.grad_hist[t][0][l][n] - ref).max() < 1e-12, (t, k, l, n)
+                    if k < K:
+                        worst_bad = max(worst_bad, float(np.abs(bad.grad_hist[t][0][l][n] - ref).max()))
+        ti = t - K + 1
+        if ti >= 0:
+            assert np.abs(b.grad_hist[t][1] - a.grad_hist[ti][1]).max() < 1e-12
+    assert worst_bad > 1e-3

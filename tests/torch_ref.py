@@ -17,8 +17,9 @@ def sinusoid_t(pos, d):
     return torch.cat([torch.sin(ang), torch.cos(ang)], dim=-1)
 
 
-def layer_forward(cfg, p, h, mem=None):
-    """One block on h [B,T,d] (mem: constant [B,Mv,d] or None)."""
+def layer_forward(cfg, p, h, mem=None, m1=None, m2=None):
+    """One block on h [B,T,d] (mem: constant [B,Mv,d] or None; m1, m2: constant dropout masks,
+    already scaled, on the attention-projection and feed-forward outputs)."""
     B, T, _ = h.shape
     d, H, dh = cfg.d_model, cfg.n_head, cfg.d_head
     Mv = 0 if mem is None else mem.shape[1]
@@ -40,8 +41,13 @@ def layer_forward(cfg, p, h, mem=None):
     s = s / math.sqrt(dh)
     s = s.masked_fill((pj > pi)[None, None], float("-inf"))
     a = (torch.softmax(s, dim=-1) @ v).permute(0, 2, 1, 3).reshape(B, T, d)
-    y = F.layer_norm(h + a @ p["W_o"], (d,), p["ln1_g"], p["ln1_b"], 1e-5)
+    o = a @ p["W_o"]
+    if m1 is not None:
+        o = o * m1
+    y = F.layer_norm(h + o, (d,), p["ln1_g"], p["ln1_b"], 1e-5)
     f = F.gelu(y @ p["W_1"] + p["b_1"]) @ p["W_2"] + p["b_2"]
+    if m2 is not None:
+        f = f * m2
     return F.layer_norm(y + f, (d,), p["ln2_g"], p["ln2_b"], 1e-5)
 
 
@@ -52,14 +58,18 @@ def embed(cfg, Vi, tokens):
     return h
 
 
-def forward(cfg, layers, Vi, Vo, tokens, targets, mems=None):
-    """layers: list of dicts of torch fp64 tensors (requires_grad leaves)."""
+def forward(cfg, layers, Vi, Vo, tokens, targets, mems=None, masks=None):
+    """layers: list of dicts of torch fp64 tensors (requires_grad leaves).  masks: optional dict
+    of constant dropout masks, keys "emb" and (layer, site)."""
     B, T = tokens.shape
     h = embed(cfg, Vi, tokens)
+    if masks is not None:
+        h = h * masks["emb"]
     inputs = []
     for l, p in enumerate(layers):
         inputs.append(h)
-        h = layer_forward(cfg, p, h, None if mems is None else mems[l])
+        h = layer_forward(cfg, p, h, None if mems is None else mems[l],
+                          None if masks is None else masks[(l, 1)], None if masks is None else masks[(l, 2)])
     logits = h @ Vo.t()
     loss = F.cross_entropy(logits.view(B * T, -1), targets.reshape(-1).long(), reduction="mean")
     return loss, inputs
