@@ -75,6 +75,12 @@ typedef struct {
                            of mini-batch t-K+k with the weights it holds at iteration t and
                            back-propagates the error gradient its upper neighbour produced
                            at iteration t-1; segment memories are stored with the inputs     */
+  float dropout;     /* p in [0, 1): inverted dropout on the embedding sum and on the outputs of
+                        the attention projection and of the feed-forward block, before the
+                        residual additions (0 = none).  Section 4.1, "Repeatable Dropout": the
+                        mask is a pure function of (seed + iteration of the mini-batch, place,
+                        element), so a recomputation reproduces it                          */
+  uint64_t seed;     /* dropout seed of iteration 0; iteration t uses seed + t               */
 } ouro_config;
 
 /* Parameter groups: group 0 is V [vocab, d_model]; group k = 1..K is module k.

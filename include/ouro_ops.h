@@ -51,6 +51,19 @@ int ouro_op_attention_bwd(void* stream, int dtype, int B, int H, int T, int S, i
                           int ldr, float* du, float* dvb, float* dr, float* scratch, int force_generic);
 size_t ouro_op_attention_bwd_scratch(int B, int H, int T, int S, int dh);
 
+/* Repeatable dropout (Section 4.1): dst[r,c] = src[r,c] * f(r*drop_ld + c), f(i) = 1/(1-p) if the high
+ * 32 bits of output i + stream_id*2^40 + 1 of the SplitMix64 sequence started at `seed` are >=
+ * floor(p*2^32), else 0.  rows x cols elements of type T, row stride ld on both sides; 0 <= p < 1. */
+int ouro_op_dropout(void* stream, int dtype, const void* src, void* dst, int rows, int cols, int ld,
+                    float p, uint64_t seed, uint32_t stream_id, int drop_ld);
+/* C = dropout(op(A) op(B) + bias) + residual with the mask above at element index m*drop_ld + n
+ * (the fused form the layers use for the attention projection and the feed-forward output).
+ * C, residual type T; bias fp32 or NULL; residual may be NULL. */
+int ouro_op_gemm_dropout(void* stream, int dtype, int transA, int transB, int M, int N, int K,
+                         const void* A, int lda, const void* B, int ldb, void* C, int ldc, const float* bias,
+                         const void* residual, int ldr, float p, uint64_t seed, uint32_t stream_id, int drop_ld,
+                         int force_generic);
+
 /* y = (x-mean)*rstd*g + b over rows of d (biased variance, eps 1e-5); g, b, mean, rstd fp32.
  * dn in (0, d): the statistics run over the first dn columns only and the other d-dn columns are
  * zero padding (x, g, b zero there; y then is zero there too).  dn = 0 means dn = d. */

@@ -65,7 +65,8 @@ class Config:
         self.optimizer, self.beta1, self.beta2, self.eps = optimizer, beta1, beta2, eps
         self.embed_warm_mode, self.emb_scale = embed_warm_mode, emb_scale
         assert 0.0 <= dropout < 1.0
-        self.dropout, self.seed = float(dropout), int(seed)
+        # the rate is a single-precision number at the boundary; the keep threshold is derived from it
+        self.dropout, self.seed = float(np.float32(dropout)), int(seed)
         if layers_per_module is None:
             layers_per_module = split_layers(n_layer, n_module)
         assert len(layers_per_module) == n_module and sum(layers_per_module) == n_layer

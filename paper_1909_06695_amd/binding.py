@@ -30,7 +30,8 @@ class Config(C.Structure):
                 ("n_module", C.c_int32), ("layers_per_module", C.POINTER(C.c_int32)),
                 ("rel_pos", C.c_int32), ("dtype", C.c_int32), ("optimizer", C.c_int32),
                 ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
-                ("embed_warm_mode", C.c_int32), ("emb_scale", C.c_float), ("schedule", C.c_int32)]
+                ("embed_warm_mode", C.c_int32), ("emb_scale", C.c_float), ("schedule", C.c_int32),
+                ("dropout", C.c_float), ("seed", C.c_uint64)]
 
 
 _lib = None
@@ -86,6 +87,9 @@ def lib():
                                         i32, vp, vp, i32, vp, i32, vp, i32, vp, i32, i32, vp, vp, vp, i32, vp, vp,
                                         vp, vp, i32]),
         "ouro_op_attention_bwd_scratch": (sz, [i32, i32, i32, i32, i32]),
+        "ouro_op_dropout": (i32, [vp, i32, vp, vp, i32, i32, i32, f32, C.c_uint64, C.c_uint32, i32]),
+        "ouro_op_gemm_dropout": (i32, [vp, i32, i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32, vp, vp, i32, f32,
+                                       C.c_uint64, C.c_uint32, i32, i32]),
         "ouro_op_layernorm_fwd": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32]),
         "ouro_op_layernorm_bwd": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32]),
         "ouro_op_colsum": (i32, [vp, i32, vp, i32, vp, i32, i32]),
@@ -118,13 +122,14 @@ def check(rc):
 
 def make_config(n_layer, d_model, n_head, d_head, d_ff, vocab, seq_len, batch, n_module=1, mem_len=0,
                 rel_pos=0, dtype=0, optimizer=0, layers_per_module=None, beta1=0.9, beta2=0.999,
-                eps=1e-8, embed_warm_mode=0, emb_scale=1.0, schedule=0, **_):
+                eps=1e-8, embed_warm_mode=0, emb_scale=1.0, schedule=0, dropout=0.0, seed=0, **_):
     cfg = Config()
     cfg.n_layer, cfg.d_model, cfg.n_head, cfg.d_head = n_layer, d_model, n_head, d_head
     cfg.d_ff, cfg.vocab, cfg.seq_len, cfg.mem_len, cfg.batch = d_ff, vocab, seq_len, mem_len, batch
     cfg.n_module, cfg.rel_pos, cfg.dtype, cfg.optimizer = n_module, rel_pos, dtype, optimizer
     cfg.beta1, cfg.beta2, cfg.eps = beta1, beta2, eps
     cfg.embed_warm_mode, cfg.emb_scale, cfg.schedule = embed_warm_mode, emb_scale, schedule
+    cfg.dropout, cfg.seed = dropout, seed
     if layers_per_module is not None:
         arr = (C.c_int32 * len(layers_per_module))(*layers_per_module)
         cfg._keep = arr

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <string.h>
 
 typedef __bf16 bf16_t;
 
@@ -52,6 +53,33 @@ __device__ __forceinline__ float gelu_grad_f(float x) {
 // transA == 0: A stored [M,K] (lda >= K); transA == 1: A stored [K,M] (lda >= M).
 // transB == 0: B stored [K,N] (ldb >= N); transB == 1: B stored [N,K] (ldb >= K).
 enum { EPI_NONE = 0, EPI_GELU = 1, EPI_GELUGRAD = 2 };
+// Repeatable dropout (Section 4.1): element i of a tensor is kept iff the high 32 bits of output
+// number i + stream*2^40 + 1 of the SplitMix64 sequence started at the seed are >= thresh; kept
+// elements are scaled.  base = seed + gamma*(stream*2^40 + 1) is formed on the host.
+struct DropDesc {
+  int on;
+  uint32_t thresh;       // floor(p * 2^32)
+  float scale;           // 1 / (1 - p)
+  uint64_t base;
+  int ld;                // row length that turns (row, column) into the element index
+};
+inline DropDesc make_drop(float p, uint64_t seed, uint32_t stream, int ld) {
+  DropDesc d;
+  d.on = p > 0.f;
+  d.thresh = (uint32_t)((double)p * 4294967296.0);
+  d.scale = 1.f / (1.f - p);
+  d.base = seed + 0x9E3779B97F4A7C15ull * (((uint64_t)stream << 40) + 1ull);
+  d.ld = ld;
+  return d;
+}
+__device__ __forceinline__ float drop_factor(const DropDesc& d, uint64_t idx) {
+  uint64_t z = d.base + 0x9E3779B97F4A7C15ull * idx;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z ^= z >> 31;
+  return (uint32_t)(z >> 32) >= d.thresh ? d.scale : 0.f;
+}
+
 struct GemmDesc {
   const void* A; const void* B; void* C;
   int M, N, K, lda, ldb, ldc;
@@ -64,6 +92,7 @@ struct GemmDesc {
   int epilogue;
   void* Z; int ldz;      // EPI_GELU: written (type T); EPI_GELUGRAD: read (type T)
   float alpha;           // scales acc before the epilogue
+  DropDesc drop;         // dropout on (alpha*acc + bias), before the residual; element index m*drop.ld + n
 };
 // MFMA tile configurations (bf16): register-staged 128x128 (any K multiple of 8), and four
 // direct-to-LDS kernels that need K % 64 == 0 and operands under 2 GiB.
@@ -122,11 +151,16 @@ hipError_t launch_layernorm_bwd_params(hipStream_t s, int dtype, const void* dy,
 // out[c] += sum over rows of x[r, c]  (fp32 accumulate into, caller zeroes)
 hipError_t launch_colsum(hipStream_t s, int dtype, const void* x, int ldx, float* out, int rows, int cols);
 // h[n,:] = scale * V[tok[n],:] (+ pe[n % T,:]); ids outside [0,vocab) set *flag and give a zero row
+// drop (optional): dropout on the sum, element index n*drop->ld + c
 hipError_t launch_embed_fwd(hipStream_t s, int dtype, const int32_t* tok, const void* V, const float* pe,
-                            void* h, int N, int T, int d, int vocab, float scale, int* flag);
+                            void* h, int N, int T, int d, int vocab, float scale, int* flag,
+                            const DropDesc* drop = nullptr);
 // dVi[tok[n],:] += scale * dh[n,:]   (fp32 atomics; caller zeroes dVi)
 hipError_t launch_embed_bwd(hipStream_t s, int dtype, const int32_t* tok, const void* dh, float* dVi,
-                            int N, int d, int vocab, float scale);
+                            int N, int d, int vocab, float scale, const DropDesc* drop = nullptr);
+// dst[r, c] = src[r, c] * mask(r*drop.ld + c) over rows x cols elements, both with row stride ld
+hipError_t launch_dropout_apply(hipStream_t s, int dtype, const void* src, void* dst, int rows, int cols, int ld,
+                                const DropDesc& drop);
 // per row n of logits [N, ld] (type T): lse, rowloss = lse - logit[target]; G = (softmax - onehot)/N as T
 // (G may alias logits: every element is read before it is overwritten by the same thread)
 hipError_t launch_ce_rows(hipStream_t s, int dtype, const void* logits, int ld, const int32_t* tgt,

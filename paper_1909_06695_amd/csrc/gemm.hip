@@ -199,6 +199,7 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
   p.out_fp32 = g.out_fp32; p.accumulate = g.accumulate;
   p.bias = g.bias; p.residual = g.residual; p.ldr = g.ldr;
   p.epilogue = g.epilogue; p.Z = g.Z; p.ldz = g.ldz; p.alpha = g.alpha;
+  p.drop = g.drop;
   p.kchunk = g.K; p.tilesN = 0; p.vec_epi = 0;
   if (g.accumulate && (!g.out_fp32 || g.bias || g.residual || g.epilogue != EPI_NONE)) return hipErrorInvalidValue;
 

@@ -17,6 +17,7 @@ struct GemmParams {
   int kchunk;      // K range per blockIdx.z
   int tilesN;      // tiles along N (MFMA kernel)
   int vec_epi;     // 1: C, Z, residual allow 16-byte row-chunk accesses (MFMA kernel)
+  DropDesc drop;
 };
 
 template <typename T>
@@ -27,6 +28,7 @@ __device__ __forceinline__ void epilogue_store(const GemmParams& p, int m, int n
     return;
   }
   if (p.bias) v += p.bias[n];
+  if (p.drop.on) v *= drop_factor(p.drop, (uint64_t)m * p.drop.ld + n);
   if (p.epilogue == EPI_GELU) {
     reinterpret_cast<T*>(p.Z)[(size_t)m * p.ldz + n] = from_f32<T>(v);
     v = gelu_f(v);
@@ -48,6 +50,11 @@ __device__ __forceinline__ void epilogue_store8(const GemmParams& p, int m, int 
   if (p.bias) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] += p.bias[n + e];
+  }
+  if (p.drop.on) {
+    const uint64_t i0 = (uint64_t)m * p.drop.ld + n;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] *= drop_factor(p.drop, i0 + e);
   }
   if (p.epilogue == EPI_GELU) {
     union { bf16_t h[8]; uint4 u; } z;

@@ -178,6 +178,8 @@ struct ouro_model {
   char *dhb[3], *dy[2], *da, *dcat, *dr_t[2];   // layer l reads dhb[l % 3], writes dhb[(l + 2) % 3]
   // gradients that the weight-gradient GEMMs read on the side stream: two sets, by layer parity
   char *ds2[2], *dz[2], *ds1[2], *dqkv[2];
+  char *ds2m[2], *ds1m[2];         // ds2 / ds1 times the dropout masks (the same buffers without dropout)
+  uint64_t cur_seed;               // dropout seed of the mini-batch being worked on
   float *attn_scratch, *dr_f32[2], *dbg_f32, *dh_f32;
   size_t dbg_floats;
   // Stored-input schedule (cfg.schedule == 1): module k < K keeps the input of its last
@@ -256,6 +258,7 @@ static int validate(const ouro_config* c, std::vector<int>& lpm) {
   if (c->optimizer != 0 && c->optimizer != 1) return fail(OURO_E_CONFIG, "optimizer must be 0 or 1");
   if (c->embed_warm_mode != 0 && c->embed_warm_mode != 1) return fail(OURO_E_CONFIG, "embed_warm_mode must be 0 or 1");
   if (c->schedule != 0 && c->schedule != 1) return fail(OURO_E_CONFIG, "schedule must be 0 or 1");
+  if (!(c->dropout >= 0.f && c->dropout < 1.f)) return fail(OURO_E_CONFIG, "dropout must be in [0, 1)");
   if (c->optimizer == 1 && !(c->beta1 >= 0 && c->beta1 < 1 && c->beta2 >= 0 && c->beta2 < 1 && c->eps > 0))
     return fail(OURO_E_CONFIG, "Adam constants out of range");
   if ((int64_t)c->batch * c->seq_len > (1 << 24)) return fail(OURO_E_CONFIG, "batch*seq_len too large");
@@ -406,6 +409,8 @@ static size_t lay_out(ouro_model& m, char* base) {
   for (int p2 = 0; p2 < 2; ++p2) {
     m.ds2[p2] = P(N * d * es); m.dz[p2] = P(N * F * es);
     m.ds1[p2] = P(N * d * es); m.dqkv[p2] = P(qkv_elems * es);
+    m.ds2m[p2] = c.dropout > 0 ? P(N * d * es) : m.ds2[p2];
+    m.ds1m[p2] = c.dropout > 0 ? P(N * d * es) : m.ds1[p2];
   }
   m.dcat = c.rel_pos ? P(B * S * d * es) : nullptr;
   for (int p2 = 0; p2 < 2; ++p2) {
@@ -635,6 +640,12 @@ static GemmDesc gd(const void* A, int lda, int tA, const void* B, int ldb, int t
 #define RUN(expr) do { int rc_ = (expr); if (rc_) return rc_; } while (0)
 
 // ------------------------------------------------------------------------------ forward
+// Dropout descriptor of a place (0: embedding sum; 2l+1 / 2l+2: attention-projection / feed-forward
+// output of layer l) under the seed of the mini-batch being worked on; rows are d_model long.
+static DropDesc drop_at(const ouro_model* m, uint32_t place) {
+  return make_drop(m->cfg.dropout, m->cur_seed, place, m->cfg.d_model);
+}
+
 // Valid rows of every segment memory at the forward pass of iteration t.
 static int mem_valid_at(const ouro_model* m, int64_t t) {
   const int64_t rows = t * (int64_t)m->cfg.seq_len;
@@ -685,7 +696,7 @@ static int layer_forward(ouro_model* m, int l, char* out_override = nullptr) {
   HIPCHK(launch_attn_fwd(m->stream, c.dtype, a, 0));
   {
     GemmDesc g = gd(b.a, hd, 0, m->wT(l, o.W_o), d, 0, b.s1, d, N, d, hd);
-    g.residual = b.x; g.ldr = d;
+    g.residual = b.x; g.ldr = d; g.drop = drop_at(m, 2 * l + 1);
     RUN(run_gemm(m, g));
   }
   HIPCHK(launch_layernorm_fwd(m->stream, c.dtype, b.s1, m->wF(l, o.ln1_g), m->wF(l, o.ln1_b), b.y, b.mean1, b.rstd1, N, d, dn));
@@ -696,7 +707,7 @@ static int layer_forward(ouro_model* m, int l, char* out_override = nullptr) {
   }
   {
     GemmDesc g = gd(b.uact, F, 0, m->wT(l, o.W_2), d, 0, b.s2, d, N, d, F);
-    g.bias = m->wF(l, o.b_2); g.residual = b.y; g.ldr = d;
+    g.bias = m->wF(l, o.b_2); g.residual = b.y; g.ldr = d; g.drop = drop_at(m, 2 * l + 2);
     RUN(run_gemm(m, g));
   }
   HIPCHK(launch_layernorm_fwd(m->stream, c.dtype, b.s2, m->wF(l, o.ln2_g), m->wF(l, o.ln2_b), out, b.mean2, b.rstd2, N, d, dn));
@@ -713,8 +724,10 @@ extern "C" int ouro_module_forward(ouro_model* m, int k, const int32_t* dev_toke
   if (k == 1) {
     if (!dev_tokens) return fail(OURO_E_ARG, "module_forward(1) needs tokens");
     m->tok = dev_tokens;
+    m->cur_seed = c.seed + (uint64_t)m->t;
     HIPCHK(launch_fill_zero(m->stream, m->flag, 256));
-    HIPCHK(launch_embed_fwd(m->stream, c.dtype, m->tok, m->vT(), m->pe, m->L[0].x, m->N, c.seq_len, m->pd, c.vocab, c.emb_scale, m->flag));
+    const DropDesc dd = drop_at(m, 0);
+    HIPCHK(launch_embed_fwd(m->stream, c.dtype, m->tok, m->vT(), m->pe, m->L[0].x, m->N, c.seq_len, m->pd, c.vocab, c.emb_scale, m->flag, &dd));
   }
   if (k == K && !dev_targets) return fail(OURO_E_ARG, "module_forward(K) needs targets");
   if (c.schedule == 1 && k < K) {
@@ -774,6 +787,9 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   const bool side = m->use_side;
   hipStream_t sw = side ? m->side : st;               // stream of the weight-gradient work
   char* ds2 = m->ds2[ps]; char* dz = m->dz[ps]; char* ds1 = m->ds1[ps]; char* dqkv = m->dqkv[ps];
+  // what flows into the two dropped branches: the LayerNorm input gradients times the masks
+  char* ds2m = m->ds2m[ps]; char* ds1m = m->ds1m[ps];
+  const bool dropping = c.dropout > 0;
   char* dy = m->dy[ps];
   // the side stream may still be reading this buffer set (layer l+2 of this module)
   if (side && m->side_busy[ps]) { HIPCHK(hipStreamWaitEvent(st, m->ev_side_done[ps], 0)); m->side_busy[ps] = false; }
@@ -787,17 +803,18 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   // with the side stream the scale/shift gradients (column sums over dh and s2) run there too
   HIPCHK(launch_layernorm_bwd(st, c.dtype, dh, b.s2, m->wF(l, o.ln2_g), b.mean2, b.rstd2, ds2,
                               side ? nullptr : gslot + o.ln2_g, gslot + o.ln2_b, N, d, dn));
+  if (dropping) HIPCHK(launch_dropout_apply(st, c.dtype, ds2, ds2m, N, d, d, drop_at(m, 2 * l + 2)));
   RUN(ready(0));
   if (side) HIPCHK(launch_layernorm_bwd_params(sw, c.dtype, dh, b.s2, b.mean2, b.rstd2, gslot + o.ln2_g, gslot + o.ln2_b, N, d));
   // FFN2
   {
-    GemmDesc g = gd(b.uact, F, 1, ds2, d, 0, gslot + o.W_2, d, F, d, N);
+    GemmDesc g = gd(b.uact, F, 1, ds2m, d, 0, gslot + o.W_2, d, F, d, N);
     g.out_fp32 = 1; g.accumulate = 1;
     RUN(run_gemm_on(m, g, sw));
   }
-  HIPCHK(launch_colsum(sw, c.dtype, ds2, d, gslot + o.b_2, N, d));
+  HIPCHK(launch_colsum(sw, c.dtype, ds2m, d, gslot + o.b_2, N, d));
   {
-    GemmDesc g = gd(ds2, d, 0, m->wT(l, o.W_2), d, 1, dz, F, N, F, d);
+    GemmDesc g = gd(ds2m, d, 0, m->wT(l, o.W_2), d, 1, dz, F, N, F, d);
     g.epilogue = EPI_GELUGRAD; g.Z = b.z; g.ldz = F;
     RUN(run_gemm(m, g));
   }
@@ -817,15 +834,16 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   // LN1
   HIPCHK(launch_layernorm_bwd(st, c.dtype, dy, b.s1, m->wF(l, o.ln1_g), b.mean1, b.rstd1, ds1,
                               side ? nullptr : gslot + o.ln1_g, gslot + o.ln1_b, N, d, dn));
+  if (dropping) HIPCHK(launch_dropout_apply(st, c.dtype, ds1, ds1m, N, d, d, drop_at(m, 2 * l + 1)));
   RUN(ready(2));
   if (side) HIPCHK(launch_layernorm_bwd_params(sw, c.dtype, dy, b.s1, b.mean1, b.rstd1, gslot + o.ln1_g, gslot + o.ln1_b, N, d));
   // output projection
   {
-    GemmDesc g = gd(b.a, hd, 1, ds1, d, 0, gslot + o.W_o, d, hd, d, N);
+    GemmDesc g = gd(b.a, hd, 1, ds1m, d, 0, gslot + o.W_o, d, hd, d, N);
     g.out_fp32 = 1; g.accumulate = 1;
     RUN(run_gemm_on(m, g, sw));
   }
-  RUN(run_gemm(m, gd(ds1, d, 0, m->wT(l, o.W_o), d, 1, m->da, hd, N, hd, d)));
+  RUN(run_gemm(m, gd(ds1m, d, 0, m->wT(l, o.W_o), d, 1, m->da, hd, N, hd, d)));
   // attention
   AttnDesc a;
   memset(&a, 0, sizeof a);
@@ -932,9 +950,11 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
     if (m->intags[k][is] != tau) return fail(OURO_E_STALE, "module %d input slot %lld holds iteration %lld, wanted %lld", k, (long long)is, (long long)m->intags[k][is], (long long)tau);
     m->in_last_slot[k] = is; m->in_last_tau[k] = tau;
     const char* src = m->inring[k] + (size_t)is * m->instride[k];
+    m->cur_seed = c.seed + (uint64_t)tau;           // the stored seed: the masks of the original pass
     if (k == 1) {
       tok = (const int32_t*)src;
-      HIPCHK(launch_embed_fwd(m->stream, c.dtype, tok, m->vT(), m->pe, m->L[0].x, N, c.seq_len, d, V, c.emb_scale, m->flag));
+      const DropDesc dd = drop_at(m, 0);
+      HIPCHK(launch_embed_fwd(m->stream, c.dtype, tok, m->vT(), m->pe, m->L[0].x, N, c.seq_len, d, V, c.emb_scale, m->flag, &dd));
     } else {
       HIPCHK(hipMemcpyAsync(m->L[first].x, src, (size_t)N * d * m->esz, hipMemcpyDeviceToDevice, m->stream));
     }
@@ -1008,9 +1028,11 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
     if (!stored) ouro_slot_index(K, 0, m->t, 1, &s0, &t0);
     float* dvi = m->slot_ptr(0, s0);
     HIPCHK(launch_fill_zero(m->stream, dvi, (size_t)m->gstride[0] * 4));
-    HIPCHK(launch_embed_bwd(m->stream, c.dtype, tok, m->dhb[2], dvi, N, d, V, c.emb_scale));
+    const DropDesc dd = drop_at(m, 0);
+    HIPCHK(launch_embed_bwd(m->stream, c.dtype, tok, m->dhb[2], dvi, N, d, V, c.emb_scale, &dd));
     m->tags[0][s0] = m->t;
   }
+  m->cur_seed = c.seed + (uint64_t)m->t;
   m->bwd_next = k - 1;
   return OURO_OK;
 }

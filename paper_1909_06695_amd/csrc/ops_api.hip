@@ -32,6 +32,23 @@ extern "C" int ouro_op_gemm(void* stream, int dtype, int transA, int transB, int
   return rc_of(launch_gemm((hipStream_t)stream, dtype, g, force_generic));
 }
 
+extern "C" int ouro_op_gemm_dropout(void* stream, int dtype, int transA, int transB, int M, int N, int K,
+                                    const void* A, int lda, const void* B, int ldb, void* C, int ldc, const float* bias,
+                                    const void* residual, int ldr, float p, uint64_t seed, uint32_t stream_id, int drop_ld,
+                                    int force_generic) {
+  if (!A || !B || !C || M < 0 || N < 0 || K < 0 || !(p >= 0.f && p < 1.f) || drop_ld < N) return OURO_E_ARG;
+  if (lda < (transA ? M : K) || ldb < (transB ? K : N) || ldc < N) return OURO_E_ARG;
+  GemmDesc g = make_gemm(transA, transB, M, N, K, 1.f, A, lda, B, ldb, C, ldc, 0, 0, bias, residual, ldr, EPI_NONE, nullptr, 0);
+  g.drop = make_drop(p, seed, stream_id, drop_ld);
+  return rc_of(launch_gemm((hipStream_t)stream, dtype, g, force_generic));
+}
+
+extern "C" int ouro_op_dropout(void* stream, int dtype, const void* src, void* dst, int rows, int cols, int ld,
+                               float p, uint64_t seed, uint32_t stream_id, int drop_ld) {
+  if (!src || !dst || rows < 0 || cols < 0 || ld < cols || !(p >= 0.f && p < 1.f) || drop_ld < cols) return OURO_E_ARG;
+  return rc_of(launch_dropout_apply((hipStream_t)stream, dtype, src, dst, rows, cols, ld, make_drop(p, seed, stream_id, drop_ld)));
+}
+
 extern "C" int ouro_op_gemm_uses_mfma(int dtype, int transA, int transB, int M, int N, int K, const void* A, int lda,
                                       const void* B, int ldb) {
   GemmDesc g = make_gemm(transA, transB, M, N, K, 1.f, A, lda, B, ldb, nullptr, N, 0, 0, nullptr, nullptr, 0, 0, nullptr, 0);

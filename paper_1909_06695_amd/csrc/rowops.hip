@@ -443,7 +443,7 @@ hipError_t launch_colsum(hipStream_t s, int dtype, const void* x, int ldx, float
 template <typename T>
 __global__ __launch_bounds__(256) void embed_fwd_kernel(const int32_t* __restrict__ tok, const T* __restrict__ V,
                                                         const float* __restrict__ pe, T* __restrict__ h, int N, int T_,
-                                                        int d, int vocab, float scale, int* flag) {
+                                                        int d, int vocab, float scale, int* flag, DropDesc drop) {
   const int lane = threadIdx.x & 63;
   const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (n >= N) return;
@@ -455,35 +455,66 @@ __global__ __launch_bounds__(256) void embed_fwd_kernel(const int32_t* __restric
   for (int c = lane; c < d; c += 64) {
     float v = ok ? scale * to_f32(row[c]) : 0.f;
     if (per) v += per[c];
+    if (drop.on) v *= drop_factor(drop, (uint64_t)n * drop.ld + c);
     h[(size_t)n * d + c] = from_f32<T>(v);
   }
 }
 
 template <typename T>
 __global__ __launch_bounds__(256) void embed_bwd_kernel(const int32_t* __restrict__ tok, const T* __restrict__ dh,
-                                                        float* __restrict__ dVi, int N, int d, int vocab, float scale) {
+                                                        float* __restrict__ dVi, int N, int d, int vocab, float scale,
+                                                        DropDesc drop) {
   const int lane = threadIdx.x & 63;
   const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (n >= N) return;
   const int id = tok[n];
   if (id < 0 || id >= vocab) return;
-  for (int c = lane; c < d; c += 64)
-    unsafeAtomicAdd(dVi + (size_t)id * d + c, scale * to_f32(dh[(size_t)n * d + c]));
+  for (int c = lane; c < d; c += 64) {
+    float g = scale * to_f32(dh[(size_t)n * d + c]);
+    if (drop.on) g *= drop_factor(drop, (uint64_t)n * drop.ld + c);
+    unsafeAtomicAdd(dVi + (size_t)id * d + c, g);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void dropout_apply_kernel(const T* __restrict__ src, T* __restrict__ dst, int rows,
+                                                            int cols, int ld, DropDesc drop) {
+  const size_t total = (size_t)rows * cols;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const size_t r = i / cols, c = i % cols;
+    dst[r * ld + c] = from_f32<T>(to_f32(src[r * ld + c]) * drop_factor(drop, (uint64_t)r * drop.ld + c));
+  }
 }
 
 hipError_t launch_embed_fwd(hipStream_t s, int dtype, const int32_t* tok, const void* V, const float* pe,
-                            void* h, int N, int T, int d, int vocab, float scale, int* flag) {
+                            void* h, int N, int T, int d, int vocab, float scale, int* flag, const DropDesc* drop) {
   dim3 grid((N + 3) / 4), block(256);
-  if (dtype == 1) hipLaunchKernelGGL(embed_fwd_kernel<bf16_t>, grid, block, 0, s, tok, (const bf16_t*)V, pe, (bf16_t*)h, N, T, d, vocab, scale, flag);
-  else hipLaunchKernelGGL(embed_fwd_kernel<float>, grid, block, 0, s, tok, (const float*)V, pe, (float*)h, N, T, d, vocab, scale, flag);
+  DropDesc dd;
+  memset(&dd, 0, sizeof dd);
+  if (drop) dd = *drop;
+  if (dtype == 1) hipLaunchKernelGGL(embed_fwd_kernel<bf16_t>, grid, block, 0, s, tok, (const bf16_t*)V, pe, (bf16_t*)h, N, T, d, vocab, scale, flag, dd);
+  else hipLaunchKernelGGL(embed_fwd_kernel<float>, grid, block, 0, s, tok, (const float*)V, pe, (float*)h, N, T, d, vocab, scale, flag, dd);
+  return hipGetLastError();
+}
+
+hipError_t launch_dropout_apply(hipStream_t s, int dtype, const void* src, void* dst, int rows, int cols, int ld,
+                                const DropDesc& drop) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  const size_t total = (size_t)rows * cols;
+  dim3 grid((unsigned)std::min<size_t>((total + 255) / 256, 4096)), block(256);
+  if (dtype == 1) hipLaunchKernelGGL(dropout_apply_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)src, (bf16_t*)dst, rows, cols, ld, drop);
+  else hipLaunchKernelGGL(dropout_apply_kernel<float>, grid, block, 0, s, (const float*)src, (float*)dst, rows, cols, ld, drop);
   return hipGetLastError();
 }
 
 hipError_t launch_embed_bwd(hipStream_t s, int dtype, const int32_t* tok, const void* dh, float* dVi,
-                            int N, int d, int vocab, float scale) {
+                            int N, int d, int vocab, float scale, const DropDesc* drop) {
   dim3 grid((N + 3) / 4), block(256);
-  if (dtype == 1) hipLaunchKernelGGL(embed_bwd_kernel<bf16_t>, grid, block, 0, s, tok, (const bf16_t*)dh, dVi, N, d, vocab, scale);
-  else hipLaunchKernelGGL(embed_bwd_kernel<float>, grid, block, 0, s, tok, (const float*)dh, dVi, N, d, vocab, scale);
+  DropDesc dd;
+  memset(&dd, 0, sizeof dd);
+  if (drop) dd = *drop;
+  if (dtype == 1) hipLaunchKernelGGL(embed_bwd_kernel<bf16_t>, grid, block, 0, s, tok, (const bf16_t*)dh, dVi, N, d, vocab, scale, dd);
+  else hipLaunchKernelGGL(embed_bwd_kernel<float>, grid, block, 0, s, tok, (const float*)dh, dVi, N, d, vocab, scale, dd);
   return hipGetLastError();
 }
 

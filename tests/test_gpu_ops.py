@@ -257,6 +257,48 @@ def test_layernorm_zero_padded_rows(dtype, rows, dn, d):
     assert rel_err(host(gb)[:dn], rb) < 1e-4 and not host(gb)[dn:].any()
 
 
+# ---------------------------------------------------------------------------- dropout
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("rows,cols,ld,drop_ld", [(37, 64, 64, 64), (130, 410, 448, 410), (3, 5, 9, 7)])
+def test_dropout_mask_bit_exact(dtype, rows, cols, ld, drop_ld):
+    """The kernel's generator against the oracle's: every element kept or dropped alike (integer
+    work: bit-exact), kept elements scaled by 1/(1-p); element index = row * drop_ld + column."""
+    pr, seed, sid = 0.3, 0xDEADBEEF12345678, 11
+    cfg = O.Config(n_layer=1, d_model=2, n_head=1, d_head=2, d_ff=1, vocab=2, seq_len=1, batch=1, dropout=pr)
+    src = np.zeros((rows, ld), np.float32)
+    src[:, :cols] = 1.0 + np.arange(rows * cols, dtype=np.float32).reshape(rows, cols) % 7
+    d_src = dev(src, dtype)
+    dst = torch.zeros_like(d_src)
+    ok(L().ouro_op_dropout(stream(), dtype, p(d_src), p(dst), rows, cols, ld, pr, seed, sid, drop_ld))
+    torch.cuda.synchronize()
+    mask = O.dropout_mask(cfg, seed, sid, (rows, drop_ld))[:, :cols]
+    got = host(dst)[:, :cols]
+    assert np.array_equal(got != 0, mask != 0)
+    assert rel_err(got, host(d_src)[:, :cols] * mask) < TOL[dtype]
+    assert 0.6 < (mask != 0).mean() < 0.8 or mask.size < 100
+
+
+@pytest.mark.parametrize("dtype,force", [(0, 0), (1, 1), (1, 0), (1, 10), (1, 11), (1, 12), (1, 13), (1, 14)])
+@pytest.mark.parametrize("M,N,K", [(200, 136, 328), (384, 520, 192), (130, 82, 128)])
+def test_gemm_with_fused_dropout(dtype, force, M, N, K):
+    """C = dropout(A B + bias) + residual in every contraction kernel's epilogue (16-byte and
+    scalar store paths, ragged tiles): the mask is the oracle's at element m*N + n."""
+    rng = np.random.default_rng(M + N + K + force)
+    A = rng.standard_normal((M, K)).astype(np.float32); B = rng.standard_normal((K, N)).astype(np.float32) / math.sqrt(K)
+    bias = rng.standard_normal(N).astype(np.float32); R = rng.standard_normal((M, N)).astype(np.float32)
+    pr, seed, sid = 0.25, 424242, 5
+    cfg = O.Config(n_layer=1, d_model=2, n_head=1, d_head=2, d_ff=1, vocab=2, seq_len=1, batch=1, dropout=pr)
+    dA, dB, dR = dev(A, dtype), dev(B, dtype), dev(R, dtype)
+    dbias = torch.from_numpy(bias).cuda()
+    Cc = torch.zeros((M, N), dtype=dA.dtype, device="cuda")
+    ok(L().ouro_op_gemm_dropout(stream(), dtype, 0, 0, M, N, K, p(dA), K, p(dB), N, p(Cc), N, p(dbias), p(dR), N,
+                                pr, seed, sid, N, force))
+    torch.cuda.synchronize()
+    mask = O.dropout_mask(cfg, seed, sid, (M, N))
+    ref = (host(dA) @ host(dB) + bias) * mask + host(dR)
+    assert rel_err(host(Cc), ref) < TOL[dtype]
+
+
 @pytest.mark.parametrize("dtype", [0, 1])
 def test_colsum(dtype):
     rng = np.random.default_rng(3)

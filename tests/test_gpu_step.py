@@ -184,6 +184,34 @@ def test_stored_input_schedule_bf16():
     run_both(c, steps=5, lr=1e-3, seed=63, std=0.05, perturb=0.05, tol=2e-2)
 
 
+@pytest.mark.parametrize("schedule", [0, 1])
+def test_dropout_fp32(schedule):
+    """Repeatable dropout (embedding sum, attention-projection and feed-forward outputs) in both
+    schedules against the oracle, fp32: the masks are bit-identical on both sides, so the usual
+    tolerance holds.  Under schedule 1 the recomputation of mini-batch t-K+k must regenerate that
+    mini-batch's masks from the stored seed (a recomputation under the running seed fails this)."""
+    c = dict(n_layer=4, d_model=40, n_head=5, d_head=8, d_ff=72, vocab=131, seq_len=19, mem_len=0, batch=3,
+             n_module=3, rel_pos=0, dtype=0, optimizer=0, schedule=schedule, dropout=0.2, seed=2 ** 40 + 17)
+    run_both(c, steps=6, lr=0.05, seed=81, std=0.1, perturb=0.1)
+
+
+def test_dropout_xl_memory_adam_fp32():
+    c = dict(n_layer=3, d_model=32, n_head=2, d_head=16, d_ff=48, vocab=61, seq_len=6, mem_len=10, batch=2,
+             n_module=3, rel_pos=1, dtype=0, optimizer=1, schedule=1, dropout=0.1, seed=5)
+    run_both(c, steps=6, lr=1e-3, seed=83, std=0.15, perturb=0.1)
+
+
+@pytest.mark.parametrize("schedule", [0, 1])
+def test_dropout_bf16(schedule):
+    """bf16: fused masks in the MFMA epilogues (16-byte store path) and through zero-padded storage."""
+    c = dict(n_layer=3, d_model=128, n_head=2, d_head=64, d_ff=256, vocab=512, seq_len=96, mem_len=0, batch=3,
+             n_module=3, rel_pos=0, dtype=1, optimizer=0, schedule=schedule, dropout=0.15, seed=99)
+    run_both(c, steps=5, lr=0.05, seed=85, std=0.05, perturb=0.05, tol=2e-2)
+    c = dict(n_layer=2, d_model=82, n_head=2, d_head=41, d_ff=100, vocab=203, seq_len=70, mem_len=0, batch=3,
+             n_module=2, rel_pos=0, dtype=1, optimizer=0, schedule=schedule, dropout=0.15, seed=7)
+    run_both(c, steps=4, lr=0.05, seed=87, std=0.05, perturb=0.05, tol=2e-2)
+
+
 def test_bf16_small_sgd():
     """bf16 mode against the fp64 oracle within 2e-2 (several tiles of the MFMA kernels)."""
     c = dict(n_layer=2, d_model=128, n_head=2, d_head=64, d_ff=512, vocab=512, seq_len=128, mem_len=0, batch=2,
