@@ -151,6 +151,27 @@ int ouro_module_backward(ouro_model* m, int k);
 int ouro_delayed_update(ouro_model* m, int group, float lr);
 int ouro_step(ouro_model* m, const int32_t* dev_tokens, const int32_t* dev_targets, float lr,
               float* host_loss);
+/* --- evaluation and checkpoints ---
+ * ouro_eval_step: a forward-only iteration with the current weights: the loss of the mini-batch
+ *   (Eq. 4; bits per character = loss / ln 2, perplexity = exp(loss)), no dropout, no gradient,
+ *   no update, nothing stored for a later backward pass.  Segment memories roll and the
+ *   iteration counter advances as after a training iteration, so a stream of consecutive
+ *   segments is evaluated with carried-over memory; evaluate on a model of its own (it may have
+ *   a longer mem_len than the training model; copy the weights with ouro_get_params /
+ *   ouro_set_params on device pointers), not between the training iterations of one model.
+ *   Only at an iteration boundary (OURO_E_SEQUENCE otherwise).
+ * ouro_state_bytes / ouro_save_state / ouro_load_state: the whole training state at an
+ *   iteration boundary as one host buffer: iteration counter, master weights and their bf16
+ *   copies, Adam moments, every gradient and input ring with its tags (the pending stale
+ *   gradients), error-gradient mailboxes, segment memories.  A model created with the same
+ *   configuration continues from a loaded state exactly where the saved one stood.  bytes must
+ *   equal ouro_state_bytes; a buffer of another configuration is refused (OURO_E_CONFIG).
+ *   Both calls synchronise the model's streams. */
+int ouro_eval_step(ouro_model* m, const int32_t* dev_tokens, const int32_t* dev_targets, float* host_loss);
+int ouro_state_bytes(const ouro_model* m, size_t* bytes);
+int ouro_save_state(ouro_model* m, void* host_dst, size_t bytes);
+int ouro_load_state(ouro_model* m, const void* host_src, size_t bytes);
+
 /* Loss of the most recent forward of module K; synchronises the stream. */
 int ouro_get_loss(ouro_model* m, float* host_loss);
 int64_t ouro_current_step(const ouro_model* m);

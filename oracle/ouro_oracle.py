@@ -515,6 +515,22 @@ class Oracle:
         self.t += 1
         return loss
 
+    def eval_step(self, tokens, targets):
+        """Forward-only pass with the current weights (Eq. 1-4, no dropout): the loss in nats
+        per token, from which the paper's tables report bits per character (loss / ln 2) or
+        perplexity (exp(loss)).  Segment memories roll and the counter advances, so that
+        consecutive segments are evaluated with carried-over memory."""
+        c = self.cfg
+        loss, fw = model_forward(c, self.layers, self.V, self.V, np.asarray(tokens), np.asarray(targets), self.mems, None)
+        if c.mem_len > 0:
+            new = []
+            for l in range(c.n_layer):
+                cat = fw["inputs"][l] if self.mems is None else np.concatenate([self.mems[l], fw["inputs"][l]], axis=1)
+                new.append(cat[:, -c.mem_len:].copy())
+            self.mems = new
+        self.t += 1
+        return loss
+
     def brute_check(self, t):
         """Re-derive, from the stored full state of step tau, every gradient that the
         update of iteration t consumed, and compare with what was used (Eq. 8-9)."""

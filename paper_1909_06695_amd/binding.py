@@ -61,6 +61,10 @@ def lib():
         "ouro_delayed_update": (i32, [vp, i32, f32]),
         "ouro_step": (i32, [vp, vp, vp, f32, P(f32)]),
         "ouro_get_loss": (i32, [vp, P(f32)]),
+        "ouro_eval_step": (i32, [vp, vp, vp, P(f32)]),
+        "ouro_state_bytes": (i32, [vp, P(sz)]),
+        "ouro_save_state": (i32, [vp, vp, sz]),
+        "ouro_load_state": (i32, [vp, vp, sz]),
         "ouro_current_step": (i64, [vp]),
         "ouro_slot_index": (i32, [i32, i32, i64, i32, P(i64), P(i64)]),
         "ouro_ring_depth": (i32, [i32, i32, P(i64)]),
@@ -226,6 +230,35 @@ class Model:
         loss = C.c_float()
         check(self.L.ouro_step(self.h, _ptr(tokens), _ptr(targets), lr, C.byref(loss) if want_loss else None))
         return loss.value if want_loss else None
+
+    def eval_step(self, tokens, targets, want_loss=True):
+        """Forward-only iteration: loss of the mini-batch in nats per token (bits per character =
+        loss / ln 2, perplexity = exp(loss)); memories roll."""
+        loss = C.c_float()
+        check(self.L.ouro_eval_step(self.h, _ptr(tokens), _ptr(targets), C.byref(loss) if want_loss else None))
+        return loss.value if want_loss else None
+
+    def copy_params_from(self, other):
+        """Device-to-device copy of every parameter group of `other` (same layer shapes)."""
+        import torch
+        for g in range(self.K + 1):
+            n = other.param_count(g)
+            buf = torch.empty(n, dtype=torch.float32, device="cuda")
+            check(other.L.ouro_get_params(other.h, g, C.c_void_p(buf.data_ptr()), n, 1))
+            check(self.L.ouro_set_params(self.h, g, C.c_void_p(buf.data_ptr()), n, 1))
+            torch.cuda.synchronize()
+
+    def save_state(self):
+        """The whole training state at an iteration boundary as a numpy byte array."""
+        n = C.c_size_t()
+        check(self.L.ouro_state_bytes(self.h, C.byref(n)))
+        buf = np.empty(n.value, dtype=np.uint8)
+        check(self.L.ouro_save_state(self.h, buf.ctypes.data_as(C.c_void_p), n.value))
+        return buf
+
+    def load_state(self, buf):
+        buf = np.ascontiguousarray(buf, dtype=np.uint8)
+        check(self.L.ouro_load_state(self.h, buf.ctypes.data_as(C.c_void_p), buf.size))
 
     def get_loss(self):
         loss = C.c_float()

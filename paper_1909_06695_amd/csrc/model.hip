@@ -180,6 +180,8 @@ struct ouro_model {
   char *ds2[2], *dz[2], *ds1[2], *dqkv[2];
   char *ds2m[2], *ds1m[2];         // ds2 / ds1 times the dropout masks (the same buffers without dropout)
   uint64_t cur_seed;               // dropout seed of the mini-batch being worked on
+  bool eval_mode;                  // inside ouro_eval_step: no dropout, no stored inputs
+  size_t persist_end;              // arena[0, persist_end): weights, moments, gradient and input rings, mailboxes
   float *attn_scratch, *dr_f32[2], *dbg_f32, *dh_f32;
   size_t dbg_floats;
   // Stored-input schedule (cfg.schedule == 1): module k < K keeps the input of its last
@@ -366,6 +368,7 @@ static size_t lay_out(ouro_model& m, char* base) {
     }
     m.hscratch = P(N * d * es);
   }
+  m.persist_end = bp.off;
   m.L.resize(L);
   const size_t qkv_elems = c.rel_pos ? (N * hd + B * S * 2 * hd) : (N * 3 * hd);
   for (int i = 0; i < L; ++i) {
@@ -482,6 +485,7 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
   m->t = 0; m->fwd_next = 1; m->bwd_next = K; m->upd_mask = 0; m->inject_mask = 0; m->mem_valid = 0;
   m->tok = m->tgt = nullptr;
   m->timing = 0;
+  m->eval_mode = false; m->cur_seed = cfg->seed;
   for (int i = 0; i < 2; ++i) { m->ev_used[i] = 0; m->timed_work[i] = 0; m->timed_launches[i] = 0; }
   m->side = nullptr; m->use_side = false; m->ev_join = nullptr;
   m->aux = nullptr; m->ev_bwd_done = m->ev_upd_done = nullptr; m->upd_pending = false;
@@ -643,7 +647,7 @@ static GemmDesc gd(const void* A, int lda, int tA, const void* B, int ldb, int t
 // Dropout descriptor of a place (0: embedding sum; 2l+1 / 2l+2: attention-projection / feed-forward
 // output of layer l) under the seed of the mini-batch being worked on; rows are d_model long.
 static DropDesc drop_at(const ouro_model* m, uint32_t place) {
-  return make_drop(m->cfg.dropout, m->cur_seed, place, m->cfg.d_model);
+  return make_drop(m->eval_mode ? 0.f : m->cfg.dropout, m->cur_seed, place, m->cfg.d_model);
 }
 
 // Valid rows of every segment memory at the forward pass of iteration t.
@@ -730,7 +734,7 @@ extern "C" int ouro_module_forward(ouro_model* m, int k, const int32_t* dev_toke
     HIPCHK(launch_embed_fwd(m->stream, c.dtype, m->tok, m->vT(), m->pe, m->L[0].x, m->N, c.seq_len, m->pd, c.vocab, c.emb_scale, m->flag, &dd));
   }
   if (k == K && !dev_targets) return fail(OURO_E_ARG, "module_forward(K) needs targets");
-  if (c.schedule == 1 && k < K) {
+  if (c.schedule == 1 && k < K && !m->eval_mode) {
     // the module's input of this iteration, for the backward pass K-k iterations from now
     const int64_t slot = m->t % m->indepth[k];
     char* dst = m->inring[k] + (size_t)slot * m->instride[k];
@@ -1183,6 +1187,133 @@ extern "C" int ouro_step(ouro_model* m, const int32_t* dev_tokens, const int32_t
   for (int k = 0; k <= K; ++k)
     if (!(done & (1ull << k))) RUN(update_group(m, k, lr, m->stream));
   if (host_loss) return read_loss(m, host_loss);
+  return OURO_OK;
+}
+
+// ------------------------------------------------------------------- evaluation, state
+extern "C" int ouro_eval_step(ouro_model* m, const int32_t* dev_tokens, const int32_t* dev_targets, float* host_loss) {
+  if (!m || !dev_tokens || !dev_targets) return fail(OURO_E_ARG, "eval_step: null argument");
+  if (m->fwd_next != 1 || m->inject_mask) return fail(OURO_E_SEQUENCE, "eval_step inside a training iteration");
+  const int K = m->cfg.n_module;
+  m->eval_mode = true;
+  int rc = OURO_OK;
+  for (int k = 1; k <= K && rc == OURO_OK; ++k) rc = ouro_module_forward(m, k, dev_tokens, dev_targets);
+  m->eval_mode = false;
+  if (rc) { m->fwd_next = 1; return rc; }
+  rc = close_iteration(m);          // segment memories roll; the counter moves on
+  if (rc) return rc;
+  if (host_loss) return read_loss(m, host_loss);
+  return OURO_OK;
+}
+
+namespace {
+struct StateHeader {
+  uint64_t magic;
+  uint32_t version, header_bytes;
+  ouro_config cfg;                  // layers_per_module pointer zeroed
+  int32_t lpm[64];
+  int64_t t;
+  int32_t mem_valid, n_tags;
+  uint64_t persist_bytes, mem_bytes;
+};
+const uint64_t STATE_MAGIC = 0x4f55524f53544154ull;   // "OUROSTAT"
+
+void fill_header(const ouro_model* m, StateHeader& h) {
+  memset(&h, 0, sizeof h);
+  h.magic = STATE_MAGIC; h.version = 1; h.header_bytes = (uint32_t)sizeof(StateHeader);
+  h.cfg = m->cfg; h.cfg.layers_per_module = nullptr;
+  for (size_t i = 0; i < m->lpm.size(); ++i) h.lpm[i] = m->lpm[i];
+  h.t = m->t; h.mem_valid = m->mem_valid;
+  size_t nt = 0;
+  for (const auto& v : m->tags) nt += v.size();
+  for (const auto& v : m->intags) nt += v.size();
+  nt += m->mailtag[0].size() + m->mailtag[1].size();
+  h.n_tags = (int32_t)nt;
+  h.persist_bytes = m->persist_end;
+  size_t mb = 0;
+  for (const LayerBuf& b : m->L) {
+    if (b.memring) mb += b.memstride * (size_t)b.memdepth;
+    else if (b.mem) mb += (size_t)m->cfg.batch * m->cfg.mem_len * m->pd * m->esz;
+  }
+  h.mem_bytes = mb;
+}
+bool same_config(const ouro_config& a, const ouro_config& b) {
+  return a.n_layer == b.n_layer && a.d_model == b.d_model && a.n_head == b.n_head && a.d_head == b.d_head &&
+         a.d_ff == b.d_ff && a.vocab == b.vocab && a.seq_len == b.seq_len && a.mem_len == b.mem_len &&
+         a.batch == b.batch && a.n_module == b.n_module && a.rel_pos == b.rel_pos && a.dtype == b.dtype &&
+         a.optimizer == b.optimizer && a.beta1 == b.beta1 && a.beta2 == b.beta2 && a.eps == b.eps &&
+         a.embed_warm_mode == b.embed_warm_mode && a.emb_scale == b.emb_scale && a.schedule == b.schedule &&
+         a.dropout == b.dropout && a.seed == b.seed;
+}
+size_t state_bytes(const StateHeader& h) { return sizeof(StateHeader) + (size_t)h.n_tags * 8 + h.persist_bytes + h.mem_bytes; }
+}  // namespace
+
+extern "C" int ouro_state_bytes(const ouro_model* m, size_t* bytes) {
+  if (!m || !bytes) return fail(OURO_E_ARG, "state_bytes: null argument");
+  StateHeader h;
+  fill_header(m, h);
+  *bytes = state_bytes(h);
+  return OURO_OK;
+}
+
+extern "C" int ouro_save_state(ouro_model* m, void* host_dst, size_t bytes) {
+  if (!m || !host_dst) return fail(OURO_E_ARG, "save_state: null argument");
+  if (m->fwd_next != 1 || m->inject_mask) return fail(OURO_E_SEQUENCE, "save_state inside an iteration");
+  StateHeader h;
+  fill_header(m, h);
+  if (bytes != state_bytes(h)) return fail(OURO_E_ARG, "save_state: buffer has %zu bytes, state has %zu", bytes, state_bytes(h));
+  char* p = (char*)host_dst;
+  memcpy(p, &h, sizeof h); p += sizeof h;
+  int64_t* tg = (int64_t*)p;
+  for (const auto& v : m->tags) for (int64_t x : v) *tg++ = x;
+  for (const auto& v : m->intags) for (int64_t x : v) *tg++ = x;
+  for (int q = 0; q < 2; ++q) for (int64_t x : m->mailtag[q]) *tg++ = x;
+  p = (char*)tg;
+  HIPCHK(hipStreamSynchronize(m->side));
+  HIPCHK(hipStreamSynchronize(m->aux));
+  HIPCHK(hipMemcpyAsync(p, m->arena, m->persist_end, hipMemcpyDeviceToHost, m->stream)); p += m->persist_end;
+  for (const LayerBuf& b : m->L) {
+    const size_t n = b.memring ? b.memstride * (size_t)b.memdepth : b.mem ? (size_t)m->cfg.batch * m->cfg.mem_len * m->pd * m->esz : 0;
+    if (!n) continue;
+    HIPCHK(hipMemcpyAsync(p, b.memring ? b.memring : b.mem, n, hipMemcpyDeviceToHost, m->stream)); p += n;
+  }
+  HIPCHK(hipStreamSynchronize(m->stream));
+  return OURO_OK;
+}
+
+extern "C" int ouro_load_state(ouro_model* m, const void* host_src, size_t bytes) {
+  if (!m || !host_src) return fail(OURO_E_ARG, "load_state: null argument");
+  if (m->fwd_next != 1 || m->inject_mask) return fail(OURO_E_SEQUENCE, "load_state inside an iteration");
+  if (bytes < sizeof(StateHeader)) return fail(OURO_E_ARG, "load_state: buffer too short");
+  StateHeader h, mine;
+  memcpy(&h, host_src, sizeof h);
+  fill_header(m, mine);
+  if (h.magic != STATE_MAGIC || h.version != 1 || h.header_bytes != sizeof(StateHeader)) return fail(OURO_E_ARG, "load_state: not a state of this library version");
+  if (!same_config(h.cfg, mine.cfg) || memcmp(h.lpm, mine.lpm, sizeof h.lpm) || h.n_tags != mine.n_tags ||
+      h.persist_bytes != mine.persist_bytes || h.mem_bytes != mine.mem_bytes)
+    return fail(OURO_E_CONFIG, "load_state: the state was saved by a model with another configuration");
+  if (bytes != state_bytes(h)) return fail(OURO_E_ARG, "load_state: buffer has %zu bytes, state has %zu", bytes, state_bytes(h));
+  const char* p = (const char*)host_src + sizeof h;
+  const int64_t* tg = (const int64_t*)p;
+  for (auto& v : m->tags) for (int64_t& x : v) x = *tg++;
+  for (auto& v : m->intags) for (int64_t& x : v) x = *tg++;
+  for (int q = 0; q < 2; ++q) for (int64_t& x : m->mailtag[q]) x = *tg++;
+  p = (const char*)tg;
+  HIPCHK(hipStreamSynchronize(m->side));
+  HIPCHK(hipStreamSynchronize(m->aux));
+  HIPCHK(hipMemcpyAsync(m->arena, p, m->persist_end, hipMemcpyHostToDevice, m->stream)); p += m->persist_end;
+  for (LayerBuf& b : m->L) {
+    const size_t n = b.memring ? b.memstride * (size_t)b.memdepth : b.mem ? (size_t)m->cfg.batch * m->cfg.mem_len * m->pd * m->esz : 0;
+    if (!n) continue;
+    HIPCHK(hipMemcpyAsync(b.memring ? b.memring : b.mem, p, n, hipMemcpyHostToDevice, m->stream)); p += n;
+  }
+  HIPCHK(hipStreamSynchronize(m->stream));
+  m->t = h.t; m->mem_valid = h.mem_valid;
+  m->cur_seed = m->cfg.seed + (uint64_t)m->t;
+  for (int l = 0; l < m->cfg.n_layer; ++l) select_memory(m, l, m->t);
+  m->upd_mask = 0; m->upd_pending = false;
+  m->side_busy[0] = m->side_busy[1] = false;
+  std::fill(m->last_slot.begin(), m->last_slot.end(), -1); std::fill(m->last_tau.begin(), m->last_tau.end(), -1);
   return OURO_OK;
 }
 

@@ -309,6 +309,89 @@ def test_long_run_with_warmup_and_cosine_schedule():
     assert final[4] < final[1] + 0.25, final
 
 
+@pytest.mark.parametrize("dtype,tol", [(0, 1e-4), (1, 2e-2)])
+def test_eval_step_with_longer_memory(dtype, tol):
+    """Evaluation path: train a Transformer-XL model for a few iterations, copy its weights on the
+    device into an evaluation model with a longer memory (and dropout configured, which
+    evaluation must ignore), and evaluate consecutive segments: losses and rolled memories
+    against the oracle's forward-only pass; the weights and the training model stay untouched."""
+    dh = 64 if dtype else 16
+    c = dict(n_layer=3, d_model=2 * dh, n_head=2, d_head=dh, d_ff=96, vocab=211, seq_len=24, mem_len=24, batch=2,
+             n_module=3, rel_pos=1, dtype=dtype, optimizer=0, embed_warm_mode=1)
+    blobs = S.init_params(c, seed=11, std=0.1, perturb=0.1)
+    tok, tgt = S.token_batches(c["vocab"], c["batch"], c["seq_len"], 9, 1.1, 12, contiguous=True)
+    dtok = torch.from_numpy(tok).cuda(); dtgt = torch.from_numpy(tgt).cuda()
+    orc = O.Oracle(O.Config(**c), blobs)
+    m = P().create_model(**c)
+    for g in range(4):
+        m.set_params(g, blobs[g])
+    for t in range(4):
+        lo, lg = orc.step(tok[t], tgt[t], 0.05), m.step(dtok[t], dtgt[t], 0.05)
+        assert abs(lg - lo) / lo < tol
+    ce = dict(c, mem_len=60, dropout=0.4, seed=3)
+    oe = O.Oracle(O.Config(**ce), [orc.module_blob(g) for g in range(4)])
+    e = P().create_model(**ce)
+    e.copy_params_from(m)
+    for g in range(4):
+        assert np.array_equal(e.get_params(g), m.get_params(g))
+    for t in range(4, 9):
+        lo, lg = oe.eval_step(tok[t], tgt[t]), e.eval_step(dtok[t], dtgt[t])
+        assert abs(lg - lo) / lo < tol, (t, lg, lo)
+        assert e.current_step() == t - 3
+        for l in range(3):
+            mem = e.get_mems(l)
+            assert mem.shape == oe.mems[l].shape and rel_err(mem, oe.mems[l]) < tol
+    with pytest.raises(P().OuroError):                       # not in the middle of a training iteration
+        m.module_forward(1, dtok[0], dtgt[0]); m.eval_step(dtok[0], dtgt[0])
+    for g in range(4):
+        assert np.array_equal(e.get_params(g), m.get_params(g))
+    m.close(); e.close()
+
+
+@pytest.mark.parametrize("schedule,dtype,opt", [(0, 0, 1), (1, 0, 0), (1, 1, 1)])
+def test_checkpoint_resume(schedule, dtype, opt):
+    """Save the whole state (weights, moments, pending stale gradients or stored inputs with their
+    tags, mailboxes, memories, counters) after 4 iterations, load it into a fresh model of the same
+    configuration and go on: the resumed run keeps following the oracle, which ran straight
+    through.  Saving again right after loading returns the same bytes; another configuration is
+    refused."""
+    tol = 2e-2 if dtype else 1e-4
+    dh = 64 if dtype else 16
+    c = dict(n_layer=3, d_model=2 * dh, n_head=2, d_head=dh, d_ff=96, vocab=211, seq_len=24, mem_len=40, batch=2,
+             n_module=3, rel_pos=1, dtype=dtype, optimizer=opt, schedule=schedule, dropout=0.1, seed=77)
+    lr = 1e-3 if opt else 0.05
+    blobs = S.init_params(c, seed=13, std=0.1, perturb=0.1)
+    tok, tgt = S.token_batches(c["vocab"], c["batch"], c["seq_len"], 9, 1.1, 14, contiguous=True)
+    dtok = torch.from_numpy(tok).cuda(); dtgt = torch.from_numpy(tgt).cuda()
+    orc = (O.RecomputeOracle if schedule else O.Oracle)(O.Config(**c), blobs)
+    a = P().create_model(**c)
+    for g in range(4):
+        a.set_params(g, blobs[g])
+    for t in range(4):
+        lo, lg = orc.step(tok[t], tgt[t], lr), a.step(dtok[t], dtgt[t], lr)
+        assert abs(lg - lo) / lo < tol
+    state = a.save_state()
+    a.close()
+    b = P().create_model(**c)
+    b.load_state(state)
+    assert b.current_step() == 4
+    assert np.array_equal(b.save_state(), state)
+    for t in range(4, 9):
+        lo, lg = orc.step(tok[t], tgt[t], lr), b.step(dtok[t], dtgt[t], lr)
+        assert abs(lg - lo) / lo < tol, (t, lg, lo)
+    if opt == 0:                                              # (Adam: see run_both on ill-conditioned elements)
+        for g in range(4):
+            assert rel_err(b.get_params(g), orc.module_blob(g)) < tol
+    for l in range(3):
+        assert rel_err(b.get_mems(l), orc.mems[l]) < tol
+    other = P().create_model(**dict(c, d_ff=128))
+    with pytest.raises(P().OuroError):
+        other.load_state(state)
+    with pytest.raises(P().OuroError):
+        b.load_state(state[:-8])
+    other.close(); b.close()
+
+
 def test_timing_hooks():
     """Per-launch timing brackets and the empty-bracket cost: plausible, positive numbers."""
     c = dict(S.CONFIGS["cfg1"])

@@ -495,3 +495,25 @@ def test_repeatable_dropout_in_the_recompute_schedule():
         if ti >= 0:
             assert np.abs(b.grad_hist[t][1] - a.grad_hist[ti][1]).max() < 1e-12
     assert worst_bad > 1e-3
+
+
+def test_eval_step_is_the_forward_pass():
+    """Evaluation = the forward half of a training iteration at frozen weights: same loss, same
+    memory roll as a training step with step size 0 and no dropout; with dropout configured it
+    still reports the loss of the network without masks; weights never move."""
+    c, cfg, blobs, tok, tgt = make(2, L=2, steps=4, rel_pos=1, mem_len=7)
+    a, b = O.Oracle(cfg, blobs), O.Oracle(cfg, blobs)
+    cd = dict(c, dropout=0.3, seed=5)
+    d = O.Oracle(O.Config(**cd), blobs)
+    w0 = [a.module_blob(k) for k in range(3)]
+    for t in range(4):
+        la, lb, ld = a.step(tok[t], tgt[t], 0.0), b.eval_step(tok[t], tgt[t]), d.eval_step(tok[t], tgt[t])
+        assert la == lb == ld
+        for l in range(2):
+            assert np.array_equal(a.mems[l], b.mems[l]) and np.array_equal(a.mems[l], d.mems[l])
+        assert b.t == t + 1
+    for k in range(3):
+        assert np.array_equal(b.module_blob(k), w0[k])
+    # uniform predictions: loss = ln(vocab) exactly, i.e. log2(vocab) bits per character
+    z = [np.zeros_like(x) for x in blobs]
+    assert abs(O.Oracle(cfg, z).eval_step(tok[0], tgt[0]) - np.log(13)) < 1e-12
