@@ -135,7 +135,34 @@ struct Bump {
   }
 };
 
-struct ouro_model {
+// What one module's backward pass works with: its streams, the events between them and its
+// scratch buffers.  The model's own members of these names are the set in use; under the
+// stored-input schedule every module has a set of its own (ouro_model::ctxs), because the K
+// backward passes of an iteration are independent and ouro_step runs them side by side.
+struct BwdCtx {
+  hipStream_t stream;          // the error-gradient chain (set 0: the caller's stream, which also carries the forward pass)
+  // Weight-gradient GEMMs and bias column sums only feed the gradient ring, so they run on
+  // a second stream beside the error-gradient chain (both default priority); events order
+  // them against the producers of their operands and against the reuse of those buffers.
+  hipStream_t side;
+  hipEvent_t ev_ready[4];      // ds2 / dz / ds1 / dqkv of the current layer written (main)
+  hipEvent_t ev_side_done[2];  // side work that reads buffer set p finished
+  bool side_busy[2];
+  hipEvent_t ev_join;
+  hipEvent_t ev_done;          // sets 1..: this module's backward pass and update are enqueued up to here
+  // backward scratch
+  char *dhb[3], *dy[2], *da, *dcat, *dr_t[2];   // layer l reads dhb[l % 3], writes dhb[(l + 2) % 3]
+  // gradients that the weight-gradient GEMMs read on the side stream: two sets, by layer parity
+  char *ds2[2], *dz[2], *ds1[2], *dqkv[2];
+  char *ds2m[2], *ds1m[2];         // ds2 / ds1 times the dropout masks (the same buffers without dropout)
+  float *attn_scratch, *dr_f32[2], *dh_f32;
+  char* hscratch;                 // output of a recomputed module's last layer (never read)
+};
+
+struct ouro_model : BwdCtx {
+  std::vector<BwdCtx> ctxs;      // [K] under the stored-input schedule (entry of the set in use is stale), else empty
+  int cur_ctx;
+  hipEvent_t ev_fwd;             // forward pass of the iteration enqueued (the other sets wait for it)
   ouro_config cfg;
   std::vector<int> lpm;          // layers per module
   std::vector<int> first_layer;  // first layer of module k (index k-1), plus end
@@ -150,7 +177,6 @@ struct ouro_model {
   int pd, pdh, phd, pF;           // stored d_model, d_head, n_head * d_head, d_ff
   std::vector<std::vector<TensorMap>> tmap;   // per group 0..K
   std::vector<int64_t> pcount;    // stored elements per group
-  hipStream_t stream;
   char* arena;
   size_t bytes;
   int esz;                        // bytes per activation element
@@ -174,15 +200,10 @@ struct ouro_model {
                                   // extent the two contractions over / onto the vocabulary run with (padding is zero)
   float *lse_ce, *rowloss, *loss;
   int* flag;
-  // backward scratch
-  char *dhb[3], *dy[2], *da, *dcat, *dr_t[2];   // layer l reads dhb[l % 3], writes dhb[(l + 2) % 3]
-  // gradients that the weight-gradient GEMMs read on the side stream: two sets, by layer parity
-  char *ds2[2], *dz[2], *ds1[2], *dqkv[2];
-  char *ds2m[2], *ds1m[2];         // ds2 / ds1 times the dropout masks (the same buffers without dropout)
   uint64_t cur_seed;               // dropout seed of the mini-batch being worked on
   bool eval_mode;                  // inside ouro_eval_step: no dropout, no stored inputs
   size_t persist_end;              // arena[0, persist_end): weights, moments, gradient and input rings, mailboxes
-  float *attn_scratch, *dr_f32[2], *dbg_f32, *dh_f32;
+  float* dbg_f32;
   size_t dbg_floats;
   // Stored-input schedule (cfg.schedule == 1): module k < K keeps the input of its last
   // K-k+1 forward passes (token ids for k = 1, the hidden state at the boundary otherwise),
@@ -194,7 +215,6 @@ struct ouro_model {
   std::vector<std::vector<int64_t>> intags;
   std::vector<char*> mail[2];
   std::vector<int64_t> mailtag[2];
-  char* hscratch;                 // output of a recomputed module's last layer (never read)
   // iteration state
   int64_t t;
   int fwd_next, bwd_next;         // next module expected by forward (1..K+1) / backward (K..0)
@@ -202,15 +222,7 @@ struct ouro_model {
   int mem_valid;                  // valid rows in every layer memory
   const int32_t* tok;
   const int32_t* tgt;
-  // Weight-gradient GEMMs and bias column sums only feed the gradient ring, so they run on
-  // a second stream beside the error-gradient chain (both default priority); events order
-  // them against the producers of their operands and against the reuse of those buffers.
-  hipStream_t side;
-  bool use_side;
-  hipEvent_t ev_ready[4];      // ds2 / dz / ds1 / dqkv of the current layer written (main)
-  hipEvent_t ev_side_done[2];  // side work that reads buffer set p finished
-  bool side_busy[2];
-  hipEvent_t ev_join;
+  bool use_side;               // run gradient-only work beside the error-gradient chain (BwdCtx::side)
   // A third stream carries (inside ouro_step) the update of a module as soon as its backward
   // pass is done, beside the backward of the modules below.
   hipStream_t aux;
@@ -358,7 +370,6 @@ static size_t lay_out(ouro_model& m, char* base) {
   }
   m.inring.assign(K + 1, nullptr); m.instride.assign(K + 1, 0); m.indepth.assign(K + 1, 0);
   for (int p2 = 0; p2 < 2; ++p2) m.mail[p2].assign(K + 1, nullptr);
-  m.hscratch = nullptr;
   if (c.schedule == 1) {
     for (int k = 1; k < K; ++k) {
       m.indepth[k] = K - k + 1;
@@ -366,7 +377,6 @@ static size_t lay_out(ouro_model& m, char* base) {
       m.inring[k] = P(m.instride[k] * (size_t)m.indepth[k]);
       for (int p2 = 0; p2 < 2; ++p2) m.mail[p2][k] = P(N * d * es);
     }
-    m.hscratch = P(N * d * es);
   }
   m.persist_end = bp.off;
   m.L.resize(L);
@@ -407,24 +417,35 @@ static size_t lay_out(ouro_model& m, char* base) {
   m.rowloss = (float*)P(N * 4);
   m.loss = (float*)P(256);
   m.flag = (int*)P(256);
-  for (int i = 0; i < 3; ++i) m.dhb[i] = P(N * d * es);
-  m.dy[0] = P(N * d * es); m.dy[1] = P(N * d * es); m.da = P(N * hd * es);
-  for (int p2 = 0; p2 < 2; ++p2) {
-    m.ds2[p2] = P(N * d * es); m.dz[p2] = P(N * F * es);
-    m.ds1[p2] = P(N * d * es); m.dqkv[p2] = P(qkv_elems * es);
-    m.ds2m[p2] = c.dropout > 0 ? P(N * d * es) : m.ds2[p2];
-    m.ds1m[p2] = c.dropout > 0 ? P(N * d * es) : m.ds1[p2];
+  // backward scratch: one set, or one per module under the stored-input schedule
+  auto scratch = [&](BwdCtx& x) {
+    for (int i = 0; i < 3; ++i) x.dhb[i] = P(N * d * es);
+    x.dy[0] = P(N * d * es); x.dy[1] = P(N * d * es); x.da = P(N * hd * es);
+    for (int p2 = 0; p2 < 2; ++p2) {
+      x.ds2[p2] = P(N * d * es); x.dz[p2] = P(N * F * es);
+      x.ds1[p2] = P(N * d * es); x.dqkv[p2] = P(qkv_elems * es);
+      x.ds2m[p2] = c.dropout > 0 ? P(N * d * es) : x.ds2[p2];
+      x.ds1m[p2] = c.dropout > 0 ? P(N * d * es) : x.ds1[p2];
+    }
+    x.dcat = c.rel_pos ? P(B * S * d * es) : nullptr;
+    for (int p2 = 0; p2 < 2; ++p2) {
+      x.dr_t[p2] = c.rel_pos ? P(S * hd * es) : nullptr;
+      x.dr_f32[p2] = c.rel_pos ? (float*)P(S * hd * 4) : nullptr;
+    }
+    x.attn_scratch = (float*)P(attn_bwd_scratch_floats(c.batch, c.n_head, c.seq_len, (int)S, m.pdh) * 4);
+    x.dh_f32 = c.dtype == 1 ? (float*)P(N * d * 4) : nullptr;
+    x.hscratch = c.schedule == 1 ? P(N * d * es) : nullptr;
+  };
+  scratch(m);
+  if (m.ctxs.empty() && c.schedule == 1 && K > 1) {
+    BwdCtx z;
+    memset(&z, 0, sizeof z);
+    m.ctxs.assign(K, z);
   }
-  m.dcat = c.rel_pos ? P(B * S * d * es) : nullptr;
-  for (int p2 = 0; p2 < 2; ++p2) {
-    m.dr_t[p2] = c.rel_pos ? P(S * hd * es) : nullptr;
-    m.dr_f32[p2] = c.rel_pos ? (float*)P(S * hd * 4) : nullptr;
-  }
-  m.attn_scratch = (float*)P(attn_bwd_scratch_floats(c.batch, c.n_head, c.seq_len, (int)S, m.pdh) * 4);
+  for (size_t i = 1; i < m.ctxs.size(); ++i) scratch(m.ctxs[i]);
   m.dbg_floats = N * d > B * M * d ? N * d : B * M * d;
   if (m.dbg_floats < S * d) m.dbg_floats = S * d;
   m.dbg_f32 = (float*)P(m.dbg_floats * 4);
-  m.dh_f32 = c.dtype == 1 ? (float*)P(N * d * 4) : nullptr;
   return bp.off;
 }
 
@@ -499,7 +520,18 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
     if (es_ == hipSuccess) es_ = hipStreamCreateWithFlags(&m->aux, hipStreamNonBlocking);
     for (hipEvent_t* pe : {&m->ev_bwd_done, &m->ev_upd_done})
       if (es_ == hipSuccess) es_ = hipEventCreateWithFlags(pe, hipEventDisableTiming);
-    if (es_ != hipSuccess) { delete m; return fail(OURO_E_HIP, "side stream / events: %s", hipGetErrorString(es_)); }
+    m->ev_done = nullptr; m->ev_fwd = nullptr; m->cur_ctx = 0;
+    if (es_ == hipSuccess) es_ = hipEventCreateWithFlags(&m->ev_fwd, hipEventDisableTiming);
+    for (size_t i = 1; i < m->ctxs.size() && es_ == hipSuccess; ++i) {
+      BwdCtx& x = m->ctxs[i];
+      es_ = hipStreamCreateWithFlags(&x.stream, hipStreamNonBlocking);
+      if (es_ == hipSuccess) es_ = hipStreamCreateWithFlags(&x.side, hipStreamNonBlocking);
+      for (int j = 0; j < 4 && es_ == hipSuccess; ++j) es_ = hipEventCreateWithFlags(&x.ev_ready[j], hipEventDisableTiming);
+      for (int j = 0; j < 2 && es_ == hipSuccess; ++j) es_ = hipEventCreateWithFlags(&x.ev_side_done[j], hipEventDisableTiming);
+      if (es_ == hipSuccess) es_ = hipEventCreateWithFlags(&x.ev_join, hipEventDisableTiming);
+      if (es_ == hipSuccess) es_ = hipEventCreateWithFlags(&x.ev_done, hipEventDisableTiming);
+    }
+    if (es_ != hipSuccess) { ouro_destroy_model(m); return fail(OURO_E_HIP, "streams / events: %s", hipGetErrorString(es_)); }
     m->use_side = true;
   }
   // zero optimizer state, rings, everything else too (one fill over the arena)
@@ -520,8 +552,25 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
   return OURO_OK;
 }
 
+// Makes backward set i the one in use (host bookkeeping only).
+static void activate(ouro_model* m, int i) {
+  if (i == m->cur_ctx || m->ctxs.empty()) return;
+  m->ctxs[m->cur_ctx] = *static_cast<BwdCtx*>(m);
+  *static_cast<BwdCtx*>(m) = m->ctxs[i];
+  m->cur_ctx = i;
+}
+
 extern "C" int ouro_destroy_model(ouro_model* m) {
   if (!m) return OURO_OK;
+  activate(m, 0);
+  for (size_t i = 1; i < m->ctxs.size(); ++i) {
+    BwdCtx& x = m->ctxs[i];
+    if (x.stream) { (void)hipStreamSynchronize(x.stream); (void)hipStreamDestroy(x.stream); }
+    if (x.side) { (void)hipStreamSynchronize(x.side); (void)hipStreamDestroy(x.side); }
+    for (hipEvent_t e : {x.ev_ready[0], x.ev_ready[1], x.ev_ready[2], x.ev_ready[3], x.ev_side_done[0], x.ev_side_done[1], x.ev_join, x.ev_done})
+      if (e) (void)hipEventDestroy(e);
+  }
+  if (m->ev_fwd) (void)hipEventDestroy(m->ev_fwd);
   (void)hipStreamSynchronize(m->stream);
   if (m->side) { (void)hipStreamSynchronize(m->side); (void)hipStreamDestroy(m->side); }
   for (int i = 0; i < 4; ++i) if (m->ev_ready[i]) (void)hipEventDestroy(m->ev_ready[i]);
@@ -1169,6 +1218,34 @@ extern "C" int ouro_step(ouro_model* m, const int32_t* dev_tokens, const int32_t
   // So each update is enqueued on the third stream right behind that backward pass and
   // overlaps the backward passes of the modules below; the results are those of the serial
   // order, since the groups are disjoint. Per-launch timing keeps the serial order.
+  if (m->cfg.schedule == 1 && K > 1 && m->use_side && !m->timing) {
+    // Stored-input schedule: the K backward passes of an iteration are independent (each works
+    // on its own mini-batch from its own stored input and mailbox), so each runs on the streams
+    // and scratch buffers of its own set, followed there by its module's update; module 1 stays
+    // on the caller's stream.  V waits for both of its halves (modules 1 and K).
+    HIPCHK(hipEventRecord(m->ev_fwd, m->stream));
+    hipEvent_t fwd = m->ev_fwd;
+    int rc = OURO_OK;
+    for (int k = K; k >= 1 && rc == OURO_OK; --k) {
+      activate(m, k - 1);
+      if (k > 1) {
+        hipError_t e = hipStreamWaitEvent(m->stream, fwd, 0);
+        if (e != hipSuccess) { rc = fail(OURO_E_HIP, "%s", hipGetErrorString(e)); break; }
+      }
+      rc = module_backward_impl(m, k, false);
+      if (rc == OURO_OK && k > 1) {
+        rc = update_group(m, k, lr, m->stream);
+        if (rc == OURO_OK && hipEventRecord(m->ev_done, m->stream) != hipSuccess) rc = fail(OURO_E_HIP, "event record failed");
+      }
+    }
+    activate(m, 0);
+    if (rc) return rc;
+    for (size_t i = 1; i < m->ctxs.size(); ++i) HIPCHK(hipStreamWaitEvent(m->stream, m->ctxs[i].ev_done, 0));
+    RUN(update_group(m, 1, lr, m->stream));
+    RUN(update_group(m, 0, lr, m->stream));
+    if (host_loss) return read_loss(m, host_loss);
+    return OURO_OK;
+  }
   const bool early = m->use_side && !m->timing;
   for (int k = K; k >= 1; --k) {
     RUN(module_backward_impl(m, k, early && k > 1));
@@ -1450,6 +1527,11 @@ extern "C" int ouro_debug_set_overlap(ouro_model* m, int on) {
   HIPCHK(hipStreamSynchronize(m->stream));
   HIPCHK(hipStreamSynchronize(m->side));
   HIPCHK(hipStreamSynchronize(m->aux));
+  for (size_t i = 1; i < m->ctxs.size(); ++i) {
+    HIPCHK(hipStreamSynchronize(m->ctxs[i].stream));
+    HIPCHK(hipStreamSynchronize(m->ctxs[i].side));
+    m->ctxs[i].side_busy[0] = m->ctxs[i].side_busy[1] = false;
+  }
   m->side_busy[0] = m->side_busy[1] = false;
   m->use_side = on != 0;
   return OURO_OK;

@@ -253,13 +253,14 @@ def test_xl_bf16_widths_off_the_tile_grid_memory_carry():
     run_both(c, steps=4, lr=0.05, seed=43, std=0.05, perturb=0.05, tol=2e-2)
 
 
-@pytest.mark.parametrize("rel_pos,mem_len", [(0, 0), (1, 96)])
-def test_stream_overlap_matches_one_stream(rel_pos, mem_len):
-    """The three-stream schedule of step() (weight gradients and updates beside the
-    error-gradient chain) against the same steps on one stream: equal up to the order of fp32
-    atomic additions, over more iterations than the rings are deep."""
+@pytest.mark.parametrize("rel_pos,mem_len,schedule", [(0, 0, 0), (1, 96, 0), (0, 0, 1), (1, 96, 1)])
+def test_stream_overlap_matches_one_stream(rel_pos, mem_len, schedule):
+    """The multi-stream execution of step() (weight gradients and updates beside the
+    error-gradient chain; under the stored-input schedule the K backward passes side by side,
+    each on its own streams and scratch buffers) against the same steps on one stream: equal up
+    to the order of fp32 atomic additions, over more iterations than the rings are deep."""
     c = dict(n_layer=4, d_model=128, n_head=2, d_head=64, d_ff=256, vocab=512, seq_len=96, mem_len=mem_len, batch=2,
-             n_module=4, rel_pos=rel_pos, dtype=1, optimizer=0, embed_warm_mode=0)
+             n_module=4, rel_pos=rel_pos, dtype=1, optimizer=0, embed_warm_mode=0, schedule=schedule, dropout=0.1 * schedule)
     steps, lr = 7, 0.05
     blobs = S.init_params(c, seed=5, std=0.05, perturb=0.05)
     tok, tgt = S.token_batches(c["vocab"], c["batch"], c["seq_len"], steps, 1.1, 6, contiguous=bool(mem_len))
