@@ -65,7 +65,8 @@ def test_config_validation_is_host_side():
     assert P.query_arena_bytes(P.make_config(**good)) > 0
     bad = [dict(n_head=3), dict(d_model=63, n_head=1, d_head=63), dict(n_module=3), dict(n_module=0),
            dict(mem_len=4), dict(dtype=2), dict(optimizer=5), dict(layers_per_module=[2, 1]),
-           dict(layers_per_module=[2, 0]), dict(vocab=1), dict(rel_pos=2)]
+           dict(layers_per_module=[2, 0]), dict(vocab=1), dict(rel_pos=2), dict(schedule=2), dict(schedule=-1),
+           dict(dropout=1.0), dict(dropout=-0.1), dict(dropout=float("nan"))]
     for b in bad:
         kw = dict(good); kw.update(b)
         with pytest.raises(P.OuroError) as e:
@@ -75,6 +76,10 @@ def test_config_validation_is_host_side():
     a = P.query_arena_bytes(P.make_config(**good))
     b = P.query_arena_bytes(P.make_config(**dict(good, optimizer=1)))
     assert b > a
+    # the stored-input schedule keeps module inputs instead of rings of gradients: for a deep
+    # pipeline of wide layers that is the smaller arena (the point of the memory paragraph)
+    big = dict(n_layer=8, d_model=256, n_head=4, d_head=64, d_ff=1024, vocab=512, seq_len=64, batch=2, n_module=8, dtype=1, optimizer=1)
+    assert P.query_arena_bytes(P.make_config(**dict(big, schedule=1))) < P.query_arena_bytes(P.make_config(**big))
 
 
 def test_create_model_rejects_bad_arena_without_touching_it():
