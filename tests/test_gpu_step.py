@@ -448,6 +448,40 @@ def test_staleness_plumbing_bit_exact():
     m.close()
 
 
+def test_stored_input_schedule_plumbing_bit_exact():
+    """The same with schedule = 1: every gradient store has depth 1 and a gradient is applied in
+    the iteration that produced it, but only once mini-batch t-K+k exists; closed-form weights."""
+    pkg = P()
+    K, T = 4, 9
+    c = dict(n_layer=4, d_model=16, n_head=2, d_head=8, d_ff=16, vocab=32, seq_len=4, mem_len=0, batch=1,
+             n_module=K, rel_pos=0, dtype=0, optimizer=0, schedule=1)
+    m = pkg.create_model(**c)
+    for g in range(K + 1):
+        m.set_params(g, np.zeros(m.param_count(g), np.float32))
+    lr = 2.0 ** -10
+    val = lambda t, store: 1000.0 * t + (0.25 if store == 0 else 0.75 if store == K + 1 else store)
+    for t in range(T):
+        for store in range(K + 2):
+            m.inject_grad(store, np.full(m.grad_count(store), val(t, store), np.float32))
+            assert m.slot_tag(store, 0) == t
+            with pytest.raises(pkg.OuroError):
+                m.slot_tag(store, 1)
+        for g in range(K + 1):
+            m.delayed_update(g, lr)
+        for k in range(1, K + 1):
+            tau = t - K + k
+            assert m.last_read(k) == ((0, tau) if tau >= 0 else (-1, -1))
+        ti = t - K + 1
+        assert m.last_read(0) == ((0, ti) if ti >= 0 else (-1, -1))
+        assert m.last_read(K + 1) == ((0, t) if ti >= 0 else (-1, -1))
+    for k in range(1, K + 1):
+        expect = np.float32(-lr * sum(val(t, k) for t in range(T) if t - K + k >= 0))
+        assert np.all(m.get_params(k) == expect)
+    expect = np.float32(-lr * sum(0.5 * val(t, K + 1) + 0.5 * val(t, 0) for t in range(T) if t - K + 1 >= 0))
+    assert np.all(m.get_params(0) == expect)
+    m.close()
+
+
 def test_frozen_until_first_gradient_and_adam_zero_step():
     pkg = P()
     K = 3
