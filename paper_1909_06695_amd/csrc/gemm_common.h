@@ -16,6 +16,7 @@ struct GemmParams {
   float alpha;
   int kchunk;      // K range per blockIdx.z
   int tilesN;      // tiles along N (MFMA kernel)
+  int tilesM, ntiles, mfast, band;   // direct-to-LDS kernels: see tile_of_block
   int vec_epi;     // 1: C, Z, residual allow 16-byte row-chunk accesses (MFMA kernel)
   DropDesc drop;
 };

@@ -77,6 +77,38 @@ __device__ __forceinline__ bf16x8 frag_col(const char* tile, int t0, int ks, int
   return u.v;
 }
 
+// Which output tile and K range a workgroup takes.  Workgroups go to the 8 XCDs round-robin, and
+// each XCD has its own L2: the grid index is turned into (XCD, position in that XCD's share)
+// and the XCD's share is a contiguous run of work items, ordered so that the workgroups in
+// flight together share operand tiles through that L2:
+//  - with split K the K range is the slowest index, so an XCD works inside one K range (or
+//    few) instead of streaming every range at once; tiles are numbered along M first when B
+//    is the larger operand (neighbours then share the B tile), else along N;
+//  - without split K and with tilesM a multiple of 8 an XCD owns a band of tilesM/8 tile rows
+//    and walks it in groups of 8 tile columns (tilesN a multiple of 8), rows fastest: the 32 to 64 tiles in flight
+//    cover (band x 8 columns), so both operands' tiles are re-used from L2 instead of one
+//    operand being re-streamed for every tile row.
+__device__ __forceinline__ void tile_of_block(const GemmParams& p, int BM, int BN, int& m0, int& n0, int& kbeg) {
+  int bid = blockIdx.x;
+  {
+    int nb = gridDim.x, q = nb >> 3, r = nb & 7, x = bid & 7, idx = bid >> 3;
+    if (p.band) {
+      const int mb = p.tilesM >> 3, per = mb * 8;            // tile rows per XCD, tiles per full group
+      const int g = idx / per, w = idx - g * per;
+      m0 = (x * mb + w % mb) * BM;
+      n0 = (g * 8 + w / mb) * BN;
+      kbeg = 0;
+      return;
+    }
+    bid = x * q + min(x, r) + idx;
+  }
+  const int kz = bid / p.ntiles;
+  const int tile = bid - kz * p.ntiles;
+  m0 = (p.mfast ? tile % p.tilesM : tile / p.tilesN) * BM;
+  n0 = (p.mfast ? tile / p.tilesM : tile % p.tilesN) * BN;
+  kbeg = kz * p.kchunk;
+}
+
 template <int BM, int BN, int WM, int WN, bool TA, bool TB, int S>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_dlds_kernel(GemmParams p) {
   constexpr int BK = 64;
@@ -93,13 +125,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dlds_kernel(GemmParams p) {
   const bf16_t* B = reinterpret_cast<const bf16_t*>(p.B);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  int bid = blockIdx.x;
-  {
-    int nb = gridDim.x, q = nb >> 3, r = nb & 7, x = bid & 7, idx = bid >> 3;
-    bid = x * q + min(x, r) + idx;
-  }
-  const int m0 = (bid / p.tilesN) * BM, n0 = (bid % p.tilesN) * BN;
-  const int kbeg = blockIdx.z * p.kchunk;
+  int m0, n0, kbeg;
+  tile_of_block(p, BM, BN, m0, n0, kbeg);
   const int kend = min(p.K, kbeg + p.kchunk);
   const int nk = (kend - kbeg) / BK;                        // launcher guarantees exact tiles
 
@@ -216,13 +243,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_pipe_kernel(GemmParams p) {
   char* lds = reinterpret_cast<char*>(smem);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  int bid = blockIdx.x;
-  {
-    int nb = gridDim.x, q = nb >> 3, r = nb & 7, x = bid & 7, idx = bid >> 3;
-    bid = x * q + min(x, r) + idx;
-  }
-  const int m0 = (bid / p.tilesN) * BM, n0 = (bid % p.tilesN) * BN;
-  const int kbeg = blockIdx.z * p.kchunk;
+  int m0, n0, kbeg;
+  tile_of_block(p, BM, BN, m0, n0, kbeg);
   const int kend = min(p.K, kbeg + p.kchunk);
   const int nk = (kend - kbeg) / BK;
 
@@ -318,9 +340,12 @@ hipError_t launch_dlds_cfg_impl(hipStream_t s, GemmParams& p, int transA, int tr
   constexpr size_t smem_main = (size_t)S * (BM + BN) * 128;
   constexpr size_t smem_epi = (size_t)WM * WN * epilogue_stage_floats<BN / WN / 32>() * sizeof(float);
   constexpr size_t smem = smem_main > smem_epi ? smem_main : smem_epi;
-  int tilesM = (p.M + BM - 1) / BM;
+  p.tilesM = (p.M + BM - 1) / BM;
   p.tilesN = (p.N + BN - 1) / BN;
-  dim3 grid(tilesM * p.tilesN, 1, splits), block(WM * WN * 64);
+  p.ntiles = p.tilesM * p.tilesN;
+  p.mfast = splits > 1 && p.N > p.M;
+  p.band = splits == 1 && p.tilesM % 8 == 0 && p.tilesN % 8 == 0 && p.tilesN > 8;
+  dim3 grid(p.ntiles * splits), block(WM * WN * 64);
 #define OURO_LAUNCH(TA_, TB_)                                                                    \
   do {                                                                                           \
     static bool attr_done = false;                                                               \
