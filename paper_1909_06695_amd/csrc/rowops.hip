@@ -583,12 +583,110 @@ __global__ __launch_bounds__(256) void ce_rows_kernel(const T* __restrict__ logi
   }
 }
 
+// The same for bf16 rows of up to NP * NT * 8 elements, 16-byte aligned: the row stays in
+// registers (NP packs per thread, NT threads) between the passes, so the logits are read once.
+template <int NP, int NT>
+__global__ __launch_bounds__(NT) void ce_rows_cached_kernel(const bf16_t* __restrict__ logits, int ld,
+                                                             const int32_t* __restrict__ tgt, bf16_t* __restrict__ G, int ldg,
+                                                             float* __restrict__ lse_out, float* __restrict__ rowloss,
+                                                             int N, int vocab, int* flag) {
+  constexpr int NWV = NT / 64;
+  __shared__ float sm_m[NWV], sm_s[NWV];
+  const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bf16_t* row = logits + (size_t)n * ld;
+  bf16_t* grow = G + (size_t)n * ldg;
+  const int t = tgt[n];
+  const bool ok = t >= 0 && t < vocab;
+  const float tl = ok ? to_f32(row[t]) : 0.f;
+  const int nvec = vocab / 8;
+  uint4 buf[NP];
+#pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    const int vi = tid + NT * i;
+    buf[i] = vi < nvec ? *reinterpret_cast<const uint4*>(row + vi * 8) : make_uint4(0, 0, 0, 0);
+  }
+  auto unpack = [](const uint4& q, float* out) __attribute__((always_inline)) {
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      out[2 * k] = __uint_as_float(w[k] << 16);
+      out[2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u);
+    }
+  };
+  // per-thread maximum first, then one exponential per element (no rescaling chain)
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NP; ++i)
+    if (tid + NT * i < nvec) {
+      float v[8];
+      unpack(buf[i], v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) m = fmaxf(m, v[e]);
+    }
+  for (int c = nvec * 8 + tid; c < vocab; c += NT) m = fmaxf(m, to_f32(row[c]));
+  const float wm = wave_max(m);
+  if (lane == 0) sm_m[wave] = wm;
+  __syncthreads();
+  float bm = sm_m[0];
+#pragma unroll
+  for (int w = 1; w < NWV; ++w) bm = fmaxf(bm, sm_m[w]);
+  float ssum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NP; ++i)
+    if (tid + NT * i < nvec) {
+      float v[8];
+      unpack(buf[i], v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ssum += __expf(v[e] - bm);
+    }
+  for (int c = nvec * 8 + tid; c < vocab; c += NT) ssum += __expf(to_f32(row[c]) - bm);
+  ssum = wave_sum(ssum);
+  if (lane == 0) sm_s[wave] = ssum;
+  __syncthreads();
+  float bs = 0.f;
+#pragma unroll
+  for (int w = 0; w < NWV; ++w) bs += sm_s[w];
+  const float lse = bm + logf(bs);
+  if (tid == 0) {
+    lse_out[n] = lse;
+    rowloss[n] = ok ? lse - tl : 0.f;
+    if (!ok) atomicOr(flag, 2);
+  }
+  const float invN = 1.f / N;
+  // the scalar tail is read before anything of this row is overwritten by this thread only
+  for (int c = nvec * 8 + tid; c < vocab; c += NT) {
+    float gval = __expf(to_f32(row[c]) - lse);
+    if (ok && c == t) gval -= 1.f;
+    grow[c] = from_f32<bf16_t>(gval * invN);
+  }
+#pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    const int vi = tid + NT * i;
+    if (vi < nvec) {
+      float v[8];
+      unpack(buf[i], v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float gval = __expf(v[e] - lse);
+        if (ok && vi * 8 + e == t) gval -= 1.f;
+        v[e] = gval * invN;
+      }
+      store_pack<bf16_t>(grow + vi * 8, v);
+    }
+  }
+}
+
 hipError_t launch_ce_rows(hipStream_t s, int dtype, const void* logits, int ld, const int32_t* tgt,
                           void* G, int ldg, float* lse, float* rowloss, int N, int vocab, int* flag) {
   dim3 grid(N), block(256);
   const int pack = dtype == 1 ? 8 : 4;
   const bool vec = ld % pack == 0 && ldg % pack == 0 && ptr16(logits) && ptr16(G);
-  if (dtype == 1) {
+  if (dtype == 1 && vec && vocab <= 16 * 512 * 8) {
+    if (vocab <= 16 * 256 * 8)
+      hipLaunchKernelGGL((ce_rows_cached_kernel<16, 256>), grid, block, 0, s, (const bf16_t*)logits, ld, tgt, (bf16_t*)G, ldg, lse, rowloss, N, vocab, flag);
+    else
+      hipLaunchKernelGGL((ce_rows_cached_kernel<16, 512>), grid, dim3(512), 0, s, (const bf16_t*)logits, ld, tgt, (bf16_t*)G, ldg, lse, rowloss, N, vocab, flag);
+  } else if (dtype == 1) {
     if (vec) hipLaunchKernelGGL((ce_rows_kernel<bf16_t, true>), grid, block, 0, s, (const bf16_t*)logits, ld, tgt, (bf16_t*)G, ldg, lse, rowloss, N, vocab, flag);
     else hipLaunchKernelGGL((ce_rows_kernel<bf16_t, false>), grid, block, 0, s, (const bf16_t*)logits, ld, tgt, (bf16_t*)G, ldg, lse, rowloss, N, vocab, flag);
   } else {

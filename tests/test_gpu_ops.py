@@ -351,7 +351,7 @@ def test_embedding_gather_scatter(dtype):
 
 
 @pytest.mark.parametrize("dtype", [0, 1])
-@pytest.mark.parametrize("N,vocab", [(12, 256), (7, 1000), (5, 50257)])
+@pytest.mark.parametrize("N,vocab", [(12, 256), (7, 1000), (5, 50257), (4, 32768), (3, 65536), (3, 65537), (6, 2056)])
 def test_softmax_cross_entropy(dtype, N, vocab):
     rng = np.random.default_rng(N + vocab)
     logits = (rng.standard_normal((N, vocab)) * 3).astype(np.float32)
