@@ -158,6 +158,11 @@ hipError_t launch_embed_fwd(hipStream_t s, int dtype, const int32_t* tok, const 
 // dVi[tok[n],:] += scale * dh[n,:]   (fp32 atomics; caller zeroes dVi)
 hipError_t launch_embed_bwd(hipStream_t s, int dtype, const int32_t* tok, const void* dh, float* dVi,
                             int N, int d, int vocab, float scale, const DropDesc* drop = nullptr);
+// One matrix of a parameter blob to be kept transposed as well: bf16 [rows, cols] at element offset
+// off of src -> [cols, rows] with leading dimension ld_out at the same offset of dst.  tile0 is the
+// running count of 64x64 tiles before this matrix (the launch covers all matrices of a table).
+struct TransposeEntry { unsigned long long off; int rows, cols, ld_out, tile0; };
+hipError_t launch_transpose_table(hipStream_t s, const void* src, void* dst, const TransposeEntry* dev_tab, int entries, int tiles);
 // dst[r, c] = src[r, c] * mask(r*drop.ld + c) over rows x cols elements, both with row stride ld
 hipError_t launch_dropout_apply(hipStream_t s, int dtype, const void* src, void* dst, int rows, int cols, int ld,
                                 const DropDesc& drop);

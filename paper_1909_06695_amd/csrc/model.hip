@@ -185,6 +185,15 @@ struct ouro_model : BwdCtx {
   std::vector<int64_t> count;
   std::vector<float*> master, adam_m, adam_v;
   std::vector<bf16_t*> shadow;
+  // bf16 mode: every weight matrix also transposed ([out, in]), at the same offsets, refreshed after
+  // each update: y = x W then contracts two operands that are both contiguous along the
+  // contraction index, the fastest form of the contraction kernels (the input-gradient
+  // contractions already have it with W itself).  V^T (leading dimension = padded vocabulary)
+  // serves dh_L = G V.
+  std::vector<bf16_t*> shadowT;
+  std::vector<std::vector<TransposeEntry>> ttab;
+  std::vector<TransposeEntry*> ttab_dev;
+  std::vector<int> ttiles;
   // gradient stores 0..K+1
   std::vector<int64_t> gcount, gstride, depth;   // elements per gradient (caller's), slot stride (stored, 256-byte multiple)
   std::vector<float*> ring;
@@ -242,6 +251,7 @@ struct ouro_model : BwdCtx {
   }
   const float* wF(int layer, size_t off) const { return master[layer_mod[layer]] + off; }
   const char* vT() const { return cfg.dtype == 1 ? (const char*)shadow[0] : (const char*)master[0]; }
+  const char* wTt(int layer, size_t off) const { return (const char*)(shadowT[layer_mod[layer]] + off); }   // bf16 mode only
   float* slot_ptr(int id, int64_t slot) const { return ring[id] + (size_t)slot * gstride[id]; }
 };
 
@@ -356,6 +366,28 @@ static size_t lay_out(ouro_model& m, char* base) {
     if (c.optimizer == 1) {
       m.adam_m[k] = (float*)P(m.pcount[k] * 4);
       m.adam_v[k] = (float*)P(m.pcount[k] * 4);
+    }
+  }
+  m.shadowT.assign(K + 1, nullptr); m.ttab.assign(K + 1, {}); m.ttab_dev.assign(K + 1, nullptr); m.ttiles.assign(K + 1, 0);
+  if (c.dtype == 1) {
+    auto add = [&](int k, size_t off, size_t rows, size_t cols, size_t ld_out) {
+      TransposeEntry t{(unsigned long long)off, (int)rows, (int)cols, (int)ld_out, m.ttiles[k]};
+      m.ttab[k].push_back(t);
+      m.ttiles[k] += (int)(((rows + 63) / 64) * ((cols + 63) / 64));
+    };
+    add(0, 0, V, d, vpad);
+    for (int li = 0; li < L; ++li) {
+      const int k = m.layer_mod[li];
+      const LayerOff& o = m.loff[li];
+      add(k, o.W_qkv, d, 3 * hd, d);
+      add(k, o.W_o, hd, d, hd);
+      if (c.rel_pos) add(k, o.W_r, d, hd, d);
+      add(k, o.W_1, d, F, d);
+      add(k, o.W_2, F, d, F);
+    }
+    for (int k = 0; k <= K; ++k) {
+      m.shadowT[k] = (bf16_t*)P((k == 0 ? vpad * d : (size_t)m.pcount[k]) * 2);
+      m.ttab_dev[k] = (TransposeEntry*)P(m.ttab[k].size() * sizeof(TransposeEntry));
     }
   }
   m.gcount.assign(K + 2, 0); m.gstride.assign(K + 2, 0); m.depth.assign(K + 2, 0); m.ring.assign(K + 2, nullptr);
@@ -537,6 +569,10 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
   // zero optimizer state, rings, everything else too (one fill over the arena)
   hipError_t e = launch_fill_zero(m->stream, m->arena, need);
   if (e != hipSuccess) { delete m; return fail(OURO_E_HIP, "arena clear: %s", hipGetErrorString(e)); }
+  for (int k = 0; k <= K && e == hipSuccess; ++k)
+    if (m->ttab_dev[k])
+      e = hipMemcpyAsync(m->ttab_dev[k], m->ttab[k].data(), m->ttab[k].size() * sizeof(TransposeEntry), hipMemcpyHostToDevice, m->stream);
+  if (e != hipSuccess) { delete m; return fail(OURO_E_HIP, "table upload: %s", hipGetErrorString(e)); }
   std::vector<float> tab;
   if (!cfg->rel_pos) {
     host_sinusoid(tab, cfg->seq_len, cfg->d_model, m->pd);
@@ -590,6 +626,13 @@ extern "C" int ouro_param_count(const ouro_model* m, int group, int64_t* n) {
   return OURO_OK;
 }
 
+// bf16 mode: the transposed copies of a group's weight matrices follow its bf16 copy
+static int refresh_transposed(ouro_model* m, int group, hipStream_t st) {
+  if (m->cfg.dtype != 1) return OURO_OK;
+  HIPCHK(launch_transpose_table(st, m->shadow[group], m->shadowT[group], m->ttab_dev[group], (int)m->ttab[group].size(), m->ttiles[group]));
+  return OURO_OK;
+}
+
 extern "C" int ouro_set_params(ouro_model* m, int group, const float* src, int64_t n, int src_is_device) {
   if (!m || !src || group < 0 || group > m->cfg.n_module) return fail(OURO_E_ARG, "set_params: bad argument");
   if (n != m->count[group]) return fail(OURO_E_ARG, "set_params: group %d has %lld elements, got %lld", group, (long long)m->count[group], (long long)n);
@@ -605,11 +648,13 @@ extern "C" int ouro_set_params(ouro_model* m, int group, const float* src, int64
     remap_group(m, group, stored.data(), const_cast<float*>(hsrc), true);
     HIPCHK(hipMemcpyAsync(m->master[group], stored.data(), stored.size() * 4, hipMemcpyHostToDevice, m->stream));
     HIPCHK(launch_convert(m->stream, 1, m->shadow[group], m->master[group], stored.size()));
+    if (int rc = refresh_transposed(m, group, m->stream)) return rc;
     HIPCHK(hipStreamSynchronize(m->stream));
     return OURO_OK;
   }
   HIPCHK(hipMemcpyAsync(m->master[group], src, (size_t)n * 4, src_is_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, m->stream));
   if (m->cfg.dtype == 1) HIPCHK(launch_convert(m->stream, 1, m->shadow[group], m->master[group], (size_t)n));
+  if (int rc = refresh_transposed(m, group, m->stream)) return rc;
   if (!src_is_device) HIPCHK(hipStreamSynchronize(m->stream));
   return OURO_OK;
 }
@@ -717,6 +762,7 @@ static int layer_forward(ouro_model* m, int l, char* out_override = nullptr) {
   const int N = m->N, T = c.seq_len, B = c.batch, es = m->esz;
   const LayerOff& o = m->loff[l];
   LayerBuf& b = m->L[l];
+  const bool bt = c.dtype == 1;               // weights are at hand transposed: both operands contraction-contiguous
   char* out = out_override ? out_override : (l + 1 < c.n_layer) ? m->L[l + 1].x : m->hL;
   const int Mv = m->mem_valid, S = Mv + T;
   AttnDesc a;
@@ -725,7 +771,8 @@ static int layer_forward(ouro_model* m, int l, char* out_override = nullptr) {
   a.scale = 1.f / std::sqrt((float)c.d_head);
   a.o = b.a; a.ldo = hd; a.lse = b.lse;
   if (!c.rel_pos) {
-    RUN(run_gemm(m, gd(b.x, d, 0, m->wT(l, o.W_qkv), 3 * hd, 0, b.qkv, 3 * hd, N, 3 * hd, d)));
+    if (bt) RUN(run_gemm(m, gd(b.x, d, 0, m->wTt(l, o.W_qkv), d, 1, b.qkv, 3 * hd, N, 3 * hd, d)));
+    else RUN(run_gemm(m, gd(b.x, d, 0, m->wT(l, o.W_qkv), 3 * hd, 0, b.qkv, 3 * hd, N, 3 * hd, d)));
     a.q = b.qkv; a.ldq = 3 * hd;
     a.k = b.qkv + (size_t)hd * es; a.ldk = 3 * hd;
     a.v = b.qkv + (size_t)2 * hd * es; a.ldv = 3 * hd;
@@ -738,9 +785,16 @@ static int layer_forward(ouro_model* m, int l, char* out_override = nullptr) {
     }
     char* q = b.qkv;
     char* kv = b.qkv + (size_t)N * hd * es;
-    RUN(run_gemm(m, gd(b.x, d, 0, m->wT(l, o.W_qkv), 3 * hd, 0, q, hd, N, hd, d)));
-    RUN(run_gemm(m, gd(cat, d, 0, m->wT(l, o.W_qkv) + (size_t)hd * es, 3 * hd, 0, kv, 2 * hd, B * S, 2 * hd, d)));
-    RUN(run_gemm(m, gd(m->rtab, d, 0, m->wT(l, o.W_r), hd, 0, b.r, hd, S, hd, d)));
+    if (bt) {
+      // rows 0..hd-1 of W_qkv^T are the query projection, the rest the key / value projections
+      RUN(run_gemm(m, gd(b.x, d, 0, m->wTt(l, o.W_qkv), d, 1, q, hd, N, hd, d)));
+      RUN(run_gemm(m, gd(cat, d, 0, m->wTt(l, o.W_qkv) + (size_t)hd * d * es, d, 1, kv, 2 * hd, B * S, 2 * hd, d)));
+      RUN(run_gemm(m, gd(m->rtab, d, 0, m->wTt(l, o.W_r), d, 1, b.r, hd, S, hd, d)));
+    } else {
+      RUN(run_gemm(m, gd(b.x, d, 0, m->wT(l, o.W_qkv), 3 * hd, 0, q, hd, N, hd, d)));
+      RUN(run_gemm(m, gd(cat, d, 0, m->wT(l, o.W_qkv) + (size_t)hd * es, 3 * hd, 0, kv, 2 * hd, B * S, 2 * hd, d)));
+      RUN(run_gemm(m, gd(m->rtab, d, 0, m->wT(l, o.W_r), hd, 0, b.r, hd, S, hd, d)));
+    }
     a.q = q; a.ldq = hd;
     a.k = kv; a.ldk = 2 * hd;
     a.v = kv + (size_t)hd * es; a.ldv = 2 * hd;
@@ -748,18 +802,18 @@ static int layer_forward(ouro_model* m, int l, char* out_override = nullptr) {
   }
   HIPCHK(launch_attn_fwd(m->stream, c.dtype, a, 0));
   {
-    GemmDesc g = gd(b.a, hd, 0, m->wT(l, o.W_o), d, 0, b.s1, d, N, d, hd);
+    GemmDesc g = bt ? gd(b.a, hd, 0, m->wTt(l, o.W_o), hd, 1, b.s1, d, N, d, hd) : gd(b.a, hd, 0, m->wT(l, o.W_o), d, 0, b.s1, d, N, d, hd);
     g.residual = b.x; g.ldr = d; g.drop = drop_at(m, 2 * l + 1);
     RUN(run_gemm(m, g));
   }
   HIPCHK(launch_layernorm_fwd(m->stream, c.dtype, b.s1, m->wF(l, o.ln1_g), m->wF(l, o.ln1_b), b.y, b.mean1, b.rstd1, N, d, dn));
   {
-    GemmDesc g = gd(b.y, d, 0, m->wT(l, o.W_1), F, 0, b.uact, F, N, F, d);
+    GemmDesc g = bt ? gd(b.y, d, 0, m->wTt(l, o.W_1), d, 1, b.uact, F, N, F, d) : gd(b.y, d, 0, m->wT(l, o.W_1), F, 0, b.uact, F, N, F, d);
     g.bias = m->wF(l, o.b_1); g.epilogue = EPI_GELU; g.Z = b.z; g.ldz = F;
     RUN(run_gemm(m, g));
   }
   {
-    GemmDesc g = gd(b.uact, F, 0, m->wT(l, o.W_2), d, 0, b.s2, d, N, d, F);
+    GemmDesc g = bt ? gd(b.uact, F, 0, m->wTt(l, o.W_2), F, 1, b.s2, d, N, d, F) : gd(b.uact, F, 0, m->wT(l, o.W_2), d, 0, b.s2, d, N, d, F);
     g.bias = m->wF(l, o.b_2); g.residual = b.y; g.ldr = d; g.drop = drop_at(m, 2 * l + 2);
     RUN(run_gemm(m, g));
   }
@@ -1039,7 +1093,8 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
       RUN(run_gemm(m, g));
     }
     m->tags[K + 1][0] = m->t;
-    GemmDesc gh = gd(m->G, m->ldv, 0, m->vT(), d, 0, dh_top, d, N, d, Vx);
+    GemmDesc gh = c.dtype == 1 ? gd(m->G, m->ldv, 0, (const char*)m->shadowT[0], m->ldv, 1, dh_top, d, N, d, Vx)
+                               : gd(m->G, m->ldv, 0, m->vT(), d, 0, dh_top, d, N, d, Vx);
     if (c.dtype == 1 && gemm_uses_mfma(c.dtype, gh) && V >= 8192) {
       // The contraction runs over the whole vocabulary onto a narrow output: split it over
       // the grid (two workgroups per CU instead of one), adding into an fp32 buffer that is
@@ -1171,6 +1226,7 @@ static int update_group(ouro_model* m, int group, float lr, hipStream_t st) {
     double per = 4.0 * ((u.g0 ? 1 : 0) + (u.g1 ? 1 : 0)) + 8.0 + (u.adam ? 16.0 : 0.0) + (u.shadow ? 2.0 : 0.0);
     RUN(timing_end(m, 1, per * (double)u.n, st));
   }
+  RUN(refresh_transposed(m, group, st));
   m->upd_mask |= 1ull << group;
   if (m->upd_mask == (1ull << (K + 1)) - 1) {
     if (m->upd_pending) {       // the next iteration reads every weight: main waits for aux

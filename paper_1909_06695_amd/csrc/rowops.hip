@@ -497,6 +497,35 @@ hipError_t launch_embed_fwd(hipStream_t s, int dtype, const int32_t* tok, const 
   return hipGetLastError();
 }
 
+__global__ __launch_bounds__(256) void transpose_table_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
+                                                              const TransposeEntry* __restrict__ tab, int entries) {
+  __shared__ bf16_t tile[64][66];
+  int e = 0;
+  while (e + 1 < entries && tab[e + 1].tile0 <= (int)blockIdx.x) ++e;
+  const TransposeEntry t = tab[e];
+  const int tiles_c = (t.cols + 63) / 64;
+  const int local = blockIdx.x - t.tile0;
+  const int r0 = (local / tiles_c) * 64, c0 = (local % tiles_c) * 64;
+  const bf16_t* a = src + t.off;
+  bf16_t* b = dst + t.off;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4) {
+    const int r = r0 + i, c = c0 + tx;
+    if (r < t.rows && c < t.cols) tile[i][tx] = a[(size_t)r * t.cols + c];
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    const int c = c0 + i, r = r0 + tx;
+    if (r < t.rows && c < t.cols) b[(size_t)c * t.ld_out + r] = tile[tx][i];
+  }
+}
+
+hipError_t launch_transpose_table(hipStream_t s, const void* src, void* dst, const TransposeEntry* dev_tab, int entries, int tiles) {
+  if (entries <= 0 || tiles <= 0) return hipSuccess;
+  hipLaunchKernelGGL(transpose_table_kernel, dim3(tiles), dim3(256), 0, s, (const bf16_t*)src, (bf16_t*)dst, dev_tab, entries);
+  return hipGetLastError();
+}
+
 hipError_t launch_dropout_apply(hipStream_t s, int dtype, const void* src, void* dst, int rows, int cols, int ld,
                                 const DropDesc& drop) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
