@@ -499,7 +499,7 @@ hipError_t launch_embed_fwd(hipStream_t s, int dtype, const int32_t* tok, const 
 
 __global__ __launch_bounds__(256) void transpose_table_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
                                                               const TransposeEntry* __restrict__ tab, int entries) {
-  __shared__ bf16_t tile[64][66];
+  __shared__ bf16_t tile[64][72];              // row stride 144 bytes: 16-byte aligned rows
   int e = 0;
   while (e + 1 < entries && tab[e + 1].tile0 <= (int)blockIdx.x) ++e;
   const TransposeEntry t = tab[e];
@@ -508,6 +508,26 @@ __global__ __launch_bounds__(256) void transpose_table_kernel(const bf16_t* __re
   const int r0 = (local / tiles_c) * 64, c0 = (local % tiles_c) * 64;
   const bf16_t* a = src + t.off;
   bf16_t* b = dst + t.off;
+  // 16-byte path: whole tile inside the matrix, rows of both layouts 16-byte aligned
+  const bool vec = r0 + 64 <= t.rows && c0 + 64 <= t.cols && !(t.cols & 7) && !(t.ld_out & 7) && !(t.off & 7);
+  if (vec) {
+    const int q = threadIdx.x & 7, rr = threadIdx.x >> 3;          // 8 threads per 64-element row, 32 rows per pass
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      const int r = rr + 32 * pass;
+      *reinterpret_cast<uint4*>(&tile[r][q * 8]) = *reinterpret_cast<const uint4*>(a + (size_t)(r0 + r) * t.cols + c0 + q * 8);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      const int c = rr + 32 * pass;                                 // output row = input column
+      union { bf16_t h[8]; uint4 v; } u;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) u.h[i] = tile[q * 8 + i][c];
+      *reinterpret_cast<uint4*>(b + (size_t)(c0 + c) * t.ld_out + r0 + q * 8) = u.v;
+    }
+    return;
+  }
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   for (int i = ty; i < 64; i += 4) {
     const int r = r0 + i, c = c0 + tx;
