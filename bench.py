@@ -67,6 +67,8 @@ def main():
     ap.add_argument("--schedule", type=int, default=0, choices=[0, 1],
                     help="0: gradient rings, Eq. 8 to the letter (the headline workload); 1: stored module inputs "
                          "and recomputation (the paper's memory-saving schedule; one more forward pass per module below K)")
+    ap.add_argument("--dropout", type=float, default=0.0,
+                    help="repeatable dropout rate (0 in the headline workload)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the K modules back to back on ONE GPU; --gpus N with N > 1 is not "
@@ -81,6 +83,7 @@ def main():
 
     c = dict(S.CONFIGS[args.config])
     c["schedule"] = args.schedule
+    c["dropout"] = args.dropout
     K = c["n_module"]
     nsteps_total = args.warmup + 2 * args.steps
     blobs = S.init_params(c, seed=0)
@@ -182,6 +185,7 @@ def main():
         "step_tflop": round(F / 1e12, 3),
         "streams": "serial" if args.serial else "overlapped",
         "schedule": "stored inputs + recompute" if args.schedule else "gradient rings (Eq. 8)",
+        "dropout": args.dropout,
         "loss_first_timed": loss, "loss_last": loss_end,
         "roofline": roofline, "update_kernel": update, "cpu_baseline": cpu,
     }
