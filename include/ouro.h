@@ -15,7 +15,18 @@
  *     calling thread.
  *   - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
  *   - The caller owns the device arena and the HIP stream.  The library carves the
- *     arena, allocates no device memory itself, and enqueues all work on that stream.
+ *     arena and allocates no device memory itself.  ouro_create_model also creates
+ *     internal non-blocking streams and events of default priority (two streams per
+ *     model, plus two per module above the first under schedule = 1) for work that may
+ *     run beside the caller's stream.  Ordering contract: every call first orders its
+ *     work after whatever the caller's stream holds at entry; ouro_step, ouro_eval_step
+ *     and the last ouro_delayed_update of an iteration join all internal streams back
+ *     into the caller's stream before they return, and so does every module-level call
+ *     for what a later call or a read through this interface depends on.  Work the
+ *     caller enqueues on the caller's stream after such a call therefore sees its
+ *     results; between the module-level calls of one iteration the arena is in use by
+ *     internal streams and must only be touched through this interface.  The caller's
+ *     own other streams are not ordered against the arena.
  *     Calls return after enqueueing unless stated otherwise.
  *   - A model object is not thread-safe; use one thread per model.
  *   - Only gfx950 code is built; there is no host fallback: without a usable GPU,
@@ -46,8 +57,8 @@ typedef struct ouro_model ouro_model; /* opaque host object */
 
 /* Model and method configuration.  Layer internals (not defined by the paper):
  * post-LayerNorm blocks y = LN(h + Attn(h)), h' = LN(y + FFN(y)); attention
- * projections without bias; FFN = GELU(y W_1 + b_1) W_2 + b_2 with the exact (erf)
- * GELU; scores scaled by 1/sqrt(d_head), causal; LayerNorm eps 1e-5; LM head
+ * projections without bias; FFN = GELU(y W_1 + b_1) W_2 + b_2 with the erf-form
+ * GELU x*Phi(x), erf evaluated to 1.5e-7 absolute (a rational approximation) in both dtypes; scores scaled by 1/sqrt(d_head), causal; LayerNorm eps 1e-5; LM head
  * logits = h_L V^T without bias; loss = mean over batch*seq_len targets of the
  * natural-log cross entropy (Eq. 4). */
 typedef struct {
@@ -70,14 +81,14 @@ typedef struct {
   float emb_scale;   /* factor on the embedding lookup (1.0)                                */
   int32_t schedule;  /* 0: Eq. 8 to the letter: the gradient of mini-batch t-K+k at the full
                            weights of iteration t-K+k, kept in a ring of gradients;
-                        1: the memory-saving schedule of Section 3.2 ("Memory Consumption"):
+                        1: the memory-saving schedule of Section 3.1 ("Memory Consumption"):
                            each module keeps its inputs instead, recomputes its activations
                            of mini-batch t-K+k with the weights it holds at iteration t and
                            back-propagates the error gradient its upper neighbour produced
                            at iteration t-1; segment memories are stored with the inputs     */
   float dropout;     /* p in [0, 1): inverted dropout on the embedding sum and on the outputs of
                         the attention projection and of the feed-forward block, before the
-                        residual additions (0 = none).  Section 4.1, "Repeatable Dropout": the
+                        residual additions (0 = none).  Section 5.2, "Repeatable Dropout": the
                         mask is a pure function of (seed + iteration of the mini-batch, place,
                         element), so a recomputation reproduces it                          */
   uint64_t seed;     /* dropout seed of iteration 0; iteration t uses seed + t               */
@@ -185,7 +196,7 @@ int64_t ouro_current_step(const ouro_model* m);
 int ouro_slot_index(int K, int id, int64_t t, int write, int64_t* slot, int64_t* tau);
 int ouro_ring_depth(int K, int id, int64_t* depth);
 
-/* --- step size (Section 4.1: gradual warm-up, then a cosine schedule); pure host function ---
+/* --- step size (Section 5.2: gradual warm-up, then a cosine schedule); pure host function ---
  * *lr = gamma_t for iteration t >= 0: base*(t+1)/warmup while t < warmup; then
  * floor + (base-floor)*(1+cos(pi*(t-warmup)/(total-warmup)))/2 until t = total; floor from
  * there on.  Requires 0 <= warmup < total (warmup = 0: no warm-up) and 0 <= floor <= base;

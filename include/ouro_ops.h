@@ -51,7 +51,7 @@ int ouro_op_attention_bwd(void* stream, int dtype, int B, int H, int T, int S, i
                           int ldr, float* du, float* dvb, float* dr, float* scratch, int force_generic);
 size_t ouro_op_attention_bwd_scratch(int B, int H, int T, int S, int dh);
 
-/* Repeatable dropout (Section 4.1): dst[r,c] = src[r,c] * f(r*drop_ld + c), f(i) = 1/(1-p) if the high
+/* Repeatable dropout (Section 5.2): dst[r,c] = src[r,c] * f(r*drop_ld + c), f(i) = 1/(1-p) if the high
  * 32 bits of output i + stream_id*2^40 + 1 of the SplitMix64 sequence started at `seed` are >=
  * floor(p*2^32), else 0.  rows x cols elements of type T, row stride ld on both sides; 0 <= p < 1. */
 int ouro_op_dropout(void* stream, int dtype, const void* src, void* dst, int rows, int cols, int ld,

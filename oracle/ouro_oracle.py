@@ -17,7 +17,7 @@ What it computes, with the passage of the paper each part follows:
     (Eq. 9; `embed_warm_mode=1` is the term-wise reading where only the V_i term is
     dropped during those steps).
   * The step size follows a linear warm-up and then a cosine decay (`learning_rate`,
-    Section 4.1).
+    Section 5.2).
   * SGD (Algorithm 1) or Adam (Algorithm 2, appendix): every group steps at every t,
     also with a zero gradient; bias correction uses the global t+1; epsilon is added
     outside the square root after bias correction.
@@ -30,8 +30,8 @@ independent autograd model in tests/, not by the paper: "parity unpinned" agains
 paper for the layer internals and for whole-trajectory loss values (the paper prints
 none).
 
-`RecomputeOracle` is the memory-saving schedule of Section 3.2 ("Memory Consumption") and
-Section 4.1 ("Repeatable Dropout"): every module stores only its input of each iteration,
+`RecomputeOracle` is the memory-saving schedule of Section 3.1 ("Memory Consumption") and
+Section 5.2 ("Repeatable Dropout"): every module stores only its input of each iteration,
 re-runs its forward pass on the input of mini-batch t-K+k with the weights it holds now, and
 back-propagates the error gradient the module above produced one iteration earlier.
 
@@ -65,8 +65,7 @@ class Config:
         self.optimizer, self.beta1, self.beta2, self.eps = optimizer, beta1, beta2, eps
         self.embed_warm_mode, self.emb_scale = embed_warm_mode, emb_scale
         assert 0.0 <= dropout < 1.0
-        # the rate is a single-precision number at the boundary; the keep threshold is derived from it
-        self.dropout, self.seed = float(np.float32(dropout)), int(seed)
+        self.dropout, self.seed = float(dropout), int(seed)
         if layers_per_module is None:
             layers_per_module = split_layers(n_layer, n_module)
         assert len(layers_per_module) == n_module and sum(layers_per_module) == n_layer
@@ -285,7 +284,7 @@ def random_u32(seed, stream, idx):
 
 
 def dropout_mask(cfg, seed, stream, shape):
-    """Inverted dropout (Srivastava et al. 2014, cited in Section 4.1): element i (row-major
+    """Inverted dropout (Srivastava et al. 2014, cited in Section 5.2): element i (row-major
     index) is kept iff its 32 random bits are >= floor(p * 2^32); kept elements are scaled
     by 1/(1-p).  The mask is a pure function of (seed, stream, i): "repeatable"."""
     n = int(np.prod(shape))
@@ -306,7 +305,7 @@ def layer_stream(l, site):
 # ------------------------------------------------------------------------------- layer
 def layer_fwd(cfg, p, x, mem, drop=None):
     """drop = (seed, layer index) switches dropout on at the two sublayer outputs, before the
-    residual additions (the paper names dropout, Section 4.1, not its places: a reading)."""
+    residual additions (the paper names dropout, Section 5.2, not its places: a reading)."""
     o, ca = attention_fwd(cfg, p, x, mem)
     m1 = m2 = None
     if drop is not None and cfg.dropout > 0:
@@ -410,7 +409,7 @@ def full_gradient(cfg, layers, V, tokens, targets, mems=None, seed=None):
 
 # -------------------------------------------------------------------------- step size
 def learning_rate(t, base, warmup, total, floor=0.0):
-    """Step size gamma_t of iteration t = 0, 1, ... (Section 4.1, "Warm-up Training" and
+    """Step size gamma_t of iteration t = 0, 1, ... (Section 5.2, "Warm-up Training" and
     the cosine schedule named beside the optimiser settings).
 
     Reading (the paper gives the two phases and the warm-up length, not the formula):
@@ -449,7 +448,7 @@ class Oracle:
             self.mV, self.vV = np.zeros_like(self.V), np.zeros_like(self.V)
 
     def seed_of(self, t):
-        """Dropout seed of mini-batch t (stored with the module inputs, Section 4.1
+        """Dropout seed of mini-batch t (stored with the module inputs, Section 5.2
         "Repeatable Dropout"): the configured seed plus t; None when dropout is off."""
         return (self.cfg.seed + t) & MASK64 if self.cfg.dropout > 0 else None
 
@@ -579,7 +578,7 @@ def module_bwd(cfg, layers_k, caches, dh):
 
 
 class RecomputeOracle(Oracle):
-    """The schedule the paper runs on its GPUs (Section 3.2, "Memory Consumption"): module k
+    """The schedule the paper runs on its GPUs (Section 3.1, "Memory Consumption"): module k
     stores its input of every iteration instead of a gradient.  At iteration t it
 
       * runs the forward pass of mini-batch t on the current weights (all modules in
@@ -603,7 +602,7 @@ class RecomputeOracle(Oracle):
     mini-batch t-K+k (zeros while that is negative), dV_i that of mini-batch t-K+1."""
 
     def __init__(self, cfg, blobs, keep_history=True, repeatable=True):
-        """repeatable=False is the ablation of Section 4.2 (recompute under the dropout seed
+        """repeatable=False is the ablation of Section 6.3 (recompute under the dropout seed
         of the running iteration instead of the stored one); tests use it as a planted error."""
         super().__init__(cfg, blobs, keep_history)
         self.repeatable = repeatable

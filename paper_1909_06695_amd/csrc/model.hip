@@ -568,11 +568,11 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
   }
   // zero optimizer state, rings, everything else too (one fill over the arena)
   hipError_t e = launch_fill_zero(m->stream, m->arena, need);
-  if (e != hipSuccess) { delete m; return fail(OURO_E_HIP, "arena clear: %s", hipGetErrorString(e)); }
+  if (e != hipSuccess) { ouro_destroy_model(m); return fail(OURO_E_HIP, "arena clear: %s", hipGetErrorString(e)); }
   for (int k = 0; k <= K && e == hipSuccess; ++k)
     if (m->ttab_dev[k])
       e = hipMemcpyAsync(m->ttab_dev[k], m->ttab[k].data(), m->ttab[k].size() * sizeof(TransposeEntry), hipMemcpyHostToDevice, m->stream);
-  if (e != hipSuccess) { delete m; return fail(OURO_E_HIP, "table upload: %s", hipGetErrorString(e)); }
+  if (e != hipSuccess) { ouro_destroy_model(m); return fail(OURO_E_HIP, "table upload: %s", hipGetErrorString(e)); }
   std::vector<float> tab;
   if (!cfg->rel_pos) {
     host_sinusoid(tab, cfg->seq_len, cfg->d_model, m->pd);
@@ -583,7 +583,7 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
     if (e == hipSuccess) e = launch_convert(m->stream, cfg->dtype, m->rtab, m->dbg_f32, tab.size());
   }
   if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
-  if (e != hipSuccess) { delete m; return fail(OURO_E_HIP, "table upload: %s", hipGetErrorString(e)); }
+  if (e != hipSuccess) { ouro_destroy_model(m); return fail(OURO_E_HIP, "table upload: %s", hipGetErrorString(e)); }
   *out = m;
   return OURO_OK;
 }

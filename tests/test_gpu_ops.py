@@ -263,7 +263,7 @@ def test_layernorm_zero_padded_rows(dtype, rows, dn, d):
 def test_dropout_mask_bit_exact(dtype, rows, cols, ld, drop_ld):
     """The kernel's generator against the oracle's: every element kept or dropped alike (integer
     work: bit-exact), kept elements scaled by 1/(1-p); element index = row * drop_ld + column."""
-    pr, seed, sid = 0.3, 0xDEADBEEF12345678, 11
+    pr, seed, sid = 0.3125, 0xDEADBEEF12345678, 11   # rates are dyadic: the same number in fp32 (boundary) and fp64 (oracle)
     cfg = O.Config(n_layer=1, d_model=2, n_head=1, d_head=2, d_ff=1, vocab=2, seq_len=1, batch=1, dropout=pr)
     src = np.zeros((rows, ld), np.float32)
     src[:, :cols] = 1.0 + np.arange(rows * cols, dtype=np.float32).reshape(rows, cols) % 7
@@ -275,7 +275,7 @@ def test_dropout_mask_bit_exact(dtype, rows, cols, ld, drop_ld):
     got = host(dst)[:, :cols]
     assert np.array_equal(got != 0, mask != 0)
     assert rel_err(got, host(d_src)[:, :cols] * mask) < TOL[dtype]
-    assert 0.6 < (mask != 0).mean() < 0.8 or mask.size < 100
+    assert 0.58 < (mask != 0).mean() < 0.8 or mask.size < 100
 
 
 @pytest.mark.parametrize("dtype,force", [(0, 0), (1, 1), (1, 0), (1, 10), (1, 11), (1, 12), (1, 13), (1, 14)])

@@ -1,6 +1,9 @@
 """End-to-end parity of the HIP training iteration against the CPU oracle, through the
 C boundary: losses, every gradient store, updated weights, segment memories, and the
 bit-exact staleness bookkeeping (Eq. 8-9)."""
+import json
+import os
+
 import numpy as np
 import pytest
 
@@ -22,38 +25,92 @@ def rel_err(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
 
 
-def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=1e-4, module_api=False):
-    """Runs `steps` iterations on both sides; returns nothing, asserts parity."""
+# Element-wise bound beside every norm ratio: |a - b| <= tol * (|b| + EW_ATOL * RMS(b)).  The norm
+# ratio alone lets a fraction tol^2 of a tensor be entirely wrong (three rows of an [8192, 512]
+# activation at the bf16 bar); under this bound one wrong element (an error of the size of the
+# tensor's RMS) fails it 1 / (tol * EW_ATOL) times over.  EW_ATOL: the kernels' rounding errors
+# are close to normal with a standard deviation of about tol/4 of the RMS in the worst tensors
+# (their norm ratios reach a quarter to a half of tol), and the largest of 5e7 such
+# draws sits near 6 standard deviations.
+EW_ATOL = 4.0
+RECORD_ONLY = bool(os.environ.get("OURO_PARITY_RECORD"))   # calibration runs: collect WORST without failing
+WORST = {}          # what -> (largest norm ratio / tol, largest element-wise excess), for the calibration record
+
+
+def assert_close(got, ref, tol, what, norm_factor=1.0):
+    got = np.asarray(got, np.float64).ravel(); ref = np.asarray(ref, np.float64).ravel()
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    if ref.size == 0:
+        return
+    assert np.all(np.isfinite(got)), (what, "non-finite values")
+    diff = np.abs(got - ref)
+    nr = float(np.linalg.norm(diff) / max(np.linalg.norm(ref), 1e-30))
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    excess = float(np.max(diff / (tol * (np.abs(ref) + EW_ATOL * rms) + 1e-300)))
+    key = what[0] if isinstance(what, tuple) else what
+    if RECORD_ONLY:
+        key = os.environ.get("PYTEST_CURRENT_TEST", "").split("::")[-1].split(" ")[0] + " :: " + key
+    w = WORST.get(key, (0.0, 0.0))
+    WORST[key] = (max(w[0], nr / tol), max(w[1], excess))
+    if RECORD_ONLY:
+        return
+    assert nr < norm_factor * tol, (what, "norm ratio", nr)
+    if excess > 1.0:
+        i = int(np.argmax(diff / (tol * (np.abs(ref) + EW_ATOL * rms) + 1e-300)))
+        raise AssertionError((what, "element", i, got[i], ref[i], "rms", rms, "excess", excess, "bad elements", int((diff > tol * (np.abs(ref) + EW_ATOL * rms)).sum())))
+
+
+@pytest.fixture(autouse=True, scope="module")
+def _dump_worst():
+    """With OURO_PARITY_RECORD=<file> the largest ratios seen per kind of tensor are written there."""
+    yield
+    if RECORD_ONLY:
+        with open(os.environ["OURO_PARITY_RECORD"], "w") as f:
+            json.dump({k: list(v) for k, v in sorted(WORST.items())}, f, indent=1)
+
+
+def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=1e-4, module_api=False, rep=1,
+             safe_floor=None):
+    """Runs `steps` iterations on both sides; returns nothing, asserts parity.
+
+    rep > 1: the HIP model runs with batch * rep streams, each of the oracle's streams
+    replicated rep times.  Streams do not interact and the loss is a mean over all targets, so
+    the loss, every gradient and every weight equal those of the oracle's batch exactly (up to
+    summation order): the full-size launch configuration is checked element by element at
+    the oracle cost of the small batch."""
     pkg = P()
     blobs = S.init_params(c, seed=seed, std=std, perturb=perturb)
     tok, tgt = S.token_batches(c["vocab"], c["batch"], c["seq_len"], steps, c.get("zipf_s", 1.1), seed + 1,
                                contiguous=bool(c.get("mem_len", 0)))
     cfg = O.Config(**c)
     stored = c.get("schedule", 0) == 1                    # stored-input / recompute schedule
-    orc = (O.RecomputeOracle if stored else O.Oracle)(cfg, blobs)
-    m = pkg.create_model(**c)
+    orc = (O.RecomputeOracle if stored else O.Oracle)(cfg, blobs, keep_history=False)
+    m = pkg.create_model(**dict(c, batch=c["batch"] * rep))
     K = c["n_module"]
     for g in range(K + 1):
         assert m.param_count(g) == blobs[g].size
         m.set_params(g, blobs[g])
-    dtok = torch.from_numpy(tok).cuda(); dtgt = torch.from_numpy(tgt).cuda()
+    dtok = torch.from_numpy(np.tile(tok, (1, rep, 1))).cuda(); dtgt = torch.from_numpy(np.tile(tgt, (1, rep, 1))).cuda()
     # Adam divides by |g|: where the oracle's gradient is tiny against the kernel's fp32 /
     # bf16 rounding noise the step lr*g/(|g|+eps) is ill-conditioned (its sign can flip), so
     # such elements are only checked against Adam's step bound, all others to `tol`.
     safe = [np.ones(b.size, bool) for b in blobs]
+    w0 = [b.astype(np.float64) for b in blobs]
+    moved = [False] * (K + 1)
     for t in range(steps):
         lo = orc.step(tok[t], tgt[t], lr)
-        if c["optimizer"] == 1:
-            for g in range(K + 1):
-                u = orc.used[t][g]
-                if g >= 1 and u >= 0:
-                    gg = orc.grad_blob(g, u)
-                elif g == 0 and u[0] >= 0:
-                    gg = 0.5 * orc.grad_hist[u[0]][2].ravel()
-                    if u[1] >= 0:
-                        gg = gg + 0.5 * orc.grad_hist[u[1]][1].ravel()
-                else:
-                    continue
+        for g in range(K + 1):
+            u = orc.used[t][g]
+            if g >= 1 and u >= 0:
+                gg = orc.grad_blob(g, u)
+            elif g == 0 and u[0] >= 0:
+                gg = 0.5 * orc.grad_hist[u[0]][2].ravel()
+                if u[1] >= 0:
+                    gg = gg + 0.5 * orc.grad_hist[u[1]][1].ravel()
+            else:
+                continue
+            moved[g] = True
+            if c["optimizer"] == 1:
                 safe[g] &= np.abs(gg) > (1e-3 if tol <= 1e-3 else 0.1) * np.sqrt(np.mean(gg * gg))
         if module_api:
             for k in range(1, K + 1):
@@ -71,9 +128,9 @@ def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=
         assert m.current_step() == t + 1
         if check_grads:
             grads, dVi, dVo = orc.grad_hist[t]
-            assert rel_err(m.get_grad_slot(K + 1, t), dVo.ravel()) < tol, ("dVo", t)
+            assert_close(m.get_grad_slot(K + 1, t), dVo, tol, ("dVo", t))
             if not stored or t - K + 1 >= 0:
-                assert rel_err(m.get_grad_slot(0, t), dVi.ravel()) < tol, ("dVi", t)
+                assert_close(m.get_grad_slot(0, t), dVi, tol, ("dVi", t))
             for k in range(1, K + 1):
                 if stored:
                     # the pass of iteration t is for mini-batch t-K+k, recomputed from input slot (t-K+k) mod (K-k+1)
@@ -84,27 +141,47 @@ def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=
                     assert m.last_read(k) == ((0, tau) if tau >= 0 else (-1, -1))
                     if tau < 0:
                         continue
-                assert rel_err(m.get_grad_slot(k, t), orc.grad_blob(k, t)) < tol, ("module grad", k, t)
+                got = m.get_grad_slot(k, t)
+                assert rel_err(got, orc.grad_blob(k, t)) < tol, ("module grad", k, t)
                 # per-parameter check so that small tensors (biases, u, v) are not drowned
                 off = 0
-                got = m.get_grad_slot(k, t)
                 for l in orc.module_layers(k):
                     for name, shape in O.param_shapes(cfg):
                         n = int(np.prod(shape))
-                        ref = grads[l][name].ravel()
-                        assert rel_err(got[off:off + n], ref) < 5 * tol, (name, l, t)
+                        assert_close(got[off:off + n], grads[l][name], tol, ("grad " + name, l, t), norm_factor=5.0)
                         off += n
         for g in range(K + 1):
             got, ref = m.get_params(g).astype(np.float64), orc.module_blob(g)
-            assert rel_err(got[safe[g]], ref[safe[g]]) < tol, ("weights", g, t)
-            assert safe[g].mean() > (0.7 if tol <= 1e-3 else 0.3)     # the conditioned check must still cover most elements
+            assert_close(got[safe[g]], ref[safe[g]], tol, ("weights", g, t))
+            floor = safe_floor if safe_floor is not None else (0.7 if tol <= 1e-3 else 0.5)
+            assert safe[g].mean() > floor, ("safe share", g, t, safe[g].mean())   # the conditioned check must still cover most elements
+            WORST["safe share min"] = (min(WORST.get("safe share min", (1.0, 0))[0], float(safe[g].mean())), 0.0)
             assert np.all(np.abs(got - ref)[~safe[g]] <= 4 * lr * (t + 1)), ("ill-conditioned Adam elements", g, t)
+            if moved[g]:
+                # the movement itself: against the size of the weights a lost update hides under tol
+                dg, dr = (got - w0[g])[safe[g]], (ref - w0[g])[safe[g]]
+                nr = rel_err(dg, dr)
+                w = WORST.get("weight movement", (0.0, 0.0))
+                WORST["weight movement"] = (max(w[0], nr / tol), 0.0)
+                assert RECORD_ONLY or nr < MOVE_FACTOR * tol, ("weight movement", g, t, nr)
+            else:
+                assert np.array_equal(got, w0[g]), ("group moved before its first gradient", g, t)
         if c.get("mem_len", 0):
             for l in range(c["n_layer"]):
                 mem = m.get_mems(l)
-                assert mem.shape == orc.mems[l].shape
-                assert rel_err(mem, orc.mems[l]) < tol
+                assert mem.shape[0] == orc.mems[l].shape[0] * rep and mem.shape[1:] == orc.mems[l].shape[1:]
+                assert_close(mem, np.tile(orc.mems[l], (rep, 1, 1)), tol, ("memory", l, t))
     m.close()
+
+
+# Bound on the relative error of the weight movement w_t - w_0 (norm ratio, in units of tol).  SGD:
+# the movement is a sum of gradients, so the gradients' own bound applies with a little slack for
+# the bf16 working copy that later iterations see.  Adam at the first real step moves every
+# element by lr * sign(g), whatever |g| is; afterwards the step depends on ratios of gradients of
+# different iterations, each with its own rounding noise, and the elements kept by the mask have
+# |g| down to a tenth of the tensor's RMS, where a noise of tol/4 of the RMS is a quarter of the
+# value: several times tol in the norm.
+MOVE_FACTOR = 10.0
 
 
 def test_config1_fp32_sgd_three_steps():
@@ -191,13 +268,13 @@ def test_dropout_fp32(schedule):
     tolerance holds.  Under schedule 1 the recomputation of mini-batch t-K+k must regenerate that
     mini-batch's masks from the stored seed (a recomputation under the running seed fails this)."""
     c = dict(n_layer=4, d_model=40, n_head=5, d_head=8, d_ff=72, vocab=131, seq_len=19, mem_len=0, batch=3,
-             n_module=3, rel_pos=0, dtype=0, optimizer=0, schedule=schedule, dropout=0.2, seed=2 ** 40 + 17)
+             n_module=3, rel_pos=0, dtype=0, optimizer=0, schedule=schedule, dropout=0.1875, seed=2 ** 40 + 17)
     run_both(c, steps=6, lr=0.05, seed=81, std=0.1, perturb=0.1)
 
 
 def test_dropout_xl_memory_adam_fp32():
     c = dict(n_layer=3, d_model=32, n_head=2, d_head=16, d_ff=48, vocab=61, seq_len=6, mem_len=10, batch=2,
-             n_module=3, rel_pos=1, dtype=0, optimizer=1, schedule=1, dropout=0.1, seed=5)
+             n_module=3, rel_pos=1, dtype=0, optimizer=1, schedule=1, dropout=0.125, seed=5)
     run_both(c, steps=6, lr=1e-3, seed=83, std=0.15, perturb=0.1)
 
 
@@ -205,10 +282,10 @@ def test_dropout_xl_memory_adam_fp32():
 def test_dropout_bf16(schedule):
     """bf16: fused masks in the MFMA epilogues (16-byte store path) and through zero-padded storage."""
     c = dict(n_layer=3, d_model=128, n_head=2, d_head=64, d_ff=256, vocab=512, seq_len=96, mem_len=0, batch=3,
-             n_module=3, rel_pos=0, dtype=1, optimizer=0, schedule=schedule, dropout=0.15, seed=99)
+             n_module=3, rel_pos=0, dtype=1, optimizer=0, schedule=schedule, dropout=0.15625, seed=99)
     run_both(c, steps=5, lr=0.05, seed=85, std=0.05, perturb=0.05, tol=2e-2)
     c = dict(n_layer=2, d_model=82, n_head=2, d_head=41, d_ff=100, vocab=203, seq_len=70, mem_len=0, batch=3,
-             n_module=2, rel_pos=0, dtype=1, optimizer=0, schedule=schedule, dropout=0.15, seed=7)
+             n_module=2, rel_pos=0, dtype=1, optimizer=0, schedule=schedule, dropout=0.15625, seed=7)
     run_both(c, steps=4, lr=0.05, seed=87, std=0.05, perturb=0.05, tol=2e-2)
 
 
@@ -277,7 +354,7 @@ def test_stream_overlap_matches_one_stream(rel_pos, mem_len, schedule):
     each on its own streams and scratch buffers) against the same steps on one stream: equal up
     to the order of fp32 atomic additions, over more iterations than the rings are deep."""
     c = dict(n_layer=4, d_model=128, n_head=2, d_head=64, d_ff=256, vocab=512, seq_len=96, mem_len=mem_len, batch=2,
-             n_module=4, rel_pos=rel_pos, dtype=1, optimizer=0, embed_warm_mode=0, schedule=schedule, dropout=0.1 * schedule)
+             n_module=4, rel_pos=rel_pos, dtype=1, optimizer=0, embed_warm_mode=0, schedule=schedule, dropout=0.125 * schedule)
     steps, lr = 7, 0.05
     blobs = S.init_params(c, seed=5, std=0.05, perturb=0.05)
     tok, tgt = S.token_batches(c["vocab"], c["batch"], c["seq_len"], steps, 1.1, 6, contiguous=bool(mem_len))
@@ -300,7 +377,7 @@ def test_stream_overlap_matches_one_stream(rel_pos, mem_len, schedule):
 
 
 def test_long_run_with_warmup_and_cosine_schedule():
-    """Section 4.1's recipe on a structured source: K = 4 with delayed gradients, Adam, linear
+    """Section 5.2's recipe on a structured source: K = 4 with delayed gradients, Adam, linear
     warm-up then cosine decay (the library's schedule function), 400 iterations on a Markov token
     source.  The run stays finite, ends well below the unigram entropy of the source (so the
     context was learnt through the stale gradients), and lands close to plain backpropagation
@@ -346,7 +423,7 @@ def test_eval_step_with_longer_memory(dtype, tol):
     for t in range(4):
         lo, lg = orc.step(tok[t], tgt[t], 0.05), m.step(dtok[t], dtgt[t], 0.05)
         assert abs(lg - lo) / lo < tol
-    ce = dict(c, mem_len=60, dropout=0.4, seed=3)
+    ce = dict(c, mem_len=60, dropout=0.375, seed=3)
     oe = O.Oracle(O.Config(**ce), [orc.module_blob(g) for g in range(4)])
     e = P().create_model(**ce)
     e.copy_params_from(m)
@@ -376,7 +453,7 @@ def test_checkpoint_resume(schedule, dtype, opt):
     tol = 2e-2 if dtype else 1e-4
     dh = 64 if dtype else 16
     c = dict(n_layer=3, d_model=2 * dh, n_head=2, d_head=dh, d_ff=96, vocab=211, seq_len=24, mem_len=40, batch=2,
-             n_module=3, rel_pos=1, dtype=dtype, optimizer=opt, schedule=schedule, dropout=0.1, seed=77)
+             n_module=3, rel_pos=1, dtype=dtype, optimizer=opt, schedule=schedule, dropout=0.125, seed=77)
     lr = 1e-3 if opt else 0.05
     blobs = S.init_params(c, seed=13, std=0.1, perturb=0.1)
     tok, tgt = S.token_batches(c["vocab"], c["batch"], c["seq_len"], 9, 1.1, 14, contiguous=True)
@@ -569,17 +646,74 @@ def test_call_order_and_error_codes():
     m.close()
 
 
-def test_bench_config_full_size_first_steps():
-    """The bench workload (12 layers, d=512, vocab 32768, 8192 tokens, K=4, Adam, bf16) at full
-    size: loss, every gradient store and the updated weights of the first two iterations
-    against the oracle.  bf16 tolerance; see run_both for the Adam-conditioned weight check."""
+def test_bench_config_full_size_steady_state():
+    """cfg2 (12 layers, d=512, vocab 32768, 8192 tokens, K=4, Adam, bf16) at full size for K+2
+    iterations: every module and V take real stale-gradient Adam steps (module 1 and V from
+    iteration K-1 on), every ring slot is written a second time and read after the wrap-around.
+    Loss, every gradient store and the weights (element by element) against the oracle."""
     c = dict(S.CONFIGS["cfg2"])
-    run_both(c, steps=2, lr=c["lr"], seed=0, tol=2e-2)
+    run_both(c, steps=c["n_module"] + 2, lr=c["lr"], seed=0, tol=2e-2)
 
 
 def test_xl_config_full_size_first_steps():
-    """The Transformer-XL workload with widths off the tile grid (16 layers, d=410, 10 heads of 41,
-    d_ff=2100, segment and memory 150) at full size, stored zero-padded: two iterations (empty,
-    then full memory) against the oracle."""
+    """cfg3: Transformer-XL with widths off the tile grid (16 layers, d=410, 10 heads of 41,
+    d_ff=2100, segment and memory 150) at full size, stored zero-padded: empty memory, full
+    memory, rolled memory against the oracle."""
     c = dict(S.CONFIGS["cfg3"])
-    run_both(c, steps=2, lr=c["lr"], seed=0, tol=2e-2)
+    run_both(c, steps=3, lr=c["lr"], seed=0, tol=2e-2)
+
+
+def test_cfg4_shapes_full_size_launch():
+    """cfg4 (24 layers, d=1024, 16 heads, d_ff=4096, vocab 50257 on the zero-padded vocabulary
+    path, T=1024: 16 key blocks per query block, K=8 with rings up to 8 deep) in the launch
+    configuration the benchmark times (8 streams, 8192 tokens): the oracle runs one stream, the
+    HIP path the same stream eight times (run_both, rep), so every tile of the full-size
+    launches is compared element by element.  5 iterations: modules 4..8 take real Adam steps."""
+    c = dict(S.CONFIGS["cfg4"], batch=1)
+    run_both(c, steps=5, lr=c["lr"], seed=0, tol=2e-2, rep=8)
+
+
+def test_cfg5_shapes_full_size_launch():
+    """cfg5 (Transformer-XL, 18 layers split 4,5,5,4 by the default rule, d=1024, segment and
+    memory 384, vocab 65536) with 16 streams on the HIP side (two oracle streams, each eight
+    times): empty, full and rolled memory, every module and V updated (K+1 = 5 iterations)."""
+    c = dict(S.CONFIGS["cfg5"], batch=2)
+    assert "layers_per_module" not in c
+    run_both(c, steps=c["n_module"] + 1, lr=c["lr"], seed=0, tol=2e-2, rep=8)
+
+
+@pytest.mark.parametrize("name,rows", [("cfg4", (0, 5)), ("cfg5", (3, 15))])
+def test_full_size_distinct_streams_forward_rows(name, rows):
+    """Full-size launches with all streams different (the benchmark's inputs): streams do not
+    interact in the forward pass, so the final hidden state of one stream is what the oracle
+    computes for that stream alone.  Two iterations at step size 0 (the second with a full
+    segment memory for the relative model), sampled streams element by element, and the loss as
+    the mean of per-stream losses cannot be formed without all streams, so it is bounded only."""
+    c = dict(S.CONFIGS[name])
+    B, T, d, L = c["batch"], c["seq_len"], c["d_model"], c["n_layer"]
+    blobs = S.init_params(c, seed=0)
+    tok, tgt = S.token_batches(c["vocab"], B, T, 2, c["zipf_s"], c["seed"], contiguous=bool(c["mem_len"]))
+    m = P().create_model(**c)
+    for g in range(c["n_module"] + 1):
+        m.set_params(g, blobs[g])
+    dtok = torch.from_numpy(tok).cuda(); dtgt = torch.from_numpy(tgt).cuda()
+    hid, losses = [], []
+    for t in range(2):
+        losses.append(m.step(dtok[t], dtgt[t], 0.0))
+        hid.append(m.get_hidden(L).reshape(B, T, d))
+    for g in range(c["n_module"] + 1):
+        assert np.array_equal(m.get_params(g), blobs[g])          # step size 0: nothing moved
+    m.close()
+    c1 = dict(c, batch=1)
+    row_losses = []
+    for b in rows:
+        orc = O.Oracle(O.Config(**c1), blobs, keep_history=False)
+        for t in range(2):
+            loss, fw = O.model_forward(orc.cfg, orc.layers, orc.V, orc.V, tok[t, b:b + 1], tgt[t, b:b + 1], orc.mems, None)
+            assert_close(hid[t][b], fw["hL"][0], 2e-2, ("final hidden state", name, b, t))
+            row_losses.append(loss)
+            if c["mem_len"]:
+                orc.mems = [fw["inputs"][l][:, -c["mem_len"]:].copy() if orc.mems is None else
+                            np.concatenate([orc.mems[l], fw["inputs"][l]], axis=1)[:, -c["mem_len"]:].copy() for l in range(L)]
+    # Zipf streams at the initial weights: per-stream losses lie close together
+    assert abs(np.mean(losses) - np.mean(row_losses)) < 0.05 * np.mean(row_losses)

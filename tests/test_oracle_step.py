@@ -214,7 +214,7 @@ def test_xl_memory_carry():
 
 
 def test_learning_rate_schedule_closed_forms():
-    """Warm-up then cosine (Section 4.1), pinned by what the two phases fix: the warm-up is an
+    """Warm-up then cosine (Section 5.2), pinned by what the two phases fix: the warm-up is an
     arithmetic progression that ends exactly at the base rate; the cosine phase starts there,
     passes the midpoint of [floor, base] half-way, is point-symmetric about it, decreases
     monotonically and ends at the floor, where it stays."""
@@ -466,7 +466,7 @@ def test_dropout_gradients_by_finite_differences_and_autograd(kw):
 
 
 def test_repeatable_dropout_in_the_recompute_schedule():
-    """Section 4.1, "Repeatable Dropout": with the seed stored beside the module input, the
+    """Section 5.2, "Repeatable Dropout": with the seed stored beside the module input, the
     recomputation sees the masks of the original pass, so at frozen weights the schedule still
     yields Eq. 8's gradient (now of the dropout network of mini-batch t-K+k).  Recomputing under
     the running iteration's seed instead (the ablation) breaks exactly that."""
