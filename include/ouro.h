@@ -225,11 +225,20 @@ int ouro_get_mems(ouro_model* m, int layer, float* host_dst, int64_t* valid_len)
  * state, of the latest forward, as fp32 [batch*seq_len, d_model]. */
 int ouro_debug_get_hidden(ouro_model* m, int layer, float* host_dst, int64_t n);
 /* Optional per-launch HIP event timing on the model's stream (slows the step while on).
- * kind 0: the MFMA contraction kernel, work = 2*M*N*K flops per launch;
- * kind 1: the delayed-update kernel (zero-gradient warm-up launches excluded), work =
- *         algorithmic bytes (gradient reads 4 B each, w 8 B, Adam moments 16 B, bf16 copy 2 B).
+ * OURO_TIMING_CONTRACTION: the MFMA contraction kernel, work = 2*M*N*K flops per launch;
+ * OURO_TIMING_UPDATE: the delayed-update kernel (zero-gradient warm-up launches excluded), work =
+ *         algorithmic bytes (gradient reads 4 B each, w 8 B, Adam moments 16 B, bf16 copy 2 B);
+ * OURO_TIMING_ATTENTION: attention forward and backward launches, work = algorithmic flops
+ *         (visible query-key pairs x 4 d_head forward, 6 d_head with the relative-position term;
+ *         a backward launch counts twice its forward);
+ * OURO_TIMING_LAYERNORM: LayerNorm forward and input-gradient launches, work = bytes (rows read
+ *         and written in the activation type, 8 B of statistics per row);
+ * OURO_TIMING_CE_ROWS: the row pass of the softmax cross entropy, work = bytes (logits read once,
+ *         the logit gradient written once).
  * timing_read synchronises the stream, returns the totals since the last read of that
  * kind and resets them. */
+enum { OURO_TIMING_CONTRACTION = 0, OURO_TIMING_UPDATE = 1, OURO_TIMING_ATTENTION = 2, OURO_TIMING_LAYERNORM = 3,
+       OURO_TIMING_CE_ROWS = 4, OURO_TIMING_KINDS = 5 };
 int ouro_debug_timing_enable(ouro_model* m, int on);
 /* Stream overlap switch. on = 1 (default): weight-gradient contractions run on a second
  * stream beside the error-gradient chain and ouro_step enqueues each module's update behind

@@ -30,6 +30,9 @@ static int fail(int code, const char* fmt, ...) {
   } while (0)
 
 extern "C" const char* ouro_last_error(void) { return g_err.c_str(); }
+namespace ouro {
+int set_error(int code, const char* msg) { g_err = msg ? msg : ""; return code; }
+}
 
 // ------------------------------------------------------------------ staleness integers
 // Eq. 8: module k at iteration t consumes the gradient of iteration t-K+k.  A ring of
@@ -237,13 +240,12 @@ struct ouro_model : BwdCtx {
   hipStream_t aux;
   hipEvent_t ev_bwd_done, ev_upd_done;
   bool upd_pending;            // updates enqueued on aux that main has not waited for yet
-  // optional per-launch HIP event timing: kind 0 = MFMA contraction kernel (work = flops),
-  // kind 1 = delayed-update kernel (work = algorithmic bytes)
+  // optional per-launch HIP event timing, by kind of kernel (see ouro_debug_timing_enable)
   int timing;
-  std::vector<hipEvent_t> ev[2];
-  size_t ev_used[2];
-  double timed_work[2];
-  int64_t timed_launches[2];
+  std::vector<hipEvent_t> ev[OURO_TIMING_KINDS];
+  size_t ev_used[OURO_TIMING_KINDS];
+  double timed_work[OURO_TIMING_KINDS];
+  int64_t timed_launches[OURO_TIMING_KINDS];
 
   const char* wT(int layer, size_t off) const {   // weight as activation-typed operand
     int k = layer_mod[layer];
@@ -539,7 +541,7 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
   m->tok = m->tgt = nullptr;
   m->timing = 0;
   m->eval_mode = false; m->cur_seed = cfg->seed;
-  for (int i = 0; i < 2; ++i) { m->ev_used[i] = 0; m->timed_work[i] = 0; m->timed_launches[i] = 0; }
+  for (int i = 0; i < OURO_TIMING_KINDS; ++i) { m->ev_used[i] = 0; m->timed_work[i] = 0; m->timed_launches[i] = 0; }
   m->side = nullptr; m->use_side = false; m->ev_join = nullptr;
   m->aux = nullptr; m->ev_bwd_done = m->ev_upd_done = nullptr; m->upd_pending = false;
   for (int i = 0; i < 4; ++i) m->ev_ready[i] = nullptr;
@@ -614,7 +616,7 @@ extern "C" int ouro_destroy_model(ouro_model* m) {
   if (m->ev_join) (void)hipEventDestroy(m->ev_join);
   if (m->aux) { (void)hipStreamSynchronize(m->aux); (void)hipStreamDestroy(m->aux); }
   for (hipEvent_t e : {m->ev_bwd_done, m->ev_upd_done}) if (e) (void)hipEventDestroy(e);
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < OURO_TIMING_KINDS; ++i)
     for (hipEvent_t e : m->ev[i]) (void)hipEventDestroy(e);
   delete m;
   return OURO_OK;
@@ -719,11 +721,28 @@ static int timing_end(ouro_model* m, int kind, double work, hipStream_t st) {
   return OURO_OK;
 }
 
+// Runs `launch` (a callable returning hipError_t) on st, inside a timing bracket of `kind` when timing is on.
+template <typename F>
+static int timed_launch(ouro_model* m, int kind, double work, hipStream_t st, F&& launch) {
+  const bool timed = m->timing != 0;
+  if (timed) { int rc = timing_begin(m, kind, st); if (rc) return rc; }
+  HIPCHK(launch());
+  if (timed) return timing_end(m, kind, work, st);
+  return OURO_OK;
+}
+// Algorithmic flops of one attention forward launch: visible (query, key) pairs x 4 d_head (scores
+// and P V), 6 d_head with the relative-position term; the backward pass counts twice that.
+static double attn_fwd_flops(const ouro_model* m, int Mv) {
+  const ouro_config& c = m->cfg;
+  const double pairs = (double)c.seq_len * Mv + 0.5 * (double)c.seq_len * (c.seq_len + 1);
+  return pairs * c.batch * c.n_head * c.d_head * (c.rel_pos ? 6.0 : 4.0);
+}
+
 static int run_gemm_on(ouro_model* m, GemmDesc g, hipStream_t st) {
   const bool timed = m->timing && gemm_uses_mfma(m->cfg.dtype, g);
-  if (timed) { int rc = timing_begin(m, 0, st); if (rc) return rc; }
+  if (timed) { int rc = timing_begin(m, OURO_TIMING_CONTRACTION, st); if (rc) return rc; }
   HIPCHK(launch_gemm(st, m->cfg.dtype, g, 0));
-  if (timed) return timing_end(m, 0, 2.0 * g.M * g.N * g.K, st);
+  if (timed) return timing_end(m, OURO_TIMING_CONTRACTION, 2.0 * g.M * g.N * g.K, st);
   return OURO_OK;
 }
 static int run_gemm(ouro_model* m, GemmDesc g) { return run_gemm_on(m, g, m->stream); }
@@ -800,13 +819,15 @@ static int layer_forward(ouro_model* m, int l, char* out_override = nullptr) {
     a.v = kv + (size_t)hd * es; a.ldv = 2 * hd;
     a.rel = 1; a.u = m->wT(l, o.u); a.vb = m->wT(l, o.v); a.r = b.r; a.ldr = hd;
   }
-  HIPCHK(launch_attn_fwd(m->stream, c.dtype, a, 0));
+  RUN(timed_launch(m, OURO_TIMING_ATTENTION, attn_fwd_flops(m, Mv), m->stream, [&] { return launch_attn_fwd(m->stream, c.dtype, a, 0); }));
   {
     GemmDesc g = bt ? gd(b.a, hd, 0, m->wTt(l, o.W_o), hd, 1, b.s1, d, N, d, hd) : gd(b.a, hd, 0, m->wT(l, o.W_o), d, 0, b.s1, d, N, d, hd);
     g.residual = b.x; g.ldr = d; g.drop = drop_at(m, 2 * l + 1);
     RUN(run_gemm(m, g));
   }
-  HIPCHK(launch_layernorm_fwd(m->stream, c.dtype, b.s1, m->wF(l, o.ln1_g), m->wF(l, o.ln1_b), b.y, b.mean1, b.rstd1, N, d, dn));
+  const double ln_fwd_bytes = 2.0 * N * dn * es + 8.0 * N;      // row read, row written, two statistics per row
+  RUN(timed_launch(m, OURO_TIMING_LAYERNORM, ln_fwd_bytes, m->stream, [&] {
+    return launch_layernorm_fwd(m->stream, c.dtype, b.s1, m->wF(l, o.ln1_g), m->wF(l, o.ln1_b), b.y, b.mean1, b.rstd1, N, d, dn); }));
   {
     GemmDesc g = bt ? gd(b.y, d, 0, m->wTt(l, o.W_1), d, 1, b.uact, F, N, F, d) : gd(b.y, d, 0, m->wT(l, o.W_1), F, 0, b.uact, F, N, F, d);
     g.bias = m->wF(l, o.b_1); g.epilogue = EPI_GELU; g.Z = b.z; g.ldz = F;
@@ -817,7 +838,8 @@ static int layer_forward(ouro_model* m, int l, char* out_override = nullptr) {
     g.bias = m->wF(l, o.b_2); g.residual = b.y; g.ldr = d; g.drop = drop_at(m, 2 * l + 2);
     RUN(run_gemm(m, g));
   }
-  HIPCHK(launch_layernorm_fwd(m->stream, c.dtype, b.s2, m->wF(l, o.ln2_g), m->wF(l, o.ln2_b), out, b.mean2, b.rstd2, N, d, dn));
+  RUN(timed_launch(m, OURO_TIMING_LAYERNORM, ln_fwd_bytes, m->stream, [&] {
+    return launch_layernorm_fwd(m->stream, c.dtype, b.s2, m->wF(l, o.ln2_g), m->wF(l, o.ln2_b), out, b.mean2, b.rstd2, N, d, dn); }));
   return OURO_OK;
 }
 
@@ -862,7 +884,9 @@ extern "C" int ouro_module_forward(ouro_model* m, int k, const int32_t* dev_toke
     const int d = m->pd, V = c.vocab, N = m->N;
     GemmDesc g = gd(m->hL, d, 0, m->vT(), d, 1, m->G, m->ldv, N, V, d);   // logits = h_L V^T (Eq. 3)
     RUN(run_gemm(m, g));
-    HIPCHK(launch_ce_rows(m->stream, c.dtype, m->G, m->ldv, m->tgt, m->G, m->ldv, m->lse_ce, m->rowloss, N, V, m->flag));
+    // logits read once, d loss / d logits written once, per row the log-sum-exp and the loss
+    RUN(timed_launch(m, OURO_TIMING_CE_ROWS, 2.0 * N * (double)V * m->esz + 12.0 * N, m->stream, [&] {
+      return launch_ce_rows(m->stream, c.dtype, m->G, m->ldv, m->tgt, m->G, m->ldv, m->lse_ce, m->rowloss, N, V, m->flag); }));
     HIPCHK(launch_sum_rows(m->stream, m->rowloss, N, m->loss));
   }
   m->fwd_next = k + 1;
@@ -908,8 +932,10 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   };
   // LN2
   // with the side stream the scale/shift gradients (column sums over dh and s2) run there too
-  HIPCHK(launch_layernorm_bwd(st, c.dtype, dh, b.s2, m->wF(l, o.ln2_g), b.mean2, b.rstd2, ds2,
-                              side ? nullptr : gslot + o.ln2_g, gslot + o.ln2_b, N, d, dn));
+  const double ln_bwd_bytes = 3.0 * N * dn * es + 8.0 * N;      // gradient and input rows read, one row written, statistics
+  RUN(timed_launch(m, OURO_TIMING_LAYERNORM, ln_bwd_bytes, st, [&] {
+    return launch_layernorm_bwd(st, c.dtype, dh, b.s2, m->wF(l, o.ln2_g), b.mean2, b.rstd2, ds2,
+                                side ? nullptr : gslot + o.ln2_g, gslot + o.ln2_b, N, d, dn); }));
   if (dropping) HIPCHK(launch_dropout_apply(st, c.dtype, ds2, ds2m, N, d, d, drop_at(m, 2 * l + 2)));
   RUN(ready(0));
   if (side) HIPCHK(launch_layernorm_bwd_params(sw, c.dtype, dh, b.s2, b.mean2, b.rstd2, gslot + o.ln2_g, gslot + o.ln2_b, N, d));
@@ -939,8 +965,9 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     RUN(run_gemm(m, g));
   }
   // LN1
-  HIPCHK(launch_layernorm_bwd(st, c.dtype, dy, b.s1, m->wF(l, o.ln1_g), b.mean1, b.rstd1, ds1,
-                              side ? nullptr : gslot + o.ln1_g, gslot + o.ln1_b, N, d, dn));
+  RUN(timed_launch(m, OURO_TIMING_LAYERNORM, ln_bwd_bytes, st, [&] {
+    return launch_layernorm_bwd(st, c.dtype, dy, b.s1, m->wF(l, o.ln1_g), b.mean1, b.rstd1, ds1,
+                                side ? nullptr : gslot + o.ln1_g, gslot + o.ln1_b, N, d, dn); }));
   if (dropping) HIPCHK(launch_dropout_apply(st, c.dtype, ds1, ds1m, N, d, d, drop_at(m, 2 * l + 1)));
   RUN(ready(2));
   if (side) HIPCHK(launch_layernorm_bwd_params(sw, c.dtype, dy, b.s1, b.mean1, b.rstd1, gslot + o.ln1_g, gslot + o.ln1_b, N, d));
@@ -964,7 +991,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     a.dq = dqkv; a.lddq = 3 * hd;
     a.dk = dqkv + (size_t)hd * es; a.lddk = 3 * hd;
     a.dv = dqkv + (size_t)2 * hd * es; a.lddv = 3 * hd;
-    HIPCHK(launch_attn_bwd(st, c.dtype, a, 0));
+    RUN(timed_launch(m, OURO_TIMING_ATTENTION, 2.0 * attn_fwd_flops(m, Mv), st, [&] { return launch_attn_bwd(st, c.dtype, a, 0); }));
     RUN(ready(3));
     {
       GemmDesc g = gd(b.x, d, 1, dqkv, 3 * hd, 0, gslot + o.W_qkv, 3 * hd, d, 3 * hd, N);
@@ -988,7 +1015,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     float* drf = m->dr_f32[ps];
     a.du = gslot + o.u; a.dvb = gslot + o.v; a.dr = drf;
     HIPCHK(launch_fill_zero(st, drf, (size_t)S * hd * 4));
-    HIPCHK(launch_attn_bwd(st, c.dtype, a, 0));
+    RUN(timed_launch(m, OURO_TIMING_ATTENTION, 2.0 * attn_fwd_flops(m, Mv), st, [&] { return launch_attn_bwd(st, c.dtype, a, 0); }));
     const void* drp = drf;
     if (c.dtype == 1) { HIPCHK(launch_convert(st, 1, m->dr_t[ps], drf, (size_t)S * hd)); drp = m->dr_t[ps]; }
     RUN(ready(3));
@@ -1219,12 +1246,12 @@ static int update_group(ouro_model* m, int group, float lr, hipStream_t st) {
     }
   }
   const bool timed = m->timing && u.g0;
-  if (timed) RUN(timing_begin(m, 1, st));
+  if (timed) RUN(timing_begin(m, OURO_TIMING_UPDATE, st));
   HIPCHK(launch_update(st, u));
   if (timed) {
     // algorithmic bytes per element: gradient(s) 4 each, w read+write 8, Adam m,v read+write 16, bf16 copy 2
     double per = 4.0 * ((u.g0 ? 1 : 0) + (u.g1 ? 1 : 0)) + 8.0 + (u.adam ? 16.0 : 0.0) + (u.shadow ? 2.0 : 0.0);
-    RUN(timing_end(m, 1, per * (double)u.n, st));
+    RUN(timing_end(m, OURO_TIMING_UPDATE, per * (double)u.n, st));
   }
   RUN(refresh_transposed(m, group, st));
   m->upd_mask |= 1ull << group;
@@ -1594,7 +1621,7 @@ extern "C" int ouro_debug_set_overlap(ouro_model* m, int on) {
 }
 
 extern "C" int ouro_debug_timing_read(ouro_model* m, int kind, double* ms, int64_t* launches, double* work) {
-  if (!m || kind < 0 || kind > 1) return fail(OURO_E_ARG, "timing_read: bad argument");
+  if (!m || kind < 0 || kind >= OURO_TIMING_KINDS) return fail(OURO_E_ARG, "timing_read: bad argument");
   HIPCHK(hipStreamSynchronize(m->stream));
   double total = 0;
   for (size_t i = 0; i + 1 < m->ev_used[kind]; i += 2) {

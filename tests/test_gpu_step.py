@@ -25,19 +25,41 @@ def rel_err(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
 
 
-# Element-wise bound beside every norm ratio: |a - b| <= tol * (|b| + EW_ATOL * RMS(b)).  The norm
-# ratio alone lets a fraction tol^2 of a tensor be entirely wrong (three rows of an [8192, 512]
-# activation at the bf16 bar); under this bound one wrong element (an error of the size of the
-# tensor's RMS) fails it 1 / (tol * EW_ATOL) times over.  EW_ATOL: the kernels' rounding errors
-# are close to normal with a standard deviation of about tol/4 of the RMS in the worst tensors
-# (their norm ratios reach a quarter to a half of tol), and the largest of 5e7 such
-# draws sits near 6 standard deviations.
-EW_ATOL = 4.0
+# Element-wise bound beside every norm ratio: |a - b| <= f * tol * (|b| + EW_ATOL * scale), f the factor
+# the norm ratio is held to (1, or 5 for a single small parameter tensor).  The norm ratio alone
+# lets a fraction tol^2 of a tensor be entirely wrong (three rows of an [8192, 512] activation at
+# the bf16 bar); under this bound one wrong element (an error of the size of its scale) fails it
+# 1 / (f * tol * EW_ATOL) times over.  `scale` is the size elements have at that place: the
+# tensor's RMS for a vector; for a matrix row RMS x column RMS / RMS, because gradient matrices
+# are sums of outer products whose rows and columns carry very different sizes (a row of dV_i
+# is the sum over the occurrences of one token: 14 % of a Zipf stream for the first id, none at all
+# for most; rows that are exactly zero must be exactly zero on both sides).  EW_ATOL = 6: rounding
+# errors are close to normal, a tensor that just meets the norm bound f * tol has a per-element
+# standard deviation of f * tol * scale, and the largest of 5e7 normal draws sits near 6 standard
+# deviations.
+EW_ATOL = 6.0
 RECORD_ONLY = bool(os.environ.get("OURO_PARITY_RECORD"))   # calibration runs: collect WORST without failing
 WORST = {}          # what -> (largest norm ratio / tol, largest element-wise excess), for the calibration record
 
 
-def assert_close(got, ref, tol, what, norm_factor=1.0):
+def elem_scale(ref, shape=None):
+    """Element-wise size of a reference tensor (flat array out): see EW_ATOL."""
+    ref = np.asarray(ref, np.float64)
+    rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
+    if shape is None or len(shape) != 2 or rms == 0.0:
+        return np.full(ref.size, rms)
+    r2 = ref.reshape(shape)
+    return (np.sqrt(np.mean(r2 * r2, axis=1))[:, None] * np.sqrt(np.mean(r2 * r2, axis=0))[None, :] / rms).ravel()
+
+
+def record(key, nr_over_tol, excess):
+    if RECORD_ONLY:
+        key = os.environ.get("PYTEST_CURRENT_TEST", "").split("::")[-1].split(" ")[0] + " :: " + key
+    w = WORST.get(key, (0.0, 0.0))
+    WORST[key] = (max(w[0], nr_over_tol), max(w[1], excess))
+
+
+def assert_close(got, ref, tol, what, norm_factor=1.0, shape=None):
     got = np.asarray(got, np.float64).ravel(); ref = np.asarray(ref, np.float64).ravel()
     assert got.shape == ref.shape, (what, got.shape, ref.shape)
     if ref.size == 0:
@@ -45,19 +67,28 @@ def assert_close(got, ref, tol, what, norm_factor=1.0):
     assert np.all(np.isfinite(got)), (what, "non-finite values")
     diff = np.abs(got - ref)
     nr = float(np.linalg.norm(diff) / max(np.linalg.norm(ref), 1e-30))
-    rms = float(np.sqrt(np.mean(ref * ref)))
-    excess = float(np.max(diff / (tol * (np.abs(ref) + EW_ATOL * rms) + 1e-300)))
-    key = what[0] if isinstance(what, tuple) else what
-    if RECORD_ONLY:
-        key = os.environ.get("PYTEST_CURRENT_TEST", "").split("::")[-1].split(" ")[0] + " :: " + key
-    w = WORST.get(key, (0.0, 0.0))
-    WORST[key] = (max(w[0], nr / tol), max(w[1], excess))
+    bound = norm_factor * tol * (np.abs(ref) + EW_ATOL * elem_scale(ref, shape))
+    over = diff > bound
+    ratio = diff / np.maximum(bound, 1e-300)
+    excess = float(np.max(ratio))
+    record(what[0] if isinstance(what, tuple) else what, nr / tol, min(excess, 1e9))
     if RECORD_ONLY:
         return
     assert nr < norm_factor * tol, (what, "norm ratio", nr)
-    if excess > 1.0:
-        i = int(np.argmax(diff / (tol * (np.abs(ref) + EW_ATOL * rms) + 1e-300)))
-        raise AssertionError((what, "element", i, got[i], ref[i], "rms", rms, "excess", excess, "bad elements", int((diff > tol * (np.abs(ref) + EW_ATOL * rms)).sum())))
+    if over.any():
+        i = int(np.argmax(ratio))
+        raise AssertionError((what, "element", i, got[i], ref[i], "bound", bound[i], "excess", excess, "bad elements", int(over.sum())))
+
+
+# Error budget of a weight after an optimiser step with a gradient that carries the rounding noise
+# the gradient bound allows (per element up to tol * (|g| + EW_ATOL * scale)).  SGD: lr times that.
+# Adam: the step lr * m^ / (sqrt(v^) + eps) does not depend on the size of g but on ratios, so the
+# error of one step is lr * (noise / sqrt(v^)) * 2 (numerator and denominator move), capped by the
+# largest change a step can make at all, ADAM_CAP * lr (a sign flip of a step of lr *
+# (1-beta1)/sqrt(1-beta2) = 3.2 lr at most, in practice of about lr); where sqrt(v^) is far below
+# the noise the step is ill-conditioned and only that cap holds.  Every element is checked against
+# the sum of its per-iteration budgets.
+ADAM_CAP = 4.0
 
 
 @pytest.fixture(autouse=True, scope="module")
@@ -69,8 +100,22 @@ def _dump_worst():
             json.dump({k: list(v) for k, v in sorted(WORST.items())}, f, indent=1)
 
 
-def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=1e-4, module_api=False, rep=1,
-             safe_floor=None):
+def param_shapes_of_groups(cfg, orc):
+    """Per parameter group a list of (offset, count, shape) of its tensors in blob order."""
+    K = cfg.n_module
+    out = [[(0, cfg.vocab * cfg.d_model, (cfg.vocab, cfg.d_model))]]
+    for k in range(1, K + 1):
+        off, lst = 0, []
+        for _ in orc.module_layers(k):
+            for _, shape in O.param_shapes(cfg):
+                n = int(np.prod(shape))
+                lst.append((off, n, shape))
+                off += n
+        out.append(lst)
+    return out
+
+
+def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=1e-4, module_api=False, rep=1):
     """Runs `steps` iterations on both sides; returns nothing, asserts parity.
 
     rep > 1: the HIP model runs with batch * rep streams, each of the oracle's streams
@@ -91,12 +136,10 @@ def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=
         assert m.param_count(g) == blobs[g].size
         m.set_params(g, blobs[g])
     dtok = torch.from_numpy(np.tile(tok, (1, rep, 1))).cuda(); dtgt = torch.from_numpy(np.tile(tgt, (1, rep, 1))).cuda()
-    # Adam divides by |g|: where the oracle's gradient is tiny against the kernel's fp32 /
-    # bf16 rounding noise the step lr*g/(|g|+eps) is ill-conditioned (its sign can flip), so
-    # such elements are only checked against Adam's step bound, all others to `tol`.
-    safe = [np.ones(b.size, bool) for b in blobs]
+    budget = [np.zeros(b.size) for b in blobs]            # per-element error budget of the weights, see ADAM_CAP
     w0 = [b.astype(np.float64) for b in blobs]
     moved = [False] * (K + 1)
+    shapes = param_shapes_of_groups(cfg, orc)
     for t in range(steps):
         lo = orc.step(tok[t], tgt[t], lr)
         for g in range(K + 1):
@@ -110,8 +153,14 @@ def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=
             else:
                 continue
             moved[g] = True
-            if c["optimizer"] == 1:
-                safe[g] &= np.abs(gg) > (1e-3 if tol <= 1e-3 else 0.1) * np.sqrt(np.mean(gg * gg))
+            f = 1.0 if g == 0 else 5.0                           # the factor its gradient check runs with
+            noise = np.concatenate([f * tol * (np.abs(gg[o:o + n]) + EW_ATOL * elem_scale(gg[o:o + n], sh)) for o, n, sh in shapes[g]])
+            if c["optimizer"] == 0:
+                budget[g] += lr * noise
+            else:
+                v = orc.vV.ravel() if g == 0 else O.pack_layers(cfg, [orc.v[l] for l in orc.module_layers(g)])
+                vhat = v / (1.0 - c.get("beta2", 0.999) ** orc.t)             # orc.t: iterations done, = t + 1
+                budget[g] += lr * np.minimum(ADAM_CAP, 2.0 * noise / np.maximum(np.sqrt(vhat), 1e-300))
         if module_api:
             for k in range(1, K + 1):
                 m.module_forward(k, dtok[t], dtgt[t])
@@ -128,9 +177,9 @@ def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=
         assert m.current_step() == t + 1
         if check_grads:
             grads, dVi, dVo = orc.grad_hist[t]
-            assert_close(m.get_grad_slot(K + 1, t), dVo, tol, ("dVo", t))
+            assert_close(m.get_grad_slot(K + 1, t), dVo, tol, ("dVo", t), shape=dVo.shape)
             if not stored or t - K + 1 >= 0:
-                assert_close(m.get_grad_slot(0, t), dVi, tol, ("dVi", t))
+                assert_close(m.get_grad_slot(0, t), dVi, tol, ("dVi", t), shape=dVi.shape)
             for k in range(1, K + 1):
                 if stored:
                     # the pass of iteration t is for mini-batch t-K+k, recomputed from input slot (t-K+k) mod (K-k+1)
@@ -148,24 +197,23 @@ def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=
                 for l in orc.module_layers(k):
                     for name, shape in O.param_shapes(cfg):
                         n = int(np.prod(shape))
-                        assert_close(got[off:off + n], grads[l][name], tol, ("grad " + name, l, t), norm_factor=5.0)
+                        assert_close(got[off:off + n], grads[l][name], tol, ("grad " + name, l, t), norm_factor=5.0, shape=shape)
                         off += n
         for g in range(K + 1):
             got, ref = m.get_params(g).astype(np.float64), orc.module_blob(g)
-            assert_close(got[safe[g]], ref[safe[g]], tol, ("weights", g, t))
-            floor = safe_floor if safe_floor is not None else (0.7 if tol <= 1e-3 else 0.5)
-            assert safe[g].mean() > floor, ("safe share", g, t, safe[g].mean())   # the conditioned check must still cover most elements
-            WORST["safe share min"] = (min(WORST.get("safe share min", (1.0, 0))[0], float(safe[g].mean())), 0.0)
-            assert np.all(np.abs(got - ref)[~safe[g]] <= 4 * lr * (t + 1)), ("ill-conditioned Adam elements", g, t)
-            if moved[g]:
-                # the movement itself: against the size of the weights a lost update hides under tol
-                dg, dr = (got - w0[g])[safe[g]], (ref - w0[g])[safe[g]]
-                nr = rel_err(dg, dr)
-                w = WORST.get("weight movement", (0.0, 0.0))
-                WORST["weight movement"] = (max(w[0], nr / tol), 0.0)
-                assert RECORD_ONLY or nr < MOVE_FACTOR * tol, ("weight movement", g, t, nr)
-            else:
+            if not moved[g]:
                 assert np.array_equal(got, w0[g]), ("group moved before its first gradient", g, t)
+                continue
+            assert np.all(np.isfinite(got)), ("weights", g, t)
+            diff = np.abs(got - ref)
+            allow = budget[g] + 1e-6 * np.abs(ref)               # + fp32 rounding of the master weights
+            excess = float(np.max(diff / np.maximum(allow, 1e-300)))
+            # the movement itself in the norm: against the size of the weights a lost update hides under tol
+            nr = rel_err(got - w0[g], ref - w0[g])
+            record("weights", nr / tol, excess)
+            if not RECORD_ONLY:
+                assert excess <= 1.0, ("weights", g, t, "element", int(np.argmax(diff / np.maximum(allow, 1e-300))), excess)
+                assert nr < MOVE_FACTOR * tol, ("weight movement", g, t, nr)
         if c.get("mem_len", 0):
             for l in range(c["n_layer"]):
                 mem = m.get_mems(l)
@@ -174,13 +222,12 @@ def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=
     m.close()
 
 
-# Bound on the relative error of the weight movement w_t - w_0 (norm ratio, in units of tol).  SGD:
-# the movement is a sum of gradients, so the gradients' own bound applies with a little slack for
-# the bf16 working copy that later iterations see.  Adam at the first real step moves every
-# element by lr * sign(g), whatever |g| is; afterwards the step depends on ratios of gradients of
-# different iterations, each with its own rounding noise, and the elements kept by the mask have
-# |g| down to a tenth of the tensor's RMS, where a noise of tol/4 of the RMS is a quarter of the
-# value: several times tol in the norm.
+# Bound on the relative error of the whole group's movement w_t - w_0 (norm ratio, in units of
+# tol).  SGD: the movement is a sum of gradients, so the gradients' own bound applies with a little
+# slack for the bf16 working copy that later iterations see.  Adam moves every element by about lr
+# per iteration whatever |g| is, so the few per cent of elements whose gradient is below the
+# rounding noise (ill-conditioned steps, see ADAM_CAP) weigh as much in the norm as all others:
+# several times tol.
 MOVE_FACTOR = 10.0
 
 
