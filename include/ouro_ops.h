@@ -64,7 +64,20 @@ int ouro_op_gemm_dropout(void* stream, int dtype, int transA, int transB, int M,
                          const void* residual, int ldr, float p, uint64_t seed, uint32_t stream_id, int drop_ld,
                          int force_generic);
 
+/* C = op(A) op(B) + bias + R, the form of the two contractions of a block that close a residual
+ * connection, with the residual taken from fp32: R[m,n] = res32[m,n] when mean is NULL, else the
+ * LayerNorm of res32 recomputed in place, (res32[m,n] - mean[m]) * rstd[m] * g[n] + b[n] (a block's
+ * input is the LayerNorm of the sum before it; its stored, rounded copy is only the contraction
+ * operand).  res32 fp32 [M, ldr32]; mean, rstd fp32 [M]; g, b fp32 [N]; C type T or fp32 (out_fp32). */
+int ouro_op_gemm_ln_residual(void* stream, int dtype, int transA, int transB, int M, int N, int K,
+                             const void* A, int lda, const void* B, int ldb, void* C, int ldc, int out_fp32,
+                             const float* bias, const float* res32, int ldr32, const float* mean,
+                             const float* rstd, const float* g, const float* b, int force_generic);
+
 /* y = (x-mean)*rstd*g + b over rows of d (biased variance, eps 1e-5); g, b, mean, rstd fp32.
+ * The two LayerNorm calls also take dtype 2: rows read (x, and dy in the backward call) are fp32,
+ * rows written (y, dx) bf16 -- the form the bf16 model runs, whose sums entering a LayerNorm and
+ * whose gradients of the normalised rows stay in fp32.
  * dn in (0, d): the statistics run over the first dn columns only and the other d-dn columns are
  * zero padding (x, g, b zero there; y then is zero there too).  dn = 0 means dn = d. */
 int ouro_op_layernorm_fwd(void* stream, int dtype, const void* x, const float* g, const float* b,

@@ -94,6 +94,8 @@ def lib():
         "ouro_op_dropout": (i32, [vp, i32, vp, vp, i32, i32, i32, f32, C.c_uint64, C.c_uint32, i32]),
         "ouro_op_gemm_dropout": (i32, [vp, i32, i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32, vp, vp, i32, f32,
                                        C.c_uint64, C.c_uint32, i32, i32]),
+        "ouro_op_gemm_ln_residual": (i32, [vp, i32, i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32, i32, vp, vp, i32, vp,
+                                           vp, vp, vp, i32]),
         "ouro_op_layernorm_fwd": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32]),
         "ouro_op_layernorm_bwd": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32]),
         "ouro_op_colsum": (i32, [vp, i32, vp, i32, vp, i32, i32]),
@@ -328,7 +330,8 @@ class Model:
         check(self.L.ouro_debug_set_overlap(self.h, int(on)))
 
     def timing_read(self, kind):
-        """(ms, launches, work): kind 0 = MFMA contraction kernel (flops), 1 = update kernel (bytes)."""
+        """(ms, launches, work) since the last read: kind 0 = MFMA contraction kernel (flops), 1 = update
+        kernel (bytes), 2 = attention (flops), 3 = LayerNorm (bytes), 4 = cross-entropy row pass (bytes)."""
         ms, n, w = C.c_double(), C.c_int64(), C.c_double()
         check(self.L.ouro_debug_timing_read(self.h, kind, C.byref(ms), C.byref(n), C.byref(w)))
         return ms.value, n.value, w.value

@@ -89,6 +89,12 @@ struct GemmDesc {
   const float* bias;     // [N] or null
   const void* residual;  // [M, ldr] element type T, or null
   int ldr;
+  // fp32 residual instead (residual must be null): res32 [M, ldr32].  With ln_mean set the residual is
+  // the LayerNorm of res32 recomputed in place, (res32[m,n] - ln_mean[m]) * ln_rstd[m] * ln_g[n] + ln_b[n]:
+  // a block's input is the LayerNorm of the sum before it, and adding it back from that fp32 sum keeps
+  // the bf16 rounding of the LayerNorm's stored output (the contraction operand) off the residual path.
+  const float* res32; int ldr32;
+  const float* ln_mean; const float* ln_rstd; const float* ln_g; const float* ln_b;
   int epilogue;
   void* Z; int ldz;      // EPI_GELU: written (type T); EPI_GELUGRAD: read (type T)
   float alpha;           // scales acc before the epilogue
@@ -139,12 +145,16 @@ hipError_t launch_attn_bwd(hipStream_t s, int dtype, const AttnDesc& a, int forc
 // Rows are d wide; the statistics run over the first dn columns (dn = 0: all d).  With dn < d the
 // remaining columns are zero padding: they must hold zero scale and shift, and the input
 // gradient is written as zero there.
+// dtype of the LayerNorm launchers: 0 fp32 rows, 1 bf16 rows, 2 fp32 rows read (x, dy) and bf16 rows
+// written (y, dx): the form bf16 models use, whose pre-normalisation sums and the gradients of the
+// normalised rows stay in fp32 (they are the path every layer's rounding error travels along).
 hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, const void* x, const float* g, const float* b,
                                 void* y, float* mean, float* rstd, int rows, int d, int dn = 0);
 // dx from dy, x, stats; dg/db (fp32) are accumulated into (caller zeroes). dg == nullptr: dx only.
+// fuse_params: dg, db come from the kernel that writes dx (one pass over dy and x instead of two).
 hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const float* g,
                                 const float* mean, const float* rstd, void* dx, float* dg, float* db,
-                                int rows, int d, int dn = 0);
+                                int rows, int d, int dn = 0, bool fuse_params = false);
 // dg[c] += sum_r dy*xhat, db[c] += sum_r dy alone (any stream that sees dy, x and the stats)
 hipError_t launch_layernorm_bwd_params(hipStream_t s, int dtype, const void* dy, const void* x, const float* mean,
                                        const float* rstd, float* dg, float* db, int rows, int d);
@@ -155,7 +165,7 @@ hipError_t launch_colsum(hipStream_t s, int dtype, const void* x, int ldx, float
 hipError_t launch_embed_fwd(hipStream_t s, int dtype, const int32_t* tok, const void* V, const float* pe,
                             void* h, int N, int T, int d, int vocab, float scale, int* flag,
                             const DropDesc* drop = nullptr);
-// dVi[tok[n],:] += scale * dh[n,:]   (fp32 atomics; caller zeroes dVi)
+// dVi[tok[n],:] += scale * dh[n,:]   (fp32 atomics; caller zeroes dVi); dtype: type of dh (1 bf16, else fp32)
 hipError_t launch_embed_bwd(hipStream_t s, int dtype, const int32_t* tok, const void* dh, float* dVi,
                             int N, int d, int vocab, float scale, const DropDesc* drop = nullptr);
 // One matrix of a parameter blob to be kept transposed as well: bf16 [rows, cols] at element offset

@@ -198,6 +198,8 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
   p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
   p.out_fp32 = g.out_fp32; p.accumulate = g.accumulate;
   p.bias = g.bias; p.residual = g.residual; p.ldr = g.ldr;
+  p.res32 = g.res32; p.ldr32 = g.ldr32; p.ln_mean = g.ln_mean; p.ln_rstd = g.ln_rstd; p.ln_g = g.ln_g; p.ln_b = g.ln_b;
+  if (g.res32 && (g.residual || g.accumulate || (g.ln_mean && !(g.ln_rstd && g.ln_g && g.ln_b)))) return hipErrorInvalidValue;
   p.epilogue = g.epilogue; p.Z = g.Z; p.ldz = g.ldz; p.alpha = g.alpha;
   p.drop = g.drop;
   p.kchunk = g.K; p.tilesN = 0; p.vec_epi = 0;
@@ -206,6 +208,7 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
   if (force_generic != 1 && gemm_uses_mfma(dtype, g)) {
     const int oe = g.out_fp32 ? 3 : 7;   // ldc granularity for 16-byte row chunks
     p.vec_epi = aligned16(g.C) && !(g.ldc & oe) && (!g.residual || (aligned16(g.residual) && !(g.ldr & 7))) &&
+                (!g.res32 || (aligned16(g.res32) && !(g.ldr32 & 3))) &&
                 (g.epilogue == EPI_NONE || (aligned16(g.Z) && !(g.ldz & 7)));
     int cfg = force_generic >= 2 ? force_generic : -1;
     if (cfg < 0) {

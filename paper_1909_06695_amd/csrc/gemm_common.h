@@ -11,6 +11,8 @@ struct GemmParams {
   int out_fp32, accumulate;
   const float* bias;
   const void* residual; int ldr;
+  const float* res32; int ldr32;
+  const float* ln_mean; const float* ln_rstd; const float* ln_g; const float* ln_b;
   int epilogue;
   void* Z; int ldz;
   float alpha;
@@ -37,6 +39,11 @@ __device__ __forceinline__ void epilogue_store(const GemmParams& p, int m, int n
     v *= gelu_grad_f(to_f32(reinterpret_cast<const T*>(p.Z)[(size_t)m * p.ldz + n]));
   }
   if (p.residual) v += to_f32(reinterpret_cast<const T*>(p.residual)[(size_t)m * p.ldr + n]);
+  if (p.res32) {
+    float r = p.res32[(size_t)m * p.ldr32 + n];
+    if (p.ln_mean) r = (r - p.ln_mean[m]) * p.ln_rstd[m] * p.ln_g[n] + p.ln_b[n];
+    v += r;
+  }
   if (p.out_fp32) reinterpret_cast<float*>(p.C)[(size_t)m * p.ldc + n] = v;
   else reinterpret_cast<T*>(p.C)[(size_t)m * p.ldc + n] = from_f32<T>(v);
 }
@@ -73,6 +80,18 @@ __device__ __forceinline__ void epilogue_store8(const GemmParams& p, int m, int 
     r.u = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.residual) + (size_t)m * p.ldr + n);
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] += (float)r.h[e];
+  }
+  if (p.res32) {
+    const float4* rp = reinterpret_cast<const float4*>(p.res32 + (size_t)m * p.ldr32 + n);
+    const float4 lo = rp[0], hi = rp[1];
+    float r[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    if (p.ln_mean) {
+      const float mu = p.ln_mean[m], rs = p.ln_rstd[m];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) r[e] = (r[e] - mu) * rs * p.ln_g[n + e] + p.ln_b[n + e];
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] += r[e];
   }
   if (p.out_fp32) {
     float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + (size_t)m * p.ldc + n);

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -116,11 +117,11 @@ struct LayerBuf {   // saved activations of one layer (element type T unless not
   char* cat;        // [B, Mv+T, d] memory ; input (relative mode with memory)
   char* qkv;        // plain: [N, 3d]; relative: q [N, d] then kv [B*S, 2d]
   char* a;          // attention output before W_o [N, d]
-  char* s1;         // x + a W_o  [N, d]
+  char* s1;         // x + a W_o  [N, d], fp32 in every mode (see lnk)
   char* y;          // LN1 output [N, d]
   char* z;          // FFN pre-activation [N, F]
   char* uact;       // GELU(z) [N, F]
-  char* s2;         // y + FFN [N, d]
+  char* s2;         // y + FFN [N, d], fp32
   char* r;          // W_r-projected distance table [S, d]
   char* mem;        // segment memory [B, Mv, d] (stored-input schedule: the ring slot in use)
   char* memring;    // stored-input schedule: the memories of iterations t-(K-k) .. t+1, slot = iteration mod memdepth
@@ -154,11 +155,11 @@ struct BwdCtx {
   hipEvent_t ev_join;
   hipEvent_t ev_done;          // sets 1..: this module's backward pass and update are enqueued up to here
   // backward scratch
-  char *dhb[3], *dy[2], *da, *dcat, *dr_t[2];   // layer l reads dhb[l % 3], writes dhb[(l + 2) % 3]
+  char *dhb[3], *dy[2], *da, *dcat, *dr_t[2];   // layer l reads dhb[l % 3], writes dhb[(l + 2) % 3]; dhb and dy are fp32
   // gradients that the weight-gradient GEMMs read on the side stream: two sets, by layer parity
   char *ds2[2], *dz[2], *ds1[2], *dqkv[2];
   char *ds2m[2], *ds1m[2];         // ds2 / ds1 times the dropout masks (the same buffers without dropout)
-  float *attn_scratch, *dr_f32[2], *dh_f32;
+  float *attn_scratch, *dr_f32[2];
   char* hscratch;                 // output of a recomputed module's last layer (never read)
 };
 
@@ -234,6 +235,7 @@ struct ouro_model : BwdCtx {
   int mem_valid;                  // valid rows in every layer memory
   const int32_t* tok;
   const int32_t* tgt;
+  bool ln_fused;               // LayerNorm scale / shift gradients from the kernel that writes the input gradient
   bool use_side;               // run gradient-only work beside the error-gradient chain (BwdCtx::side)
   // A third stream carries (inside ouro_step) the update of a module as soon as its backward
   // pass is done, beside the backward of the modules below.
@@ -409,7 +411,7 @@ static size_t lay_out(ouro_model& m, char* base) {
       m.indepth[k] = K - k + 1;
       m.instride[k] = ((k == 1 ? N * 4 : N * d * es) + 255) & ~(size_t)255;
       m.inring[k] = P(m.instride[k] * (size_t)m.indepth[k]);
-      for (int p2 = 0; p2 < 2; ++p2) m.mail[p2][k] = P(N * d * es);
+      for (int p2 = 0; p2 < 2; ++p2) m.mail[p2][k] = P(N * d * 4);
     }
   }
   m.persist_end = bp.off;
@@ -421,11 +423,11 @@ static size_t lay_out(ouro_model& m, char* base) {
     b.cat = (M > 0) ? P(B * S * d * es) : nullptr;
     b.qkv = P(qkv_elems * es);
     b.a = P(N * hd * es);
-    b.s1 = P(N * d * es);
+    b.s1 = P(N * d * 4);
     b.y = P(N * d * es);
     b.z = P(N * F * es);
     b.uact = P(N * F * es);
-    b.s2 = P(N * d * es);
+    b.s2 = P(N * d * 4);
     b.r = c.rel_pos ? P(S * hd * es) : nullptr;
     b.memring = nullptr; b.memstride = 0; b.memdepth = 0;
     if (M > 0 && c.schedule == 1) {
@@ -453,8 +455,8 @@ static size_t lay_out(ouro_model& m, char* base) {
   m.flag = (int*)P(256);
   // backward scratch: one set, or one per module under the stored-input schedule
   auto scratch = [&](BwdCtx& x) {
-    for (int i = 0; i < 3; ++i) x.dhb[i] = P(N * d * es);
-    x.dy[0] = P(N * d * es); x.dy[1] = P(N * d * es); x.da = P(N * hd * es);
+    for (int i = 0; i < 3; ++i) x.dhb[i] = P(N * d * 4);
+    x.dy[0] = P(N * d * 4); x.dy[1] = P(N * d * 4); x.da = P(N * hd * es);
     for (int p2 = 0; p2 < 2; ++p2) {
       x.ds2[p2] = P(N * d * es); x.dz[p2] = P(N * F * es);
       x.ds1[p2] = P(N * d * es); x.dqkv[p2] = P(qkv_elems * es);
@@ -467,7 +469,6 @@ static size_t lay_out(ouro_model& m, char* base) {
       x.dr_f32[p2] = c.rel_pos ? (float*)P(S * hd * 4) : nullptr;
     }
     x.attn_scratch = (float*)P(attn_bwd_scratch_floats(c.batch, c.n_head, c.seq_len, (int)S, m.pdh) * 4);
-    x.dh_f32 = c.dtype == 1 ? (float*)P(N * d * 4) : nullptr;
     x.hscratch = c.schedule == 1 ? P(N * d * es) : nullptr;
   };
   scratch(m);
@@ -543,6 +544,7 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
   m->eval_mode = false; m->cur_seed = cfg->seed;
   for (int i = 0; i < OURO_TIMING_KINDS; ++i) { m->ev_used[i] = 0; m->timed_work[i] = 0; m->timed_launches[i] = 0; }
   m->side = nullptr; m->use_side = false; m->ev_join = nullptr;
+  m->ln_fused = getenv("OURO_LN_SPLIT") == nullptr;
   m->aux = nullptr; m->ev_bwd_done = m->ev_upd_done = nullptr; m->upd_pending = false;
   for (int i = 0; i < 4; ++i) m->ev_ready[i] = nullptr;
   for (int i = 0; i < 2; ++i) { m->ev_side_done[i] = nullptr; m->side_busy[i] = false; }
@@ -774,8 +776,10 @@ static void select_memory(ouro_model* m, int l, int64_t t) {
   if (b.memring) b.mem = b.memring + (size_t)(t % b.memdepth) * b.memstride;
 }
 
-// out_override: where the layer's output goes instead of the next layer's input buffer
-static int layer_forward(ouro_model* m, int l, char* out_override = nullptr) {
+// out_override: where the layer's output goes instead of the next layer's input buffer.
+// x_is_ln_of_prev: the layer's input b.x is the stored (rounded) output of layer l-1's second LayerNorm
+// in this same pass, so the residual addition takes it unrounded from that layer's fp32 sum.
+static int layer_forward(ouro_model* m, int l, char* out_override = nullptr, bool x_is_ln_of_prev = false) {
   const ouro_config& c = m->cfg;
   const int d = m->pd, F = m->pF, hd = m->phd, dn = c.d_model;   // stored widths; dn = normalised width
   const int N = m->N, T = c.seq_len, B = c.batch, es = m->esz;
@@ -822,12 +826,23 @@ static int layer_forward(ouro_model* m, int l, char* out_override = nullptr) {
   RUN(timed_launch(m, OURO_TIMING_ATTENTION, attn_fwd_flops(m, Mv), m->stream, [&] { return launch_attn_fwd(m->stream, c.dtype, a, 0); }));
   {
     GemmDesc g = bt ? gd(b.a, hd, 0, m->wTt(l, o.W_o), hd, 1, b.s1, d, N, d, hd) : gd(b.a, hd, 0, m->wT(l, o.W_o), d, 0, b.s1, d, N, d, hd);
-    g.residual = b.x; g.ldr = d; g.drop = drop_at(m, 2 * l + 1);
+    if (x_is_ln_of_prev && l > 0) {
+      const LayerBuf& pb = m->L[l - 1];
+      const LayerOff& po = m->loff[l - 1];
+      g.res32 = (const float*)pb.s2; g.ldr32 = d; g.ln_mean = pb.mean2; g.ln_rstd = pb.rstd2;
+      g.ln_g = m->wF(l - 1, po.ln2_g); g.ln_b = m->wF(l - 1, po.ln2_b);
+    } else {
+      g.residual = b.x; g.ldr = d;
+    }
+    g.drop = drop_at(m, 2 * l + 1); g.out_fp32 = 1;
     RUN(run_gemm(m, g));
   }
-  const double ln_fwd_bytes = 2.0 * N * dn * es + 8.0 * N;      // row read, row written, two statistics per row
+  // The sums that enter a LayerNorm stay in fp32 (in bf16 mode too): every layer's rounding error travels
+  // along this path, and bf16 sums alone put the gradients of a 24-layer model at the 2e-2 bar.
+  const int lnk = c.dtype == 1 ? 2 : 0;
+  const double ln_fwd_bytes = (double)N * dn * (4 + es) + 8.0 * N;      // fp32 row read, row written, two statistics per row
   RUN(timed_launch(m, OURO_TIMING_LAYERNORM, ln_fwd_bytes, m->stream, [&] {
-    return launch_layernorm_fwd(m->stream, c.dtype, b.s1, m->wF(l, o.ln1_g), m->wF(l, o.ln1_b), b.y, b.mean1, b.rstd1, N, d, dn); }));
+    return launch_layernorm_fwd(m->stream, lnk, b.s1, m->wF(l, o.ln1_g), m->wF(l, o.ln1_b), b.y, b.mean1, b.rstd1, N, d, dn); }));
   {
     GemmDesc g = bt ? gd(b.y, d, 0, m->wTt(l, o.W_1), d, 1, b.uact, F, N, F, d) : gd(b.y, d, 0, m->wT(l, o.W_1), F, 0, b.uact, F, N, F, d);
     g.bias = m->wF(l, o.b_1); g.epilogue = EPI_GELU; g.Z = b.z; g.ldz = F;
@@ -835,11 +850,14 @@ static int layer_forward(ouro_model* m, int l, char* out_override = nullptr) {
   }
   {
     GemmDesc g = bt ? gd(b.uact, F, 0, m->wTt(l, o.W_2), F, 1, b.s2, d, N, d, F) : gd(b.uact, F, 0, m->wT(l, o.W_2), d, 0, b.s2, d, N, d, F);
-    g.bias = m->wF(l, o.b_2); g.residual = b.y; g.ldr = d; g.drop = drop_at(m, 2 * l + 2);
+    g.bias = m->wF(l, o.b_2);
+    g.res32 = (const float*)b.s1; g.ldr32 = d; g.ln_mean = b.mean1; g.ln_rstd = b.rstd1;      // y, unrounded
+    g.ln_g = m->wF(l, o.ln1_g); g.ln_b = m->wF(l, o.ln1_b);
+    g.drop = drop_at(m, 2 * l + 2); g.out_fp32 = 1;
     RUN(run_gemm(m, g));
   }
   RUN(timed_launch(m, OURO_TIMING_LAYERNORM, ln_fwd_bytes, m->stream, [&] {
-    return launch_layernorm_fwd(m->stream, c.dtype, b.s2, m->wF(l, o.ln2_g), m->wF(l, o.ln2_b), out, b.mean2, b.rstd2, N, d, dn); }));
+    return launch_layernorm_fwd(m->stream, lnk, b.s2, m->wF(l, o.ln2_g), m->wF(l, o.ln2_b), out, b.mean2, b.rstd2, N, d, dn); }));
   return OURO_OK;
 }
 
@@ -868,7 +886,7 @@ extern "C" int ouro_module_forward(ouro_model* m, int k, const int32_t* dev_toke
     m->intags[k][slot] = m->t;
   }
   for (int l = m->first_layer[k - 1]; l < m->first_layer[k]; ++l) {
-    RUN(layer_forward(m, l));
+    RUN(layer_forward(m, l, nullptr, l > 0));       // layer l-1 ran earlier in this forward pass
     LayerBuf& b = m->L[l];
     if (b.memring) {
       // the memory of iteration t+1 = last M rows of [memory ; layer input], taken now: the
@@ -896,13 +914,13 @@ extern "C" int ouro_module_forward(ouro_model* m, int k, const int32_t* dev_toke
 
 // ----------------------------------------------------------------------------- backward
 template <typename T>
-__global__ void add_rows_kernel(T* dst, size_t dst_bstride, const T* src, size_t src_bstride, size_t src_off, size_t n) {
+__global__ void add_rows_kernel(float* dst, size_t dst_bstride, const T* src, size_t src_bstride, size_t src_off, size_t n) {
   const int b = blockIdx.y;
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (; i < n; i += stride) {
     size_t di = b * dst_bstride + i;
-    dst[di] = from_f32<T>(to_f32(dst[di]) + to_f32(src[b * src_bstride + src_off + i]));
+    dst[di] += to_f32(src[b * src_bstride + src_off + i]);
   }
 }
 
@@ -932,13 +950,16 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   };
   // LN2
   // with the side stream the scale/shift gradients (column sums over dh and s2) run there too
-  const double ln_bwd_bytes = 3.0 * N * dn * es + 8.0 * N;      // gradient and input rows read, one row written, statistics
+  // dh, dy (gradients of the normalised rows) and the saved sums s1, s2 are fp32 in every mode
+  const int lnk = c.dtype == 1 ? 2 : 0;
+  const bool lnp_side = side && !m->ln_fused;         // scale / shift gradients as a kernel of their own on the side stream
+  const double ln_bwd_bytes = (double)N * dn * (8 + es) + 8.0 * N;      // fp32 gradient and input rows read, one row written, statistics
   RUN(timed_launch(m, OURO_TIMING_LAYERNORM, ln_bwd_bytes, st, [&] {
-    return launch_layernorm_bwd(st, c.dtype, dh, b.s2, m->wF(l, o.ln2_g), b.mean2, b.rstd2, ds2,
-                                side ? nullptr : gslot + o.ln2_g, gslot + o.ln2_b, N, d, dn); }));
+    return launch_layernorm_bwd(st, lnk, dh, b.s2, m->wF(l, o.ln2_g), b.mean2, b.rstd2, ds2,
+                                lnp_side ? nullptr : gslot + o.ln2_g, gslot + o.ln2_b, N, d, dn, m->ln_fused); }));
   if (dropping) HIPCHK(launch_dropout_apply(st, c.dtype, ds2, ds2m, N, d, d, drop_at(m, 2 * l + 2)));
   RUN(ready(0));
-  if (side) HIPCHK(launch_layernorm_bwd_params(sw, c.dtype, dh, b.s2, b.mean2, b.rstd2, gslot + o.ln2_g, gslot + o.ln2_b, N, d));
+  if (lnp_side) HIPCHK(launch_layernorm_bwd_params(sw, lnk, dh, b.s2, b.mean2, b.rstd2, gslot + o.ln2_g, gslot + o.ln2_b, N, d));
   // FFN2
   {
     GemmDesc g = gd(b.uact, F, 1, ds2m, d, 0, gslot + o.W_2, d, F, d, N);
@@ -961,16 +982,16 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   HIPCHK(launch_colsum(sw, c.dtype, dz, F, gslot + o.b_1, N, F));
   {
     GemmDesc g = gd(dz, F, 0, m->wT(l, o.W_1), F, 1, dy, d, N, d, F);
-    g.residual = ds2; g.ldr = d;
+    g.residual = ds2; g.ldr = d; g.out_fp32 = 1;
     RUN(run_gemm(m, g));
   }
   // LN1
   RUN(timed_launch(m, OURO_TIMING_LAYERNORM, ln_bwd_bytes, st, [&] {
-    return launch_layernorm_bwd(st, c.dtype, dy, b.s1, m->wF(l, o.ln1_g), b.mean1, b.rstd1, ds1,
-                                side ? nullptr : gslot + o.ln1_g, gslot + o.ln1_b, N, d, dn); }));
+    return launch_layernorm_bwd(st, lnk, dy, b.s1, m->wF(l, o.ln1_g), b.mean1, b.rstd1, ds1,
+                                lnp_side ? nullptr : gslot + o.ln1_g, gslot + o.ln1_b, N, d, dn, m->ln_fused); }));
   if (dropping) HIPCHK(launch_dropout_apply(st, c.dtype, ds1, ds1m, N, d, d, drop_at(m, 2 * l + 1)));
   RUN(ready(2));
-  if (side) HIPCHK(launch_layernorm_bwd_params(sw, c.dtype, dy, b.s1, b.mean1, b.rstd1, gslot + o.ln1_g, gslot + o.ln1_b, N, d));
+  if (lnp_side) HIPCHK(launch_layernorm_bwd_params(sw, lnk, dy, b.s1, b.mean1, b.rstd1, gslot + o.ln1_g, gslot + o.ln1_b, N, d));
   // output projection
   {
     GemmDesc g = gd(b.a, hd, 1, ds1m, d, 0, gslot + o.W_o, d, hd, d, N);
@@ -1000,7 +1021,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     }
     {
       GemmDesc g = gd(dqkv, 3 * hd, 0, m->wT(l, o.W_qkv), 3 * hd, 1, dx, d, N, d, 3 * hd);
-      g.residual = ds1; g.ldr = d;
+      g.residual = ds1; g.ldr = d; g.out_fp32 = 1;
       RUN(run_gemm(m, g));
     }
   } else {
@@ -1037,7 +1058,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     }
     {
       GemmDesc g = gd(dq, hd, 0, m->wT(l, o.W_qkv), 3 * hd, 1, dx, d, N, d, hd);
-      g.residual = ds1; g.ldr = d;
+      g.residual = ds1; g.ldr = d; g.out_fp32 = 1;
       RUN(run_gemm(m, g));
     }
     // the memory rows are constants: only the current rows of d[mem ; x] reach dx
@@ -1045,7 +1066,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     {
       size_t n = (size_t)T * d;
       dim3 grid((unsigned)std::min<size_t>((n + 255) / 256, 1024), B), block(256);
-      if (c.dtype == 1) hipLaunchKernelGGL(add_rows_kernel<bf16_t>, grid, block, 0, st, (bf16_t*)dx, n, (const bf16_t*)m->dcat, (size_t)S * d, (size_t)Mv * d, n);
+      if (c.dtype == 1) hipLaunchKernelGGL(add_rows_kernel<bf16_t>, grid, block, 0, st, (float*)dx, n, (const bf16_t*)m->dcat, (size_t)S * d, (size_t)Mv * d, n);
       else hipLaunchKernelGGL(add_rows_kernel<float>, grid, block, 0, st, (float*)dx, n, (const float*)m->dcat, (size_t)S * d, (size_t)Mv * d, n);
       HIPCHK(hipGetLastError());
     }
@@ -1095,7 +1116,7 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
     m->mem_valid = mem_valid_at(m, tau);            // this module works on iteration tau's memories
     for (int l = first; l <= last; ++l) {
       select_memory(m, l, tau);
-      RUN(layer_forward(m, l, l == last ? m->hscratch : nullptr));
+      RUN(layer_forward(m, l, l == last ? m->hscratch : nullptr, l > first));   // the first layer's input is the stored one
     }
     // error gradient of this module's output, left by module k+1 one iteration ago
     const int pr = (int)((m->t + 1) & 1);
@@ -1122,14 +1143,13 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
     m->tags[K + 1][0] = m->t;
     GemmDesc gh = c.dtype == 1 ? gd(m->G, m->ldv, 0, (const char*)m->shadowT[0], m->ldv, 1, dh_top, d, N, d, Vx)
                                : gd(m->G, m->ldv, 0, m->vT(), d, 0, dh_top, d, N, d, Vx);
+    gh.out_fp32 = 1;                                  // the error gradient between layers is fp32
     if (c.dtype == 1 && gemm_uses_mfma(c.dtype, gh) && V >= 8192) {
       // The contraction runs over the whole vocabulary onto a narrow output: split it over
-      // the grid (two workgroups per CU instead of one), adding into an fp32 buffer that is
-      // then rounded to the activation type.
-      HIPCHK(launch_fill_zero(m->stream, m->dh_f32, (size_t)N * d * 4));
-      gh.C = m->dh_f32; gh.out_fp32 = 1; gh.accumulate = 1;
+      // the grid (two workgroups per CU instead of one), adding into the zeroed fp32 result.
+      HIPCHK(launch_fill_zero(m->stream, dh_top, (size_t)N * d * 4));
+      gh.accumulate = 1;
       RUN(run_gemm(m, gh));
-      HIPCHK(launch_convert(m->stream, c.dtype, dh_top, m->dh_f32, (size_t)N * d));
     } else {
       RUN(run_gemm(m, gh));
     }
@@ -1164,7 +1184,7 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
     float* dvi = m->slot_ptr(0, s0);
     HIPCHK(launch_fill_zero(m->stream, dvi, (size_t)m->gstride[0] * 4));
     const DropDesc dd = drop_at(m, 0);
-    HIPCHK(launch_embed_bwd(m->stream, c.dtype, tok, m->dhb[2], dvi, N, d, V, c.emb_scale, &dd));
+    HIPCHK(launch_embed_bwd(m->stream, 0, tok, m->dhb[2], dvi, N, d, V, c.emb_scale, &dd));   // dh is fp32
     m->tags[0][s0] = m->t;
   }
   m->cur_seed = c.seed + (uint64_t)m->t;

@@ -43,6 +43,18 @@ extern "C" int ouro_op_gemm_dropout(void* stream, int dtype, int transA, int tra
   return rc_of(launch_gemm((hipStream_t)stream, dtype, g, force_generic));
 }
 
+extern "C" int ouro_op_gemm_ln_residual(void* stream, int dtype, int transA, int transB, int M, int N, int K, const void* A,
+                                        int lda, const void* B, int ldb, void* C, int ldc, int out_fp32, const float* bias,
+                                        const float* res32, int ldr32, const float* mean, const float* rstd, const float* g,
+                                        const float* b, int force_generic) {
+  if (!A || !B || !C || !res32 || M < 0 || N < 0 || K < 0 || ldr32 < N) return OURO_E_ARG;
+  if (mean && (!rstd || !g || !b)) return OURO_E_ARG;
+  if (lda < (transA ? M : K) || ldb < (transB ? K : N) || ldc < N) return OURO_E_ARG;
+  GemmDesc gd = make_gemm(transA, transB, M, N, K, 1.f, A, lda, B, ldb, C, ldc, out_fp32, 0, bias, nullptr, 0, EPI_NONE, nullptr, 0);
+  gd.res32 = res32; gd.ldr32 = ldr32; gd.ln_mean = mean; gd.ln_rstd = rstd; gd.ln_g = g; gd.ln_b = b;
+  return rc_of(launch_gemm((hipStream_t)stream, dtype, gd, force_generic));
+}
+
 extern "C" int ouro_op_dropout(void* stream, int dtype, const void* src, void* dst, int rows, int cols, int ld,
                                float p, uint64_t seed, uint32_t stream_id, int drop_ld) {
   if (!src || !dst || rows < 0 || cols < 0 || ld < cols || !(p >= 0.f && p < 1.f) || drop_ld < cols) return OURO_E_ARG;
@@ -104,17 +116,17 @@ extern "C" int ouro_op_attention_bwd(void* stream, int dtype, int B, int H, int 
 
 extern "C" int ouro_op_layernorm_fwd(void* stream, int dtype, const void* x, const float* g, const float* b, void* y,
                                      float* mean, float* rstd, int rows, int d, int dn) {
-  if (!x || !g || !b || !y || !mean || !rstd || rows < 0 || d < 1 || dn < 0 || dn > d) return OURO_E_ARG;
+  if (!x || !g || !b || !y || !mean || !rstd || rows < 0 || d < 1 || dn < 0 || dn > d || dtype < 0 || dtype > 2) return OURO_E_ARG;
   return rc_of(launch_layernorm_fwd((hipStream_t)stream, dtype, x, g, b, y, mean, rstd, rows, d, dn));
 }
 
 extern "C" int ouro_op_layernorm_bwd(void* stream, int dtype, const void* dy, const void* x, const float* g,
                                      const float* mean, const float* rstd, void* dx, float* dg, float* db, int rows,
                                      int d, int dn) {
-  if (!dy || !x || !g || !mean || !rstd || !dx || !dg || !db || rows < 0 || d < 1 || dn < 0 || dn > d) return OURO_E_ARG;
+  if (!dy || !x || !g || !mean || !rstd || !dx || !dg || !db || rows < 0 || d < 1 || dn < 0 || dn > d || dtype < 0 || dtype > 2) return OURO_E_ARG;
   hipStream_t s = (hipStream_t)stream;
   if (launch_fill_zero(s, dg, (size_t)d * 4) != hipSuccess || launch_fill_zero(s, db, (size_t)d * 4) != hipSuccess) return OURO_E_HIP;
-  return rc_of(launch_layernorm_bwd(s, dtype, dy, x, g, mean, rstd, dx, dg, db, rows, d, dn));
+  return rc_of(launch_layernorm_bwd(s, dtype, dy, x, g, mean, rstd, dx, dg, db, rows, d, dn, true));
 }
 
 extern "C" int ouro_op_colsum(void* stream, int dtype, const void* x, int ldx, float* out, int rows, int cols) {

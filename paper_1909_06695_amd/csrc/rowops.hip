@@ -34,14 +34,28 @@ template <> __device__ __forceinline__ void store_pack<bf16_t>(bf16_t* p, const 
   *reinterpret_cast<uint4*>(p) = u.v;
 }
 
+// N consecutive elements (N = 4 or 8) in 16-byte accesses: a group of 8 fp32 takes two of them
+template <typename T, int N> __device__ __forceinline__ void load_n(const T* p, float* out) {
+  if constexpr (sizeof(T) == 4 && N == 8) { load_pack<T>(p, out); load_pack<T>(p + 4, out + 4); }
+  else { static_assert(Pack<T>::N == N, "group size"); load_pack<T>(p, out); }
+}
+template <typename T, int N> __device__ __forceinline__ void store_n(T* p, const float* in) {
+  if constexpr (sizeof(T) == 4 && N == 8) { store_pack<T>(p, in); store_pack<T>(p + 4, in + 4); }
+  else { static_assert(Pack<T>::N == N, "group size"); store_pack<T>(p, in); }
+}
+// Elements per lane group of a row kernel whose operands have the types A and B: 8 as soon as one
+// of them is bf16 (its 16-byte pack), else 4.
+template <typename A, typename B> struct Group { static constexpr int N = (sizeof(A) == 2 || sizeof(B) == 2) ? 8 : 4; };
+
 // ------------------------------------------------------------------------ LayerNorm fwd
-// One wavefront per row.  VEC: row held in registers as up to MAXI 16-byte packs per lane.
-template <typename T, int MAXI>
-__global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const T* __restrict__ x, const float* __restrict__ g,
-                                                         const float* __restrict__ b, T* __restrict__ y,
+// One wavefront per row.  VEC: row held in registers as up to MAXI groups per lane.  TX: type of
+// the rows read (the pre-normalisation sums: fp32 in bf16 models), TY: type of the rows written.
+template <typename TX, typename TY, int MAXI>
+__global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const TX* __restrict__ x, const float* __restrict__ g,
+                                                         const float* __restrict__ b, TY* __restrict__ y,
                                                          float* __restrict__ mean, float* __restrict__ rstd,
                                                          int rows, int d, int dn) {
-  constexpr int N = Pack<T>::N;
+  constexpr int N = Group<TX, TY>::N;
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -52,7 +66,7 @@ __global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const T* __restrict__ x
   for (int i = 0; i < MAXI; ++i) {
     int vi = lane + 64 * i;
     if (vi < nvec) {
-      load_pack<T>(x + (size_t)row * d + vi * N, v[i]);
+      load_n<TX, N>(x + (size_t)row * d + vi * N, v[i]);
 #pragma unroll
       for (int e = 0; e < N; ++e) s += v[i][e];
     }
@@ -76,20 +90,20 @@ __global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const T* __restrict__ x
       float out[N];
 #pragma unroll
       for (int e = 0; e < N; ++e) out[e] = (v[i][e] - mu) * rs * g[vi * N + e] + b[vi * N + e];
-      store_pack<T>(y + (size_t)row * d + vi * N, out);
+      store_n<TY, N>(y + (size_t)row * d + vi * N, out);
     }
   }
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void ln_fwd_scalar_kernel(const T* __restrict__ x, const float* __restrict__ g,
-                                                            const float* __restrict__ b, T* __restrict__ y,
+template <typename TX, typename TY>
+__global__ __launch_bounds__(256) void ln_fwd_scalar_kernel(const TX* __restrict__ x, const float* __restrict__ g,
+                                                            const float* __restrict__ b, TY* __restrict__ y,
                                                             float* __restrict__ mean, float* __restrict__ rstd,
                                                             int rows, int d, int dn) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
-  const T* xr = x + (size_t)row * d;
+  const TX* xr = x + (size_t)row * d;
   float s = 0.f;
   for (int c = lane; c < dn; c += 64) s += to_f32(xr[c]);
   const float mu = wave_sum(s) / dn;
@@ -98,40 +112,47 @@ __global__ __launch_bounds__(256) void ln_fwd_scalar_kernel(const T* __restrict_
   const float rs = rsqrtf(wave_sum(q) / dn + 1e-5f);
   if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
   for (int c = lane; c < d; c += 64)
-    y[(size_t)row * d + c] = from_f32<T>((to_f32(xr[c]) - mu) * rs * g[c] + b[c]);
+    y[(size_t)row * d + c] = from_f32<TY>((to_f32(xr[c]) - mu) * rs * g[c] + b[c]);
 }
 
+static inline bool ptr16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// dtype 0: fp32 rows in and out; 1: bf16 in and out; 2: fp32 rows in, bf16 rows out (bf16 models keep the
+// sums that enter a LayerNorm in fp32).
 hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, const void* x, const float* g, const float* b,
                                 void* y, float* mean, float* rstd, int rows, int d, int dn) {
   if (rows <= 0) return hipSuccess;
   if (dn <= 0 || dn > d) dn = d;
   dim3 grid((rows + 3) / 4), block(256);
-  if (dtype == 1) {
-    if (d % 8 == 0 && d / 8 <= 256)
-      hipLaunchKernelGGL((ln_fwd_vec_kernel<bf16_t, 4>), grid, block, 0, s, (const bf16_t*)x, g, b, (bf16_t*)y, mean, rstd, rows, d, dn);
-    else
-      hipLaunchKernelGGL(ln_fwd_scalar_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, g, b, (bf16_t*)y, mean, rstd, rows, d, dn);
-  } else {
-    if (d % 4 == 0 && d / 4 <= 256)
-      hipLaunchKernelGGL((ln_fwd_vec_kernel<float, 4>), grid, block, 0, s, (const float*)x, g, b, (float*)y, mean, rstd, rows, d, dn);
-    else
-      hipLaunchKernelGGL(ln_fwd_scalar_kernel<float>, grid, block, 0, s, (const float*)x, g, b, (float*)y, mean, rstd, rows, d, dn);
-  }
+  const int grp = dtype == 0 ? 4 : 8;
+  const bool vec = d % grp == 0 && d / grp <= 256 && ptr16(x) && ptr16(y);
+  const int npl = (d / grp + 63) / 64;
+#define OURO_LNF(TX_, TY_)                                                                                                                  \
+  do {                                                                                                                                      \
+    if (!vec) hipLaunchKernelGGL((ln_fwd_scalar_kernel<TX_, TY_>), grid, block, 0, s, (const TX_*)x, g, b, (TY_*)y, mean, rstd, rows, d, dn); \
+    else if (npl <= 1) hipLaunchKernelGGL((ln_fwd_vec_kernel<TX_, TY_, 1>), grid, block, 0, s, (const TX_*)x, g, b, (TY_*)y, mean, rstd, rows, d, dn); \
+    else if (npl <= 2) hipLaunchKernelGGL((ln_fwd_vec_kernel<TX_, TY_, 2>), grid, block, 0, s, (const TX_*)x, g, b, (TY_*)y, mean, rstd, rows, d, dn); \
+    else hipLaunchKernelGGL((ln_fwd_vec_kernel<TX_, TY_, 4>), grid, block, 0, s, (const TX_*)x, g, b, (TY_*)y, mean, rstd, rows, d, dn);  \
+  } while (0)
+  if (dtype == 1) OURO_LNF(bf16_t, bf16_t);
+  else if (dtype == 2) OURO_LNF(float, bf16_t);
+  else OURO_LNF(float, float);
+#undef OURO_LNF
   return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------ LayerNorm bwd
 // dx = rstd * (dyg - mean(dyg) - xhat * mean(dyg * xhat)), dyg = dy * g
-template <typename T>
-__global__ __launch_bounds__(256) void ln_bwd_dx_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+template <typename TI, typename TO>
+__global__ __launch_bounds__(256) void ln_bwd_dx_kernel(const TI* __restrict__ dy, const TI* __restrict__ x,
                                                         const float* __restrict__ g, const float* __restrict__ mean,
-                                                        const float* __restrict__ rstd, T* __restrict__ dx,
+                                                        const float* __restrict__ rstd, TO* __restrict__ dx,
                                                         int rows, int d, int dn) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
-  const T* xr = x + (size_t)row * d;
-  const T* dyr = dy + (size_t)row * d;
+  const TI* xr = x + (size_t)row * d;
+  const TI* dyr = dy + (size_t)row * d;
   const float mu = mean[row], rs = rstd[row];
   float s1 = 0.f, s2 = 0.f;
   for (int c = lane; c < d; c += 64) {
@@ -145,7 +166,7 @@ __global__ __launch_bounds__(256) void ln_bwd_dx_kernel(const T* __restrict__ dy
   for (int c = lane; c < d; c += 64) {
     float xh = (to_f32(xr[c]) - mu) * rs;
     float t = to_f32(dyr[c]) * g[c];
-    dx[(size_t)row * d + c] = from_f32<T>(c < dn ? rs * (t - s1 - xh * s2) : 0.f);
+    dx[(size_t)row * d + c] = from_f32<TO>(c < dn ? rs * (t - s1 - xh * s2) : 0.f);
   }
 }
 
@@ -191,13 +212,13 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, in
 // Vector path of the LayerNorm backward: one wavefront per row, rows strided over the grid;
 // the row's packs stay in registers, dg / db partial sums are kept per lane over all the
 // wave's rows, reduced over the block's four waves through LDS and added atomically once.
-template <typename T, int MAXI, bool PARAMS>
-__global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+template <typename TI, typename TO, int MAXI, bool PARAMS>
+__global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const TI* __restrict__ dy, const TI* __restrict__ x,
                                                            const float* __restrict__ g, const float* __restrict__ mean,
-                                                           const float* __restrict__ rstd, T* __restrict__ dx,
+                                                           const float* __restrict__ rstd, TO* __restrict__ dx,
                                                            float* __restrict__ dg, float* __restrict__ db, int rows, int d,
                                                            int dn) {
-  constexpr int N = Pack<T>::N;
+  constexpr int N = Group<TI, TO>::N;
   extern __shared__ float red[];                 // [4][d]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nvec = d / N;
@@ -225,8 +246,8 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* __restrict__
         for (int i = 0; i < MAXI; ++i) {
           int vi = lane + 64 * i;
           if (vi < nvec) {
-            load_pack<T>(x + (size_t)row * d + vi * N, xh[u][i]);
-            load_pack<T>(dy + (size_t)row * d + vi * N, t[u][i]);
+            load_n<TI, N>(x + (size_t)row * d + vi * N, xh[u][i]);
+            load_n<TI, N>(dy + (size_t)row * d + vi * N, t[u][i]);
           }
         }
       }
@@ -262,7 +283,7 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* __restrict__
           float out[N];
 #pragma unroll
           for (int e = 0; e < N; ++e) out[e] = vi * N + e < dn ? rs[u] * (t[u][i][e] - s1 - xh[u][i][e] * s2) : 0.f;
-          store_pack<T>(dx + (size_t)row * d + vi * N, out);
+          store_n<TO, N>(dx + (size_t)row * d + vi * N, out);
         }
       }
     }
@@ -316,12 +337,11 @@ __global__ __launch_bounds__(256) void colsum_vec_kernel(const T* __restrict__ x
 // A wave covers 64 packs of one row, the block's sixteen waves take alternate rows; the partial
 // sums meet in LDS and leave as one atomic per column and block.  Adds to one address complete
 // one after the other, so the grid has few, large blocks.
-template <typename T>
+template <typename T, int N>
 __global__ __launch_bounds__(1024) void ln_param_vec_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                             const float* __restrict__ mean, const float* __restrict__ rstd,
                                                             float* __restrict__ dg, float* __restrict__ db, int rows, int d,
                                                             int rows_per_block) {
-  constexpr int N = Pack<T>::N;
   constexpr int NWV = 16;
   extern __shared__ float red[];                 // [2][NWV][64 * N]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -335,8 +355,8 @@ __global__ __launch_bounds__(1024) void ln_param_vec_kernel(const T* __restrict_
   if (live) {
     for (int r = rbeg + wave; r < rend; r += NWV) {
       float v[N], xv[N];
-      load_pack<T>(dy + (size_t)r * d + c0, v);
-      load_pack<T>(x + (size_t)r * d + c0, xv);
+      load_n<T, N>(dy + (size_t)r * d + c0, v);
+      load_n<T, N>(x + (size_t)r * d + c0, xv);
       const float mu = mean[r], rs = rstd[r];
 #pragma unroll
       for (int e = 0; e < N; ++e) {
@@ -363,51 +383,66 @@ __global__ __launch_bounds__(1024) void ln_param_vec_kernel(const T* __restrict_
   }
 }
 
-static inline bool ptr16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
-
 static bool ln_vec_ok(int dtype, const void* dy, const void* x, int d) {
-  const int pack = dtype == 1 ? 8 : 4;
-  return d % pack == 0 && d / pack <= 256 && ptr16(dy) && ptr16(x);
+  const int grp = dtype == 0 ? 4 : 8;
+  return d % grp == 0 && d / grp <= 256 && ptr16(dy) && ptr16(x);
 }
 
+// dtype 0: fp32 throughout; 1: bf16 throughout; 2: dy and x fp32, dx bf16 (bf16 models keep the
+// gradients and sums on the normalised path in fp32).
 // dg == nullptr: input gradient only (the parameter gradients then come from
-// launch_layernorm_bwd_params, on any stream that sees dy and x).
+// launch_layernorm_bwd_params, on any stream that sees dy and x).  fuse_params: dg and db (which
+// must be zero or hold what is to be added to) are produced by the same kernel that writes dx.
 hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const float* g,
                                 const float* mean, const float* rstd, void* dx, float* dg, float* db,
-                                int rows, int d, int dn) {
+                                int rows, int d, int dn, bool fuse_params) {
   if (rows <= 0) return hipSuccess;
   if (dn <= 0 || dn > d) dn = d;
   dim3 grid((rows + 3) / 4), block(256);
+  bool fused = false;
   if (ln_vec_ok(dtype, dy, x, d) && ptr16(dx)) {
-    const int pack = dtype == 1 ? 8 : 4;
+    const int grp = dtype == 0 ? 4 : 8;
     dim3 gf(std::min((rows + 3) / 4, 512));
-    const int npl = (d / pack + 63) / 64;      // packs per lane
-#define OURO_LNB(T_, MI_) hipLaunchKernelGGL((ln_bwd_fused_kernel<T_, MI_, false>), gf, block, 0, s, (const T_*)dy, (const T_*)x, g, mean, rstd, (T_*)dx, nullptr, nullptr, rows, d, dn)
-    if (dtype == 1) { if (npl <= 1) OURO_LNB(bf16_t, 1); else if (npl <= 2) OURO_LNB(bf16_t, 2); else OURO_LNB(bf16_t, 4); }
-    else { if (npl <= 1) OURO_LNB(float, 1); else if (npl <= 2) OURO_LNB(float, 2); else OURO_LNB(float, 4); }
+    const int npl = (d / grp + 63) / 64;      // groups per lane
+    fused = fuse_params && dg && db;
+    const size_t smem = fused ? (size_t)4 * d * sizeof(float) : 0;
+#define OURO_LNB2(TI_, TO_, MI_, PAR_) hipLaunchKernelGGL((ln_bwd_fused_kernel<TI_, TO_, MI_, PAR_>), gf, block, smem, s, (const TI_*)dy, (const TI_*)x, g, mean, rstd, (TO_*)dx, dg, db, rows, d, dn)
+#define OURO_LNB(TI_, TO_)                                                                  \
+  do {                                                                                      \
+    if (fused) { if (npl <= 1) OURO_LNB2(TI_, TO_, 1, true); else if (npl <= 2) OURO_LNB2(TI_, TO_, 2, true); else OURO_LNB2(TI_, TO_, 4, true); } \
+    else { if (npl <= 1) OURO_LNB2(TI_, TO_, 1, false); else if (npl <= 2) OURO_LNB2(TI_, TO_, 2, false); else OURO_LNB2(TI_, TO_, 4, false); }  \
+  } while (0)
+    if (dtype == 1) OURO_LNB(bf16_t, bf16_t);
+    else if (dtype == 2) OURO_LNB(float, bf16_t);
+    else OURO_LNB(float, float);
 #undef OURO_LNB
+#undef OURO_LNB2
   } else if (dtype == 1) {
-    hipLaunchKernelGGL(ln_bwd_dx_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)dy, (const bf16_t*)x, g, mean, rstd, (bf16_t*)dx, rows, d, dn);
+    hipLaunchKernelGGL((ln_bwd_dx_kernel<bf16_t, bf16_t>), grid, block, 0, s, (const bf16_t*)dy, (const bf16_t*)x, g, mean, rstd, (bf16_t*)dx, rows, d, dn);
+  } else if (dtype == 2) {
+    hipLaunchKernelGGL((ln_bwd_dx_kernel<float, bf16_t>), grid, block, 0, s, (const float*)dy, (const float*)x, g, mean, rstd, (bf16_t*)dx, rows, d, dn);
   } else {
-    hipLaunchKernelGGL(ln_bwd_dx_kernel<float>, grid, block, 0, s, (const float*)dy, (const float*)x, g, mean, rstd, (float*)dx, rows, d, dn);
+    hipLaunchKernelGGL((ln_bwd_dx_kernel<float, float>), grid, block, 0, s, (const float*)dy, (const float*)x, g, mean, rstd, (float*)dx, rows, d, dn);
   }
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess || !dg) return e;
+  if (e != hipSuccess || !dg || fused) return e;
   return launch_layernorm_bwd_params(s, dtype, dy, x, mean, rstd, dg, db, rows, d);
 }
 
+// dtype as above (2: dy and x are fp32).
 hipError_t launch_layernorm_bwd_params(hipStream_t s, int dtype, const void* dy, const void* x, const float* mean,
                                        const float* rstd, float* dg, float* db, int rows, int d) {
   if (rows <= 0) return hipSuccess;
   dim3 block(256);
   if (ln_vec_ok(dtype, dy, x, d)) {
-    const int pack = dtype == 1 ? 8 : 4;
-    const int gx = (d + 64 * pack - 1) / (64 * pack);
+    const int grp = dtype == 0 ? 4 : 8;
+    const int gx = (d + 64 * grp - 1) / (64 * grp);
     const int rpb = 64;                          // four rows per wave
     dim3 grid(gx, (rows + rpb - 1) / rpb), blk(1024);
-    const size_t smem = 2 * 16 * 64 * (size_t)pack * sizeof(float);
-    if (dtype == 1) hipLaunchKernelGGL(ln_param_vec_kernel<bf16_t>, grid, blk, smem, s, (const bf16_t*)dy, (const bf16_t*)x, mean, rstd, dg, db, rows, d, rpb);
-    else hipLaunchKernelGGL(ln_param_vec_kernel<float>, grid, blk, smem, s, (const float*)dy, (const float*)x, mean, rstd, dg, db, rows, d, rpb);
+    const size_t smem = 2 * 16 * 64 * (size_t)grp * sizeof(float);
+    if (dtype == 1) hipLaunchKernelGGL((ln_param_vec_kernel<bf16_t, 8>), grid, blk, smem, s, (const bf16_t*)dy, (const bf16_t*)x, mean, rstd, dg, db, rows, d, rpb);
+    else if (dtype == 2) hipLaunchKernelGGL((ln_param_vec_kernel<float, 8>), grid, blk, smem, s, (const float*)dy, (const float*)x, mean, rstd, dg, db, rows, d, rpb);
+    else hipLaunchKernelGGL((ln_param_vec_kernel<float, 4>), grid, blk, smem, s, (const float*)dy, (const float*)x, mean, rstd, dg, db, rows, d, rpb);
     return hipGetLastError();
   }
   const int rpb = 128;

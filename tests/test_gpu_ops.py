@@ -195,16 +195,42 @@ def test_attention_xl_mfma_kernel(B, H, T, Mv):
     _attn_case(1, B, H, T, Mv, 64, 1, seed=200 + T + Mv, force=0)
 
 
+@pytest.mark.parametrize("dtype,force", [(0, 0), (1, 1), (1, 0), (1, 10), (1, 11), (1, 12), (1, 13), (1, 14)])
+@pytest.mark.parametrize("M,N,K,ln", [(200, 136, 328, 1), (384, 520, 192, 1), (130, 88, 128, 0), (260, 256, 64, 1)])
+def test_gemm_with_fp32_layernorm_residual(dtype, force, M, N, K, ln):
+    """C = A B + bias + R with R the LayerNorm of an fp32 matrix recomputed in the epilogue (ln = 1) or
+    that fp32 matrix itself (ln = 0); fp32 result; every contraction kernel, ragged tiles."""
+    rng = np.random.default_rng(M + N + K + force + ln)
+    A = rng.standard_normal((M, K)).astype(np.float32); B = rng.standard_normal((K, N)).astype(np.float32) / math.sqrt(K)
+    bias = rng.standard_normal(N).astype(np.float32)
+    S_ = (rng.standard_normal((M, N)) * 2 + 0.3).astype(np.float32)
+    g = (1 + 0.3 * rng.standard_normal(N)).astype(np.float32); b = (0.2 * rng.standard_normal(N)).astype(np.float32)
+    dA, dB = dev(A, dtype), dev(B, dtype)
+    dS, dbias, dg, db = (torch.from_numpy(x).cuda() for x in (S_, bias, g, b))
+    R, cache = O.layernorm_fwd(S_.astype(np.float64), g.astype(np.float64), b.astype(np.float64))
+    mean = torch.from_numpy(S_.astype(np.float64).mean(axis=1).astype(np.float32)).cuda()      # row statistics are inputs here
+    rstd = torch.from_numpy(cache[1][:, 0].astype(np.float32)).cuda()
+    Cc = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    ok(L().ouro_op_gemm_ln_residual(stream(), dtype, 0, 0, M, N, K, p(dA), K, p(dB), N, p(Cc), N, 1, p(dbias), p(dS), N,
+                                    p(mean) if ln else None, p(rstd) if ln else None, p(dg) if ln else None,
+                                    p(db) if ln else None, force))
+    torch.cuda.synchronize()
+    ref = host(dA) @ host(dB) + bias + (R if ln else S_.astype(np.float64))
+    assert rel_err(host(Cc), ref) < TOL[dtype]
+    assert np.abs(host(Cc) - ref).max() < (1e-4 if dtype == 0 else 0.1) * np.abs(ref).max()
+
+
 # ------------------------------------------------------------------ row-wise kernels
-@pytest.mark.parametrize("dtype", [0, 1])
-@pytest.mark.parametrize("rows,d", [(37, 64), (130, 512), (9, 410), (5, 1024), (3, 4100)])
+@pytest.mark.parametrize("dtype", [0, 1, 2])
+@pytest.mark.parametrize("rows,d", [(37, 64), (130, 512), (9, 410), (5, 1024), (3, 4100), (517, 1024), (66, 2048)])
 def test_layernorm(dtype, rows, d):
+    """dtype 2: fp32 rows read, bf16 rows written (the bf16 model's form)."""
     rng = np.random.default_rng(rows + d)
     x = (rng.standard_normal((rows, d)) * 2 + 0.5).astype(np.float32)
     dy = rng.standard_normal((rows, d)).astype(np.float32)
     g = (1 + 0.3 * rng.standard_normal(d)).astype(np.float32)
     b = (0.2 * rng.standard_normal(d)).astype(np.float32)
-    dx_, ddy = dev(x, dtype), dev(dy, dtype)
+    dx_, ddy = dev(x, 1 if dtype == 1 else 0), dev(dy, 1 if dtype == 1 else 0)
     dg_, db_ = torch.from_numpy(g).cuda(), torch.from_numpy(b).cuda()
     tdt = torch.bfloat16 if dtype else torch.float32
     y = torch.zeros((rows, d), dtype=tdt, device="cuda")
@@ -212,14 +238,14 @@ def test_layernorm(dtype, rows, d):
     ok(L().ouro_op_layernorm_fwd(stream(), dtype, p(dx_), p(dg_), p(db_), p(y), p(mean), p(rstd), rows, d, 0))
     yr, cache = O.layernorm_fwd(host(dx_), g.astype(np.float64), b.astype(np.float64))
     torch.cuda.synchronize()
-    assert rel_err(host(y), yr) < TOL[dtype]
+    assert rel_err(host(y), yr) < TOL[min(dtype, 1)]
     assert rel_err(host(rstd), cache[1][:, 0]) < 1e-5
     gx = torch.zeros((rows, d), dtype=tdt, device="cuda")
     gg = torch.full((d,), 7.0, device="cuda"); gb = torch.full((d,), 7.0, device="cuda")
     ok(L().ouro_op_layernorm_bwd(stream(), dtype, p(ddy), p(dx_), p(dg_), p(mean), p(rstd), p(gx), p(gg), p(gb), rows, d, 0))
     torch.cuda.synchronize()
     rx, rg, rb = O.layernorm_bwd(host(ddy), g.astype(np.float64), cache)
-    assert rel_err(host(gx), rx) < TOL[dtype]
+    assert rel_err(host(gx), rx) < TOL[min(dtype, 1)]
     assert rel_err(host(gg), rg) < 1e-4
     assert rel_err(host(gb), rb) < 1e-4
 
