@@ -50,6 +50,22 @@ int ouro_op_attention_bwd(void* stream, int dtype, int B, int H, int T, int S, i
                           void* dv, int lddv, int rel, const void* u, const void* vb, const void* r,
                           int ldr, float* du, float* dvb, float* dr, float* scratch, int force_generic);
 size_t ouro_op_attention_bwd_scratch(int B, int H, int T, int S, int dh);
+/* ouro_op_attention_bwd for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same arguments without
+ * `scratch`; the workspace is a device array inside the library, 4 Mi floats (16 MiB) on every
+ * GPU the library runs on, held until the process ends.  Sizes whose
+ * ouro_op_attention_bwd_scratch() exceeds 4194304 floats are refused with OURO_E_ARG
+ * (ouro_last_error says how much was needed).  The call allocates and frees nothing; it clears
+ * the part of the workspace it uses with a fill kernel on `stream`, then enqueues the same
+ * kernels as ouro_op_attention_bwd.  All calls on one GPU share that GPU's workspace: calls
+ * that may overlap on one GPU (different streams, different threads) race; keep them on one
+ * stream or order them with events. */
+int ouro_op_attention_bwd_noalloc(void* stream, int dtype, int B, int H, int T, int S, int dh, int Mv,
+                                  float scale, const void* q, int ldq, const void* k, int ldk,
+                                  const void* v, int ldv, const void* o, int ldo, const float* lse,
+                                  const void* d_o, int lddo, void* dq, int lddq, void* dk, int lddk,
+                                  void* dv, int lddv, int rel, const void* u, const void* vb, const void* r,
+                                  int ldr, float* du, float* dvb, float* dr, int force_generic);
 
 /* Repeatable dropout (Section 5.2): dst[r,c] = src[r,c] * f(r*drop_ld + c), f(i) = 1/(1-p) if the high
  * 32 bits of output i + stream_id*2^40 + 1 of the SplitMix64 sequence started at `seed` are >=

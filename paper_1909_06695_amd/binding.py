@@ -91,6 +91,9 @@ def lib():
                                         i32, vp, vp, i32, vp, i32, vp, i32, vp, i32, i32, vp, vp, vp, i32, vp, vp,
                                         vp, vp, i32]),
         "ouro_op_attention_bwd_scratch": (sz, [i32, i32, i32, i32, i32]),
+        "ouro_op_attention_bwd_noalloc": (i32, [vp, i32, i32, i32, i32, i32, i32, i32, f32, vp, i32, vp, i32, vp, i32, vp,
+                                                i32, vp, vp, i32, vp, i32, vp, i32, vp, i32, i32, vp, vp, vp, i32, vp, vp,
+                                                vp, i32]),
         "ouro_op_dropout": (i32, [vp, i32, vp, vp, i32, i32, i32, f32, C.c_uint64, C.c_uint32, i32]),
         "ouro_op_gemm_dropout": (i32, [vp, i32, i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32, vp, vp, i32, f32,
                                        C.c_uint64, C.c_uint32, i32, i32]),

@@ -137,6 +137,8 @@ struct AttnDesc {
   float* scratch;                  // fp32 workspace, attn_bwd_scratch_floats() elements
 };
 size_t attn_bwd_scratch_floats(int B, int H, int T, int S, int dh);
+// records msg as the calling thread's last error (ouro_last_error) and returns code
+int set_error(int code, const char* msg);
 hipError_t launch_attn_fwd(hipStream_t s, int dtype, const AttnDesc& a, int force_generic);
 hipError_t launch_attn_bwd(hipStream_t s, int dtype, const AttnDesc& a, int force_generic);
 

@@ -4,6 +4,7 @@
 #include "../../include/ouro_ops.h"
 
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 
 using namespace ouro;
@@ -112,6 +113,44 @@ extern "C" int ouro_op_attention_bwd(void* stream, int dtype, int B, int H, int 
     if (e != hipSuccess) return OURO_E_HIP;
   }
   return rc_of(launch_attn_bwd(s, dtype, a, force_generic));
+}
+
+// ---- attention backward for callers that cannot allocate: the workspace is a device array of the library
+constexpr size_t NOALLOC_SCRATCH_FLOATS = (size_t)4 << 20;       // 16 MiB per GPU, held until the process ends
+static __device__ __align__(256) float scratch[NOALLOC_SCRATCH_FLOATS];
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static float* g_scratch_ptr[NOALLOC_MAX_DEVICES];                 // device address of `scratch` on each GPU (host-side table)
+
+extern "C" int ouro_op_attention_bwd_noalloc(void* stream, int dtype, int B, int H, int T, int S, int dh, int Mv, float scale,
+                                             const void* q, int ldq, const void* k, int ldk, const void* v, int ldv,
+                                             const void* o, int ldo, const float* lse, const void* d_o, int lddo, void* dq,
+                                             int lddq, void* dk, int lddk, void* dv, int lddv, int rel, const void* u,
+                                             const void* vb, const void* r, int ldr, float* du, float* dvb, float* dr,
+                                             int force_generic) {
+  if (B < 1 || H < 1 || T < 1 || dh < 1 || Mv < 0 || S != Mv + T) return set_error(OURO_E_ARG, "attention_bwd_noalloc: bad sizes");
+  const size_t need = attn_bwd_scratch_floats(B, H, T, S, dh);
+  if (need > NOALLOC_SCRATCH_FLOATS) {
+    char msg[200];
+    snprintf(msg, sizeof msg, "attention_bwd_noalloc: needs %zu workspace floats, the built-in workspace holds %zu", need,
+             NOALLOC_SCRATCH_FLOATS);
+    return set_error(OURO_E_ARG, msg);
+  }
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= NOALLOC_MAX_DEVICES)
+    return set_error(OURO_E_HIP, "attention_bwd_noalloc: no current device (or more than 64 devices)");
+  if (!g_scratch_ptr[dev]) {
+    // the array's name is a host-side stand-in: its address on the current device comes from the runtime
+    float* ptr = nullptr;
+    hipError_t e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) return set_error(OURO_E_HIP, "attention_bwd_noalloc: hipGetSymbolAddress failed");
+    g_scratch_ptr[dev] = ptr;
+  }
+  float* ws = g_scratch_ptr[dev];
+  // the array keeps the previous call's contents: start the part in use from zero (a fill kernel, not a memset
+  // node, so that the call can be captured into a graph)
+  if (launch_fill_zero((hipStream_t)stream, ws, need * sizeof(float)) != hipSuccess) return set_error(OURO_E_HIP, "attention_bwd_noalloc: clear failed");
+  return ouro_op_attention_bwd(stream, dtype, B, H, T, S, dh, Mv, scale, q, ldq, k, ldk, v, ldv, o, ldo, lse, d_o, lddo, dq, lddq,
+                               dk, lddk, dv, lddv, rel, u, vb, r, ldr, du, dvb, dr, ws, force_generic);
 }
 
 extern "C" int ouro_op_layernorm_fwd(void* stream, int dtype, const void* x, const float* g, const float* b, void* y,
