@@ -8,8 +8,12 @@
 //   row-form operand (k contiguous):  [rows][64 k], 128-byte rows, 16-byte chunk c of row r
 //     stored at chunk c ^ swz(r);
 //   column-form operand (row index contiguous): [64 k][ROWS], chunk c of k-row k stored at
-//     chunk c ^ ((k & 3) << 1), so the four k-rows one transpose-read touches fall into
-//     different banks.
+//     chunk c ^ colswz(k).  One transpose-read serves 32 lanes per cycle: four k-rows times eight
+//     8-byte pieces that span four chunks of each k-row.  K-rows of 256 bytes or more start at the
+//     same bank, so the four k-rows get four disjoint chunk groups (XOR with 0, 4, 8, 12); k-rows
+//     of 128 bytes (ROWS = 64) alternate between the two halves of the banks, and the two k-rows
+//     of a half get the two chunk groups of that row (XOR with 0 or 4).  (Measured with
+//     SQ_LDS_BANK_CONFLICT: none left; an XOR with 0, 2, 4, 6 had every second cycle in conflict.)
 // A direct load writes lane i's 16 bytes to (wave-uniform base) + 16*i, so the swizzle is
 // applied by choosing which global chunk each lane fetches.
 #include "gemm_common.h"
@@ -17,6 +21,12 @@
 namespace ouro {
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+template <int ROWS>
+__device__ __forceinline__ int colswz(int k) {
+  static_assert(ROWS == 64 || ROWS % 128 == 0, "column-form tiles are 64 or a multiple of 128 rows wide");
+  return ROWS >= 128 ? ((k & 3) << 2) : (((k >> 1) & 1) << 2);
+}
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void gbl_void;
 
@@ -50,7 +60,7 @@ struct OperandTile {
       const int gr = min(row0 + lr, rmax - 1);
       return (size_t)gr * ld + 8 * c;                      // + k0
     } else {
-      const int c = pc ^ ((lr & 3) << 1);
+      const int c = pc ^ colswz<ROWS>(lr);
       const int gm = min(row0 + 8 * c, rmax - 8);
       return (size_t)lr * ld + gm;                         // + k0 * ld
     }
@@ -69,7 +79,7 @@ __device__ __forceinline__ bf16x8 frag_col(const char* tile, int t0, int ks, int
   const int g4 = lane >> 4, i = lane & 15;
   const int k = 16 * ks + 8 * (g4 >> 1) + (i >> 2);
   const int m = t0 + 16 * (g4 & 1) + 4 * (i & 3);
-  const char* a = tile + k * (ROWS * 2) + (((m >> 3) ^ ((k & 3) << 1)) << 4) + ((m & 7) << 1);
+  const char* a = tile + k * (ROWS * 2) + (((m >> 3) ^ colswz<ROWS>(k)) << 4) + ((m & 7) << 1);
   s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)a);
   s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a + 4 * (ROWS * 2)));
   union { struct { s16x4 l, h; } p; bf16x8 v; } u;
