@@ -3,6 +3,7 @@
 // bounds-checked tiled kernel for fp32 operands and shapes the MFMA kernel does not take.
 #include "gemm_common.h"
 
+#include <algorithm>
 #include <cstdlib>
 
 namespace ouro {
@@ -227,12 +228,36 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
     }
     const size_t bytesA = 2 * (size_t)(g.transA ? g.K : g.M) * g.lda, bytesB = 2 * (size_t)(g.transB ? g.N : g.K) * g.ldb;
     // direct global->LDS loads need whole 64-wide K tiles and 32-bit operand offsets
-    if ((g.K % 64) != 0 || bytesA >= (1ull << 31) || bytesB >= (1ull << 31)) cfg = GEMM_TILE_STAGED128;
+    const bool direct_ok = (g.K % 64) == 0 && bytesA < (1ull << 31) && bytesB < (1ull << 31);
+    int splits = 1;
+    bool modelled = false;
+    if (g.accumulate && force_generic < 2 && direct_ok && g.K >= 512) {
+      modelled = true;
+      // Split-K launch: tile shape and number of K ranges together, so that the grid fills the
+      // chip in whole rounds.  Cost of a candidate in units of (tile area x K-tiles) per CU:
+      // rounds x workgroups per CU x tile area x (K-tiles per workgroup + fixed cost) / rate,
+      // the fixed cost (ring fill, atomic epilogue) taken as 6 K-tiles, the rate of the 128x64
+      // tiles as 0.8 of the 128x128 ones (more operand bytes per flop).
+      double best = 1e30;
+      for (int c = 0; c < 2; ++c) {
+        const int bm = 128, bn = c ? 64 : 128, per_cu = c ? 3 : 2;
+        const long tiles = (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn);
+        const int max_s = std::min(16, g.K / 256);
+        for (int sp = 1; sp <= max_s; ++sp) {
+          const int kc = ((g.K + sp - 1) / sp + 63) / 64 * 64;
+          const int real = (g.K + kc - 1) / kc;
+          if (real != sp) continue;
+          const long rounds = (tiles * sp + 256L * per_cu - 1) / (256L * per_cu);
+          const double cost = (double)rounds * per_cu * bm * bn * (kc / 64 + 6) / (c ? 0.8 : 1.0);
+          if (cost < best) { best = cost; cfg = c ? GEMM_TILE_128x64 : GEMM_TILE_128x128; splits = sp; }
+        }
+      }
+    }
+    if (!direct_ok) cfg = GEMM_TILE_STAGED128;
     if (cfg < GEMM_TILE_STAGED128 || cfg > GEMM_TILE_256x256) return hipErrorInvalidValue;
     const int BM = cfg == GEMM_TILE_256x256 ? 256 : 128, BN = cfg == GEMM_TILE_128x64 ? 64 : BM;
     int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-    int splits = 1;
-    if (g.accumulate && tiles < 384 && g.K >= 512) {
+    if (g.accumulate && !modelled && tiles < 384 && g.K >= 512) {
       splits = (512 + tiles - 1) / tiles;
       int maxs = g.K / 256;
       if (splits > maxs) splits = maxs;
