@@ -7,7 +7,6 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -235,7 +234,6 @@ struct ouro_model : BwdCtx {
   int mem_valid;                  // valid rows in every layer memory
   const int32_t* tok;
   const int32_t* tgt;
-  bool ln_fused;               // LayerNorm scale / shift gradients from the kernel that writes the input gradient
   bool use_side;               // run gradient-only work beside the error-gradient chain (BwdCtx::side)
   // A third stream carries (inside ouro_step) the update of a module as soon as its backward
   // pass is done, beside the backward of the modules below.
@@ -544,7 +542,6 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
   m->eval_mode = false; m->cur_seed = cfg->seed;
   for (int i = 0; i < OURO_TIMING_KINDS; ++i) { m->ev_used[i] = 0; m->timed_work[i] = 0; m->timed_launches[i] = 0; }
   m->side = nullptr; m->use_side = false; m->ev_join = nullptr;
-  m->ln_fused = getenv("OURO_LN_SPLIT") == nullptr;
   m->aux = nullptr; m->ev_bwd_done = m->ev_upd_done = nullptr; m->upd_pending = false;
   for (int i = 0; i < 4; ++i) m->ev_ready[i] = nullptr;
   for (int i = 0; i < 2; ++i) { m->ev_side_done[i] = nullptr; m->side_busy[i] = false; }
@@ -949,17 +946,15 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     return OURO_OK;
   };
   // LN2
-  // with the side stream the scale/shift gradients (column sums over dh and s2) run there too
+  // the scale / shift gradients come from the same kernel (one pass over dh and s2)
   // dh, dy (gradients of the normalised rows) and the saved sums s1, s2 are fp32 in every mode
   const int lnk = c.dtype == 1 ? 2 : 0;
-  const bool lnp_side = side && !m->ln_fused;         // scale / shift gradients as a kernel of their own on the side stream
   const double ln_bwd_bytes = (double)N * dn * (8 + es) + 8.0 * N;      // fp32 gradient and input rows read, one row written, statistics
   RUN(timed_launch(m, OURO_TIMING_LAYERNORM, ln_bwd_bytes, st, [&] {
     return launch_layernorm_bwd(st, lnk, dh, b.s2, m->wF(l, o.ln2_g), b.mean2, b.rstd2, ds2,
-                                lnp_side ? nullptr : gslot + o.ln2_g, gslot + o.ln2_b, N, d, dn, m->ln_fused); }));
+                                gslot + o.ln2_g, gslot + o.ln2_b, N, d, dn, true); }));
   if (dropping) HIPCHK(launch_dropout_apply(st, c.dtype, ds2, ds2m, N, d, d, drop_at(m, 2 * l + 2)));
   RUN(ready(0));
-  if (lnp_side) HIPCHK(launch_layernorm_bwd_params(sw, lnk, dh, b.s2, b.mean2, b.rstd2, gslot + o.ln2_g, gslot + o.ln2_b, N, d));
   // FFN2
   {
     GemmDesc g = gd(b.uact, F, 1, ds2m, d, 0, gslot + o.W_2, d, F, d, N);
@@ -988,10 +983,9 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   // LN1
   RUN(timed_launch(m, OURO_TIMING_LAYERNORM, ln_bwd_bytes, st, [&] {
     return launch_layernorm_bwd(st, lnk, dy, b.s1, m->wF(l, o.ln1_g), b.mean1, b.rstd1, ds1,
-                                lnp_side ? nullptr : gslot + o.ln1_g, gslot + o.ln1_b, N, d, dn, m->ln_fused); }));
+                                gslot + o.ln1_g, gslot + o.ln1_b, N, d, dn, true); }));
   if (dropping) HIPCHK(launch_dropout_apply(st, c.dtype, ds1, ds1m, N, d, d, drop_at(m, 2 * l + 1)));
   RUN(ready(2));
-  if (lnp_side) HIPCHK(launch_layernorm_bwd_params(sw, lnk, dy, b.s1, b.mean1, b.rstd1, gslot + o.ln1_g, gslot + o.ln1_b, N, d));
   // output projection
   {
     GemmDesc g = gd(b.a, hd, 1, ds1m, d, 0, gslot + o.W_o, d, hd, d, N);
