@@ -35,10 +35,14 @@ typedef __attribute__((address_space(1))) const void gbl_void;
 constexpr int TILE_BYTES = 64 * 128;
 constexpr int NSTAGE = 3;
 
-// chunk swizzle of a tile row: a bijection of the low three row bits whose values over
-// four consecutive rows differ in bits 1-2, so that both the 16-byte row reads and the
-// transposed 4-row reads spread over the banks
-__device__ __forceinline__ int swza(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+// Chunk swizzle of a tile row (128-byte rows: two rows per 256-byte bank window).  A 16-byte row
+// read serves 16 consecutive rows per cycle at one chunk index: the eight rows of each parity
+// need eight different swizzle values, so the value is a bijection of row bits 1-3.  A
+// transposed read serves four consecutive rows per cycle, each over four adjacent chunks: the
+// two rows of each parity need different chunk groups of four, so swizzle bit 2 is row bit 1.
+// (SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE of the attention kernels: 25-40 % with a swizzle of
+// row bits 0-2 only, whose rows r and r+8 collide in the row reads.)
+__device__ __forceinline__ int swza(int row) { return (((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1) | ((row >> 3) & 1); }
 
 template <int N>
 __device__ __forceinline__ void fa_wait_vmcnt() {
