@@ -879,6 +879,17 @@ __device__ __forceinline__ float upd_one(float w, float g, float& m, float& v, c
   float mh = m / p.bc1, vh = v / p.bc2;
   return w - p.lr * (mh / (sqrtf(vh) + p.eps));
 }
+// Streaming accesses of the update: every byte is touched once per iteration, so it is kept out of
+// the caches' way (the bf16 copy, which the next forward pass reads, is stored normally).
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 nt_load4(const float4* p) {
+  f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void nt_store4(float4* p, float4 a) {
+  f32x4_t v = {a.x, a.y, a.z, a.w};
+  __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t*>(p));
+}
 template <bool ADAM>
 __global__ __launch_bounds__(256) void update_kernel(UpdParams p) {
   const size_t n4 = p.n / 4;
@@ -895,10 +906,10 @@ __global__ __launch_bounds__(256) void update_kernel(UpdParams p) {
       g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
       m[u] = g[u]; v[u] = g[u]; w[u] = g[u];
       if (on[u]) {
-        w[u] = reinterpret_cast<float4*>(p.w)[j];
-        if (p.g0) { float4 a = reinterpret_cast<const float4*>(p.g0)[j]; g[u].x = p.s0 * a.x; g[u].y = p.s0 * a.y; g[u].z = p.s0 * a.z; g[u].w = p.s0 * a.w; }
-        if (p.g1) { float4 a = reinterpret_cast<const float4*>(p.g1)[j]; g[u].x += p.s1 * a.x; g[u].y += p.s1 * a.y; g[u].z += p.s1 * a.z; g[u].w += p.s1 * a.w; }
-        if (ADAM) { m[u] = reinterpret_cast<float4*>(p.m)[j]; v[u] = reinterpret_cast<float4*>(p.v)[j]; }
+        w[u] = nt_load4(reinterpret_cast<const float4*>(p.w) + j);
+        if (p.g0) { float4 a = nt_load4(reinterpret_cast<const float4*>(p.g0) + j); g[u].x = p.s0 * a.x; g[u].y = p.s0 * a.y; g[u].z = p.s0 * a.z; g[u].w = p.s0 * a.w; }
+        if (p.g1) { float4 a = nt_load4(reinterpret_cast<const float4*>(p.g1) + j); g[u].x += p.s1 * a.x; g[u].y += p.s1 * a.y; g[u].z += p.s1 * a.z; g[u].w += p.s1 * a.w; }
+        if (ADAM) { m[u] = nt_load4(reinterpret_cast<const float4*>(p.m) + j); v[u] = nt_load4(reinterpret_cast<const float4*>(p.v) + j); }
       }
     }
 #pragma unroll
@@ -909,8 +920,8 @@ __global__ __launch_bounds__(256) void update_kernel(UpdParams p) {
       w[u].y = upd_one<ADAM>(w[u].y, g[u].y, m[u].y, v[u].y, p);
       w[u].z = upd_one<ADAM>(w[u].z, g[u].z, m[u].z, v[u].z, p);
       w[u].w = upd_one<ADAM>(w[u].w, g[u].w, m[u].w, v[u].w, p);
-      reinterpret_cast<float4*>(p.w)[j] = w[u];
-      if (ADAM) { reinterpret_cast<float4*>(p.m)[j] = m[u]; reinterpret_cast<float4*>(p.v)[j] = v[u]; }
+      nt_store4(reinterpret_cast<float4*>(p.w) + j, w[u]);
+      if (ADAM) { nt_store4(reinterpret_cast<float4*>(p.m) + j, m[u]); nt_store4(reinterpret_cast<float4*>(p.v) + j, v[u]); }
       if (p.shadow) {
         union { bf16_t h[4]; uint2 q; } cv;
         cv.h[0] = (bf16_t)w[u].x; cv.h[1] = (bf16_t)w[u].y; cv.h[2] = (bf16_t)w[u].z; cv.h[3] = (bf16_t)w[u].w;
