@@ -38,18 +38,34 @@ def rel_err(a, b):
 # standard deviation of f * tol * scale, and the largest of 5e7 normal draws sits near 6 standard
 # deviations.
 EW_ATOL = 6.0
+# The element-wise bound never runs tighter than EW_FLOOR x tol: the errors' tails are heavier than
+# normal (a few elements in 4e6 reach 2.7 x tol x (|b| + 6 scale) after four Adam iterations, when the
+# two sides' weights have also drifted apart); a wrong element still fails 1 / (4 x 0.02 x 6) = 2 times over.
+EW_FLOOR = 4.0
 RECORD_ONLY = bool(os.environ.get("OURO_PARITY_RECORD"))   # calibration runs: collect WORST without failing
 WORST = {}          # what -> (largest norm ratio / tol, largest element-wise excess), for the calibration record
 
 
-def elem_scale(ref, shape=None):
-    """Element-wise size of a reference tensor (flat array out): see EW_ATOL."""
+def elem_scale(ref, shape=None, whole=False):
+    """Element-wise size of a reference tensor (flat array out): see EW_ATOL.  `whole`: never below
+    the whole tensor's RMS (see cancels_by_rows)."""
     ref = np.asarray(ref, np.float64)
     rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
     if shape is None or len(shape) != 2 or rms == 0.0:
         return np.full(ref.size, rms)
     r2 = ref.reshape(shape)
-    return np.maximum(np.sqrt(np.mean(r2 * r2, axis=1))[:, None], np.sqrt(np.mean(r2 * r2, axis=0))[None, :]).ravel()
+    sc = np.maximum(np.sqrt(np.mean(r2 * r2, axis=1))[:, None], np.sqrt(np.mean(r2 * r2, axis=0))[None, :]).ravel()
+    return np.maximum(sc, rms) if whole else sc
+
+
+def cancels_by_rows(name):
+    """The gradient of W_r has rows that vanish by cancellation, not because their summands are small:
+    the low-frequency cosine features of the distance encoding (Section 5.2's Transformer-XL attention)
+    are close to 1 at every distance, so their rows of the gradient are close to sum_ij dS_ij (q_i + v),
+    and the softmax gradient dS sums to zero over the keys of every query.  The oracle's fp64 sum
+    reaches 1e-3 of the tensor's RMS there; rounded summands cannot, so the scale of such a tensor's
+    elements is never taken below the tensor's own RMS."""
+    return name == "W_r"
 
 
 def record(key, nr_over_tol, excess):
@@ -59,7 +75,7 @@ def record(key, nr_over_tol, excess):
     WORST[key] = (max(w[0], nr_over_tol), max(w[1], excess))
 
 
-def assert_close(got, ref, tol, what, norm_factor=1.0, shape=None):
+def assert_close(got, ref, tol, what, norm_factor=1.0, shape=None, whole=False):
     got = np.asarray(got, np.float64).ravel(); ref = np.asarray(ref, np.float64).ravel()
     assert got.shape == ref.shape, (what, got.shape, ref.shape)
     if ref.size == 0:
@@ -67,7 +83,7 @@ def assert_close(got, ref, tol, what, norm_factor=1.0, shape=None):
     assert np.all(np.isfinite(got)), (what, "non-finite values")
     diff = np.abs(got - ref)
     nr = float(np.linalg.norm(diff) / max(np.linalg.norm(ref), 1e-30))
-    bound = norm_factor * tol * (np.abs(ref) + EW_ATOL * elem_scale(ref, shape))
+    bound = max(norm_factor, EW_FLOOR) * tol * (np.abs(ref) + EW_ATOL * elem_scale(ref, shape, whole))
     over = diff > bound
     ratio = diff / np.maximum(bound, 1e-300)
     excess = float(np.max(ratio))
@@ -117,13 +133,13 @@ def tensor_factor(name, shape):
 def param_shapes_of_groups(cfg, orc):
     """Per parameter group a list of (offset, count, shape, tolerance factor) of its tensors in blob order."""
     K = cfg.n_module
-    out = [[(0, cfg.vocab * cfg.d_model, (cfg.vocab, cfg.d_model), 1.0)]]
+    out = [[(0, cfg.vocab * cfg.d_model, (cfg.vocab, cfg.d_model), 1.0, False)]]
     for k in range(1, K + 1):
         off, lst = 0, []
         for _ in orc.module_layers(k):
             for name, shape in O.param_shapes(cfg):
                 n = int(np.prod(shape))
-                lst.append((off, n, shape, tensor_factor(name, shape)))
+                lst.append((off, n, shape, tensor_factor(name, shape), cancels_by_rows(name)))
                 off += n
         out.append(lst)
     return out
@@ -167,7 +183,7 @@ def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=
             else:
                 continue
             moved[g] = True
-            noise = np.concatenate([f * tol * (np.abs(gg[o:o + n]) + EW_ATOL * elem_scale(gg[o:o + n], sh)) for o, n, sh, f in shapes[g]])
+            noise = np.concatenate([max(f, EW_FLOOR) * tol * (np.abs(gg[o:o + n]) + EW_ATOL * elem_scale(gg[o:o + n], sh, wh)) for o, n, sh, f, wh in shapes[g]])
             if c["optimizer"] == 0:
                 budget[g] += lr * noise
             else:
@@ -212,7 +228,7 @@ def run_both(c, steps, lr, seed=0, std=0.02, perturb=0.0, check_grads=True, tol=
                 for l in orc.module_layers(k):
                     for name, shape in O.param_shapes(cfg):
                         n = int(np.prod(shape))
-                        assert_close(got[off:off + n], grads[l][name], tol, ("grad " + name, l, t), norm_factor=tensor_factor(name, shape), shape=shape)
+                        assert_close(got[off:off + n], grads[l][name], tol, ("grad " + name, l, t), norm_factor=tensor_factor(name, shape), shape=shape, whole=cancels_by_rows(name))
                         off += n
         for g in range(K + 1):
             got, ref = m.get_params(g).astype(np.float64), orc.module_blob(g)
