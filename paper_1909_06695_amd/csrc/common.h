@@ -154,14 +154,22 @@ hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, const void* x, const f
                                 void* y, float* mean, float* rstd, int rows, int d, int dn = 0);
 // dx from dy, x, stats; dg/db (fp32) are accumulated into (caller zeroes). dg == nullptr: dx only.
 // fuse_params: dg, db come from the kernel that writes dx (one pass over dy and x instead of two).
+// copy_stride (floats, 0 = one copy): dg / db / out are the first of 8 copies that far apart.  Many
+// blocks add to the same few addresses, and adds from different XCDs move the line from L2 to L2;
+// the vector kernels therefore add into the copy of the XCD the block runs on (blocks are dealt to
+// the 8 XCDs in launch order), and the caller sums the copies (launch_sum_segments).
 hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const float* g,
                                 const float* mean, const float* rstd, void* dx, float* dg, float* db,
-                                int rows, int d, int dn = 0, bool fuse_params = false);
+                                int rows, int d, int dn = 0, bool fuse_params = false, size_t copy_stride = 0);
 // dg[c] += sum_r dy*xhat, db[c] += sum_r dy alone (any stream that sees dy, x and the stats)
 hipError_t launch_layernorm_bwd_params(hipStream_t s, int dtype, const void* dy, const void* x, const float* mean,
                                        const float* rstd, float* dg, float* db, int rows, int d);
 // out[c] += sum over rows of x[r, c]  (fp32 accumulate into, caller zeroes)
-hipError_t launch_colsum(hipStream_t s, int dtype, const void* x, int ldx, float* out, int rows, int cols);
+hipError_t launch_colsum(hipStream_t s, int dtype, const void* x, int ldx, float* out, int rows, int cols, size_t copy_stride = 0);
+// One piece of a gathered sum: dst[dst_off + i] += sum over 8 copies of src[c * stride + src_off + i], i < len <= 256
+struct SumSegment { unsigned src_off, dst_off, len; };
+// All pieces of a device table in one launch; the copies are left zero.
+hipError_t launch_sum_segments(hipStream_t s, const SumSegment* table, int count, float* src, size_t stride, float* dst);
 // h[n,:] = scale * V[tok[n],:] (+ pe[n % T,:]); ids outside [0,vocab) set *flag and give a zero row
 // drop (optional): dropout on the sum, element index n*drop->ld + c
 hipError_t launch_embed_fwd(hipStream_t s, int dtype, const int32_t* tok, const void* V, const float* pe,

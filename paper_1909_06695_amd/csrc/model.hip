@@ -217,6 +217,17 @@ struct ouro_model : BwdCtx {
   size_t persist_end;              // arena[0, persist_end): weights, moments, gradient and input rings, mailboxes
   float* dbg_f32;
   size_t dbg_floats;
+  // Gradients of a layer's vectors (LayerNorm scales and shifts, the two FFN biases) are sums
+  // over all rows that many blocks add to: they are collected in 8 copies (one per XCD, see
+  // launch_layernorm_bwd), vec_stride floats apart, layer l's vectors at vec_off[l] in the
+  // order ln2_g, ln2_b, b_2, ln1_g, ln1_b, b_1; at the end of a module's backward pass one
+  // launch adds the sum of the copies to the gradient slot (segs: the pieces, per module) and
+  // leaves the copies zero.
+  float* vec_copies;
+  size_t vec_stride;
+  std::vector<size_t> vec_off;
+  std::vector<std::vector<SumSegment>> segs;
+  std::vector<SumSegment*> segs_dev;
   // Stored-input schedule (cfg.schedule == 1): module k < K keeps the input of its last
   // K-k+1 forward passes (token ids for k = 1, the hidden state at the boundary otherwise),
   // tagged with the iteration; the error gradient of module k's output travels from module
@@ -479,6 +490,24 @@ static size_t lay_out(ouro_model& m, char* base) {
   m.dbg_floats = N * d > B * M * d ? N * d : B * M * d;
   if (m.dbg_floats < S * d) m.dbg_floats = S * d;
   m.dbg_f32 = (float*)P(m.dbg_floats * 4);
+  m.vec_off.assign(L, 0);
+  m.segs.assign(K + 1, {});
+  m.segs_dev.assign(K + 1, nullptr);
+  size_t vtot = 0;
+  for (int li = 0; li < L; ++li) {
+    m.vec_off[li] = vtot;
+    const LayerOff& o = m.loff[li];
+    const size_t dst[6] = {o.ln2_g, o.ln2_b, o.b_2, o.ln1_g, o.ln1_b, o.b_1};
+    for (int i = 0; i < 6; ++i) {
+      const size_t len = i == 5 ? F : d;
+      for (size_t c0 = 0; c0 < len; c0 += 256)
+        m.segs[m.layer_mod[li]].push_back({(unsigned)(vtot + c0), (unsigned)(dst[i] + c0), (unsigned)std::min<size_t>(256, len - c0)});
+      vtot += len;
+    }
+  }
+  m.vec_stride = (vtot + 63) / 64 * 64;
+  m.vec_copies = (float*)P(8 * m.vec_stride * 4);
+  for (int k = 1; k <= K; ++k) m.segs_dev[k] = (SumSegment*)P(m.segs[k].size() * sizeof(SumSegment));
   return bp.off;
 }
 
@@ -573,6 +602,9 @@ extern "C" int ouro_create_model(const ouro_config* cfg, void* dev_arena, size_t
   for (int k = 0; k <= K && e == hipSuccess; ++k)
     if (m->ttab_dev[k])
       e = hipMemcpyAsync(m->ttab_dev[k], m->ttab[k].data(), m->ttab[k].size() * sizeof(TransposeEntry), hipMemcpyHostToDevice, m->stream);
+  for (int k = 1; k <= K && e == hipSuccess; ++k)
+    if (!m->segs[k].empty())
+      e = hipMemcpyAsync(m->segs_dev[k], m->segs[k].data(), m->segs[k].size() * sizeof(SumSegment), hipMemcpyHostToDevice, m->stream);
   if (e != hipSuccess) { ouro_destroy_model(m); return fail(OURO_E_HIP, "table upload: %s", hipGetErrorString(e)); }
   std::vector<float> tab;
   if (!cfg->rel_pos) {
@@ -945,6 +977,8 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     HIPCHK(hipStreamWaitEvent(sw, m->ev_ready[i], 0));
     return OURO_OK;
   };
+  // the gradients of this layer's vectors gather in the per-XCD copies; module_backward adds them to gslot
+  float* vc = m->vec_copies + m->vec_off[l];
   // LN2
   // the scale / shift gradients come from the same kernel (one pass over dh and s2)
   // dh, dy (gradients of the normalised rows) and the saved sums s1, s2 are fp32 in every mode
@@ -952,7 +986,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   const double ln_bwd_bytes = (double)N * dn * (8 + es) + 8.0 * N;      // fp32 gradient and input rows read, one row written, statistics
   RUN(timed_launch(m, OURO_TIMING_LAYERNORM, ln_bwd_bytes, st, [&] {
     return launch_layernorm_bwd(st, lnk, dh, b.s2, m->wF(l, o.ln2_g), b.mean2, b.rstd2, ds2,
-                                gslot + o.ln2_g, gslot + o.ln2_b, N, d, dn, true); }));
+                                vc, vc + d, N, d, dn, true, m->vec_stride); }));
   if (dropping) HIPCHK(launch_dropout_apply(st, c.dtype, ds2, ds2m, N, d, d, drop_at(m, 2 * l + 2)));
   RUN(ready(0));
   // FFN2
@@ -961,7 +995,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     g.out_fp32 = 1; g.accumulate = 1;
     RUN(run_gemm_on(m, g, sw));
   }
-  HIPCHK(launch_colsum(sw, c.dtype, ds2m, d, gslot + o.b_2, N, d));
+  HIPCHK(launch_colsum(sw, c.dtype, ds2m, d, vc + 2 * d, N, d, m->vec_stride));
   {
     GemmDesc g = gd(ds2m, d, 0, m->wT(l, o.W_2), d, 1, dz, F, N, F, d);
     g.epilogue = EPI_GELUGRAD; g.Z = b.z; g.ldz = F;
@@ -974,7 +1008,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     g.out_fp32 = 1; g.accumulate = 1;
     RUN(run_gemm_on(m, g, sw));
   }
-  HIPCHK(launch_colsum(sw, c.dtype, dz, F, gslot + o.b_1, N, F));
+  HIPCHK(launch_colsum(sw, c.dtype, dz, F, vc + 5 * d, N, F, m->vec_stride));
   {
     GemmDesc g = gd(dz, F, 0, m->wT(l, o.W_1), F, 1, dy, d, N, d, F);
     g.residual = ds2; g.ldr = d; g.out_fp32 = 1;
@@ -983,7 +1017,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   // LN1
   RUN(timed_launch(m, OURO_TIMING_LAYERNORM, ln_bwd_bytes, st, [&] {
     return launch_layernorm_bwd(st, lnk, dy, b.s1, m->wF(l, o.ln1_g), b.mean1, b.rstd1, ds1,
-                                gslot + o.ln1_g, gslot + o.ln1_b, N, d, dn, true); }));
+                                vc + 3 * d, vc + 4 * d, N, d, dn, true, m->vec_stride); }));
   if (dropping) HIPCHK(launch_dropout_apply(st, c.dtype, ds1, ds1m, N, d, d, drop_at(m, 2 * l + 1)));
   RUN(ready(2));
   // output projection
@@ -1163,6 +1197,9 @@ static int module_backward_impl(ouro_model* m, int k, bool defer_join) {
     RUN(layer_backward(m, l, dh, dx, gslot));
   }
   if (stored) m->mem_valid = mem_valid_at(m, m->t);
+  // the layers' vector gradients: sum of the copies into the slot.  On the stream of the
+  // weight-gradient work, which has waited for every LayerNorm kernel of the module.
+  HIPCHK(launch_sum_segments(m->use_side ? m->side : m->stream, m->segs_dev[k], (int)m->segs[k].size(), m->vec_copies, m->vec_stride, gslot));
   if (m->use_side) {          // the module's gradient is complete once the side work has joined
     HIPCHK(hipEventRecord(m->ev_join, m->side));
     if (!defer_join) {

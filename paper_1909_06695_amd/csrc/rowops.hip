@@ -217,7 +217,7 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const TI* __restrict_
                                                            const float* __restrict__ g, const float* __restrict__ mean,
                                                            const float* __restrict__ rstd, TO* __restrict__ dx,
                                                            float* __restrict__ dg, float* __restrict__ db, int rows, int d,
-                                                           int dn) {
+                                                           int dn, size_t copy_stride) {
   constexpr int N = Group<TI, TO>::N;
   extern __shared__ float red[];                 // [4][d]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -289,6 +289,10 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const TI* __restrict_
     }
   }
   if (!PARAMS) return;
+  // every block adds d sums to the same d addresses; with copy_stride the adds of the blocks of
+  // one XCD (blocks are dealt to the 8 XCDs in launch order) go to that XCD's own copy
+  dg += (blockIdx.x & 7) * copy_stride;
+  db += (blockIdx.x & 7) * copy_stride;
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
 #pragma unroll
@@ -310,7 +314,7 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const TI* __restrict_
 // alternate rows; partial sums are reduced through LDS and added atomically.
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_vec_kernel(const T* __restrict__ x, int ldx, float* __restrict__ out,
-                                                         int rows, int rows_per_block) {
+                                                         int rows, int rows_per_block, size_t copy_stride) {
   constexpr int N = Pack<T>::N;
   __shared__ float red[4][64 * N];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -329,6 +333,7 @@ __global__ __launch_bounds__(256) void colsum_vec_kernel(const T* __restrict__ x
 #pragma unroll
   for (int e = 0; e < N; ++e) red[wave][lane * N + e] = acc[e];
   __syncthreads();
+  out += ((blockIdx.x + gridDim.x * blockIdx.y) & 7) * copy_stride;     // the XCD's own copy (see ln_bwd_fused_kernel)
   for (int c = threadIdx.x; c < 64 * N; c += 256)
     unsafeAtomicAdd(out + blockIdx.x * 64 * N + c, red[0][c] + red[1][c] + red[2][c] + red[3][c]);
 }
@@ -393,9 +398,11 @@ static bool ln_vec_ok(int dtype, const void* dy, const void* x, int d) {
 // dg == nullptr: input gradient only (the parameter gradients then come from
 // launch_layernorm_bwd_params, on any stream that sees dy and x).  fuse_params: dg and db (which
 // must be zero or hold what is to be added to) are produced by the same kernel that writes dx.
+// copy_stride: dg and db are the first of 8 copies that far apart (floats); a kernel that adds
+// from many blocks spreads its adds over them by XCD and the caller sums the copies (0: one copy).
 hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const float* g,
                                 const float* mean, const float* rstd, void* dx, float* dg, float* db,
-                                int rows, int d, int dn, bool fuse_params) {
+                                int rows, int d, int dn, bool fuse_params, size_t copy_stride) {
   if (rows <= 0) return hipSuccess;
   if (dn <= 0 || dn > d) dn = d;
   dim3 grid((rows + 3) / 4), block(256);
@@ -406,7 +413,7 @@ hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const 
     const int npl = (d / grp + 63) / 64;      // groups per lane
     fused = fuse_params && dg && db;
     const size_t smem = fused ? (size_t)4 * d * sizeof(float) : 0;
-#define OURO_LNB2(TI_, TO_, MI_, PAR_) hipLaunchKernelGGL((ln_bwd_fused_kernel<TI_, TO_, MI_, PAR_>), gf, block, smem, s, (const TI_*)dy, (const TI_*)x, g, mean, rstd, (TO_*)dx, dg, db, rows, d, dn)
+#define OURO_LNB2(TI_, TO_, MI_, PAR_) hipLaunchKernelGGL((ln_bwd_fused_kernel<TI_, TO_, MI_, PAR_>), gf, block, smem, s, (const TI_*)dy, (const TI_*)x, g, mean, rstd, (TO_*)dx, dg, db, rows, d, dn, copy_stride)
 #define OURO_LNB(TI_, TO_)                                                                  \
   do {                                                                                      \
     if (fused) { if (npl <= 1) OURO_LNB2(TI_, TO_, 1, true); else if (npl <= 2) OURO_LNB2(TI_, TO_, 2, true); else OURO_LNB2(TI_, TO_, 4, true); } \
@@ -454,15 +461,35 @@ hipError_t launch_layernorm_bwd_params(hipStream_t s, int dtype, const void* dy,
   return hipGetLastError();
 }
 
-hipError_t launch_colsum(hipStream_t s, int dtype, const void* x, int ldx, float* out, int rows, int cols) {
+// One block per segment: sums the 8 copies, zeroes them, adds the sum to its place in dst.
+__global__ __launch_bounds__(256) void sum_segments_kernel(const SumSegment* __restrict__ table, float* __restrict__ src,
+                                                           size_t stride, float* __restrict__ dst) {
+  const SumSegment sg = table[blockIdx.x];
+  if (threadIdx.x >= sg.len) return;
+  float t = 0.f;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    float* p = src + c * stride + sg.src_off + threadIdx.x;
+    t += *p;
+    *p = 0.f;
+  }
+  dst[sg.dst_off + threadIdx.x] += t;
+}
+hipError_t launch_sum_segments(hipStream_t s, const SumSegment* table, int count, float* src, size_t stride, float* dst) {
+  if (count <= 0) return hipSuccess;
+  hipLaunchKernelGGL(sum_segments_kernel, dim3(count), dim3(256), 0, s, table, src, stride, dst);
+  return hipGetLastError();
+}
+
+hipError_t launch_colsum(hipStream_t s, int dtype, const void* x, int ldx, float* out, int rows, int cols, size_t copy_stride) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
   dim3 block(256);
   const int pack = dtype == 1 ? 8 : 4;
   if (cols % (64 * pack) == 0 && ldx % pack == 0 && ptr16(x)) {
     const int rpb = 64;
     dim3 grid(cols / (64 * pack), (rows + rpb - 1) / rpb);
-    if (dtype == 1) hipLaunchKernelGGL(colsum_vec_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, ldx, out, rows, rpb);
-    else hipLaunchKernelGGL(colsum_vec_kernel<float>, grid, block, 0, s, (const float*)x, ldx, out, rows, rpb);
+    if (dtype == 1) hipLaunchKernelGGL(colsum_vec_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, ldx, out, rows, rpb, copy_stride);
+    else hipLaunchKernelGGL(colsum_vec_kernel<float>, grid, block, 0, s, (const float*)x, ldx, out, rows, rpb, copy_stride);
     return hipGetLastError();
   }
   const int rpb = 128;
