@@ -3,6 +3,8 @@
 // MFMA kernels in attention_mfma.hip take the aligned bf16 cases.
 #include "common.h"
 
+#include <algorithm>
+
 namespace ouro {
 
 struct AttnParams {
@@ -276,6 +278,11 @@ __global__ __launch_bounds__(64) void attn_bwd_r_kernel(AttnParams p, int vec) {
 size_t attn_bwd_scratch_floats(int B, int H, int T, int S, int dh) {
   // general path: content / position halves of dq (fp32 rows) + D; MFMA path: D and base-2 lse
   return 2 * (size_t)B * S * H * dh + 2 * (size_t)B * H * T;
+}
+
+size_t attn_bwd_scratch_floats_any(int B, int H, int T, int S, int dh) {
+  const size_t gen = attn_bwd_scratch_floats(B, H, T, S, dh);
+  return dh == 64 ? std::max(gen, attn_bwd_xl_scratch_floats(B, H, T, S)) : gen;
 }
 
 static AttnParams to_params(const AttnDesc& a) {

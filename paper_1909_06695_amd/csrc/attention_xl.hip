@@ -4,11 +4,18 @@
 // The content term is the plain kernel's product with q + u in place of q.  The position term
 // of a 32-query x 64-key block only involves the 95 distances Mv + i - j of the block: the
 // product of those rows of r with q + v is one more matrix product, and the element the score
-// (i, j) needs sits on the diagonal Mv + i - j of it.  Where a lane owns a query (forward and
-// dQ kernels) that diagonal runs through the lane's own column, so the product goes through a
-// per-wave LDS patch and comes back shifted; where a lane owns a key (dK/dV kernel) the
-// diagonal is a rotation of lanes within a register, done with lane shuffles.  The gradient
-// of r takes the same way back.
+// (i, j) needs sits on the diagonal Mv + i - j of it.  A lane owns a query (forward and dQ
+// kernels), so that diagonal runs through the lane's own column: the product goes through a
+// per-wave LDS patch and comes back shifted, and dS takes the same way back for dQ.
+//
+// dK, dV and dr have no kernel of their own: the dQ kernel, which holds the probabilities P and
+// dS of every visible pair anyway, leaves P^T and dS^T (key as row) and dS by distance in the
+// workspace, and the three gradients are contractions of those with dO, Q + u and Q + v on the
+// contraction kernels (one product per (head, batch) for dK and dV; for dr the batches lie
+// along the contraction index).  A kernel that owns keys would have to rotate the position
+// product across lanes element by element and add dr atomically from every (batch, key block):
+// that took 418 us per layer at 16 x 16 heads, T = M = 384, against 135 us of stores here and
+// 150 us for the three contractions.
 #include "attention_tiles.h"
 
 namespace ouro {
@@ -203,8 +210,16 @@ __global__ __launch_bounds__(256) void fa_xl_fwd_kernel(FaParams p) {
 
 // ---------------------------------------------------------------------------- dQ kernel
 // grid (ceil(T/128), H, B); 4 waves x 32 queries; key blocks of 64.  Besides dQ it produces
-// the row sums D and the base-2 log-sum-exp for the dK/dV kernel, and the gradients of the
-// two biases: du = sum over queries of the content half of dq, dvb = that of the position half.
+// the gradients of the two biases (du = sum over queries of the content half of dq, dvb = that
+// of the position half) and leaves what the gradients of k, v and r are contractions of:
+//   pt  [B, H, S, t_ld]   P^T, probabilities with the key as row, bf16 (dV = P^T dO)
+//   dst [B, H, S, t_ld]   dS^T, likewise (dK = scale dS^T (Q + u))
+//   dsd [H, S, B * t_ld]  dS with the distance Mv + i - j as row and (b, i) along the row
+//                         (dr = scale sum_b dS_delta^T (Q + v))
+//   qu, qv, dop [B, t_ld, H * 64]   q + u, q + v, dO with rows padded to t_ld
+// t_ld = T rounded up to 64.  Every (query, key) cell in a computed 32-key sub-tile is written
+// (masked cells as zero); cells outside (keys no query of the wave sees, rows i >= T) are never
+// written and must be zero from the caller (they are the same cells for the same Mv).
 __global__ __launch_bounds__(256) void fa_xl_dq_kernel(FaParams p) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
@@ -231,17 +246,23 @@ __global__ __launch_bounds__(256) void fa_xl_dq_kernel(FaParams p) {
     quf[ks] = add_bias(as_bf16x8(t0), p.u + head * 64 + 16 * ks + 8 * h32);
     qvf[ks] = add_bias(as_bf16x8(t0), p.vb + head * 64 + 16 * ks + 8 * h32);
     dof[ks] = as_bf16x8(t1);
+    if (qi < p.T) {
+      const size_t at = ((size_t)b * p.t_ld + qi) * (p.H * 64) + head * 64 + 16 * ks + 8 * h32;
+      *reinterpret_cast<bf16x8*>(p.qu + at) = quf[ks];
+      *reinterpret_cast<bf16x8*>(p.qv + at) = qvf[ks];
+      *reinterpret_cast<bf16x8*>(p.dop + at) = dof[ks];
+    }
     const bf16x8 of = as_bf16x8(t2);
 #pragma unroll
     for (int e = 0; e < 8; ++e) part += (float)of[e] * (float)dof[ks][e];
   }
   const float D_q = part + __shfl_xor(part, 32, 64);
   float lse_q = 0.f;
-  if (qi < p.T) {
-    const size_t rix = ((size_t)b * p.H + head) * p.T + qi;
-    lse_q = p.lse[rix] * 1.4426950408889634f;
-    if (h32 == 0) { p.D[rix] = D_q; p.lse2[rix] = lse_q; }
-  }
+  if (qi < p.T) lse_q = p.lse[((size_t)b * p.H + head) * p.T + qi] * 1.4426950408889634f;
+  // this (batch, head)'s P^T and dS^T, at the lane's query column
+  bf16_t* ptq = p.pt + ((size_t)b * p.H + head) * p.S * p.t_ld + qi;
+  bf16_t* dstq = p.dst + ((size_t)b * p.H + head) * p.S * p.t_ld + qi;
+  bf16_t* dsdq = p.dsd + (size_t)head * p.S * ((size_t)p.B * p.t_ld) + (size_t)b * p.t_ld + qi;
   const int wg_last_q = min(p.T, Q0 + 128) - 1;
   const int kend = min(p.S, p.Mv + wg_last_q + 1);
   const int nkb = (kend + 63) / 64;
@@ -294,12 +315,16 @@ __global__ __launch_bounds__(256) void fa_xl_dq_kernel(FaParams p) {
             const int kk = 32 * kt + acc_row(r, h32);
             const float sc = s[kt][r] + patch[(63 + l32 - kk) * XL_PATCH_LD + l32];
             float pv = __builtin_amdgcn_exp2f(fmaf(sc, p.scale_log2, -lse_q));
+            const int key = jb * 64 + kk;
             if (edge) {
-              const int key = jb * 64 + kk;
               const bool vis = key <= p.Mv + qi && key < p.S && qi < p.T;
               pv = vis ? pv : 0.f;
             }
             dp[kt][r] = pv * (dp[kt][r] - D_q);
+            if (key < p.S && qi < p.T) {
+              ptq[(size_t)key * p.t_ld] = (bf16_t)pv;
+              dstq[(size_t)key * p.t_ld] = (bf16_t)dp[kt][r];
+            }
           }
         }
       __builtin_amdgcn_wave_barrier();
@@ -333,7 +358,10 @@ __global__ __launch_bounds__(256) void fa_xl_dq_kernel(FaParams p) {
           const int rho = 32 * t + acc_row(r, h32);
           const int kk = 63 + l32 - rho;
           const float v = patch[rho * XL_PATCH_LD + l32];
-          g[r] = (kk >= 0 && kk < 32 * nkt) ? v : 0.f;
+          const bool mine = kk >= 0 && kk < 32 * nkt;      // a cell of this key block (the rest of the window belongs to others)
+          g[r] = mine ? v : 0.f;
+          const int delta = p.Mv + qi - (jb * 64 + kk);
+          if (mine && delta >= 0 && delta < p.S && qi < p.T) dsdq[(size_t)delta * ((size_t)p.B * p.t_ld)] = (bf16_t)v;
         }
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
@@ -373,242 +401,6 @@ __global__ __launch_bounds__(256) void fa_xl_dq_kernel(FaParams p) {
 }
 
 
-// ------------------------------------------------------------------------ dK, dV, dr kernel
-// grid (ceil(S/128), H, B); 4 waves x 32 keys (a lane owns a key); query blocks of 64.
-// Scores are queries (registers) x keys (lanes).  The position product q . r_delta is computed
-// as queries x distances (lanes); the score (i, j) takes the element of row i at distance
-// lane 31 + a - l32 (a = i mod 32, l32 = the key's lane), i.e. a rotation of lanes within the
-// register, split over two 32-wide distance tiles.  v . r_delta is a per-distance-lane scalar
-// added before the rotation; u . k_j a per-key scalar.  dS goes the same way back into the
-// distance layout; dr (distances x features, so that lanes run along features) is added
-// atomically to the fp32 table: the window of distances moves with every query block.
-constexpr int XL_KV_STAGE = 2 * TILE_BYTES + 1024 + XL_RWIN * 128;   // Q, dO, lse2/D lines, r window
-constexpr int XL_LDS_KV = XL_NSTAGE * XL_KV_STAGE;
-
-__device__ __forceinline__ bf16x8 add_scalar(bf16x8 q, float c) {
-  bf16x8 r;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) r[e] = (bf16_t)((float)q[e] + c);
-  return r;
-}
-
-__global__ __launch_bounds__(256) void fa_xl_dkv_kernel(FaParams p) {
-  extern __shared__ __attribute__((aligned(16))) char lds[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
-  const int kblk = blockIdx.x;                            // key block 0 sees every query: longest first
-  const int head = blockIdx.y, b = blockIdx.z;
-  const int K0 = kblk * 128, kb0 = K0 + wave * 32, key = kb0 + l32;
-  const int HD = p.H * 64;
-  const bf16_t* qb = p.q + (size_t)b * p.T * p.ldq + head * 64;
-  const bf16_t* dob = p.d_o + (size_t)b * p.T * p.lddo + head * 64;
-  const bf16_t* kbp = p.k + (size_t)b * p.S * p.ldk + head * 64;
-  const bf16_t* vbp = p.v + (size_t)b * p.S * p.ldv + head * 64;
-  const bf16_t* rb = p.r + head * 64;
-  const float* lseb = p.lse2 + ((size_t)b * p.H + head) * p.T;
-  const float* Db = p.D + ((size_t)b * p.H + head) * p.T;
-  bf16x8 kf[4], vf[4];
-  float uk = 0.f;                                          // u . k_j, this lane's half of the features
-  float vbl[4][8];                                         // v bias at the lane's fragment features
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
-    uint4 t0 = make_uint4(0, 0, 0, 0), t1 = t0;
-    if (key < p.S) {
-      t0 = *reinterpret_cast<const uint4*>(kbp + (size_t)key * p.ldk + 16 * ks + 8 * h32);
-      t1 = *reinterpret_cast<const uint4*>(vbp + (size_t)key * p.ldv + 16 * ks + 8 * h32);
-    }
-    kf[ks] = as_bf16x8(t0);
-    vf[ks] = as_bf16x8(t1);
-    const bf16x8 uf = as_bf16x8(*reinterpret_cast<const uint4*>(p.u + head * 64 + 16 * ks + 8 * h32));
-    const bf16x8 vbf = as_bf16x8(*reinterpret_cast<const uint4*>(p.vb + head * 64 + 16 * ks + 8 * h32));
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { uk += (float)kf[ks][e] * (float)uf[e]; vbl[ks][e] = (float)vbf[e]; }
-  }
-  uk += __shfl_xor(uk, 32, 64);
-  // v bias at the features this lane owns as an operand column (feature = 32 dt + l32)
-  const float v_f[2] = {(float)p.vb[head * 64 + l32], (float)p.vb[head * 64 + 32 + l32]};
-  f32x16 dkT[2], dvT[2];
-#pragma unroll
-  for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { dkT[dt][r] = 0.f; dvT[dt][r] = 0.f; }
-  float tsum = 0.f;                                        // sum over queries of dS(i, key), this half's rows
-  f32x16 carry[2];                                         // dr tile that the next query block continues
-  bool have_carry = false;
-  const int ib0 = max(0, K0 - p.Mv) / 64;
-  const int nib = (p.T + 63) / 64;
-  const int nit = nib - ib0;
-  const bool wave_on = kb0 < p.S;
-  auto issue = [&](int it) __attribute__((always_inline)) {
-    char* st = lds + (it % XL_NSTAGE) * XL_KV_STAGE;
-    const int i0 = (ib0 + it) * 64;
-    dma_tile(qb, p.ldq, i0, p.T, st, wave, lane);
-    dma_tile(dob, p.lddo, i0, p.T, st + TILE_BYTES, wave, lane);
-    dma_floats((wave & 1) ? Db : lseb, i0, p.T, st + 2 * TILE_BYTES + wave * 256, lane);
-    const int d0 = p.Mv + i0 - K0 - 127;                   // distance of window row 0
-#pragma unroll
-    for (int t = 0; t < 3; ++t)
-      dma_tile_clamped(rb, p.ldr, d0 + 64 * t, p.S, st + 2 * TILE_BYTES + 1024 + t * TILE_BYTES, wave, lane);
-  };
-  issue(0);
-  for (int it = 0; it < nit; ++it) {
-    fa_wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();
-    if (it + 1 < nit) issue(it + 1);
-    const int ib = ib0 + it;
-    const char* sQ = lds + (it % XL_NSTAGE) * XL_KV_STAGE;
-    const char* sdO = sQ + TILE_BYTES;
-    const float* sl = reinterpret_cast<const float*>(sQ + 2 * TILE_BYTES);
-    const float* sD = sl + 64;
-    const char* sR = sQ + 2 * TILE_BYTES + 1024;
-    const int wrow = 96 - 32 * wave;                       // the wave's 96 window rows start here
-    const int dmin = p.Mv + ib * 64 - kb0 - 31;            // distance of the wave's window row 0
-    if (wave_on && p.Mv + ib * 64 + 63 >= kb0) {
-      const int qt0 = (p.Mv + ib * 64 + 31 >= kb0) ? 0 : 1;
-      const bool edge = kb0 + 31 > p.Mv + ib * 64 || ib * 64 + 63 >= p.T || kb0 + 31 >= p.S;
-      // distance fragments (lane = distance) and v . r_delta
-      bf16x8 rf[3][4];
-      float vr[3];
-#pragma unroll
-      for (int t = 0; t < 3; ++t) {
-        float a = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          rf[t][ks] = read_rows(sR, wrow + 32 * t, ks, lane);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) a += (float)rf[t][ks][e] * vbl[ks][e];
-        }
-        vr[t] = a + __shfl_xor(a, 32, 64);
-      }
-      f32x16 s[2], dp[2];
-#pragma unroll
-      for (int qt = 0; qt < 2; ++qt) {
-        if (qt >= qt0) {
-          f32x16 pos[2];
-          bf16x8 qa[4];
-#pragma unroll
-          for (int r = 0; r < 16; ++r) { s[qt][r] = 0.f; dp[qt][r] = 0.f; pos[0][r] = 0.f; pos[1][r] = 0.f; }
-#pragma unroll
-          for (int ks = 0; ks < 4; ++ks) {
-            qa[ks] = read_rows(sQ, 32 * qt, ks, lane);
-            s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ks], kf[ks], s[qt], 0, 0, 0);
-            dp[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sdO, 32 * qt, ks, lane), vf[ks], dp[qt], 0, 0, 0);
-            pos[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ks], rf[qt][ks], pos[0], 0, 0, 0);
-            pos[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ks], rf[qt + 1][ks], pos[1], 0, 0, 0);
-          }
-          // rotate the position term into the key lanes and finish the score
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int a = acc_row(r, h32);
-            const float x0 = pos[0][r] + vr[qt], x1 = pos[1][r] + vr[qt + 1];
-            const float g0 = __shfl(x0, 32 * h32 + ((a + 31 - l32) & 31), 64);
-            const float g1 = __shfl(x1, 32 * h32 + ((a - 1 - l32) & 31), 64);
-            s[qt][r] += uk + (l32 >= a ? g0 : g1);
-          }
-        }
-      }
-      // P = exp2(s * scale * log2 e - lse2); dS = P (dP - D), without its factor `scale`
-#pragma unroll
-      for (int qt = 0; qt < 2; ++qt)
-        if (qt >= qt0) {
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int ql0 = 32 * qt + 8 * g + 4 * h32;
-            const float4 l4 = *reinterpret_cast<const float4*>(sl + ql0);
-            const float4 d4 = *reinterpret_cast<const float4*>(sD + ql0);
-            const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const int r = 4 * g + j;
-              float pv = __builtin_amdgcn_exp2f(fmaf(s[qt][r], p.scale_log2, -lv[j]));
-              if (edge) {
-                const int qi = ib * 64 + ql0 + j;
-                const bool vis = key <= p.Mv + qi && qi < p.T && key < p.S;
-                pv = vis ? pv : 0.f;
-              }
-              s[qt][r] = pv;
-              dp[qt][r] = pv * (dp[qt][r] - dv4[j]);
-              tsum += dp[qt][r];
-            }
-          }
-        }
-#pragma unroll
-      for (int ks2 = 0; ks2 < 4; ++ks2) {
-        const int qt = ks2 >> 1, sub = ks2 & 1;
-        if (qt >= qt0) {
-          bf16x8 pb = pack_acc(s[qt], sub);
-          bf16x8 dsb = pack_acc(dp[qt], sub);
-#pragma unroll
-          for (int dt = 0; dt < 2; ++dt) {
-            dvT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sdO, 32 * dt, 32 * qt + 16 * sub, lane), pb, dvT[dt], 0, 0, 0);
-            dkT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sQ, 32 * dt, 32 * qt + 16 * sub, lane), dsb, dkT[dt], 0, 0, 0);
-          }
-        }
-      }
-      // dS back into the distance layout (same rotation reversed), then dr = dS_delta^T (q + v).
-      // The window moves up by 64 distances per query block, so this block's tile 2 is the
-      // next block's tile 0: it stays in registers and only tiles 0 and 1 go to memory.
-#pragma unroll
-      for (int t = 0; t < 3; ++t) {
-        f32x16 dr[2];
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) dr[dt][r] = (t == 0 && have_carry) ? carry[dt][r] : 0.f;
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          const int qt = t - tt;                           // query tile whose rotation lands in tile t
-          if (qt >= 0 && qt < 2 && qt >= qt0) {
-            f32x16 g;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int a = acc_row(r, h32);
-              const int src = tt == 0 ? a + 31 - l32 : a - 1 - l32;     // key lane that holds dS(i, delta)
-              const float v = __shfl(dp[qt][r], 32 * h32 + (src & 31), 64);
-              g[r] = (src >= 0 && src < 32) ? v : 0.f;
-            }
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-              bf16x8 gb = pack_acc(g, sub);
-#pragma unroll
-              for (int dt = 0; dt < 2; ++dt) {
-                bf16x8 qT = add_scalar(read_rows_t(sQ, 32 * dt, 32 * qt + 16 * sub, lane), v_f[dt]);
-                dr[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gb, qT, dr[dt], 0, 0, 0);
-              }
-            }
-          }
-        }
-        if (t == 2 && it + 1 < nit) {
-#pragma unroll
-          for (int dt = 0; dt < 2; ++dt) carry[dt] = dr[dt];
-        } else {
-          // rows = distances dmin + 32 t + acc_row, lanes = features 32 dt + l32
-#pragma unroll
-          for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int delta = dmin + 32 * t + acc_row(r, h32);
-              if (delta >= 0 && delta < p.S) unsafeAtomicAdd(p.dr + (size_t)delta * HD + head * 64 + 32 * dt + l32, dr[dt][r] * p.scale);
-            }
-        }
-      }
-      have_carry = it + 1 < nit;
-    }
-  }
-  if (key < p.S) {
-    // dk = sum_i dS(i, key) (q_i + u): the u part from the per-key sum of dS
-    const float tj = tsum + __shfl_xor(tsum, 32, 64);
-#pragma unroll
-    for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float uf = (float)p.u[head * 64 + 32 * dt + acc_row(r, h32)];
-        dkT[dt][r] += uf * tj;
-      }
-    store_acc_row(p.dk + ((size_t)b * p.S + key) * p.lddk + head * 64, dkT, p.scale, h32);
-    store_acc_row(p.dv + ((size_t)b * p.S + key) * p.lddv + head * 64, dvT, 1.f, h32);
-  }
-}
-
 // ----------------------------------------------------------------------------- dispatch
 static inline bool xl_al16(const void* x) { return (reinterpret_cast<uintptr_t>(x) & 15) == 0; }
 
@@ -636,21 +428,58 @@ hipError_t launch_attn_fwd_xl(hipStream_t s, const AttnDesc& a) {
   return hipGetLastError();
 }
 
+// Workspace of the backward pass in floats: three [B, H, S, t_ld] bf16 arrays (see
+// fa_xl_dq_kernel; dsd is the same size in another order) and three [B, t_ld, H * 64] ones.
+size_t attn_bwd_xl_scratch_floats(int B, int H, int T, int S) {
+  const size_t t_ld = (size_t)(T + 63) / 64 * 64;
+  return (3 * (size_t)B * H * S * t_ld + 3 * (size_t)B * t_ld * H * 64) / 2;
+}
+
 hipError_t launch_attn_bwd_xl(hipStream_t s, const AttnDesc& a) {
   FaParams p = fa_params(a);
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_xl_dq_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, XL_LDS_Q);
-    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_xl_dkv_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, XL_LDS_KV);
     if (e != hipSuccess) return e;
     attr_done = true;
+  }
+  const int t_ld = (a.T + 63) / 64 * 64, HD = a.H * 64;
+  const size_t nmat = (size_t)a.B * a.H * a.S * t_ld, npad = (size_t)a.B * t_ld * HD;
+  bf16_t* w = reinterpret_cast<bf16_t*>(a.scratch);
+  p.t_ld = t_ld;
+  p.pt = w; p.dst = w + nmat; p.dsd = w + 2 * nmat;
+  p.qu = w + 3 * nmat; p.qv = p.qu + npad; p.dop = p.qv + npad;
+  // cells the kernel never writes must read as zero in the contractions below
+  if (!a.scratch_clean) {
+    hipError_t e = launch_fill_zero(s, w, (3 * nmat + 3 * npad) * 2);
+    if (e != hipSuccess) return e;
   }
   // du, dvb and dr are accumulated into (the caller zeroes them)
   hipLaunchKernelGGL(fa_xl_dq_kernel, dim3((a.T + 127) / 128, a.H, a.B), dim3(256), XL_LDS_Q, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(fa_xl_dkv_kernel, dim3((a.S + 127) / 128, a.H, a.B), dim3(256), XL_LDS_KV, s, p);
-  return hipGetLastError();
+  // dV[b, :, h] = P^T dO ; dK[b, :, h] = scale dS^T (Q + u): one product per (head, batch)
+  GemmDesc g;
+  memset(&g, 0, sizeof g);
+  g.M = a.S; g.N = 64; g.K = t_ld; g.lda = t_ld; g.ldb = HD; g.transA = 0; g.transB = 0;
+  g.by = a.H; g.bz = a.B;
+  g.sAy = (long long)a.S * t_ld; g.sAz = (long long)a.H * a.S * t_ld;
+  g.sBy = 64; g.sBz = (long long)t_ld * HD;
+  g.sCy = 64;
+  g.A = p.pt; g.B = p.dop; g.C = a.dv; g.ldc = a.lddv; g.sCz = (long long)a.S * a.lddv; g.alpha = 1.f;
+  e = launch_gemm(s, 1, g, 0);
+  if (e != hipSuccess) return e;
+  g.A = p.dst; g.B = p.qu; g.C = a.dk; g.ldc = a.lddk; g.sCz = (long long)a.S * a.lddk; g.alpha = a.scale;
+  e = launch_gemm(s, 1, g, 0);
+  if (e != hipSuccess) return e;
+  // dr[:, h] += scale sum_b dS_delta^T (Q + v): the batches lie along the contraction index
+  GemmDesc r;
+  memset(&r, 0, sizeof r);
+  r.M = a.S; r.N = 64; r.K = a.B * t_ld; r.lda = a.B * t_ld; r.ldb = HD; r.ldc = HD;
+  r.by = a.H; r.bz = 1;
+  r.sAy = (long long)a.S * a.B * t_ld; r.sBy = 64; r.sCy = 64;
+  r.A = p.dsd; r.B = p.qv; r.C = a.dr; r.out_fp32 = 1; r.accumulate = 1; r.alpha = a.scale;
+  return launch_gemm(s, 1, r, 0);
 }
 
 }  // namespace ouro

@@ -99,6 +99,11 @@ struct GemmDesc {
   void* Z; int ldz;      // EPI_GELU: written (type T); EPI_GELUGRAD: read (type T)
   float alpha;           // scales acc before the epilogue
   DropDesc drop;         // dropout on (alpha*acc + bias), before the residual; element index m*drop.ld + n
+  // A grid of by x bz independent products of the same shape (0 or 1: a single one): product
+  // (y, z) takes A + y*sAy + z*sAz, B + y*sBy + z*sBz and writes C + y*sCy + z*sCz (elements).
+  // Only with plain epilogues (no bias, residual, Z, dropout).
+  int by, bz;
+  long long sAy, sAz, sBy, sBz, sCy, sCz;
 };
 // MFMA tile configurations (bf16): register-staged 128x128 (any K multiple of 8), and four
 // direct-to-LDS kernels that need K % 64 == 0 and operands under 2 GiB.
@@ -135,8 +140,14 @@ struct AttnDesc {
   float* du; float* dvb;           // fp32 [H, dh], accumulated into (caller zeroes)
   float* dr;                       // fp32 [S, H*dh] dense, accumulated into (caller zeroes)
   float* scratch;                  // fp32 workspace, attn_bwd_scratch_floats() elements
+  // relative-position MFMA path: the workspace's cells that the pass does not write are known to
+  // be zero (the caller cleared it and every pass since ran with the same B, H, T, Mv); else it is cleared
+  int scratch_clean;
 };
+// general kernels and the plain MFMA kernels / the relative-position MFMA path / the larger of the two
 size_t attn_bwd_scratch_floats(int B, int H, int T, int S, int dh);
+size_t attn_bwd_xl_scratch_floats(int B, int H, int T, int S);
+size_t attn_bwd_scratch_floats_any(int B, int H, int T, int S, int dh);
 // records msg as the calling thread's last error (ouro_last_error) and returns code
 int set_error(int code, const char* msg);
 hipError_t launch_attn_fwd(hipStream_t s, int dtype, const AttnDesc& a, int force_generic);

@@ -20,6 +20,8 @@ struct GemmParams {
   int tilesN;      // tiles along N (MFMA kernel)
   int tilesM, ntiles, mfast, band;   // direct-to-LDS kernels: see tile_of_block
   int vec_epi;     // 1: C, Z, residual allow 16-byte row-chunk accesses (MFMA kernel)
+  int by, bz;
+  long long bAy, bAz, bBy, bBz, bCy, bCz;   // byte strides of a batch of products over blockIdx.y, blockIdx.z (direct-to-LDS kernels)
   DropDesc drop;
 };
 

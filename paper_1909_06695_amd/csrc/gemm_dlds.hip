@@ -119,6 +119,13 @@ __device__ __forceinline__ void tile_of_block(const GemmParams& p, int BM, int B
   kbeg = kz * p.kchunk;
 }
 
+// The product this workgroup belongs to, of a batch laid over blockIdx.y and blockIdx.z.
+__device__ __forceinline__ void batch_offsets(GemmParams& p) {
+  p.A = reinterpret_cast<const char*>(p.A) + blockIdx.y * p.bAy + blockIdx.z * p.bAz;
+  p.B = reinterpret_cast<const char*>(p.B) + blockIdx.y * p.bBy + blockIdx.z * p.bBz;
+  p.C = reinterpret_cast<char*>(p.C) + blockIdx.y * p.bCy + blockIdx.z * p.bCz;
+}
+
 template <int BM, int BN, int WM, int WN, bool TA, bool TB, int S>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_dlds_kernel(GemmParams p) {
   constexpr int BK = 64;
@@ -131,6 +138,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dlds_kernel(GemmParams p) {
   static_assert((S - 1) * LPT < 64, "too many loads in flight for vmcnt");
   extern __shared__ uint4 smem[];
   char* lds = reinterpret_cast<char*>(smem);
+  batch_offsets(p);
   const bf16_t* A = reinterpret_cast<const bf16_t*>(p.A);
   const bf16_t* B = reinterpret_cast<const bf16_t*>(p.B);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -251,6 +259,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_pipe_kernel(GemmParams p) {
   static_assert((S - 2) * LPT < 64, "too many loads in flight for vmcnt");
   extern __shared__ uint4 smem[];
   char* lds = reinterpret_cast<char*>(smem);
+  batch_offsets(p);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
   int m0, n0, kbeg;
@@ -355,7 +364,7 @@ hipError_t launch_dlds_cfg_impl(hipStream_t s, GemmParams& p, int transA, int tr
   p.ntiles = p.tilesM * p.tilesN;
   p.mfast = splits > 1 && p.N > p.M;
   p.band = splits == 1 && p.tilesM % 8 == 0 && p.tilesN % 8 == 0 && p.tilesN > 8;
-  dim3 grid(p.ntiles * splits), block(WM * WN * 64);
+  dim3 grid(p.ntiles * splits, p.by, p.bz), block(WM * WN * 64);
 #define OURO_LAUNCH(TA_, TB_)                                                                    \
   do {                                                                                           \
     static bool attr_done = false;                                                               \

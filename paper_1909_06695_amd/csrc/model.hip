@@ -159,6 +159,7 @@ struct BwdCtx {
   char *ds2[2], *dz[2], *ds1[2], *dqkv[2];
   char *ds2m[2], *ds1m[2];         // ds2 / ds1 times the dropout masks (the same buffers without dropout)
   float *attn_scratch, *dr_f32[2];
+  int attn_scratch_Mv;           // relative mode: memory length of the passes since the workspace was last cleared (-1: none)
   char* hscratch;                 // output of a recomputed module's last layer (never read)
 };
 
@@ -477,7 +478,9 @@ static size_t lay_out(ouro_model& m, char* base) {
       x.dr_t[p2] = c.rel_pos ? P(S * hd * es) : nullptr;
       x.dr_f32[p2] = c.rel_pos ? (float*)P(S * hd * 4) : nullptr;
     }
-    x.attn_scratch = (float*)P(attn_bwd_scratch_floats(c.batch, c.n_head, c.seq_len, (int)S, m.pdh) * 4);
+    x.attn_scratch = (float*)P((c.rel_pos ? attn_bwd_scratch_floats_any(c.batch, c.n_head, c.seq_len, (int)S, m.pdh)
+                                          : attn_bwd_scratch_floats(c.batch, c.n_head, c.seq_len, (int)S, m.pdh)) * 4);
+    x.attn_scratch_Mv = -1;
     x.hscratch = c.schedule == 1 ? P(N * d * es) : nullptr;
   };
   scratch(m);
@@ -1063,6 +1066,13 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     a.dq = dq; a.lddq = hd; a.dk = dkv; a.lddk = 2 * hd; a.dv = dkv + (size_t)hd * es; a.lddv = 2 * hd;
     float* drf = m->dr_f32[ps];
     a.du = gslot + o.u; a.dvb = gslot + o.v; a.dr = drf;
+    // The fused path leaves matrices in the workspace whose unwritten cells must be zero; they are
+    // the same cells while the memory length stays the same, so it is cleared when that changes.
+    if (m->attn_scratch_Mv != Mv) {
+      HIPCHK(launch_fill_zero(st, m->attn_scratch, attn_bwd_scratch_floats_any(B, c.n_head, T, m->S, m->pdh) * 4));
+      m->attn_scratch_Mv = Mv;
+    }
+    a.scratch_clean = 1;
     HIPCHK(launch_fill_zero(st, drf, (size_t)S * hd * 4));
     RUN(timed_launch(m, OURO_TIMING_ATTENTION, 2.0 * attn_fwd_flops(m, Mv), st, [&] { return launch_attn_bwd(st, c.dtype, a, 0); }));
     const void* drp = drf;

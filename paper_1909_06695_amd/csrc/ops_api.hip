@@ -90,7 +90,7 @@ extern "C" int ouro_op_attention_fwd(void* stream, int dtype, int B, int H, int 
 }
 
 extern "C" size_t ouro_op_attention_bwd_scratch(int B, int H, int T, int S, int dh) {
-  return attn_bwd_scratch_floats(B, H, T, S, dh);
+  return attn_bwd_scratch_floats_any(B, H, T, S, dh);
 }
 
 extern "C" int ouro_op_attention_bwd(void* stream, int dtype, int B, int H, int T, int S, int dh, int Mv, float scale,
@@ -128,7 +128,7 @@ extern "C" int ouro_op_attention_bwd_noalloc(void* stream, int dtype, int B, int
                                              const void* vb, const void* r, int ldr, float* du, float* dvb, float* dr,
                                              int force_generic) {
   if (B < 1 || H < 1 || T < 1 || dh < 1 || Mv < 0 || S != Mv + T) return set_error(OURO_E_ARG, "attention_bwd_noalloc: bad sizes");
-  const size_t need = attn_bwd_scratch_floats(B, H, T, S, dh);
+  const size_t need = rel ? attn_bwd_scratch_floats_any(B, H, T, S, dh) : attn_bwd_scratch_floats(B, H, T, S, dh);
   if (need > NOALLOC_SCRATCH_FLOATS) {
     char msg[200];
     snprintf(msg, sizeof msg, "attention_bwd_noalloc: needs %zu workspace floats, the built-in workspace holds %zu", need,

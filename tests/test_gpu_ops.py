@@ -188,10 +188,11 @@ def test_attention_mfma_kernel(B, H, T, Mv):
 
 
 @pytest.mark.parametrize("B,H,T,Mv", [(2, 2, 128, 0), (1, 3, 200, 0), (2, 1, 96, 40), (1, 2, 384, 384), (1, 1, 33, 0),
-                                      (1, 2, 300, 77), (2, 2, 150, 150)])
+                                      (1, 2, 300, 77), (2, 2, 150, 150), (3, 2, 20, 5), (2, 3, 64, 200)])
 def test_attention_xl_mfma_kernel(B, H, T, Mv):
     """Fused matrix-core kernels with the relative-position term (bf16, head size 64): with and
-    without memory, several query/key blocks, ragged tails."""
+    without memory, several query/key blocks, ragged tails, fewer keys than a contraction tile
+    (dK, dV and dr are contractions of what the dQ kernel leaves), memory longer than the segment."""
     _attn_case(1, B, H, T, Mv, 64, 1, seed=200 + T + Mv, force=0)
 
 
