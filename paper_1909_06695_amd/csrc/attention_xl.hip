@@ -467,11 +467,17 @@ hipError_t launch_attn_bwd_xl(hipStream_t s, const AttnDesc& a) {
   g.sBy = 64; g.sBz = (long long)t_ld * HD;
   g.sCy = 64;
   g.A = p.pt; g.B = p.dop; g.C = a.dv; g.ldc = a.lddv; g.sCz = (long long)a.S * a.lddv; g.alpha = 1.f;
-  e = launch_gemm(s, 1, g, 0);
-  if (e != hipSuccess) return e;
-  g.A = p.dst; g.B = p.qu; g.C = a.dk; g.ldc = a.lddk; g.sCz = (long long)a.S * a.lddk; g.alpha = a.scale;
-  e = launch_gemm(s, 1, g, 0);
-  if (e != hipSuccess) return e;
+  if (a.lddk == a.lddv) {          // both grids in one launch
+    g.A2 = p.dst; g.B2 = p.qu; g.C2 = a.dk; g.alpha2 = a.scale;
+    e = launch_gemm(s, 1, g, 0);
+    if (e != hipSuccess) return e;
+  } else {
+    e = launch_gemm(s, 1, g, 0);
+    if (e != hipSuccess) return e;
+    g.A = p.dst; g.B = p.qu; g.C = a.dk; g.ldc = a.lddk; g.sCz = (long long)a.S * a.lddk; g.alpha = a.scale;
+    e = launch_gemm(s, 1, g, 0);
+    if (e != hipSuccess) return e;
+  }
   // dr[:, h] += scale sum_b dS_delta^T (Q + v): the batches lie along the contraction index
   GemmDesc r;
   memset(&r, 0, sizeof r);

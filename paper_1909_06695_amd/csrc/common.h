@@ -104,6 +104,10 @@ struct GemmDesc {
   // Only with plain epilogues (no bias, residual, Z, dropout).
   int by, bz;
   long long sAy, sAz, sBy, sBz, sCy, sCz;
+  // A second grid of products of the same shape, strides and leading dimensions in the same
+  // launch (C2 != null): A2, B2, C2 and alpha2 in place of A, B, C and alpha.  Two grids of short
+  // products are bound by memory latency; side by side they keep twice as many loads in flight.
+  const void* A2; const void* B2; void* C2; float alpha2;
 };
 // MFMA tile configurations (bf16): register-staged 128x128 (any K multiple of 8), and four
 // direct-to-LDS kernels that need K % 64 == 0 and operands under 2 GiB.

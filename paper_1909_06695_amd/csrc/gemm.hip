@@ -208,26 +208,32 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
   // a batch of products: over the grid's y and z in the direct-to-LDS kernels, else one launch each
   const int by = std::max(1, g.by), bz = std::max(1, g.bz);
   const size_t esz = dtype == 1 ? 2 : 4, csz = g.out_fp32 ? 4 : esz;
-  p.by = by; p.bz = bz;
+  const int grids = g.C2 ? 2 : 1;
+  if (g.C2 && (!g.A2 || !g.B2)) return hipErrorInvalidValue;
+  p.by = by; p.bz = bz * grids; p.bz1 = bz;
+  p.A2 = g.A2; p.B2 = g.B2; p.C2 = g.C2; p.alpha2 = g.alpha2;
   p.bAy = g.sAy * (long long)esz; p.bAz = g.sAz * (long long)esz;
   p.bBy = g.sBy * (long long)esz; p.bBz = g.sBz * (long long)esz;
   p.bCy = g.sCy * (long long)csz; p.bCz = g.sCz * (long long)csz;
-  if (by * bz > 1) {
+  if (by * bz * grids > 1) {
     if (g.bias || g.residual || g.res32 || g.epilogue != EPI_NONE || g.drop.on) return hipErrorInvalidValue;
     const size_t bA = 2 * (size_t)(g.transA ? g.K : g.M) * g.lda, bB = 2 * (size_t)(g.transB ? g.N : g.K) * g.ldb;
     const bool in_grid = force_generic != 1 && gemm_uses_mfma(dtype, g) && (g.K % 64) == 0 && bA < (1ull << 31) && bB < (1ull << 31) &&
-                         !((p.bAy | p.bAz | p.bBy | p.bBz | p.bCy | p.bCz) & 15);
+                         !((p.bAy | p.bAz | p.bBy | p.bBz | p.bCy | p.bCz) & 15) &&
+                         (!g.C2 || (aligned16(g.A2) && aligned16(g.B2) && aligned16(g.C2) == aligned16(g.C)));
     if (!in_grid) {
-      for (int z = 0; z < bz; ++z)
-        for (int y = 0; y < by; ++y) {
-          GemmDesc h = g;
-          h.by = h.bz = 0;
-          h.A = (const char*)g.A + y * p.bAy + z * p.bAz;
-          h.B = (const char*)g.B + y * p.bBy + z * p.bBz;
-          h.C = (char*)g.C + y * p.bCy + z * p.bCz;
-          hipError_t e = launch_gemm(s, dtype, h, force_generic);
-          if (e != hipSuccess) return e;
-        }
+      for (int w = 0; w < grids; ++w)
+        for (int z = 0; z < bz; ++z)
+          for (int y = 0; y < by; ++y) {
+            GemmDesc h = g;
+            h.by = h.bz = 0; h.A2 = h.B2 = nullptr; h.C2 = nullptr;
+            h.A = (const char*)(w ? g.A2 : g.A) + y * p.bAy + z * p.bAz;
+            h.B = (const char*)(w ? g.B2 : g.B) + y * p.bBy + z * p.bBz;
+            h.C = (char*)(w ? g.C2 : g.C) + y * p.bCy + z * p.bCz;
+            if (w) h.alpha = g.alpha2;
+            hipError_t e = launch_gemm(s, dtype, h, force_generic);
+            if (e != hipSuccess) return e;
+          }
       return hipSuccess;
     }
   }
@@ -267,7 +273,7 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
       double best = 1e30;
       for (int c = 0; c < 2; ++c) {
         const int bm = 128, bn = c ? 64 : 128, per_cu = c ? 3 : 2;
-        const long tiles = (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) * by * bz;
+        const long tiles = (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) * by * bz * grids;
         const int max_s = std::min(16, g.K / 256);
         for (int sp = 1; sp <= max_s; ++sp) {
           const int kc = ((g.K + sp - 1) / sp + 63) / 64 * 64;
@@ -282,7 +288,7 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
     if (!direct_ok) cfg = GEMM_TILE_STAGED128;
     if (cfg < GEMM_TILE_STAGED128 || cfg > GEMM_TILE_256x256) return hipErrorInvalidValue;
     const int BM = cfg == GEMM_TILE_256x256 ? 256 : 128, BN = cfg == GEMM_TILE_128x64 ? 64 : BM;
-    int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN) * by * bz;
+    int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN) * by * bz * grids;
     if (g.accumulate && !modelled && tiles < 384 && g.K >= 512) {
       splits = (512 + tiles - 1) / tiles;
       int maxs = g.K / 256;

@@ -20,7 +20,8 @@ struct GemmParams {
   int tilesN;      // tiles along N (MFMA kernel)
   int tilesM, ntiles, mfast, band;   // direct-to-LDS kernels: see tile_of_block
   int vec_epi;     // 1: C, Z, residual allow 16-byte row-chunk accesses (MFMA kernel)
-  int by, bz;
+  int by, bz, bz1;                          // bz1: blockIdx.z from here on belongs to the second grid of products
+  const void* A2; const void* B2; void* C2; float alpha2;
   long long bAy, bAz, bBy, bBz, bCy, bCz;   // byte strides of a batch of products over blockIdx.y, blockIdx.z (direct-to-LDS kernels)
   DropDesc drop;
 };

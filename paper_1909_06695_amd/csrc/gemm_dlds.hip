@@ -121,9 +121,11 @@ __device__ __forceinline__ void tile_of_block(const GemmParams& p, int BM, int B
 
 // The product this workgroup belongs to, of a batch laid over blockIdx.y and blockIdx.z.
 __device__ __forceinline__ void batch_offsets(GemmParams& p) {
-  p.A = reinterpret_cast<const char*>(p.A) + blockIdx.y * p.bAy + blockIdx.z * p.bAz;
-  p.B = reinterpret_cast<const char*>(p.B) + blockIdx.y * p.bBy + blockIdx.z * p.bBz;
-  p.C = reinterpret_cast<char*>(p.C) + blockIdx.y * p.bCy + blockIdx.z * p.bCz;
+  int z = blockIdx.z;
+  if (z >= p.bz1) { z -= p.bz1; p.A = p.A2; p.B = p.B2; p.C = p.C2; p.alpha = p.alpha2; }
+  p.A = reinterpret_cast<const char*>(p.A) + blockIdx.y * p.bAy + z * p.bAz;
+  p.B = reinterpret_cast<const char*>(p.B) + blockIdx.y * p.bBy + z * p.bBz;
+  p.C = reinterpret_cast<char*>(p.C) + blockIdx.y * p.bCy + z * p.bCz;
 }
 
 template <int BM, int BN, int WM, int WN, bool TA, bool TB, int S>
