@@ -56,9 +56,9 @@ size_t ouro_op_attention_bwd_scratch(int B, int H, int T, int S, int dh);
 /* ouro_op_attention_bwd for callers that cannot allocate device memory (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): the same arguments without
  * `scratch`; the workspace is a device array inside the library, 4 Mi floats (16 MiB) on every
- * GPU the library runs on, held until the process ends.  Sizes whose
- * ouro_op_attention_bwd_scratch() exceeds 4194304 floats are refused with OURO_E_ARG
- * (ouro_last_error says how much was needed).  The call allocates and frees nothing; it clears
+ * GPU the library runs on, held until the process ends.  Sizes that need more than 4194304
+ * floats (rel != 0: ouro_op_attention_bwd_scratch(); rel == 0: 2*B*S*H*dh + 2*B*H*T) are refused
+ * with OURO_E_ARG (ouro_last_error says how much was needed).  The call allocates and frees nothing; it clears
  * the part of the workspace it uses with a fill kernel on `stream`, then enqueues the same
  * kernels as ouro_op_attention_bwd.  All calls on one GPU share that GPU's workspace: calls
  * that may overlap on one GPU (different streams, different threads) race; keep them on one
