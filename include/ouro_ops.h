@@ -44,8 +44,8 @@ int ouro_op_attention_fwd(void* stream, int dtype, int B, int H, int T, int S, i
 /* Backward of the above.  du, dvb (fp32 [H,dh]) and dr (fp32 [S, H*dh]) are overwritten when
  * rel != 0 (may be NULL otherwise).  scratch: fp32, ouro_op_attention_bwd_scratch() floats,
  * 16-byte aligned: enough for either form (with rel != 0, bf16 and dh == 64 the pass leaves the
- * probabilities and score gradients there, about 1.5 * B*H*S*T floats, and forms dk, dv and dr as
- * contractions of them). */
+ * probabilities and score gradients there, about B*H*S*T floats, and forms dk, dv and dr from
+ * them). */
 int ouro_op_attention_bwd(void* stream, int dtype, int B, int H, int T, int S, int dh, int Mv,
                           float scale, const void* q, int ldq, const void* k, int ldk,
                           const void* v, int ldv, const void* o, int ldo, const float* lse,

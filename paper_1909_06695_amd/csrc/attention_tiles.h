@@ -27,7 +27,7 @@ struct FaParams {
   const bf16_t* r; int ldr;
   float* du; float* dvb; float* dr;
   // what the relative-position dQ kernel leaves for the contractions that give dK, dV and dr
-  bf16_t *pt, *dst, *dsd, *qu, *qv, *dop;
+  bf16_t *pt, *dst, *qu, *qv, *dop;
   int t_ld;
 };
 
@@ -151,7 +151,7 @@ inline FaParams fa_params(const AttnDesc& a) {
   p.lse2 = a.scratch ? a.scratch + (size_t)a.B * a.H * a.T : nullptr;
   p.u = (const bf16_t*)a.u; p.vb = (const bf16_t*)a.vb; p.r = (const bf16_t*)a.r; p.ldr = a.ldr;
   p.du = a.du; p.dvb = a.dvb; p.dr = a.dr;
-  p.pt = p.dst = p.dsd = p.qu = p.qv = p.dop = nullptr; p.t_ld = 0;
+  p.pt = p.dst = p.qu = p.qv = p.dop = nullptr; p.t_ld = 0;
   return p;
 }
 

@@ -8,15 +8,16 @@
 // kernels), so that diagonal runs through the lane's own column: the product goes through a
 // per-wave LDS patch and comes back shifted, and dS takes the same way back for dQ.
 //
-// dK, dV and dr have no kernel of their own: the dQ kernel, which holds the probabilities P and
-// dS of every visible pair anyway, leaves P^T and dS^T (key as row) and dS by distance in the
-// workspace, and the three gradients are contractions of those with dO, Q + u and Q + v on the
-// contraction kernels (one product per (head, batch) for dK and dV; for dr the batches lie
-// along the contraction index).  A kernel that owns keys would have to rotate the position
-// product across lanes element by element and add dr atomically from every (batch, key block):
-// that took 418 us per layer at 16 x 16 heads, T = M = 384, against 135 us of stores here and
-// 150 us for the three contractions.
+// dK and dV have no attention kernel of their own: the dQ kernel, which holds the probabilities
+// P and dS of every visible pair anyway, leaves P^T and dS^T (key as row) in the workspace, and
+// dV = P^T dO, dK = scale dS^T (Q + u) are contractions on the contraction kernels (one product
+// per (head, batch)); dr is gathered from dS^T along its diagonals by fa_xl_dr_kernel.  A kernel
+// that owns keys would have to rotate the position product across lanes element by element and
+// add dr atomically from every (batch, key block): that took 418 us per layer at 16 x 16 heads,
+// T = M = 384.
 #include "attention_tiles.h"
+
+#include <algorithm>
 
 namespace ouro {
 
@@ -213,9 +214,7 @@ __global__ __launch_bounds__(256) void fa_xl_fwd_kernel(FaParams p) {
 // the gradients of the two biases (du = sum over queries of the content half of dq, dvb = that
 // of the position half) and leaves what the gradients of k, v and r are contractions of:
 //   pt  [B, H, S, t_ld]   P^T, probabilities with the key as row, bf16 (dV = P^T dO)
-//   dst [B, H, S, t_ld]   dS^T, likewise (dK = scale dS^T (Q + u))
-//   dsd [H, S, B * t_ld]  dS with the distance Mv + i - j as row and (b, i) along the row
-//                         (dr = scale sum_b dS_delta^T (Q + v))
+//   dst [B, H, S, t_ld]   dS^T, likewise (dK = scale dS^T (Q + u); dr: fa_xl_dr_kernel)
 //   qu, qv, dop [B, t_ld, H * 64]   q + u, q + v, dO with rows padded to t_ld
 // t_ld = T rounded up to 64.  Every (query, key) cell in a computed 32-key sub-tile is written
 // (masked cells as zero); cells outside (keys no query of the wave sees, rows i >= T) are never
@@ -262,7 +261,6 @@ __global__ __launch_bounds__(256) void fa_xl_dq_kernel(FaParams p) {
   // this (batch, head)'s P^T and dS^T, at the lane's query column
   bf16_t* ptq = p.pt + ((size_t)b * p.H + head) * p.S * p.t_ld + qi;
   bf16_t* dstq = p.dst + ((size_t)b * p.H + head) * p.S * p.t_ld + qi;
-  bf16_t* dsdq = p.dsd + (size_t)head * p.S * ((size_t)p.B * p.t_ld) + (size_t)b * p.t_ld + qi;
   const int wg_last_q = min(p.T, Q0 + 128) - 1;
   const int kend = min(p.S, p.Mv + wg_last_q + 1);
   const int nkb = (kend + 63) / 64;
@@ -358,10 +356,7 @@ __global__ __launch_bounds__(256) void fa_xl_dq_kernel(FaParams p) {
           const int rho = 32 * t + acc_row(r, h32);
           const int kk = 63 + l32 - rho;
           const float v = patch[rho * XL_PATCH_LD + l32];
-          const bool mine = kk >= 0 && kk < 32 * nkt;      // a cell of this key block (the rest of the window belongs to others)
-          g[r] = mine ? v : 0.f;
-          const int delta = p.Mv + qi - (jb * 64 + kk);
-          if (mine && delta >= 0 && delta < p.S && qi < p.T) dsdq[(size_t)delta * ((size_t)p.B * p.t_ld)] = (bf16_t)v;
+          g[r] = (kk >= 0 && kk < 32 * nkt) ? v : 0.f;
         }
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
@@ -401,6 +396,83 @@ __global__ __launch_bounds__(256) void fa_xl_dq_kernel(FaParams p) {
 }
 
 
+// ------------------------------------------------------------------------------ dr kernel
+// dr[delta, f] += scale * sum over (b, i) of dS(b, i, j = Mv + i - delta) * (q + v)(b, i, f), from
+// the dS^T the dQ kernel left (key as row).  grid (ceil(S/64) distance blocks, H, batch groups);
+// 4 waves: wave = (32 of the 64 distances) x (32 of the 64 features).  Per (batch, 64 queries)
+// the cells that meet the block's distances lie in 127 key rows of dS^T; they are staged in LDS
+// with rows of 33 dwords, so that the lanes of a fragment read, which walk a diagonal (next
+// distance = previous key row, same query column), fall on 32 different banks.  Rows outside
+// [0, S) are staged as zeros.  The fragment's eight contraction slots hold the queries
+// 8 (e / 4) + 4 half + e % 4 of a 16-query step, the order of the transposing LDS read that
+// fetches the (q + v) operand.
+constexpr int DR_LD = 132;                               // bytes per staged row
+constexpr int DR_STAGE = 128 * DR_LD + TILE_BYTES;       // dS^T rows + the (q + v) tile
+constexpr int XL_LDS_DR = 2 * DR_STAGE;
+
+__global__ __launch_bounds__(256) void fa_xl_dr_kernel(FaParams p, int bpw) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
+  const int D0 = blockIdx.x * 64, head = blockIdx.y;
+  const int b0 = blockIdx.z * bpw, nb = min(p.B, b0 + bpw) - b0;
+  const int wd = wave & 1, wf = wave >> 1;
+  const int HD = p.H * 64;
+  const int nib = (p.T + 63) / 64;
+  const int ib_lo = max(0, D0 - p.Mv) / 64;              // first query block with a key at these distances
+  const int nper = nib - ib_lo;
+  const int nit = nb * nper;
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  uint4 stage[4];
+  auto fetch = [&](int it) __attribute__((always_inline)) {
+    const int b = b0 + it / nper, i0 = (ib_lo + it % nper) * 64;
+    const int jbase = p.Mv + i0 - D0 - 63;
+    const bf16_t* src = p.dst + ((size_t)b * p.H + head) * p.S * p.t_ld + i0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = tid + 256 * q, r = c >> 3, cc = c & 7, j = jbase + r;
+      stage[q] = make_uint4(0, 0, 0, 0);
+      if (j >= 0 && j < p.S) stage[q] = *reinterpret_cast<const uint4*>(src + (size_t)j * p.t_ld + 8 * cc);
+    }
+    dma_tile(p.qv + (size_t)b * p.t_ld * HD + head * 64, HD, i0, p.t_ld, lds + (it & 1) * DR_STAGE + 128 * DR_LD, wave, lane);
+  };
+  auto put = [&](int it) __attribute__((always_inline)) {
+    char* sT = lds + (it & 1) * DR_STAGE;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = tid + 256 * q, r = c >> 3, cc = c & 7;
+      uint32_t* d = reinterpret_cast<uint32_t*>(sT + r * DR_LD + cc * 16);
+      d[0] = stage[q].x; d[1] = stage[q].y; d[2] = stage[q].z; d[3] = stage[q].w;
+    }
+  };
+  if (nit > 0) { fetch(0); put(0); }
+  for (int it = 0; it < nit; ++it) {
+    fa_wait_vmcnt<0>();                                   // this iteration's (q + v) tile has landed
+    __syncthreads();                                      // ... and every wave's share of the staged rows is written
+    if (it + 1 < nit) fetch(it + 1);
+    const char* sT = lds + (it & 1) * DR_STAGE;
+    const char* sQ = sT + 128 * DR_LD;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      union { uint16_t h[8]; bf16x8 v; } a;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int qq = 16 * ks + 8 * (e >> 2) + 4 * h32 + (e & 3);
+        const int row = qq - (32 * wd + l32) + 63;
+        a.h[e] = *reinterpret_cast<const uint16_t*>(sT + row * DR_LD + qq * 2);
+      }
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, read_rows_t(sQ, 32 * wf, 16 * ks, lane), acc, 0, 0, 0);
+    }
+    if (it + 1 < nit) put(it + 1);                         // the other buffer: last read before the barrier above
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int delta = D0 + 32 * wd + acc_row(r, h32);
+    if (delta < p.S && nit > 0) unsafeAtomicAdd(p.dr + (size_t)delta * HD + head * 64 + 32 * wf + l32, acc[r] * p.scale);
+  }
+}
+
 // ----------------------------------------------------------------------------- dispatch
 static inline bool xl_al16(const void* x) { return (reinterpret_cast<uintptr_t>(x) & 15) == 0; }
 
@@ -428,11 +500,11 @@ hipError_t launch_attn_fwd_xl(hipStream_t s, const AttnDesc& a) {
   return hipGetLastError();
 }
 
-// Workspace of the backward pass in floats: three [B, H, S, t_ld] bf16 arrays (see
-// fa_xl_dq_kernel; dsd is the same size in another order) and three [B, t_ld, H * 64] ones.
+// Workspace of the backward pass in floats: two [B, H, S, t_ld] bf16 arrays (see
+// fa_xl_dq_kernel) and three [B, t_ld, H * 64] ones.
 size_t attn_bwd_xl_scratch_floats(int B, int H, int T, int S) {
   const size_t t_ld = (size_t)(T + 63) / 64 * 64;
-  return (3 * (size_t)B * H * S * t_ld + 3 * (size_t)B * t_ld * H * 64) / 2;
+  return (2 * (size_t)B * H * S * t_ld + 3 * (size_t)B * t_ld * H * 64) / 2;
 }
 
 hipError_t launch_attn_bwd_xl(hipStream_t s, const AttnDesc& a) {
@@ -447,11 +519,11 @@ hipError_t launch_attn_bwd_xl(hipStream_t s, const AttnDesc& a) {
   const size_t nmat = (size_t)a.B * a.H * a.S * t_ld, npad = (size_t)a.B * t_ld * HD;
   bf16_t* w = reinterpret_cast<bf16_t*>(a.scratch);
   p.t_ld = t_ld;
-  p.pt = w; p.dst = w + nmat; p.dsd = w + 2 * nmat;
-  p.qu = w + 3 * nmat; p.qv = p.qu + npad; p.dop = p.qv + npad;
+  p.pt = w; p.dst = w + nmat;
+  p.qu = w + 2 * nmat; p.qv = p.qu + npad; p.dop = p.qv + npad;
   // cells the kernel never writes must read as zero in the contractions below
   if (!a.scratch_clean) {
-    hipError_t e = launch_fill_zero(s, w, (3 * nmat + 3 * npad) * 2);
+    hipError_t e = launch_fill_zero(s, w, (2 * nmat + 3 * npad) * 2);
     if (e != hipSuccess) return e;
   }
   // du, dvb and dr are accumulated into (the caller zeroes them)
@@ -478,14 +550,11 @@ hipError_t launch_attn_bwd_xl(hipStream_t s, const AttnDesc& a) {
     e = launch_gemm(s, 1, g, 0);
     if (e != hipSuccess) return e;
   }
-  // dr[:, h] += scale sum_b dS_delta^T (Q + v): the batches lie along the contraction index
-  GemmDesc r;
-  memset(&r, 0, sizeof r);
-  r.M = a.S; r.N = 64; r.K = a.B * t_ld; r.lda = a.B * t_ld; r.ldb = HD; r.ldc = HD;
-  r.by = a.H; r.bz = 1;
-  r.sAy = (long long)a.S * a.B * t_ld; r.sBy = 64; r.sCy = 64;
-  r.A = p.dsd; r.B = p.qv; r.C = a.dr; r.out_fp32 = 1; r.accumulate = 1; r.alpha = a.scale;
-  return launch_gemm(s, 1, r, 0);
+  // dr += scale sum over (b, i) of dS at distance delta times (q + v): about 768 workgroups
+  const int ndb = (a.S + 63) / 64;
+  const int bpw = std::max(1, (int)((long long)a.B * ndb * a.H / 768));
+  hipLaunchKernelGGL(fa_xl_dr_kernel, dim3(ndb, a.H, (a.B + bpw - 1) / bpw), dim3(256), XL_LDS_DR, s, p, bpw);
+  return hipGetLastError();
 }
 
 }  // namespace ouro
