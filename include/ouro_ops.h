@@ -28,6 +28,17 @@ int ouro_op_gemm(void* stream, int dtype, int transA, int transB, int M, int N, 
                  const void* A, int lda, const void* B, int ldb, void* C, int ldc, int out_fp32,
                  int accumulate, const float* bias, const void* residual, int ldr, int epilogue,
                  void* Z, int ldz, int force_generic);
+/* A grid of by x bz products of one shape in one call (plain epilogue): product (y, z) reads
+ * A + y*sAy + z*sAz and B + y*sBy + z*sBz and writes C + y*sCy + z*sCz (strides in elements).
+ * With C2 != NULL a second grid of the same shape, strides and leading dimensions runs in the
+ * same launch with A2, B2, C2, alpha2.  bf16 products with K % 64 == 0 and 16-byte aligned
+ * strides run as one launch of the MFMA kernel, anything else as one launch per product.
+ * The relative-position attention backward forms dK, dV (Eq. 6 inside the attention block) this way. */
+int ouro_op_gemm_batched(void* stream, int dtype, int transA, int transB, int M, int N, int K, float alpha,
+                         const void* A, int lda, const void* B, int ldb, void* C, int ldc, int out_fp32,
+                         int accumulate, int by, int bz, long long sAy, long long sAz, long long sBy,
+                         long long sBz, long long sCy, long long sCz, const void* A2, const void* B2,
+                         void* C2, float alpha2, int force_generic);
 /* 1 if ouro_op_gemm would run the MFMA kernel for these arguments (host only). */
 int ouro_op_gemm_uses_mfma(int dtype, int transA, int transB, int M, int N, int K, const void* A,
                            int lda, const void* B, int ldb);

@@ -84,6 +84,9 @@ def lib():
         # single-kernel entry points
         "ouro_op_gemm": (i32, [vp, i32, i32, i32, i32, i32, i32, f32, vp, i32, vp, i32, vp, i32, i32, i32, vp, vp,
                                i32, i32, vp, i32, i32]),
+        "ouro_op_gemm_batched": (i32, [vp, i32, i32, i32, i32, i32, i32, f32, vp, i32, vp, i32, vp, i32, i32, i32, i32, i32,
+                                       C.c_longlong, C.c_longlong, C.c_longlong, C.c_longlong, C.c_longlong, C.c_longlong,
+                                       vp, vp, vp, f32, i32]),
         "ouro_op_gemm_uses_mfma": (i32, [i32, i32, i32, i32, i32, i32, vp, i32, vp, i32]),
         "ouro_op_attention_fwd": (i32, [vp, i32, i32, i32, i32, i32, i32, i32, f32, vp, i32, vp, i32, vp, i32, vp,
                                         i32, vp, i32, vp, vp, vp, i32, i32]),

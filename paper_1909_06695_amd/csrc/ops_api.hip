@@ -33,6 +33,20 @@ extern "C" int ouro_op_gemm(void* stream, int dtype, int transA, int transB, int
   return rc_of(launch_gemm((hipStream_t)stream, dtype, g, force_generic));
 }
 
+extern "C" int ouro_op_gemm_batched(void* stream, int dtype, int transA, int transB, int M, int N, int K, float alpha,
+                                    const void* A, int lda, const void* B, int ldb, void* C, int ldc, int out_fp32,
+                                    int accumulate, int by, int bz, long long sAy, long long sAz, long long sBy,
+                                    long long sBz, long long sCy, long long sCz, const void* A2, const void* B2,
+                                    void* C2, float alpha2, int force_generic) {
+  if (!A || !B || !C || M < 0 || N < 0 || K < 0 || by < 1 || bz < 1 || by > 65535 || bz > 32767) return OURO_E_ARG;
+  if (lda < (transA ? M : K) || ldb < (transB ? K : N) || ldc < N) return OURO_E_ARG;
+  if (C2 && (!A2 || !B2)) return OURO_E_ARG;
+  GemmDesc g = make_gemm(transA, transB, M, N, K, alpha, A, lda, B, ldb, C, ldc, out_fp32, accumulate, nullptr, nullptr, 0, EPI_NONE, nullptr, 0);
+  g.by = by; g.bz = bz; g.sAy = sAy; g.sAz = sAz; g.sBy = sBy; g.sBz = sBz; g.sCy = sCy; g.sCz = sCz;
+  g.A2 = A2; g.B2 = B2; g.C2 = C2; g.alpha2 = alpha2;
+  return rc_of(launch_gemm((hipStream_t)stream, dtype, g, force_generic));
+}
+
 extern "C" int ouro_op_gemm_dropout(void* stream, int dtype, int transA, int transB, int M, int N, int K,
                                     const void* A, int lda, const void* B, int ldb, void* C, int ldc, const float* bias,
                                     const void* residual, int ldr, float p, uint64_t seed, uint32_t stream_id, int drop_ld,

@@ -71,6 +71,40 @@ def test_gemm_forms(dtype, force, tA, tB, M, N, K):
         assert L().ouro_op_gemm_uses_mfma(dtype, tA, tB, M, N, K, p(dA), dA.shape[1], p(dB), dB.shape[1]) == 1
 
 
+@pytest.mark.parametrize("dtype,tA,tB,M,N,K,by,bz,second,acc", [
+    (1, 0, 0, 200, 64, 128, 3, 2, True, 0),      # one launch of the MFMA kernel over the grid, two grids, ragged M
+    (1, 0, 1, 136, 72, 192, 2, 1, False, 0),
+    (1, 1, 0, 128, 64, 2048, 3, 1, False, 1),    # split K with atomic adds inside a grid of products
+    (1, 0, 0, 20, 64, 64, 2, 2, True, 0),        # fewer rows than an MFMA tile: one launch per product
+    (1, 0, 0, 72, 40, 40, 2, 3, False, 0),       # K off the tile grid: one launch per product
+    (0, 0, 1, 33, 17, 29, 2, 2, True, 0)])       # fp32
+def test_gemm_batched(dtype, tA, tB, M, N, K, by, bz, second, acc):
+    """Grids of equal products (operands laid out back to back, batch y fastest), optionally two
+    grids in one call, against the fp64 product of the rounded operands."""
+    rng = np.random.default_rng(1000 * M + 10 * K + by + bz)
+    nb = by * bz
+    shA, shB = ((K, M) if tA else (M, K)), ((N, K) if tB else (K, N))
+    grids = 2 if second else 1
+    A = rng.standard_normal((grids, nb) + shA).astype(np.float32)
+    B = rng.standard_normal((grids, nb) + shB).astype(np.float32)
+    dA, dB = dev(A, dtype), dev(B, dtype)
+    init = rng.standard_normal((grids, nb, M, N)).astype(np.float32) if acc else np.zeros((grids, nb, M, N), np.float32)
+    out = torch.from_numpy(init.copy()).cuda()
+    nA, nB, nC = shA[0] * shA[1], shB[0] * shB[1], M * N
+    at = lambda t, g: C.c_void_p(t.data_ptr() + g * nb * (t.numel() // (grids * nb)) * t.element_size())
+    ok(L().ouro_op_gemm_batched(stream(), dtype, tA, tB, M, N, K, 0.5, at(dA, 0), shA[1], at(dB, 0), shB[1], at(out, 0), N,
+                                1, acc, by, bz, nA, by * nA, nB, by * nB, nC, by * nC,
+                                at(dA, 1) if second else None, at(dB, 1) if second else None, at(out, 1) if second else None, -2.0, 0))
+    torch.cuda.synchronize()
+    a64, b64, got = host(dA), host(dB), host(out)
+    for g in range(grids):
+        alpha = -2.0 if g else 0.5
+        for i in range(nb):
+            a, b = a64[g, i], b64[g, i]
+            ref = init[g, i] + alpha * ((a.T if tA else a) @ (b.T if tB else b))
+            assert rel_err(got[g, i], ref) < 2e-6, (g, i)
+
+
 @pytest.mark.parametrize("dtype,force", [(0, 0), (1, 0), (1, 10), (1, 11), (1, 12), (1, 13), (1, 14)])
 def test_gemm_epilogues_and_strides(dtype, force):
     rng = np.random.default_rng(5)
