@@ -19,8 +19,15 @@ namespace ouro {
 
 // ------------------------------------------------------------------------------ forward
 // grid (ceil(T/128), H, B); 4 waves x 32 queries; key blocks of 64.
-__global__ __launch_bounds__(256) void fa_fwd_kernel(FaParams p) {
-  __shared__ __attribute__((aligned(16))) char lds[NSTAGE * 2 * TILE_BYTES];
+// The forward kernel runs four waves per SIMD (four workgroups per CU): it fits 128 registers, and
+// a two-stage K/V ring (32 KB) leaves room for four workgroups in LDS.  The kernel is a chain of
+// matrix instructions, softmax arithmetic and matrix instructions again per key block, so what
+// it needs is other waves to run meanwhile, not a deeper ring: 46 -> 35 us at T = 1024, 8 x 16 heads.
+// The dQ kernel works through one 32-key sub-tile at a time so that it fits three waves per SIMD
+// (76 -> 69 us); the dK/dV kernel needs 190 registers without spilling and stays at two.
+constexpr int FWD_NSTAGE = 2;
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void fa_fwd_kernel(FaParams p) {
+  __shared__ __attribute__((aligned(16))) char lds[FWD_NSTAGE * 2 * TILE_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
   int rank, head, b;
   fa_decode_block(rank, head, b);
@@ -48,20 +55,20 @@ __global__ __launch_bounds__(256) void fa_fwd_kernel(FaParams p) {
     for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
   float m = -INFINITY, l = 0.f;
   auto issue = [&](int jb) __attribute__((always_inline)) {
-    char* st = lds + (jb % NSTAGE) * (2 * TILE_BYTES);
+    char* st = lds + (jb % FWD_NSTAGE) * (2 * TILE_BYTES);
     dma_tile(kb, p.ldk, jb * 64, p.S, st, wave, lane);
     dma_tile(vb, p.ldv, jb * 64, p.S, st + TILE_BYTES, wave, lane);
   };
   constexpr int LPT = 4;                                   // loads per thread per stage
 #pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s)
+  for (int s = 0; s < FWD_NSTAGE - 1; ++s)
     if (s < nkb) issue(s);
   for (int jb = 0; jb < nkb; ++jb) {
-    if (jb + NSTAGE - 1 <= nkb) fa_wait_vmcnt<(NSTAGE - 2) * LPT>();
+    if (jb + FWD_NSTAGE - 1 <= nkb) fa_wait_vmcnt<(FWD_NSTAGE - 2) * LPT>();
     else fa_wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();   // unfenced: younger tiles' loads stay in flight
-    if (jb + NSTAGE - 1 < nkb) issue(jb + NSTAGE - 1);
-    const char* sK = lds + (jb % NSTAGE) * (2 * TILE_BYTES);
+    if (jb + FWD_NSTAGE - 1 < nkb) issue(jb + FWD_NSTAGE - 1);
+    const char* sK = lds + (jb % FWD_NSTAGE) * (2 * TILE_BYTES);
     const char* sV = sK + TILE_BYTES;
     if (wave_on && jb * 64 <= wave_kmax) {
       // keys 32..63 of a diagonal block are masked for every query of some waves: skip them
@@ -213,24 +220,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       const int qt0 = (p.Mv + ib * 64 + 31 >= kb0) ? 0 : 1;
       // nothing is masked when the block's first query sees the wave's last key
       const bool edge = kb0 + 31 > p.Mv + ib * 64 || ib * 64 + 63 >= p.T || kb0 + 31 >= p.S;
-      f32x16 s[2], dp[2];
+      // one 32-query sub-tile at a time: scores and dP of a single sub-tile are live
 #pragma unroll
       for (int qt = 0; qt < 2; ++qt) {
         if (qt >= qt0) {
+          f32x16 s, dp;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) { s[qt][r] = 0.f; dp[qt][r] = 0.f; }
+          for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
           for (int ks = 0; ks < 4; ++ks) {
-            s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sQ, 32 * qt, ks, lane), kf[ks], s[qt], 0, 0, 0);
-            dp[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sdO, 32 * qt, ks, lane), vf[ks], dp[qt], 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sQ, 32 * qt, ks, lane), kf[ks], s, 0, 0, 0);
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sdO, 32 * qt, ks, lane), vf[ks], dp, 0, 0, 0);
           }
-        }
-      }
-      // P = exp2(s * scale * log2 e - lse2); dS = P (dP - D); the factor `scale` of dS is
-      // applied once, to the finished dK
-#pragma unroll
-      for (int qt = 0; qt < 2; ++qt)
-        if (qt >= qt0) {
+          // P = exp2(s * scale * log2 e - lse2); dS = P (dP - D); the factor `scale` of dS is
+          // applied once, to the finished dK
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
             const int ql0 = 32 * qt + 8 * g + 4 * h32;
@@ -240,27 +243,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
               const int r = 4 * g + j;
-              float pv = __builtin_amdgcn_exp2f(fmaf(s[qt][r], p.scale_log2, -lv[j]));
+              float pv = __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -lv[j]));
               if (edge) {
                 const int qi = ib * 64 + ql0 + j;
                 const bool vis = key <= p.Mv + qi && qi < p.T && key < p.S;
                 pv = vis ? pv : 0.f;
               }
-              s[qt][r] = pv;
-              dp[qt][r] = pv * (dp[qt][r] - dv4[j]);
+              s[r] = pv;
+              dp[r] = pv * (dp[r] - dv4[j]);
             }
           }
-        }
 #pragma unroll
-      for (int ks2 = 0; ks2 < 4; ++ks2) {
-        const int qt = ks2 >> 1, sub = ks2 & 1;
-        if (qt >= qt0) {
-          bf16x8 pb = pack_acc(s[qt], sub);
-          bf16x8 dsb = pack_acc(dp[qt], sub);
+          for (int sub = 0; sub < 2; ++sub) {
+            bf16x8 pb = pack_acc(s, sub);
+            bf16x8 dsb = pack_acc(dp, sub);
 #pragma unroll
-          for (int dt = 0; dt < 2; ++dt) {
-            dvT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sdO, 32 * dt, 32 * qt + 16 * sub, lane), pb, dvT[dt], 0, 0, 0);
-            dkT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sQ, 32 * dt, 32 * qt + 16 * sub, lane), dsb, dkT[dt], 0, 0, 0);
+            for (int dt = 0; dt < 2; ++dt) {
+              dvT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sdO, 32 * dt, 32 * qt + 16 * sub, lane), pb, dvT[dt], 0, 0, 0);
+              dkT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sQ, 32 * dt, 32 * qt + 16 * sub, lane), dsb, dkT[dt], 0, 0, 0);
+            }
           }
         }
       }
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // ---------------------------------------------------------------------------- dQ kernel
 // grid (ceil(T/128), H, B); 4 waves x 32 queries; key blocks of 64: S^T = K Q^T and
 // dP^T = V dO^T read K / V rows, dQ^T += K^T dS^T reads the K tile transposed.
-__global__ __launch_bounds__(256) void fa_bwd_dq_kernel(FaParams p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void fa_bwd_dq_kernel(FaParams p) {
   __shared__ __attribute__((aligned(16))) char lds[NSTAGE * 2 * TILE_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
   int rank, head, b;
@@ -347,42 +348,37 @@ __global__ __launch_bounds__(256) void fa_bwd_dq_kernel(FaParams p) {
     if (wave_on && jb * 64 <= wave_kmax) {
       const int nkt = (jb * 64 + 32 <= wave_kmax) ? 2 : 1;
       const bool edge = jb * 64 + 63 > p.Mv + q0 || jb * 64 + 63 >= p.S || q0 + 31 >= p.T;
-      f32x16 s[2], dp[2];
+      // one 32-key sub-tile at a time: scores and dP of a single sub-tile are live, which keeps
+      // the kernel at three waves per SIMD
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt) {
         if (kt < nkt) {
+          f32x16 s, dp;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) { s[kt][r] = 0.f; dp[kt][r] = 0.f; }
+          for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
           for (int ks = 0; ks < 4; ++ks) {
-            s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sK, 32 * kt, ks, lane), qf[ks], s[kt], 0, 0, 0);
-            dp[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sV, 32 * kt, ks, lane), dof[ks], dp[kt], 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sK, 32 * kt, ks, lane), qf[ks], s, 0, 0, 0);
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sV, 32 * kt, ks, lane), dof[ks], dp, 0, 0, 0);
           }
-        }
-      }
-      // dS without its factor `scale`, which the finished dQ takes once
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-        if (kt < nkt) {
+          // dS without its factor `scale`, which the finished dQ takes once
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            float pv = __builtin_amdgcn_exp2f(fmaf(s[kt][r], p.scale_log2, -lse_q));
+            float pv = __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -lse_q));
             if (edge) {
               const int key = jb * 64 + 32 * kt + 8 * (r >> 2) + 4 * h32 + (r & 3);
               const bool vis = key <= p.Mv + qi && key < p.S && qi < p.T;
               pv = vis ? pv : 0.f;
             }
-            dp[kt][r] = pv * (dp[kt][r] - D_q);
+            dp[r] = pv * (dp[r] - D_q);
           }
-        }
 #pragma unroll
-      for (int ks2 = 0; ks2 < 4; ++ks2) {
-        const int kt = ks2 >> 1, sub = ks2 & 1;
-        if (kt < nkt) {
-          bf16x8 dsb = pack_acc(dp[kt], sub);
+          for (int sub = 0; sub < 2; ++sub) {
+            bf16x8 dsb = pack_acc(dp, sub);
 #pragma unroll
-          for (int dt = 0; dt < 2; ++dt)
-            dqT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sK, 32 * dt, 32 * kt + 16 * sub, lane), dsb, dqT[dt], 0, 0, 0);
+            for (int dt = 0; dt < 2; ++dt)
+              dqT[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sK, 32 * dt, 32 * kt + 16 * sub, lane), dsb, dqT[dt], 0, 0, 0);
+          }
         }
       }
     }
