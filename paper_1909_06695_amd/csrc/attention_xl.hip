@@ -290,63 +290,49 @@ __global__ __launch_bounds__(256) void fa_xl_dq_kernel(FaParams p) {
     if (wave_on && jb * 64 <= wave_kmax) {
       const int nkt = (jb * 64 + 32 <= wave_kmax) ? 2 : 1;
       const bool edge = jb * 64 + 63 > p.Mv + q0 || jb * 64 + 63 >= p.S || q0 + 31 >= p.T;
-      f32x16 s[2], dp[2];
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-        if (kt < nkt) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) { s[kt][r] = 0.f; dp[kt][r] = 0.f; }
-#pragma unroll
-          for (int ks = 0; ks < 4; ++ks) {
-            s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sK, 32 * kt, ks, lane), quf[ks], s[kt], 0, 0, 0);
-            dp[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sV, 32 * kt, ks, lane), dof[ks], dp[kt], 0, 0, 0);
-          }
-        }
-      }
       xl_position_product(sR, qvf, patch, wave, lane);
-      // dS without its factor `scale`, which the finished gradients take once
+      // One 32-key sub-tile at a time (scores and dP of a single sub-tile are live).  A cell of the
+      // patch belongs to one (query lane, key): the lane reads its position term there and puts
+      // dS, without its factor `scale` (the finished gradients take it once), back in its place,
+      // which is dS at its distance row.
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
         if (kt < nkt) {
+          f32x16 s, dp;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) {
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sK, 32 * kt, ks, lane), quf[ks], s, 0, 0, 0);
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sV, 32 * kt, ks, lane), dof[ks], dp, 0, 0, 0);
+          }
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int kk = 32 * kt + acc_row(r, h32);
-            const float sc = s[kt][r] + patch[(63 + l32 - kk) * XL_PATCH_LD + l32];
+            float* cell = patch + (63 + l32 - kk) * XL_PATCH_LD + l32;
+            const float sc = s[r] + *cell;
             float pv = __builtin_amdgcn_exp2f(fmaf(sc, p.scale_log2, -lse_q));
             const int key = jb * 64 + kk;
             if (edge) {
               const bool vis = key <= p.Mv + qi && key < p.S && qi < p.T;
               pv = vis ? pv : 0.f;
             }
-            dp[kt][r] = pv * (dp[kt][r] - D_q);
+            dp[r] = pv * (dp[r] - D_q);
+            *cell = dp[r];
             if (key < p.S && qi < p.T) {
               ptq[(size_t)key * p.t_ld] = (bf16_t)pv;
-              dstq[(size_t)key * p.t_ld] = (bf16_t)dp[kt][r];
+              dstq[(size_t)key * p.t_ld] = (bf16_t)dp[r];
             }
           }
-        }
-      __builtin_amdgcn_wave_barrier();
-      // the same diagonal backwards: dS goes into the patch at its distance row
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-        if (kt < nkt) {
+          for (int sub = 0; sub < 2; ++sub) {
+            bf16x8 dsb = pack_acc(dp, sub);
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int kk = 32 * kt + acc_row(r, h32);
-            patch[(63 + l32 - kk) * XL_PATCH_LD + l32] = dp[kt][r];
+            for (int dt = 0; dt < 2; ++dt)
+              dqa[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sK, 32 * dt, 32 * kt + 16 * sub, lane), dsb, dqa[dt], 0, 0, 0);
           }
         }
       __builtin_amdgcn_wave_barrier();
-#pragma unroll
-      for (int ks2 = 0; ks2 < 4; ++ks2) {
-        const int kt = ks2 >> 1, sub = ks2 & 1;
-        if (kt < nkt) {
-          bf16x8 dsb = pack_acc(dp[kt], sub);
-#pragma unroll
-          for (int dt = 0; dt < 2; ++dt)
-            dqa[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sK, 32 * dt, 32 * kt + 16 * sub, lane), dsb, dqa[dt], 0, 0, 0);
-        }
-      }
       // rows of the patch that hold a gradient: 0 <= 63 + l32 - rho < 32 * nkt
 #pragma unroll
       for (int t = 0; t < 3; ++t) {
