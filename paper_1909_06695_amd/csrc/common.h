@@ -109,6 +109,8 @@ struct GemmDesc {
   // products are bound by memory latency; side by side they keep twice as many loads in flight.
   const void* A2; const void* B2; void* C2; float alpha2;
 };
+// Most products one grouped launch takes (launch_gemm_group).
+constexpr int GEMM_GROUP_MAX = 6;
 // MFMA tile configurations (bf16): register-staged 128x128 (any K multiple of 8), and four
 // direct-to-LDS kernels that need K % 64 == 0 and operands under 2 GiB.
 enum { GEMM_TILE_STAGED128 = 10, GEMM_TILE_128x128 = 11, GEMM_TILE_128x64 = 12, GEMM_TILE_PIPE128 = 13, GEMM_TILE_256x256 = 14 };
@@ -116,6 +118,10 @@ enum { GEMM_TILE_STAGED128 = 10, GEMM_TILE_128x128 = 11, GEMM_TILE_128x64 = 12, 
 // plain tiled kernel, GEMM_TILE_* = that MFMA configuration where the problem admits MFMA
 // (a direct-to-LDS configuration falls back to the staged one when its conditions fail).
 hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_generic);
+// n <= GEMM_GROUP_MAX accumulating products (fp32 C += alpha A^T B, plain epilogue, no batch) in one
+// launch when all of them are bf16 with transA = 1, transB = 0 and admit the direct-to-LDS MFMA
+// kernel; otherwise one launch_gemm each.  *grouped (optional) tells which it was.
+hipError_t launch_gemm_group(hipStream_t s, int dtype, const GemmDesc* g, int n, bool* grouped = nullptr);
 // true if launch_gemm would take the MFMA path for this problem
 bool gemm_uses_mfma(int dtype, const GemmDesc& g);
 

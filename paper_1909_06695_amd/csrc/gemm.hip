@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <cstring>
 
 namespace ouro {
 
@@ -152,6 +153,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmParams p) {
 
 // ----------------------------------------------------------------------------- launch
 hipError_t launch_gemm_dlds(hipStream_t s, GemmParams& p, int transA, int transB, int splits, int cfg);
+hipError_t launch_gemm_dlds_group(hipStream_t s, GemmParams* ps, int n, int transA, int transB);
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 bool gemm_uses_mfma(int dtype, const GemmDesc& g) {
@@ -314,6 +316,56 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
   if (dtype == 1) OURO_PLAIN(bf16_t); else OURO_PLAIN(float);
 #undef OURO_PLAIN
   return hipGetLastError();
+}
+
+hipError_t launch_gemm_group(hipStream_t s, int dtype, const GemmDesc* g, int n, bool* grouped) {
+  if (grouped) *grouped = false;
+  if (n < 1 || n > GEMM_GROUP_MAX) return hipErrorInvalidValue;
+  // products that do not admit the grouped kernel go by themselves
+  GemmDesc in[GEMM_GROUP_MAX];
+  int ni = 0;
+  for (int i = 0; i < n; ++i) {
+    const GemmDesc& d = g[i];
+    const size_t bA = 2 * (size_t)d.K * d.lda, bB = 2 * (size_t)d.K * d.ldb;
+    const bool ok = dtype == 1 && d.transA == 1 && d.transB == 0 && d.accumulate && d.out_fp32 && !d.bias && !d.residual &&
+                    !d.res32 && d.epilogue == EPI_NONE && !d.drop.on && d.by <= 1 && d.bz <= 1 && !d.C2 && d.M > 0 && d.N > 0 &&
+                    gemm_uses_mfma(dtype, d) && (d.K % 64) == 0 && d.K >= 512 && bA < (1ull << 31) && bB < (1ull << 31);
+    if (ok) { in[ni++] = d; continue; }
+    hipError_t e = launch_gemm(s, dtype, d, 0);
+    if (e != hipSuccess) return e;
+  }
+  if (ni == 0) return hipSuccess;
+  if (ni == 1) return launch_gemm(s, dtype, in[0], 0);
+  g = in; n = ni;
+  // One K-range length for all products: whole rounds of workgroups (two per CU) times the K-tiles
+  // of a workgroup plus its fixed cost (ring fill, atomic epilogue: 6 K-tiles), as in launch_gemm.
+  int kmax = 0;
+  for (int i = 0; i < n; ++i) kmax = std::max(kmax, g[i].K);
+  double best = 1e30;
+  int kchunk = kmax;
+  for (int kc = 256; kc <= kmax; kc += 64) {
+    long wgs = 0;
+    for (int i = 0; i < n; ++i)
+      wgs += (long)((g[i].M + 127) / 128) * ((g[i].N + 127) / 128) * ((g[i].K + kc - 1) / kc);
+    const long rounds = (wgs + 511) / 512;
+    const double cost = (double)rounds * (kc / 64 + 6);
+    if (cost < best - 1e-9) { best = cost; kchunk = kc; }
+  }
+  GemmParams ps[GEMM_GROUP_MAX];
+  for (int i = 0; i < n; ++i) {
+    const GemmDesc& d = g[i];
+    GemmParams& p = ps[i];
+    memset(&p, 0, sizeof p);
+    p.A = d.A; p.B = d.B; p.C = d.C;
+    p.M = d.M; p.N = d.N; p.K = d.K; p.lda = d.lda; p.ldb = d.ldb; p.ldc = d.ldc;
+    p.out_fp32 = 1; p.accumulate = 1; p.epilogue = EPI_NONE; p.alpha = d.alpha;
+    p.by = p.bz = p.bz1 = 1;
+    // every product splits into ranges of the same length, rounded so that the last is not a sliver
+    const int splits = (d.K + kchunk - 1) / kchunk;
+    p.kchunk = ((d.K + splits - 1) / splits + 63) / 64 * 64;
+  }
+  if (grouped) *grouped = true;
+  return launch_gemm_dlds_group(s, ps, n, 1, 0);
 }
 
 }  // namespace ouro

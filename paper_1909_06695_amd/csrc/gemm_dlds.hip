@@ -98,10 +98,9 @@ __device__ __forceinline__ bf16x8 frag_col(const char* tile, int t0, int ks, int
 //    and walks it in groups of 8 tile columns (tilesN a multiple of 8), rows fastest: the 32 to 64 tiles in flight
 //    cover (band x 8 columns), so both operands' tiles are re-used from L2 instead of one
 //    operand being re-streamed for every tile row.
-__device__ __forceinline__ void tile_of_block(const GemmParams& p, int BM, int BN, int& m0, int& n0, int& kbeg) {
-  int bid = blockIdx.x;
+__device__ __forceinline__ void tile_of_block(const GemmParams& p, int BM, int BN, int bid, int nb, int& m0, int& n0, int& kbeg) {
   {
-    int nb = gridDim.x, q = nb >> 3, r = nb & 7, x = bid & 7, idx = bid >> 3;
+    int q = nb >> 3, r = nb & 7, x = bid & 7, idx = bid >> 3;
     if (p.band) {
       const int mb = p.tilesM >> 3, per = mb * 8;            // tile rows per XCD, tiles per full group
       const int g = idx / per, w = idx - g * per;
@@ -128,8 +127,9 @@ __device__ __forceinline__ void batch_offsets(GemmParams& p) {
   p.C = reinterpret_cast<char*>(p.C) + blockIdx.y * p.bCy + z * p.bCz;
 }
 
+// One workgroup's share of a product: work item `bid` of `nb` (see tile_of_block).
 template <int BM, int BN, int WM, int WN, bool TA, bool TB, int S>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_dlds_kernel(GemmParams p) {
+__device__ __forceinline__ void gemm_dlds_body(const GemmParams& p, int bid, int nb, uint4* smem) {
   constexpr int BK = 64;
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -138,15 +138,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dlds_kernel(GemmParams p) {
   constexpr int STAGE = TileA::BYTES + TileB::BYTES;
   constexpr int LPT = TileA::PER + TileB::PER;             // loads per thread per K-tile
   static_assert((S - 1) * LPT < 64, "too many loads in flight for vmcnt");
-  extern __shared__ uint4 smem[];
   char* lds = reinterpret_cast<char*>(smem);
-  batch_offsets(p);
   const bf16_t* A = reinterpret_cast<const bf16_t*>(p.A);
   const bf16_t* B = reinterpret_cast<const bf16_t*>(p.B);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
   int m0, n0, kbeg;
-  tile_of_block(p, BM, BN, m0, n0, kbeg);
+  tile_of_block(p, BM, BN, bid, nb, m0, n0, kbeg);
+  if (kbeg >= p.K) return;                                  // a work item past the last K range (grouped launches round up)
   const int kend = min(p.K, kbeg + p.kchunk);
   const int nk = (kend - kbeg) / BK;                        // launcher guarantees exact tiles
 
@@ -244,6 +243,32 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dlds_kernel(GemmParams p) {
   mfma_epilogue<TM, TN>(p, acc, smem, m0 + wm * (TM * 32), n0 + wn * (TN * 32), lane, wave);
 }
 
+template <int BM, int BN, int WM, int WN, bool TA, bool TB, int S>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_dlds_kernel(GemmParams p) {
+  extern __shared__ uint4 smem[];
+  batch_offsets(p);
+  gemm_dlds_body<BM, BN, WM, WN, TA, TB, S>(p, blockIdx.x, gridDim.x, smem);
+}
+
+// Several products in one launch (weight gradients of a layer: small outputs, long contractions).
+// Product i owns the work items [first[i], first[i+1]), a multiple of 8 each so that the low bits
+// of a work item still name its XCD.  With all of them in flight together every workgroup can take a
+// long K range and the grid still fills the chip in whole rounds, which no product does alone.
+struct GemmGroupParams {
+  int n;
+  int first[GEMM_GROUP_MAX + 1];
+  GemmParams p[GEMM_GROUP_MAX];
+};
+static_assert(sizeof(GemmGroupParams) <= 4096, "kernel arguments are limited to 4 KiB");
+template <int BM, int BN, int WM, int WN, bool TA, bool TB, int S>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_dlds_group_kernel(GemmGroupParams g) {
+  extern __shared__ uint4 smem[];
+  const int bid = blockIdx.x;
+  int i = 0;
+  while (i + 1 < g.n && bid >= g.first[i + 1]) ++i;
+  gemm_dlds_body<BM, BN, WM, WN, TA, TB, S>(g.p[i], bid - g.first[i], g.first[i + 1] - g.first[i], smem);
+}
+
 // Same ring, deeper software pipeline: the fragments of a whole K-tile live in registers and
 // are refilled for K-tile kt+1 right behind the matrix instructions of K-tile kt that last
 // used them, so an LDS read has a full K-tile of matrix work to hide behind.  Stage kt+1 is
@@ -265,7 +290,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_pipe_kernel(GemmParams p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
   int m0, n0, kbeg;
-  tile_of_block(p, BM, BN, m0, n0, kbeg);
+  tile_of_block(p, BM, BN, blockIdx.x, gridDim.x, m0, n0, kbeg);
   const int kend = min(p.K, kbeg + p.kchunk);
   const int nk = (kend - kbeg) / BK;
 
@@ -394,6 +419,47 @@ hipError_t launch_dlds_cfg(hipStream_t s, GemmParams& p, int transA, int transB,
 template <int BM, int BN, int WM, int WN, int S>
 hipError_t launch_pipe_cfg(hipStream_t s, GemmParams& p, int transA, int transB, int splits) {
   return launch_dlds_cfg_impl<BM, BN, WM, WN, S, true>(s, p, transA, transB, splits);
+}
+
+// Products ps[0..n) (kchunk set, accumulate form) in one launch of the 128x128 kernel.
+hipError_t launch_gemm_dlds_group(hipStream_t s, GemmParams* ps, int n, int transA, int transB) {
+  constexpr int BM = 128, BN = 128, WM = 2, WN = 4, S = 2;
+  constexpr size_t smem_main = (size_t)S * (BM + BN) * 128;
+  constexpr size_t smem_epi = (size_t)WM * WN * epilogue_stage_floats<BN / WN / 32>() * sizeof(float);
+  constexpr size_t smem = smem_main > smem_epi ? smem_main : smem_epi;
+  if (n < 1 || n > GEMM_GROUP_MAX) return hipErrorInvalidValue;
+  GemmGroupParams g;
+  g.n = n;
+  g.first[0] = 0;
+  for (int i = 0; i < n; ++i) {
+    GemmParams& p = ps[i];
+    p.tilesM = (p.M + BM - 1) / BM;
+    p.tilesN = (p.N + BN - 1) / BN;
+    p.ntiles = p.tilesM * p.tilesN;
+    const int splits = (p.K + p.kchunk - 1) / p.kchunk;
+    p.mfast = splits > 1 && p.N > p.M;
+    p.band = 0;
+    g.p[i] = p;
+    g.first[i + 1] = g.first[i] + (p.ntiles * splits + 7) / 8 * 8;
+  }
+  for (int i = n; i < GEMM_GROUP_MAX; ++i) { g.p[i] = ps[0]; g.first[i + 1] = g.first[n]; }
+  dim3 grid(g.first[n]), block(WM * WN * 64);
+#define OURO_LAUNCH(TA_, TB_)                                                                    \
+  do {                                                                                           \
+    static bool attr_done = false;                                                               \
+    auto kern = gemm_dlds_group_kernel<BM, BN, WM, WN, TA_, TB_, S>;                             \
+    if (!attr_done) {                                                                            \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                    \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
+      if (e != hipSuccess) return e;                                                             \
+      attr_done = true;                                                                          \
+    }                                                                                            \
+    hipLaunchKernelGGL(kern, grid, block, smem, s, g);                                           \
+  } while (0)
+  if (transA && !transB) OURO_LAUNCH(true, false);
+  else return hipErrorInvalidValue;
+#undef OURO_LAUNCH
+  return hipGetLastError();
 }
 
 hipError_t launch_gemm_dlds(hipStream_t s, GemmParams& p, int transA, int transB, int splits, int cfg) {

@@ -780,6 +780,17 @@ static int run_gemm_on(ouro_model* m, GemmDesc g, hipStream_t st) {
   return OURO_OK;
 }
 static int run_gemm(ouro_model* m, GemmDesc g) { return run_gemm_on(m, g, m->stream); }
+// The weight-gradient contractions of a layer in one launch where they admit it (launch_gemm_group).
+static int run_gemm_group_on(ouro_model* m, const GemmDesc* g, int n, hipStream_t st) {
+  if (n == 0) return OURO_OK;
+  bool timed = m->timing;
+  double flops = 0;
+  for (int i = 0; i < n; ++i) { timed = timed && gemm_uses_mfma(m->cfg.dtype, g[i]); flops += 2.0 * g[i].M * g[i].N * g[i].K; }
+  if (timed) { int rc = timing_begin(m, OURO_TIMING_CONTRACTION, st); if (rc) return rc; }
+  HIPCHK(launch_gemm_group(st, m->cfg.dtype, g, n));
+  if (timed) return timing_end(m, OURO_TIMING_CONTRACTION, flops, st);
+  return OURO_OK;
+}
 
 static GemmDesc gd(const void* A, int lda, int tA, const void* B, int ldb, int tB, void* C, int ldc, int M, int N, int K) {
   GemmDesc g;
@@ -982,6 +993,11 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   };
   // the gradients of this layer's vectors gather in the per-XCD copies; module_backward adds them to gslot
   float* vc = m->vec_copies + m->vec_off[l];
+  // The layer's weight-gradient contractions (small outputs, contraction over all tokens) are
+  // collected and go out together once the last operand exists: each alone cannot give its
+  // workgroups a long K range and fill the chip in whole rounds.
+  GemmDesc wg[GEMM_GROUP_MAX];
+  int nwg = 0;
   // LN2
   // the scale / shift gradients come from the same kernel (one pass over dh and s2)
   // dh, dy (gradients of the normalised rows) and the saved sums s1, s2 are fp32 in every mode
@@ -996,7 +1012,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   {
     GemmDesc g = gd(b.uact, F, 1, ds2m, d, 0, gslot + o.W_2, d, F, d, N);
     g.out_fp32 = 1; g.accumulate = 1;
-    RUN(run_gemm_on(m, g, sw));
+    wg[nwg++] = g;
   }
   HIPCHK(launch_colsum(sw, c.dtype, ds2m, d, vc + 2 * d, N, d, m->vec_stride));
   {
@@ -1009,7 +1025,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   {
     GemmDesc g = gd(b.y, d, 1, dz, F, 0, gslot + o.W_1, F, d, F, N);
     g.out_fp32 = 1; g.accumulate = 1;
-    RUN(run_gemm_on(m, g, sw));
+    wg[nwg++] = g;
   }
   HIPCHK(launch_colsum(sw, c.dtype, dz, F, vc + 5 * d, N, F, m->vec_stride));
   {
@@ -1027,7 +1043,7 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
   {
     GemmDesc g = gd(b.a, hd, 1, ds1m, d, 0, gslot + o.W_o, d, hd, d, N);
     g.out_fp32 = 1; g.accumulate = 1;
-    RUN(run_gemm_on(m, g, sw));
+    wg[nwg++] = g;
   }
   RUN(run_gemm(m, gd(ds1m, d, 0, m->wT(l, o.W_o), d, 1, m->da, hd, N, hd, d)));
   // attention
@@ -1048,8 +1064,9 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     {
       GemmDesc g = gd(b.x, d, 1, dqkv, 3 * hd, 0, gslot + o.W_qkv, 3 * hd, d, 3 * hd, N);
       g.out_fp32 = 1; g.accumulate = 1;
-      RUN(run_gemm_on(m, g, sw));
+      wg[nwg++] = g;
     }
+    RUN(run_gemm_group_on(m, wg, nwg, sw));
     {
       GemmDesc g = gd(dqkv, 3 * hd, 0, m->wT(l, o.W_qkv), 3 * hd, 1, dx, d, N, d, 3 * hd);
       g.residual = ds1; g.ldr = d; g.out_fp32 = 1;
@@ -1082,18 +1099,19 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
     {
       GemmDesc g = gd(m->rtab, d, 1, drp, hd, 0, gslot + o.W_r, hd, d, hd, S);
       g.out_fp32 = 1; g.accumulate = 1;
-      RUN(run_gemm_on(m, g, sw));
+      wg[nwg++] = g;
     }
     {
       GemmDesc g = gd(b.x, d, 1, dq, hd, 0, gslot + o.W_qkv, 3 * hd, d, hd, N);
       g.out_fp32 = 1; g.accumulate = 1;
-      RUN(run_gemm_on(m, g, sw));
+      wg[nwg++] = g;
     }
     {
       GemmDesc g = gd(cat, d, 1, dkv, 2 * hd, 0, gslot + o.W_qkv + hd, 3 * hd, d, 2 * hd, B * S);
       g.out_fp32 = 1; g.accumulate = 1;
-      RUN(run_gemm_on(m, g, sw));
+      wg[nwg++] = g;
     }
+    RUN(run_gemm_group_on(m, wg, nwg, sw));
     {
       GemmDesc g = gd(dq, hd, 0, m->wT(l, o.W_qkv), 3 * hd, 1, dx, d, N, d, hd);
       g.residual = ds1; g.ldr = d; g.out_fp32 = 1;
