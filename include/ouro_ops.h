@@ -39,6 +39,13 @@ int ouro_op_gemm_batched(void* stream, int dtype, int transA, int transB, int M,
                          int accumulate, int by, int bz, long long sAy, long long sAz, long long sBy,
                          long long sBz, long long sCy, long long sCz, const void* A2, const void* B2,
                          void* C2, float alpha2, int force_generic);
+/* n <= 6 accumulating products C_i (fp32 [M_i, N_i]) += alpha * A_i^T B_i with A_i [K_i, M_i] and
+ * B_i [K_i, N_i] (the weight-gradient contractions of a layer, Eq. 6-7: contraction over all
+ * tokens onto small outputs).  Products that admit it (bf16, K_i a multiple of 64 and >= 512) share
+ * one launch in which every workgroup takes a long K range; the rest run one by one. */
+int ouro_op_gemm_group(void* stream, int dtype, int n, const int* M, const int* N, const int* K,
+                       const void* const* A, const int* lda, const void* const* B, const int* ldb,
+                       float* const* C, const int* ldc, float alpha);
 /* 1 if ouro_op_gemm would run the MFMA kernel for these arguments (host only). */
 int ouro_op_gemm_uses_mfma(int dtype, int transA, int transB, int M, int N, int K, const void* A,
                            int lda, const void* B, int ldb);

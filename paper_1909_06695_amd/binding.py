@@ -87,6 +87,7 @@ def lib():
         "ouro_op_gemm_batched": (i32, [vp, i32, i32, i32, i32, i32, i32, f32, vp, i32, vp, i32, vp, i32, i32, i32, i32, i32,
                                        C.c_longlong, C.c_longlong, C.c_longlong, C.c_longlong, C.c_longlong, C.c_longlong,
                                        vp, vp, vp, f32, i32]),
+        "ouro_op_gemm_group": (i32, [vp, i32, i32, P(i32), P(i32), P(i32), P(vp), P(i32), P(vp), P(i32), P(vp), P(i32), f32]),
         "ouro_op_gemm_uses_mfma": (i32, [i32, i32, i32, i32, i32, i32, vp, i32, vp, i32]),
         "ouro_op_attention_fwd": (i32, [vp, i32, i32, i32, i32, i32, i32, i32, f32, vp, i32, vp, i32, vp, i32, vp,
                                         i32, vp, i32, vp, vp, vp, i32, i32]),

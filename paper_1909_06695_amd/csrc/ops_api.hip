@@ -47,6 +47,18 @@ extern "C" int ouro_op_gemm_batched(void* stream, int dtype, int transA, int tra
   return rc_of(launch_gemm((hipStream_t)stream, dtype, g, force_generic));
 }
 
+extern "C" int ouro_op_gemm_group(void* stream, int dtype, int n, const int* M, const int* N, const int* K,
+                                  const void* const* A, const int* lda, const void* const* B, const int* ldb,
+                                  float* const* C, const int* ldc, float alpha) {
+  if (n < 1 || n > GEMM_GROUP_MAX || !M || !N || !K || !A || !lda || !B || !ldb || !C || !ldc) return OURO_E_ARG;
+  GemmDesc g[GEMM_GROUP_MAX];
+  for (int i = 0; i < n; ++i) {
+    if (!A[i] || !B[i] || !C[i] || M[i] < 0 || N[i] < 0 || K[i] < 0 || lda[i] < M[i] || ldb[i] < N[i] || ldc[i] < N[i]) return OURO_E_ARG;
+    g[i] = make_gemm(1, 0, M[i], N[i], K[i], alpha, A[i], lda[i], B[i], ldb[i], C[i], ldc[i], 1, 1, nullptr, nullptr, 0, EPI_NONE, nullptr, 0);
+  }
+  return rc_of(launch_gemm_group((hipStream_t)stream, dtype, g, n));
+}
+
 extern "C" int ouro_op_gemm_dropout(void* stream, int dtype, int transA, int transB, int M, int N, int K,
                                     const void* A, int lda, const void* B, int ldb, void* C, int ldc, const float* bias,
                                     const void* residual, int ldr, float p, uint64_t seed, uint32_t stream_id, int drop_ld,

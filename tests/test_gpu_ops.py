@@ -105,6 +105,29 @@ def test_gemm_batched(dtype, tA, tB, M, N, K, by, bz, second, acc):
             assert rel_err(got[g, i], ref) < 2e-6, (g, i)
 
 
+@pytest.mark.parametrize("dtype,shapes", [
+    (1, [(256, 128, 2048), (128, 384, 2048), (136, 72, 1024), (128, 128, 512)]),     # all in one launch, ragged tiles
+    (1, [(256, 128, 1024), (72, 40, 1000), (128, 256, 4096), (64, 64, 320)]),        # two of them go by themselves
+    (1, [(128, 128, 1024)]),
+    (0, [(33, 17, 29), (40, 24, 64)])])                                              # fp32: one by one
+def test_gemm_group(dtype, shapes):
+    """Several accumulating products C_i += alpha A_i^T B_i in one call against fp64."""
+    rng = np.random.default_rng(sum(m + n + k for m, n, k in shapes))
+    n = len(shapes)
+    dA = [dev(rng.standard_normal((k, m)).astype(np.float32), dtype) for m, nn, k in shapes]
+    dB = [dev(rng.standard_normal((k, nn)).astype(np.float32), dtype) for m, nn, k in shapes]
+    init = [rng.standard_normal((m, nn)).astype(np.float32) for m, nn, k in shapes]
+    out = [torch.from_numpy(x.copy()).cuda() for x in init]
+    ia = lambda v: (C.c_int * n)(*v)
+    pa = lambda ts: (C.c_void_p * n)(*[t.data_ptr() for t in ts])
+    ok(L().ouro_op_gemm_group(stream(), dtype, n, ia([s[0] for s in shapes]), ia([s[1] for s in shapes]), ia([s[2] for s in shapes]),
+                              pa(dA), ia([s[0] for s in shapes]), pa(dB), ia([s[1] for s in shapes]), pa(out), ia([s[1] for s in shapes]), 0.25))
+    torch.cuda.synchronize()
+    for i in range(n):
+        ref = init[i] + 0.25 * (host(dA[i]).T @ host(dB[i]))
+        assert rel_err(host(out[i]), ref) < 2e-6, i
+
+
 @pytest.mark.parametrize("dtype,force", [(0, 0), (1, 0), (1, 10), (1, 11), (1, 12), (1, 13), (1, 14)])
 def test_gemm_epilogues_and_strides(dtype, force):
     rng = np.random.default_rng(5)
