@@ -24,20 +24,18 @@ namespace ouro {
 constexpr int XL_RWIN = 192;                         // rows of r a workgroup needs per block
 constexpr int XL_STAGE = 2 * TILE_BYTES + XL_RWIN * 128;   // K, V, r window
 constexpr int XL_NSTAGE = 2;
-constexpr int XL_PATCH_LD = 33;                      // floats per patch row (32 queries + pad)
-constexpr int XL_PATCH = 96 * XL_PATCH_LD * 4;       // bytes per wave
-constexpr int XL_LDS_Q = XL_NSTAGE * XL_STAGE + 4 * XL_PATCH;
+constexpr int XL8_LD = 34;                           // floats per patch row (33: 218 us in the dQ kernel, 32: 227, 34: 214)
+constexpr int XL8_PATCH = 64 * XL8_LD * 4;           // bytes per wave
+constexpr int XL_LDS_Q8 = XL_NSTAGE * XL_STAGE + 8 * XL8_PATCH;
 
-// Direct load of 64 rows (row index clamped to [0, rmax-1]) x 64 features into an LDS tile.
-__device__ __forceinline__ void dma_tile_clamped(const bf16_t* src, int ld, int row0, int rmax, char* tile, int wave, int lane) {
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int j = wave * 2 + i;
-    const int row = 8 * j + (lane >> 3);
-    const int c = (lane & 7) ^ swza(row);
-    const int gr = max(0, min(row0 + row, rmax - 1));
-    __builtin_amdgcn_global_load_lds((gbl_void*)(src + (size_t)gr * ld + 8 * c), (lds_void*)(tile + j * 1024), 16, 0, 0);
-  }
+// One wave's share (8 rows) of a direct load of 64 rows x 64 features into an LDS tile; the row
+// index is clamped to [0 or -inf, rmax-1].
+__device__ __forceinline__ void dma_tile8(const bf16_t* src, int ld, int row0, int rmax, char* tile, int wave, int lane, bool clamp_low) {
+  const int row = 8 * wave + (lane >> 3);
+  const int c = (lane & 7) ^ swza(row);
+  int gr = min(row0 + row, rmax - 1);
+  if (clamp_low) gr = max(0, gr);
+  __builtin_amdgcn_global_load_lds((gbl_void*)(src + (size_t)gr * ld + 8 * c), (lds_void*)(tile + wave * 1024), 16, 0, 0);
 }
 
 // q + bias for the lane's fragment features (fp32 add, rounded to bf16 once)
@@ -51,37 +49,47 @@ __device__ __forceinline__ bf16x8 add_bias(bf16x8 q, const bf16_t* bias8) {
 // row of the accumulator element r of the lane's half: 8*(r/4) + 4*half + r%4
 __device__ __forceinline__ constexpr int acc_row(int r, int h32) { return 8 * (r >> 2) + 4 * h32 + (r & 3); }
 
-// Position term of a block for a wave whose lanes own queries: acc2 = rows [32*wave, +96) of
-// the r window times (q + v), written to the wave's patch as patch[rho][query].
-__device__ __forceinline__ void xl_position_product(const char* sR, const bf16x8 (&qvf)[4], float* patch, int wave, int lane) {
+// Position term of a 32-key sub-tile for a wave whose lanes own queries: rows [rrow0, +64) of
+// the r window times (q + v), written to the wave's patch as patch[rho][query].  Key kk of the
+// sub-tile and the lane's query meet at patch row 31 + lane%32 - kk.
+__device__ __forceinline__ void xl_position_product(const char* sR, int rrow0, const bf16x8 (&qvf)[4], float* patch, int lane) {
   const int h32 = lane >> 5, l32 = lane & 31;
 #pragma unroll
-  for (int t = 0; t < 3; ++t) {
+  for (int t = 0; t < 2; ++t) {
     f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sR, 32 * wave + 32 * t, ks, lane), qvf[ks], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sR, rrow0 + 32 * t, ks, lane), qvf[ks], acc, 0, 0, 0);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) patch[(32 * t + acc_row(r, h32)) * XL_PATCH_LD + l32] = acc[r];
+    for (int r = 0; r < 16; ++r) patch[(32 * t + acc_row(r, h32)) * XL8_LD + l32] = acc[r];
   }
-  __builtin_amdgcn_wave_barrier();
 }
 
+// Both kernels below: grid (ceil(T/128), H, B); 8 waves = (4 groups of 32 queries) x (the two
+// 32-key halves of a 64-key block), waves w and w + 4 (one query group) on one SIMD; one
+// workgroup per CU, so two waves per SIMD (with four waves owning whole 64-key blocks, one per
+// SIMD, the forward pass took 93 us and the dQ kernel 266 us per layer at 16 x 16 heads,
+// T = M = 384; in this form 89 and 214).  A wave's patch holds the 63 distances of its 32 x 32
+// sub-tile (64 rows).  Stages hold K, V and the r window of the 128 queries; every wave issues
+// one 1 KiB load per tile.
+
 // ------------------------------------------------------------------------------ forward
-// grid (ceil(T/128), H, B); 4 waves x 32 queries; key blocks of 64; one workgroup per CU.
-__global__ __launch_bounds__(256) void fa_xl_fwd_kernel(FaParams p) {
+// The two key halves of a query group keep their own running maximum, sum and output; the
+// second half hands its state to the first through LDS at the end.
+__global__ __launch_bounds__(512) void fa_xl_fwd_kernel(FaParams p) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
+  const int qg = wave & 3, kh = wave >> 2;
   const int qblk = gridDim.x - 1 - blockIdx.x;            // longest rows first
   const int head = blockIdx.y, b = blockIdx.z;
-  const int Q0 = qblk * 128, q0 = Q0 + wave * 32, qi = q0 + l32;
+  const int Q0 = qblk * 128, q0 = Q0 + qg * 32, qi = q0 + l32;
   const bf16_t* qb = p.q + (size_t)b * p.T * p.ldq + head * 64;
   const bf16_t* kb = p.k + (size_t)b * p.S * p.ldk + head * 64;
   const bf16_t* vb = p.v + (size_t)b * p.S * p.ldv + head * 64;
   const bf16_t* rb = p.r + head * 64;
-  float* patch = reinterpret_cast<float*>(lds + XL_NSTAGE * XL_STAGE + wave * XL_PATCH);
+  float* patch = reinterpret_cast<float*>(lds + XL_NSTAGE * XL_STAGE + wave * XL8_PATCH);
   bf16x8 quf[4], qvf[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
@@ -95,6 +103,7 @@ __global__ __launch_bounds__(256) void fa_xl_fwd_kernel(FaParams p) {
   const int nkb = (kend + 63) / 64;
   const bool wave_on = q0 < p.T;
   const int wave_kmax = p.Mv + min(p.T - 1, q0 + 31);
+  const int rrow0 = 32 * qg + 32 * (1 - kh);                // window row of the wave's patch row 0
   f32x16 oacc[2];
 #pragma unroll
   for (int dt = 0; dt < 2; ++dt)
@@ -103,11 +112,11 @@ __global__ __launch_bounds__(256) void fa_xl_fwd_kernel(FaParams p) {
   float m = -INFINITY, l = 0.f;
   auto issue = [&](int jb) __attribute__((always_inline)) {
     char* st = lds + (jb % XL_NSTAGE) * XL_STAGE;
-    dma_tile(kb, p.ldk, jb * 64, p.S, st, wave, lane);
-    dma_tile(vb, p.ldv, jb * 64, p.S, st + TILE_BYTES, wave, lane);
+    dma_tile8(kb, p.ldk, jb * 64, p.S, st, wave, lane, false);
+    dma_tile8(vb, p.ldv, jb * 64, p.S, st + TILE_BYTES, wave, lane, false);
     const int d0 = p.Mv + Q0 - jb * 64 - 63;              // distance of window row 0
 #pragma unroll
-    for (int t = 0; t < 3; ++t) dma_tile_clamped(rb, p.ldr, d0 + 64 * t, p.S, st + 2 * TILE_BYTES + t * TILE_BYTES, wave, lane);
+    for (int t = 0; t < 3; ++t) dma_tile8(rb, p.ldr, d0 + 64 * t, p.S, st + 2 * TILE_BYTES + t * TILE_BYTES, wave, lane, true);
   };
   issue(0);
   for (int jb = 0; jb < nkb; ++jb) {
@@ -117,52 +126,32 @@ __global__ __launch_bounds__(256) void fa_xl_fwd_kernel(FaParams p) {
     const char* sK = lds + (jb % XL_NSTAGE) * XL_STAGE;
     const char* sV = sK + TILE_BYTES;
     const char* sR = sK + 2 * TILE_BYTES;
-    if (wave_on && jb * 64 <= wave_kmax) {
-      const int nkt = (jb * 64 + 32 <= wave_kmax) ? 2 : 1;
-      const bool edge = jb * 64 + 63 > p.Mv + q0 || jb * 64 + 63 >= p.S || q0 + 31 >= p.T;
-      f32x16 s[2];
+    const int key0 = jb * 64 + 32 * kh;                     // first key of the wave's sub-tile
+    if (wave_on && key0 <= wave_kmax) {
+      const bool edge = key0 + 31 > p.Mv + q0 || key0 + 31 >= p.S || q0 + 31 >= p.T;
+      xl_position_product(sR, rrow0, qvf, patch, lane);
+      f32x16 s;
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-        if (kt < nkt) {
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+      for (int ks = 0; ks < 4; ++ks)
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sK, 32 * kh, ks, lane), quf[ks], s, 0, 0, 0);
+      __builtin_amdgcn_wave_barrier();
+      const float* cell0 = patch + (31 + l32 - 4 * h32) * XL8_LD + l32;
 #pragma unroll
-          for (int ks = 0; ks < 4; ++ks)
-            s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sK, 32 * kt, ks, lane), quf[ks], s[kt], 0, 0, 0);
-        }
-      }
-      // position term: key kk of the block and the lane's query meet at patch row 63 + l32 - kk
-      xl_position_product(sR, qvf, patch, wave, lane);
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-        if (kt < nkt) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int kk = 32 * kt + acc_row(r, h32);
-            s[kt][r] += patch[(63 + l32 - kk) * XL_PATCH_LD + l32];
-          }
-        }
+      for (int r = 0; r < 16; ++r) s[r] += cell0[-(8 * (r >> 2) + (r & 3)) * XL8_LD];
       __builtin_amdgcn_wave_barrier();
       float mloc = -INFINITY;
       if (edge) {
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-          if (kt < nkt) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              int key = jb * 64 + 32 * kt + acc_row(r, h32);
-              bool vis = key <= p.Mv + qi && key < p.S && qi < p.T;
-              float val = vis ? s[kt][r] : -INFINITY;
-              s[kt][r] = val;
-              mloc = fmaxf(mloc, val);
-            }
-          }
-      } else {
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[kt][r]);
+        for (int r = 0; r < 16; ++r) {
+          const int key = key0 + acc_row(r, h32);
+          const bool vis = key <= p.Mv + qi && key < p.S && qi < p.T;
+          s[r] = vis ? s[r] : -INFINITY;
+        }
       }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[r]);
       mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64)) * p.scale_log2;
       const bool grow = mloc > m + 8.f;                    // lazy reference maximum, as in the plain kernel
       if (__any(grow)) {
@@ -178,60 +167,76 @@ __global__ __launch_bounds__(256) void fa_xl_fwd_kernel(FaParams p) {
       const float neg_m = (m == -INFINITY) ? 0.f : -m;
       float lsum = 0.f;
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-        if (kt < nkt) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float pv = __builtin_amdgcn_exp2f(fmaf(s[kt][r], p.scale_log2, neg_m));
-            s[kt][r] = pv;
-            lsum += pv;
-          }
-        }
+      for (int r = 0; r < 16; ++r) {
+        s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, neg_m));
+        lsum += s[r];
+      }
       lsum += __shfl_xor(lsum, 32, 64);
       l += lsum;
 #pragma unroll
-      for (int ks2 = 0; ks2 < 4; ++ks2) {
-        const int kt = ks2 >> 1, sub = ks2 & 1;
-        if (kt < nkt) {
-          bf16x8 pb = pack_acc(s[kt], sub);
+      for (int sub = 0; sub < 2; ++sub) {
+        bf16x8 pb = pack_acc(s, sub);
 #pragma unroll
-          for (int dt = 0; dt < 2; ++dt)
-            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sV, 32 * dt, 32 * kt + 16 * sub, lane), pb, oacc[dt], 0, 0, 0);
-        }
+        for (int dt = 0; dt < 2; ++dt)
+          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sV, 32 * dt, 32 * kh + 16 * sub, lane), pb, oacc[dt], 0, 0, 0);
       }
     }
   }
-  if (qi < p.T) {
+  // merge the two key halves: state of the second through its patch (34 floats per lane)
+  if (kh == 1) {
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) patch[(16 * dt + r) * 64 + lane] = oacc[dt][r];
+    patch[32 * 64 + lane] = m;
+    patch[33 * 64 + lane] = l;
+  }
+  __syncthreads();
+  if (kh == 0 && qi < p.T) {
+    const float* other = reinterpret_cast<const float*>(lds + XL_NSTAGE * XL_STAGE + (wave + 4) * XL8_PATCH);
+    const float m1 = other[32 * 64 + lane], l1 = other[33 * 64 + lane];
+    const float mm = fmaxf(m, m1);
+    const float a0 = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mm);
+    const float a1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m1 - mm);
+    l = l * a0 + l1 * a1;
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[dt][r] = oacc[dt][r] * a0 + other[(16 * dt + r) * 64 + lane] * a1;
     const float inv = l > 0.f ? 1.f / l : 0.f;
     store_acc_row(p.o + ((size_t)b * p.T + qi) * p.ldo + head * 64, oacc, inv, h32);
-    if (h32 == 0) p.lse[((size_t)b * p.H + head) * p.T + qi] = (m + log2f(l)) * 0.6931471805599453f;
+    if (h32 == 0) p.lse[((size_t)b * p.H + head) * p.T + qi] = (mm + log2f(l)) * 0.6931471805599453f;
   }
 }
 
 
 // ---------------------------------------------------------------------------- dQ kernel
-// grid (ceil(T/128), H, B); 4 waves x 32 queries; key blocks of 64.  Besides dQ it produces
-// the gradients of the two biases (du = sum over queries of the content half of dq, dvb = that
-// of the position half) and leaves what the gradients of k, v and r are contractions of:
+// The two key halves of a query group add their dQ through LDS at the end.  Besides dQ the
+// kernel produces the gradients of the two biases (du = sum over queries of the content half of
+// dq, dvb = that of the position half) and leaves what the gradients of k, v and r are
+// contractions of:
 //   pt  [B, H, S, t_ld]   P^T, probabilities with the key as row, bf16 (dV = P^T dO)
 //   dst [B, H, S, t_ld]   dS^T, likewise (dK = scale dS^T (Q + u); dr: fa_xl_dr_kernel)
 //   qu, qv, dop [B, t_ld, H * 64]   q + u, q + v, dO with rows padded to t_ld
-// t_ld = T rounded up to 64.  Every (query, key) cell in a computed 32-key sub-tile is written
-// (masked cells as zero); cells outside (keys no query of the wave sees, rows i >= T) are never
-// written and must be zero from the caller (they are the same cells for the same Mv).
-__global__ __launch_bounds__(256) void fa_xl_dq_kernel(FaParams p) {
+// t_ld = T rounded up to 64; a cell of pt / dst is addressed by a 32-bit byte offset within its
+// (batch, head) matrix, so S * t_ld * 2 < 2^32 (attn_xl_ok).  Every (query, key) cell in a
+// computed 32-key sub-tile is written (masked cells as zero); cells outside (keys no query of
+// the wave sees, rows i >= T) are never written and must be zero from the caller (they are the
+// same cells for the same Mv).
+__global__ __launch_bounds__(512) void fa_xl_dq_kernel(FaParams p) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
+  const int qg = wave & 3, kh = wave >> 2;                  // waves w and w + 4 share a SIMD
   const int qblk = gridDim.x - 1 - blockIdx.x;
   const int head = blockIdx.y, b = blockIdx.z;
-  const int Q0 = qblk * 128, q0 = Q0 + wave * 32, qi = q0 + l32;
+  const int Q0 = qblk * 128, q0 = Q0 + qg * 32, qi = q0 + l32;
   const bf16_t* qb = p.q + (size_t)b * p.T * p.ldq + head * 64;
   const bf16_t* dob = p.d_o + (size_t)b * p.T * p.lddo + head * 64;
   const bf16_t* ob = p.o + (size_t)b * p.T * p.ldo + head * 64;
   const bf16_t* kb = p.k + (size_t)b * p.S * p.ldk + head * 64;
   const bf16_t* vb = p.v + (size_t)b * p.S * p.ldv + head * 64;
   const bf16_t* rb = p.r + head * 64;
-  float* patch = reinterpret_cast<float*>(lds + XL_NSTAGE * XL_STAGE + wave * XL_PATCH);
+  float* patch = reinterpret_cast<float*>(lds + XL_NSTAGE * XL_STAGE + wave * XL8_PATCH);
   bf16x8 quf[4], qvf[4], dof[4];
   float part = 0.f;
 #pragma unroll
@@ -245,7 +250,7 @@ __global__ __launch_bounds__(256) void fa_xl_dq_kernel(FaParams p) {
     quf[ks] = add_bias(as_bf16x8(t0), p.u + head * 64 + 16 * ks + 8 * h32);
     qvf[ks] = add_bias(as_bf16x8(t0), p.vb + head * 64 + 16 * ks + 8 * h32);
     dof[ks] = as_bf16x8(t1);
-    if (qi < p.T) {
+    if (qi < p.T && kh == 0) {
       const size_t at = ((size_t)b * p.t_ld + qi) * (p.H * 64) + head * 64 + 16 * ks + 8 * h32;
       *reinterpret_cast<bf16x8*>(p.qu + at) = quf[ks];
       *reinterpret_cast<bf16x8*>(p.qv + at) = qvf[ks];
@@ -258,26 +263,27 @@ __global__ __launch_bounds__(256) void fa_xl_dq_kernel(FaParams p) {
   const float D_q = part + __shfl_xor(part, 32, 64);
   float lse_q = 0.f;
   if (qi < p.T) lse_q = p.lse[((size_t)b * p.H + head) * p.T + qi] * 1.4426950408889634f;
-  // this (batch, head)'s P^T and dS^T, at the lane's query column
-  bf16_t* ptq = p.pt + ((size_t)b * p.H + head) * p.S * p.t_ld + qi;
-  bf16_t* dstq = p.dst + ((size_t)b * p.H + head) * p.S * p.t_ld + qi;
+  // this (batch, head)'s P^T and dS^T (uniform bases; a cell's offset fits 32 bits)
+  bf16_t* ptb = p.pt + ((size_t)b * p.H + head) * p.S * p.t_ld;
+  bf16_t* dstb = p.dst + ((size_t)b * p.H + head) * p.S * p.t_ld;
   const int wg_last_q = min(p.T, Q0 + 128) - 1;
   const int kend = min(p.S, p.Mv + wg_last_q + 1);
   const int nkb = (kend + 63) / 64;
   const bool wave_on = q0 < p.T;
   const int wave_kmax = p.Mv + min(p.T - 1, q0 + 31);
-  f32x16 dqa[2], dqb[2];                                   // content / position halves of dQ^T
+  const int rrow0 = 32 * qg + 32 * (1 - kh);                // window row of the wave's patch row 0
+  f32x16 dqa[2], dqb[2];
 #pragma unroll
   for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dqa[dt][r] = 0.f; dqb[dt][r] = 0.f; }
   auto issue = [&](int jb) __attribute__((always_inline)) {
     char* st = lds + (jb % XL_NSTAGE) * XL_STAGE;
-    dma_tile(kb, p.ldk, jb * 64, p.S, st, wave, lane);
-    dma_tile(vb, p.ldv, jb * 64, p.S, st + TILE_BYTES, wave, lane);
+    dma_tile8(kb, p.ldk, jb * 64, p.S, st, wave, lane, false);
+    dma_tile8(vb, p.ldv, jb * 64, p.S, st + TILE_BYTES, wave, lane, false);
     const int d0 = p.Mv + Q0 - jb * 64 - 63;
 #pragma unroll
-    for (int t = 0; t < 3; ++t) dma_tile_clamped(rb, p.ldr, d0 + 64 * t, p.S, st + 2 * TILE_BYTES + t * TILE_BYTES, wave, lane);
+    for (int t = 0; t < 3; ++t) dma_tile8(rb, p.ldr, d0 + 64 * t, p.S, st + 2 * TILE_BYTES + t * TILE_BYTES, wave, lane, true);
   };
   issue(0);
   for (int jb = 0; jb < nkb; ++jb) {
@@ -287,81 +293,90 @@ __global__ __launch_bounds__(256) void fa_xl_dq_kernel(FaParams p) {
     const char* sK = lds + (jb % XL_NSTAGE) * XL_STAGE;
     const char* sV = sK + TILE_BYTES;
     const char* sR = sK + 2 * TILE_BYTES;
-    if (wave_on && jb * 64 <= wave_kmax) {
-      const int nkt = (jb * 64 + 32 <= wave_kmax) ? 2 : 1;
-      const bool edge = jb * 64 + 63 > p.Mv + q0 || jb * 64 + 63 >= p.S || q0 + 31 >= p.T;
-      xl_position_product(sR, qvf, patch, wave, lane);
-      // One 32-key sub-tile at a time (scores and dP of a single sub-tile are live).  A cell of the
-      // patch belongs to one (query lane, key): the lane reads its position term there and puts
-      // dS, without its factor `scale` (the finished gradients take it once), back in its place,
-      // which is dS at its distance row.
+    const int key0 = jb * 64 + 32 * kh;                     // first key of the wave's sub-tile
+    if (wave_on && key0 <= wave_kmax) {
+      const bool edge = key0 + 31 > p.Mv + q0 || key0 + 31 >= p.S || q0 + 31 >= p.T;
+      xl_position_product(sR, rrow0, qvf, patch, lane);
+      f32x16 s, dp;
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-        if (kt < nkt) {
-          f32x16 s, dp;
+      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
-          for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-          for (int ks = 0; ks < 4; ++ks) {
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sK, 32 * kt, ks, lane), quf[ks], s, 0, 0, 0);
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sV, 32 * kt, ks, lane), dof[ks], dp, 0, 0, 0);
-          }
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int kk = 32 * kt + acc_row(r, h32);
-            float* cell = patch + (63 + l32 - kk) * XL_PATCH_LD + l32;
-            const float sc = s[r] + *cell;
-            float pv = __builtin_amdgcn_exp2f(fmaf(sc, p.scale_log2, -lse_q));
-            const int key = jb * 64 + kk;
-            if (edge) {
-              const bool vis = key <= p.Mv + qi && key < p.S && qi < p.T;
-              pv = vis ? pv : 0.f;
-            }
-            dp[r] = pv * (dp[r] - D_q);
-            *cell = dp[r];
-            if (key < p.S && qi < p.T) {
-              ptq[(size_t)key * p.t_ld] = (bf16_t)pv;
-              dstq[(size_t)key * p.t_ld] = (bf16_t)dp[r];
-            }
-          }
-#pragma unroll
-          for (int sub = 0; sub < 2; ++sub) {
-            bf16x8 dsb = pack_acc(dp, sub);
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
-              dqa[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sK, 32 * dt, 32 * kt + 16 * sub, lane), dsb, dqa[dt], 0, 0, 0);
-          }
-        }
+      for (int ks = 0; ks < 4; ++ks) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sK, 32 * kh, ks, lane), quf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sV, 32 * kh, ks, lane), dof[ks], dp, 0, 0, 0);
+      }
       __builtin_amdgcn_wave_barrier();
-      // rows of the patch that hold a gradient: 0 <= 63 + l32 - rho < 32 * nkt
+      // key kk of the sub-tile and the lane's query meet at patch row 31 + l32 - kk: the lane
+      // takes its position terms from there, forms P and dS, and puts dS (without its factor
+      // `scale`: the finished gradients take it once) back in the same cells
+      float* cell0 = patch + (31 + l32 - 4 * h32) * XL8_LD + l32;
 #pragma unroll
-      for (int t = 0; t < 3; ++t) {
+      for (int r = 0; r < 16; ++r) s[r] += cell0[-(8 * (r >> 2) + (r & 3)) * XL8_LD];
+      if (edge) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = key0 + acc_row(r, h32);
+          const bool vis = key <= p.Mv + qi && key < p.S && qi < p.T;
+          s[r] = vis ? __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -lse_q)) : 0.f;
+          dp[r] = s[r] * (dp[r] - D_q);
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -lse_q));
+          dp[r] = s[r] * (dp[r] - D_q);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) cell0[-(8 * (r >> 2) + (r & 3)) * XL8_LD] = dp[r];
+      // bf16 once: the rounded dS feeds dQ below and, with P, goes to the workspace
+      bf16x8 pb[2], dsb[2];
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) { pb[sub] = pack_acc(s, sub); dsb[sub] = pack_acc(dp, sub); }
+      const unsigned at0 = ((unsigned)(key0 + 4 * h32) * (unsigned)p.t_ld + (unsigned)qi) * 2u;   // byte offset
+      if (edge) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (key0 + acc_row(r, h32) < p.S && qi < p.T) {
+            const unsigned at = at0 + (unsigned)(8 * (r >> 2) + (r & 3)) * (unsigned)p.t_ld * 2u;
+            *reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(ptb) + at) = pb[r >> 3][r & 7];
+            *reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(dstb) + at) = dsb[r >> 3][r & 7];
+          }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const unsigned at = at0 + (unsigned)(8 * (r >> 2) + (r & 3)) * (unsigned)p.t_ld * 2u;
+          *reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(ptb) + at) = pb[r >> 3][r & 7];
+          *reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(dstb) + at) = dsb[r >> 3][r & 7];
+        }
+      }
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+          dqa[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sK, 32 * dt, 32 * kh + 16 * sub, lane), dsb[sub], dqa[dt], 0, 0, 0);
+      __builtin_amdgcn_wave_barrier();
+      // rows of the patch that hold a gradient: 0 <= 31 + l32 - rho < 32
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
         f32x16 g;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int rho = 32 * t + acc_row(r, h32);
-          const int kk = 63 + l32 - rho;
-          const float v = patch[rho * XL_PATCH_LD + l32];
-          g[r] = (kk >= 0 && kk < 32 * nkt) ? v : 0.f;
+          const int kk = 31 + l32 - rho;
+          const float v = patch[rho * XL8_LD + l32];
+          g[r] = (kk >= 0 && kk < 32) ? v : 0.f;
         }
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
           bf16x8 gb = pack_acc(g, sub);
 #pragma unroll
           for (int dt = 0; dt < 2; ++dt)
-            dqb[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sR, 32 * dt, 32 * wave + 32 * t + 16 * sub, lane), gb, dqb[dt], 0, 0, 0);
+            dqb[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows_t(sR, 32 * dt, rrow0 + 32 * t + 16 * sub, lane), gb, dqb[dt], 0, 0, 0);
         }
       }
       __builtin_amdgcn_wave_barrier();
     }
-  }
-  if (qi < p.T) {
-    f32x16 sum[2];
-#pragma unroll
-    for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sum[dt][r] = dqa[dt][r] + dqb[dt][r];
-    store_acc_row(p.dq + ((size_t)b * p.T + qi) * p.lddq + head * 64, sum, p.scale, h32);
   }
   // bias gradients: sums over the wave's queries (lanes of a half), one atomic per feature
   if (wave_on) {
@@ -378,6 +393,24 @@ __global__ __launch_bounds__(256) void fa_xl_dq_kernel(FaParams p) {
           unsafeAtomicAdd(p.dvb + f, c * p.scale);
         }
       }
+  }
+  // dQ: the second key half hands its sum to the first through its patch
+  __syncthreads();
+  if (kh == 1) {
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) patch[(16 * dt + r) * 64 + lane] = dqa[dt][r] + dqb[dt][r];
+  }
+  __syncthreads();
+  if (kh == 0 && qi < p.T) {
+    const float* other = reinterpret_cast<const float*>(lds + XL_NSTAGE * XL_STAGE + (wave + 4) * XL8_PATCH);
+    f32x16 sum[2];
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum[dt][r] = dqa[dt][r] + dqb[dt][r] + other[(16 * dt + r) * 64 + lane];
+    store_acc_row(p.dq + ((size_t)b * p.T + qi) * p.lddq + head * 64, sum, p.scale, h32);
   }
 }
 
@@ -469,6 +502,7 @@ bool attn_xl_ok(int dtype, const AttnDesc& a) {
   if (a.d_o) {
     if ((a.lddo | a.lddq | a.lddk | a.lddv) & 7) return false;
     if (!xl_al16(a.d_o) || !xl_al16(a.dq) || !xl_al16(a.dk) || !xl_al16(a.dv)) return false;
+    if ((size_t)a.S * ((a.T + 63) / 64 * 64) * 2 >= ((size_t)1 << 32)) return false;   // 32-bit offsets into P^T, dS^T
   }
   return true;
 }
@@ -477,12 +511,12 @@ hipError_t launch_attn_fwd_xl(hipStream_t s, const AttnDesc& a) {
   FaParams p = fa_params(a);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_xl_fwd_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, XL_LDS_Q);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_xl_fwd_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, XL_LDS_Q8);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  dim3 grid((a.T + 127) / 128, a.H, a.B), block(256);
-  hipLaunchKernelGGL(fa_xl_fwd_kernel, grid, block, XL_LDS_Q, s, p);
+  dim3 grid((a.T + 127) / 128, a.H, a.B), block(512);
+  hipLaunchKernelGGL(fa_xl_fwd_kernel, grid, block, XL_LDS_Q8, s, p);
   return hipGetLastError();
 }
 
@@ -497,7 +531,7 @@ hipError_t launch_attn_bwd_xl(hipStream_t s, const AttnDesc& a) {
   FaParams p = fa_params(a);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_xl_dq_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, XL_LDS_Q);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_xl_dq_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, XL_LDS_Q8);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
@@ -513,7 +547,7 @@ hipError_t launch_attn_bwd_xl(hipStream_t s, const AttnDesc& a) {
     if (e != hipSuccess) return e;
   }
   // du, dvb and dr are accumulated into (the caller zeroes them)
-  hipLaunchKernelGGL(fa_xl_dq_kernel, dim3((a.T + 127) / 128, a.H, a.B), dim3(256), XL_LDS_Q, s, p);
+  hipLaunchKernelGGL(fa_xl_dq_kernel, dim3((a.T + 127) / 128, a.H, a.B), dim3(512), XL_LDS_Q8, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   // dV[b, :, h] = P^T dO ; dK[b, :, h] = scale dS^T (Q + u): one product per (head, batch)
