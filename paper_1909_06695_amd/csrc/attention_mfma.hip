@@ -233,24 +233,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sdO, 32 * qt, ks, lane), vf[ks], dp, 0, 0, 0);
           }
           // P = exp2(s * scale * log2 e - lse2); dS = P (dP - D); the factor `scale` of dS is
-          // applied once, to the finished dK
+          // applied once, to the finished dK.  Two copies of the loop: the test for masked
+          // elements stays out of the blocks the diagonal does not cross.
+          if (edge) {
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int ql0 = 32 * qt + 8 * g + 4 * h32;
-            const float4 l4 = *reinterpret_cast<const float4*>(sl + ql0);
-            const float4 d4 = *reinterpret_cast<const float4*>(sD + ql0);
-            const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+            for (int g = 0; g < 4; ++g) {
+              const int ql0 = 32 * qt + 8 * g + 4 * h32;
+              const float4 l4 = *reinterpret_cast<const float4*>(sl + ql0);
+              const float4 d4 = *reinterpret_cast<const float4*>(sD + ql0);
+              const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const int r = 4 * g + j;
-              float pv = __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -lv[j]));
-              if (edge) {
+              for (int j = 0; j < 4; ++j) {
+                const int r = 4 * g + j;
                 const int qi = ib * 64 + ql0 + j;
                 const bool vis = key <= p.Mv + qi && qi < p.T && key < p.S;
-                pv = vis ? pv : 0.f;
+                const float pv = vis ? __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -lv[j])) : 0.f;
+                s[r] = pv;
+                dp[r] = pv * (dp[r] - dv4[j]);
               }
-              s[r] = pv;
-              dp[r] = pv * (dp[r] - dv4[j]);
+            }
+          } else {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              const int ql0 = 32 * qt + 8 * g + 4 * h32;
+              const float4 l4 = *reinterpret_cast<const float4*>(sl + ql0);
+              const float4 d4 = *reinterpret_cast<const float4*>(sD + ql0);
+              const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                const int r = 4 * g + j;
+                const float pv = __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -lv[j]));
+                s[r] = pv;
+                dp[r] = pv * (dp[r] - dv4[j]);
+              }
             }
           }
 #pragma unroll
@@ -361,16 +376,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sK, 32 * kt, ks, lane), qf[ks], s, 0, 0, 0);
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows(sV, 32 * kt, ks, lane), dof[ks], dp, 0, 0, 0);
           }
-          // dS without its factor `scale`, which the finished dQ takes once
+          // dS without its factor `scale`, which the finished dQ takes once.  Two copies of the
+          // loop: the test for masked elements stays out of the blocks the diagonal does not cross.
+          if (edge) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float pv = __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -lse_q));
-            if (edge) {
+            for (int r = 0; r < 16; ++r) {
               const int key = jb * 64 + 32 * kt + 8 * (r >> 2) + 4 * h32 + (r & 3);
               const bool vis = key <= p.Mv + qi && key < p.S && qi < p.T;
-              pv = vis ? pv : 0.f;
+              const float pv = vis ? __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -lse_q)) : 0.f;
+              dp[r] = pv * (dp[r] - D_q);
             }
-            dp[r] = pv * (dp[r] - D_q);
+          } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const float pv = __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -lse_q));
+              dp[r] = pv * (dp[r] - D_q);
+            }
           }
 #pragma unroll
           for (int sub = 0; sub < 2; ++sub) {
