@@ -163,8 +163,10 @@ __device__ __forceinline__ void gemm_dlds_body(const GemmParams& p, int bid, int
   const char* Ab = reinterpret_cast<const char*>(A);
   const char* Bb = reinterpret_cast<const char*>(B);
 
-  auto issue = [&](int kt) __attribute__((always_inline)) {
-    char* st = lds + (kt % S) * STAGE;
+  // `slot` (the ring stage) is a compile-time value at every call, so LDS addresses are a lane
+  // term plus an immediate offset
+  auto issue = [&](int kt, int slot) __attribute__((always_inline)) {
+    char* st = lds + slot * STAGE;
     const uint32_t ka = (uint32_t)kt * stepA, kb = (uint32_t)kt * stepB;
 #pragma unroll
     for (int i = 0; i < TileA::PER; ++i)
@@ -185,9 +187,10 @@ __device__ __forceinline__ void gemm_dlds_body(const GemmParams& p, int bid, int
 
 #pragma unroll
   for (int s = 0; s < S - 1; ++s)
-    if (s < nk) issue(s);
+    if (s < nk) issue(s, s);
 
-  for (int kt = 0; kt < nk; ++kt) {
+  // one K-tile: wait for it, refill the stage read last, multiply
+  auto step = [&](int kt, int slot) __attribute__((always_inline)) {
     // tile kt has landed once at most the loads of the younger tiles are outstanding
     if (kt + S - 1 <= nk) wait_vmcnt<(S - 2) * LPT>();
     else wait_vmcnt<0>();
@@ -195,49 +198,53 @@ __device__ __forceinline__ void gemm_dlds_body(const GemmParams& p, int bid, int
     // Before it every wave has waited for its own share of tile kt and for its LDS reads of
     // tile kt-1; after it tile kt is complete in LDS and stage (kt-1)%S may be refilled.
     __builtin_amdgcn_s_barrier();
-    if (kt + S - 1 < nk) issue(kt + S - 1);
-    const char* sa = lds + (kt % S) * STAGE;
+    if (kt + S - 1 < nk) issue(kt + S - 1, (slot + S - 1) % S);
+    const char* sa = lds + slot * STAGE;
     const char* sb = sa + TileA::BYTES;
-    {
-      // fragments of substep ks+1 are fetched before the matrix instructions of substep ks
-      // are issued, so LDS latency hides behind the matrix pipe even with one wave per SIMD
-      bf16x8 af[2][TM], bfr[2][TN];
+    // fragments of substep ks+1 are fetched before the matrix instructions of substep ks
+    // are issued, so LDS latency hides behind the matrix pipe even with one wave per SIMD
+    bf16x8 af[2][TM], bfr[2][TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-        af[0][i] = TA ? frag_col<BM>(sa, wm * (TM * 32) + i * 32, 0, lane) : frag_row(sa, wm * (TM * 32) + i * 32, 0, lane);
+    for (int i = 0; i < TM; ++i)
+      af[0][i] = TA ? frag_col<BM>(sa, wm * (TM * 32) + i * 32, 0, lane) : frag_row(sa, wm * (TM * 32) + i * 32, 0, lane);
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        bfr[0][j] = TB ? frag_row(sb, wn * (TN * 32) + j * 32, 0, lane) : frag_col<BN>(sb, wn * (TN * 32) + j * 32, 0, lane);
+    for (int j = 0; j < TN; ++j)
+      bfr[0][j] = TB ? frag_row(sb, wn * (TN * 32) + j * 32, 0, lane) : frag_col<BN>(sb, wn * (TN * 32) + j * 32, 0, lane);
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const int cur = ks & 1, nxt = cur ^ 1;
-        if (ks < 3) {
-#pragma unroll
-          for (int i = 0; i < TM; ++i)
-            af[nxt][i] = TA ? frag_col<BM>(sa, wm * (TM * 32) + i * 32, ks + 1, lane)
-                            : frag_row(sa, wm * (TM * 32) + i * 32, ks + 1, lane);
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            bfr[nxt][j] = TB ? frag_row(sb, wn * (TN * 32) + j * 32, ks + 1, lane)
-                             : frag_col<BN>(sb, wn * (TN * 32) + j * 32, ks + 1, lane);
-        }
+    for (int ks = 0; ks < 4; ++ks) {
+      const int cur = ks & 1, nxt = cur ^ 1;
+      if (ks < 3) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
+          af[nxt][i] = TA ? frag_col<BM>(sa, wm * (TM * 32) + i * 32, ks + 1, lane)
+                          : frag_row(sa, wm * (TM * 32) + i * 32, ks + 1, lane);
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
-        if (ks < 3) {
-          // interleave: one LDS fragment read per group of matrix instructions
-          constexpr int NRD = (TA ? 2 : 1) * TM + (TB ? 1 : 2) * TN;
-          constexpr int PERG = (TM * TN + NRD - 1) / NRD;
+        for (int j = 0; j < TN; ++j)
+          bfr[nxt][j] = TB ? frag_row(sb, wn * (TN * 32) + j * 32, ks + 1, lane)
+                           : frag_col<BN>(sb, wn * (TN * 32) + j * 32, ks + 1, lane);
+      }
 #pragma unroll
-          for (int g = 0; g < NRD; ++g) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, PERG, 0);
-          }
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+      if (ks < 3) {
+        // interleave: one LDS fragment read per group of matrix instructions
+        constexpr int NRD = (TA ? 2 : 1) * TM + (TB ? 1 : 2) * TN;
+        constexpr int PERG = (TM * TN + NRD - 1) / NRD;
+#pragma unroll
+        for (int g = 0; g < NRD; ++g) {
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, PERG, 0);
         }
       }
     }
+  };
+  // the K loop goes round the ring once per trip
+  for (int kt = 0; kt < nk; kt += S) {
+#pragma unroll
+    for (int slot = 0; slot < S; ++slot)
+      if (kt + slot < nk) step(kt + slot, slot);
   }
   __syncthreads();                                          // operand reads done: LDS reusable
   mfma_epilogue<TM, TN>(p, acc, smem, m0 + wm * (TM * 32), n0 + wn * (TN * 32), lane, wave);
