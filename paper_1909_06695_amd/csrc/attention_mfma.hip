@@ -28,7 +28,7 @@ namespace ouro {
 constexpr int FWD_NSTAGE = 2;
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void fa_fwd_kernel(FaParams p) {
   __shared__ __attribute__((aligned(16))) char lds[FWD_NSTAGE * 2 * TILE_BYTES];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), h32 = lane >> 5, l32 = lane & 31;
   int rank, head, b;
   fa_decode_block(rank, head, b);
   const int qblk = gridDim.x - 1 - rank;                  // the last query block has the longest rows
@@ -161,7 +161,7 @@ constexpr int DKV_STAGE = 2 * TILE_BYTES + 1024;   // Q, dO, lse[64], D[64], two
 // two workgroups per compute unit (256 registers per lane): both halves of a complementary pair resident
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void fa_bwd_dkv_kernel(FaParams p) {
   __shared__ __attribute__((aligned(16))) char lds[NSTAGE * DKV_STAGE];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), h32 = lane >> 5, l32 = lane & 31;
   int kblk, head, b;                                      // key block 0 sees every query: the heaviest
   fa_decode_block(kblk, head, b);
   const int kb0 = kblk * 128 + wave * 32, key = kb0 + l32;
@@ -293,7 +293,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // dP^T = V dO^T read K / V rows, dQ^T += K^T dS^T reads the K tile transposed.
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void fa_bwd_dq_kernel(FaParams p) {
   __shared__ __attribute__((aligned(16))) char lds[NSTAGE * 2 * TILE_BYTES];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), h32 = lane >> 5, l32 = lane & 31;
   int rank, head, b;
   fa_decode_block(rank, head, b);
   const int qblk = gridDim.x - 1 - rank;

@@ -80,7 +80,7 @@ __device__ __forceinline__ void xl_position_product(const char* sR, int rrow0, c
 // second half hands its state to the first through LDS at the end.
 __global__ __launch_bounds__(512) void fa_xl_fwd_kernel(FaParams p) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), h32 = lane >> 5, l32 = lane & 31;
   const int qg = wave & 3, kh = wave >> 2;
   const int qblk = gridDim.x - 1 - blockIdx.x;            // longest rows first
   const int head = blockIdx.y, b = blockIdx.z;
@@ -225,7 +225,7 @@ __global__ __launch_bounds__(512) void fa_xl_fwd_kernel(FaParams p) {
 // same cells for the same Mv).
 __global__ __launch_bounds__(512) void fa_xl_dq_kernel(FaParams p) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), h32 = lane >> 5, l32 = lane & 31;
   const int qg = wave & 3, kh = wave >> 2;                  // waves w and w + 4 share a SIMD
   const int qblk = gridDim.x - 1 - blockIdx.x;
   const int head = blockIdx.y, b = blockIdx.z;
@@ -431,7 +431,7 @@ constexpr int XL_LDS_DR = 2 * DR_STAGE;
 
 __global__ __launch_bounds__(256) void fa_xl_dr_kernel(FaParams p, int bpw) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h32 = lane >> 5, l32 = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), h32 = lane >> 5, l32 = lane & 31;
   const int D0 = blockIdx.x * 64, head = blockIdx.y;
   const int b0 = blockIdx.z * bpw, nb = min(p.B, b0 + bpw) - b0;
   const int wd = wave & 1, wf = wave >> 1;

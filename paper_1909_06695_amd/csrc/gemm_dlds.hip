@@ -141,7 +141,7 @@ __device__ __forceinline__ void gemm_dlds_body(const GemmParams& p, int bid, int
   char* lds = reinterpret_cast<char*>(smem);
   const bf16_t* A = reinterpret_cast<const bf16_t*>(p.A);
   const bf16_t* B = reinterpret_cast<const bf16_t*>(p.B);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: kept in a scalar register
   const int wm = wave / WN, wn = wave % WN;
   int m0, n0, kbeg;
   tile_of_block(p, BM, BN, bid, nb, m0, n0, kbeg);
@@ -201,6 +201,32 @@ __device__ __forceinline__ void gemm_dlds_body(const GemmParams& p, int bid, int
     if (kt + S - 1 < nk) issue(kt + S - 1, (slot + S - 1) % S);
     const char* sa = lds + slot * STAGE;
     const char* sb = sa + TileA::BYTES;
+    if constexpr (TM * TN <= 2) {
+      // small wave tiles: every fragment of the K-tile is requested up front (48 registers) and
+      // the matrix instructions start as the fragments arrive, so a wave meets the LDS latency
+      // once per K-tile
+      bf16x8 af[4][TM], bfr[4][TN];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+          af[ks][i] = TA ? frag_col<BM>(sa, wm * (TM * 32) + i * 32, ks, lane) : frag_row(sa, wm * (TM * 32) + i * 32, ks, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          bfr[ks][j] = TB ? frag_row(sb, wn * (TN * 32) + j * 32, ks, lane) : frag_col<BN>(sb, wn * (TN * 32) + j * 32, ks, lane);
+      }
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], bfr[ks][j], acc[i][j], 0, 0, 0);
+      // keep the requests ahead of the matrix instructions
+      constexpr int NRD = 4 * ((TA ? 2 : 1) * TM + (TB ? 1 : 2) * TN);
+      __builtin_amdgcn_sched_group_barrier(0x100, NRD, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 4 * TM * TN, 0);
+    } else {
     // fragments of substep ks+1 are fetched before the matrix instructions of substep ks
     // are issued, so LDS latency hides behind the matrix pipe even with one wave per SIMD
     bf16x8 af[2][TM], bfr[2][TN];
@@ -238,6 +264,7 @@ __device__ __forceinline__ void gemm_dlds_body(const GemmParams& p, int bid, int
           __builtin_amdgcn_sched_group_barrier(0x008, PERG, 0);
         }
       }
+    }
     }
   };
   // the K loop goes round the ring once per trip
@@ -294,7 +321,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_pipe_kernel(GemmParams p) {
   extern __shared__ uint4 smem[];
   char* lds = reinterpret_cast<char*>(smem);
   batch_offsets(p);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: kept in a scalar register
   const int wm = wave / WN, wn = wave % WN;
   int m0, n0, kbeg;
   tile_of_block(p, BM, BN, blockIdx.x, gridDim.x, m0, n0, kbeg);
