@@ -340,8 +340,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_pipe_kernel(GemmParams p) {
   const char* Ab = reinterpret_cast<const char*>(p.A);
   const char* Bb = reinterpret_cast<const char*>(p.B);
 
-  auto issue = [&](int kt) __attribute__((always_inline)) {
-    char* st = lds + (kt % S) * STAGE;
+  // `slot` (the ring stage) is a compile-time value at every call: LDS addresses are a lane term
+  // plus an immediate offset
+  auto issue = [&](int kt, int slot) __attribute__((always_inline)) {
+    char* st = lds + slot * STAGE;
     const uint32_t ka = (uint32_t)kt * stepA, kb = (uint32_t)kt * stepB;
 #pragma unroll
     for (int i = 0; i < TileA::PER; ++i)
@@ -352,8 +354,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_pipe_kernel(GemmParams p) {
                                        (lds_void*)(st + TileA::BYTES + (wave + i * NW) * 1024), 16, 0, 0);
   };
   bf16x8 af[4][TM], bfr[4][TN];
-  auto fetch = [&](int kt, int ks) __attribute__((always_inline)) {
-    const char* sa = lds + (kt % S) * STAGE;
+  auto fetch = [&](int slot, int ks) __attribute__((always_inline)) {
+    const char* sa = lds + slot * STAGE;
     const char* sb = sa + TileA::BYTES;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -374,21 +376,21 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_pipe_kernel(GemmParams p) {
   // tiles 0 .. S-2 on their way; tile 0 into registers
 #pragma unroll
   for (int s = 0; s < S - 1; ++s)
-    if (s < nk) issue(s);
+    if (s < nk) issue(s, s);
   if (nk >= S - 1) wait_vmcnt<(S - 2) * LPT>();
   else wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) fetch(0, ks);
 
-  for (int kt = 0; kt < nk; ++kt) {
+  auto step = [&](int kt, int slot) __attribute__((always_inline)) {
     // tile kt+1 has landed once only the loads of tiles kt+2 .. kt+S-2 are outstanding
     if (kt + S - 1 <= nk) wait_vmcnt<(S - 3) * LPT>();
     else wait_vmcnt<0>();
     // After this barrier tile kt+1 is complete in LDS, and every wave has issued the matrix
     // instructions of tile kt-1, which consumed the last reads of stage (kt-1)%S: refill it.
     __builtin_amdgcn_s_barrier();
-    if (kt + S - 1 < nk) issue(kt + S - 1);
+    if (kt + S - 1 < nk) issue(kt + S - 1, (slot + S - 1) % S);
     const bool more = kt + 1 < nk;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -398,9 +400,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_pipe_kernel(GemmParams p) {
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], bfr[ks][j], acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      if (more) fetch(kt + 1, ks);
+      if (more) fetch((slot + 1) % S, ks);
       __builtin_amdgcn_sched_barrier(0);
     }
+  };
+  // the K loop goes round the ring once per trip
+  for (int kt = 0; kt < nk; kt += S) {
+#pragma unroll
+    for (int slot = 0; slot < S; ++slot)
+      if (kt + slot < nk) step(kt + slot, slot);
   }
   __syncthreads();                                          // operand reads done: LDS reusable
   mfma_epilogue<TM, TN>(p, acc, smem, m0 + wm * (TM * 32), n0 + wn * (TN * 32), lane, wave);
