@@ -44,7 +44,10 @@ def step_flops(c):
         per_layer = 4 * d * d + 2 * d * F
         attn = 4 * d * (T + 1) / 2
     fwd = 2 * (L * per_layer + V * d) + L * attn
-    return 3.0 * B * T * fwd
+    flops = 3.0 * B * T * fwd
+    if c["rel_pos"]:
+        flops -= B * T * L * 2 * (2 * d * d) * M / T    # the memory rows are constants: no input gradient for them
+    return flops
 
 
 def hbm_traffic_per_launch(config):

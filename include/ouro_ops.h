@@ -33,7 +33,11 @@ int ouro_op_gemm(void* stream, int dtype, int transA, int transB, int M, int N, 
  * With C2 != NULL a second grid of the same shape, strides and leading dimensions runs in the
  * same launch with A2, B2, C2, alpha2.  bf16 products with K % 64 == 0 and 16-byte aligned
  * strides run as one launch of the MFMA kernel, anything else as one launch per product.
- * The relative-position attention backward forms dK, dV (Eq. 6 inside the attention block) this way. */
+ * accumulate: 0 C = alpha A B; 1 fp32 C += alpha A B with the contraction split over workgroups
+ * (atomic adds); 2 fp32 C += alpha A B in the epilogue of a single pass (one grid only).
+ * The relative-position attention backward forms dK, dV (Eq. 6 inside the attention block) this
+ * way, and adds the input gradient of the key / value projection over the current rows of every
+ * batch element (the memory rows of [memory ; segment] are constants) with accumulate = 2. */
 int ouro_op_gemm_batched(void* stream, int dtype, int transA, int transB, int M, int N, int K, float alpha,
                          const void* A, int lda, const void* B, int ldb, void* C, int ldc, int out_fp32,
                          int accumulate, int by, int bz, long long sAy, long long sAz, long long sBy,

@@ -101,7 +101,8 @@ struct GemmDesc {
   DropDesc drop;         // dropout on (alpha*acc + bias), before the residual; element index m*drop.ld + n
   // A grid of by x bz independent products of the same shape (0 or 1: a single one): product
   // (y, z) takes A + y*sAy + z*sAz, B + y*sBy + z*sBz and writes C + y*sCy + z*sCz (elements).
-  // Only with plain epilogues (no bias, residual, Z, dropout).
+  // Only with plain epilogues (no bias, residual, Z, dropout), except res32 without the
+  // LayerNorm terms on an fp32 output: it then follows C's batch strides (res32 == C adds in place).
   int by, bz;
   long long sAy, sAz, sBy, sBz, sCy, sCz;
   // A second grid of products of the same shape, strides and leading dimensions in the same

@@ -218,7 +218,8 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
   p.bBy = g.sBy * (long long)esz; p.bBz = g.sBz * (long long)esz;
   p.bCy = g.sCy * (long long)csz; p.bCz = g.sCz * (long long)csz;
   if (by * bz * grids > 1) {
-    if (g.bias || g.residual || g.res32 || g.epilogue != EPI_NONE || g.drop.on) return hipErrorInvalidValue;
+    if (g.bias || g.residual || g.epilogue != EPI_NONE || g.drop.on) return hipErrorInvalidValue;
+    if (g.res32 && (!g.out_fp32 || g.ln_mean || g.C2)) return hipErrorInvalidValue;
     const size_t bA = 2 * (size_t)(g.transA ? g.K : g.M) * g.lda, bB = 2 * (size_t)(g.transB ? g.N : g.K) * g.ldb;
     const bool in_grid = force_generic != 1 && gemm_uses_mfma(dtype, g) && (g.K % 64) == 0 && bA < (1ull << 31) && bB < (1ull << 31) &&
                          !((p.bAy | p.bAz | p.bBy | p.bBz | p.bCy | p.bCz) & 15) &&
@@ -232,6 +233,7 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
             h.A = (const char*)(w ? g.A2 : g.A) + y * p.bAy + z * p.bAz;
             h.B = (const char*)(w ? g.B2 : g.B) + y * p.bBy + z * p.bBz;
             h.C = (char*)(w ? g.C2 : g.C) + y * p.bCy + z * p.bCz;
+            if (g.res32) h.res32 = reinterpret_cast<const float*>(reinterpret_cast<const char*>(g.res32) + y * p.bCy + z * p.bCz);
             if (w) h.alpha = g.alpha2;
             hipError_t e = launch_gemm(s, dtype, h, force_generic);
             if (e != hipSuccess) return e;
@@ -257,7 +259,7 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
       // (the logits) or one per CU with a long contraction (dV_o)
       if (!g.accumulate && (t256 >= 1024 || (t256 >= 256 && g.K >= 4096))) cfg = GEMM_TILE_256x256;
       else if (g.accumulate && t128 >= 192) cfg = GEMM_TILE_128x128;   // split-K with two workgroups per CU
-      else if (g.accumulate || t128 <= 384) cfg = (!g.accumulate && t128 <= 256 && g.K >= 1024 && g.K <= 8192) ? GEMM_TILE_PIPE128 : GEMM_TILE_128x64;
+      else if (g.accumulate || t128 <= 384) cfg = (!g.accumulate && (long)t128 * by * bz * grids <= 256 && g.K >= 1024 && g.K <= 8192) ? GEMM_TILE_PIPE128 : GEMM_TILE_128x64;
       else cfg = GEMM_TILE_128x128;
     }
     const size_t bytesA = 2 * (size_t)(g.transA ? g.K : g.M) * g.lda, bytesB = 2 * (size_t)(g.transB ? g.N : g.K) * g.ldb;

@@ -125,6 +125,7 @@ __device__ __forceinline__ void batch_offsets(GemmParams& p) {
   p.A = reinterpret_cast<const char*>(p.A) + blockIdx.y * p.bAy + z * p.bAz;
   p.B = reinterpret_cast<const char*>(p.B) + blockIdx.y * p.bBy + z * p.bBz;
   p.C = reinterpret_cast<char*>(p.C) + blockIdx.y * p.bCy + z * p.bCz;
+  if (p.res32) p.res32 = reinterpret_cast<const float*>(reinterpret_cast<const char*>(p.res32) + blockIdx.y * p.bCy + z * p.bCz);
 }
 
 // One workgroup's share of a product: work item `bid` of `nb` (see tile_of_block).

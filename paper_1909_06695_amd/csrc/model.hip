@@ -473,7 +473,7 @@ static size_t lay_out(ouro_model& m, char* base) {
       x.ds2m[p2] = c.dropout > 0 ? P(N * d * es) : x.ds2[p2];
       x.ds1m[p2] = c.dropout > 0 ? P(N * d * es) : x.ds1[p2];
     }
-    x.dcat = c.rel_pos ? P(B * S * d * es) : nullptr;
+    x.dcat = (c.rel_pos && c.dtype != 1) ? P(B * S * d * es) : nullptr;   // fp32 mode: d[mem ; x] before its current rows are added to dx
     for (int p2 = 0; p2 < 2; ++p2) {
       x.dr_t[p2] = c.rel_pos ? P(S * hd * es) : nullptr;
       x.dr_f32[p2] = c.rel_pos ? (float*)P(S * hd * 4) : nullptr;
@@ -776,7 +776,7 @@ static int run_gemm_on(ouro_model* m, GemmDesc g, hipStream_t st) {
   const bool timed = m->timing && gemm_uses_mfma(m->cfg.dtype, g);
   if (timed) { int rc = timing_begin(m, OURO_TIMING_CONTRACTION, st); if (rc) return rc; }
   HIPCHK(launch_gemm(st, m->cfg.dtype, g, 0));
-  if (timed) return timing_end(m, OURO_TIMING_CONTRACTION, 2.0 * g.M * g.N * g.K, st);
+  if (timed) return timing_end(m, OURO_TIMING_CONTRACTION, 2.0 * g.M * g.N * g.K * std::max(1, g.by) * std::max(1, g.bz), st);
   return OURO_OK;
 }
 static int run_gemm(ouro_model* m, GemmDesc g) { return run_gemm_on(m, g, m->stream); }
@@ -1118,12 +1118,17 @@ static int layer_backward(ouro_model* m, int l, char* dh, char* dx, float* gslot
       RUN(run_gemm(m, g));
     }
     // the memory rows are constants: only the current rows of d[mem ; x] reach dx
-    RUN(run_gemm(m, gd(dkv, 2 * hd, 0, m->wT(l, o.W_qkv) + (size_t)hd * es, 3 * hd, 1, m->dcat, d, B * S, d, 2 * hd)));
-    {
+    if (c.dtype == 1) {
+      // one product per batch element over its T current rows of dkv, added to dx in place
+      GemmDesc g = gd(dkv + (size_t)Mv * 2 * hd * es, 2 * hd, 0, m->wT(l, o.W_qkv) + (size_t)hd * es, 3 * hd, 1, dx, d, T, d, 2 * hd);
+      g.by = B; g.sAy = (long long)S * 2 * hd; g.sCy = (long long)T * d;
+      g.out_fp32 = 1; g.res32 = (const float*)dx; g.ldr32 = d;
+      RUN(run_gemm(m, g));
+    } else {
+      RUN(run_gemm(m, gd(dkv, 2 * hd, 0, m->wT(l, o.W_qkv) + (size_t)hd * es, 3 * hd, 1, m->dcat, d, B * S, d, 2 * hd)));
       size_t n = (size_t)T * d;
       dim3 grid((unsigned)std::min<size_t>((n + 255) / 256, 1024), B), block(256);
-      if (c.dtype == 1) hipLaunchKernelGGL(add_rows_kernel<bf16_t>, grid, block, 0, st, (float*)dx, n, (const bf16_t*)m->dcat, (size_t)S * d, (size_t)Mv * d, n);
-      else hipLaunchKernelGGL(add_rows_kernel<float>, grid, block, 0, st, (float*)dx, n, (const float*)m->dcat, (size_t)S * d, (size_t)Mv * d, n);
+      hipLaunchKernelGGL(add_rows_kernel<float>, grid, block, 0, st, (float*)dx, n, (const float*)m->dcat, (size_t)S * d, (size_t)Mv * d, n);
       HIPCHK(hipGetLastError());
     }
   }

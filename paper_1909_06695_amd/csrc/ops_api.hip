@@ -41,7 +41,9 @@ extern "C" int ouro_op_gemm_batched(void* stream, int dtype, int transA, int tra
   if (!A || !B || !C || M < 0 || N < 0 || K < 0 || by < 1 || bz < 1 || by > 65535 || bz > 32767) return OURO_E_ARG;
   if (lda < (transA ? M : K) || ldb < (transB ? K : N) || ldc < N) return OURO_E_ARG;
   if (C2 && (!A2 || !B2)) return OURO_E_ARG;
-  GemmDesc g = make_gemm(transA, transB, M, N, K, alpha, A, lda, B, ldb, C, ldc, out_fp32, accumulate, nullptr, nullptr, 0, EPI_NONE, nullptr, 0);
+  if (accumulate < 0 || accumulate > 2 || (accumulate == 2 && (!out_fp32 || C2))) return OURO_E_ARG;
+  GemmDesc g = make_gemm(transA, transB, M, N, K, alpha, A, lda, B, ldb, C, ldc, out_fp32, accumulate == 1, nullptr, nullptr, 0, EPI_NONE, nullptr, 0);
+  if (accumulate == 2) { g.res32 = reinterpret_cast<const float*>(C); g.ldr32 = ldc; }   // every product adds to its own C in the epilogue
   g.by = by; g.bz = bz; g.sAy = sAy; g.sAz = sAz; g.sBy = sBy; g.sBz = sBz; g.sCy = sCy; g.sCz = sCz;
   g.A2 = A2; g.B2 = B2; g.C2 = C2; g.alpha2 = alpha2;
   return rc_of(launch_gemm((hipStream_t)stream, dtype, g, force_generic));

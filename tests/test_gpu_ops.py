@@ -77,6 +77,9 @@ def test_gemm_forms(dtype, force, tA, tB, M, N, K):
     (1, 1, 0, 128, 64, 2048, 3, 1, False, 1),    # split K with atomic adds inside a grid of products
     (1, 0, 0, 20, 64, 64, 2, 2, True, 0),        # fewer rows than an MFMA tile: one launch per product
     (1, 0, 0, 72, 40, 40, 2, 3, False, 0),       # K off the tile grid: one launch per product
+    (1, 0, 1, 200, 136, 256, 3, 2, False, 2),    # added to C in the epilogue, one launch
+    (1, 0, 1, 72, 40, 40, 2, 1, False, 2),       # ... one launch per product
+    (0, 0, 1, 33, 17, 29, 2, 2, False, 2),       # ... fp32
     (0, 0, 1, 33, 17, 29, 2, 2, True, 0)])       # fp32
 def test_gemm_batched(dtype, tA, tB, M, N, K, by, bz, second, acc):
     """Grids of equal products (operands laid out back to back, batch y fastest), optionally two
