@@ -265,6 +265,32 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& g, int force_ge
     const size_t bytesA = 2 * (size_t)(g.transA ? g.K : g.M) * g.lda, bytesB = 2 * (size_t)(g.transB ? g.N : g.K) * g.ldb;
     // direct global->LDS loads need whole 64-wide K tiles and 32-bit operand offsets
     const bool direct_ok = (g.K % 64) == 0 && bytesA < (1ull << 31) && bytesB < (1ull << 31);
+    // 256x256 tiles run one workgroup per CU, so a launch takes whole rounds of 256 tiles.  A
+    // few tile rows beyond the last full round would cost a whole round more (dV_o of a
+    // 50257-word vocabulary: 788 tiles, 3.08 rounds): those rows go out as a second, split-K
+    // launch that adds into the zeroed rows of the fp32 result.
+    if (cfg == GEMM_TILE_256x256 && force_generic == 0 && direct_ok && g.out_fp32 && !g.accumulate && !g.bias && !g.residual &&
+        !g.res32 && g.epilogue == EPI_NONE && !g.drop.on && by * bz * grids == 1 && g.ldc == g.N && g.K >= 2048) {
+      const int tn = (g.N + 255) / 256;
+      if (tn <= 256 && 256 % tn == 0) {
+        const int rows_round = 256 / tn * 256;
+        const int main = g.M / rows_round * rows_round, tail = g.M - main;
+        if (main > 0 && tail > 0 && ((tail + 255) / 256) * tn <= 64) {
+          GemmDesc a = g;
+          a.M = main;
+          hipError_t e = launch_gemm(s, dtype, a, 0);
+          if (e != hipSuccess) return e;
+          GemmDesc b = g;
+          b.M = tail;
+          b.A = reinterpret_cast<const char*>(g.A) + 2 * (g.transA ? (size_t)main : (size_t)main * g.lda);
+          b.C = reinterpret_cast<float*>(g.C) + (size_t)main * g.ldc;
+          b.accumulate = 1;
+          e = launch_fill_zero(s, b.C, (size_t)tail * g.ldc * 4);
+          if (e != hipSuccess) return e;
+          return launch_gemm(s, dtype, b, 0);
+        }
+      }
+    }
     int splits = 1;
     bool modelled = false;
     if (g.accumulate && force_generic < 2 && direct_ok && g.K >= 512) {

@@ -71,6 +71,23 @@ def test_gemm_forms(dtype, force, tA, tB, M, N, K):
         assert L().ouro_op_gemm_uses_mfma(dtype, tA, tB, M, N, K, p(dA), dA.shape[1], p(dB), dB.shape[1]) == 1
 
 
+def test_gemm_row_tail():
+    """A product on 256x256 tiles whose tile rows end a little past a full round of workgroups:
+    the rows of the last partial round come from a second, split-K launch.  Rows on both sides
+    of the seam and the last rows against fp64."""
+    M, N, K = 16384 + 520, 1024, 4096
+    rng = np.random.default_rng(77)
+    dA = dev(rng.standard_normal((K, M)).astype(np.float32), 1)
+    dB = dev(rng.standard_normal((K, N)).astype(np.float32), 1)
+    out = torch.full((M, N), 7.0, dtype=torch.float32, device="cuda")
+    ok(L().ouro_op_gemm(stream(), 1, 1, 0, M, N, K, 1.0, p(dA), M, p(dB), N, p(out), N, 1, 0, None, None, 0, 0, None, 0, 0))
+    torch.cuda.synchronize()
+    rows = np.r_[0:4, 8190:8194, 16376:16392, 16640:16644, M - 9:M]
+    a64, b64 = host(dA), host(dB)
+    ref = a64[:, rows].T @ b64
+    assert rel_err(host(out)[rows], ref) < 2e-6
+
+
 @pytest.mark.parametrize("dtype,tA,tB,M,N,K,by,bz,second,acc", [
     (1, 0, 0, 200, 64, 128, 3, 2, True, 0),      # one launch of the MFMA kernel over the grid, two grids, ragged M
     (1, 0, 1, 136, 72, 192, 2, 1, False, 0),
