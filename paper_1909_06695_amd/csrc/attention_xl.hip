@@ -394,8 +394,7 @@ __global__ __launch_bounds__(512) void fa_xl_dq_kernel(FaParams p) {
         }
       }
   }
-  // dQ: the second key half hands its sum to the first through its patch
-  __syncthreads();
+  // dQ: the second key half hands its sum to the first through its (own) patch
   if (kh == 1) {
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt)

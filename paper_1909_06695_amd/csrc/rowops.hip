@@ -881,9 +881,24 @@ __global__ void copy_rows_kernel(T* dst, size_t dst_bstride, size_t dst_off, con
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (; i < n; i += stride) dst[b * dst_bstride + dst_off + i] = src[b * src_bstride + src_off + i];
 }
+// The same copy in 16-byte pieces (all strides, offsets and the row block a multiple of 16 bytes).
+__global__ void copy_rows_vec_kernel(uint4* dst, size_t dst_bstride, size_t dst_off, const uint4* src, size_t src_bstride,
+                                     size_t src_off, size_t n) {
+  const int b = blockIdx.y;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[b * dst_bstride + dst_off + i] = src[b * src_bstride + src_off + i];
+}
 hipError_t launch_copy_rows(hipStream_t s, int dtype, void* dst, size_t dst_bstride, size_t dst_off,
                             const void* src, size_t src_bstride, size_t src_off, int B, int rows, int d) {
   if (B <= 0 || rows <= 0) return hipSuccess;
+  const size_t esz = dtype == 1 ? 2 : 4, per = 16 / esz, n = (size_t)rows * d;
+  if (!((dst_bstride | dst_off | src_bstride | src_off | n) % per) && !((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15)) {
+    dim3 grid(grid_for(n / per, 256, 1024), B), block(256);
+    hipLaunchKernelGGL(copy_rows_vec_kernel, grid, block, 0, s, (uint4*)dst, dst_bstride / per, dst_off / per, (const uint4*)src,
+                       src_bstride / per, src_off / per, n / per);
+    return hipGetLastError();
+  }
   dim3 grid(grid_for((size_t)rows * d, 256, 1024), B), block(256);
   if (dtype == 1) hipLaunchKernelGGL(copy_rows_kernel<bf16_t>, grid, block, 0, s, (bf16_t*)dst, dst_bstride, dst_off, (const bf16_t*)src, src_bstride, src_off, rows, d);
   else hipLaunchKernelGGL(copy_rows_kernel<float>, grid, block, 0, s, (float*)dst, dst_bstride, dst_off, (const float*)src, src_bstride, src_off, rows, d);
