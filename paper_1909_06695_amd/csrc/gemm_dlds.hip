@@ -250,21 +250,14 @@ __device__ __forceinline__ void gemm_dlds_body(const GemmParams& p, int bid, int
           bfr[nxt][j] = TB ? frag_row(sb, wn * (TN * 32) + j * 32, ks + 1, lane)
                            : frag_col<BN>(sb, wn * (TN * 32) + j * 32, ks + 1, lane);
       }
+      // the requests of substep ks+1 stay ahead of the matrix instructions of substep ks
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
-      if (ks < 3) {
-        // interleave: one LDS fragment read per group of matrix instructions
-        constexpr int NRD = (TA ? 2 : 1) * TM + (TB ? 1 : 2) * TN;
-        constexpr int PERG = (TM * TN + NRD - 1) / NRD;
-#pragma unroll
-        for (int g = 0; g < NRD; ++g) {
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x008, PERG, 0);
-        }
-      }
+      __builtin_amdgcn_sched_barrier(0);
     }
     }
   };
