@@ -166,8 +166,7 @@ __device__ __forceinline__ void gemm_dlds_body(const GemmParams& p, int bid, int
 
   // `slot` (the ring stage) is a compile-time value at every call, so LDS addresses are a lane
   // term plus an immediate offset
-  auto issue = [&](int kt, int slot) __attribute__((always_inline)) {
-    char* st = lds + slot * STAGE;
+  auto issue = [&](int kt, char* st) __attribute__((always_inline)) {
     const uint32_t ka = (uint32_t)kt * stepA, kb = (uint32_t)kt * stepB;
 #pragma unroll
     for (int i = 0; i < TileA::PER; ++i)
@@ -188,10 +187,15 @@ __device__ __forceinline__ void gemm_dlds_body(const GemmParams& p, int bid, int
 
 #pragma unroll
   for (int s = 0; s < S - 1; ++s)
-    if (s < nk) issue(s, s);
+    if (s < nk) issue(s, lds + s * STAGE);
 
-  // one K-tile: wait for it, refill the stage read last, multiply
-  auto step = [&](int kt, int slot) __attribute__((always_inline)) {
+  // One K-tile: wait for it, refill the stage read last, multiply.  The stage that is filled and
+  // the stage that is read are distinct `__restrict__` objects of this call: without that the
+  // compiler cannot tell a transposing LDS read from the target of the loads just issued and
+  // drains them (s_waitcnt vmcnt(0)) before the first fragment read, which takes the ring's
+  // prefetch distance to zero.  What orders the fill of a stage and its reads is the explicit
+  // wait and barrier below.
+  auto step = [&](int kt, char* __restrict__ fill, const char* __restrict__ sa) __attribute__((always_inline)) {
     // tile kt has landed once at most the loads of the younger tiles are outstanding
     if (kt + S - 1 <= nk) wait_vmcnt<(S - 2) * LPT>();
     else wait_vmcnt<0>();
@@ -199,8 +203,7 @@ __device__ __forceinline__ void gemm_dlds_body(const GemmParams& p, int bid, int
     // Before it every wave has waited for its own share of tile kt and for its LDS reads of
     // tile kt-1; after it tile kt is complete in LDS and stage (kt-1)%S may be refilled.
     __builtin_amdgcn_s_barrier();
-    if (kt + S - 1 < nk) issue(kt + S - 1, (slot + S - 1) % S);
-    const char* sa = lds + slot * STAGE;
+    if (kt + S - 1 < nk) issue(kt + S - 1, fill);
     const char* sb = sa + TileA::BYTES;
     if constexpr (TM * TN <= 2) {
       // small wave tiles: every fragment of the K-tile is requested up front (48 registers) and
@@ -265,7 +268,7 @@ __device__ __forceinline__ void gemm_dlds_body(const GemmParams& p, int bid, int
   for (int kt = 0; kt < nk; kt += S) {
 #pragma unroll
     for (int slot = 0; slot < S; ++slot)
-      if (kt + slot < nk) step(kt + slot, slot);
+      if (kt + slot < nk) step(kt + slot, lds + ((slot + S - 1) % S) * STAGE, lds + slot * STAGE);
   }
   __syncthreads();                                          // operand reads done: LDS reusable
   mfma_epilogue<TM, TN>(p, acc, smem, m0 + wm * (TM * 32), n0 + wn * (TN * 32), lane, wave);
@@ -336,8 +339,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_pipe_kernel(GemmParams p) {
 
   // `slot` (the ring stage) is a compile-time value at every call: LDS addresses are a lane term
   // plus an immediate offset
-  auto issue = [&](int kt, int slot) __attribute__((always_inline)) {
-    char* st = lds + slot * STAGE;
+  auto issue = [&](int kt, char* st) __attribute__((always_inline)) {
     const uint32_t ka = (uint32_t)kt * stepA, kb = (uint32_t)kt * stepB;
 #pragma unroll
     for (int i = 0; i < TileA::PER; ++i)
@@ -348,8 +350,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_pipe_kernel(GemmParams p) {
                                        (lds_void*)(st + TileA::BYTES + (wave + i * NW) * 1024), 16, 0, 0);
   };
   bf16x8 af[4][TM], bfr[4][TN];
-  auto fetch = [&](int slot, int ks) __attribute__((always_inline)) {
-    const char* sa = lds + slot * STAGE;
+  auto fetch = [&](const char* sa, int ks) __attribute__((always_inline)) {
     const char* sb = sa + TileA::BYTES;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -370,21 +371,23 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_pipe_kernel(GemmParams p) {
   // tiles 0 .. S-2 on their way; tile 0 into registers
 #pragma unroll
   for (int s = 0; s < S - 1; ++s)
-    if (s < nk) issue(s, s);
+    if (s < nk) issue(s, lds + s * STAGE);
   if (nk >= S - 1) wait_vmcnt<(S - 2) * LPT>();
   else wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) fetch(0, ks);
+  for (int ks = 0; ks < 4; ++ks) fetch(lds, ks);
 
-  auto step = [&](int kt, int slot) __attribute__((always_inline)) {
+  // `fill` and `next` (the stage refilled and the stage read) are distinct objects of a call, see
+  // gemm_dlds_body
+  auto step = [&](int kt, char* __restrict__ fill, const char* __restrict__ next) __attribute__((always_inline)) {
     // tile kt+1 has landed once only the loads of tiles kt+2 .. kt+S-2 are outstanding
     if (kt + S - 1 <= nk) wait_vmcnt<(S - 3) * LPT>();
     else wait_vmcnt<0>();
     // After this barrier tile kt+1 is complete in LDS, and every wave has issued the matrix
     // instructions of tile kt-1, which consumed the last reads of stage (kt-1)%S: refill it.
     __builtin_amdgcn_s_barrier();
-    if (kt + S - 1 < nk) issue(kt + S - 1, (slot + S - 1) % S);
+    if (kt + S - 1 < nk) issue(kt + S - 1, fill);
     const bool more = kt + 1 < nk;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -394,7 +397,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_pipe_kernel(GemmParams p) {
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], bfr[ks][j], acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      if (more) fetch((slot + 1) % S, ks);
+      if (more) fetch(next, ks);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -402,7 +405,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_pipe_kernel(GemmParams p) {
   for (int kt = 0; kt < nk; kt += S) {
 #pragma unroll
     for (int slot = 0; slot < S; ++slot)
-      if (kt + slot < nk) step(kt + slot, slot);
+      if (kt + slot < nk) step(kt + slot, lds + ((slot + S - 1) % S) * STAGE, lds + ((slot + 1) % S) * STAGE);
   }
   __syncthreads();                                          // operand reads done: LDS reusable
   mfma_epilogue<TM, TN>(p, acc, smem, m0 + wm * (TM * 32), n0 + wn * (TN * 32), lane, wave);
