@@ -476,7 +476,7 @@ hipError_t launch_gemm_dlds_group(hipStream_t s, GemmParams* ps, int n, int tran
     p.tilesN = (p.N + BN - 1) / BN;
     p.ntiles = p.tilesM * p.tilesN;
     const int splits = (p.K + p.kchunk - 1) / p.kchunk;
-    p.mfast = splits > 1 && p.N > p.M;
+    p.mfast = p.N > p.M;                                    // neighbours share the larger operand's tile (two equal 1024 x 4096 products, one K range: 173 -> 150 us)
     p.band = 0;
     g.p[i] = p;
     g.first[i + 1] = g.first[i] + (p.ntiles * splits + 7) / 8 * 8;
