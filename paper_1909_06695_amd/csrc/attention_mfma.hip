@@ -15,6 +15,8 @@
 // log-sum-exp is saved for the backward kernels.
 #include "attention_tiles.h"
 
+#include <algorithm>
+
 namespace ouro {
 
 // ------------------------------------------------------------------------------ forward
@@ -155,22 +157,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 }
 
 // ------------------------------------------------------------------------ dK, dV kernel
-// grid (ceil(S/128), H, B); 4 waves x 32 keys; query blocks of 64: S = Q K^T and dP = dO V^T
+// grid (ceil(ceil(S/128) / 2), H, B); 4 waves x 32 keys; query blocks of 64: S = Q K^T and dP = dO V^T
 // read Q / dO rows, dV^T += dO^T P and dK^T += Q^T dS read the same tiles transposed.
 constexpr int DKV_STAGE = 2 * TILE_BYTES + 1024;   // Q, dO, lse[64], D[64], two spare lines
-// two workgroups per compute unit (256 registers per lane): both halves of a complementary pair resident
+// two workgroups per compute unit (256 registers per lane)
+template <bool PAIR>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void fa_bwd_dkv_kernel(FaParams p) {
   __shared__ __attribute__((aligned(16))) char lds[NSTAGE * DKV_STAGE];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), h32 = lane >> 5, l32 = lane & 31;
-  int kblk, head, b;                                      // key block 0 sees every query: the heaviest
-  fa_decode_block(kblk, head, b);
-  const int kb0 = kblk * 128 + wave * 32, key = kb0 + l32;
+  int first, head, b;                                     // key block 0 sees every query: the heaviest
+  if (PAIR) { first = blockIdx.x; head = blockIdx.y; b = blockIdx.z; }
+  else fa_decode_block(first, head, b);
   const bf16_t* qb = p.q + (size_t)b * p.T * p.ldq + head * 64;
   const bf16_t* dob = p.d_o + (size_t)b * p.T * p.lddo + head * 64;
   const bf16_t* kbp = p.k + (size_t)b * p.S * p.ldk + head * 64;
   const bf16_t* vbp = p.v + (size_t)b * p.S * p.ldv + head * 64;
   const float* lseb = p.lse2 + ((size_t)b * p.H + head) * p.T;
   const float* Db = p.D + ((size_t)b * p.H + head) * p.T;
+  // Key block k sees the queries from 128 k - Mv on, so its work falls linearly with k.  Where
+  // the launch still fills the chip that way (PAIR), a workgroup takes block k and then block
+  // (last - k), and every workgroup has the same amount of work: with one block each the resident
+  // waves per SIMD averaged 1.1 of 2 over the launch, the slots of the light blocks standing empty
+  // while the heavy ones finished (T = 1024, 8 x 16 heads: 77 -> 62 us).
+  const int nkblk = (p.S + 127) / 128;
+  for (int pass = 0; pass < (PAIR ? 2 : 1); ++pass) {
+  const int kblk = pass == 0 ? first : nkblk - 1 - first;
+  if (pass == 1) {
+    if (kblk <= first) break;                             // odd count: the middle block has no partner
+    fa_wait_vmcnt<0>();                                   // the first block's stores and loads are done,
+    __syncthreads();                                      // ... and every wave is past its last LDS read
+  }
+  const int kb0 = kblk * 128 + wave * 32, key = kb0 + l32;
   bf16x8 kf[4], vf[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
@@ -286,22 +303,35 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     store_acc_row(p.dk + ((size_t)b * p.S + key) * p.lddk + head * 64, dkT, p.scale, h32);
     store_acc_row(p.dv + ((size_t)b * p.S + key) * p.lddv + head * 64, dvT, 1.f, h32);
   }
+  }
 }
 
 // ---------------------------------------------------------------------------- dQ kernel
-// grid (ceil(T/128), H, B); 4 waves x 32 queries; key blocks of 64: S^T = K Q^T and
+// grid (ceil(ceil(T/128) / 2), H, B); 4 waves x 32 queries; key blocks of 64: S^T = K Q^T and
 // dP^T = V dO^T read K / V rows, dQ^T += K^T dS^T reads the K tile transposed.
+template <bool PAIR>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void fa_bwd_dq_kernel(FaParams p) {
   __shared__ __attribute__((aligned(16))) char lds[NSTAGE * 2 * TILE_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), h32 = lane >> 5, l32 = lane & 31;
-  int rank, head, b;
-  fa_decode_block(rank, head, b);
-  const int qblk = gridDim.x - 1 - rank;
-  const int q0 = qblk * 128 + wave * 32, qi = q0 + l32;
+  int rank, head, b;                                      // rank 0: the last query block, the heaviest
+  if (PAIR) { rank = blockIdx.x; head = blockIdx.y; b = blockIdx.z; }
+  else fa_decode_block(rank, head, b);
   const bf16_t* qb = p.q + (size_t)b * p.T * p.ldq + head * 64;
   const bf16_t* dob = p.d_o + (size_t)b * p.T * p.lddo + head * 64;
   const bf16_t* kb = p.k + (size_t)b * p.S * p.ldk + head * 64;
   const bf16_t* vb = p.v + (size_t)b * p.S * p.ldv + head * 64;
+  // the work of query block q grows linearly with q: with PAIR a workgroup takes block
+  // (last - rank) and then block rank, so that all workgroups of the launch carry the same load
+  // (see the dK/dV kernel; 59 -> 53 us)
+  const int nqblk = (p.T + 127) / 128;
+  for (int pass = 0; pass < (PAIR ? 2 : 1); ++pass) {
+  const int qblk = pass == 0 ? nqblk - 1 - rank : rank;
+  if (pass == 1) {
+    if (qblk >= nqblk - 1 - rank) break;                  // odd count: the middle block has no partner
+    fa_wait_vmcnt<0>();                                   // the first block's stores and loads are done,
+    __syncthreads();                                      // ... and every wave is past its last LDS read
+  }
+  const int q0 = qblk * 128 + wave * 32, qi = q0 + l32;
   bf16x8 qf[4], dof[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
@@ -405,6 +435,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     }
   }
   if (qi < p.T) store_acc_row(p.dq + ((size_t)b * p.T + qi) * p.lddq + head * 64, dqT, p.scale, h32);
+  }
 }
 
 // ----------------------------------------------------------------------------- dispatch
@@ -430,11 +461,16 @@ hipError_t launch_attn_fwd_mfma(hipStream_t s, const AttnDesc& a) {
 
 hipError_t launch_attn_bwd_mfma(hipStream_t s, const AttnDesc& a) {
   FaParams p = fa_params(a);
+  // two blocks of the causal axis per workgroup where that still leaves two workgroups per compute unit
+  const int nq = (a.T + 127) / 128, nk = (a.S + 127) / 128;
+  const bool pair = (long)((std::min(nq, nk) + 1) / 2) * a.H * a.B >= 512;
   // the dQ kernel also produces the row sums D and the base-2 log-sum-exp the dK/dV kernel reads
-  hipLaunchKernelGGL(fa_bwd_dq_kernel, dim3((a.T + 127) / 128, a.H, a.B), dim3(256), 0, s, p);
+  if (pair) hipLaunchKernelGGL(fa_bwd_dq_kernel<true>, dim3((nq + 1) / 2, a.H, a.B), dim3(256), 0, s, p);
+  else hipLaunchKernelGGL(fa_bwd_dq_kernel<false>, dim3(nq, a.H, a.B), dim3(256), 0, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(fa_bwd_dkv_kernel, dim3((a.S + 127) / 128, a.H, a.B), dim3(256), 0, s, p);
+  if (pair) hipLaunchKernelGGL(fa_bwd_dkv_kernel<true>, dim3((nk + 1) / 2, a.H, a.B), dim3(256), 0, s, p);
+  else hipLaunchKernelGGL(fa_bwd_dkv_kernel<false>, dim3(nk, a.H, a.B), dim3(256), 0, s, p);
   return hipGetLastError();
 }
 

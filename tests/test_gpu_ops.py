@@ -257,10 +257,12 @@ def test_attention_general_kernel(dtype, B, H, T, Mv, dh, rel):
 
 
 @pytest.mark.parametrize("B,H,T,Mv", [(2, 2, 128, 0), (1, 3, 200, 0), (2, 1, 96, 40), (1, 2, 512, 0), (1, 1, 33, 0),
-                                      (1, 2, 300, 77)])
+                                      (1, 2, 300, 77), (32, 16, 256, 0), (16, 16, 384, 0), (16, 16, 300, 90)])
 def test_attention_mfma_kernel(B, H, T, Mv):
     """Fused matrix-core kernels (bf16, head size 64): several query/key blocks, ragged
-    tails, and a key prefix (Mv) that every query sees."""
+    tails, and a key prefix (Mv) that every query sees.  The last three cases have enough
+    (batch, head) pairs for the backward kernels to take two blocks per workgroup (an even
+    count, an odd one whose middle block goes alone, and unequal query / key block counts)."""
     _attn_case(1, B, H, T, Mv, 64, 0, seed=100 + T + Mv, force=0)
 
 
