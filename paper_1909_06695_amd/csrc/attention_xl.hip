@@ -67,6 +67,18 @@ __device__ __forceinline__ void xl_position_product(const char* sR, int rrow0, c
   }
 }
 
+// Forward kernel: workgroup -> (query block, head, batch), longest rows first over the whole launch: the
+// dispatcher hands out workgroups in linear id order, so all workgroups of the last query block
+// (the most keys) start first and the lighter blocks fill the slots as they free up.
+__device__ __forceinline__ void xl_decode_block(int& qblk, int& head, int& b) {
+  const int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  const int per = gridDim.y * gridDim.z;
+  const int rest = lin % per;
+  qblk = gridDim.x - 1 - lin / per;
+  head = rest % gridDim.y;
+  b = rest / gridDim.y;
+}
+
 // Both kernels below: grid (ceil(T/128), H, B); 8 waves = (4 groups of 32 queries) x (the two
 // 32-key halves of a 64-key block), waves w and w + 4 (one query group) on one SIMD; one
 // workgroup per CU, so two waves per SIMD (with four waves owning whole 64-key blocks, one per
@@ -82,8 +94,8 @@ __global__ __launch_bounds__(512) void fa_xl_fwd_kernel(FaParams p) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), h32 = lane >> 5, l32 = lane & 31;
   const int qg = wave & 3, kh = wave >> 2;
-  const int qblk = gridDim.x - 1 - blockIdx.x;            // longest rows first
-  const int head = blockIdx.y, b = blockIdx.z;
+  int qblk, head, b;
+  xl_decode_block(qblk, head, b);
   const int Q0 = qblk * 128, q0 = Q0 + qg * 32, qi = q0 + l32;
   const bf16_t* qb = p.q + (size_t)b * p.T * p.ldq + head * 64;
   const bf16_t* kb = p.k + (size_t)b * p.S * p.ldk + head * 64;
@@ -227,6 +239,8 @@ __global__ __launch_bounds__(512) void fa_xl_dq_kernel(FaParams p) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), h32 = lane >> 5, l32 = lane & 31;
   const int qg = wave & 3, kh = wave >> 2;                  // waves w and w + 4 share a SIMD
+  // (the launch-wide heaviest-first order of the forward kernel measured 10 % slower here: the three
+  // query blocks of a (batch, head) then write their parts of P^T and dS^T far apart in time)
   const int qblk = gridDim.x - 1 - blockIdx.x;
   const int head = blockIdx.y, b = blockIdx.z;
   const int Q0 = qblk * 128, q0 = Q0 + qg * 32, qi = q0 + l32;
