@@ -409,7 +409,7 @@ hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, const void* dy, const 
   bool fused = false;
   if (ln_vec_ok(dtype, dy, x, d) && ptr16(dx)) {
     const int grp = dtype == 0 ? 4 : 8;
-    dim3 gf(std::min((rows + 3) / 4, 512));
+    dim3 gf(std::min((rows + 3) / 4, 384));   // every block ends with 2 d atomic adds: 384 blocks measured best in the step (256, 512: +0.5 %)
     const int npl = (d / grp + 63) / 64;      // groups per lane
     fused = fuse_params && dg && db;
     const size_t smem = fused ? (size_t)4 * d * sizeof(float) : 0;
